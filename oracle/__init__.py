@@ -1,0 +1,166 @@
+"""CPU oracle for the emulated 1/e/m floating-point arithmetic -- TEST INFRASTRUCTURE ONLY.
+
+A thin ctypes loader around ``fmt_oracle.c`` (plain C, fp64, written from the paper's
+definitions: Sec. III Def. III.1/III.2, Table I, Sec. III-B FMACS, Sec. IV-A roundfp,
+Sec. V denormal fraction).  It shares nothing with the GPU library and must not be
+imported by it: only ``tests/``, the smoke check and the benchmark's ``cpu_baseline``
+leg may use it.  Arrays in, arrays out; no GPU, no torch.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fmt_oracle.c")
+_LIB = os.path.join(_HERE, "libfmt_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+NBINS = 64
+CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no contraction, no fast-math) and return the .so path."""
+    with _lock:
+        stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+        if force or stale:
+            tmp = _LIB + ".tmp.%d" % os.getpid()
+            cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+                   "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
+                   "-o", tmp, _SRC, "-lm"]
+            subprocess.run(cmd, check=True)
+            os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        f32p = ctypes.POINTER(ctypes.c_float)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        lib.oracle_format_constants.argtypes = [ctypes.c_int, ctypes.c_int] + \
+            [ctypes.POINTER(ctypes.c_double)] * 3 + [ctypes.POINTER(ctypes.c_int)] * 2
+        lib.oracle_format_constants.restype = ctypes.c_int
+        lib.oracle_quantize_one.argtypes = [ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_quantize_one.restype = ctypes.c_float
+        lib.oracle_quantize.argtypes = [f32p, f32p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_quantize.restype = ctypes.c_int
+        lib.oracle_histogram.argtypes = [f32p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                         ctypes.POINTER(ctypes.c_uint64)]
+        lib.oracle_histogram.restype = ctypes.c_int
+        lib.oracle_gemm.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                    f32p, ctypes.c_int64, f32p, ctypes.c_int64, f32p, ctypes.c_int64,
+                                    ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_gemm.restype = ctypes.c_int
+        lib.oracle_gemm_sampled.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                            ctypes.c_int64, f32p, ctypes.c_int64, f32p, ctypes.c_int64,
+                                            i64p, i64p, ctypes.c_int64, f32p,
+                                            ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_gemm_sampled.restype = ctypes.c_int
+        lib.oracle_encode.argtypes = [ctypes.c_float, ctypes.c_int, ctypes.c_int]
+        lib.oracle_encode.restype = ctypes.c_uint32
+        _lib = lib
+    return _lib
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def format_constants(e: int, m: int) -> dict:
+    """maxN, minN, minD, Emin, Emax of the 1/e/m format (Sec. III; Table I)."""
+    lib = _load()
+    mx, mn, md = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    lo, hi = ctypes.c_int(), ctypes.c_int()
+    rc = lib.oracle_format_constants(e, m, mx, mn, md, lo, hi)
+    if rc:
+        raise ValueError("unsupported format 1/%d/%d" % (e, m))
+    return {"maxN": mx.value, "minN": mn.value, "minD": md.value, "Emin": lo.value, "Emax": hi.value}
+
+
+def quantize(x, e: int, m: int, d: bool) -> np.ndarray:
+    """roundfp(X, e, m, d) of Sec. IV-A on a float32 array; returns a float32 array of the same shape."""
+    lib = _load()
+    xa = _f32(x)
+    y = np.empty_like(xa)
+    rc = lib.oracle_quantize(_ptr(xa), _ptr(y), xa.size, e, m, int(bool(d)))
+    if rc:
+        raise ValueError("unsupported format 1/%d/%d" % (e, m))
+    return y
+
+
+def quantize_one(x: float, e: int, m: int, d: bool) -> np.float32:
+    return np.float32(_load().oracle_quantize_one(np.float32(x), e, m, int(bool(d))))
+
+
+def histogram(x, e: int, m: int, exp_lo: int = -48) -> dict:
+    """Class counts and 64 binade bins of a float32 tensor (Sec. V); integer counts."""
+    lib = _load()
+    xa = _f32(x)
+    out = np.zeros(8 + NBINS, dtype=np.uint64)
+    rc = lib.oracle_histogram(_ptr(xa), xa.size, e, m, exp_lo,
+                              out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)))
+    if rc:
+        raise ValueError("unsupported format 1/%d/%d" % (e, m))
+    res = {name: int(out[i]) for i, name in enumerate(CLASS_NAMES)}
+    res["bins"] = out[8:].copy()
+    return res
+
+
+def _lead(a: np.ndarray) -> int:
+    return a.shape[1] if a.ndim == 2 else 1
+
+
+def gemm(A, B, e: int, m: int, d: bool, transA: bool = False, transB: bool = False) -> np.ndarray:
+    """C = Q(op(A)) Q(op(B)), exact products, fp64 sum rounded once to fp32 (FMACS reference)."""
+    lib = _load()
+    Aa, Ba = _f32(A), _f32(B)
+    M, K = (Aa.shape[1], Aa.shape[0]) if transA else Aa.shape
+    K2, N = (Ba.shape[1], Ba.shape[0]) if transB else Ba.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, K2))
+    C = np.zeros((M, N), dtype=np.float32)
+    rc = lib.oracle_gemm(int(transA), int(transB), M, N, K, _ptr(Aa), max(_lead(Aa), 1),
+                         _ptr(Ba), max(_lead(Ba), 1), _ptr(C), max(N, 1), e, m, int(bool(d)))
+    if rc:
+        raise ValueError("oracle_gemm failed: %d" % rc)
+    return C
+
+
+def gemm_sampled(A, B, rows, cols, e: int, m: int, d: bool,
+                 transA: bool = False, transB: bool = False) -> np.ndarray:
+    """The same sum as :func:`gemm` for the listed output positions only."""
+    lib = _load()
+    Aa, Ba = _f32(A), _f32(B)
+    M, K = (Aa.shape[1], Aa.shape[0]) if transA else Aa.shape
+    K2, N = (Ba.shape[1], Ba.shape[0]) if transB else Ba.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, K2))
+    r = np.ascontiguousarray(rows, dtype=np.int64)
+    c = np.ascontiguousarray(cols, dtype=np.int64)
+    out = np.zeros(r.size, dtype=np.float32)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    rc = lib.oracle_gemm_sampled(int(transA), int(transB), M, N, K, _ptr(Aa), _lead(Aa), _ptr(Ba), _lead(Ba),
+                                 r.ctypes.data_as(i64p), c.ctypes.data_as(i64p), r.size, _ptr(out),
+                                 e, m, int(bool(d)))
+    if rc:
+        raise ValueError("oracle_gemm_sampled failed: %d" % rc)
+    return out
+
+
+def encode(v, e: int, m: int) -> np.ndarray:
+    """(1+e+m)-bit codes of values that already belong to the format (Sec. III encoding)."""
+    lib = _load()
+    va = _f32(v).ravel()
+    return np.array([lib.oracle_encode(float(t), e, m) for t in va], dtype=np.uint32).reshape(np.shape(v))

@@ -1,0 +1,229 @@
+/*
+ * CPU oracle for emulated 1/e/m floating-point arithmetic.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the GPU
+ * library is checked against.  It shares no code, header, table or helper with
+ * the GPU path and must never be called from it.  Only tests, the smoke check and
+ * the benchmark's cpu_baseline leg load it.
+ *
+ * Everything is written from the paper's definitions:
+ *   - a floating-point number x = M * 2^(E-p+1)                      (Sec. III, Def. III.1)
+ *   - normal / denormal split and the hidden-bit convention          (Sec. III)
+ *   - the system quadruple s/e/p/d                                    (Sec. III, Def. III.2)
+ *   - the constants of the three 16-bit formats                      (Table I)
+ *   - roundfp: round each fp32 element to the nearest representable
+ *     value with e exponent bits and p stored mantissa bits, denormal
+ *     range allowed (d) or flushed (n)                                (Sec. IV-A)
+ *   - FMACS matmul: operands in the format, exact products,
+ *     accumulation in a wider type                                    (Sec. III-B, Sec. IV-A)
+ *   - denormal fraction of a tensor                                   (Sec. V)
+ *
+ * Notation used below: e = exponent bits, m = stored mantissa bits (the "p" of
+ * Def. III.2 and Table I), bias = 2^(e-1)-1 ("vanilla" bias), Emax = bias,
+ * Emin = 1-bias, minN = 2^Emin, minD = 2^(Emin-m), maxN = (2-2^-m) * 2^Emax.
+ *
+ * All floating-point work is done in fp64 with frexp / ldexp / nearbyint: an fp32
+ * input has at most 24 significant bits and every scale used is a power of two
+ * >= 2^-149, so each intermediate quantity is exact in fp64.  No bit tricks.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_NBINS 64
+/* layout of the 72-entry count vector written by oracle_histogram */
+enum { O_TOTAL = 0, O_ZERO, O_UNDERFLOW, O_DENORMAL, O_NORMAL, O_OVERFLOW, O_INF, O_NAN, O_BINS };
+
+static int fmt_ok(int e, int m) { return e >= 2 && e <= 8 && m >= 1 && m <= 23; }
+
+/* Closed-form constants of the format (Sec. III; Table I lists three instances). */
+int oracle_format_constants(int e, int m, double *maxN, double *minN, double *minD,
+                            int *Emin, int *Emax)
+{
+    if (!fmt_ok(e, m)) return -1;
+    int bias = (1 << (e - 1)) - 1;
+    int emax = bias, emin = 1 - bias;
+    if (Emin) *Emin = emin;
+    if (Emax) *Emax = emax;
+    if (minN) *minN = ldexp(1.0, emin);
+    if (minD) *minD = ldexp(1.0, emin - m);
+    if (maxN) *maxN = ldexp(2.0 - ldexp(1.0, -m), emax);
+    return 0;
+}
+
+static float canonical_nan(void)
+{
+    uint32_t u = 0x7FC00000u;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/*
+ * Magnitude of Q_{e,m,d}(x) for finite non-zero x, as an fp64 (may be +inf).
+ * Round-to-nearest, ties to even, onto the grid of spacing 2^(max(E,Emin)-m),
+ * where E = floor(log2|x|); anything that rounds to 2^(Emax+1) or more is
+ * overflow and becomes infinity (Sec. IV-A: "nearest representable"; the tie
+ * rule, the overflow rule are the IEEE-754 ones the paper defers to in Sec. III).
+ */
+static double round_magnitude_d(double a, int e, int m)
+{
+    int bias = (1 << (e - 1)) - 1;
+    int emax = bias, emin = 1 - bias;
+    int ex;
+    (void)frexp(a, &ex);          /* a = f * 2^ex with f in [0.5, 1)  =>  E = ex - 1 */
+    int E = ex - 1;
+    int q = (E > emin ? E : emin) - m;
+    double k = nearbyint(ldexp(a, -q));   /* default rounding mode: nearest, ties to even */
+    double r = ldexp(k, q);
+    if (r >= ldexp(1.0, emax + 1)) return INFINITY;
+    return r;
+}
+
+/* roundfp(x, e, m, d) for one element (Sec. IV-A). d != 0: denormal range allowed. */
+float oracle_quantize_one(float x, int e, int m, int d)
+{
+    if (isnan(x)) return canonical_nan();
+    if (isinf(x) || x == 0.0f) return x;                 /* signed zero / infinity kept */
+    double r = round_magnitude_d(fabs((double)x), e, m);
+    if (!d) {                                            /* "n": denormals are flushed to 0 (Sec. V-C) */
+        int emin = 2 - (1 << (e - 1));
+        if (r < ldexp(1.0, emin)) r = 0.0;
+    }
+    return (float)copysign(r, (double)x);                /* exact: r is an fp32 value */
+}
+
+int oracle_quantize(const float *x, float *y, size_t n, int e, int m, int d)
+{
+    if (!fmt_ok(e, m)) return -1;
+    for (size_t i = 0; i < n; ++i) y[i] = oracle_quantize_one(x[i], e, m, d);
+    return 0;
+}
+
+/*
+ * Per-tensor statistics (Sec. V: the denormal fraction of a tensor; the bins are the
+ * distribution of element magnitudes by binade).  out[0..7] = total, zero, underflow,
+ * denormal, normal, overflow, inf, nan; out[8..71] = bins.  Classes are judged on
+ * the value the element has after rounding with denormals allowed; the bin is the
+ * binade floor(log2|x|) of the input, shifted by exp_lo and clamped into [0, 63].
+ * NaN and zero are not binned; infinities go to the top bin.
+ */
+int oracle_histogram(const float *x, size_t n, int e, int m, int exp_lo, uint64_t *out)
+{
+    if (!fmt_ok(e, m)) return -1;
+    int emin = 2 - (1 << (e - 1));
+    double minN = ldexp(1.0, emin);
+    for (int i = 0; i < O_BINS + ORACLE_NBINS; ++i) out[i] = 0;
+    for (size_t i = 0; i < n; ++i) {
+        float v = x[i];
+        out[O_TOTAL]++;
+        if (isnan(v)) { out[O_NAN]++; continue; }
+        if (v == 0.0f) { out[O_ZERO]++; continue; }
+        if (isinf(v)) { out[O_INF]++; out[O_BINS + ORACLE_NBINS - 1]++; continue; }
+        double a = fabs((double)v);
+        double r = round_magnitude_d(a, e, m);
+        if (r == 0.0) out[O_UNDERFLOW]++;
+        else if (isinf(r)) out[O_OVERFLOW]++;
+        else if (r < minN) out[O_DENORMAL]++;
+        else out[O_NORMAL]++;
+        int ex;
+        (void)frexp(a, &ex);
+        long b = (long)(ex - 1) - (long)exp_lo;
+        if (b < 0) b = 0;
+        if (b > ORACLE_NBINS - 1) b = ORACLE_NBINS - 1;
+        out[O_BINS + b]++;
+    }
+    return 0;
+}
+
+/* element (i,k) of op(A), op(A) being M x K: A is M x K row-major, or K x M when transposed */
+static inline float op_at(const float *A, int64_t ld, int trans, int64_t i, int64_t k)
+{
+    return trans ? A[k * ld + i] : A[i * ld + k];
+}
+
+/*
+ * FMACS matrix product (Sec. III-B, Sec. IV-A): C = Q(op(A)) * Q(op(B)), products not
+ * rounded, sum taken in fp64 in plain k order and rounded once to fp32.  The
+ * quantized operands have <= 24-bit significands, so each product is exact in fp64;
+ * the fp64 sum is the reference that an fp32-accumulating FMACS chain approximates.
+ * op(A) is M x K, op(B) is K x N, row-major with leading dimensions in elements.
+ */
+int oracle_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                const float *A, int64_t lda, const float *B, int64_t ldb,
+                float *C, int64_t ldc, int e, int m, int d)
+{
+    if (!fmt_ok(e, m) || M < 0 || N < 0 || K < 0) return -1;
+    if (M == 0 || N == 0) return 0;
+    /* quantized operands, held as fp64; qb is stored N x K so the k loop is contiguous */
+    double *qa = (double *)malloc(sizeof(double) * (size_t)(M * (K ? K : 1)));
+    double *qb = (double *)malloc(sizeof(double) * (size_t)(N * (K ? K : 1)));
+    if (!qa || !qb) { free(qa); free(qb); return -2; }
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t k = 0; k < K; ++k)
+            qa[i * K + k] = (double)oracle_quantize_one(op_at(A, lda, transA, i, k), e, m, d);
+    for (int64_t j = 0; j < N; ++j)
+        for (int64_t k = 0; k < K; ++k)
+            qb[j * K + k] = (double)oracle_quantize_one(op_at(B, ldb, !transB, j, k), e, m, d);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) acc += qa[i * K + k] * qb[j * K + k];
+            C[i * ldc + j] = (float)acc;
+        }
+    }
+    free(qa);
+    free(qb);
+    return 0;
+}
+
+/* The same sum for a list of output positions only: out[s] = C[rows[s], cols[s]]. */
+int oracle_gemm_sampled(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                        const float *A, int64_t lda, const float *B, int64_t ldb,
+                        const int64_t *rows, const int64_t *cols, int64_t nsamples,
+                        float *out, int e, int m, int d)
+{
+    if (!fmt_ok(e, m) || M < 0 || N < 0 || K < 0) return -1;
+    for (int64_t s = 0; s < nsamples; ++s) {
+        int64_t i = rows[s], j = cols[s];
+        if (i < 0 || i >= M || j < 0 || j >= N) return -3;
+        double acc = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double a = (double)oracle_quantize_one(op_at(A, lda, transA, i, k), e, m, d);
+            double b = (double)oracle_quantize_one(op_at(B, ldb, !transB, j, k), e, m, d);
+            acc += a * b;
+        }
+        out[s] = (float)acc;
+    }
+    return 0;
+}
+
+/*
+ * 16-bit (1+e+m-bit) code of a value of the format (Sec. III: stored exponent field 0 for
+ * zero/denormal, all ones for infinity/NaN, hidden bit not stored).  v must already be a
+ * value of the format (the output of oracle_quantize_one).
+ */
+uint32_t oracle_encode(float v, int e, int m)
+{
+    int bias = (1 << (e - 1)) - 1;
+    int emin = 1 - bias;
+    uint32_t sign = signbit(v) ? 1u : 0u;
+    uint32_t top = ((1u << e) - 1u);
+    if (isnan(v)) return (top << m) | (1u << (m - 1));
+    uint32_t field, mant;
+    double a = fabs((double)v);
+    if (isinf(v)) { field = top; mant = 0; }
+    else if (a == 0.0) { field = 0; mant = 0; }
+    else if (a < ldexp(1.0, emin)) { field = 0; mant = (uint32_t)ldexp(a, m - emin); }
+    else {
+        int ex;
+        double f = frexp(a, &ex);             /* a = f*2^ex, f in [0.5,1) */
+        int E = ex - 1;
+        field = (uint32_t)(E + bias);
+        mant = (uint32_t)(ldexp(f, m + 1)) - (1u << m);
+    }
+    return (sign << (e + m)) | (field << m) | mant;
+}
