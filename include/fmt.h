@@ -1,0 +1,190 @@
+/*
+ * libfmt -- emulated mixed-precision training arithmetic in parametrised 1/e/m
+ * floating-point formats on AMD MI355X (gfx950).
+ *
+ * The formats are those of the paper "Representation range needs for 16-bit neural
+ * network training": one sign bit, e exponent bits with the usual ("vanilla") bias
+ * 2^(e-1)-1, m stored mantissa bits with a hidden leading bit, and a flag that says
+ * whether the denormal range is kept ("d") or flushed to zero ("n")  (Sec. III,
+ * Def. III.1 and Def. III.2; Table I lists 1/5/10/d, 1/6/9/d and 1/8/7/n).  Derived
+ * constants: Emax = bias, Emin = 1 - bias, minN = 2^Emin, minD = 2^(Emin-m),
+ * maxN = (2 - 2^-m) * 2^Emax.
+ *
+ * Three operations are exported, each taking the format as the triple the paper's
+ * rounding kernel takes (Sec. IV-A, roundfp_cuda(X, e, p, d)):
+ *
+ *   fmt_quantize   elementwise fp32 -> nearest value of the format (result kept as fp32),
+ *                  optionally fused with the statistics of fmt_histogram
+ *   fmt_histogram  per-tensor statistics: how many elements are zero / underflow /
+ *                  denormal / normal / overflow / inf / nan in the format (the "denormal
+ *                  fraction" the paper logs for every tensor, Sec. V) and a 64-bin
+ *                  histogram of the elements' binades
+ *   fmt_gemm       C = Q(op(A)) * Q(op(B)) with exact products and fp32 accumulation:
+ *                  the FMACS instruction of Sec. III-B applied to a matrix product, as
+ *                  used for fully connected layers and im2col convolutions in forward,
+ *                  dgrad and wgrad (Sec. IV-A)
+ *
+ * Conventions common to all calls
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     frees or keeps caller memory.  `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).  Calls are asynchronous on that stream: results are
+ *     valid once the caller has synchronised with it.
+ *   - The library keeps small per-(device, stream) scratch buffers of its own (partial
+ *     histogram counts; pre-split GEMM operands).  They are created on first use with
+ *     hipMalloc, grow when a larger problem arrives, and live until fmt_release_scratch()
+ *     or process exit.  Calls on one stream are serialised by the stream; calls on
+ *     different streams use different scratch and may overlap.
+ *   - Arguments are validated before any GPU call, so argument errors are reported
+ *     even on a host without a GPU.  No exception or abort crosses this boundary:
+ *     every call returns FMT_OK (0) or a negative fmt_status.
+ *   - Supported formats: 2 <= e <= 8, 1 <= m <= 23 (the upper limits are the paper's,
+ *     Sec. IV-A; the lower limits keep at least one normal binade and one mantissa bit).
+ */
+#ifndef FMT_H_
+#define FMT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fmt_status {
+    FMT_OK = 0,
+    FMT_ERR_FORMAT = -1, /* e outside [2,8] or m outside [1,23]                              */
+    FMT_ERR_NULL = -2,   /* a required pointer is NULL                                       */
+    FMT_ERR_SHAPE = -3,  /* negative dimension, leading dimension too small, size too large  */
+    FMT_ERR_ALIGN = -4,  /* a data pointer is not aligned to its element size                */
+    FMT_ERR_RANGE = -5,  /* exp_lo outside [FMT_EXP_LO_MIN, FMT_EXP_LO_MAX]                  */
+    FMT_ERR_ALIAS = -6,  /* GEMM output overlaps an input                                    */
+    FMT_ERR_HIP = -7     /* a HIP runtime call failed (launch, allocation, no device)        */
+} fmt_status;
+
+/* The format triple of Def. III.2 (sign bits are always 1).
+ * denorm: 1 = "d", denormal range allowed; 0 = "n", denormal results flushed to zero. */
+typedef struct fmt_format {
+    int32_t e;      /* exponent bits,        2..8  */
+    int32_t m;      /* stored mantissa bits, 1..23 (the paper's p of Def. III.2 / Table I) */
+    int32_t denorm; /* 1 = d, 0 = n */
+} fmt_format_t;
+
+#define FMT_NBINS 64
+#define FMT_EXP_LO_MIN (-192)
+#define FMT_EXP_LO_MAX 128
+#define FMT_EXP_LO_DEFAULT (-48)
+
+/*
+ * Per-tensor statistics; lives in DEVICE memory (576 bytes, 8-byte aligned).
+ * All members are integer counts, so the result does not depend on the order in which
+ * the GPU visits the elements.
+ *
+ * Classes are judged on r = |Q_{e,m,d}(x)|, the magnitude after rounding with the
+ * denormal range allowed -- for the "n" variant of a format the `denormal` count is
+ * therefore exactly the number of elements the quantizer flushes:
+ *   nan        x is NaN                         (not binned)
+ *   inf        x is +-infinity                  (counted in the last bin)
+ *   zero       x is +-0                         (not binned)
+ *   underflow  x finite, non-zero, r == 0
+ *   denormal   0 < r < minN
+ *   normal     minN <= r <= maxN
+ *   overflow   x finite, r == infinity
+ * total = number of elements = sum of the seven classes.
+ * bins[b] counts the non-zero, non-NaN elements with
+ *   b = clamp(floor(log2|x|) - exp_lo, 0, FMT_NBINS-1),
+ * i.e. one bin per binade of the INPUT over the window [exp_lo, exp_lo+63]; everything
+ * below the window lands in bin 0, everything above it (and infinities) in bin 63.
+ * The denormal fraction of Sec. V is denormal / total (or / (total - zero)).
+ */
+typedef struct fmt_hist {
+    uint64_t total, zero, underflow, denormal, normal, overflow, inf, nan;
+    uint64_t bins[FMT_NBINS];
+} fmt_hist_t;
+
+/*
+ * fmt_quantize -- the rounding kernel of Sec. IV-A (roundfp_cuda(X, e, p, d)).
+ *
+ *   y[i] = Q_{e,m,d|n}(x[i]) for i in [0, n): round to nearest, ties to even, onto the
+ *   values of the format; magnitudes that round to 2^(Emax+1) or more become +-infinity;
+ *   magnitudes of at most minD/2 become +-0 (the tie at minD/2 goes to zero); with
+ *   denorm == 0 any result below minN is replaced by +-0 (the flush acts on the rounded
+ *   value, so inputs that round up to minN survive).  The sign of x is kept, also on
+ *   zeros.  Any NaN becomes the quiet NaN 0x7FC00000.  fp32-denormal inputs are
+ *   handled exactly.  The result is stored as fp32.
+ *
+ *   x     device, n contiguous floats, 4-byte aligned (16-byte alignment of x and y
+ *         enables the fastest path; any 4-byte alignment is accepted)
+ *   y     device, n floats; y == x (in place) is allowed, partial overlap is not
+ *   hist  device, or NULL.  When given, the statistics of fmt_histogram(x, n, f, hist,
+ *         exp_lo) are produced in the same pass over x; *hist is overwritten.
+ *   n == 0 succeeds without a launch (*hist, when given, is zeroed).
+ *   n must be below 2^40.
+ */
+int fmt_quantize(const float *x, float *y, size_t n, fmt_format_t f,
+                 fmt_hist_t *hist, int32_t exp_lo, void *stream);
+
+/*
+ * fmt_histogram -- per-tensor statistics without writing a quantized copy (the
+ * logging of Sec. V: denormal fraction of activations, weights and gradients).
+ * *hist (device) is overwritten with the counts described at fmt_hist_t.  The counts
+ * do not depend on f.denorm.  n == 0 zeroes *hist.  n must be below 2^40.
+ */
+int fmt_histogram(const float *x, size_t n, fmt_format_t f,
+                  fmt_hist_t *hist, int32_t exp_lo, void *stream);
+
+/*
+ * fmt_gemm -- matrix product with FMACS semantics (Sec. III-B: a32 = o(a32 + x16*y16);
+ * Sec. IV-A: operands are rounded to the format, products are not rounded).
+ *
+ *   C[i][j] = sum_k Q(op(A))[i][k] * Q(op(B))[k][j],   i < M, j < N, k < K
+ *
+ * Each product is exact; the sum is accumulated in fp32 (order unspecified) and C is
+ * returned as unrounded fp32 -- the caller applies fmt_quantize to C where the layer
+ * formula of Sec. IV-A rounds the output.  Row-major storage, leading dimensions in
+ * elements:
+ *   transA == 0: A is M x K (lda >= K);   transA != 0: A is K x M (lda >= M)
+ *   transB == 0: B is K x N (ldb >= N);   transB != 0: B is N x K (ldb >= K)
+ *   C is M x N (ldc >= N).
+ * A fully connected layer Y = X W^T is (transA, transB) = (0, 1); its dgrad dX = dY W is
+ * (0, 0); its wgrad dW = dY^T X is (1, 0).  A convolution is the same three products on
+ * the im2col matrix, which the caller materialises.
+ * A, B, C are device pointers, 4-byte aligned; C must not overlap A or B.  M, N or K
+ * equal to 0 succeeds (K == 0 with M, N > 0 zero-fills C).  Dimensions must be below 2^31.
+ * Infinite or NaN operands (including finite inputs that overflow the format) give
+ * non-finite results in the affected outputs; whether such an output is an infinity or
+ * a NaN is not specified.
+ */
+int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda, const float *B, int64_t ldb,
+             float *C, int64_t ldc, fmt_format_t f, void *stream);
+
+/*
+ * fmt_format_info -- closed-form constants of a format (Sec. III; Table I), computed on
+ * the host.  Any output pointer may be NULL.  Returns FMT_ERR_FORMAT for an unsupported
+ * format.
+ */
+int fmt_format_info(fmt_format_t f, double *maxN, double *minN, double *minD,
+                    int32_t *Emin, int32_t *Emax);
+
+/*
+ * fmt_format_thresholds -- the three decision thresholds of a format on the fp32 bit pattern
+ * of |x| (sign bit cleared; the pattern is monotone in |x|), computed on the host:
+ *   out[0] = t_zero: Q(x) is +-0            <=>  pattern <= t_zero   (pattern of minD/2)
+ *   out[1] = t_den:  |Q_d(x)| < minN        <=>  pattern <  t_den    (pattern of minN - minD/2)
+ *   out[2] = t_ovf:  Q(x) is +-infinity     <=>  pattern >= t_ovf, pattern <= 0x7F800000
+ * These are the comparisons the kernels use for the underflow, flush and overflow rules of
+ * fmt_quantize and for the classes of fmt_hist_t; exported so that they can be checked on a
+ * host without a GPU.  out is a HOST pointer to three uint32_t.
+ */
+int fmt_format_thresholds(fmt_format_t f, uint32_t *out);
+
+/* Frees the library-owned scratch buffers of the current device (synchronises it first). */
+int fmt_release_scratch(void);
+
+/* Human-readable name of a status code; never NULL. */
+const char *fmt_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FMT_H_ */

@@ -1,0 +1,207 @@
+"""Thin Python binding of libfmt (C ABI declared in ``include/fmt.h``).
+
+Argument marshalling only: every step of the path -- the rounding kernel of Sec. IV-A, the
+per-tensor statistics of Sec. V and the FMACS matrix product of Sec. III-B -- runs in the
+hand-written HIP kernels behind the C ABI.  PyTorch is used for device memory and streams.
+There is no CPU fallback: if ``libfmt.so`` has not been built, importing this package raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfmt.so")
+
+FMT_NBINS = 64
+EXP_LO_DEFAULT = -48
+CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
+EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_format_info", "fmt_format_thresholds",
+           "fmt_release_scratch", "fmt_status_string")
+
+
+class Format(NamedTuple):
+    """The triple of Def. III.2: e exponent bits, m stored mantissa bits, denormals kept or flushed."""
+    e: int
+    m: int
+    denorm: bool = True
+
+    @property
+    def name(self) -> str:
+        return "1/%d/%d/%s" % (self.e, self.m, "d" if self.denorm else "n")
+
+
+BINARY16 = Format(5, 10, True)
+BFLOAT16 = Format(8, 7, False)
+FP169 = Format(6, 9, True)
+
+
+class _CFormat(ctypes.Structure):
+    _fields_ = [("e", ctypes.c_int32), ("m", ctypes.c_int32), ("denorm", ctypes.c_int32)]
+
+
+class FmtError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libfmt.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(or `python paper_2103_15940_amd/build.py`) first; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.fmt_quantize.argtypes = [vp, vp, sz, _CFormat, vp, i32, vp]
+    lib.fmt_quantize.restype = ctypes.c_int
+    lib.fmt_histogram.argtypes = [vp, sz, _CFormat, vp, i32, vp]
+    lib.fmt_histogram.restype = ctypes.c_int
+    lib.fmt_gemm.argtypes = [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64, vp, i64, _CFormat, vp]
+    lib.fmt_gemm.restype = ctypes.c_int
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+    lib.fmt_format_info.argtypes = [_CFormat, dp, dp, dp, ip, ip]
+    lib.fmt_format_info.restype = ctypes.c_int
+    lib.fmt_format_thresholds.argtypes = [_CFormat, ctypes.POINTER(ctypes.c_uint32)]
+    lib.fmt_format_thresholds.restype = ctypes.c_int
+    lib.fmt_release_scratch.argtypes = []
+    lib.fmt_release_scratch.restype = ctypes.c_int
+    lib.fmt_status_string.argtypes = [ctypes.c_int]
+    lib.fmt_status_string.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def _cfmt(f) -> _CFormat:
+    e, m, d = f
+    return _CFormat(int(e), int(m), 1 if d else 0)
+
+
+def status_string(status: int) -> str:
+    return _lib.fmt_status_string(int(status)).decode()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise FmtError(rc, where)
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_f32(t, name: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.float32:
+        raise TypeError("%s must be a float32 tensor on the GPU" % name)
+    return t
+
+
+def new_hist(device="cuda"):
+    """Device buffer for one fmt_hist_t (72 x int64)."""
+    import torch
+    return torch.empty(8 + FMT_NBINS, dtype=torch.int64, device=device)
+
+
+def hist_to_dict(hist) -> dict:
+    """Copies a device fmt_hist_t to the host: class counts as ints, bins as a numpy uint64 array."""
+    import numpy as np
+    h = hist.cpu().numpy().astype(np.uint64)
+    out = {name: int(h[i]) for i, name in enumerate(CLASS_NAMES)}
+    out["bins"] = h[8:].copy()
+    return out
+
+
+def fmt_quantize(x, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None):
+    """y = Q_{e,m,d|n}(x) elementwise (Sec. IV-A roundfp); ``out`` may be ``x`` itself.  When a
+    ``hist`` buffer (see :func:`new_hist`) is given, the statistics of :func:`fmt_histogram` are
+    produced in the same pass.  Asynchronous on ``stream`` (default: torch's current stream)."""
+    import torch
+    _dev_f32(x, "x")
+    if not x.is_contiguous():
+        raise ValueError("x must be contiguous")
+    if out is None:
+        out = torch.empty_like(x)
+    _dev_f32(out, "out")
+    if not out.is_contiguous() or out.numel() != x.numel():
+        raise ValueError("out must be contiguous and as large as x")
+    hp = None
+    if hist is not None:
+        if hist.dtype != torch.int64 or hist.numel() != 8 + FMT_NBINS or not hist.is_cuda:
+            raise TypeError("hist must be a GPU int64 tensor of 72 elements")
+        hp = hist.data_ptr()
+    rc = _lib.fmt_quantize(x.data_ptr(), out.data_ptr(), x.numel(), _cfmt(fmt), hp, int(exp_lo), _stream_ptr(stream))
+    _check(rc, "fmt_quantize")
+    return out
+
+
+def fmt_histogram(x, fmt, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None):
+    """Per-tensor class counts and 64 binade bins (Sec. V) into a device fmt_hist_t; returns it."""
+    import torch
+    _dev_f32(x, "x")
+    if not x.is_contiguous():
+        raise ValueError("x must be contiguous")
+    if hist is None:
+        hist = new_hist(x.device)
+    if hist.dtype != torch.int64 or hist.numel() != 8 + FMT_NBINS or not hist.is_cuda:
+        raise TypeError("hist must be a GPU int64 tensor of 72 elements")
+    rc = _lib.fmt_histogram(x.data_ptr(), x.numel(), _cfmt(fmt), hist.data_ptr(), int(exp_lo), _stream_ptr(stream))
+    _check(rc, "fmt_histogram")
+    return hist
+
+
+def fmt_gemm(A, B, fmt, transA: bool = False, transB: bool = False, out=None, stream=None):
+    """C = Q(op(A)) Q(op(B)) with exact products and fp32 accumulation (FMACS, Sec. III-B).
+    A, B are 2-D row-major float32 GPU tensors (a row stride larger than the row length is
+    passed on as the leading dimension)."""
+    import torch
+    for t, name in ((A, "A"), (B, "B")):
+        _dev_f32(t, name)
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("%s must be 2-D with unit column stride" % name)
+    M, K = (A.shape[1], A.shape[0]) if transA else (A.shape[0], A.shape[1])
+    K2, N = (B.shape[1], B.shape[0]) if transB else (B.shape[0], B.shape[1])
+    if K != K2:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, K2))
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    _dev_f32(out, "out")
+    if out.dim() != 2 or tuple(out.shape) != (M, N) or (N > 1 and out.stride(1) != 1):
+        raise ValueError("out must be an M x N tensor with unit column stride")
+    lda = A.stride(0) if A.shape[0] > 1 else max(A.shape[1], 1)
+    ldb = B.stride(0) if B.shape[0] > 1 else max(B.shape[1], 1)
+    ldc = out.stride(0) if M > 1 else max(N, 1)
+    rc = _lib.fmt_gemm(int(transA), int(transB), M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb,
+                       out.data_ptr(), ldc, _cfmt(fmt), _stream_ptr(stream))
+    _check(rc, "fmt_gemm")
+    return out
+
+
+def fmt_format_info(fmt) -> dict:
+    """Closed-form constants of a format (Sec. III; Table I)."""
+    mx, mn, md = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    lo, hi = ctypes.c_int32(), ctypes.c_int32()
+    _check(_lib.fmt_format_info(_cfmt(fmt), mx, mn, md, lo, hi), "fmt_format_info")
+    return {"maxN": mx.value, "minN": mn.value, "minD": md.value, "Emin": lo.value, "Emax": hi.value}
+
+
+def fmt_format_thresholds(fmt) -> dict:
+    """Bit-pattern thresholds of the underflow, flush and overflow rules (host computation)."""
+    out = (ctypes.c_uint32 * 3)()
+    _check(_lib.fmt_format_thresholds(_cfmt(fmt), out), "fmt_format_thresholds")
+    return {"t_zero": int(out[0]), "t_den": int(out[1]), "t_ovf": int(out[2])}
+
+
+def fmt_release_scratch() -> None:
+    _check(_lib.fmt_release_scratch(), "fmt_release_scratch")
+
+
+def raw_library() -> ctypes.CDLL:
+    """The loaded C library (for tests of the C ABI itself)."""
+    return _lib

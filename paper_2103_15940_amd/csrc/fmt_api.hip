@@ -1,0 +1,229 @@
+// C-ABI entry points of libfmt: argument validation, format constants, scratch management.
+// The arithmetic lives in fmt_stream.hip (quantize / histogram) and fmt_gemm.hip.
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
+
+#include "fmt_internal.h"
+
+namespace fmt {
+
+static bool format_ok(fmt_format_t f) { return f.e >= 2 && f.e <= 8 && f.m >= 1 && f.m <= 23; }
+
+// Thresholds of the format on the fp32 bit pattern of |x| (Sec. III: Emax = bias,
+// Emin = 1 - bias, minD = 2^(Emin-m); rounding is to nearest, ties to even).
+int make_quant_params(fmt_format_t f, int32_t exp_lo, QuantParams *p)
+{
+    if (!format_ok(f)) return FMT_ERR_FORMAT;
+    if (exp_lo < FMT_EXP_LO_MIN || exp_lo > FMT_EXP_LO_MAX) return FMT_ERR_RANGE;
+    const int e = f.e, m = f.m;
+    const int bias = (1 << (e - 1)) - 1;
+    const int emin = 1 - bias, emax = bias;
+    const uint32_t shift = 23u - (uint32_t)m;
+    const uint32_t minn_bits = (uint32_t)(emin + 127) << 23;
+
+    p->shift = shift;
+    p->lsb_width = shift ? 1u : 0u;
+    p->rbias = shift ? ((1u << (shift - 1)) - 1u) : 0u;
+    p->nmask = ~((1u << shift) - 1u);
+    p->mode = (e == 8) ? 1 : (m <= 22 ? 0 : 2);
+    p->minn_bits = minn_bits;
+    p->shift23 = shift << 23;
+    const uint32_t cbits = (uint32_t)(emin + 23 - m + 127) << 23;  // 2^(Emin+23-m), a normal fp32 for every e, m
+    std::memcpy(&p->cmagic, &cbits, sizeof(float));
+
+    if (e < 8) {
+        // minD/2 = 2^(Emin-m-1) is a normal fp32; below minN the fp32 spacing is 2^(Emin-24)
+        p->t_zero = (uint32_t)(emin - m - 1 + 127) << 23;
+        p->t_den = minn_bits - (1u << shift);
+    } else {
+        // Emin = -126 is fp32's own: inputs below minN are fp32 denormals, spacing 2^-149
+        p->t_zero = (m <= 22) ? (1u << (22 - m)) : 0u;
+        p->t_den = (m <= 22) ? minn_bits - (1u << (22 - m)) : minn_bits;
+    }
+    const uint32_t maxn_bits = ((uint32_t)(emax + 127) << 23) | (((1u << m) - 1u) << shift);
+    p->t_ovf = (m <= 22) ? maxn_bits + (1u << (shift - 1)) : (uint32_t)(emax + 128) << 23;
+    p->exp_lo = exp_lo;
+    return FMT_OK;
+}
+
+// ------------------------------------------------------------------ scratch
+static std::mutex g_mu;
+static std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
+
+static int grow(void **buf, size_t *have, size_t want)
+{
+    if (want <= *have) return FMT_OK;
+    if (*buf) {
+        FMT_HIP_CHECK(hipFree(*buf));  // synchronises the device: no kernel still uses it
+        *buf = nullptr;
+        *have = 0;
+    }
+    size_t cap = (want + 4095) & ~(size_t)4095;
+    FMT_HIP_CHECK(hipMalloc(buf, cap));
+    *have = cap;
+    return FMT_OK;
+}
+
+int get_scratch(hipStream_t stream, size_t hist_bytes, size_t gemm_bytes, Scratch *out)
+{
+    int dev = 0;
+    FMT_HIP_CHECK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_mu);
+    Scratch &s = g_scratch[std::make_pair(dev, stream)];
+    int rc = grow(&s.hist_partials, &s.hist_bytes, hist_bytes);
+    if (rc != FMT_OK) return rc;
+    rc = grow(&s.gemm_ws, &s.gemm_bytes, gemm_bytes);
+    if (rc != FMT_OK) return rc;
+    *out = s;
+    return FMT_OK;
+}
+
+int device_cu_count(int *cus)
+{
+    static std::mutex mu;
+    static std::map<int, int> cache;
+    int dev = 0;
+    FMT_HIP_CHECK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = cache.find(dev);
+    if (it == cache.end()) {
+        int n = 0;
+        FMT_HIP_CHECK(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        it = cache.emplace(dev, n > 0 ? n : 256).first;
+    }
+    *cus = it->second;
+    return FMT_OK;
+}
+
+static bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static bool overlap(const void *a, size_t abytes, const void *b, size_t bbytes)
+{
+    uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+}  // namespace fmt
+
+using namespace fmt;
+
+extern "C" {
+
+int fmt_quantize(const float *x, float *y, size_t n, fmt_format_t f,
+                 fmt_hist_t *hist, int32_t exp_lo, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, hist ? exp_lo : FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (n >= ((size_t)1 << 40)) return FMT_ERR_SHAPE;
+    if (n > 0 && (!x || !y)) return FMT_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y, 4) || !aligned(hist, 8)) return FMT_ERR_ALIGN;
+    if (n > 0 && x != y && overlap(x, n * 4, y, n * 4)) return FMT_ERR_ALIAS;
+    if (n == 0 && !hist) return FMT_OK;
+    return launch_stream(x, y, n, p, f.denorm == 0, hist, static_cast<hipStream_t>(stream));
+}
+
+int fmt_histogram(const float *x, size_t n, fmt_format_t f,
+                  fmt_hist_t *hist, int32_t exp_lo, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, exp_lo, &p);
+    if (rc != FMT_OK) return rc;
+    if (n >= ((size_t)1 << 40)) return FMT_ERR_SHAPE;
+    if (!hist || (n > 0 && !x)) return FMT_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(hist, 8)) return FMT_ERR_ALIGN;
+    return launch_stream(x, nullptr, n, p, false, hist, static_cast<hipStream_t>(stream));
+}
+
+int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda, const float *B, int64_t ldb,
+             float *C, int64_t ldc, fmt_format_t f, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    const int64_t lim = (int64_t)1 << 31;
+    if (M < 0 || N < 0 || K < 0 || M >= lim || N >= lim || K >= lim) return FMT_ERR_SHAPE;
+    if (M == 0 || N == 0) return FMT_OK;
+    if (!C) return FMT_ERR_NULL;
+    if (K > 0 && (!A || !B)) return FMT_ERR_NULL;
+    if (ldc < N) return FMT_ERR_SHAPE;
+    if (K > 0) {
+        if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return FMT_ERR_SHAPE;
+        if (lda >= lim || ldb >= lim) return FMT_ERR_SHAPE;
+    }
+    if (ldc >= lim) return FMT_ERR_SHAPE;
+    if (!aligned(A, 4) || !aligned(B, 4) || !aligned(C, 4)) return FMT_ERR_ALIGN;
+    if (K > 0) {
+        const size_t abytes = 4 * (size_t)(((transA ? K : M) - 1) * lda + (transA ? M : K));
+        const size_t bbytes = 4 * (size_t)(((transB ? N : K) - 1) * ldb + (transB ? K : N));
+        const size_t cbytes = 4 * (size_t)((M - 1) * ldc + N);
+        if (overlap(C, cbytes, A, abytes) || overlap(C, cbytes, B, bbytes)) return FMT_ERR_ALIAS;
+    }
+    return launch_gemm(transA != 0, transB != 0, M, N, K, A, lda, B, ldb, C, ldc, f, p,
+                       static_cast<hipStream_t>(stream));
+}
+
+int fmt_format_info(fmt_format_t f, double *maxN, double *minN, double *minD,
+                    int32_t *Emin, int32_t *Emax)
+{
+    if (!format_ok(f)) return FMT_ERR_FORMAT;
+    const int bias = (1 << (f.e - 1)) - 1;
+    const int emin = 1 - bias, emax = bias;
+    if (Emin) *Emin = emin;
+    if (Emax) *Emax = emax;
+    if (minN) *minN = std::ldexp(1.0, emin);
+    if (minD) *minD = std::ldexp(1.0, emin - f.m);
+    if (maxN) *maxN = std::ldexp(2.0 - std::ldexp(1.0, -f.m), emax);
+    return FMT_OK;
+}
+
+int fmt_format_thresholds(fmt_format_t f, uint32_t *out)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (!out) return FMT_ERR_NULL;
+    out[0] = p.t_zero;
+    out[1] = p.t_den;
+    out[2] = p.t_ovf;
+    return FMT_OK;
+}
+
+int fmt_release_scratch(void)
+{
+    int dev = 0;
+    FMT_HIP_CHECK(hipGetDevice(&dev));
+    FMT_HIP_CHECK(hipDeviceSynchronize());
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (auto it = g_scratch.begin(); it != g_scratch.end();) {
+        if (it->first.first == dev) {
+            if (it->second.hist_partials) (void)hipFree(it->second.hist_partials);
+            if (it->second.gemm_ws) (void)hipFree(it->second.gemm_ws);
+            it = g_scratch.erase(it);
+        } else {
+            ++it;
+        }
+    }
+    return FMT_OK;
+}
+
+const char *fmt_status_string(int status)
+{
+    switch (status) {
+        case FMT_OK: return "ok";
+        case FMT_ERR_FORMAT: return "unsupported format: need 2 <= e <= 8 and 1 <= m <= 23";
+        case FMT_ERR_NULL: return "a required pointer is NULL";
+        case FMT_ERR_SHAPE: return "bad shape: negative or too large dimension, or leading dimension too small";
+        case FMT_ERR_ALIGN: return "a data pointer is not aligned to its element size";
+        case FMT_ERR_RANGE: return "exp_lo outside the supported window range";
+        case FMT_ERR_ALIAS: return "output overlaps an input";
+        case FMT_ERR_HIP: return "a HIP runtime call failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

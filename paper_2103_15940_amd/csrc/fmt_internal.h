@@ -1,0 +1,64 @@
+// Internal declarations shared by the translation units of libfmt (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fmt.h"
+
+namespace fmt {
+
+// Bit-level description of one format, derived on the host from (e, m) (Sec. III).
+// All thresholds are on a = |x| taken as an unsigned integer (the fp32 bit pattern with
+// the sign cleared), which is monotone in |x| over zeros, denormals, normals and infinity.
+struct QuantParams {
+    uint32_t shift;       // 23 - m: low fp32 mantissa bits that the format drops
+    uint32_t lsb_width;   // 1 when shift > 0, else 0 (width of the "last kept bit" field)
+    uint32_t rbias;       // 2^(shift-1) - 1 (0 when shift == 0): RNE = add rbias + last kept bit, truncate
+    uint32_t nmask;       // ~(2^shift - 1)
+    int32_t mode;         // how the rounding is carried out (see fmt_stream.hip)
+    uint32_t minn_bits;   // pattern of minN = 2^Emin
+    uint32_t shift23;     // shift << 23: added to an exponent field it gives the pattern of 2^(E+23-m)
+    float cmagic;         // 2^(Emin + 23 - m): adding and subtracting it rounds to a multiple of minD
+    uint32_t t_zero;      // result is zero        <=>  a <= t_zero   (minD/2, the tie goes to zero)
+    uint32_t t_den;       // result is below minN  <=>  a <  t_den    (minN - minD/2, the tie goes to minN)
+    uint32_t t_ovf;       // result is infinite    <=>  a >= t_ovf    (maxN + ulp/2, the tie goes to infinity)
+    int32_t exp_lo;       // lowest binade of the histogram window
+};
+
+// Fills p from the format; returns FMT_OK or FMT_ERR_FORMAT / FMT_ERR_RANGE.
+int make_quant_params(fmt_format_t f, int32_t exp_lo, QuantParams *p);
+
+// Library-owned scratch of one (device, stream) pair.
+struct Scratch {
+    void *hist_partials = nullptr;  // per-workgroup partial counts of the stream kernels
+    size_t hist_bytes = 0;
+    void *gemm_ws = nullptr;        // pre-split GEMM operands
+    size_t gemm_bytes = 0;
+};
+
+// Returns the scratch record for (current device, stream), growing the requested buffers.
+int get_scratch(hipStream_t stream, size_t hist_bytes, size_t gemm_bytes, Scratch *out);
+
+int device_cu_count(int *cus);
+
+// Stream kernels (fmt_stream.hip)
+int launch_stream(const float *x, float *y, size_t n, const QuantParams &p, bool ftz,
+                  fmt_hist_t *hist, hipStream_t stream);
+
+// GEMM (fmt_gemm.hip)
+int launch_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                const float *A, int64_t lda, const float *B, int64_t ldb,
+                float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
+
+#define FMT_HIP_CHECK(expr)                          \
+    do {                                             \
+        hipError_t err__ = (expr);                   \
+        if (err__ != hipSuccess) {                   \
+            (void)hipGetLastError();                 \
+            return FMT_ERR_HIP;                      \
+        }                                            \
+    } while (0)
+
+}  // namespace fmt

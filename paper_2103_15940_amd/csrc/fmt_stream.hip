@@ -1,0 +1,338 @@
+// Stream kernels of libfmt: the rounding kernel of Sec. IV-A (fp32 -> 1/e/m, result kept as
+// fp32) and the per-tensor statistics of Sec. V, separately or fused in one pass over x.
+//
+// Both are HBM streams: 4 B read (+ 4 B written) per element, 128-bit accesses, a persistent
+// grid-stride launch.  The rounding works on the fp32 bit pattern:
+//   * e < 8: the format's grid around |x| has spacing 2^(max(E,Emin)-m), E = floor(log2|x|), and
+//     (|x| + C) - C with C = 2^(max(E,Emin)+23-m) lands on it with the hardware's own RNE --
+//     exact, since the addition is one correctly rounded fp32 operation whose ulp is that
+//     spacing and the subtraction is exact.  C comes from the exponent field of |x| with two
+//     integer operations.  fp32-denormal inputs are far below minD/2 there, so a flush of
+//     them could only give the same zero;
+//   * e = 8: fp32's own denormal grid is the format's, so round-to-nearest-even is done on the
+//     integer pattern (add "half minus one plus the last kept bit", clear the dropped bits; a
+//     mantissa carry walks into the exponent by itself), fp32-denormal inputs included;
+//   * overflow, zero and flush decisions are comparisons of |x|'s pattern with thresholds
+//     computed on the host (the ties at minD/2, minN - minD/2 and maxN + ulp/2 all go to the
+//     even neighbour).
+// Statistics: each element adds one to an LDS table indexed by its 8-bit fp32 exponent field,
+// replicated 32 times so that lane l only ever touches bank l%32 (no bank or address
+// conflicts, however concentrated the distribution); the class counts are per-lane
+// compare-and-add counters.  Each workgroup folds its table into 64 bins and writes one
+// partial record; a second tiny kernel sums the records into the caller's fmt_hist_t.
+#include "fmt_internal.h"
+
+namespace fmt {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 512;              // threads per workgroup
+constexpr int kCopies = 32;              // replicas of the exponent table (one per LDS bank)
+constexpr int kRows = 256 + 24;          // exponent fields 0..255, then the 23 binades of fp32 denormals
+constexpr int kUnroll = 4;               // independent 128-bit loads in flight per thread
+constexpr int kSlots = 72;               // uint64 per partial record
+// slots of a partial record
+enum { P_Z = 0, P_ZU, P_ZUD, P_TOP, P_INFNAN, P_NAN, P_BINS = 8 };
+
+struct Counts {                          // per-lane counters, reduced once at the end
+    uint32_t z = 0, zu = 0, zud = 0, top = 0, infnan = 0, nan = 0;
+};
+
+// How the rounding is carried out (uniform per launch, chosen on the host from (e, m)):
+enum : int {
+    kModeMagic = 0,    // e < 8, m <= 22: (|x| + C) - C with C = 2^(max(E, Emin) + 23 - m)
+    kModeInteger = 1,  // e == 8: RNE on the integer pattern (fp32's denormal grid is the format's own)
+    kModeMixed = 2     // e < 8, m == 23: nothing to round at or above minN, fixed grid below
+};
+
+// Q_{e,m,d|n} on one fp32 bit pattern.
+template <int MODE, bool FTZ>
+__device__ __forceinline__ uint32_t quantize_bits(uint32_t u, const QuantParams &p)
+{
+    const uint32_t a = u & 0x7FFFFFFFu;
+    uint32_t r;
+    if (MODE == kModeMagic) {
+        // C has ulp 2^(max(E,Emin)-m) and |x| < C, so the hardware's RNE addition lands on the
+        // format's grid and the subtraction is exact.  For |x| >= t_ovf the pattern of C may be
+        // meaningless; those lanes are overwritten below.
+        const uint32_t ce = max(a & 0x7F800000u, p.minn_bits) + p.shift23;
+        const float c = __uint_as_float(ce);
+        r = __float_as_uint((__uint_as_float(a) + c) - c);
+    } else if (MODE == kModeInteger) {
+        const uint32_t lsb = __builtin_amdgcn_ubfe(a, p.shift, p.lsb_width);
+        r = (a + p.rbias + lsb) & p.nmask;
+    } else {
+        const float rbf = (__uint_as_float(a) + p.cmagic) - p.cmagic;
+        r = (a < p.minn_bits) ? __float_as_uint(rbf) : a;
+    }
+    if (FTZ) r = (a < p.t_den) ? 0u : r;
+    r = (a >= p.t_ovf) ? 0x7F800000u : r;
+    r |= (u & 0x80000000u);
+    return (a > 0x7F800000u) ? 0x7FC00000u : r;
+}
+
+// Statistics of one element: one LDS increment and four compare-and-count steps (six when the
+// wave holds an overflowing or non-finite element).
+template <bool DEEP>
+__device__ __forceinline__ void account(uint32_t a, bool valid, const QuantParams &p, uint32_t *tbl,
+                                        uint32_t lane32, Counts &w)
+{
+    uint32_t row = a >> 23;
+    if (DEEP) {
+        // fp32-denormal inputs get a row per binade so that windows reaching below 2^-126 stay exact
+        if (a - 1u < 0x007FFFFFu) row = 256u + (31u - (uint32_t)__builtin_clz(a));
+    }
+    if (valid) __hip_atomic_fetch_add(&tbl[row * kCopies + lane32], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    w.z += (valid && a == 0u) ? 1u : 0u;
+    w.zu += (valid && a <= p.t_zero) ? 1u : 0u;
+    w.zud += (valid && a < p.t_den) ? 1u : 0u;
+    const bool top = valid && a >= p.t_ovf;
+    if (__ballot(top)) {                 // wave-uniform: rare for real tensors
+        w.top += top ? 1u : 0u;
+        w.infnan += (valid && a >= 0x7F800000u) ? 1u : 0u;
+        w.nan += (valid && a > 0x7F800000u) ? 1u : 0u;
+    }
+}
+
+template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP>
+__device__ __forceinline__ u32x4 do_vec(u32x4 v, bool valid, const QuantParams &p, uint32_t *tbl, uint32_t lane32,
+                                        Counts &w)
+{
+    u32x4 o = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t u = v[j];
+        if (HIST) account<DEEP>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
+        if (STORE) o[j] = quantize_bits<MODE, FTZ>(u, p);
+    }
+    return o;
+}
+
+// x, y: element pointers.  The vector body covers elements [head, head + 4*nvec) and needs
+// x + head (and y + head when STORE) 16-byte aligned; the at most 6 remaining elements at both
+// ends are handled one per lane by the first wave of workgroup 0.  VEC = false is the fallback
+// for x and y misaligned relative to each other: the whole range goes one dword per lane.
+template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC>
+__global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restrict__ x, uint32_t *__restrict__ y,
+                                                        size_t n, size_t head, size_t nvec, QuantParams p,
+                                                        unsigned long long *__restrict__ partials)
+{
+    __shared__ uint32_t tbl[HIST ? kRows * kCopies : 1];
+    __shared__ uint32_t s_bins[FMT_NBINS];
+    __shared__ uint32_t s_cls[8];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane32 = tid & (kCopies - 1);
+    Counts w;
+
+    if (HIST) {
+        for (int i = tid; i < kRows * kCopies; i += kBlock) tbl[i] = 0;
+        if (tid < FMT_NBINS) s_bins[tid] = 0;
+        if (tid < 8) s_cls[tid] = 0;
+        __syncthreads();
+    }
+
+    if (VEC) {
+        const u32x4 *xv = reinterpret_cast<const u32x4 *>(x + head);
+        u32x4 *yv = reinterpret_cast<u32x4 *>(y + head);
+        const size_t stride = (size_t)gridDim.x * kBlock;
+        // Loop bounds are taken from the wave's first lane so that every trip is wave-uniform.
+        const uint32_t lane = tid & 63u;
+        size_t ib = (size_t)blockIdx.x * kBlock + __builtin_amdgcn_readfirstlane(tid & ~63u);
+        for (; ib + 63 + (kUnroll - 1) * stride < nvec; ib += kUnroll * stride) {
+            const size_t i = ib + lane;
+            u32x4 v[kUnroll];
+#pragma unroll
+            for (int k = 0; k < kUnroll; ++k) v[k] = __builtin_nontemporal_load(xv + i + k * stride);
+#pragma unroll
+            for (int k = 0; k < kUnroll; ++k) {
+                u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v[k], true, p, tbl, lane32, w);
+                if (STORE) __builtin_nontemporal_store(o, yv + i + k * stride);
+            }
+        }
+        for (; ib < nvec; ib += stride) {
+            const size_t i = ib + lane;
+            const bool valid = i < nvec;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (valid) v = __builtin_nontemporal_load(xv + i);
+            u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v, valid, p, tbl, lane32, w);
+            if (STORE && valid) __builtin_nontemporal_store(o, yv + i);
+        }
+        if (blockIdx.x == 0 && tid < 64) {
+            // leftovers: [0, head) and [head + 4*nvec, n)
+            const size_t body_end = head + 4 * nvec;
+            const size_t ntail = n - body_end;
+            size_t idx = tid < head ? tid : body_end + (tid - head);
+            const bool valid = tid < head + ntail;
+            if (!valid) idx = 0;
+            const uint32_t u = valid ? x[idx] : 0u;
+            if (HIST) account<DEEP>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
+            if (STORE && valid) y[idx] = quantize_bits<MODE, FTZ>(u, p);
+        }
+    } else {
+        const size_t stride = (size_t)gridDim.x * kBlock;
+        // every lane runs the same number of trips
+        const size_t trips = (n + stride - 1) / stride;
+        size_t i = (size_t)blockIdx.x * kBlock + tid;
+        for (size_t t = 0; t < trips; ++t, i += stride) {
+            const bool valid = i < n;
+            const uint32_t u = valid ? x[i] : 0u;
+            if (HIST) account<DEEP>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
+            if (STORE && valid) y[i] = quantize_bits<MODE, FTZ>(u, p);
+        }
+    }
+
+    if (HIST) {
+        uint32_t c[6] = {w.z, w.zu, w.zud, w.top, w.infnan, w.nan};
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) c[q] += __shfl_xor(c[q], off, 64);
+        }
+        if ((tid & 63) == 0) {
+#pragma unroll
+            for (int q = 0; q < 6; ++q) if (c[q]) atomicAdd(&s_cls[q], c[q]);
+        }
+        __syncthreads();
+        if (tid < kRows) {
+            uint32_t sum = 0;
+#pragma unroll 8
+            for (int c = 0; c < kCopies; ++c) sum += tbl[tid * kCopies + ((c + tid) & (kCopies - 1))];
+            int E;
+            if (tid < 256) {
+                E = (int)tid - 127;
+                if (tid == 0) sum -= s_cls[P_Z];      // zeros are not binned; what is left are fp32 denormals
+                if (tid == 255) { sum -= s_cls[P_NAN]; E = 1 << 20; }   // infinities -> top bin, NaN not binned
+            } else {
+                E = (int)tid - 256 - 149;             // binade of an fp32 denormal with leading bit tid-256
+            }
+            int b = E - p.exp_lo;
+            b = b < 0 ? 0 : (b > FMT_NBINS - 1 ? FMT_NBINS - 1 : b);
+            if (sum) atomicAdd(&s_bins[b], sum);
+        }
+        __syncthreads();
+        unsigned long long *rec = partials + (size_t)blockIdx.x * kSlots;
+        if (tid < 8) rec[tid] = s_cls[tid];
+        else if (tid < 8 + FMT_NBINS) rec[tid] = s_bins[tid - 8];
+    }
+}
+
+// Sums the per-workgroup records into the caller's fmt_hist_t (one workgroup, 1008 lanes busy).
+constexpr int kFinSplit = 14;
+__global__ __launch_bounds__(1024) void finalize_kernel(const unsigned long long *__restrict__ partials, int nrec,
+                                                        unsigned long long n, unsigned long long *__restrict__ hist)
+{
+    __shared__ unsigned long long acc[kSlots * kFinSplit];
+    __shared__ unsigned long long tot[kSlots];
+    const int tid = threadIdx.x;
+    const int slot = tid % kSlots, part = tid / kSlots;
+    if (part < kFinSplit) {
+        unsigned long long s = 0;
+        for (int r = part; r < nrec; r += kFinSplit) s += partials[(size_t)r * kSlots + slot];
+        acc[part * kSlots + slot] = s;
+    }
+    __syncthreads();
+    if (tid < kSlots) {
+        unsigned long long s = 0;
+        for (int q = 0; q < kFinSplit; ++q) s += acc[q * kSlots + tid];
+        tot[tid] = s;
+    }
+    __syncthreads();
+    if (tid < kSlots) {
+        unsigned long long v;
+        const unsigned long long z = tot[P_Z], zu = tot[P_ZU], zud = tot[P_ZUD], top = tot[P_TOP],
+                                 infnan = tot[P_INFNAN], nan = tot[P_NAN];
+        switch (tid) {
+            case 0: v = n; break;                    // total
+            case 1: v = z; break;                    // zero
+            case 2: v = zu - z; break;               // underflow
+            case 3: v = zud - zu; break;             // denormal
+            case 4: v = n - zud - top; break;        // normal
+            case 5: v = top - infnan; break;         // overflow
+            case 6: v = infnan - nan; break;         // inf
+            case 7: v = nan; break;                  // nan
+            default: v = tot[tid]; break;            // bins
+        }
+        hist[tid] = v;
+    }
+}
+
+template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC>
+static int launch_variant(const float *x, float *y, size_t n, size_t head, size_t nvec, const QuantParams &p,
+                          int max_grid, fmt_hist_t *hist, hipStream_t stream)
+{
+    auto kern = stream_kernel<MODE, STORE, FTZ, HIST, DEEP, VEC>;
+    static int occ = 0;   // per instantiation
+    if (occ == 0) {
+        int o = 0;
+        FMT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, kBlock, 0));
+        occ = o > 0 ? o : 1;
+    }
+    int cus = 0;
+    int rc = device_cu_count(&cus);
+    if (rc != FMT_OK) return rc;
+    const size_t per_block = (size_t)kBlock * (VEC ? 4 * kUnroll : 4);
+    size_t want = (n + per_block - 1) / per_block;
+    size_t cap = (size_t)cus * occ;
+    if ((size_t)max_grid < cap) cap = max_grid;
+    int grid = (int)(want < cap ? want : cap);
+    if (grid < 1) grid = 1;
+    unsigned long long *partials = nullptr;
+    if (HIST) {
+        Scratch s;
+        rc = get_scratch(stream, (size_t)max_grid * kSlots * sizeof(unsigned long long), 0, &s);
+        if (rc != FMT_OK) return rc;
+        partials = static_cast<unsigned long long *>(s.hist_partials);
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, stream, reinterpret_cast<const uint32_t *>(x),
+                       reinterpret_cast<uint32_t *>(y), n, head, nvec, p, partials);
+    FMT_HIP_CHECK(hipGetLastError());
+    if (HIST) {
+        hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, stream, partials, grid, (unsigned long long)n,
+                           reinterpret_cast<unsigned long long *>(hist));
+        FMT_HIP_CHECK(hipGetLastError());
+    }
+    return FMT_OK;
+}
+
+int launch_stream(const float *x, float *y, size_t n, const QuantParams &p, bool ftz, fmt_hist_t *hist,
+                  hipStream_t stream)
+{
+    const bool store = y != nullptr;
+    const bool do_hist = hist != nullptr;
+    const bool deep = do_hist && p.exp_lo < -126;
+    if (n == 0) {
+        if (do_hist) {
+            hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, stream, nullptr, 0, 0ull,
+                               reinterpret_cast<unsigned long long *>(hist));
+            FMT_HIP_CHECK(hipGetLastError());
+        }
+        return FMT_OK;
+    }
+    // elements before the first 16-byte boundary of x (and of y: both must agree for the vector path)
+    const size_t hx = ((16 - (reinterpret_cast<uintptr_t>(x) & 15)) & 15) / 4;
+    const size_t hy = store ? ((16 - (reinterpret_cast<uintptr_t>(y) & 15)) & 15) / 4 : hx;
+    const bool vec = hx == hy;
+    size_t head = hx < n ? hx : n;
+    size_t nvec = vec ? (n - head) / 4 : 0;
+    if (!vec) head = 0;
+    const int max_grid = 1 << 12;        // the scratch buffer holds this many partial records
+
+#define FMT_LAUNCH_M(MD, S, F, H, D)                                                                         \
+    (vec ? launch_variant<MD, S, F, H, D, true>(x, y, n, head, nvec, p, max_grid, hist, stream)               \
+         : launch_variant<MD, S, F, H, D, false>(x, y, n, head, nvec, p, max_grid, hist, stream))
+#define FMT_LAUNCH(S, F, H, D)                                                                               \
+    (p.mode == kModeMagic ? FMT_LAUNCH_M(kModeMagic, S, F, H, D)                                             \
+     : p.mode == kModeInteger ? FMT_LAUNCH_M(kModeInteger, S, F, H, D)                                       \
+                              : FMT_LAUNCH_M(kModeMixed, S, F, H, D))
+    // the statistics do not depend on how the rounding is carried out: one instantiation serves all
+    if (!store)
+        return deep ? FMT_LAUNCH_M(kModeMagic, false, false, true, true)
+                    : FMT_LAUNCH_M(kModeMagic, false, false, true, false);
+    if (!do_hist) return ftz ? FMT_LAUNCH(true, true, false, false) : FMT_LAUNCH(true, false, false, false);
+    if (deep) return ftz ? FMT_LAUNCH(true, true, true, true) : FMT_LAUNCH(true, false, true, true);
+    return ftz ? FMT_LAUNCH(true, true, true, false) : FMT_LAUNCH(true, false, true, false);
+#undef FMT_LAUNCH_M
+#undef FMT_LAUNCH
+}
+
+}  // namespace fmt

@@ -1,0 +1,113 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the header declares,
+validates arguments before touching the device, and its host-side format logic (closed-form
+constants, bit-pattern thresholds) agrees with the oracle for every supported (e, m)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2103_15940_amd as fmt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "fmt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(fmt_[a-z_]+)\s*\(", text))
+    assert declared == set(fmt.EXPORTS)
+    lib = ctypes.CDLL(fmt.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout():
+    text = open(os.path.join(ROOT, "include", "fmt.h")).read()
+    assert "uint64_t total, zero, underflow, denormal, normal, overflow, inf, nan;" in text
+    assert ctypes.sizeof(fmt._CFormat) == 12
+    assert 8 * (8 + fmt.FMT_NBINS) == 576
+
+
+def test_status_strings():
+    for code in range(0, -8, -1):
+        s = fmt.status_string(code)
+        assert isinstance(s, str) and s and (code == 0 or s != "ok")
+    assert fmt.status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("e,m", [(5, 10), (6, 9), (8, 7), (2, 1), (8, 23), (7, 16)])
+def test_format_info_matches_oracle_closed_forms(e, m):
+    assert fmt.fmt_format_info((e, m, True)) == oracle.format_constants(e, m)
+
+
+def test_unsupported_formats_rejected():
+    lib = fmt.raw_library()
+    for e, m in [(1, 5), (9, 7), (5, 0), (5, 24), (-1, 3)]:
+        with pytest.raises(fmt.FmtError) as ei:
+            fmt.fmt_format_info((e, m, True))
+        assert ei.value.status == -1
+        # the compute entry points refuse the format before looking at any pointer
+        assert lib.fmt_quantize(None, None, 0, fmt._CFormat(e, m, 1), None, -48, None) == -1
+        assert lib.fmt_histogram(None, 0, fmt._CFormat(e, m, 1), None, -48, None) == -1
+        assert lib.fmt_gemm(0, 0, 1, 1, 1, None, 1, None, 1, None, 1, fmt._CFormat(e, m, 1), None) == -1
+
+
+def test_argument_validation_without_gpu():
+    """All of these return before any HIP call, so they run on a host without a GPU."""
+    lib = fmt.raw_library()
+    f = fmt._CFormat(6, 9, 1)
+    buf = (ctypes.c_float * 64)()
+    base = ctypes.addressof(buf)
+    # null pointers
+    assert lib.fmt_quantize(None, base, 4, f, None, -48, None) == -2
+    assert lib.fmt_quantize(base, None, 4, f, None, -48, None) == -2
+    assert lib.fmt_histogram(base, 4, f, None, -48, None) == -2
+    assert lib.fmt_gemm(0, 0, 2, 2, 2, None, 2, base, 2, base + 64, 2, f, None) == -2
+    # misaligned
+    assert lib.fmt_quantize(base + 2, base, 4, f, None, -48, None) == -4
+    assert lib.fmt_histogram(base, 4, f, base + 4, -48, None) == -4
+    assert lib.fmt_gemm(0, 0, 2, 2, 2, base + 1, 2, base + 64, 2, base + 128, 2, f, None) == -4
+    # exp_lo window
+    assert lib.fmt_histogram(base, 4, f, base + 64, -193, None) == -5
+    assert lib.fmt_histogram(base, 4, f, base + 64, 129, None) == -5
+    # sizes
+    assert lib.fmt_quantize(base, base, 1 << 40, f, None, -48, None) == -3
+    assert lib.fmt_gemm(0, 0, -1, 2, 2, base, 2, base, 2, base, 2, f, None) == -3
+    assert lib.fmt_gemm(0, 0, 2, 2, 4, base, 3, base + 64, 2, base + 128, 2, f, None) == -3     # lda < K
+    assert lib.fmt_gemm(1, 0, 4, 2, 2, base, 3, base + 64, 2, base + 128, 2, f, None) == -3     # lda < M (A^T)
+    assert lib.fmt_gemm(0, 1, 2, 2, 4, base, 4, base + 64, 3, base + 128, 2, f, None) == -3     # ldb < K (B^T)
+    assert lib.fmt_gemm(0, 0, 2, 4, 2, base, 2, base + 64, 4, base + 128, 3, f, None) == -3     # ldc < N
+    # aliasing
+    assert lib.fmt_quantize(base, base + 8, 4, f, None, -48, None) == -6                          # partial overlap
+    assert lib.fmt_gemm(0, 0, 2, 2, 2, base, 2, base + 64, 2, base + 8, 2, f, None) == -6
+    # empty problems succeed without a launch
+    assert lib.fmt_quantize(None, None, 0, f, None, -48, None) == 0
+    assert lib.fmt_gemm(0, 0, 0, 5, 3, None, 3, None, 5, None, 5, f, None) == 0
+    assert lib.fmt_gemm(0, 0, 5, 0, 3, None, 3, None, 1, None, 1, f, None) == 0
+
+
+def _f32(bits):
+    return np.array(bits, dtype=np.uint32).view(np.float32)
+
+
+def test_thresholds_match_oracle_for_every_format():
+    """For all 7 x 23 supported (e, m): the three bit-pattern thresholds the kernels compare
+    against sit exactly where the oracle's rounding changes class."""
+    for e in range(2, 9):
+        for m in range(1, 24):
+            t = fmt.fmt_format_thresholds((e, m, True))
+            c = oracle.format_constants(e, m)
+            tz, td, to = t["t_zero"], t["t_den"], t["t_ovf"]
+            probe = _f32([tz, tz + 1, td - 1, td, to - 1, to, max(tz, 1) - 1])
+            q = oracle.quantize(probe, e, m, True).astype(np.float64)
+            assert q[0] == 0.0, (e, m)
+            assert q[1] > 0.0, (e, m)
+            if td - 1 > 0:
+                assert q[2] < c["minN"], (e, m)
+            assert q[3] >= c["minN"], (e, m)
+            assert np.isfinite(q[4]) and q[4] == c["maxN"], (e, m)
+            assert np.isinf(q[5]), (e, m)
+            assert tz < td < to <= 0x7F800000

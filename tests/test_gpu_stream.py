@@ -1,0 +1,223 @@
+"""GPU parity of fmt_quantize / fmt_histogram (through the C ABI) against the CPU oracle:
+bit-exact values, bit-exact integer counts."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+VARIANTS = [(5, 10, True), (5, 10, False), (6, 9, True), (6, 9, False), (8, 7, True), (8, 7, False)]
+OTHER = [(2, 1, True), (3, 2, False), (4, 3, True), (7, 16, False), (8, 23, True), (7, 23, True), (5, 23, False),
+         (8, 1, False), (2, 22, True)]
+
+
+@pytest.fixture(scope="module")
+def fmt():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_2103_15940_amd as lib
+    return lib
+
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def assert_same_values(got, want, what):
+    g, w = bits(got), bits(want)
+    if not np.array_equal(g, w):
+        bad = np.flatnonzero(g != w)
+        i = bad[0]
+        raise AssertionError("%s: %d of %d elements differ; first at %d: got %08x want %08x" %
+                             (what, bad.size, g.size, i, g[i], w[i]))
+
+
+def assert_same_hist(fmtlib, hist, want, what):
+    h = fmtlib.hist_to_dict(hist)
+    for k in fmtlib.CLASS_NAMES:
+        assert h[k] == want[k], "%s: class %s got %d want %d" % (what, k, h[k], want[k])
+    assert np.array_equal(h["bins"], want["bins"]), "%s: bins differ\n%s\n%s" % (what, h["bins"], want["bins"])
+
+
+def mixed(n, seed):
+    rng = np.random.default_rng(seed)
+    parts = [workloads.random_bits(n // 3, seed), workloads.log2_normal(n // 3, -14, 6, 0.01, rng)]
+    rest = n - sum(p.size for p in parts)
+    sp = workloads.special_values()
+    parts.append(np.resize(sp, rest))
+    x = np.concatenate(parts)
+    rng.shuffle(x)
+    return x
+
+
+@pytest.mark.parametrize("e,m,d", VARIANTS + OTHER)
+def test_quantize_and_fused_hist_bit_exact(fmt, e, m, d):
+    n = (1 << 18) + 37                      # several workgroups' worth of tiles and a ragged tail
+    x = mixed(n, 17 * e + m)
+    xd = dev(x)
+    hist = fmt.new_hist()
+    y = fmt.fmt_quantize(xd, (e, m, d), hist=hist)
+    y2 = fmt.fmt_quantize(xd, (e, m, d))   # store-only kernel
+    torch.cuda.synchronize()
+    want = oracle.quantize(x, e, m, d)
+    assert_same_values(y.cpu().numpy(), want, "fused 1/%d/%d/%s" % (e, m, d))
+    assert_same_values(y2.cpu().numpy(), want, "plain 1/%d/%d/%s" % (e, m, d))
+    assert_same_hist(fmt, hist, oracle.histogram(x, e, m), "fused hist 1/%d/%d" % (e, m))
+    h2 = fmt.fmt_histogram(xd, (e, m, d))
+    torch.cuda.synchronize()
+    assert_same_hist(fmt, h2, oracle.histogram(x, e, m), "hist-only 1/%d/%d" % (e, m))
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 7, 63, 64, 65, 511, 2048, 2049, 8191, 8192 * 4 + 1, 70001])
+def test_ragged_sizes(fmt, n):
+    x = mixed(max(n, 8), n)[:n]
+    xd = dev(x)
+    for (e, m, d) in [(6, 9, True), (5, 10, False), (8, 7, True)]:
+        hist = fmt.new_hist()
+        y = fmt.fmt_quantize(xd, (e, m, d), hist=hist)
+        torch.cuda.synchronize()
+        assert_same_values(y.cpu().numpy(), oracle.quantize(x, e, m, d), "n=%d" % n)
+        assert_same_hist(fmt, hist, oracle.histogram(x, e, m), "n=%d" % n)
+
+
+def test_empty_input(fmt):
+    xd = torch.empty(0, dtype=torch.float32, device="cuda")
+    hist = torch.full((72,), 7, dtype=torch.int64, device="cuda")
+    y = fmt.fmt_quantize(xd, (6, 9, True), hist=hist)
+    torch.cuda.synchronize()
+    assert y.numel() == 0 and int(hist.abs().sum()) == 0
+    hist.fill_(5)
+    fmt.fmt_histogram(xd, (6, 9, True), hist=hist)
+    torch.cuda.synchronize()
+    assert int(hist.abs().sum()) == 0
+
+
+@pytest.mark.parametrize("ox,oy", [(0, 0), (1, 1), (3, 3), (1, 0), (0, 2), (2, 3)])
+def test_misaligned_pointers(fmt, ox, oy):
+    """Offsets in elements from a 256-byte aligned base: equal offsets take the vector path with a
+    scalar head, unequal ones the dword fallback."""
+    n = 50003
+    x = mixed(n + 8, 5 + ox * 4 + oy)
+    xb = dev(x)
+    yb = torch.zeros(n + 8, dtype=torch.float32, device="cuda")
+    xs, ys = xb[ox:ox + n], yb[oy:oy + n]
+    hist = fmt.new_hist()
+    fmt.fmt_quantize(xs, (6, 9, False), out=ys, hist=hist)
+    h2 = fmt.fmt_histogram(xs, (6, 9, False))
+    torch.cuda.synchronize()
+    assert_same_values(ys.cpu().numpy(), oracle.quantize(x[ox:ox + n], 6, 9, False), "offsets %d,%d" % (ox, oy))
+    want = oracle.histogram(x[ox:ox + n], 6, 9)
+    assert_same_hist(fmt, hist, want, "fused")
+    assert_same_hist(fmt, h2, want, "hist-only")
+    # nothing outside [oy, oy+n) was written
+    full = yb.cpu().numpy()
+    assert np.all(full[:oy] == 0) and np.all(full[oy + n:] == 0)
+
+
+def test_in_place(fmt):
+    x = mixed(100000, 3)
+    xd = dev(x)
+    out = fmt.fmt_quantize(xd, (5, 10, True), out=xd)
+    torch.cuda.synchronize()
+    assert out.data_ptr() == xd.data_ptr()
+    assert_same_values(xd.cpu().numpy(), oracle.quantize(x, 5, 10, True), "in place")
+
+
+@pytest.mark.parametrize("exp_lo", [-192, -160, -149, -127, -126, -48, -24, 0, 64, 128])
+def test_histogram_windows(fmt, exp_lo):
+    """Windows that reach into the fp32-denormal binades use the per-binade rows."""
+    den = (workloads.random_bits(60000, 9).view(np.uint32) & np.uint32(0x807FFFFF)).view(np.float32)   # fp32 denormals
+    x = np.concatenate([mixed(60000, exp_lo + 500), den])
+    xd = dev(x)
+    hist = fmt.fmt_histogram(xd, (8, 7, True), exp_lo=exp_lo)
+    h2 = fmt.new_hist()
+    y = fmt.fmt_quantize(xd, (8, 7, True), hist=h2, exp_lo=exp_lo)
+    torch.cuda.synchronize()
+    want = oracle.histogram(x, 8, 7, exp_lo=exp_lo)
+    assert_same_hist(fmt, hist, want, "exp_lo=%d" % exp_lo)
+    assert_same_hist(fmt, h2, want, "fused exp_lo=%d" % exp_lo)
+    assert_same_values(y.cpu().numpy(), oracle.quantize(x, 8, 7, True), "values")
+
+
+@pytest.mark.parametrize("e,m", [(5, 10), (6, 9), (8, 7)])
+def test_exhaustive_codes_and_boundaries(fmt, e, m):
+    """Every code of the format, every midpoint between adjacent codes and the fp32 neighbours of
+    each midpoint, both signs -- the same probes that pin the oracle, now through the GPU."""
+    from fmtdef import decode_codes
+    v = decode_codes(e, m)
+    pos = v[: 1 << 15].astype(np.float64)
+    last = ((1 << e) - 1) << m
+    lo, hi = pos[:last].copy(), pos[1:last + 1].copy()
+    hi[-1] = 2.0 ** (2 ** (e - 1))
+    mid = ((lo + hi) / 2).astype(np.float32)
+    probes = np.concatenate([v, mid, np.nextafter(mid, np.float32(0)), np.nextafter(mid, np.float32(np.inf))])
+    probes = np.concatenate([probes, -probes])
+    xd = dev(probes)
+    for d in (True, False):
+        hist = fmt.new_hist()
+        y = fmt.fmt_quantize(xd, (e, m, d), hist=hist)
+        torch.cuda.synchronize()
+        got, want = y.cpu().numpy(), oracle.quantize(probes, e, m, d)
+        nan = np.isnan(want)
+        assert_same_values(got, want, "codes 1/%d/%d/%s" % (e, m, d))
+        assert np.all(bits(got[nan]) == 0x7FC00000)
+        assert_same_hist(fmt, hist, oracle.histogram(probes, e, m), "codes hist")
+
+
+def test_config1_full(fmt):
+    """Configuration 1: 2^20 values, log2|x| ~ N(-14, 6^2), 1 % zeros, 1/6/9 with denormals and flushed."""
+    x = workloads.config1()["x"]
+    xd = dev(x)
+    ho = oracle.histogram(x, 6, 9)
+    for d in (True, False):
+        hist = fmt.new_hist()
+        y = fmt.fmt_quantize(xd, (6, 9, d), hist=hist)
+        torch.cuda.synchronize()
+        assert_same_values(y.cpu().numpy(), oracle.quantize(x, 6, 9, d), "config1 d=%s" % d)
+        assert_same_hist(fmt, hist, ho, "config1")
+
+
+def test_config5_reduced_all_variants(fmt):
+    """Configuration 5's heavy-tailed tensor at 2^23 elements: all six variants element by element."""
+    x = workloads.config5(n=1 << 23)
+    xd = dev(x)
+    for (e, m, d) in VARIANTS:
+        hist = fmt.new_hist()
+        y = fmt.fmt_quantize(xd, (e, m, d), hist=hist)
+        torch.cuda.synchronize()
+        assert_same_values(y.cpu().numpy(), oracle.quantize(x, e, m, d), "config5 1/%d/%d/%s" % (e, m, d))
+        assert_same_hist(fmt, hist, oracle.histogram(x, e, m), "config5 hist")
+
+
+def test_repeated_calls_are_deterministic(fmt):
+    x = workloads.config5(n=1 << 22)
+    xd = dev(x)
+    ref = None
+    for _ in range(5):
+        hist = fmt.fmt_histogram(xd, (5, 10, True))
+        torch.cuda.synchronize()
+        h = hist.cpu().numpy()
+        if ref is None:
+            ref = h
+        assert np.array_equal(h, ref)
+
+
+def test_non_default_stream(fmt):
+    x = mixed(300000, 77)
+    s = torch.cuda.Stream()
+    xd = dev(x)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        hist = fmt.new_hist()
+        y = fmt.fmt_quantize(xd, (6, 9, True), hist=hist, stream=s)
+    s.synchronize()
+    assert_same_values(y.cpu().numpy(), oracle.quantize(x, 6, 9, True), "side stream")
+    assert_same_hist(fmt, hist, oracle.histogram(x, 6, 9), "side stream")
