@@ -21,6 +21,7 @@
 // compare-and-add counters.  Each workgroup folds its table into 64 bins and writes one
 // partial record; a second tiny kernel sums the records into the caller's fmt_hist_t.
 #include "fmt_internal.h"
+#include "fmt_quant.h"
 
 namespace fmt {
 
@@ -37,39 +38,6 @@ enum { P_Z = 0, P_ZU, P_ZUD, P_TOP, P_INFNAN, P_NAN, P_BINS = 8 };
 struct Counts {                          // per-lane counters, reduced once at the end
     uint32_t z = 0, zu = 0, zud = 0, top = 0, infnan = 0, nan = 0;
 };
-
-// How the rounding is carried out (uniform per launch, chosen on the host from (e, m)):
-enum : int {
-    kModeMagic = 0,    // e < 8, m <= 22: (|x| + C) - C with C = 2^(max(E, Emin) + 23 - m)
-    kModeInteger = 1,  // e == 8: RNE on the integer pattern (fp32's denormal grid is the format's own)
-    kModeMixed = 2     // e < 8, m == 23: nothing to round at or above minN, fixed grid below
-};
-
-// Q_{e,m,d|n} on one fp32 bit pattern.
-template <int MODE, bool FTZ>
-__device__ __forceinline__ uint32_t quantize_bits(uint32_t u, const QuantParams &p)
-{
-    const uint32_t a = u & 0x7FFFFFFFu;
-    uint32_t r;
-    if (MODE == kModeMagic) {
-        // C has ulp 2^(max(E,Emin)-m) and |x| < C, so the hardware's RNE addition lands on the
-        // format's grid and the subtraction is exact.  For |x| >= t_ovf the pattern of C may be
-        // meaningless; those lanes are overwritten below.
-        const uint32_t ce = max(a & 0x7F800000u, p.minn_bits) + p.shift23;
-        const float c = __uint_as_float(ce);
-        r = __float_as_uint((__uint_as_float(a) + c) - c);
-    } else if (MODE == kModeInteger) {
-        const uint32_t lsb = __builtin_amdgcn_ubfe(a, p.shift, p.lsb_width);
-        r = (a + p.rbias + lsb) & p.nmask;
-    } else {
-        const float rbf = (__uint_as_float(a) + p.cmagic) - p.cmagic;
-        r = (a < p.minn_bits) ? __float_as_uint(rbf) : a;
-    }
-    if (FTZ) r = (a < p.t_den) ? 0u : r;
-    r = (a >= p.t_ovf) ? 0x7F800000u : r;
-    r |= (u & 0x80000000u);
-    return (a > 0x7F800000u) ? 0x7FC00000u : r;
-}
 
 // Statistics of one element: one LDS increment and four compare-and-count steps (six when the
 // wave holds an overflowing or non-finite element).

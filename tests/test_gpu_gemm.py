@@ -1,0 +1,256 @@
+"""GPU parity of fmt_gemm (through the C ABI) against the CPU oracle.
+
+Tolerance: relative Frobenius error <= 1e-5 against the fp64-accumulated oracle; where every
+partial sum is exactly representable in fp32 the results must be identical."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL = 1e-5
+VARIANTS = [(5, 10, True), (5, 10, False), (6, 9, True), (6, 9, False), (8, 7, True), (8, 7, False)]
+LAYOUTS = [(False, False), (False, True), (True, False), (True, True)]
+
+
+@pytest.fixture(scope="module")
+def fmt():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_2103_15940_amd as lib
+    return lib
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_fro(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got)
+
+
+def run(fmt, A, B, f, tA=False, tB=False):
+    """A is M x K and B is K x N on the host; they are stored transposed when asked."""
+    Ain = np.ascontiguousarray(A.T) if tA else A
+    Bin = np.ascontiguousarray(B.T) if tB else B
+    C = fmt.fmt_gemm(dev(Ain), dev(Bin), f, transA=tA, transB=tB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm(Ain, Bin, f[0], f[1], f[2], transA=tA, transB=tB)
+    return C.cpu().numpy(), ref
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+@pytest.mark.parametrize("e,m", [(5, 10), (6, 9), (8, 7), (7, 20), (4, 3)])
+def test_exact_integer_case(fmt, e, m, tA, tB):
+    """Small integers times powers of two: every partial sum is exact in fp32, so the GPU must equal
+    the oracle bit for bit whatever its accumulation order.  Ragged in M, N and K."""
+    rng = np.random.default_rng(3)
+    M, N, K = 131, 67, 93
+    Ai = rng.integers(-7, 8, (M, K))
+    Bi = rng.integers(-7, 8, (K, N))
+    lim = 2 if e == 4 else 6
+    A = (Ai * np.exp2(rng.integers(-lim, lim + 1, (M, 1)))).astype(np.float32)
+    B = (Bi * np.exp2(rng.integers(-lim, lim + 1, (1, N)))).astype(np.float32)
+    got, ref = run(fmt, A, B, (e, m, True), tA, tB)
+    assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+@pytest.mark.parametrize("e,m,d", VARIANTS)
+def test_random_operands_all_layouts(fmt, e, m, d, tA, tB):
+    rng = np.random.default_rng(100 * e + m)
+    M, N, K = 200, 136, 300                  # two tiles each way with ragged edges, 10 k-blocks (last partial)
+    A = (rng.standard_normal((M, K)) * 2.0 ** -10).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * 2.0 ** -10).astype(np.float32)
+    got, ref = run(fmt, A, B, (e, m, d), tA, tB)
+    assert rel_fro(got, ref) <= TOL
+    # the operands really were rounded: an unrounded product is further away than the tolerance
+    raw = A.astype(np.float64) @ B.astype(np.float64)
+    assert rel_fro(raw, ref) > 10 * TOL or (e, m) == (8, 23)
+
+
+@pytest.mark.parametrize("e,m,d", [(6, 9, True), (5, 10, False), (8, 7, True), (7, 16, True), (8, 23, True),
+                                     (3, 12, False)])
+def test_wide_range_operands(fmt, e, m, d):
+    """Log-normal magnitudes straddling the format's denormal, underflow and normal ranges."""
+    rng = np.random.default_rng(7 * e + m)
+    c = oracle.format_constants(e, m)
+    M, N, K = 96, 80, 160
+    centre = max(c["Emin"], -40) + 2
+    A = workloads.log2_normal((M, K), centre, min(5.0, (c["Emax"] - centre) / 6.0), 0.05, rng)
+    B = workloads.log2_normal((K, N), -2, min(3.0, (c["Emax"] + 2) / 6.0), 0.05, rng)
+    got, ref = run(fmt, A, B, (e, m, d), False, True)
+    assert np.all(np.isfinite(ref))
+    assert rel_fro(got, ref) <= TOL
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (1, 7, 3), (5, 1, 40), (33, 31, 1), (128, 128, 32), (129, 127, 33),
+                                   (256, 10, 1024), (10, 1024, 256), (64, 300, 17)])
+def test_shapes(fmt, shape):
+    M, N, K = shape
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    for (tA, tB) in [(False, True), (False, False), (True, False)]:
+        got, ref = run(fmt, A, B, (6, 9, True), tA, tB)
+        assert rel_fro(got, ref) <= TOL, (shape, tA, tB)
+
+
+def test_identity_and_outer_product_are_exact(fmt):
+    rng = np.random.default_rng(11)
+    A = workloads.log2_normal((70, 50), -14, 6, 0.05, rng)
+    for (e, m, d) in [(5, 10, True), (6, 9, False), (8, 7, False)]:
+        qa = oracle.quantize(A, e, m, d)
+        Ain = np.where(np.isfinite(qa), A, 0).astype(np.float32)        # keep inf*0 out of this case
+        got, ref = run(fmt, Ain, np.eye(50, dtype=np.float32), (e, m, d))
+        assert np.array_equal(got, ref)
+        assert np.array_equal(got, oracle.quantize(Ain, e, m, d))
+    # K = 1: exact, unrounded products of two 10-bit significands
+    a = workloads.log2_normal((40, 1), -3, 2, 0, rng)
+    b = workloads.log2_normal((1, 45), -3, 2, 0, rng)
+    got, ref = run(fmt, a, b, (6, 9, True))
+    assert np.array_equal(got, ref)
+
+
+def test_leading_dimensions_and_output_view(fmt):
+    """Row strides larger than the row length on A, B and C; untouched padding in C."""
+    rng = np.random.default_rng(12)
+    M, N, K = 70, 45, 90
+    Abig = rng.standard_normal((M, K + 11)).astype(np.float32)
+    Bbig = rng.standard_normal((N, K + 5)).astype(np.float32)       # stored N x K (transB)
+    Ad, Bd = dev(Abig), dev(Bbig)
+    Cbig = torch.full((M, N + 9), -7.0, dtype=torch.float32, device="cuda")
+    fmt.fmt_gemm(Ad[:, :K], Bd[:, :K], (6, 9, True), transB=True, out=Cbig[:, :N])
+    torch.cuda.synchronize()
+    ref = oracle.gemm(Abig[:, :K], Bbig[:, :K], 6, 9, True, transB=True)
+    out = Cbig.cpu().numpy()
+    assert rel_fro(out[:, :N], ref) <= TOL
+    assert np.all(out[:, N:] == -7.0)
+
+
+def test_k_zero_fills_zero_and_empty_succeeds(fmt):
+    A = torch.empty((6, 0), dtype=torch.float32, device="cuda")
+    B = torch.empty((0, 9), dtype=torch.float32, device="cuda")
+    C = torch.full((6, 9), 3.0, dtype=torch.float32, device="cuda")
+    fmt.fmt_gemm(A, B, (6, 9, True), out=C)
+    torch.cuda.synchronize()
+    assert float(C.abs().sum()) == 0.0
+    C0 = fmt.fmt_gemm(torch.empty((0, 4), dtype=torch.float32, device="cuda"),
+                      torch.empty((4, 5), dtype=torch.float32, device="cuda"), (6, 9, True))
+    assert tuple(C0.shape) == (0, 5)
+
+
+def test_nonfinite_operands_give_nonfinite_outputs_in_the_same_places(fmt):
+    rng = np.random.default_rng(13)
+    A = rng.standard_normal((40, 64)).astype(np.float32)
+    B = rng.standard_normal((64, 40)).astype(np.float32)
+    A[3, 5] = np.inf
+    A[17, 60] = np.nan
+    A[30, 2] = 1e30          # finite, but overflows binary16
+    B[9, 21] = -np.inf
+    got, ref = run(fmt, A, B, (5, 10, True))
+    assert np.array_equal(np.isfinite(got), np.isfinite(ref))
+    fin = np.isfinite(ref)
+    assert rel_fro(got[fin], ref[fin]) <= TOL
+
+
+def test_bf16_denormal_operands(fmt):
+    """1/8/7/d keeps values below 2^-126 (bf16 denormals); their products with large values are
+    ordinary numbers and must not be lost."""
+    rng = np.random.default_rng(14)
+    A = (rng.integers(1, 128, (64, 64)) * 2.0 ** -133).astype(np.float32)     # every bf16 denormal magnitude
+    B = (rng.standard_normal((64, 64)) * 2.0 ** 100).astype(np.float32)
+    got, ref = run(fmt, A, B, (8, 7, True))
+    assert np.linalg.norm(ref) > 0
+    assert rel_fro(got, ref) <= TOL
+    got_n, ref_n = run(fmt, A, B, (8, 7, False))
+    assert np.all(ref_n == 0) and np.all(got_n == 0)
+
+
+def test_config1_gemm(fmt):
+    cfg = workloads.config1()
+    got, ref = run(fmt, cfg["A"], cfg["B"], (6, 9, True))
+    assert rel_fro(got, ref) <= TOL
+
+
+def test_config2_mlp_shapes(fmt):
+    """All eight GEMMs of one forward+backward step of the 784-1024-1024-10 MLP at batch 256, on the
+    tensors such a step produces (call-by-call parity on identical inputs)."""
+    cfg = workloads.config2()
+    f = (6, 9, True)
+    X, W = cfg["X"], cfg["W"]
+    acts = [X]
+    for l in range(3):                                     # forward, NT
+        A, B = acts[-1], W[l]
+        C = fmt.fmt_gemm(dev(A), dev(B), f, transB=True)
+        torch.cuda.synchronize()
+        out = C.cpu().numpy()
+        assert rel_fro(out, oracle.gemm(A, B, *f, transB=True)) <= TOL, ("fwd", l)
+        acts.append(np.maximum(out, 0) if l < 2 else out)
+    z = acts[-1].astype(np.float64)
+    p = np.exp(z - z.max(1, keepdims=True))
+    p /= p.sum(1, keepdims=True)
+    p[np.arange(z.shape[0]), cfg["labels"]] -= 1.0
+    dY = (p / z.shape[0] * cfg["loss_scale"]).astype(np.float32)
+    for l in (2, 1, 0):
+        Xl = acts[l]
+        dW = fmt.fmt_gemm(dev(dY), dev(Xl), f, transA=True)           # wgrad, TN
+        torch.cuda.synchronize()
+        assert rel_fro(dW.cpu().numpy(), oracle.gemm(dY, Xl, *f, transA=True)) <= TOL, ("wgrad", l)
+        if l > 0:
+            dX = fmt.fmt_gemm(dev(dY), dev(W[l]), f)                   # dgrad, NN
+            torch.cuda.synchronize()
+            out = dX.cpu().numpy()
+            assert rel_fro(out, oracle.gemm(dY, W[l], *f)) <= TOL, ("dgrad", l)
+            dY = (out * (acts[l] > 0)).astype(np.float32)
+
+
+def _sampled_check(fmt, A, B, f, tA, tB, nsamp, seed):
+    """Full-size product on the GPU; the oracle computes `nsamp` sampled outputs one by one."""
+    Ad, Bd = dev(A), dev(B)
+    C = fmt.fmt_gemm(Ad, Bd, f, transA=tA, transB=tB)
+    torch.cuda.synchronize()
+    M, N = C.shape
+    rng = np.random.default_rng(seed)
+    rows = rng.integers(0, M, nsamp)
+    cols = rng.integers(0, N, nsamp)
+    # always include the corners and the last row/column (ragged-edge handling)
+    rows[:4] = [0, 0, M - 1, M - 1]
+    cols[:4] = [0, N - 1, 0, N - 1]
+    got = C[torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()].cpu().numpy()
+    ref = oracle.gemm_sampled(A, B, rows, cols, f[0], f[1], f[2], transA=tA, transB=tB)
+    return rel_fro(got, ref), C
+
+
+def test_config3_conv_im2col_full_size(fmt):
+    """ResNet-style 3x3 conv as im2col GEMM at batch 64: fwd (NT), dgrad (NN), wgrad (TN) in all six
+    variants at full size (M=12544, N=256, K=2304 and permutations); sampled outputs vs the oracle."""
+    cfg = workloads.config3()
+    Xcol = workloads.im2col_3x3(cfg["X"])                  # 12544 x 2304
+    W, dY = cfg["W"], cfg["dY"]
+    assert Xcol.shape == (12544, 2304) and W.shape == (256, 2304) and dY.shape == (12544, 256)
+    for f in VARIANTS:
+        e1, _ = _sampled_check(fmt, Xcol, W, f, False, True, 1500, 1)       # Y = Xcol W^T
+        e2, _ = _sampled_check(fmt, dY, W, f, False, False, 1500, 2)        # dXcol = dY W
+        e3, _ = _sampled_check(fmt, dY, Xcol, f, True, False, 1500, 3)      # dW = dY^T Xcol
+        assert e1 <= TOL and e2 <= TOL and e3 <= TOL, (f, e1, e2, e3)
+
+
+def test_config4_bert_layer_full_size(fmt):
+    """BERT-Large-shaped encoder GEMMs at 4096 tokens, 1/6/9: fwd, dgrad, wgrad of the four linear
+    layers; sampled outputs vs the oracle."""
+    cfg = workloads.config4()
+    f = (6, 9, True)
+    for layer in cfg["layers"]:
+        X, W, dY = layer["X"], layer["W"], layer["dY"]
+        e1, _ = _sampled_check(fmt, X, W, f, False, True, 1000, 4)
+        e2, _ = _sampled_check(fmt, dY, W, f, False, False, 1000, 5)
+        e3, _ = _sampled_check(fmt, dY, X, f, True, False, 1000, 6)
+        assert e1 <= TOL and e2 <= TOL and e3 <= TOL, (layer["name"], e1, e2, e3)
