@@ -63,6 +63,8 @@ static int grow(void **buf, size_t *have, size_t want)
     }
     size_t cap = (want + 4095) & ~(size_t)4095;
     FMT_HIP_CHECK(hipMalloc(buf, cap));
+    FMT_HIP_CHECK(hipMemset(*buf, 0, cap));   // the partial histogram records must start at zero
+    FMT_HIP_CHECK(hipDeviceSynchronize());    // ... before a kernel on any stream adds to them
     *have = cap;
     return FMT_OK;
 }

@@ -1,8 +1,9 @@
 // Stream kernels of libfmt: the rounding kernel of Sec. IV-A (fp32 -> 1/e/m, result kept as
 // fp32) and the per-tensor statistics of Sec. V, separately or fused in one pass over x.
 //
-// Both are HBM streams: 4 B read (+ 4 B written) per element, 128-bit accesses, a persistent
-// grid-stride launch.  The rounding works on the fp32 bit pattern:
+// Both are HBM streams: 4 B read (+ 4 B written) per element, 128-bit non-temporal accesses.
+// A workgroup walks over tiles of 16 KiB of consecutive input (tile b, b+grid, ...): contiguous
+// tiles handed out in launch order measured faster on MI355X than a thread-granular grid stride.  The rounding works on the fp32 bit pattern:
 //   * e < 8: the format's grid around |x| has spacing 2^(max(E,Emin)-m), E = floor(log2|x|), and
 //     (|x| + C) - C with C = 2^(max(E,Emin)+23-m) lands on it with the hardware's own RNE --
 //     exact, since the addition is one correctly rounded fp32 operation whose ulp is that
@@ -18,20 +19,33 @@
 // Statistics: each element adds one to an LDS table indexed by its 8-bit fp32 exponent field,
 // replicated 32 times so that lane l only ever touches bank l%32 (no bank or address
 // conflicts, however concentrated the distribution); the class counts are per-lane
-// compare-and-add counters.  Each workgroup folds its table into 64 bins and writes one
-// partial record; a second tiny kernel sums the records into the caller's fmt_hist_t.
+// compare-and-add counters.  Each workgroup folds its table into 64 bins and adds them, with one
+// 64-bit atomic per non-zero slot, into one of 64 partial records in library scratch; a second
+// tiny kernel sums the 64 records into the caller's fmt_hist_t and clears them again.
 #include "fmt_internal.h"
 #include "fmt_quant.h"
+
+#ifndef FMT_STREAM_BLOCK
+#define FMT_STREAM_BLOCK 256
+#endif
+#ifndef FMT_STREAM_UNROLL
+#define FMT_STREAM_UNROLL 4
+#endif
+#ifndef FMT_STREAM_GRID_PER_CU
+#define FMT_STREAM_GRID_PER_CU 16
+#endif
 
 namespace fmt {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBlock = 512;              // threads per workgroup
+constexpr int kBlock = FMT_STREAM_BLOCK;  // threads per workgroup
 constexpr int kCopies = 32;              // replicas of the exponent table (one per LDS bank)
 constexpr int kRows = 256 + 24;          // exponent fields 0..255, then the 23 binades of fp32 denormals
-constexpr int kUnroll = 4;               // independent 128-bit loads in flight per thread
+constexpr int kUnroll = FMT_STREAM_UNROLL;  // independent 128-bit loads in flight per thread
 constexpr int kSlots = 72;               // uint64 per partial record
+constexpr int kShards = 64;              // partial records in global memory (workgroup b adds into b % 64)
+constexpr int kGridPerCU = FMT_STREAM_GRID_PER_CU;   // workgroups launched per compute unit (at most)
 // slots of a partial record
 enum { P_Z = 0, P_ZU, P_ZUD, P_TOP, P_INFNAN, P_NAN, P_BINS = 8 };
 
@@ -85,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
                                                         size_t n, size_t head, size_t nvec, QuantParams p,
                                                         unsigned long long *__restrict__ partials)
 {
-    __shared__ uint32_t tbl[HIST ? kRows * kCopies : 1];
+    __shared__ __attribute__((aligned(16))) uint32_t tbl[HIST ? kRows * kCopies : 4];
     __shared__ uint32_t s_bins[FMT_NBINS];
     __shared__ uint32_t s_cls[8];
     const uint32_t tid = threadIdx.x;
@@ -93,7 +107,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
     Counts w;
 
     if (HIST) {
-        for (int i = tid; i < kRows * kCopies; i += kBlock) tbl[i] = 0;
+        for (int i = tid; i < kRows * kCopies / 4; i += kBlock) reinterpret_cast<u32x4 *>(tbl)[i] = u32x4{0u, 0u, 0u, 0u};
         if (tid < FMT_NBINS) s_bins[tid] = 0;
         if (tid < 8) s_cls[tid] = 0;
         __syncthreads();
@@ -102,28 +116,32 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
     if (VEC) {
         const u32x4 *xv = reinterpret_cast<const u32x4 *>(x + head);
         u32x4 *yv = reinterpret_cast<u32x4 *>(y + head);
-        const size_t stride = (size_t)gridDim.x * kBlock;
-        // Loop bounds are taken from the wave's first lane so that every trip is wave-uniform.
-        const uint32_t lane = tid & 63u;
-        size_t ib = (size_t)blockIdx.x * kBlock + __builtin_amdgcn_readfirstlane(tid & ~63u);
-        for (; ib + 63 + (kUnroll - 1) * stride < nvec; ib += kUnroll * stride) {
-            const size_t i = ib + lane;
+        // A tile is kBlock*kUnroll consecutive vectors; workgroup b takes tiles b, b+grid, ...
+        // Every lane of the workgroup runs the same trips, and all tiles but the last are full.
+        constexpr size_t kTileVec = (size_t)kBlock * kUnroll;
+        const size_t full_tiles = nvec / kTileVec;
+        for (size_t t = blockIdx.x; t < full_tiles; t += gridDim.x) {
+            const size_t i = t * kTileVec + tid;
             u32x4 v[kUnroll];
 #pragma unroll
-            for (int k = 0; k < kUnroll; ++k) v[k] = __builtin_nontemporal_load(xv + i + k * stride);
+            for (int k = 0; k < kUnroll; ++k) v[k] = __builtin_nontemporal_load(xv + i + k * kBlock);
 #pragma unroll
             for (int k = 0; k < kUnroll; ++k) {
                 u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v[k], true, p, tbl, lane32, w);
-                if (STORE) __builtin_nontemporal_store(o, yv + i + k * stride);
+                if (STORE) __builtin_nontemporal_store(o, yv + i + k * kBlock);
             }
         }
-        for (; ib < nvec; ib += stride) {
-            const size_t i = ib + lane;
-            const bool valid = i < nvec;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (valid) v = __builtin_nontemporal_load(xv + i);
-            u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v, valid, p, tbl, lane32, w);
-            if (STORE && valid) __builtin_nontemporal_store(o, yv + i);
+        if (blockIdx.x == full_tiles % gridDim.x && full_tiles * kTileVec < nvec) {
+            // the ragged last tile, lane by lane
+#pragma unroll
+            for (int k = 0; k < kUnroll; ++k) {
+                const size_t i = full_tiles * kTileVec + k * kBlock + tid;
+                const bool valid = i < nvec;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (valid) v = __builtin_nontemporal_load(xv + i);
+                u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v, valid, p, tbl, lane32, w);
+                if (STORE && valid) __builtin_nontemporal_store(o, yv + i);
+            }
         }
         if (blockIdx.x == 0 && tid < 64) {
             // leftovers: [0, head) and [head + 4*nvec, n)
@@ -161,32 +179,36 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
             for (int q = 0; q < 6; ++q) if (c[q]) atomicAdd(&s_cls[q], c[q]);
         }
         __syncthreads();
-        if (tid < kRows) {
+        for (int row = tid; row < kRows; row += kBlock) {
             uint32_t sum = 0;
 #pragma unroll 8
-            for (int c = 0; c < kCopies; ++c) sum += tbl[tid * kCopies + ((c + tid) & (kCopies - 1))];
+            for (int c = 0; c < kCopies; ++c) sum += tbl[row * kCopies + ((c + row) & (kCopies - 1))];
             int E;
-            if (tid < 256) {
-                E = (int)tid - 127;
-                if (tid == 0) sum -= s_cls[P_Z];      // zeros are not binned; what is left are fp32 denormals
-                if (tid == 255) { sum -= s_cls[P_NAN]; E = 1 << 20; }   // infinities -> top bin, NaN not binned
+            if (row < 256) {
+                E = row - 127;
+                if (row == 0) sum -= s_cls[P_Z];      // zeros are not binned; what is left are fp32 denormals
+                if (row == 255) { sum -= s_cls[P_NAN]; E = 1 << 20; }   // infinities -> top bin, NaN not binned
             } else {
-                E = (int)tid - 256 - 149;             // binade of an fp32 denormal with leading bit tid-256
+                E = row - 256 - 149;                  // binade of an fp32 denormal with leading bit row-256
             }
             int b = E - p.exp_lo;
             b = b < 0 ? 0 : (b > FMT_NBINS - 1 ? FMT_NBINS - 1 : b);
             if (sum) atomicAdd(&s_bins[b], sum);
         }
         __syncthreads();
-        unsigned long long *rec = partials + (size_t)blockIdx.x * kSlots;
-        if (tid < 8) rec[tid] = s_cls[tid];
-        else if (tid < 8 + FMT_NBINS) rec[tid] = s_bins[tid - 8];
+        // one 64-bit add per non-zero slot into this workgroup's shard of the partial records
+        unsigned long long *rec = partials + (size_t)(blockIdx.x % kShards) * kSlots;
+        if (tid < kSlots) {
+            const uint32_t v = tid < 8 ? s_cls[tid] : s_bins[tid - 8];
+            if (v) atomicAdd(&rec[tid], (unsigned long long)v);
+        }
     }
 }
 
-// Sums the per-workgroup records into the caller's fmt_hist_t (one workgroup, 1008 lanes busy).
+// Sums the shard records into the caller's fmt_hist_t and clears them for the next call (one
+// workgroup; the stream orders it after the kernel that filled them).
 constexpr int kFinSplit = 14;
-__global__ __launch_bounds__(1024) void finalize_kernel(const unsigned long long *__restrict__ partials, int nrec,
+__global__ __launch_bounds__(1024) void finalize_kernel(unsigned long long *__restrict__ partials, int nrec,
                                                         unsigned long long n, unsigned long long *__restrict__ hist)
 {
     __shared__ unsigned long long acc[kSlots * kFinSplit];
@@ -195,7 +217,10 @@ __global__ __launch_bounds__(1024) void finalize_kernel(const unsigned long long
     const int slot = tid % kSlots, part = tid / kSlots;
     if (part < kFinSplit) {
         unsigned long long s = 0;
-        for (int r = part; r < nrec; r += kFinSplit) s += partials[(size_t)r * kSlots + slot];
+        for (int r = part; r < nrec; r += kFinSplit) {
+            s += partials[(size_t)r * kSlots + slot];
+            partials[(size_t)r * kSlots + slot] = 0;
+        }
         acc[part * kSlots + slot] = s;
     }
     __syncthreads();
@@ -226,28 +251,21 @@ __global__ __launch_bounds__(1024) void finalize_kernel(const unsigned long long
 
 template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC>
 static int launch_variant(const float *x, float *y, size_t n, size_t head, size_t nvec, const QuantParams &p,
-                          int max_grid, fmt_hist_t *hist, hipStream_t stream)
+                          fmt_hist_t *hist, hipStream_t stream)
 {
     auto kern = stream_kernel<MODE, STORE, FTZ, HIST, DEEP, VEC>;
-    static int occ = 0;   // per instantiation
-    if (occ == 0) {
-        int o = 0;
-        FMT_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, kBlock, 0));
-        occ = o > 0 ? o : 1;
-    }
     int cus = 0;
     int rc = device_cu_count(&cus);
     if (rc != FMT_OK) return rc;
     const size_t per_block = (size_t)kBlock * (VEC ? 4 * kUnroll : 4);
-    size_t want = (n + per_block - 1) / per_block;
-    size_t cap = (size_t)cus * occ;
-    if ((size_t)max_grid < cap) cap = max_grid;
+    const size_t want = (n + per_block - 1) / per_block;
+    const size_t cap = (size_t)cus * kGridPerCU;
     int grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
     unsigned long long *partials = nullptr;
     if (HIST) {
         Scratch s;
-        rc = get_scratch(stream, (size_t)max_grid * kSlots * sizeof(unsigned long long), 0, &s);
+        rc = get_scratch(stream, kShards * kSlots * sizeof(unsigned long long), 0, &s);
         if (rc != FMT_OK) return rc;
         partials = static_cast<unsigned long long *>(s.hist_partials);
     }
@@ -255,7 +273,7 @@ static int launch_variant(const float *x, float *y, size_t n, size_t head, size_
                        reinterpret_cast<uint32_t *>(y), n, head, nvec, p, partials);
     FMT_HIP_CHECK(hipGetLastError());
     if (HIST) {
-        hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, stream, partials, grid, (unsigned long long)n,
+        hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, stream, partials, kShards, (unsigned long long)n,
                            reinterpret_cast<unsigned long long *>(hist));
         FMT_HIP_CHECK(hipGetLastError());
     }
@@ -283,11 +301,10 @@ int launch_stream(const float *x, float *y, size_t n, const QuantParams &p, bool
     size_t head = hx < n ? hx : n;
     size_t nvec = vec ? (n - head) / 4 : 0;
     if (!vec) head = 0;
-    const int max_grid = 1 << 12;        // the scratch buffer holds this many partial records
 
 #define FMT_LAUNCH_M(MD, S, F, H, D)                                                                         \
-    (vec ? launch_variant<MD, S, F, H, D, true>(x, y, n, head, nvec, p, max_grid, hist, stream)               \
-         : launch_variant<MD, S, F, H, D, false>(x, y, n, head, nvec, p, max_grid, hist, stream))
+    (vec ? launch_variant<MD, S, F, H, D, true>(x, y, n, head, nvec, p, hist, stream)               \
+         : launch_variant<MD, S, F, H, D, false>(x, y, n, head, nvec, p, hist, stream))
 #define FMT_LAUNCH(S, F, H, D)                                                                               \
     (p.mode == kModeMagic ? FMT_LAUNCH_M(kModeMagic, S, F, H, D)                                             \
      : p.mode == kModeInteger ? FMT_LAUNCH_M(kModeInteger, S, F, H, D)                                       \

@@ -49,20 +49,35 @@ def log2_normal(n, mean: float, sigma: float, zero_frac: float, rng: np.random.G
     return out.reshape(shape)
 
 
+def _student_chunk(args):
+    seed_key, idx, count, center, scale, dof, zero_frac = args
+    rng = _rng(*seed_key, idx)
+    L = center + scale * rng.standard_t(dof, count)
+    sign = np.where(rng.random(count) < 0.5, -1.0, 1.0)
+    with np.errstate(over="ignore", under="ignore"):
+        v = sign * np.exp2(L)
+    if zero_frac > 0:
+        v[rng.random(count) < zero_frac] = 0.0
+    return _cast32(v)
+
+
 def log2_student_t(n: int, center: float, scale: float, dof: float, zero_frac: float,
-                   rng: np.random.Generator, chunk: int = 1 << 24) -> np.ndarray:
+                   seed_key=(5,), chunk: int = 1 << 22, workers: int = 0) -> np.ndarray:
     """x = +-2^L with L = center + scale*T, T ~ Student-t(dof); no clipping, so the fp32 cast
-    produces a few infinities, fp32 denormals and extra zeros on purpose."""
-    out = np.empty(int(n), dtype=np.float32)
-    for s in range(0, int(n), chunk):
-        c = min(chunk, int(n) - s)
-        L = center + scale * rng.standard_t(dof, c)
-        sign = np.where(rng.random(c) < 0.5, -1.0, 1.0)
-        with np.errstate(over="ignore", under="ignore"):
-            v = sign * np.exp2(L)
-        if zero_frac > 0:
-            v[rng.random(c) < zero_frac] = 0.0
-        out[s:s + c] = _cast32(v)
+    produces a few infinities, fp32 denormals and extra zeros on purpose.  The tensor is drawn in
+    chunks of 2^22, chunk i from its own generator seeded (seed_key, i), so the result does not
+    depend on how many threads draw it."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    n = int(n)
+    out = np.empty(n, dtype=np.float32)
+    jobs = [(tuple(seed_key), i, min(chunk, n - s), center, scale, dof, zero_frac)
+            for i, s in enumerate(range(0, n, chunk))]
+    if workers <= 0:
+        workers = min(16, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        for i, part in enumerate(pool.map(_student_chunk, jobs)):
+            out[i * chunk:i * chunk + part.size] = part
     return out
 
 
@@ -146,7 +161,7 @@ def config4(seed: int = 4, tokens: int = BERT_TOKENS) -> dict:
 
 def config5(seed: int = 5, n: int = 1 << 28) -> np.ndarray:
     """Heavy-tailed gradient tensor: log2|x| = -18 + 8*T, T ~ Student-t(3), 2 % zeros."""
-    return log2_student_t(n, -18.0, 8.0, 3.0, 0.02, _rng(seed))
+    return log2_student_t(n, -18.0, 8.0, 3.0, 0.02, seed_key=(seed,))
 
 
 def special_values() -> np.ndarray:
