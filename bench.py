@@ -7,14 +7,19 @@ One "step" is one pass of the whole hot path over one batch of synthetic, paper-
                                      heavy-tailed fp32 gradient tensor, one pass per format
                                      variant (binary16, bfloat16, 1/6/9, each d and n): 6 passes,
                                      8 B of algorithmic HBM traffic per element and pass
-  GEMM section (configuration 3)     the ResNet-style 3x3 conv as im2col GEMM in 1/6/9/d:
+  GEMM section (configuration 4)     BERT-Large-shaped encoder-layer GEMMs at 4096 tokens in
+                                     1/6/9/d: for each of the four linear layers (QKV, attention
+                                     output, FFN1, FFN2) fused quantize + histogram of X, W and
+                                     dY, then forward (NT), dgrad (NN) and wgrad (TN): 12 products,
+                                     309 GFLOP
+  conv section (configuration 3)     the ResNet-style 3x3 conv as im2col GEMM in 1/6/9/d:
                                      fused quantize + histogram of X_col, W and dY, then the
-                                     forward (NT), dgrad (NN) and wgrad (TN) products
-                                     (M=12544, N=256, K=2304 and permutations, 14.8 GFLOP each)
+                                     forward, dgrad and wgrad products (M=12544, N=256, K=2304
+                                     and permutations, 14.8 GFLOP each)
 
 `value` is the quantize+histogram HBM rate of the stream section (GB/s, algorithmic bytes over
 the section's event-timed duration); the GEMM section's useful TFLOP/s and its MFMA fraction are
-reported beside it under "gemm".  Inputs are resident in HBM before the timed region starts.
+reported beside it under "gemm" (configuration 4) and "gemm_config3".  Inputs are resident in HBM before the timed region starts.
 The CPU oracle is timed on a bounded sample of the same tensor as a baseline.
 """
 from __future__ import annotations
@@ -77,6 +82,16 @@ def main() -> int:
     out_fwd = torch.empty((M, N), dtype=torch.float32, device=dev)
     out_dgrad = torch.empty((M, K), dtype=torch.float32, device=dev)
     out_wgrad = torch.empty((N, K), dtype=torch.float32, device=dev)
+    cfg4 = workloads.config4()
+    layers = []
+    for L in cfg4["layers"]:
+        X4, W4, dY4 = (torch.from_numpy(L[k]).to(dev) for k in ("X", "W", "dY"))
+        layers.append({"X": X4, "W": W4, "dY": dY4, "Xq": torch.empty_like(X4), "Wq": torch.empty_like(W4),
+                       "dYq": torch.empty_like(dY4),
+                       "Y": torch.empty((X4.shape[0], W4.shape[0]), dtype=torch.float32, device=dev),
+                       "dX": torch.empty_like(X4), "dW": torch.empty_like(W4),
+                       "h": [fmt.new_hist(dev) for _ in range(3)]})
+    cfg4_flops = sum(3 * 2.0 * L["X"].shape[0] * L["W"].shape[0] * L["W"].shape[1] for L in layers)
     hists = [fmt.new_hist(dev) for _ in range(9)]
     variants = list(workloads.FORMATS.values())
     f169 = workloads.FORMATS["1/6/9/d"]
@@ -86,24 +101,38 @@ def main() -> int:
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def step(record=None):
-        if record is not None:
-            a, b, c, d = ev(), ev(), ev(), ev()
-            a.record()
-        for i, f in enumerate(variants):
+        marks = []
+
+        def mark():
+            if record is not None:
+                e = ev()
+                e.record()
+                marks.append(e)
+
+        mark()
+        for i, f in enumerate(variants):                                     # configuration 5
             fmt.fmt_quantize(x, f, out=y, hist=hists[i])
-        if record is not None:
-            b.record()
-        fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6])
+        mark()
+        for L in layers:                                                     # configuration 4, quantize
+            fmt.fmt_quantize(L["X"], f169, out=L["Xq"], hist=L["h"][0])
+            fmt.fmt_quantize(L["W"], f169, out=L["Wq"], hist=L["h"][1])
+            fmt.fmt_quantize(L["dY"], f169, out=L["dYq"], hist=L["h"][2])
+        mark()
+        for L in layers:                                                     # configuration 4, products
+            fmt.fmt_gemm(L["Xq"], L["Wq"], f169, transB=True, out=L["Y"])    # Y  = X W^T
+            fmt.fmt_gemm(L["dYq"], L["Wq"], f169, out=L["dX"])               # dX = dY W
+            fmt.fmt_gemm(L["dYq"], L["Xq"], f169, transA=True, out=L["dW"])  # dW = dY^T X
+        mark()
+        fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6])              # configuration 3
         fmt.fmt_quantize(w, f169, out=w_q, hist=hists[7])
         fmt.fmt_quantize(dy, f169, out=dy_q, hist=hists[8])
+        mark()
+        fmt.fmt_gemm(xcol_q, w_q, f169, transB=True, out=out_fwd)            # Y    = X_col W^T
+        fmt.fmt_gemm(dy_q, w_q, f169, out=out_dgrad)                         # dX   = dY W
+        fmt.fmt_gemm(dy_q, xcol_q, f169, transA=True, out=out_wgrad)         # dW   = dY^T X_col
+        mark()
         if record is not None:
-            c.record()
-        fmt.fmt_gemm(xcol_q, w_q, f169, transB=True, out=out_fwd)          # Y    = X_col W^T
-        fmt.fmt_gemm(dy_q, w_q, f169, out=out_dgrad)                        # dX   = dY W
-        fmt.fmt_gemm(dy_q, xcol_q, f169, transA=True, out=out_wgrad)        # dW   = dY^T X_col
-        if record is not None:
-            d.record()
-            record.append((a, b, c, d))
+            record.append(marks)
 
     for _ in range(args.warmup):
         step()
@@ -116,15 +145,16 @@ def main() -> int:
     wall_ms = (time.perf_counter() - t_start) * 1e3
     ms_per_step = wall_ms / args.steps
 
-    stream_ms = sum(a.elapsed_time(b) for a, b, c, d in records) / args.steps
-    cfg3_stream_ms = sum(b.elapsed_time(c) for a, b, c, d in records) / args.steps
-    gemm_ms = sum(c.elapsed_time(d) for a, b, c, d in records) / args.steps
+    def section(i):
+        return sum(m[i].elapsed_time(m[i + 1]) for m in records) / args.steps
+
+    stream_ms, cfg4_q_ms, cfg4_gemm_ms, cfg3_q_ms, cfg3_gemm_ms = (section(i) for i in range(5))
 
     stream_bytes = 8.0 * n * len(variants)
     stream_gbs = stream_bytes / (stream_ms * 1e-3) / 1e9
     per_launch_ms = stream_ms / len(variants)
-    gemm_flops = 3 * 2.0 * M * N * K
-    gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12
+    cfg4_tflops = cfg4_flops / (cfg4_gemm_ms * 1e-3) / 1e12
+    cfg3_tflops = 3 * 2.0 * M * N * K / (cfg3_gemm_ms * 1e-3) / 1e12
 
     result = {
         "metric": "quantize+histogram HBM GB/s; 1/6/9-operand GEMM TFLOP/s (% of peak)",
@@ -141,20 +171,30 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": "config 5 stream: fused quantize+64-bin histogram of a 2^%d-element heavy-tailed fp32 "
-                        "tensor, six format variants, one pass each; config 3 GEMMs: 3x3 conv 256->256 at 14x14, "
-                        "batch 64 as im2col (M=12544, N=256, K=2304), fwd+dgrad+wgrad in 1/6/9/d with fused "
-                        "quantize+histogram of X_col, W, dY" % (n.bit_length() - 1),
+                        "tensor, six format variants, one pass each; config 4 GEMMs: BERT-Large-shaped encoder "
+                        "layer at 4096 tokens, fwd+dgrad+wgrad of QKV/attn-out/FFN1/FFN2 in 1/6/9/d with fused "
+                        "quantize+histogram of X, W, dY; config 3 GEMMs: 3x3 conv 256->256 at 14x14, batch 64 as "
+                        "im2col (M=12544, N=256, K=2304), fwd+dgrad+wgrad in 1/6/9/d" % (n.bit_length() - 1),
             "stream_elements": n,
             "stream_passes": len(variants),
-            "gemm_shape": [M, N, K],
+            "config4_gemm_gflop": round(cfg4_flops / 1e9, 1),
+            "config3_gemm_shape": [M, N, K],
         },
-        "sections_ms": {"stream": round(stream_ms, 4), "config3_quantize": round(cfg3_stream_ms, 4),
-                        "config3_gemms": round(gemm_ms, 4)},
+        "sections_ms": {"config5_stream": round(stream_ms, 4), "config4_quantize": round(cfg4_q_ms, 4),
+                        "config4_gemms": round(cfg4_gemm_ms, 4), "config3_quantize": round(cfg3_q_ms, 4),
+                        "config3_gemms": round(cfg3_gemm_ms, 4)},
         "gemm": {
-            "value": round(gemm_tflops, 2), "unit": "TFLOP/s (useful, 2MNK per product)",
-            "issued_tflops": round(4 * gemm_tflops, 2),
-            "mfma_frac": round(4 * gemm_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
-            "note": "1/6/9 operands are split exactly into two bf16 pieces: 4 MFMA products per multiply",
+            "workload": "config 4, 12 products, 1/6/9/d",
+            "value": round(cfg4_tflops, 2), "unit": "TFLOP/s (useful, 2MNK per product, whole fmt_gemm calls)",
+            "issued_tflops": round(4 * cfg4_tflops, 2),
+            "mfma_frac": round(4 * cfg4_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
+            "note": "1/6/9 operands are split exactly into two bf16 pieces: 4 MFMA products per multiply; "
+                    "mfma_frac = issued / 2500 TFLOP/s dense bf16 peak",
+        },
+        "gemm_config3": {
+            "workload": "config 3, 3 products, 1/6/9/d",
+            "value": round(cfg3_tflops, 2), "unit": "TFLOP/s (useful)",
+            "mfma_frac": round(4 * cfg3_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
         },
         "roofline": {
             "kernel": "stream_kernel (fused quantize + histogram)",

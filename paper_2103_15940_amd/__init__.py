@@ -12,7 +12,8 @@ import os
 from typing import NamedTuple, Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfmt.so")
+# FMT_LIB_PATH selects another build of the same library (tuning builds); default: the in-tree one
+LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48

@@ -22,12 +22,13 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every HIP source for gfx950 and link libfmt.so next to this file."""
+def build(verbose: bool = False, extra_flags=(), output: str = LIB, tag: str = "") -> str:
+    """Compile every HIP source for gfx950 and link libfmt.so next to this file (or to `output`,
+    with object files suffixed by `tag`, for tuning builds with extra -D flags)."""
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        obj = os.path.join(CSRC, src.replace(".hip", tag + ".o"))
         cmd = [hipcc(), *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -46,13 +47,13 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(out)
     if failed:
         raise RuntimeError("libfmt build failed")
-    tmp = LIB + ".tmp.%d" % os.getpid()
+    tmp = output + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, output)
+    return output
 
 
 if __name__ == "__main__":

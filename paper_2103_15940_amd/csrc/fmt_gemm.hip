@@ -15,10 +15,21 @@
 //            order the product kernel consumes: units of 32 rows x 32 k per piece, each unit
 //            stored as [k-chunk of 8][row][8 x bf16] so that a wave's MFMA operand fetch is one
 //            contiguous 1 KiB read.
-//   product  a 128x128 workgroup tile, 4 waves each owning 64x64 (2x2 MFMA 32x32x16 tiles),
-//            register-prefetched global loads, one LDS stage of 32 k.
+//   product  workgroup tiles of 64x64 up to 256x128, 4 waves of MFMA 32x32x16 tiles each, operand
+//            stages loaded from global memory straight into LDS (double-buffered, 32 k per
+//            stage), optional split of the k range with a deterministic reduction.
+#include <cstdio>
+#include <cstdlib>
+
 #include "fmt_internal.h"
 #include "fmt_quant.h"
+
+#ifndef FMT_GEMM_KS
+#define FMT_GEMM_KS 2      // 16-k steps per LDS stage
+#endif
+#ifndef FMT_GEMM_NST
+#define FMT_GEMM_NST 2     // LDS stage buffers
+#endif
 
 namespace fmt {
 
@@ -29,8 +40,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kUnitRows = 32;                 // rows per unit (one MFMA fragment)
 constexpr int kUnitK = 32;                    // k per unit (two MFMA steps of 16)
 constexpr int kUnitVec = kUnitRows * kUnitK * 2 / 16;   // 16-byte vectors per unit per piece = 128
-constexpr int kTile = 128;                    // workgroup tile edge (rows of op(A), columns of op(B))
-constexpr int kTileUnits = kTile / kUnitRows; // 4
+constexpr int kRowPad = 256;                  // prepared operands are padded to a multiple of this many rows
 
 // Rounds one fp32 pattern to the format and splits the result into P bf16 patterns.
 template <int MODE, bool FTZ, int P>
@@ -102,103 +112,166 @@ __global__ __launch_bounds__(256) void prepare_kernel(const uint32_t *__restrict
     }
 }
 
-// product: Aw / Bw are prepared operands (rows padded to a multiple of 128, k to a multiple of 32).
-template <int P>
+// product: Aw / Bw are prepared operands (rows padded to a multiple of kRowPad, k to a multiple
+// of 32).  A workgroup is 2 x 2 waves; each wave owns TM x TN MFMA tiles of 32 x 32, so the
+// workgroup tile is (64*TM) x (64*TN).  Operand stages of KS*16 k go from global memory straight
+// into LDS (global_load_lds, 16 bytes per lane) through a ring of NST stage buffers, one barrier
+// per stage.  With SPLIT the k range is cut into parts and each part writes its own M x N slab
+// of partial sums (summed by reduce_kernel).
+template <int P, int TM, int TN, int KS, int NST, bool SPLIT>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int kblocks,
-                                                      int tiles_n)
+                                                      int tiles_m, int tiles_n, int kb_per_split)
 {
-    constexpr int kStageVec = kTileUnits * P * kUnitVec;     // 16-byte vectors per operand per stage
-    constexpr int kLoads = kStageVec / 256;                   // per thread per operand (2 * P)
-    __shared__ u32x4 sA[kStageVec];
-    __shared__ u32x4 sB[kStageVec];
+    constexpr int UA = 2 * TM, UB = 2 * TN;              // 32-row units per operand in the workgroup tile
+    constexpr int kHalf = 64;                            // vectors of one piece of one unit per 16 k
+    constexpr int SV = kHalf * KS;                       // ... per stage
+    constexpr int VA = UA * P * SV, VB = UB * P * SV;    // 16-byte vectors per operand per stage
+    constexpr int LA = (VA + 255) / 256, LB = (VB + 255) / 256;   // loads per lane per stage
+    constexpr int kWaitLanded = ((NST - 2) * (LA + LB));  // stage loads that may still be in flight
+    static_assert(kWaitLanded < 64 && (KS == 1 || KS == 2) && NST >= 2, "unsupported pipeline shape");
+    extern __shared__ u32x4 smem[];                      // [NST][VA + VB]
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef const __attribute__((address_space(1))) void glb_void;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
 
-    // Stage image = [unit row-block 0..3][piece][128 vectors]; in the workspace the four row-blocks
-    // of one k-block are kblocks*P*128 vectors apart.
+    // Workgroup -> (tile, k part).  Consecutive workgroup ids go to different XCDs (8 of them,
+    // each with its own L2), so ids are remapped to give every XCD a contiguous run of tiles.
+    const int ntiles = tiles_m * tiles_n;
+    const int per_xcd = (ntiles + 7) / 8;
+    const int wg = blockIdx.x % (per_xcd * 8);
+    const int split = blockIdx.x / (per_xcd * 8);
+    const int tile = (wg % 8) * per_xcd + wg / 8;
+    if (tile >= ntiles) return;
+    // Within the run, tiles are walked in groups of kGroup tile rows, column by column, so that
+    // the 32 tiles an XCD works on at a time cover few distinct operand panels.
+    constexpr int kGroup = 16 / TM;                      // 1024 rows of op(A) per group
+    const int per_group = kGroup * tiles_n;
+    const int group = tile / per_group, in_group = tile % per_group;
+    const int rows_here = min(kGroup, tiles_m - group * kGroup);
+    const int tm = group * kGroup + in_group % rows_here, tn = in_group / rows_here;
+    const int kb0 = SPLIT ? split * kb_per_split : 0;
+    const int kb1 = SPLIT ? min(kblocks, kb0 + kb_per_split) : kblocks;
+    const int steps = (kb1 - kb0) * (2 / KS);            // stages to consume
+
+    // Stage image per operand = [unit row-block][piece][SV vectors]; in the workspace a unit's
+    // piece is 128 vectors (two 16-k halves) and row-blocks are kblocks*P*128 vectors apart.
     const size_t rb_stride = (size_t)kblocks * P * kUnitVec;
-    const u32x4 *ga[kLoads], *gb[kLoads];
+    const u32x4 *ga[LA], *gb[LB];
 #pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-        const int q = j * 256 + tid;
-        const int rbl = q / (P * kUnitVec), rest = q % (P * kUnitVec);
-        ga[j] = Aw + ((size_t)tm * kTileUnits + rbl) * rb_stride + rest;
-        gb[j] = Bw + ((size_t)tn * kTileUnits + rbl) * rb_stride + rest;
+    for (int j = 0; j < LA; ++j) {
+        const int q = min(j * 256 + tid, VA - 1);
+        const int rbl = q / (P * SV), piece = (q % (P * SV)) / SV, v = q % SV;
+        ga[j] = Aw + ((size_t)tm * UA + rbl) * rb_stride + (size_t)kb0 * P * kUnitVec + piece * kUnitVec + v;
+    }
+#pragma unroll
+    for (int j = 0; j < LB; ++j) {
+        const int q = min(j * 256 + tid, VB - 1);
+        const int rbl = q / (P * SV), piece = (q % (P * SV)) / SV, v = q % SV;
+        gb[j] = Bw + ((size_t)tn * UB + rbl) * rb_stride + (size_t)kb0 * P * kUnitVec + piece * kUnitVec + v;
     }
 
-    floatx16 acc[2][2];
+    floatx16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    u32x4 ra[kLoads], rb[kLoads];
+    // Loads of stage t (clamped to the last one, so that the number of loads in flight is the
+    // same in every trip; a clamped load lands in a buffer nobody reads any more).
+    auto issue = [&](int t) {
+        const int tc = min(t, steps - 1);
+        u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
+        const size_t off = KS == 2 ? (size_t)tc * P * kUnitVec : (size_t)(tc >> 1) * P * kUnitVec + (tc & 1) * kHalf;
+#ifdef FMT_GEMM_EXPERIMENT_SAMEK
+        (void)off;
+#define off ((size_t)0)
+#endif
 #pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-        ra[j] = ga[j][0];
-        rb[j] = gb[j][0];
-    }
+        for (int j = 0; j < LA; ++j)
+            if (j * 256 + wave * 64 < VA)
+                __builtin_amdgcn_global_load_lds((glb_void *)(ga[j] + off), (lds_void *)(sa + j * 256 + wave * 64), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < LB; ++j)
+            if (j * 256 + wave * 64 < VB)
+                __builtin_amdgcn_global_load_lds((glb_void *)(gb[j] + off), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
+#ifdef FMT_GEMM_EXPERIMENT_SAMEK
+#undef off
+#endif
+    };
 
-    for (int kb = 0; kb < kblocks; ++kb) {
+    if (steps > 0) {
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            sA[j * 256 + tid] = ra[j];
-            sB[j * 256 + tid] = rb[j];
-        }
-        __syncthreads();
-        if (kb + 1 < kblocks) {
-            const size_t off = (size_t)(kb + 1) * P * kUnitVec;
+        for (int t = 0; t < NST - 1; ++t) issue(t);
+    }
+    for (int t = 0; t < steps; ++t) {
+        // stage t has landed once at most the loads of the NST-2 younger stages are in flight
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLanded & 0xF) | ((kWaitLanded >> 4) << 14));
+        __syncthreads();                         // ... for every wave; and stage t-1 is no longer read
+        issue(t + NST - 1);                      // refills the buffer of stage t-1
+        const u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
 #pragma unroll
-            for (int j = 0; j < kLoads; ++j) {
-                ra[j] = ga[j][off];
-                rb[j] = gb[j][off];
-            }
-        }
+        for (int kk = 0; kk < KS; ++kk) {
+            bf16x8 fa[TM][P], fb[TN][P];
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            bf16x8 fa[2][P], fb[2][P];
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int q = 0; q < P; ++q)
+                    fa[i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
 #pragma unroll
-                for (int q = 0; q < P; ++q) {
-                    fa[i][q] = __builtin_bit_cast(bf16x8, sA[((wm * 2 + i) * P + q) * kUnitVec + kk * 64 + lane]);
-                    fb[i][q] = __builtin_bit_cast(bf16x8, sB[((wn * 2 + i) * P + q) * kUnitVec + kk * 64 + lane]);
-                }
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int q = 0; q < P; ++q)
+                    fb[j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int qa = 0; qa < P; ++qa)
 #pragma unroll
                         for (int qb = 0; qb < P; ++qb)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][qa], fb[j][qb], acc[i][j], 0, 0, 0);
         }
-        __syncthreads();
     }
+    // every load-to-LDS of this wave must have landed before the workgroup's LDS is handed back
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 
     // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    float *out = SPLIT ? C + (size_t)split * M * ldc : C;
     const int col_in = lane & 31, row_half = (lane >> 5) * 4;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = tn * kTile + wn * 64 + j * 32 + col_in;
-            const int row0 = tm * kTile + wm * 64 + i * 32 + row_half;
+        for (int j = 0; j < TN; ++j) {
+            const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
+            const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
             if (col < N) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < M) C[(size_t)row * ldc + col] = acc[i][j][v];
+                    if (row < M) out[(size_t)row * ldc + col] = acc[i][j][v];
                 }
             }
         }
+}
+
+// C[r][c] = sum over the k parts of part[s][r][c]  (parts are dense M x N slabs)
+__global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ part, int nsplit, float *__restrict__ C,
+                                                     int M, int N, int64_t ldc)
+{
+    const size_t total = (size_t)M * N;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        float s = 0.0f;
+        for (int q = 0; q < nsplit; ++q) s += part[(size_t)q * total + i];
+        C[(i / N) * ldc + i % N] = s;
+    }
 }
 
 __global__ void zero_fill_kernel(float *__restrict__ C, int M, int N, int64_t ldc, int col_blocks)
@@ -208,48 +281,149 @@ __global__ void zero_fill_kernel(float *__restrict__ C, int M, int N, int64_t ld
     if (col < N && row < M) C[(size_t)row * ldc + col] = 0.0f;
 }
 
+struct Plan {
+    int tm, tn;      // wave tile in MFMA tiles; workgroup tile = 64*tm x 64*tn
+    int nsplit;      // k parts
+};
+
+// Pipeline shape per tile shape: k16 steps per stage and number of stage buffers.
+template <int TM, int TN> struct Pipe { static constexpr int ks = FMT_GEMM_KS, nst = FMT_GEMM_NST; };
+
+static constexpr size_t lds_bytes(int tm, int tn, int pieces, int ks, int nst)
+{
+    return (size_t)nst * (2 * tm + 2 * tn) * pieces * 64 * ks * sizeof(u32x4);
+}
+
+// Picks the workgroup tile and the number of k parts from a small cost model: large tiles move
+// fewer LDS and L2 bytes per MFMA, but the grid has to fill 256 compute units; cutting k fills
+// them at the price of writing and re-reading partial sums.
+static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
+{
+    static const struct { int tm, tn; double eff; } shapes[] = {{4, 4, 1.15}, {4, 2, 1.0}, {2, 4, 1.0}, {2, 2, 0.8}, {1, 1, 0.45}};
+    if (const char *env = getenv("FMT_GEMM_PLAN")) {      // tuning override: "tm,tn,nsplit"
+        Plan forced{2, 2, 1};
+        if (sscanf(env, "%d,%d,%d", &forced.tm, &forced.tn, &forced.nsplit) == 3) {
+            for (const auto &sh : shapes)
+                if (sh.tm == forced.tm && sh.tn == forced.tn && forced.nsplit >= 1 && forced.nsplit <= 64 &&
+                    lds_bytes(sh.tm, sh.tn, pieces, FMT_GEMM_KS, FMT_GEMM_NST) <= 160 * 1024)
+                    return forced;
+        }
+    }
+    Plan best{2, 2, 1};
+    double best_t = 1e300;
+    for (const auto &sh : shapes) {
+        if (lds_bytes(sh.tm, sh.tn, pieces, FMT_GEMM_KS, FMT_GEMM_NST) > 160 * 1024) continue;
+        const int bm = 64 * sh.tm, bn = 64 * sh.tn;
+        const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+        for (int ns = 1; ns <= 32; ns = ns < 4 ? ns + 1 : ns * 2) {
+            if (ns > 1 && kblocks / ns < 8) break;
+            const int kb_per = (kblocks + ns - 1) / ns;
+            const long wgs = tiles * ns;
+            const long rounds = (wgs + cus - 1) / cus;
+            // MFMA time of one workgroup (arbitrary units) + fixed start-up/epilogue cost
+            const double t_wg = (double)bm * bn * kb_per / sh.eff + 40.0 * bm * bn / 128.0;
+            double t = rounds * t_wg;
+            if (ns > 1) t += 2.5 * (double)M * N * (ns + 1) / cus * 8.0;   // partial sums out and back
+            if (t < best_t) { best_t = t; best = Plan{sh.tm, sh.tn, ns}; }
+        }
+    }
+    return best;
+}
+
+template <int P, int TM, int TN>
+static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int kblocks, int nsplit,
+                          float *part, hipStream_t stream)
+{
+    constexpr int KS = Pipe<TM, TN>::ks, NST = Pipe<TM, TN>::nst;
+    constexpr size_t lds = lds_bytes(TM, TN, P, KS, NST);
+    if (lds > 160 * 1024) return FMT_ERR_SHAPE;            // never chosen by make_plan
+    const int tiles_m = (M + 64 * TM - 1) / (64 * TM), tiles_n = (N + 64 * TN - 1) / (64 * TN);
+    const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
+    if (per_xcd * 8 * nsplit >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
+    const int kb_per = (kblocks + nsplit - 1) / nsplit;
+    if (nsplit == 1) {
+        auto kern = product_kernel<P, TM, TN, KS, NST, false>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), lds, stream, Aw, Bw, C, M, N, ldc, kblocks,
+                           tiles_m, tiles_n, kb_per);
+        FMT_HIP_CHECK(hipGetLastError());
+    } else {
+        auto kern = product_kernel<P, TM, TN, KS, NST, true>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), lds, stream, Aw, Bw, part, M, N,
+                           (int64_t)N, kblocks, tiles_m, tiles_n, kb_per);
+        FMT_HIP_CHECK(hipGetLastError());
+        const size_t total = (size_t)M * N;
+        const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
+        hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, nsplit, C, M, N, ldc);
+        FMT_HIP_CHECK(hipGetLastError());
+    }
+    return FMT_OK;
+}
+
 template <int MODE, bool FTZ, int P>
 static int run(int transA, int transB, int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
                float *C, int64_t ldc, const QuantParams &p, hipStream_t stream)
 {
+    int cus = 0;
+    int rc = device_cu_count(&cus);
+    if (rc != FMT_OK) return rc;
     const int kblocks = (K + kUnitK - 1) / kUnitK;
-    const int tiles_m = (M + kTile - 1) / kTile, tiles_n = (N + kTile - 1) / kTile;
-    const size_t a_vec = (size_t)tiles_m * kTileUnits * kblocks * P * kUnitVec;
-    const size_t b_vec = (size_t)tiles_n * kTileUnits * kblocks * P * kUnitVec;
+    const Plan plan = make_plan(M, N, kblocks, cus, P);
+    const int units_m = (M + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
+    const int units_n = (N + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
+    const size_t a_vec = (size_t)units_m * kblocks * P * kUnitVec;
+    const size_t b_vec = (size_t)units_n * kblocks * P * kUnitVec;
+    const size_t part_bytes = plan.nsplit > 1 ? (size_t)plan.nsplit * M * N * sizeof(float) : 0;
     Scratch s;
-    int rc = get_scratch(stream, 0, (a_vec + b_vec) * sizeof(u32x4), &s);
+    rc = get_scratch(stream, 0, (a_vec + b_vec) * sizeof(u32x4) + part_bytes, &s);
     if (rc != FMT_OK) return rc;
     u32x4 *Aw = static_cast<u32x4 *>(s.gemm_ws);
     u32x4 *Bw = Aw + a_vec;
+    float *part = reinterpret_cast<float *>(Bw + b_vec);
     const uint32_t *Au = reinterpret_cast<const uint32_t *>(A), *Bu = reinterpret_cast<const uint32_t *>(B);
 
     // op(A) is M x K: k-contiguous unless transposed.  op(B) is K x N, consumed as N rows of K:
     // k-contiguous when B is stored transposed (N x K).
     const int slabs64 = (kblocks + 1) / 2;
     const int64_t lim = (int64_t)1 << 31;
-    if ((int64_t)slabs64 * tiles_m * kTileUnits >= lim || (int64_t)slabs64 * tiles_n * kTileUnits >= lim ||
-        (int64_t)kblocks * tiles_m * 2 >= lim || (int64_t)kblocks * tiles_n * 2 >= lim)
+    if ((int64_t)slabs64 * units_m >= lim || (int64_t)slabs64 * units_n >= lim || (int64_t)kblocks * units_m >= lim ||
+        (int64_t)kblocks * units_n >= lim)
         return FMT_ERR_SHAPE;
     if (!transA) {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true>), dim3(slabs64 * tiles_m * kTileUnits), dim3(256), 0,
-                           stream, Au, lda, M, K, kblocks, slabs64, p, Aw);
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true>), dim3(slabs64 * units_m), dim3(256), 0, stream, Au, lda, M,
+                           K, kblocks, slabs64, p, Aw);
     } else {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false>), dim3(kblocks * tiles_m * kTileUnits / 2), dim3(256), 0,
-                           stream, Au, lda, M, K, kblocks, kblocks, p, Aw);
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false>), dim3(kblocks * units_m / 2), dim3(256), 0, stream, Au,
+                           lda, M, K, kblocks, kblocks, p, Aw);
     }
     FMT_HIP_CHECK(hipGetLastError());
     if (transB) {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true>), dim3(slabs64 * tiles_n * kTileUnits), dim3(256), 0,
-                           stream, Bu, ldb, N, K, kblocks, slabs64, p, Bw);
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true>), dim3(slabs64 * units_n), dim3(256), 0, stream, Bu, ldb, N,
+                           K, kblocks, slabs64, p, Bw);
     } else {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false>), dim3(kblocks * tiles_n * kTileUnits / 2), dim3(256), 0,
-                           stream, Bu, ldb, N, K, kblocks, kblocks, p, Bw);
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false>), dim3(kblocks * units_n / 2), dim3(256), 0, stream, Bu,
+                           ldb, N, K, kblocks, kblocks, p, Bw);
     }
     FMT_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL((product_kernel<P>), dim3(tiles_m * tiles_n), dim3(256), 0, stream, Aw, Bw, C, M, N, ldc, kblocks,
-                       tiles_n);
-    FMT_HIP_CHECK(hipGetLastError());
-    return FMT_OK;
+#define FMT_PRODUCT(TMV, TNV) \
+    launch_product<P, TMV, TNV>(Aw, Bw, C, M, N, ldc, kblocks, plan.nsplit, part, stream)
+    if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
+    if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
+    if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
+    if (plan.tm == 2 && plan.tn == 2) return FMT_PRODUCT(2, 2);
+    return FMT_PRODUCT(1, 1);
+#undef FMT_PRODUCT
 }
 
 template <int MODE, bool FTZ>
@@ -275,7 +449,6 @@ int launch_gemm(int transA, int transB, int64_t M64, int64_t N64, int64_t K64, c
         FMT_HIP_CHECK(hipGetLastError());
         return FMT_OK;
     }
-    if ((int64_t)((M + kTile - 1) / kTile) * ((N + kTile - 1) / kTile) >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
     const int pieces = f.m <= 7 ? 1 : (f.m <= 15 ? 2 : 3);
     const bool ftz = f.denorm == 0;
 #define FMT_RUN(MD)                                                                                       \
