@@ -37,8 +37,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), scaled by the same counters on a plain copy kernel; None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# (profiles/stream_kernel_config5_hbm_traffic.md), scaled by the same counters on a plain 1 GiB copy.
+MEASURED_TRAFFIC_BYTES = 2150088704   # profiles/stream_kernel_config5_hbm_traffic.md
 
 
 def main() -> int:
@@ -48,6 +48,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--n", type=int, default=1 << 28, help="elements of the stream tensor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-copy", action="store_true",
+                    help="also run three plain device-to-device copies of the stream tensor before the warm-up: "
+                         "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); "
@@ -134,6 +138,10 @@ def main() -> int:
         if record is not None:
             record.append(marks)
 
+    if args.profile_copy:
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -203,7 +211,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(8.0 * n / (per_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES,
+            "traffic": MEASURED_TRAFFIC_BYTES if n == (1 << 28) else None,
             "launch_ms": round(per_launch_ms, 4),
             "algorithmic_bytes_per_launch": 8 * n,
         },
