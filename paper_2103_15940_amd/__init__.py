@@ -11,6 +11,12 @@ import ctypes
 import os
 from typing import NamedTuple, Optional
 
+# torch is imported before libfmt.so is loaded on purpose: torch ships its own copy of the HIP
+# runtime, and the tensors whose pointers are handed to libfmt live in that runtime's context.
+# Loading torch first makes libfmt bind to the same runtime (same SONAME) instead of bringing a
+# second one into the process, which would not see torch's device.
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # FMT_LIB_PATH selects another build of the same library (tuning builds); default: the in-tree one
 LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")

@@ -1,6 +1,8 @@
 // C-ABI entry points of libfmt: argument validation, format constants, scratch management.
 // The arithmetic lives in fmt_stream.hip (quantize / histogram) and fmt_gemm.hip.
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -9,6 +11,12 @@
 #include "fmt_internal.h"
 
 namespace fmt {
+
+void report_hip_error(const char *expr, const char *file, int line, hipError_t err)
+{
+    if (std::getenv("FMT_VERBOSE"))
+        std::fprintf(stderr, "libfmt: %s failed at %s:%d: %s\n", expr, file, line, hipGetErrorString(err));
+}
 
 static bool format_ok(fmt_format_t f) { return f.e >= 2 && f.e <= 8 && f.m >= 1 && f.m <= 23; }
 

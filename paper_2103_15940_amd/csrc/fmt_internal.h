@@ -52,13 +52,17 @@ int launch_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
                 const float *A, int64_t lda, const float *B, int64_t ldb,
                 float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
 
-#define FMT_HIP_CHECK(expr)                          \
-    do {                                             \
-        hipError_t err__ = (expr);                   \
-        if (err__ != hipSuccess) {                   \
-            (void)hipGetLastError();                 \
-            return FMT_ERR_HIP;                      \
-        }                                            \
+// Reports a failed HIP call on stderr when the environment variable FMT_VERBOSE is set.
+void report_hip_error(const char *expr, const char *file, int line, hipError_t err);
+
+#define FMT_HIP_CHECK(expr)                                          \
+    do {                                                             \
+        hipError_t err__ = (expr);                                   \
+        if (err__ != hipSuccess) {                                   \
+            ::fmt::report_hip_error(#expr, __FILE__, __LINE__, err__); \
+            (void)hipGetLastError();                                 \
+            return FMT_ERR_HIP;                                      \
+        }                                                            \
     } while (0)
 
 }  // namespace fmt
