@@ -71,7 +71,7 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
 
 // prepare: X is the fp32 operand, `rows` x K after op(); element (r, k) sits at X[r*ld + k]
 // (KCONTIG) or X[k*ld + r].  1-D grid of nslabs * (row groups): slab = 64 k (KCONTIG) or 32 k.
-template <int MODE, bool FTZ, int P, bool KCONTIG>
+template <int MODE, bool FTZ, int P, bool KCONTIG, bool VEC4>
 __global__ __launch_bounds__(256) void prepare_kernel(const uint32_t *__restrict__ X, int64_t ld, int rows, int K,
                                                       int kblocks, int nslabs, QuantParams p, u32x4 *__restrict__ W)
 {
@@ -89,12 +89,23 @@ __global__ __launch_bounds__(256) void prepare_kernel(const uint32_t *__restrict
     }
     if (k0 >= kblocks * kUnitK) return;      // KCONTIG slabs cover two k-blocks; the last may be half
     uint32_t v[8];
+    if (KCONTIG && VEC4 && row < rows && k0 + 8 <= K) {
+        // two 128-bit loads (host checked: base 16-byte aligned, ld a multiple of 4)
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(X + (size_t)row * ld + k0);
+        const u32x4 lo = __builtin_nontemporal_load(src), hi = __builtin_nontemporal_load(src + 1);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int k = k0 + j;
-        const bool ok = row < rows && k < K;
-        const size_t idx = KCONTIG ? (size_t)row * ld + k : (size_t)k * ld + row;
-        v[j] = ok ? X[idx] : 0u;
+        for (int j = 0; j < 4; ++j) {
+            v[j] = lo[j];
+            v[4 + j] = hi[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = k0 + j;
+            const bool ok = row < rows && k < K;
+            const size_t idx = KCONTIG ? (size_t)row * ld + k : (size_t)k * ld + row;
+            v[j] = ok ? X[idx] : 0u;
+        }
     }
     uint32_t pc[8][P];
 #pragma unroll
@@ -400,20 +411,29 @@ static int run(int transA, int transB, int M, int N, int K, const float *A, int6
     if ((int64_t)slabs64 * units_m >= lim || (int64_t)slabs64 * units_n >= lim || (int64_t)kblocks * units_m >= lim ||
         (int64_t)kblocks * units_n >= lim)
         return FMT_ERR_SHAPE;
+    auto vec_ok = [](const void *ptr, int64_t ld) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0 && ld % 4 == 0; };
     if (!transA) {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true>), dim3(slabs64 * units_m), dim3(256), 0, stream, Au, lda, M,
-                           K, kblocks, slabs64, p, Aw);
+        if (vec_ok(A, lda))
+            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, true>), dim3(slabs64 * units_m), dim3(256), 0, stream,
+                               Au, lda, M, K, kblocks, slabs64, p, Aw);
+        else
+            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, false>), dim3(slabs64 * units_m), dim3(256), 0, stream,
+                               Au, lda, M, K, kblocks, slabs64, p, Aw);
     } else {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false>), dim3(kblocks * units_m / 2), dim3(256), 0, stream, Au,
-                           lda, M, K, kblocks, kblocks, p, Aw);
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false, false>), dim3(kblocks * units_m / 2), dim3(256), 0, stream,
+                           Au, lda, M, K, kblocks, kblocks, p, Aw);
     }
     FMT_HIP_CHECK(hipGetLastError());
     if (transB) {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true>), dim3(slabs64 * units_n), dim3(256), 0, stream, Bu, ldb, N,
-                           K, kblocks, slabs64, p, Bw);
+        if (vec_ok(B, ldb))
+            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, true>), dim3(slabs64 * units_n), dim3(256), 0, stream,
+                               Bu, ldb, N, K, kblocks, slabs64, p, Bw);
+        else
+            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, false>), dim3(slabs64 * units_n), dim3(256), 0, stream,
+                               Bu, ldb, N, K, kblocks, slabs64, p, Bw);
     } else {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false>), dim3(kblocks * units_n / 2), dim3(256), 0, stream, Bu,
-                           ldb, N, K, kblocks, kblocks, p, Bw);
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false, false>), dim3(kblocks * units_n / 2), dim3(256), 0, stream,
+                           Bu, ldb, N, K, kblocks, kblocks, p, Bw);
     }
     FMT_HIP_CHECK(hipGetLastError());
 #define FMT_PRODUCT(TMV, TNV) \
