@@ -69,28 +69,46 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
     return (((size_t)rb * kblocks + kb) * P + piece) * kUnitVec + c * kUnitRows + row;
 }
 
-// prepare: X is the fp32 operand, `rows` x K after op(); element (r, k) sits at X[r*ld + k]
-// (KCONTIG) or X[k*ld + r].  1-D grid of nslabs * (row groups): slab = 64 k (KCONTIG) or 32 k.
-template <int MODE, bool FTZ, int P, bool KCONTIG, bool VEC4>
-__global__ __launch_bounds__(256) void prepare_kernel(const uint32_t *__restrict__ X, int64_t ld, int rows, int K,
-                                                      int kblocks, int nslabs, QuantParams p, u32x4 *__restrict__ W)
+// One operand of a prepare launch: X is fp32, `rows` x K after op(); element (r, k) sits at
+// X[r*ld + k] (kcontig) or X[k*ld + r].  vec4: base 16-byte aligned and ld a multiple of 4.
+struct PrepOperand {
+    const uint32_t *X;
+    u32x4 *W;
+    int64_t ld;
+    int rows;
+    int kcontig;
+    int vec4;
+    unsigned nblocks;   // workgroups of this operand: slabs * row groups
+};
+
+// prepare: both operands of a product in one launch (workgroups [0, a.nblocks) take op(A), the
+// rest op(B)).  k-contiguous input: a workgroup takes 32 rows x 64 k, 8 neighbouring lanes read
+// 256 contiguous bytes of a row; transposed input: 64 rows x 32 k, a wave reads 256 contiguous
+// bytes for each k.
+template <int MODE, bool FTZ, int P>
+__global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p)
 {
     const int tid = threadIdx.x;
-    const int bx = blockIdx.x % nslabs, by = blockIdx.x / nslabs;
+    const bool second = blockIdx.x >= a.nblocks;
+    const PrepOperand &o = second ? b : a;
+    const unsigned bid = blockIdx.x - (second ? a.nblocks : 0u);
+    const uint32_t *__restrict__ X = o.X;
+    const int64_t ld = o.ld;
+    const int rows = o.rows;
+    const bool kcontig = o.kcontig != 0;
+    const int nslabs = kcontig ? (kblocks + 1) / 2 : kblocks;
+    const int bx = bid % nslabs, by = bid / nslabs;
     int row, k0;
-    if (KCONTIG) {
-        // 32 rows x 64 k per workgroup; 8 neighbouring lanes read 256 contiguous bytes of one row
+    if (kcontig) {
         row = by * 32 + tid / 8;
         k0 = bx * 64 + (tid % 8) * 8;
     } else {
-        // 64 rows x 32 k per workgroup; a wave reads 256 contiguous bytes for each k
         row = by * 64 + tid % 64;
         k0 = bx * 32 + (tid / 64) * 8;
     }
-    if (k0 >= kblocks * kUnitK) return;      // KCONTIG slabs cover two k-blocks; the last may be half
+    if (k0 >= kblocks * kUnitK) return;      // k-contiguous slabs cover two k-blocks; the last may be half
     uint32_t v[8];
-    if (KCONTIG && VEC4 && row < rows && k0 + 8 <= K) {
-        // two 128-bit loads (host checked: base 16-byte aligned, ld a multiple of 4)
+    if (kcontig && o.vec4 && row < rows && k0 + 8 <= K) {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(X + (size_t)row * ld + k0);
         const u32x4 lo = __builtin_nontemporal_load(src), hi = __builtin_nontemporal_load(src + 1);
 #pragma unroll
@@ -103,7 +121,7 @@ __global__ __launch_bounds__(256) void prepare_kernel(const uint32_t *__restrict
         for (int j = 0; j < 8; ++j) {
             const int k = k0 + j;
             const bool ok = row < rows && k < K;
-            const size_t idx = KCONTIG ? (size_t)row * ld + k : (size_t)k * ld + row;
+            const size_t idx = kcontig ? (size_t)row * ld + k : (size_t)k * ld + row;
             v[j] = ok ? X[idx] : 0u;
         }
     }
@@ -114,12 +132,12 @@ __global__ __launch_bounds__(256) void prepare_kernel(const uint32_t *__restrict
     const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
 #pragma unroll
     for (int q = 0; q < P; ++q) {
-        u32x4 o;
-        o[0] = pc[0][q] | (pc[1][q] << 16);
-        o[1] = pc[2][q] | (pc[3][q] << 16);
-        o[2] = pc[4][q] | (pc[5][q] << 16);
-        o[3] = pc[6][q] | (pc[7][q] << 16);
-        W[unit_vec_index(rb, kb, kblocks, P, q, c, rr)] = o;
+        u32x4 w;
+        w[0] = pc[0][q] | (pc[1][q] << 16);
+        w[1] = pc[2][q] | (pc[3][q] << 16);
+        w[2] = pc[4][q] | (pc[5][q] << 16);
+        w[3] = pc[6][q] | (pc[7][q] << 16);
+        o.W[unit_vec_index(rb, kb, kblocks, P, q, c, rr)] = w;
     }
 }
 
@@ -129,7 +147,7 @@ __global__ __launch_bounds__(256) void prepare_kernel(const uint32_t *__restrict
 // into LDS (global_load_lds, 16 bytes per lane) through a ring of NST stage buffers, one barrier
 // per stage.  With SPLIT the k range is cut into parts and each part writes its own M x N slab
 // of partial sums (summed by reduce_kernel).
-template <int P, int TM, int TN, int KS, int NST, bool SPLIT>
+template <int P, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int kblocks,
                                                       int tiles_m, int tiles_n, int kb_per_split)
@@ -206,11 +224,11 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
 #endif
 #pragma unroll
         for (int j = 0; j < LA; ++j)
-            if (j * 256 + wave * 64 < VA)
+            if (VA % 256 == 0 || j * 256 + wave * 64 < VA)
                 __builtin_amdgcn_global_load_lds((glb_void *)(ga[j] + off), (lds_void *)(sa + j * 256 + wave * 64), 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < LB; ++j)
-            if (j * 256 + wave * 64 < VB)
+            if (VB % 256 == 0 || j * 256 + wave * 64 < VB)
                 __builtin_amdgcn_global_load_lds((glb_void *)(gb[j] + off), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
 #ifdef FMT_GEMM_EXPERIMENT_SAMEK
 #undef off
@@ -225,21 +243,27 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
         // stage t has landed once at most the loads of the NST-2 younger stages are in flight
         __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLanded & 0xF) | ((kWaitLanded >> 4) << 14));
         __syncthreads();                         // ... for every wave; and stage t-1 is no longer read
-        issue(t + NST - 1);                      // refills the buffer of stage t-1
         const u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
+        // all operand fragments of the stage first, then the refill of stage t-1's buffer: the
+        // compiler keeps LDS reads and loads-to-LDS in program order, so only this order lets
+        // it thread the global loads between the MFMAs
+        bf16x8 fa[KS][TM][P], fb[KS][TN][P];
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
-            bf16x8 fa[TM][P], fb[TN][P];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int q = 0; q < P; ++q)
-                    fa[i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
+                    fa[kk][i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int q = 0; q < P; ++q)
-                    fb[j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
+                    fb[kk][j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
+        }
+        issue(t + NST - 1);                      // refills the buffer of stage t-1
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -248,7 +272,26 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                     for (int qa = 0; qa < P; ++qa)
 #pragma unroll
                         for (int qb = 0; qb < P; ++qb)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][qa], fb[j][qb], acc[i][j], 0, 0, 0);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i][qa], fb[kk][j][qb], acc[i][j], 0, 0, 0);
+        }
+        // Issue order inside one trip: a few operand reads up front, then LDS reads and the next
+        // stage's global loads threaded between MFMAs so that they issue in the MFMAs' shadow.
+        if (SCHED) {
+            constexpr int kMfma = TM * TN * P * P * KS, kReads = (TM + TN) * P * KS, kLoads = LA + LB;
+            constexpr int kFront = (TM + TN) * P / 2 > 4 ? (TM + TN) * P / 2 : 4;
+            __builtin_amdgcn_sched_group_barrier(0x100, kFront, 0);
+#pragma unroll
+            for (int r = 0; r < kReads - kFront; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            constexpr int kLeft = kMfma - (kReads - kFront);
+            constexpr int kPer = kLeft / (kLoads + 1) > 0 ? kLeft / (kLoads + 1) : 1;
+#pragma unroll
+            for (int r = 0; r < kLoads; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
         }
     }
     // every load-to-LDS of this wave must have landed before the workgroup's LDS is handed back
@@ -295,6 +338,7 @@ __global__ void zero_fill_kernel(float *__restrict__ C, int M, int N, int64_t ld
 struct Plan {
     int tm, tn;      // wave tile in MFMA tiles; workgroup tile = 64*tm x 64*tn
     int nsplit;      // k parts
+    int sched;       // 1: pin the issue order inside a trip (sched_group_barrier), 0: leave it to the compiler
 };
 
 // Pipeline shape per tile shape: k16 steps per stage and number of stage buffers.
@@ -305,22 +349,25 @@ static constexpr size_t lds_bytes(int tm, int tn, int pieces, int ks, int nst)
     return (size_t)nst * (2 * tm + 2 * tn) * pieces * 64 * ks * sizeof(u32x4);
 }
 
-// Picks the workgroup tile and the number of k parts from a small cost model: large tiles move
-// fewer LDS and L2 bytes per MFMA, but the grid has to fill 256 compute units; cutting k fills
-// them at the price of writing and re-reading partial sums.
+// Picks the workgroup tile and the number of k parts from a small cost model fitted to
+// measurements on MI355X: large tiles move fewer LDS and L2 bytes per MFMA, small tiles need
+// several resident workgroups per compute unit to reach their rate, the busiest compute unit sets
+// the time, and cutting k fills the machine at the price of writing and re-reading partial sums.
 static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
 {
-    static const struct { int tm, tn; double eff; } shapes[] = {{4, 4, 1.15}, {4, 2, 1.0}, {2, 4, 1.0}, {2, 2, 0.8}, {1, 1, 0.45}};
-    if (const char *env = getenv("FMT_GEMM_PLAN")) {      // tuning override: "tm,tn,nsplit"
-        Plan forced{2, 2, 1};
-        if (sscanf(env, "%d,%d,%d", &forced.tm, &forced.tn, &forced.nsplit) == 3) {
+    // eff1 / effmax: relative MFMA rate of a compute unit with one / with max_occ resident workgroups
+    static const struct { int tm, tn, max_occ; double eff1, effmax; } shapes[] = {
+        {4, 4, 1, 1.15, 1.15}, {4, 2, 1, 1.0, 1.0}, {2, 4, 1, 1.03, 1.03}, {2, 2, 2, 0.80, 0.95}, {1, 1, 4, 0.45, 0.78}};
+    if (const char *env = getenv("FMT_GEMM_PLAN")) {      // tuning override: "tm,tn,nsplit[,sched]"
+        Plan forced{2, 2, 1, 1};
+        if (sscanf(env, "%d,%d,%d,%d", &forced.tm, &forced.tn, &forced.nsplit, &forced.sched) >= 3) {
             for (const auto &sh : shapes)
                 if (sh.tm == forced.tm && sh.tn == forced.tn && forced.nsplit >= 1 && forced.nsplit <= 64 &&
                     lds_bytes(sh.tm, sh.tn, pieces, FMT_GEMM_KS, FMT_GEMM_NST) <= 160 * 1024)
                     return forced;
         }
     }
-    Plan best{2, 2, 1};
+    Plan best{2, 2, 1, 0};
     double best_t = 1e300;
     for (const auto &sh : shapes) {
         if (lds_bytes(sh.tm, sh.tn, pieces, FMT_GEMM_KS, FMT_GEMM_NST) > 160 * 1024) continue;
@@ -330,55 +377,58 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
             if (ns > 1 && kblocks / ns < 8) break;
             const int kb_per = (kblocks + ns - 1) / ns;
             const long wgs = tiles * ns;
-            const long rounds = (wgs + cus - 1) / cus;
-            // MFMA time of one workgroup (arbitrary units) + fixed start-up/epilogue cost
-            const double t_wg = (double)bm * bn * kb_per / sh.eff + 40.0 * bm * bn / 128.0;
-            double t = rounds * t_wg;
+            const long per_cu = (wgs + cus - 1) / cus;                  // workgroups on the busiest compute unit
+            const long resident = per_cu < sh.max_occ ? per_cu : sh.max_occ;
+            const double eff = sh.max_occ > 1 ? sh.eff1 + (sh.effmax - sh.eff1) * (resident - 1) / (sh.max_occ - 1) : sh.eff1;
+            // MFMA time on that compute unit (arbitrary units) + start-up / epilogue cost per workgroup
+            double t = per_cu * ((double)bm * bn * kb_per / eff + 40.0 * bm * bn / 128.0);
             if (ns > 1) t += 2.5 * (double)M * N * (ns + 1) / cus * 8.0;   // partial sums out and back
-            if (t < best_t) { best_t = t; best = Plan{sh.tm, sh.tn, ns}; }
+            if (t < best_t) { best_t = t; best = Plan{sh.tm, sh.tn, ns, sh.tm * sh.tn > 4}; }
         }
     }
     return best;
 }
 
-template <int P, int TM, int TN>
-static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int kblocks, int nsplit,
-                          float *part, hipStream_t stream)
+template <int P, int TM, int TN, bool SPLIT, bool SCHED>
+static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int kblocks,
+                            int nsplit, hipStream_t stream)
 {
     constexpr int KS = Pipe<TM, TN>::ks, NST = Pipe<TM, TN>::nst;
     constexpr size_t lds = lds_bytes(TM, TN, P, KS, NST);
-    if (lds > 160 * 1024) return FMT_ERR_SHAPE;            // never chosen by make_plan
     const int tiles_m = (M + 64 * TM - 1) / (64 * TM), tiles_n = (N + 64 * TN - 1) / (64 * TN);
     const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
     if (per_xcd * 8 * nsplit >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
     const int kb_per = (kblocks + nsplit - 1) / nsplit;
-    if (nsplit == 1) {
-        auto kern = product_kernel<P, TM, TN, KS, NST, false>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            attr_done = true;
-        }
-        hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), lds, stream, Aw, Bw, C, M, N, ldc, kblocks,
-                           tiles_m, tiles_n, kb_per);
-        FMT_HIP_CHECK(hipGetLastError());
-    } else {
-        auto kern = product_kernel<P, TM, TN, KS, NST, true>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            attr_done = true;
-        }
-        hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), lds, stream, Aw, Bw, part, M, N,
-                           (int64_t)N, kblocks, tiles_m, tiles_n, kb_per);
-        FMT_HIP_CHECK(hipGetLastError());
-        const size_t total = (size_t)M * N;
-        const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
-        hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, nsplit, C, M, N, ldc);
-        FMT_HIP_CHECK(hipGetLastError());
+    auto kern = product_kernel<P, TM, TN, KS, NST, SPLIT, SCHED>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_done = true;
     }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), lds, stream, Aw, Bw, out, M, N, ld,
+                       kblocks, tiles_m, tiles_n, kb_per);
+    FMT_HIP_CHECK(hipGetLastError());
+    return FMT_OK;
+}
+
+template <int P, int TM, int TN>
+static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int kblocks,
+                          const Plan &plan, float *part, hipStream_t stream)
+{
+    if (lds_bytes(TM, TN, P, Pipe<TM, TN>::ks, Pipe<TM, TN>::nst) > 160 * 1024) return FMT_ERR_SHAPE;   // never planned
+    if (plan.nsplit == 1) {
+        return plan.sched ? launch_product_v<P, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream)
+                          : launch_product_v<P, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream);
+    }
+    int rc = plan.sched
+                 ? launch_product_v<P, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream)
+                 : launch_product_v<P, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream);
+    if (rc != FMT_OK) return rc;
+    const size_t total = (size_t)M * N;
+    const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
+    hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc);
+    FMT_HIP_CHECK(hipGetLastError());
     return FMT_OK;
 }
 
@@ -406,38 +456,25 @@ static int run(int transA, int transB, int M, int N, int K, const float *A, int6
 
     // op(A) is M x K: k-contiguous unless transposed.  op(B) is K x N, consumed as N rows of K:
     // k-contiguous when B is stored transposed (N x K).
-    const int slabs64 = (kblocks + 1) / 2;
-    const int64_t lim = (int64_t)1 << 31;
-    if ((int64_t)slabs64 * units_m >= lim || (int64_t)slabs64 * units_n >= lim || (int64_t)kblocks * units_m >= lim ||
-        (int64_t)kblocks * units_n >= lim)
-        return FMT_ERR_SHAPE;
-    auto vec_ok = [](const void *ptr, int64_t ld) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0 && ld % 4 == 0; };
-    if (!transA) {
-        if (vec_ok(A, lda))
-            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, true>), dim3(slabs64 * units_m), dim3(256), 0, stream,
-                               Au, lda, M, K, kblocks, slabs64, p, Aw);
-        else
-            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, false>), dim3(slabs64 * units_m), dim3(256), 0, stream,
-                               Au, lda, M, K, kblocks, slabs64, p, Aw);
-    } else {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false, false>), dim3(kblocks * units_m / 2), dim3(256), 0, stream,
-                           Au, lda, M, K, kblocks, kblocks, p, Aw);
-    }
-    FMT_HIP_CHECK(hipGetLastError());
-    if (transB) {
-        if (vec_ok(B, ldb))
-            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, true>), dim3(slabs64 * units_n), dim3(256), 0, stream,
-                               Bu, ldb, N, K, kblocks, slabs64, p, Bw);
-        else
-            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, true, false>), dim3(slabs64 * units_n), dim3(256), 0, stream,
-                               Bu, ldb, N, K, kblocks, slabs64, p, Bw);
-    } else {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P, false, false>), dim3(kblocks * units_n / 2), dim3(256), 0, stream,
-                           Bu, ldb, N, K, kblocks, kblocks, p, Bw);
-    }
+    if ((int64_t)kblocks * units_m + (int64_t)kblocks * units_n >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
+    auto operand = [&](const uint32_t *X, int64_t ld, int rows, int units, bool kcontig, u32x4 *W) {
+        PrepOperand o;
+        o.X = X;
+        o.W = W;
+        o.ld = ld;
+        o.rows = rows;
+        o.kcontig = kcontig;
+        o.vec4 = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 4 == 0;
+        o.nblocks = kcontig ? (unsigned)((kblocks + 1) / 2) * units : (unsigned)kblocks * (units / 2);
+        return o;
+    };
+    const PrepOperand oa = operand(Au, lda, M, units_m, !transA, Aw);
+    const PrepOperand ob = operand(Bu, ldb, N, units_n, transB != 0, Bw);
+    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P>), dim3(oa.nblocks + ob.nblocks), dim3(256), 0, stream, oa, ob, K,
+                       kblocks, p);
     FMT_HIP_CHECK(hipGetLastError());
 #define FMT_PRODUCT(TMV, TNV) \
-    launch_product<P, TMV, TNV>(Aw, Bw, C, M, N, ldc, kblocks, plan.nsplit, part, stream)
+    launch_product<P, TMV, TNV>(Aw, Bw, C, M, N, ldc, kblocks, plan, part, stream)
     if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
     if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
     if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
