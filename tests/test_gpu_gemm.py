@@ -254,3 +254,24 @@ def test_config4_bert_layer_full_size(fmt):
         e2, _ = _sampled_check(fmt, dY, W, f, False, False, 1000, 5)
         e3, _ = _sampled_check(fmt, dY, X, f, True, False, 1000, 6)
         assert e1 <= TOL and e2 <= TOL and e3 <= TOL, (layer["name"], e1, e2, e3)
+
+
+@pytest.mark.parametrize("plan", ["1,1,1", "1,1,3", "2,2,1,0", "2,2,1,1", "2,2,4", "2,4,1", "2,4,2", "4,2,1", "4,2,3",
+                                  "4,4,1,0", "4,4,1,1", "4,4,2"])
+def test_every_tile_shape_and_split(fmt, plan, monkeypatch):
+    """The product kernel's tile shapes, issue-order variants and k splits, forced through the tuning
+    override, on a shape with ragged tiles in M, N and K (K spans several splits)."""
+    monkeypatch.setenv("FMT_GEMM_PLAN", plan)
+    rng = np.random.default_rng(21)
+    M, N, K = 300, 270, 1100
+    A = (rng.standard_normal((M, K)) * 2.0 ** -6).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * 2.0 ** -6).astype(np.float32)
+    for f in [(6, 9, True), (8, 7, False), (7, 18, True)]:
+        for (tA, tB) in [(False, True), (True, False)]:
+            got, ref = run(fmt, A, B, f, tA, tB)
+            assert rel_fro(got, ref) <= TOL, (plan, f, tA, tB)
+    # exact case: bit-identical whatever the tile or the split
+    Ai = rng.integers(-7, 8, (M, K)).astype(np.float32)
+    Bi = rng.integers(-7, 8, (K, N)).astype(np.float32)
+    got, ref = run(fmt, Ai, Bi, (6, 9, True))
+    assert np.array_equal(got, ref)

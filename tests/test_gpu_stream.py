@@ -221,3 +221,33 @@ def test_non_default_stream(fmt):
     s.synchronize()
     assert_same_values(y.cpu().numpy(), oracle.quantize(x, 6, 9, True), "side stream")
     assert_same_hist(fmt, hist, oracle.histogram(x, 6, 9), "side stream")
+
+
+def test_config5_full_size(fmt):
+    """Configuration 5 at its full size (2^28 elements, the launch shape bench.py times): the
+    integer statistics must equal the oracle's over the whole tensor, and the values are checked
+    element by element on a 2^22-element sample made of 64 slices spread over the tensor
+    (including its first and last elements)."""
+    n = 1 << 28
+    x = workloads.config5(n=n)
+    xd = dev(x)
+    y = torch.empty_like(xd)
+    want_hist = oracle.histogram(x, 6, 9)                     # one pass of the oracle over 2^28 elements
+    rng = np.random.default_rng(55)
+    starts = np.concatenate([[0, n - (1 << 16)], rng.integers(0, n - (1 << 16), 62)])
+    for (e, m, d) in [(6, 9, True), (6, 9, False)]:
+        hist = fmt.new_hist()
+        fmt.fmt_quantize(xd, (e, m, d), out=y, hist=hist)
+        torch.cuda.synchronize()
+        assert_same_hist(fmt, hist, want_hist, "config5 full 1/%d/%d" % (e, m))
+        for s in starts:
+            s = int(s)
+            got = y[s:s + (1 << 16)].cpu().numpy()
+            assert_same_values(got, oracle.quantize(x[s:s + (1 << 16)], e, m, d), "slice at %d" % s)
+    # the other formats: statistics must satisfy the format-independent invariants at full size
+    for (e, m) in [(5, 10), (8, 7)]:
+        h = fmt.hist_to_dict(fmt.fmt_histogram(xd, (e, m, True)))
+        assert h["total"] == n == sum(h[k] for k in fmt.CLASS_NAMES[1:])
+        assert np.array_equal(h["bins"], want_hist["bins"])
+        assert int(h["bins"].sum()) == n - h["zero"] - h["nan"]
+        assert h["zero"] == want_hist["zero"] and h["nan"] == want_hist["nan"] and h["inf"] == want_hist["inf"]
