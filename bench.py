@@ -218,6 +218,24 @@ def main() -> int:
         "input_generation_s": round(gen_s, 1),
     }
 
+    # configuration 3 in all six variants (outside the step; informational): useful TFLOP/s of fwd+dgrad+wgrad
+    per_format = {}
+    for name, f in workloads.FORMATS.items():
+        def conv3():
+            fmt.fmt_gemm(xcol, w, f, transB=True, out=out_fwd)
+            fmt.fmt_gemm(dy, w, f, out=out_dgrad)
+            fmt.fmt_gemm(dy, xcol, f, transA=True, out=out_wgrad)
+        conv3()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(max(args.steps // 2, 1)):
+            conv3()
+        b.record()
+        torch.cuda.synchronize()
+        per_format[name] = round(3 * 2.0 * M * N * K / (a.elapsed_time(b) / max(args.steps // 2, 1) * 1e-3) / 1e12, 1)
+    result["gemm_config3"]["useful_tflops_by_format"] = per_format
+
     if not args.no_cpu_baseline:
         import oracle
         sample = min(n, 1 << 26)

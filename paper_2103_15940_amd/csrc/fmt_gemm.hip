@@ -7,7 +7,8 @@
 // exponent range, so every piece of a format with e <= 8 fits.  A product r*s is then the sum
 // of the P*P piece products, each exact inside the bf16 MFMA, accumulated in its fp32
 // accumulator: exact products, fp32 accumulation -- FMACS.  P = 1 for m <= 7 (bfloat16),
-// P = 2 for m <= 15 (1/6/9, binary16), P = 3 up to m = 23.
+// P = 2 for m <= 15 (1/6/9), P = 3 up to m = 23.  Formats whose values are all binary16 values
+// (e <= 5, m <= 10: binary16 itself) need no split: one fp16 piece on the fp16 MFMA.
 //
 // Two kernels:
 //   prepare  reads one fp32 operand (either layout), rounds it to the format, splits it and
@@ -34,6 +35,10 @@
 namespace fmt {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// Piece scheme PS: 1, 2, 3 = that many bf16 pieces; 0 = one fp16 piece (formats inside binary16).
+constexpr int pieces_of(int ps) { return ps == 0 ? 1 : ps; }
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -42,11 +47,23 @@ constexpr int kUnitK = 32;                    // k per unit (two MFMA steps of 1
 constexpr int kUnitVec = kUnitRows * kUnitK * 2 / 16;   // 16-byte vectors per unit per piece = 128
 constexpr int kRowPad = 256;                  // prepared operands are padded to a multiple of this many rows
 
-// Rounds one fp32 pattern to the format and splits the result into P bf16 patterns.
-template <int MODE, bool FTZ, int P>
-__device__ __forceinline__ void round_and_split(uint32_t u, const QuantParams &p, uint32_t (&piece)[P])
+// Rounds one fp32 pattern to the format and splits the result into the 16-bit patterns of its
+// pieces: P bf16 pieces, or the single fp16 pattern when the format's values are all binary16
+// values (e <= 5, m <= 10).
+template <int MODE, bool FTZ, int PS>
+__device__ __forceinline__ void round_and_split(uint32_t u, const QuantParams &p, uint32_t (&piece)[pieces_of(PS)])
 {
+    constexpr int P = pieces_of(PS);
     const uint32_t r = quantize_bits<MODE, FTZ>(u, p);
+    if (PS == 0) {
+        // exact fp32 -> fp16 of a value known to be representable: normal numbers by moving the
+        // fields, denormals as the integer count of 2^-24 steps (an exact fp32 product)
+        const uint32_t a = r & 0x7FFFFFFFu;
+        uint32_t h = a >= 0x38800000u ? (a - 0x38000000u) >> 13 : (uint32_t)(__uint_as_float(a) * 16777216.0f);
+        h = a >= 0x7F800000u ? (a > 0x7F800000u ? 0x7E00u : 0x7C00u) : h;
+        piece[0] = h | ((r >> 16) & 0x8000u);
+        return;
+    }
     const uint32_t hi = r & 0xFFFF0000u;
     piece[0] = hi >> 16;
     if (P >= 2) {
@@ -54,10 +71,10 @@ __device__ __forceinline__ void round_and_split(uint32_t u, const QuantParams &p
         const bool finite = (r & 0x7F800000u) != 0x7F800000u;
         const float rem = finite ? __uint_as_float(r) - __uint_as_float(hi) : 0.0f;   // exact
         const uint32_t rb = __float_as_uint(rem);
-        piece[1] = rb >> 16;
+        piece[P >= 2 ? 1 : 0] = rb >> 16;
         if (P >= 3) {
             const float rem2 = rem - __uint_as_float(rb & 0xFFFF0000u);                // exact
-            piece[2] = __float_as_uint(rem2) >> 16;
+            piece[P >= 3 ? 2 : 0] = __float_as_uint(rem2) >> 16;
         }
     }
 }
@@ -85,9 +102,10 @@ struct PrepOperand {
 // rest op(B)).  k-contiguous input: a workgroup takes 32 rows x 64 k, 8 neighbouring lanes read
 // 256 contiguous bytes of a row; transposed input: 64 rows x 32 k, a wave reads 256 contiguous
 // bytes for each k.
-template <int MODE, bool FTZ, int P>
+template <int MODE, bool FTZ, int PS>
 __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p)
 {
+    constexpr int P = pieces_of(PS);
     const int tid = threadIdx.x;
     const bool second = blockIdx.x >= a.nblocks;
     const PrepOperand &o = second ? b : a;
@@ -127,7 +145,7 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
     }
     uint32_t pc[8][P];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, P>(v[j], p, pc[j]);
+    for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
     const int rb = row / kUnitRows, rr = row % kUnitRows;
     const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
 #pragma unroll
@@ -147,11 +165,12 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
 // into LDS (global_load_lds, 16 bytes per lane) through a ring of NST stage buffers, one barrier
 // per stage.  With SPLIT the k range is cut into parts and each part writes its own M x N slab
 // of partial sums (summed by reduce_kernel).
-template <int P, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED>
+template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int kblocks,
                                                       int tiles_m, int tiles_n, int kb_per_split)
 {
+    constexpr int P = pieces_of(PS);
     constexpr int UA = 2 * TM, UB = 2 * TN;              // 32-row units per operand in the workgroup tile
     constexpr int kHalf = 64;                            // vectors of one piece of one unit per 16 k
     constexpr int SV = kHalf * KS;                       // ... per stage
@@ -272,7 +291,10 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                     for (int qa = 0; qa < P; ++qa)
 #pragma unroll
                         for (int qb = 0; qb < P; ++qb)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i][qa], fb[kk][j][qb], acc[i][j], 0, 0, 0);
+                            acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[kk][i][qa]),
+                                                                                         __builtin_bit_cast(f16x8, fb[kk][j][qb]),
+                                                                                         acc[i][j], 0, 0, 0)
+                                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i][qa], fb[kk][j][qb], acc[i][j], 0, 0, 0);
         }
         // Issue order inside one trip: a few operand reads up front, then LDS reads and the next
         // stage's global loads threaded between MFMAs so that they issue in the MFMAs' shadow.
@@ -389,17 +411,17 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
     return best;
 }
 
-template <int P, int TM, int TN, bool SPLIT, bool SCHED>
+template <int PS, int TM, int TN, bool SPLIT, bool SCHED>
 static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int kblocks,
                             int nsplit, hipStream_t stream)
 {
     constexpr int KS = Pipe<TM, TN>::ks, NST = Pipe<TM, TN>::nst;
-    constexpr size_t lds = lds_bytes(TM, TN, P, KS, NST);
+    constexpr size_t lds = lds_bytes(TM, TN, pieces_of(PS), KS, NST);
     const int tiles_m = (M + 64 * TM - 1) / (64 * TM), tiles_n = (N + 64 * TN - 1) / (64 * TN);
     const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
     if (per_xcd * 8 * nsplit >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
     const int kb_per = (kblocks + nsplit - 1) / nsplit;
-    auto kern = product_kernel<P, TM, TN, KS, NST, SPLIT, SCHED>;
+    auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED>;
     static bool attr_done = false;
     if (!attr_done) {
         FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -412,18 +434,18 @@ static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M,
     return FMT_OK;
 }
 
-template <int P, int TM, int TN>
+template <int PS, int TM, int TN>
 static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int kblocks,
                           const Plan &plan, float *part, hipStream_t stream)
 {
-    if (lds_bytes(TM, TN, P, Pipe<TM, TN>::ks, Pipe<TM, TN>::nst) > 160 * 1024) return FMT_ERR_SHAPE;   // never planned
+    if (lds_bytes(TM, TN, pieces_of(PS), Pipe<TM, TN>::ks, Pipe<TM, TN>::nst) > 160 * 1024) return FMT_ERR_SHAPE;   // never planned
     if (plan.nsplit == 1) {
-        return plan.sched ? launch_product_v<P, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream)
-                          : launch_product_v<P, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream);
+        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream)
+                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream);
     }
     int rc = plan.sched
-                 ? launch_product_v<P, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream)
-                 : launch_product_v<P, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream);
+                 ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream)
+                 : launch_product_v<PS, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream);
     if (rc != FMT_OK) return rc;
     const size_t total = (size_t)M * N;
     const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
@@ -432,10 +454,11 @@ static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int
     return FMT_OK;
 }
 
-template <int MODE, bool FTZ, int P>
+template <int MODE, bool FTZ, int PS>
 static int run(int transA, int transB, int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
                float *C, int64_t ldc, const QuantParams &p, hipStream_t stream)
 {
+    constexpr int P = pieces_of(PS);
     int cus = 0;
     int rc = device_cu_count(&cus);
     if (rc != FMT_OK) return rc;
@@ -470,11 +493,11 @@ static int run(int transA, int transB, int M, int N, int K, const float *A, int6
     };
     const PrepOperand oa = operand(Au, lda, M, units_m, !transA, Aw);
     const PrepOperand ob = operand(Bu, ldb, N, units_n, transB != 0, Bw);
-    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, P>), dim3(oa.nblocks + ob.nblocks), dim3(256), 0, stream, oa, ob, K,
+    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(oa.nblocks + ob.nblocks), dim3(256), 0, stream, oa, ob, K,
                        kblocks, p);
     FMT_HIP_CHECK(hipGetLastError());
 #define FMT_PRODUCT(TMV, TNV) \
-    launch_product<P, TMV, TNV>(Aw, Bw, C, M, N, ldc, kblocks, plan, part, stream)
+    launch_product<PS, TMV, TNV>(Aw, Bw, C, M, N, ldc, kblocks, plan, part, stream)
     if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
     if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
     if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
@@ -488,6 +511,7 @@ static int run_p(int pieces, int transA, int transB, int M, int N, int K, const 
                  int64_t ldb, float *C, int64_t ldc, const QuantParams &p, hipStream_t stream)
 {
     switch (pieces) {
+        case 0: return run<MODE, FTZ, 0>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
         case 1: return run<MODE, FTZ, 1>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
         case 2: return run<MODE, FTZ, 2>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
         default: return run<MODE, FTZ, 3>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
@@ -506,7 +530,8 @@ int launch_gemm(int transA, int transB, int64_t M64, int64_t N64, int64_t K64, c
         FMT_HIP_CHECK(hipGetLastError());
         return FMT_OK;
     }
-    const int pieces = f.m <= 7 ? 1 : (f.m <= 15 ? 2 : 3);
+    // piece scheme: one fp16 piece for formats inside binary16, else 1-3 bf16 pieces by significand width
+    const int pieces = f.m <= 7 ? 1 : (f.e <= 5 && f.m <= 10 ? 0 : (f.m <= 15 ? 2 : 3));
     const bool ftz = f.denorm == 0;
 #define FMT_RUN(MD)                                                                                       \
     (ftz ? run_p<MD, true>(pieces, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream)              \

@@ -275,3 +275,23 @@ def test_every_tile_shape_and_split(fmt, plan, monkeypatch):
     Bi = rng.integers(-7, 8, (K, N)).astype(np.float32)
     got, ref = run(fmt, Ai, Bi, (6, 9, True))
     assert np.array_equal(got, ref)
+
+
+def test_binary16_denormal_operands(fmt):
+    """1/5/10/d operands below 2^-14 (binary16 denormals) times large values: nothing may be
+    flushed on the way through the fp16 matrix path; products are small integers times powers of
+    two, so the result is exact."""
+    rng = np.random.default_rng(15)
+    A = (rng.integers(-1023, 1024, (70, 64)) * 2.0 ** -24).astype(np.float32)     # all binary16 denormals
+    B = (rng.integers(-3, 4, (64, 50)) * 2.0 ** 13).astype(np.float32)
+    got, ref = run(fmt, A, B, (5, 10, True))
+    assert np.linalg.norm(ref) > 0
+    assert np.array_equal(got, ref)
+    got_n, ref_n = run(fmt, A, B, (5, 10, False))
+    assert np.all(ref_n == 0) and np.all(got_n == 0)
+    # every binary16 value once, against the identity: the fp16 piece conversion is exact
+    from fmtdef import decode_codes
+    v = decode_codes(5, 10)
+    v = v[np.isfinite(v)].reshape(-1, 64)[:960]
+    got, ref = run(fmt, v, np.eye(64, dtype=np.float32), (5, 10, True))
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
