@@ -64,6 +64,12 @@ def _load():
                                             i64p, i64p, ctypes.c_int64, f32p,
                                             ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.oracle_gemm_sampled.restype = ctypes.c_int
+        lib.oracle_fmac.argtypes = [ctypes.c_float] * 3 + [ctypes.c_int] * 3
+        lib.oracle_fmac.restype = ctypes.c_float
+        lib.oracle_fmac8_dot.argtypes = [f32p, ctypes.c_int64, f32p, ctypes.c_int64, ctypes.c_int64] + [ctypes.c_int] * 3
+        lib.oracle_fmac8_dot.restype = ctypes.c_float
+        lib.oracle_gemm_fmac8.argtypes = lib.oracle_gemm.argtypes
+        lib.oracle_gemm_fmac8.restype = ctypes.c_int
         lib.oracle_encode.argtypes = [ctypes.c_float, ctypes.c_int, ctypes.c_int]
         lib.oracle_encode.restype = ctypes.c_uint32
         _lib = lib
@@ -157,6 +163,35 @@ def gemm_sampled(A, B, rows, cols, e: int, m: int, d: bool,
     if rc:
         raise ValueError("oracle_gemm_sampled failed: %d" % rc)
     return out
+
+
+def fmac(a: float, w: float, x: float, e: int, m: int, d: bool) -> np.float32:
+    """FMAC of Sec. III-B: the exact a + w*x rounded once to the format (a, w, x values of the format)."""
+    return np.float32(_load().oracle_fmac(np.float32(a), np.float32(w), np.float32(x), e, m, int(bool(d))))
+
+
+def fmac8_dot(w, x, e: int, m: int, d: bool) -> np.float32:
+    """Algorithm 1 (FMAC-8) on two vectors of values of the format."""
+    wa, xa = _f32(w).ravel(), _f32(x).ravel()
+    if wa.size != xa.size:
+        raise ValueError("length mismatch")
+    return np.float32(_load().oracle_fmac8_dot(_ptr(wa), 1, _ptr(xa), 1, wa.size, e, m, int(bool(d))))
+
+
+def gemm_fmac8(A, B, e: int, m: int, d: bool, transA: bool = False, transB: bool = False) -> np.ndarray:
+    """C[i][j] = FMAC-8 dot product (Algorithm 1) of row i of Q(op(A)) and column j of Q(op(B))."""
+    lib = _load()
+    Aa, Ba = _f32(A), _f32(B)
+    M, K = (Aa.shape[1], Aa.shape[0]) if transA else Aa.shape
+    K2, N = (Ba.shape[1], Ba.shape[0]) if transB else Ba.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, K2))
+    C = np.zeros((M, N), dtype=np.float32)
+    rc = lib.oracle_gemm_fmac8(int(transA), int(transB), M, N, K, _ptr(Aa), max(_lead(Aa), 1),
+                               _ptr(Ba), max(_lead(Ba), 1), _ptr(C), max(N, 1), e, m, int(bool(d)))
+    if rc:
+        raise ValueError("oracle_gemm_fmac8 failed: %d" % rc)
+    return C
 
 
 def encode(v, e: int, m: int) -> np.ndarray:

@@ -16,6 +16,7 @@
  *     range allowed (d) or flushed (n)                                (Sec. IV-A)
  *   - FMACS matmul: operands in the format, exact products,
  *     accumulation in a wider type                                    (Sec. III-B, Sec. IV-A)
+ *   - FMAC and the FMAC-8 dot product                                 (Sec. III-B, Sec. IV-A, Algorithm 1)
  *   - denormal fraction of a tensor                                   (Sec. V)
  *
  * Notation used below: e = exponent bits, m = stored mantissa bits (the "p" of
@@ -198,6 +199,95 @@ int oracle_gemm_sampled(int transA, int transB, int64_t M, int64_t N, int64_t K,
         }
         out[s] = (float)acc;
     }
+    return 0;
+}
+
+/*
+ * FMAC (Sec. III-B): a16 = o(a16 + x16 * y16), one rounding of the exact sum to the format.
+ * a, w, x are values of the format.  The product of two <= 24-bit significands is exact in fp64.
+ * The sum a + w*x is in general NOT exact in fp64 (the exponents may be far apart), and rounding
+ * it to fp64 first and to the format second could round twice.  The sum is therefore taken with
+ * "round to odd": TwoSum gives the fp64 sum s and its exact error err; when err != 0 the exact sum
+ * lies strictly between two fp64 neighbours, and the one whose last bit is odd is kept.  A value
+ * rounded to odd at 53 bits rounds to any format of <= 51 bits exactly as the exact sum would
+ * (the classic double-rounding remedy).  The format rounding is then the same as in roundfp.
+ */
+static double sum_round_to_odd(double a, double p)
+{
+    double s = a + p;
+    if (isnan(s) || isinf(s)) return s;
+    double bb = s - a;                        /* TwoSum (Knuth): err = (a - (s - bb)) + (p - bb), exact */
+    double err = (a - (s - bb)) + (p - bb);
+    if (err != 0.0) {
+        uint64_t u;
+        memcpy(&u, &s, sizeof u);
+        if ((u & 1u) == 0)                    /* s is the even neighbour: the odd one lies on err's side */
+            s = nextafter(s, err > 0.0 ? INFINITY : -INFINITY);
+    }
+    return s;
+}
+
+static float round_double_to_format(double s, int e, int m, int d)
+{
+    if (isnan(s)) return canonical_nan();
+    if (isinf(s) || s == 0.0) return (float)s;
+    double r = round_magnitude_d(fabs(s), e, m);
+    if (!d) {
+        int emin = 2 - (1 << (e - 1));
+        if (r < ldexp(1.0, emin)) r = 0.0;
+    }
+    return (float)copysign(r, s);
+}
+
+float oracle_fmac(float a, float w, float x, int e, int m, int d)
+{
+    double p = (double)w * (double)x;         /* exact */
+    return round_double_to_format(sum_round_to_odd((double)a, p), e, m, d);
+}
+
+/*
+ * FMAC-8 dot product (Sec. IV-A, Algorithm 1), in the listing's own order: a 16-bit accumulator
+ * a takes 8 consecutive FMACs; at every i that is a multiple of 8 it is first added into the
+ * fp32 master accumulator A with an fp32 addition and reset; after the loop A takes the last a
+ * and the result is R(A).  w and x hold values of the format.
+ */
+float oracle_fmac8_dot(const float *w, int64_t sw, const float *x, int64_t sx, int64_t n, int e, int m, int d)
+{
+    float A = 0.0f;
+    float a = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        if (i % 8 == 0) {
+            A = A + a;                        /* single-precision addition */
+            a = 0.0f;
+        }
+        a = oracle_fmac(a, w[i * sw], x[i * sx], e, m, d);
+    }
+    A = A + a;
+    return oracle_quantize_one(A, e, m, d);
+}
+
+/* C[i][j] = FMAC-8 dot product of row i of Q(op(A)) and column j of Q(op(B)). */
+int oracle_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                      const float *A, int64_t lda, const float *B, int64_t ldb,
+                      float *C, int64_t ldc, int e, int m, int d)
+{
+    if (!fmt_ok(e, m) || M < 0 || N < 0 || K < 0) return -1;
+    if (M == 0 || N == 0) return 0;
+    float *qa = (float *)malloc(sizeof(float) * (size_t)(M * (K ? K : 1)));
+    float *qb = (float *)malloc(sizeof(float) * (size_t)(N * (K ? K : 1)));
+    if (!qa || !qb) { free(qa); free(qb); return -2; }
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t k = 0; k < K; ++k)
+            qa[i * K + k] = oracle_quantize_one(op_at(A, lda, transA, i, k), e, m, d);
+    for (int64_t j = 0; j < N; ++j)
+        for (int64_t k = 0; k < K; ++k)
+            qb[j * K + k] = oracle_quantize_one(op_at(B, ldb, !transB, j, k), e, m, d);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j)
+            C[i * ldc + j] = oracle_fmac8_dot(qa + i * K, 1, qb + j * K, 1, K, e, m, d);
+    free(qa);
+    free(qb);
     return 0;
 }
 
