@@ -23,6 +23,8 @@
  *                  the FMACS instruction of Sec. III-B applied to a matrix product, as
  *                  used for fully connected layers and im2col convolutions in forward,
  *                  dgrad and wgrad (Sec. IV-A)
+ * and, beyond these three:
+ *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
  *
  * Conventions common to all calls
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
@@ -157,6 +159,25 @@ int fmt_histogram(const float *x, size_t n, fmt_format_t f,
 int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
              const float *A, int64_t lda, const float *B, int64_t ldb,
              float *C, int64_t ldc, fmt_format_t f, void *stream);
+
+/*
+ * fmt_gemm_fmac8 -- matrix product with the FMAC-8 accumulation of Sec. IV-A, Algorithm 1, for
+ * hardware that only offers FMAC (Sec. III-B: a16 = o(a16 + x16*y16), one rounding).
+ *
+ * C[i][j] is the dot product of row i of Q(op(A)) and column j of Q(op(B)) computed exactly as
+ * the algorithm lists it: a 16-bit accumulator a (a value of the format) takes 8 consecutive
+ * fused multiply-adds, each rounding the EXACT sum a + w_k*x_k once to the format (with the
+ * format's overflow and denormal/flush rules); at every k that is a multiple of 8 it is first
+ * added into an fp32 master accumulator with an fp32 addition and reset to zero; after the last
+ * k the master takes the last a and the result is Q(master), stored as fp32.  The order of the
+ * roundings is fixed by the algorithm, so the result is reproducible bit for bit.
+ *
+ * Arguments, layouts, limits and errors as for fmt_gemm (K == 0 gives zeros).  This path runs
+ * on the vector ALUs (a sequential chain of roundings per output), not on the matrix cores.
+ */
+int fmt_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                   const float *A, int64_t lda, const float *B, int64_t ldb,
+                   float *C, int64_t ldc, fmt_format_t f, void *stream);
 
 /*
  * fmt_format_info -- closed-form constants of a format (Sec. III; Table I), computed on

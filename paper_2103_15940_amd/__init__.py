@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_format_info", "fmt_format_thresholds",
            "fmt_release_scratch", "fmt_status_string")
 
 
@@ -67,6 +67,8 @@ def _load() -> ctypes.CDLL:
     lib.fmt_histogram.restype = ctypes.c_int
     lib.fmt_gemm.argtypes = [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64, vp, i64, _CFormat, vp]
     lib.fmt_gemm.restype = ctypes.c_int
+    lib.fmt_gemm_fmac8.argtypes = lib.fmt_gemm.argtypes
+    lib.fmt_gemm_fmac8.restype = ctypes.c_int
     dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
     lib.fmt_format_info.argtypes = [_CFormat, dp, dp, dp, ip, ip]
     lib.fmt_format_info.restype = ctypes.c_int
@@ -163,11 +165,7 @@ def fmt_histogram(x, fmt, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None):
     return hist
 
 
-def fmt_gemm(A, B, fmt, transA: bool = False, transB: bool = False, out=None, stream=None):
-    """C = Q(op(A)) Q(op(B)) with exact products and fp32 accumulation (FMACS, Sec. III-B).
-    A, B are 2-D row-major float32 GPU tensors (a row stride larger than the row length is
-    passed on as the leading dimension)."""
-    import torch
+def _gemm_call(entry, where, A, B, fmt, transA, transB, out, stream):
     for t, name in ((A, "A"), (B, "B")):
         _dev_f32(t, name)
         if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
@@ -184,10 +182,23 @@ def fmt_gemm(A, B, fmt, transA: bool = False, transB: bool = False, out=None, st
     lda = A.stride(0) if A.shape[0] > 1 else max(A.shape[1], 1)
     ldb = B.stride(0) if B.shape[0] > 1 else max(B.shape[1], 1)
     ldc = out.stride(0) if M > 1 else max(N, 1)
-    rc = _lib.fmt_gemm(int(transA), int(transB), M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb,
-                       out.data_ptr(), ldc, _cfmt(fmt), _stream_ptr(stream))
-    _check(rc, "fmt_gemm")
+    rc = entry(int(transA), int(transB), M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb,
+               out.data_ptr(), ldc, _cfmt(fmt), _stream_ptr(stream))
+    _check(rc, where)
     return out
+
+
+def fmt_gemm(A, B, fmt, transA: bool = False, transB: bool = False, out=None, stream=None):
+    """C = Q(op(A)) Q(op(B)) with exact products and fp32 accumulation (FMACS, Sec. III-B).
+    A, B are 2-D row-major float32 GPU tensors (a row stride larger than the row length is
+    passed on as the leading dimension)."""
+    return _gemm_call(_lib.fmt_gemm, "fmt_gemm", A, B, fmt, transA, transB, out, stream)
+
+
+def fmt_gemm_fmac8(A, B, fmt, transA: bool = False, transB: bool = False, out=None, stream=None):
+    """The same product with the FMAC-8 accumulation of Sec. IV-A, Algorithm 1; the result is a
+    tensor of values of the format."""
+    return _gemm_call(_lib.fmt_gemm_fmac8, "fmt_gemm_fmac8", A, B, fmt, transA, transB, out, stream)
 
 
 def fmt_format_info(fmt) -> dict:

@@ -148,13 +148,11 @@ int fmt_histogram(const float *x, size_t n, fmt_format_t f,
     return launch_stream(x, nullptr, n, p, false, hist, static_cast<hipStream_t>(stream));
 }
 
-int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
-             const float *A, int64_t lda, const float *B, int64_t ldb,
-             float *C, int64_t ldc, fmt_format_t f, void *stream)
+// Shared argument checks of the two matrix products; *launch is set when a kernel must run.
+static int check_gemm_args(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                           const float *B, int64_t ldb, float *C, int64_t ldc, bool *launch)
 {
-    QuantParams p;
-    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
-    if (rc != FMT_OK) return rc;
+    *launch = false;
     const int64_t lim = (int64_t)1 << 31;
     if (M < 0 || N < 0 || K < 0 || M >= lim || N >= lim || K >= lim) return FMT_ERR_SHAPE;
     if (M == 0 || N == 0) return FMT_OK;
@@ -173,8 +171,36 @@ int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
         const size_t cbytes = 4 * (size_t)((M - 1) * ldc + N);
         if (overlap(C, cbytes, A, abytes) || overlap(C, cbytes, B, bbytes)) return FMT_ERR_ALIAS;
     }
+    *launch = true;
+    return FMT_OK;
+}
+
+int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda, const float *B, int64_t ldb,
+             float *C, int64_t ldc, fmt_format_t f, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    bool launch = false;
+    rc = check_gemm_args(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, &launch);
+    if (rc != FMT_OK || !launch) return rc;
     return launch_gemm(transA != 0, transB != 0, M, N, K, A, lda, B, ldb, C, ldc, f, p,
                        static_cast<hipStream_t>(stream));
+}
+
+int fmt_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                   const float *A, int64_t lda, const float *B, int64_t ldb,
+                   float *C, int64_t ldc, fmt_format_t f, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    bool launch = false;
+    rc = check_gemm_args(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, &launch);
+    if (rc != FMT_OK || !launch) return rc;
+    return launch_gemm_fmac8(transA != 0, transB != 0, M, N, K, A, lda, B, ldb, C, ldc, f, p,
+                             static_cast<hipStream_t>(stream));
 }
 
 int fmt_format_info(fmt_format_t f, double *maxN, double *minN, double *minD,

@@ -52,6 +52,11 @@ int launch_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
                 const float *A, int64_t lda, const float *B, int64_t ldb,
                 float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
 
+// FMAC-8 GEMM (fmt_fmac8.hip)
+int launch_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                      const float *A, int64_t lda, const float *B, int64_t ldb,
+                      float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
+
 // Reports a failed HIP call on stderr when the environment variable FMT_VERBOSE is set.
 void report_hip_error(const char *expr, const char *file, int line, hipError_t err);
 

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_header_symbols_are_exported():
     text = open(os.path.join(ROOT, "include", "fmt.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(fmt_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(fmt_[a-z0-9_]+)\s*\(", text))
     assert declared == set(fmt.EXPORTS)
     lib = ctypes.CDLL(fmt.LIB_PATH)
     for name in declared:

@@ -1,0 +1,106 @@
+"""GPU parity of fmt_gemm_fmac8 (Sec. IV-A, Algorithm 1) against the CPU oracle: the order of the
+roundings is fixed by the algorithm, so the results must be identical bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+VARIANTS = [(5, 10, True), (5, 10, False), (6, 9, True), (6, 9, False), (8, 7, True), (8, 7, False)]
+LAYOUTS = [(False, False), (False, True), (True, False), (True, True)]
+
+
+@pytest.fixture(scope="module")
+def fmt():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_2103_15940_amd as lib
+    return lib
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run(fmt, A, B, f, tA=False, tB=False):
+    Ain = np.ascontiguousarray(A.T) if tA else A
+    Bin = np.ascontiguousarray(B.T) if tB else B
+    C = fmt.fmt_gemm_fmac8(dev(Ain), dev(Bin), f, transA=tA, transB=tB)
+    torch.cuda.synchronize()
+    ref = oracle.gemm_fmac8(Ain, Bin, f[0], f[1], f[2], transA=tA, transB=tB)
+    return C.cpu().numpy(), ref
+
+
+def assert_bits(got, ref, what):
+    g, r = got.view(np.uint32), ref.view(np.uint32)
+    if not np.array_equal(g, r):
+        bad = np.argwhere(g != r)
+        i, j = bad[0]
+        raise AssertionError("%s: %d outputs differ; first at (%d,%d): got %r want %r" %
+                             (what, len(bad), i, j, got[i, j], ref[i, j]))
+
+
+@pytest.mark.parametrize("tA,tB", LAYOUTS)
+@pytest.mark.parametrize("e,m,d", VARIANTS)
+def test_bit_exact_random(fmt, e, m, d, tA, tB):
+    rng = np.random.default_rng(100 * e + m)
+    M, N, K = 150, 70, 203                # ragged tiles; K not a multiple of 8 or of the stage
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * 2.0 ** -3).astype(np.float32)
+    got, ref = run(fmt, A, B, (e, m, d), tA, tB)
+    assert_bits(got, ref, "1/%d/%d/%s" % (e, m, d))
+    # results are values of the format
+    assert np.array_equal(oracle.quantize(got, e, m, d).view(np.uint32), got.view(np.uint32))
+
+
+@pytest.mark.parametrize("e,m,d", VARIANTS + [(4, 3, True), (7, 14, False), (3, 5, True)])
+def test_bit_exact_wide_range(fmt, e, m, d):
+    """Operands spread over the whole range of the format: accumulator and product exponents far
+    apart (the sticky-bit cases), denormal and flushed accumulators, overflowing accumulators."""
+    rng = np.random.default_rng(7 * e + m)
+    c = oracle.format_constants(e, m)
+    span = c["Emax"] - c["Emin"]
+    A = workloads.log2_normal((90, 130), (c["Emin"] + c["Emax"]) / 4, span / 6, 0.05, rng)
+    B = workloads.log2_normal((130, 75), (c["Emin"] + c["Emax"]) / 4, span / 6, 0.05, rng)
+    got, ref = run(fmt, A, B, (e, m, d), False, True)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert_bits(np.where(nan, 0, got).astype(np.float32), np.where(nan, 0, ref).astype(np.float32), "wide range")
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (64, 64, 8), (65, 63, 9), (10, 300, 40), (200, 17, 1000)])
+def test_shapes(fmt, shape):
+    M, N, K = shape
+    rng = np.random.default_rng(M + 3 * N + 5 * K)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    got, ref = run(fmt, A, B, (6, 9, True))
+    assert_bits(got, ref, str(shape))
+
+
+def test_k_zero_and_nonfinite(fmt):
+    C = fmt.fmt_gemm_fmac8(torch.empty((4, 0), device="cuda"), torch.empty((0, 6), device="cuda"), (6, 9, True))
+    torch.cuda.synchronize()
+    assert float(C.abs().sum()) == 0.0
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((20, 24)).astype(np.float32)
+    B = rng.standard_normal((24, 20)).astype(np.float32)
+    A[2, 3] = np.inf
+    A[5, 7] = np.nan
+    B[1, 4] = 1e30                     # overflows binary16
+    got, ref = run(fmt, A, B, (5, 10, True))
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    fin = ~np.isnan(ref)
+    assert np.array_equal(got[fin].view(np.uint32), ref[fin].view(np.uint32))
+
+
+def test_mlp_layer_shapes(fmt):
+    """Configuration 2's first layer (256 x 784 -> 1024) forward with FMAC-8 in 1/6/9 and binary16."""
+    cfg = workloads.config2()
+    for f in [(6, 9, True), (5, 10, True)]:
+        got, ref = run(fmt, cfg["X"], cfg["W"][0].T.copy(), f)
+        assert_bits(got, ref, "mlp layer 1 %s" % (f,))
