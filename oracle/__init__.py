@@ -64,6 +64,9 @@ def _load():
                                             i64p, i64p, ctypes.c_int64, f32p,
                                             ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.oracle_gemm_sampled.restype = ctypes.c_int
+        lib.oracle_linear_epilogue.argtypes = [f32p, ctypes.c_int64, f32p, ctypes.c_int64, ctypes.c_int64,
+                                               f32p, ctypes.c_int64, f32p, ctypes.c_int64] + [ctypes.c_int] * 3
+        lib.oracle_linear_epilogue.restype = ctypes.c_int
         lib.oracle_fmac.argtypes = [ctypes.c_float] * 3 + [ctypes.c_int] * 3
         lib.oracle_fmac.restype = ctypes.c_float
         lib.oracle_fmac8_dot.argtypes = [f32p, ctypes.c_int64, f32p, ctypes.c_int64, ctypes.c_int64] + [ctypes.c_int] * 3
@@ -163,6 +166,32 @@ def gemm_sampled(A, B, rows, cols, e: int, m: int, d: bool,
     if rc:
         raise ValueError("oracle_gemm_sampled failed: %d" % rc)
     return out
+
+
+def linear_epilogue(acc, bias, e: int, m: int, d: bool):
+    """(Y, T) with T = R(acc) + R(bias) (fp32 addition, bias per column, may be None) and Y = R(T):
+    the output roundings of the quantized Linear layer of Sec. IV-A."""
+    lib = _load()
+    a = _f32(acc)
+    if a.ndim != 2:
+        raise ValueError("acc must be 2-D")
+    M, N = a.shape
+    b = None if bias is None else _f32(bias).ravel()
+    if b is not None and b.size != N:
+        raise ValueError("bias must have one value per column")
+    Y, T = np.empty_like(a), np.empty_like(a)
+    bp = None if b is None else _ptr(b)
+    rc = lib.oracle_linear_epilogue(_ptr(a), max(N, 1), bp, M, N, _ptr(Y), max(N, 1), _ptr(T), max(N, 1),
+                                    e, m, int(bool(d)))
+    if rc:
+        raise ValueError("oracle_linear_epilogue failed: %d" % rc)
+    return Y, T
+
+
+def linear(X, W, bias, e: int, m: int, d: bool):
+    """Quantized Linear forward of Sec. IV-A: Y = R(R(R(X) R(W)^T) + R(b)) with X [batch, in],
+    W [out, in]; the inner product is the FMACS reference of :func:`gemm`.  Returns (Y, T)."""
+    return linear_epilogue(gemm(X, W, e, m, d, transB=True), bias, e, m, d)
 
 
 def fmac(a: float, w: float, x: float, e: int, m: int, d: bool) -> np.float32:

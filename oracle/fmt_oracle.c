@@ -16,6 +16,7 @@
  *     range allowed (d) or flushed (n)                                (Sec. IV-A)
  *   - FMACS matmul: operands in the format, exact products,
  *     accumulation in a wider type                                    (Sec. III-B, Sec. IV-A)
+ *   - the quantized Linear layer Y = R(R(R(W^T) R(X)) + R(B))          (Sec. IV-A)
  *   - FMAC and the FMAC-8 dot product                                 (Sec. III-B, Sec. IV-A, Algorithm 1)
  *   - denormal fraction of a tensor                                   (Sec. V)
  *
@@ -199,6 +200,27 @@ int oracle_gemm_sampled(int transA, int transB, int64_t M, int64_t N, int64_t K,
         }
         out[s] = (float)acc;
     }
+    return 0;
+}
+
+/*
+ * Layer epilogue of the quantized Linear layer (Sec. IV-A): Y = R( R(acc) + R(b) ), where acc is
+ * the matrix product R(W^T) . R(X) before any output rounding, b the bias (one value per output
+ * column) and "+" a single-precision addition.  t = R(acc) + R(b) (the value that enters the last
+ * rounding) is returned too, since that is the tensor whose statistics are logged.
+ * bias may be NULL (then t = R(acc)).
+ */
+int oracle_linear_epilogue(const float *acc, int64_t ldacc, const float *bias, int64_t M, int64_t N,
+                           float *Y, int64_t ldy, float *T, int64_t ldt, int e, int m, int d)
+{
+    if (!fmt_ok(e, m) || M < 0 || N < 0) return -1;
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            float t = oracle_quantize_one(acc[i * ldacc + j], e, m, d);
+            if (bias) t = t + oracle_quantize_one(bias[j], e, m, d);      /* fp32 addition */
+            if (T) T[i * ldt + j] = t;
+            Y[i * ldy + j] = oracle_quantize_one(t, e, m, d);
+        }
     return 0;
 }
 
