@@ -180,6 +180,33 @@ int fmt_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
                    float *C, int64_t ldc, fmt_format_t f, void *stream);
 
 /*
+ * fmt_linear -- forward pass of the quantized fully connected layer of Sec. IV-A:
+ *
+ *     Y = R( R( R(X) R(W)^T ) + R(b) )
+ *
+ * X is the M x K input (row-major, leading dimension ldx >= K; M = batch), W the N x K weight
+ * ([out, in] as the layer stores it, ldw >= K), b the bias of N values or NULL, Y the M x N
+ * output (ldy >= N).  R is fmt_quantize's rounding to format f; the inner product is fmt_gemm's
+ * (exact products of the rounded operands, fp32 accumulation, see there for its error bound);
+ * its result is rounded to the format, the rounded bias is added with ONE single-precision
+ * addition, and the sum t is rounded again.  Given the accumulator values, t and Y are
+ * determined bit for bit.
+ *
+ * If hist is not NULL it receives the statistics (Sec. V, as fmt_histogram defines them, window
+ * starting at 2^exp_lo) of t = R(acc) + R(b), the M*N values that enter the last rounding: the
+ * classes say what that rounding does to the layer's output (how much underflows, overflows or
+ * lands in the denormal range).  hist is a DEVICE pointer; exp_lo is ignored when hist is NULL.
+ *
+ * All pointers are device pointers, 4-byte aligned; Y must not overlap X, W or b.  M or N equal
+ * to 0 succeeds (an all-zero fmt_hist_t is written); K == 0 gives t = R(b).  Dimensions and
+ * leading dimensions must be below 2^31.  Errors as for fmt_gemm and fmt_histogram.
+ */
+int fmt_linear(int64_t M, int64_t N, int64_t K,
+               const float *X, int64_t ldx, const float *W, int64_t ldw, const float *b,
+               float *Y, int64_t ldy, fmt_format_t f,
+               fmt_hist_t *hist, int32_t exp_lo, void *stream);
+
+/*
  * fmt_format_info -- closed-form constants of a format (Sec. III; Table I), computed on
  * the host.  Any output pointer may be NULL.  Returns FMT_ERR_FORMAT for an unsupported
  * format.

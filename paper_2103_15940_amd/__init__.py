@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_format_info", "fmt_format_thresholds",
            "fmt_release_scratch", "fmt_status_string")
 
 
@@ -69,6 +69,8 @@ def _load() -> ctypes.CDLL:
     lib.fmt_gemm.restype = ctypes.c_int
     lib.fmt_gemm_fmac8.argtypes = lib.fmt_gemm.argtypes
     lib.fmt_gemm_fmac8.restype = ctypes.c_int
+    lib.fmt_linear.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, _CFormat, vp, i32, vp]
+    lib.fmt_linear.restype = ctypes.c_int
     dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
     lib.fmt_format_info.argtypes = [_CFormat, dp, dp, dp, ip, ip]
     lib.fmt_format_info.restype = ctypes.c_int
@@ -199,6 +201,44 @@ def fmt_gemm_fmac8(A, B, fmt, transA: bool = False, transB: bool = False, out=No
     """The same product with the FMAC-8 accumulation of Sec. IV-A, Algorithm 1; the result is a
     tensor of values of the format."""
     return _gemm_call(_lib.fmt_gemm_fmac8, "fmt_gemm_fmac8", A, B, fmt, transA, transB, out, stream)
+
+
+def fmt_linear(X, W, bias, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None):
+    """Quantized fully connected layer of Sec. IV-A: Y = R(R(R(X) R(W)^T) + R(b)) with X [batch, in],
+    W [out, in], bias [out] or None.  With a ``hist`` buffer the statistics of t = R(acc) + R(b),
+    the values entering the last rounding, are produced in the same pass."""
+    import torch
+    for t, name in ((X, "X"), (W, "W")):
+        _dev_f32(t, name)
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("%s must be 2-D with unit column stride" % name)
+    M, K = X.shape
+    N, K2 = W.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, K2))
+    bp = None
+    if bias is not None:
+        _dev_f32(bias, "bias")
+        if bias.dim() != 1 or bias.numel() != N or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous vector with one value per output column")
+        bp = bias.data_ptr()
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    _dev_f32(out, "out")
+    if out.dim() != 2 or tuple(out.shape) != (M, N) or (N > 1 and out.stride(1) != 1):
+        raise ValueError("out must be an M x N tensor with unit column stride")
+    hp = None
+    if hist is not None:
+        if hist.dtype != torch.int64 or hist.numel() != 8 + FMT_NBINS or not hist.is_cuda:
+            raise TypeError("hist must be a GPU int64 tensor of 72 elements")
+        hp = hist.data_ptr()
+    ldx = X.stride(0) if M > 1 else max(K, 1)
+    ldw = W.stride(0) if N > 1 else max(K, 1)
+    ldy = out.stride(0) if M > 1 else max(N, 1)
+    rc = _lib.fmt_linear(M, N, K, X.data_ptr(), ldx, W.data_ptr(), ldw, bp, out.data_ptr(), ldy, _cfmt(fmt),
+                         hp, int(exp_lo), _stream_ptr(stream))
+    _check(rc, "fmt_linear")
+    return out
 
 
 def fmt_format_info(fmt) -> dict:

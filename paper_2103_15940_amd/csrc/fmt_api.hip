@@ -203,6 +203,29 @@ int fmt_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
                              static_cast<hipStream_t>(stream));
 }
 
+int fmt_linear(int64_t M, int64_t N, int64_t K,
+               const float *X, int64_t ldx, const float *W, int64_t ldw, const float *b,
+               float *Y, int64_t ldy, fmt_format_t f,
+               fmt_hist_t *hist, int32_t exp_lo, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, hist ? exp_lo : FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (hist && !aligned(hist, 8)) return FMT_ERR_ALIGN;
+    bool launch = false;
+    rc = check_gemm_args(0, 1, M, N, K, X, ldx, W, ldw, Y, ldy, &launch);
+    if (rc != FMT_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!launch) return launch_linear_epilogue(Y, ldy, 0, 0, nullptr, p, f.denorm == 0, hist, s);
+    if (b) {
+        if (!aligned(b, 4)) return FMT_ERR_ALIGN;
+        if (overlap(Y, 4 * (size_t)((M - 1) * ldy + N), b, 4 * (size_t)N)) return FMT_ERR_ALIAS;
+    }
+    rc = launch_gemm(0, 1, M, N, K, X, ldx, W, ldw, Y, ldy, f, p, s);
+    if (rc != FMT_OK) return rc;
+    return launch_linear_epilogue(Y, ldy, M, N, b, p, f.denorm == 0, hist, s);
+}
+
 int fmt_format_info(fmt_format_t f, double *maxN, double *minN, double *minD,
                     int32_t *Emin, int32_t *Emax)
 {

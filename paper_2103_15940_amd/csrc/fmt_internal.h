@@ -57,6 +57,10 @@ int launch_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const float *A, int64_t lda, const float *B, int64_t ldb,
                       float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
 
+// Output roundings of the Linear layer, in place on Y (fmt_linear.hip)
+int launch_linear_epilogue(float *Y, int64_t ldy, int64_t M, int64_t N, const float *bias, const QuantParams &p,
+                           bool ftz, fmt_hist_t *hist, hipStream_t stream);
+
 // Reports a failed HIP call on stderr when the environment variable FMT_VERBOSE is set.
 void report_hip_error(const char *expr, const char *file, int line, hipError_t err);
 

@@ -22,6 +22,7 @@
 // compare-and-add counters.  Each workgroup folds its table into 64 bins and adds them, with one
 // 64-bit atomic per non-zero slot, into one of 64 partial records in library scratch; a second
 // tiny kernel sums the 64 records into the caller's fmt_hist_t and clears them again.
+#include "fmt_hist.h"
 #include "fmt_internal.h"
 #include "fmt_quant.h"
 
@@ -41,41 +42,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlock = FMT_STREAM_BLOCK;  // threads per workgroup
 constexpr int kCopies = 32;              // replicas of the exponent table (one per LDS bank)
-constexpr int kRows = 256 + 24;          // exponent fields 0..255, then the 23 binades of fp32 denormals
 constexpr int kUnroll = FMT_STREAM_UNROLL;  // independent 128-bit loads in flight per thread
-constexpr int kSlots = 72;               // uint64 per partial record
-constexpr int kShards = 64;              // partial records in global memory (workgroup b adds into b % 64)
 constexpr int kGridPerCU = FMT_STREAM_GRID_PER_CU;   // workgroups launched per compute unit (at most)
-// slots of a partial record
-enum { P_Z = 0, P_ZU, P_ZUD, P_TOP, P_INFNAN, P_NAN, P_BINS = 8 };
-
-struct Counts {                          // per-lane counters, reduced once at the end
-    uint32_t z = 0, zu = 0, zud = 0, top = 0, infnan = 0, nan = 0;
-};
-
-// Statistics of one element: one LDS increment and four compare-and-count steps (six when the
-// wave holds an overflowing or non-finite element).
-template <bool DEEP>
-__device__ __forceinline__ void account(uint32_t a, bool valid, const QuantParams &p, uint32_t *tbl,
-                                        uint32_t lane32, Counts &w)
-{
-    uint32_t row = a >> 23;
-    if (DEEP) {
-        // fp32-denormal inputs get a row per binade so that windows reaching below 2^-126 stay exact
-        if (a - 1u < 0x007FFFFFu) row = 256u + (31u - (uint32_t)__builtin_clz(a));
-    }
-    if (valid) __hip_atomic_fetch_add(&tbl[row * kCopies + lane32], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    w.z += (valid && a == 0u) ? 1u : 0u;
-    w.zu += (valid && a <= p.t_zero) ? 1u : 0u;
-    w.zud += (valid && a < p.t_den) ? 1u : 0u;
-    const bool top = valid && a >= p.t_ovf;
-    if (__ballot(top)) {                 // wave-uniform: rare for real tensors
-        w.top += top ? 1u : 0u;
-        w.infnan += (valid && a >= 0x7F800000u) ? 1u : 0u;
-        w.nan += (valid && a > 0x7F800000u) ? 1u : 0u;
-    }
-}
-
 template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP>
 __device__ __forceinline__ u32x4 do_vec(u32x4 v, bool valid, const QuantParams &p, uint32_t *tbl, uint32_t lane32,
                                         Counts &w)
@@ -84,7 +52,7 @@ __device__ __forceinline__ u32x4 do_vec(u32x4 v, bool valid, const QuantParams &
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t u = v[j];
-        if (HIST) account<DEEP>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
+        if (HIST) account<DEEP, kCopies>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
         if (STORE) o[j] = quantize_bits<MODE, FTZ>(u, p);
     }
     return o;
@@ -99,19 +67,14 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
                                                         size_t n, size_t head, size_t nvec, QuantParams p,
                                                         unsigned long long *__restrict__ partials)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t tbl[HIST ? kRows * kCopies : 4];
+    __shared__ __attribute__((aligned(16))) uint32_t tbl[HIST ? kHistRows * kCopies : 4];
     __shared__ uint32_t s_bins[FMT_NBINS];
     __shared__ uint32_t s_cls[8];
     const uint32_t tid = threadIdx.x;
     const uint32_t lane32 = tid & (kCopies - 1);
     Counts w;
 
-    if (HIST) {
-        for (int i = tid; i < kRows * kCopies / 4; i += kBlock) reinterpret_cast<u32x4 *>(tbl)[i] = u32x4{0u, 0u, 0u, 0u};
-        if (tid < FMT_NBINS) s_bins[tid] = 0;
-        if (tid < 8) s_cls[tid] = 0;
-        __syncthreads();
-    }
+    if (HIST) hist_begin<kCopies, kBlock>(tbl, s_bins, s_cls, tid);
 
     if (VEC) {
         const u32x4 *xv = reinterpret_cast<const u32x4 *>(x + head);
@@ -151,7 +114,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
             const bool valid = tid < head + ntail;
             if (!valid) idx = 0;
             const uint32_t u = valid ? x[idx] : 0u;
-            if (HIST) account<DEEP>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
+            if (HIST) account<DEEP, kCopies>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
             if (STORE && valid) y[idx] = quantize_bits<MODE, FTZ>(u, p);
         }
     } else {
@@ -162,47 +125,12 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
         for (size_t t = 0; t < trips; ++t, i += stride) {
             const bool valid = i < n;
             const uint32_t u = valid ? x[i] : 0u;
-            if (HIST) account<DEEP>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
+            if (HIST) account<DEEP, kCopies>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
             if (STORE && valid) y[i] = quantize_bits<MODE, FTZ>(u, p);
         }
     }
 
-    if (HIST) {
-        uint32_t c[6] = {w.z, w.zu, w.zud, w.top, w.infnan, w.nan};
-#pragma unroll
-        for (int q = 0; q < 6; ++q) {
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) c[q] += __shfl_xor(c[q], off, 64);
-        }
-        if ((tid & 63) == 0) {
-#pragma unroll
-            for (int q = 0; q < 6; ++q) if (c[q]) atomicAdd(&s_cls[q], c[q]);
-        }
-        __syncthreads();
-        for (int row = tid; row < kRows; row += kBlock) {
-            uint32_t sum = 0;
-#pragma unroll 8
-            for (int c = 0; c < kCopies; ++c) sum += tbl[row * kCopies + ((c + row) & (kCopies - 1))];
-            int E;
-            if (row < 256) {
-                E = row - 127;
-                if (row == 0) sum -= s_cls[P_Z];      // zeros are not binned; what is left are fp32 denormals
-                if (row == 255) { sum -= s_cls[P_NAN]; E = 1 << 20; }   // infinities -> top bin, NaN not binned
-            } else {
-                E = row - 256 - 149;                  // binade of an fp32 denormal with leading bit row-256
-            }
-            int b = E - p.exp_lo;
-            b = b < 0 ? 0 : (b > FMT_NBINS - 1 ? FMT_NBINS - 1 : b);
-            if (sum) atomicAdd(&s_bins[b], sum);
-        }
-        __syncthreads();
-        // one 64-bit add per non-zero slot into this workgroup's shard of the partial records
-        unsigned long long *rec = partials + (size_t)(blockIdx.x % kShards) * kSlots;
-        if (tid < kSlots) {
-            const uint32_t v = tid < 8 ? s_cls[tid] : s_bins[tid - 8];
-            if (v) atomicAdd(&rec[tid], (unsigned long long)v);
-        }
-    }
+    if (HIST) hist_end<kCopies, kBlock>(tbl, s_bins, s_cls, w, p, partials, blockIdx.x % kShards, tid);
 }
 
 // Sums the shard records into the caller's fmt_hist_t and clears them for the next call (one
@@ -249,6 +177,14 @@ __global__ __launch_bounds__(1024) void finalize_kernel(unsigned long long *__re
     }
 }
 
+int launch_hist_finalize(unsigned long long *partials, size_t n, fmt_hist_t *hist, hipStream_t stream)
+{
+    hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, stream, partials, partials ? kShards : 0,
+                       (unsigned long long)n, reinterpret_cast<unsigned long long *>(hist));
+    FMT_HIP_CHECK(hipGetLastError());
+    return FMT_OK;
+}
+
 template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC>
 static int launch_variant(const float *x, float *y, size_t n, size_t head, size_t nvec, const QuantParams &p,
                           fmt_hist_t *hist, hipStream_t stream)
@@ -265,18 +201,14 @@ static int launch_variant(const float *x, float *y, size_t n, size_t head, size_
     unsigned long long *partials = nullptr;
     if (HIST) {
         Scratch s;
-        rc = get_scratch(stream, kShards * kSlots * sizeof(unsigned long long), 0, &s);
+        rc = get_scratch(stream, kHistScratchBytes, 0, &s);
         if (rc != FMT_OK) return rc;
         partials = static_cast<unsigned long long *>(s.hist_partials);
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, stream, reinterpret_cast<const uint32_t *>(x),
                        reinterpret_cast<uint32_t *>(y), n, head, nvec, p, partials);
     FMT_HIP_CHECK(hipGetLastError());
-    if (HIST) {
-        hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, stream, partials, kShards, (unsigned long long)n,
-                           reinterpret_cast<unsigned long long *>(hist));
-        FMT_HIP_CHECK(hipGetLastError());
-    }
+    if (HIST) return launch_hist_finalize(partials, n, hist, stream);
     return FMT_OK;
 }
 
@@ -287,11 +219,7 @@ int launch_stream(const float *x, float *y, size_t n, const QuantParams &p, bool
     const bool do_hist = hist != nullptr;
     const bool deep = do_hist && p.exp_lo < -126;
     if (n == 0) {
-        if (do_hist) {
-            hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, stream, nullptr, 0, 0ull,
-                               reinterpret_cast<unsigned long long *>(hist));
-            FMT_HIP_CHECK(hipGetLastError());
-        }
+        if (do_hist) return launch_hist_finalize(nullptr, 0, hist, stream);
         return FMT_OK;
     }
     // elements before the first 16-byte boundary of x (and of y: both must agree for the vector path)

@@ -87,6 +87,20 @@ def test_argument_validation_without_gpu():
     assert lib.fmt_quantize(None, None, 0, f, None, -48, None) == 0
     assert lib.fmt_gemm(0, 0, 0, 5, 3, None, 3, None, 5, None, 5, f, None) == 0
     assert lib.fmt_gemm(0, 0, 5, 0, 3, None, 3, None, 1, None, 1, f, None) == 0
+    # fmt_linear: X is M x K, W is N x K; same checks, plus the bias and the statistics record
+    bad = fmt._CFormat(9, 7, 1)
+    assert lib.fmt_linear(2, 2, 2, None, 2, None, 2, None, None, 2, bad, None, -48, None) == -1
+    assert lib.fmt_linear(2, 2, 2, None, 2, base + 64, 2, None, base + 128, 2, f, None, -48, None) == -2
+    assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, None, None, 2, f, None, -48, None) == -2
+    assert lib.fmt_linear(2, 2, 4, base, 3, base + 64, 4, None, base + 128, 2, f, None, -48, None) == -3   # ldx < K
+    assert lib.fmt_linear(2, 2, 4, base, 4, base + 64, 3, None, base + 128, 2, f, None, -48, None) == -3   # ldw < K
+    assert lib.fmt_linear(2, 4, 2, base, 2, base + 64, 2, None, base + 128, 3, f, None, -48, None) == -3   # ldy < N
+    assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, base + 33, base + 128, 2, f, None, -48, None) == -4
+    assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, None, base + 128, 2, f, base + 196, -48, None) == -4
+    assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, None, base + 128, 2, f, base + 192, 129, None) == -5
+    assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, None, base + 8, 2, f, None, -48, None) == -6     # Y over X
+    assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, base + 132, base + 128, 2, f, None, -48, None) == -6  # Y over b
+    assert lib.fmt_linear(0, 2, 2, None, 2, None, 2, None, None, 2, f, None, -48, None) == 0
 
 
 def _f32(bits):
