@@ -31,6 +31,9 @@
 #ifndef FMT_GEMM_NST
 #define FMT_GEMM_NST 2     // LDS stage buffers
 #endif
+#ifndef FMT_GEMM_REGSTAGE_P1
+#define FMT_GEMM_REGSTAGE_P1 1
+#endif
 
 namespace fmt {
 
@@ -178,6 +181,11 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
     constexpr int LA = (VA + 255) / 256, LB = (VB + 255) / 256;   // loads per lane per stage
     constexpr int kWaitLanded = ((NST - 2) * (LA + LB));  // stage loads that may still be in flight
     static_assert(kWaitLanded < 64 && (KS == 1 || KS == 2) && NST >= 2, "unsupported pipeline shape");
+    // Stage copies: loads straight into LDS, or through registers.  Single-piece operands move
+    // four times the bytes per MFMA; their small tiles are bound by the L2 -> compute unit
+    // bandwidth and measure about 10 % faster with plain loads and a late LDS store.
+    constexpr bool kDma = !(FMT_GEMM_REGSTAGE_P1 && P == 1 && TM * TN <= 4);
+    static_assert(kDma || NST == 2, "register staging uses two stage buffers");
     extern __shared__ u32x4 smem[];                      // [NST][VA + VB]
     typedef __attribute__((address_space(3))) void lds_void;
     typedef const __attribute__((address_space(1))) void glb_void;
@@ -237,10 +245,6 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
         const int tc = min(t, steps - 1);
         u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
         const size_t off = KS == 2 ? (size_t)tc * P * kUnitVec : (size_t)(tc >> 1) * P * kUnitVec + (tc & 1) * kHalf;
-#ifdef FMT_GEMM_EXPERIMENT_SAMEK
-        (void)off;
-#define off ((size_t)0)
-#endif
 #pragma unroll
         for (int j = 0; j < LA; ++j)
             if (VA % 256 == 0 || j * 256 + wave * 64 < VA)
@@ -249,18 +253,43 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
         for (int j = 0; j < LB; ++j)
             if (VB % 256 == 0 || j * 256 + wave * 64 < VB)
                 __builtin_amdgcn_global_load_lds((glb_void *)(gb[j] + off), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
-#ifdef FMT_GEMM_EXPERIMENT_SAMEK
-#undef off
-#endif
+    };
+
+    // Register-staged variant of the same stage copy: global -> VGPR (gload), VGPR -> LDS (lstore).
+    u32x4 ra[kDma ? 1 : LA], rb[kDma ? 1 : LB];
+    auto gload = [&](int t) {
+        const int tc = min(t, steps - 1);
+        const size_t off = KS == 2 ? (size_t)tc * P * kUnitVec : (size_t)(tc >> 1) * P * kUnitVec + (tc & 1) * kHalf;
+#pragma unroll
+        for (int j = 0; j < LA; ++j) ra[kDma ? 0 : j] = ga[j][off];
+#pragma unroll
+        for (int j = 0; j < LB; ++j) rb[kDma ? 0 : j] = gb[j][off];
+    };
+    auto lstore = [&](int t) {
+        u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
+#pragma unroll
+        for (int j = 0; j < LA; ++j)
+            if (VA % 256 == 0 || j * 256 + tid < VA) sa[j * 256 + tid] = ra[kDma ? 0 : j];
+#pragma unroll
+        for (int j = 0; j < LB; ++j)
+            if (VB % 256 == 0 || j * 256 + tid < VB) sb[j * 256 + tid] = rb[kDma ? 0 : j];
     };
 
     if (steps > 0) {
+        if (kDma) {
 #pragma unroll
-        for (int t = 0; t < NST - 1; ++t) issue(t);
+            for (int t = 0; t < NST - 1; ++t) issue(t);
+        } else {
+            gload(0);
+            lstore(0);
+            gload(1);
+        }
     }
     for (int t = 0; t < steps; ++t) {
-        // stage t has landed once at most the loads of the NST-2 younger stages are in flight
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLanded & 0xF) | ((kWaitLanded >> 4) << 14));
+        if (kDma) {
+            // stage t has landed once at most the loads of the NST-2 younger stages are in flight
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLanded & 0xF) | ((kWaitLanded >> 4) << 14));
+        }
         __syncthreads();                         // ... for every wave; and stage t-1 is no longer read
         const u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
         // all operand fragments of the stage first, then the refill of stage t-1's buffer: the
@@ -280,7 +309,7 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 for (int q = 0; q < P; ++q)
                     fb[kk][j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
         }
-        issue(t + NST - 1);                      // refills the buffer of stage t-1
+        if (kDma) issue(t + NST - 1);            // refills the buffer of stage t-1
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
@@ -314,6 +343,12 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
                 __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
+        }
+        if (!kDma) {
+            // stage t+1 (in registers since the previous trip) goes into the buffer stage t-1 was
+            // read from, then the loads of stage t+2 start
+            lstore(t + 1);
+            gload(t + 2);
         }
     }
     // every load-to-LDS of this wave must have landed before the workgroup's LDS is handed back
