@@ -39,6 +39,18 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+class DlsState(ctypes.Structure):
+    """State of the loss-scale controller (see oracle_dls_step in fmt_oracle.c)."""
+    _fields_ = [("loss_scale", ctypes.c_float), ("good_steps", ctypes.c_int32), ("skip", ctypes.c_int32),
+                ("steps", ctypes.c_int32), ("nonfinite", ctypes.c_uint64), ("worst_tensor", ctypes.c_int64),
+                ("worst_denormal", ctypes.c_uint64), ("worst_total", ctypes.c_uint64),
+                ("peak_tensor", ctypes.c_int64), ("peak_step", ctypes.c_int64),
+                ("peak_denormal", ctypes.c_uint64), ("peak_total", ctypes.c_uint64)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
 def _load():
     global _lib
     if _lib is None:
@@ -75,6 +87,9 @@ def _load():
         lib.oracle_gemm_fmac8.restype = ctypes.c_int
         lib.oracle_encode.argtypes = [ctypes.c_float, ctypes.c_int, ctypes.c_int]
         lib.oracle_encode.restype = ctypes.c_uint32
+        lib.oracle_dls_step.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int64, ctypes.c_float, ctypes.c_float,
+                                        ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.POINTER(DlsState)]
+        lib.oracle_dls_step.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -228,3 +243,25 @@ def encode(v, e: int, m: int) -> np.ndarray:
     lib = _load()
     va = _f32(v).ravel()
     return np.array([lib.oracle_encode(float(t), e, m) for t in va], dtype=np.uint32).reshape(np.shape(v))
+
+
+def dls_init(loss_scale: float) -> DlsState:
+    """Fresh controller state: scale S, no steps seen, no peak yet."""
+    st = DlsState()
+    st.loss_scale = loss_scale
+    st.worst_tensor = -1
+    st.peak_tensor = -1
+    st.peak_step = -1
+    return st
+
+
+def dls_step(hists, state: DlsState, growth: float = 2.0, backoff: float = 0.5, interval: int = 2000,
+             min_scale: float = 1.0, max_scale: float = 2.0 ** 24) -> DlsState:
+    """One step of the loss-scale controller on the statistics of the step's gradient tensors
+    (array of shape [count, 72], uint64); updates and returns ``state``."""
+    h = np.ascontiguousarray(np.asarray(hists, dtype=np.uint64).reshape(-1, 8 + NBINS))
+    rc = _load().oracle_dls_step(h.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)), h.shape[0], growth, backoff,
+                                 interval, min_scale, max_scale, ctypes.byref(state))
+    if rc:
+        raise ValueError("oracle_dls_step failed: %d" % rc)
+    return state

@@ -339,3 +339,82 @@ uint32_t oracle_encode(float v, int e, int m)
     }
     return (sign << (e + m)) | (field << m) | mant;
 }
+
+/*
+ * Loss-scale controller and denormal-fraction monitor, one call per training step.
+ *
+ * Sec. II describes loss scaling (the loss is multiplied by a factor S before backpropagation so
+ * that small gradients do not underflow; weight gradients are divided by S again) and names
+ * dynamic loss scaling as the automated choice of S from the gradient distribution; Sec. V logs
+ * the denormal fraction of every tensor and reports the highest one observed.  The paper gives
+ * no update rule or parameters; this is the usual controller, written out:
+ *   - the step's records are the fmt_hist-style statistics (72 uint64 each: total, zero,
+ *     underflow, denormal, normal, overflow, inf, nan, 64 bins) of the scaled gradient tensors;
+ *   - nonfinite = sum over the records of overflow + inf + nan;
+ *   - nonfinite > 0: the step is skipped, S <- max(S * backoff, min_scale), the run of good
+ *     steps restarts;
+ *   - otherwise the run grows by one, and when it reaches `interval`,
+ *     S <- min(S * growth, max_scale) and the run restarts;
+ *   - worst tensor of the step = largest denormal / total (fp64 quotient, records with
+ *     total == 0 ignored, ties to the lowest index); the running peak over all steps is replaced
+ *     when the step's worst fraction is strictly larger.
+ * The products S * backoff and S * growth are single-precision multiplications.
+ */
+typedef struct {
+    float loss_scale;
+    int32_t good_steps;
+    int32_t skip;
+    int32_t steps;
+    uint64_t nonfinite;
+    int64_t worst_tensor;
+    uint64_t worst_denormal, worst_total;
+    int64_t peak_tensor;
+    int64_t peak_step;
+    uint64_t peak_denormal, peak_total;
+} oracle_dls_state;
+
+int oracle_dls_step(const uint64_t *hists, int64_t count, float growth, float backoff, int32_t interval,
+                    float min_scale, float max_scale, oracle_dls_state *st)
+{
+    if (count < 0 || !st || interval < 1) return -1;
+    uint64_t nonfinite = 0;
+    int64_t worst = -1;
+    double worst_frac = -1.0;
+    for (int64_t i = 0; i < count; ++i) {
+        const uint64_t *h = hists + 72 * i;
+        nonfinite += h[5] + h[6] + h[7];
+        if (h[0] > 0) {
+            double frac = (double)h[3] / (double)h[0];
+            if (frac > worst_frac) { worst_frac = frac; worst = i; }
+        }
+    }
+    st->nonfinite = nonfinite;
+    st->worst_tensor = worst;
+    st->worst_denormal = worst >= 0 ? hists[72 * worst + 3] : 0;
+    st->worst_total = worst >= 0 ? hists[72 * worst + 0] : 0;
+    if (nonfinite > 0) {
+        st->skip = 1;
+        float s = st->loss_scale * backoff;
+        st->loss_scale = s < min_scale ? min_scale : s;
+        st->good_steps = 0;
+    } else {
+        st->skip = 0;
+        st->good_steps += 1;
+        if (st->good_steps >= interval) {
+            float s = st->loss_scale * growth;
+            st->loss_scale = s > max_scale ? max_scale : s;
+            st->good_steps = 0;
+        }
+    }
+    if (worst >= 0) {
+        double peak_frac = st->peak_total > 0 ? (double)st->peak_denormal / (double)st->peak_total : -1.0;
+        if (worst_frac > peak_frac) {
+            st->peak_tensor = worst;
+            st->peak_step = st->steps;
+            st->peak_denormal = st->worst_denormal;
+            st->peak_total = st->worst_total;
+        }
+    }
+    st->steps += 1;
+    return 0;
+}
