@@ -25,6 +25,8 @@
  *                  dgrad and wgrad (Sec. IV-A)
  * and, beyond these three:
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
+ *   fmt_linear     the quantized fully connected layer of Sec. IV-A (product, bias, output roundings, statistics)
+ *   fmt_dls_step   loss-scale controller and denormal-fraction monitor on the device (Sec. II, Sec. V)
  *
  * Conventions common to all calls
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
@@ -58,7 +60,7 @@ typedef enum fmt_status {
     FMT_ERR_NULL = -2,   /* a required pointer is NULL                                       */
     FMT_ERR_SHAPE = -3,  /* negative dimension, leading dimension too small, size too large  */
     FMT_ERR_ALIGN = -4,  /* a data pointer is not aligned to its element size                */
-    FMT_ERR_RANGE = -5,  /* exp_lo outside [FMT_EXP_LO_MIN, FMT_EXP_LO_MAX]                  */
+    FMT_ERR_RANGE = -5,  /* a scalar parameter is out of range (exp_lo window, loss-scale parameters) */
     FMT_ERR_ALIAS = -6,  /* GEMM output overlaps an input                                    */
     FMT_ERR_HIP = -7     /* a HIP runtime call failed (launch, allocation, no device)        */
 } fmt_status;
@@ -205,6 +207,62 @@ int fmt_linear(int64_t M, int64_t N, int64_t K,
                const float *X, int64_t ldx, const float *W, int64_t ldw, const float *b,
                float *Y, int64_t ldy, fmt_format_t f,
                fmt_hist_t *hist, int32_t exp_lo, void *stream);
+
+/*
+ * Loss scaling (Sec. II) and the per-step monitoring of Sec. V, kept on the device so that a
+ * training step never waits for the host.
+ *
+ * Sec. II: the loss is multiplied by a factor S before backpropagation so that small activation
+ * gradients do not fall into the denormal range or underflow; weight gradients are divided by S
+ * before the update; dynamic loss scaling chooses S from the gradients themselves.  Sec. V: the
+ * denormal fraction of every tensor is logged as it is computed and the highest fraction observed
+ * over all tensors is reported.  The paper states no update rule or parameters; the controller
+ * here is the customary one, with every parameter supplied by the caller.
+ *
+ * fmt_dls_state_t lives in DEVICE memory (8-byte aligned).  fmt_dls_init writes a fresh state.
+ * fmt_dls_step inspects the statistics of one training step -- `count` fmt_hist_t records,
+ * contiguous in device memory, of the step's (scaled) gradient tensors, as produced by
+ * fmt_quantize / fmt_histogram / fmt_linear -- and updates *state:
+ *   nonfinite     = sum over the records of overflow + inf + nan
+ *   nonfinite > 0 : skip = 1 (the caller must drop this step's update),
+ *                   loss_scale = max(loss_scale * backoff, min_scale), good_steps = 0
+ *   otherwise     : skip = 0, good_steps += 1, and when good_steps reaches `interval`:
+ *                   loss_scale = min(loss_scale * growth, max_scale), good_steps = 0
+ *   worst_*       = index and counts of the record with the largest denormal / total (fp64
+ *                   quotient; records with total == 0 are ignored; ties go to the lowest index;
+ *                   worst_tensor = -1 when there is none)
+ *   peak_*        = the largest such fraction over all steps so far, with the step (0-based) and
+ *                   the record index where it occurred; replaced only by a strictly larger one
+ *   steps        += 1
+ * The two products are single-precision multiplications, so the sequence of scales is reproducible
+ * bit for bit.  count == 0 is a clean step without tensors.
+ * Parameter limits (else FMT_ERR_RANGE): growth >= 1, 0 < backoff <= 1, interval >= 1,
+ * 0 < min_scale <= max_scale, all finite; fmt_dls_init: loss_scale > 0 and finite.
+ */
+typedef struct fmt_dls_state {
+    float loss_scale;      /* S: multiply the loss by it, divide the weight gradients by it */
+    int32_t good_steps;    /* length of the current run of steps without non-finite gradients */
+    int32_t skip;          /* 1: the step just inspected must be skipped */
+    int32_t steps;         /* steps inspected so far */
+    uint64_t nonfinite;    /* overflow + inf + nan over the records of the last step */
+    int64_t worst_tensor;  /* last step: record with the largest denormal fraction, or -1 */
+    uint64_t worst_denormal, worst_total;
+    int64_t peak_tensor;   /* all steps: where the largest denormal fraction occurred, or -1 */
+    int64_t peak_step;
+    uint64_t peak_denormal, peak_total;
+} fmt_dls_state_t;
+
+typedef struct fmt_dls_params {
+    float growth;          /* factor applied after `interval` clean steps, e.g. 2   */
+    float backoff;         /* factor applied on a non-finite gradient, e.g. 0.5     */
+    int32_t interval;      /* clean steps before the scale grows, e.g. 2000         */
+    float min_scale;
+    float max_scale;
+} fmt_dls_params_t;
+
+int fmt_dls_init(fmt_dls_state_t *state, float loss_scale, void *stream);
+int fmt_dls_step(const fmt_hist_t *hists, int64_t count, fmt_dls_params_t prm,
+                 fmt_dls_state_t *state, void *stream);
 
 /*
  * fmt_format_info -- closed-form constants of a format (Sec. III; Table I), computed on

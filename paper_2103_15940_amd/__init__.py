@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_release_scratch", "fmt_status_string")
 
 
@@ -46,6 +46,19 @@ FP169 = Format(6, 9, True)
 
 class _CFormat(ctypes.Structure):
     _fields_ = [("e", ctypes.c_int32), ("m", ctypes.c_int32), ("denorm", ctypes.c_int32)]
+
+
+class _CDlsParams(ctypes.Structure):
+    _fields_ = [("growth", ctypes.c_float), ("backoff", ctypes.c_float), ("interval", ctypes.c_int32),
+                ("min_scale", ctypes.c_float), ("max_scale", ctypes.c_float)]
+
+
+class _CDlsState(ctypes.Structure):
+    _fields_ = [("loss_scale", ctypes.c_float), ("good_steps", ctypes.c_int32), ("skip", ctypes.c_int32),
+                ("steps", ctypes.c_int32), ("nonfinite", ctypes.c_uint64), ("worst_tensor", ctypes.c_int64),
+                ("worst_denormal", ctypes.c_uint64), ("worst_total", ctypes.c_uint64),
+                ("peak_tensor", ctypes.c_int64), ("peak_step", ctypes.c_int64),
+                ("peak_denormal", ctypes.c_uint64), ("peak_total", ctypes.c_uint64)]
 
 
 class FmtError(RuntimeError):
@@ -71,6 +84,10 @@ def _load() -> ctypes.CDLL:
     lib.fmt_gemm_fmac8.restype = ctypes.c_int
     lib.fmt_linear.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, _CFormat, vp, i32, vp]
     lib.fmt_linear.restype = ctypes.c_int
+    lib.fmt_dls_init.argtypes = [vp, ctypes.c_float, vp]
+    lib.fmt_dls_init.restype = ctypes.c_int
+    lib.fmt_dls_step.argtypes = [vp, i64, _CDlsParams, vp, vp]
+    lib.fmt_dls_step.restype = ctypes.c_int
     dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
     lib.fmt_format_info.argtypes = [_CFormat, dp, dp, dp, ip, ip]
     lib.fmt_format_info.restype = ctypes.c_int
@@ -239,6 +256,45 @@ def fmt_linear(X, W, bias, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAUL
                          hp, int(exp_lo), _stream_ptr(stream))
     _check(rc, "fmt_linear")
     return out
+
+
+DLS_STATE_BYTES = ctypes.sizeof(_CDlsState)
+
+
+def fmt_dls_init(loss_scale: float, device=None, state=None, stream=None):
+    """A fresh loss-scale controller state in device memory (a uint8 tensor of DLS_STATE_BYTES)."""
+    import torch
+    if state is None:
+        state = torch.empty(DLS_STATE_BYTES, dtype=torch.uint8, device=device if device is not None else "cuda")
+    if state.dtype != torch.uint8 or state.numel() != DLS_STATE_BYTES or not state.is_cuda:
+        raise TypeError("state must be a GPU uint8 tensor of %d bytes" % DLS_STATE_BYTES)
+    _check(_lib.fmt_dls_init(state.data_ptr(), float(loss_scale), _stream_ptr(stream)), "fmt_dls_init")
+    return state
+
+
+def fmt_dls_step(hists, state, growth: float = 2.0, backoff: float = 0.5, interval: int = 2000,
+                 min_scale: float = 1.0, max_scale: float = 2.0 ** 24, stream=None):
+    """One step of the loss-scale controller / denormal-fraction monitor (Sec. II, Sec. V) on the
+    statistics of the step's gradient tensors: ``hists`` is a GPU int64 tensor [count, 72] (rows as
+    :func:`new_hist`), or None for a step without tensors.  Updates ``state`` on the device."""
+    import torch
+    count, hp = 0, None
+    if hists is not None:
+        if hists.dtype != torch.int64 or not hists.is_cuda or not hists.is_contiguous() or \
+                hists.numel() % (8 + FMT_NBINS):
+            raise TypeError("hists must be a contiguous GPU int64 tensor of [count, 72]")
+        count = hists.numel() // (8 + FMT_NBINS)
+        hp = hists.data_ptr() if count else None
+    prm = _CDlsParams(growth, backoff, interval, min_scale, max_scale)
+    _check(_lib.fmt_dls_step(hp, count, prm, state.data_ptr(), _stream_ptr(stream)), "fmt_dls_step")
+    return state
+
+
+def dls_state_to_dict(state) -> dict:
+    """Copies a device fmt_dls_state_t to the host."""
+    raw = bytes(state.cpu().numpy().tobytes())
+    st = _CDlsState.from_buffer_copy(raw)
+    return {name: getattr(st, name) for name, _ in _CDlsState._fields_}
 
 
 def fmt_format_info(fmt) -> dict:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfmt.so")
-SOURCES = ["fmt_api.hip", "fmt_stream.hip", "fmt_gemm.hip", "fmt_fmac8.hip", "fmt_linear.hip"]
+SOURCES = ["fmt_api.hip", "fmt_stream.hip", "fmt_gemm.hip", "fmt_fmac8.hip", "fmt_linear.hip", "fmt_dls.hip"]
 # packed-fp32 instructions are kept out of the generated code on purpose
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -226,6 +226,27 @@ int fmt_linear(int64_t M, int64_t N, int64_t K,
     return launch_linear_epilogue(Y, ldy, M, N, b, p, f.denorm == 0, hist, s);
 }
 
+int fmt_dls_init(fmt_dls_state_t *state, float loss_scale, void *stream)
+{
+    if (!state) return FMT_ERR_NULL;
+    if (!aligned(state, 8)) return FMT_ERR_ALIGN;
+    if (!(loss_scale > 0.0f) || !std::isfinite(loss_scale)) return FMT_ERR_RANGE;
+    return launch_dls_init(state, loss_scale, static_cast<hipStream_t>(stream));
+}
+
+int fmt_dls_step(const fmt_hist_t *hists, int64_t count, fmt_dls_params_t prm,
+                 fmt_dls_state_t *state, void *stream)
+{
+    if (count < 0 || count >= ((int64_t)1 << 40)) return FMT_ERR_SHAPE;
+    if (!state || (count > 0 && !hists)) return FMT_ERR_NULL;
+    if (!aligned(state, 8) || !aligned(hists, 8)) return FMT_ERR_ALIGN;
+    const bool ok = std::isfinite(prm.growth) && std::isfinite(prm.backoff) && std::isfinite(prm.min_scale) &&
+                    std::isfinite(prm.max_scale) && prm.growth >= 1.0f && prm.backoff > 0.0f && prm.backoff <= 1.0f &&
+                    prm.interval >= 1 && prm.min_scale > 0.0f && prm.min_scale <= prm.max_scale;
+    if (!ok) return FMT_ERR_RANGE;
+    return launch_dls_step(hists, count, prm, state, static_cast<hipStream_t>(stream));
+}
+
 int fmt_format_info(fmt_format_t f, double *maxN, double *minN, double *minD,
                     int32_t *Emin, int32_t *Emax)
 {
@@ -278,7 +299,7 @@ const char *fmt_status_string(int status)
         case FMT_ERR_NULL: return "a required pointer is NULL";
         case FMT_ERR_SHAPE: return "bad shape: negative or too large dimension, or leading dimension too small";
         case FMT_ERR_ALIGN: return "a data pointer is not aligned to its element size";
-        case FMT_ERR_RANGE: return "exp_lo outside the supported window range";
+        case FMT_ERR_RANGE: return "a scalar parameter is out of range (exp_lo window, loss-scale parameters)";
         case FMT_ERR_ALIAS: return "output overlaps an input";
         case FMT_ERR_HIP: return "a HIP runtime call failed";
         default: return "unknown status";

@@ -61,6 +61,11 @@ int launch_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
 int launch_linear_epilogue(float *Y, int64_t ldy, int64_t M, int64_t N, const float *bias, const QuantParams &p,
                            bool ftz, fmt_hist_t *hist, hipStream_t stream);
 
+// Loss-scale controller (fmt_dls.hip)
+int launch_dls_init(fmt_dls_state_t *state, float loss_scale, hipStream_t stream);
+int launch_dls_step(const fmt_hist_t *hists, int64_t count, fmt_dls_params_t prm, fmt_dls_state_t *state,
+                    hipStream_t stream);
+
 // Reports a failed HIP call on stderr when the environment variable FMT_VERBOSE is set.
 void report_hip_error(const char *expr, const char *file, int line, hipError_t err);
 

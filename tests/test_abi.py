@@ -29,6 +29,7 @@ def test_struct_layout():
     assert "uint64_t total, zero, underflow, denormal, normal, overflow, inf, nan;" in text
     assert ctypes.sizeof(fmt._CFormat) == 12
     assert 8 * (8 + fmt.FMT_NBINS) == 576
+    assert ctypes.sizeof(fmt._CDlsState) == 80 and ctypes.sizeof(fmt._CDlsParams) == 20
 
 
 def test_status_strings():
@@ -59,7 +60,7 @@ def test_argument_validation_without_gpu():
     """All of these return before any HIP call, so they run on a host without a GPU."""
     lib = fmt.raw_library()
     f = fmt._CFormat(6, 9, 1)
-    buf = (ctypes.c_float * 64)()
+    buf = (ctypes.c_float * 1024)()
     base = ctypes.addressof(buf)
     # null pointers
     assert lib.fmt_quantize(None, base, 4, f, None, -48, None) == -2
@@ -101,6 +102,21 @@ def test_argument_validation_without_gpu():
     assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, None, base + 8, 2, f, None, -48, None) == -6     # Y over X
     assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, base + 132, base + 128, 2, f, None, -48, None) == -6  # Y over b
     assert lib.fmt_linear(0, 2, 2, None, 2, None, 2, None, None, 2, f, None, -48, None) == 0
+    # loss-scale controller
+    P = fmt._CDlsParams
+    good = P(2.0, 0.5, 2000, 1.0, 65536.0)
+    assert lib.fmt_dls_init(None, 1024.0, None) == -2
+    assert lib.fmt_dls_init(base + 4, 1024.0, None) == -4
+    for bad_scale in (0.0, -1.0, float("inf"), float("nan")):
+        assert lib.fmt_dls_init(base, bad_scale, None) == -5
+    assert lib.fmt_dls_step(base, 1, good, None, None) == -2
+    assert lib.fmt_dls_step(None, 1, good, base, None) == -2
+    assert lib.fmt_dls_step(base, -1, good, base + 1024, None) == -3
+    assert lib.fmt_dls_step(base + 4, 1, good, base + 1024, None) == -4
+    for bad_prm in (P(0.5, 0.5, 10, 1.0, 2.0), P(2.0, 0.0, 10, 1.0, 2.0), P(2.0, 1.5, 10, 1.0, 2.0), P(2.0, 0.5, 0, 1.0, 2.0),
+                    P(2.0, 0.5, 10, 0.0, 2.0), P(2.0, 0.5, 10, 4.0, 2.0), P(float("nan"), 0.5, 10, 1.0, 2.0),
+                    P(2.0, 0.5, 10, 1.0, float("inf"))):
+        assert lib.fmt_dls_step(base, 1, bad_prm, base + 1024, None) == -5
 
 
 def _f32(bits):
