@@ -87,6 +87,9 @@ def _load():
         lib.oracle_gemm_fmac8.restype = ctypes.c_int
         lib.oracle_encode.argtypes = [ctypes.c_float, ctypes.c_int, ctypes.c_int]
         lib.oracle_encode.restype = ctypes.c_uint32
+        lib.oracle_conv2d.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int32), f32p, f32p, i64p, ctypes.c_int64, f32p,
+                                      ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_conv2d.restype = ctypes.c_int
         lib.oracle_dls_step.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int64, ctypes.c_float, ctypes.c_float,
                                         ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.POINTER(DlsState)]
         lib.oracle_dls_step.restype = ctypes.c_int
@@ -265,3 +268,57 @@ def dls_step(hists, state: DlsState, growth: float = 2.0, backoff: float = 0.5, 
     if rc:
         raise ValueError("oracle_dls_step failed: %d" % rc)
     return state
+
+
+def conv_out_size(h: int, w: int, r: int, s: int, pad, stride):
+    """Output height and width of a convolution with zero padding and no dilation."""
+    return (h + 2 * pad[0] - r) // stride[0] + 1, (w + 2 * pad[1] - s) // stride[1] + 1
+
+
+def _conv(which: int, a, b, geom, out_shape, e, m, d, sample):
+    lib = _load()
+    g = (ctypes.c_int32 * 11)(*[int(v) for v in geom])
+    aa, ba = _f32(a), _f32(b)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    if sample is None:
+        out = np.empty(out_shape, dtype=np.float32)
+        rc = lib.oracle_conv2d(which, g, _ptr(aa), _ptr(ba), None, out.size, _ptr(out), e, m, int(bool(d)))
+    else:
+        idx = np.ascontiguousarray(sample, dtype=np.int64).ravel()
+        out = np.empty(idx.size, dtype=np.float32)
+        rc = lib.oracle_conv2d(which, g, _ptr(aa), _ptr(ba), idx.ctypes.data_as(i64p), idx.size, _ptr(out),
+                               e, m, int(bool(d)))
+    if rc:
+        raise ValueError("oracle_conv2d failed: %d" % rc)
+    return out
+
+
+def _geom(xshape, wshape, pad, stride):
+    n, c, h, w = xshape
+    k, c2, r, s = wshape
+    if c != c2:
+        raise ValueError("channel mismatch")
+    return (n, c, h, w, k, r, s, pad[0], pad[1], stride[0], stride[1])
+
+
+def conv2d_fwd(X, W, e, m, d, pad=(1, 1), stride=(1, 1), sample=None) -> np.ndarray:
+    """Y[n,k,p,q] = sum_{c,r,s} Q(X)[n,c,p*sh-ph+r,q*sw-pw+s] * Q(W)[k,c,r,s] (Sec. IV-A, FMACS reference:
+    exact products, fp64 sum, one rounding to fp32).  ``sample``: flat output indices to compute only those."""
+    X, W = _f32(X), _f32(W)
+    g = _geom(X.shape, W.shape, pad, stride)
+    P, Q = conv_out_size(g[2], g[3], g[5], g[6], pad, stride)
+    return _conv(0, X, W, g, (g[0], g[4], P, Q), e, m, d, sample)
+
+
+def conv2d_dgrad(dY, W, xshape, e, m, d, pad=(1, 1), stride=(1, 1), sample=None) -> np.ndarray:
+    """dX[n,c,h,w] = sum_{k,r,s} Q(dY)[n,k,p,q] * Q(W)[k,c,r,s] over the (p, q) that read (h, w) through tap (r, s)."""
+    dY, W = _f32(dY), _f32(W)
+    g = _geom(xshape, W.shape, pad, stride)
+    return _conv(1, dY, W, g, tuple(xshape), e, m, d, sample)
+
+
+def conv2d_wgrad(dY, X, wshape, e, m, d, pad=(1, 1), stride=(1, 1), sample=None) -> np.ndarray:
+    """dW[k,c,r,s] = sum_{n,p,q} Q(dY)[n,k,p,q] * Q(X)[n,c,p*sh-ph+r,q*sw-pw+s]."""
+    dY, X = _f32(dY), _f32(X)
+    g = _geom(X.shape, wshape, pad, stride)
+    return _conv(2, dY, X, g, tuple(wshape), e, m, d, sample)

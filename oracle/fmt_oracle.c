@@ -418,3 +418,101 @@ int oracle_dls_step(const uint64_t *hists, int64_t count, float growth, float ba
     st->steps += 1;
     return 0;
 }
+
+/*
+ * Convolution layers (Sec. IV-A: the inner matrix multiplies "or convolutions" of the forward and
+ * backward pass use FMACS: operands rounded to the format, products not rounded, fp32 result).
+ * Plain definitions, NCHW tensors, filter [K][C][R][S], zero padding, no dilation, no groups.
+ * Every sum is taken in fp64 in the order written (exact products of <= 24-bit significands) and
+ * rounded once to fp32, as in oracle_gemm.
+ *   geometry g[11] = { N, C, H, W, K, R, S, pad_h, pad_w, stride_h, stride_w };
+ *   P = (H + 2 pad_h - R) / stride_h + 1,  Q = (W + 2 pad_w - S) / stride_w + 1.
+ *   forward  Y[n][k][p][q]  = sum_{c,r,s} Q(X[n][c][p*sh - ph + r][q*sw - pw + s]) * Q(Wt[k][c][r][s])
+ *   dgrad    dX[n][c][h][w] = sum_{k,r,s} Q(dY[n][k][p][q]) * Q(Wt[k][c][r][s]),  p*sh - ph + r = h, q*sw - pw + s = w
+ *   wgrad    dW[k][c][r][s] = sum_{n,p,q} Q(dY[n][k][p][q]) * Q(X[n][c][p*sh - ph + r][q*sw - pw + s])
+ * (out-of-range input positions contribute zero).  Each has a variant that computes only a list
+ * of output elements given by their flat indices.
+ */
+typedef struct { int64_t N, C, H, W, K, R, S, ph, pw, sh, sw, P, Q; } conv_geom;
+
+static int conv_geom_from(const int32_t *g, conv_geom *o)
+{
+    o->N = g[0]; o->C = g[1]; o->H = g[2]; o->W = g[3]; o->K = g[4]; o->R = g[5]; o->S = g[6];
+    o->ph = g[7]; o->pw = g[8]; o->sh = g[9]; o->sw = g[10];
+    if (o->N < 0 || o->C < 0 || o->H < 1 || o->W < 1 || o->K < 0 || o->R < 1 || o->S < 1) return -1;
+    if (o->ph < 0 || o->pw < 0 || o->sh < 1 || o->sw < 1) return -1;
+    if (o->H + 2 * o->ph < o->R || o->W + 2 * o->pw < o->S) return -1;
+    o->P = (o->H + 2 * o->ph - o->R) / o->sh + 1;
+    o->Q = (o->W + 2 * o->pw - o->S) / o->sw + 1;
+    return 0;
+}
+
+static float conv_fwd_one(const conv_geom *g, const float *X, const float *Wt, int64_t idx, int e, int m, int d)
+{
+    int64_t q = idx % g->Q, p = (idx / g->Q) % g->P, k = (idx / (g->Q * g->P)) % g->K, n = idx / (g->Q * g->P * g->K);
+    double acc = 0.0;
+    for (int64_t c = 0; c < g->C; ++c)
+        for (int64_t r = 0; r < g->R; ++r)
+            for (int64_t s = 0; s < g->S; ++s) {
+                int64_t h = p * g->sh - g->ph + r, w = q * g->sw - g->pw + s;
+                if (h < 0 || h >= g->H || w < 0 || w >= g->W) continue;
+                double x = (double)oracle_quantize_one(X[((n * g->C + c) * g->H + h) * g->W + w], e, m, d);
+                double f = (double)oracle_quantize_one(Wt[((k * g->C + c) * g->R + r) * g->S + s], e, m, d);
+                acc += x * f;
+            }
+    return (float)acc;
+}
+
+static float conv_dgrad_one(const conv_geom *g, const float *dY, const float *Wt, int64_t idx, int e, int m, int d)
+{
+    int64_t w = idx % g->W, h = (idx / g->W) % g->H, c = (idx / (g->W * g->H)) % g->C, n = idx / (g->W * g->H * g->C);
+    double acc = 0.0;
+    for (int64_t k = 0; k < g->K; ++k)
+        for (int64_t r = 0; r < g->R; ++r)
+            for (int64_t s = 0; s < g->S; ++s) {
+                int64_t ph = h + g->ph - r, pw = w + g->pw - s;
+                if (ph < 0 || pw < 0 || ph % g->sh || pw % g->sw) continue;
+                int64_t p = ph / g->sh, q = pw / g->sw;
+                if (p >= g->P || q >= g->Q) continue;
+                double y = (double)oracle_quantize_one(dY[((n * g->K + k) * g->P + p) * g->Q + q], e, m, d);
+                double f = (double)oracle_quantize_one(Wt[((k * g->C + c) * g->R + r) * g->S + s], e, m, d);
+                acc += y * f;
+            }
+    return (float)acc;
+}
+
+static float conv_wgrad_one(const conv_geom *g, const float *dY, const float *X, int64_t idx, int e, int m, int d)
+{
+    int64_t s = idx % g->S, r = (idx / g->S) % g->R, c = (idx / (g->S * g->R)) % g->C, k = idx / (g->S * g->R * g->C);
+    double acc = 0.0;
+    for (int64_t n = 0; n < g->N; ++n)
+        for (int64_t p = 0; p < g->P; ++p)
+            for (int64_t q = 0; q < g->Q; ++q) {
+                int64_t h = p * g->sh - g->ph + r, w = q * g->sw - g->pw + s;
+                if (h < 0 || h >= g->H || w < 0 || w >= g->W) continue;
+                double y = (double)oracle_quantize_one(dY[((n * g->K + k) * g->P + p) * g->Q + q], e, m, d);
+                double x = (double)oracle_quantize_one(X[((n * g->C + c) * g->H + h) * g->W + w], e, m, d);
+                acc += y * x;
+            }
+    return (float)acc;
+}
+
+/* which: 0 forward (a = X, b = Wt, out = Y), 1 dgrad (a = dY, b = Wt, out = dX), 2 wgrad (a = dY, b = X, out = dW).
+ * idx == NULL: all `count` = size-of-output elements in order; else out[i] = element idx[i]. */
+int oracle_conv2d(int which, const int32_t *geom, const float *a, const float *b, const int64_t *idx, int64_t count,
+                  float *out, int e, int m, int d)
+{
+    conv_geom g;
+    if (!fmt_ok(e, m) || conv_geom_from(geom, &g)) return -1;
+    int64_t total = which == 0 ? g.N * g.K * g.P * g.Q : which == 1 ? g.N * g.C * g.H * g.W : g.K * g.C * g.R * g.S;
+    if (!idx && count != total) return -2;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < count; ++i) {
+        int64_t j = idx ? idx[i] : i;
+        if (j < 0 || j >= total) { out[i] = NAN; continue; }
+        out[i] = which == 0 ? conv_fwd_one(&g, a, b, j, e, m, d)
+               : which == 1 ? conv_dgrad_one(&g, a, b, j, e, m, d)
+                            : conv_wgrad_one(&g, a, b, j, e, m, d);
+    }
+    return 0;
+}
