@@ -26,6 +26,7 @@
  * and, beyond these three:
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
  *   fmt_linear     the quantized fully connected layer of Sec. IV-A (product, bias, output roundings, statistics)
+ *   fmt_conv2d_*   convolution forward / dgrad / wgrad as the same product on patches gathered on the fly
  *   fmt_dls_step   loss-scale controller and denormal-fraction monitor on the device (Sec. II, Sec. V)
  *
  * Conventions common to all calls
@@ -207,6 +208,39 @@ int fmt_linear(int64_t M, int64_t N, int64_t K,
                const float *X, int64_t ldx, const float *W, int64_t ldw, const float *b,
                float *Y, int64_t ldy, fmt_format_t f,
                fmt_hist_t *hist, int32_t exp_lo, void *stream);
+
+/*
+ * Convolution layers (Sec. IV-A: the inner matrix multiplies "or convolutions" of the forward and
+ * backward pass use FMACS -- operands rounded to the format, products not rounded, fp32
+ * accumulation).  2-D convolution with zero padding, no dilation, no groups, on dense tensors:
+ *   X, dX   [n][c][h][w]            (NCHW)
+ *   W, dW   [k][c][r][s]            (k filters)
+ *   Y, dY   [n][k][P][Q],  P = (h + 2 pad_h - r) / stride_h + 1,  Q = (w + 2 pad_w - s) / stride_w + 1
+ *
+ *   fmt_conv2d_fwd    Y[n][k][p][q]  = sum_{c,r,s} Q(X)[n][c][p*stride_h - pad_h + r][q*stride_w - pad_w + s] * Q(W)[k][c][r][s]
+ *   fmt_conv2d_dgrad  dX[n][c][h][w] = sum over (k, r, s) and the (p, q) with p*stride_h - pad_h + r = h,
+ *                                      q*stride_w - pad_w + s = w  of  Q(dY)[n][k][p][q] * Q(W)[k][c][r][s]
+ *   fmt_conv2d_wgrad  dW[k][c][r][s] = sum_{n,p,q} Q(dY)[n][k][p][q] * Q(X)[n][c][p*stride_h - pad_h + r][q*stride_w - pad_w + s]
+ * (positions outside the tensor contribute zero).  These are fmt_gemm's products on the patch
+ * matrix of the convolution -- same rounding of the operands, exact products, fp32 accumulation in
+ * unspecified order, unrounded fp32 result, same error bound -- but the patch matrix (r*s times
+ * the size of the tensor) is never written to memory: the operand loader gathers the patches
+ * while it rounds.
+ *
+ * All pointers are device pointers, 4-byte aligned; the output must not overlap an input.
+ * Sizes: n, c, k >= 0; h, w, r, s >= 1; pad >= 0; stride >= 1; h + 2 pad_h >= r, w + 2 pad_w >= s;
+ * every tensor and each of n*P*Q, n*h*w, c*r*s, k*r*s must have fewer than 2^31 elements
+ * (else FMT_ERR_SHAPE).  An empty output succeeds without a launch; an empty sum gives zeros.
+ */
+typedef struct fmt_conv2d {
+    int32_t n, c, h, w;          /* input: batch, channels, height, width */
+    int32_t k, r, s;             /* filters, filter height, filter width  */
+    int32_t pad_h, pad_w, stride_h, stride_w;
+} fmt_conv2d_t;
+
+int fmt_conv2d_fwd(fmt_conv2d_t g, const float *X, const float *W, float *Y, fmt_format_t f, void *stream);
+int fmt_conv2d_dgrad(fmt_conv2d_t g, const float *dY, const float *W, float *dX, fmt_format_t f, void *stream);
+int fmt_conv2d_wgrad(fmt_conv2d_t g, const float *dY, const float *X, float *dW, fmt_format_t f, void *stream);
 
 /*
  * Loss scaling (Sec. II) and the per-step monitoring of Sec. V, kept on the device so that a

@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_release_scratch", "fmt_status_string")
 
 
@@ -46,6 +46,11 @@ FP169 = Format(6, 9, True)
 
 class _CFormat(ctypes.Structure):
     _fields_ = [("e", ctypes.c_int32), ("m", ctypes.c_int32), ("denorm", ctypes.c_int32)]
+
+
+class _CConv2d(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int32) for name in ("n", "c", "h", "w", "k", "r", "s", "pad_h", "pad_w",
+                                                     "stride_h", "stride_w")]
 
 
 class _CDlsParams(ctypes.Structure):
@@ -84,6 +89,9 @@ def _load() -> ctypes.CDLL:
     lib.fmt_gemm_fmac8.restype = ctypes.c_int
     lib.fmt_linear.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, _CFormat, vp, i32, vp]
     lib.fmt_linear.restype = ctypes.c_int
+    for fn in (lib.fmt_conv2d_fwd, lib.fmt_conv2d_dgrad, lib.fmt_conv2d_wgrad):
+        fn.argtypes = [_CConv2d, vp, vp, vp, _CFormat, vp]
+        fn.restype = ctypes.c_int
     lib.fmt_dls_init.argtypes = [vp, ctypes.c_float, vp]
     lib.fmt_dls_init.restype = ctypes.c_int
     lib.fmt_dls_step.argtypes = [vp, i64, _CDlsParams, vp, vp]
@@ -255,6 +263,73 @@ def fmt_linear(X, W, bias, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAUL
     rc = _lib.fmt_linear(M, N, K, X.data_ptr(), ldx, W.data_ptr(), ldw, bp, out.data_ptr(), ldy, _cfmt(fmt),
                          hp, int(exp_lo), _stream_ptr(stream))
     _check(rc, "fmt_linear")
+    return out
+
+
+def _pair(v):
+    return (int(v), int(v)) if isinstance(v, int) else (int(v[0]), int(v[1]))
+
+
+def _conv_geom(xshape, wshape, pad, stride):
+    n, c, h, w = (int(v) for v in xshape)
+    k, c2, r, s = (int(v) for v in wshape)
+    if c != c2:
+        raise ValueError("channel mismatch: input has %d, filter has %d" % (c, c2))
+    (ph, pw), (sh, sw) = _pair(pad), _pair(stride)
+    if sh < 1 or sw < 1 or h + 2 * ph < r or w + 2 * pw < s:
+        raise ValueError("bad convolution geometry")
+    P, Q = (h + 2 * ph - r) // sh + 1, (w + 2 * pw - s) // sw + 1
+    return _CConv2d(n, c, h, w, k, r, s, ph, pw, sh, sw), (n, k, P, Q)
+
+
+def _dense4(t, name, shape=None):
+    _dev_f32(t, name)
+    if t.dim() != 4 or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous 4-D tensor" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %r" % (name, tuple(shape)))
+
+
+def fmt_conv2d_fwd(X, W, fmt, pad=1, stride=1, out=None, stream=None):
+    """Y = conv(Q(X), Q(W)) with exact products and fp32 accumulation (Sec. IV-A); X [n,c,h,w], W [k,c,r,s],
+    Y [n,k,P,Q].  The patch matrix is gathered on the fly, never materialised."""
+    import torch
+    _dense4(X, "X")
+    _dense4(W, "W")
+    g, yshape = _conv_geom(X.shape, W.shape, pad, stride)
+    if out is None:
+        out = torch.empty(yshape, dtype=torch.float32, device=X.device)
+    _dense4(out, "out", yshape)
+    _check(_lib.fmt_conv2d_fwd(g, X.data_ptr(), W.data_ptr(), out.data_ptr(), _cfmt(fmt), _stream_ptr(stream)),
+           "fmt_conv2d_fwd")
+    return out
+
+
+def fmt_conv2d_dgrad(dY, W, xshape, fmt, pad=1, stride=1, out=None, stream=None):
+    """dX of the same convolution from dY [n,k,P,Q] and W [k,c,r,s]; ``xshape`` = (n, c, h, w)."""
+    import torch
+    _dense4(W, "W")
+    g, yshape = _conv_geom(xshape, W.shape, pad, stride)
+    _dense4(dY, "dY", yshape)
+    if out is None:
+        out = torch.empty(tuple(int(v) for v in xshape), dtype=torch.float32, device=dY.device)
+    _dense4(out, "out", xshape)
+    _check(_lib.fmt_conv2d_dgrad(g, dY.data_ptr(), W.data_ptr(), out.data_ptr(), _cfmt(fmt), _stream_ptr(stream)),
+           "fmt_conv2d_dgrad")
+    return out
+
+
+def fmt_conv2d_wgrad(dY, X, wshape, fmt, pad=1, stride=1, out=None, stream=None):
+    """dW of the same convolution from dY [n,k,P,Q] and X [n,c,h,w]; ``wshape`` = (k, c, r, s)."""
+    import torch
+    _dense4(X, "X")
+    g, yshape = _conv_geom(X.shape, wshape, pad, stride)
+    _dense4(dY, "dY", yshape)
+    if out is None:
+        out = torch.empty(tuple(int(v) for v in wshape), dtype=torch.float32, device=dY.device)
+    _dense4(out, "out", wshape)
+    _check(_lib.fmt_conv2d_wgrad(g, dY.data_ptr(), X.data_ptr(), out.data_ptr(), _cfmt(fmt), _stream_ptr(stream)),
+           "fmt_conv2d_wgrad")
     return out
 
 

@@ -226,6 +226,60 @@ int fmt_linear(int64_t M, int64_t N, int64_t K,
     return launch_linear_epilogue(Y, ldy, M, N, b, p, f.denorm == 0, hist, s);
 }
 
+// Validates a convolution call; *launch is false when the output is empty.  which: 0 forward
+// (a = X, b = W, out = Y), 1 dgrad (dY, W, dX), 2 wgrad (dY, X, dW).
+static int check_conv_args(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, bool *launch)
+{
+    *launch = false;
+    const int64_t lim = (int64_t)1 << 31;
+    if (g.n < 0 || g.c < 0 || g.k < 0 || g.h < 1 || g.w < 1 || g.r < 1 || g.s < 1) return FMT_ERR_SHAPE;
+    if (g.pad_h < 0 || g.pad_w < 0 || g.stride_h < 1 || g.stride_w < 1) return FMT_ERR_SHAPE;
+    if ((int64_t)g.h + 2 * (int64_t)g.pad_h < g.r || (int64_t)g.w + 2 * (int64_t)g.pad_w < g.s) return FMT_ERR_SHAPE;
+    if (g.pad_h >= (1 << 20) || g.pad_w >= (1 << 20)) return FMT_ERR_SHAPE;
+    const int64_t P = (g.h + 2 * g.pad_h - g.r) / g.stride_h + 1, Q = (g.w + 2 * g.pad_w - g.s) / g.stride_w + 1;
+    const int64_t hw = (int64_t)g.h * g.w, pq = P * Q, rs = (int64_t)g.r * g.s;
+    if (hw >= lim || pq >= lim || rs >= lim) return FMT_ERR_SHAPE;
+    const int64_t x_elems = (int64_t)g.n * g.c, y_elems = (int64_t)g.n * g.k, w_elems = (int64_t)g.k * g.c;
+    if (x_elems >= lim || y_elems >= lim || w_elems >= lim) return FMT_ERR_SHAPE;
+    if (x_elems * hw >= lim || y_elems * pq >= lim || w_elems * rs >= lim) return FMT_ERR_SHAPE;
+    if ((int64_t)g.n * pq >= lim || (int64_t)g.n * hw >= lim || g.c * rs >= lim || g.k * rs >= lim) return FMT_ERR_SHAPE;
+    const size_t xb = 4 * (size_t)(x_elems * hw), yb = 4 * (size_t)(y_elems * pq), wb = 4 * (size_t)(w_elems * rs);
+    const size_t ab = which == 0 ? xb : yb, bb = which == 2 ? xb : wb, ob = which == 0 ? yb : (which == 1 ? xb : wb);
+    if (ob == 0) return FMT_OK;
+    if (!out || (ab > 0 && !a) || (bb > 0 && !b)) return FMT_ERR_NULL;
+    if (!aligned(a, 4) || !aligned(b, 4) || !aligned(out, 4)) return FMT_ERR_ALIGN;
+    if ((ab > 0 && overlap(out, ob, a, ab)) || (bb > 0 && overlap(out, ob, b, bb))) return FMT_ERR_ALIAS;
+    *launch = true;
+    return FMT_OK;
+}
+
+static int conv_entry(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, fmt_format_t f,
+                      void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    bool launch = false;
+    rc = check_conv_args(which, g, a, b, out, &launch);
+    if (rc != FMT_OK || !launch) return rc;
+    return launch_conv2d(which, g, a, b, out, f, p, static_cast<hipStream_t>(stream));
+}
+
+int fmt_conv2d_fwd(fmt_conv2d_t g, const float *X, const float *W, float *Y, fmt_format_t f, void *stream)
+{
+    return conv_entry(0, g, X, W, Y, f, stream);
+}
+
+int fmt_conv2d_dgrad(fmt_conv2d_t g, const float *dY, const float *W, float *dX, fmt_format_t f, void *stream)
+{
+    return conv_entry(1, g, dY, W, dX, f, stream);
+}
+
+int fmt_conv2d_wgrad(fmt_conv2d_t g, const float *dY, const float *X, float *dW, fmt_format_t f, void *stream)
+{
+    return conv_entry(2, g, dY, X, dW, f, stream);
+}
+
 int fmt_dls_init(fmt_dls_state_t *state, float loss_scale, void *stream)
 {
     if (!state) return FMT_ERR_NULL;

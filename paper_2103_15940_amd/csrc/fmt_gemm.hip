@@ -89,8 +89,36 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
     return (((size_t)rb * kblocks + kb) * P + piece) * kUnitVec + c * kUnitRows + row;
 }
 
-// One operand of a prepare launch: X is fp32, `rows` x K after op(); element (r, k) sits at
-// X[r*ld + k] (kcontig) or X[k*ld + r].  vec4: base 16-byte aligned and ld a multiple of 4.
+// How element (row, k) of an operand is found in memory.
+enum {
+    kSrcMatrix = 0,     // X[row*ld + k] (kcontig) or X[k*ld + row]
+    kSrcPatchRows = 1,  // convolution patches: row = (n, y, x) on a grid gy x gx, k = (ch, r, s)
+    kSrcPatchK = 2,     // the same patches transposed: row = (ch, r, s), k = (n, y, x)
+    kSrcChannelRows = 3,  // NCHW tensor as a matrix: row = channel, k = (n, position)
+    kSrcFilterT = 4     // filter [K][C][R][S] with row = c, k = (kout, r, s)
+};
+
+// Geometry of a gathered operand.  Patches read T[n][ch][iy][ix] of an NCHW tensor with tc
+// channels of th x tw, where iy = (y*mul_y + off_y + tap*r) / den_y must divide exactly and lie in
+// [0, th) (else the element is zero), likewise ix.  Forward and wgrad: mul = stride, off = -pad,
+// tap = +1, den = 1; dgrad (patches of dY seen from an input position): mul = 1, off = +pad,
+// tap = -1, den = stride.
+struct Gather {
+    int kind;
+    int tc, th, tw;
+    int gy, gx;
+    int R, S;
+    int mul_y, mul_x, off_y, off_x, tap, den_y, den_x;
+    // pre != 0: the tensor was rounded and split beforehand (round_split_kernel); X then points to
+    // the piece patterns, two per 32-bit word, in (P+1)/2 planes of `plane` elements each (a patch
+    // element is reused R*S times, so rounding it once pays)
+    int pre, plane;
+};
+
+// One operand of a prepare launch: X is fp32, `rows` x K after op(); for a plain matrix element
+// (r, k) sits at X[r*ld + k] (kcontig) or X[k*ld + r]; vec4: base 16-byte aligned and ld a
+// multiple of 4.  kcontig also selects the lane mapping (8 lanes along k per row, or lanes
+// along rows) for the gathered kinds.
 struct PrepOperand {
     const uint32_t *X;
     u32x4 *W;
@@ -99,7 +127,124 @@ struct PrepOperand {
     int kcontig;
     int vec4;
     unsigned nblocks;   // workgroups of this operand: slabs * row groups
+    Gather g;
 };
+
+// Offset of tap (r, s) seen from the spatial base (by, bx) = (y*mul + off) inside one h x w plane,
+// or -1 when the tap falls outside the tensor (or, for dgrad, between the strides).  All tensors
+// have fewer than 2^31 elements, so 32-bit offsets suffice.
+template <bool DIV>
+__device__ __forceinline__ int tap_offset(const Gather &g, int by, int bx, int r, int s)
+{
+    int iy = by + g.tap * r, ix = bx + g.tap * s;
+    if (DIV) {
+        if (iy < 0 || ix < 0) return -1;
+        const int qy = iy / g.den_y, qx = ix / g.den_x;
+        if (qy * g.den_y != iy || qx * g.den_x != ix) return -1;
+        iy = qy;
+        ix = qx;
+    }
+    return ((unsigned)iy < (unsigned)g.th && (unsigned)ix < (unsigned)g.tw) ? iy * g.tw + ix : -1;
+}
+
+template <bool DIV>
+__device__ __forceinline__ void gather_patches(const PrepOperand &o, int row, int k0, int K, int (&idx)[8])
+{
+    const Gather &g = o.g;
+    const int hw = g.th * g.tw;
+    if (g.kind == kSrcPatchRows) {
+        // fixed position (n, y, x); k runs over (ch, r, s)
+        const int x = row % g.gx, t = row / g.gx, y = t % g.gy, n = t / g.gy;
+        const int by = y * g.mul_y + g.off_y, bx = x * g.mul_x + g.off_x;
+        int s = k0 % g.S, t2 = k0 / g.S, r = t2 % g.R;
+        int plane = (n * g.tc + t2 / g.R) * hw;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int off = tap_offset<DIV>(g, by, bx, r, s);
+            if (k0 + j < K && off >= 0) idx[j] = plane + off;
+            if (++s == g.S) {
+                s = 0;
+                if (++r == g.R) {
+                    r = 0;
+                    plane += hw;
+                }
+            }
+        }
+    } else {
+        // fixed tap (ch, r, s); k runs over the positions (n, y, x)
+        const int s = row % g.S, t = row / g.S, r = t % g.R, ch = t / g.R;
+        int x = k0 % g.gx, t2 = k0 / g.gx, y = t2 % g.gy;
+        int plane = ((t2 / g.gy) * g.tc + ch) * hw;
+        const int step = g.tc * hw;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int off = tap_offset<DIV>(g, y * g.mul_y + g.off_y, x * g.mul_x + g.off_x, r, s);
+            if (k0 + j < K && off >= 0) idx[j] = plane + off;
+            if (++x == g.gx) {
+                x = 0;
+                if (++y == g.gy) {
+                    y = 0;
+                    plane += step;
+                }
+            }
+        }
+    }
+}
+
+// Element offsets of (row, k0 .. k0+7) of a gathered operand in its tensor; -1 = a zero (padding,
+// a tap between the strides, beyond rows / K).
+__device__ __forceinline__ void gather8(const PrepOperand &o, int row, int k0, int K, int (&idx)[8])
+{
+    const Gather &g = o.g;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) idx[j] = -1;
+    if (row >= o.rows || k0 >= K) return;
+    if (g.kind == kSrcPatchRows || g.kind == kSrcPatchK) {
+        if (g.den_y == 1 && g.den_x == 1)
+            gather_patches<false>(o, row, k0, K, idx);
+        else
+            gather_patches<true>(o, row, k0, K, idx);
+    } else if (g.kind == kSrcChannelRows) {
+        const int L = g.th * g.tw;
+        int pos = k0 % L;
+        int base = ((k0 / L) * g.tc + row) * L;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (k0 + j < K) idx[j] = base + pos;
+            if (++pos == L) {
+                pos = 0;
+                base += g.tc * L;
+            }
+        }
+    } else {   // kSrcFilterT
+        const int RS = g.R * g.S;
+        int rs = k0 % RS;
+        int base = ((k0 / RS) * g.tc + row) * RS;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (k0 + j < K) idx[j] = base + rs;
+            if (++rs == RS) {
+                rs = 0;
+                base += g.tc * RS;
+            }
+        }
+    }
+}
+
+// Rounds a tensor to the format and splits it once, elementwise, for operands that are gathered
+// many times: word plane w (at out + w*n) holds piece 2w in its low half and piece 2w+1 in its high half.
+template <int MODE, bool FTZ, int PS>
+__global__ __launch_bounds__(256) void round_split_kernel(const uint32_t *__restrict__ x, uint32_t *__restrict__ out,
+                                                          int n, QuantParams p)
+{
+    constexpr int P = pieces_of(PS);
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
+        uint32_t pc[P];
+        round_and_split<MODE, FTZ, PS>(x[i], p, pc);
+        out[i] = pc[0] | (P >= 2 ? pc[P >= 2 ? 1 : 0] << 16 : 0u);
+        if (P >= 3) out[(size_t)n + i] = pc[P >= 3 ? 2 : 0];
+    }
+}
 
 // prepare: both operands of a product in one launch (workgroups [0, a.nblocks) take op(A), the
 // rest op(B)).  k-contiguous input: a workgroup takes 32 rows x 64 k, 8 neighbouring lanes read
@@ -129,7 +274,26 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
     }
     if (k0 >= kblocks * kUnitK) return;      // k-contiguous slabs cover two k-blocks; the last may be half
     uint32_t v[8];
-    if (kcontig && o.vec4 && row < rows && k0 + 8 <= K) {
+    uint32_t pc[8][P];
+    bool rounded = false;
+    if (o.g.kind != kSrcMatrix) {
+        int idx[8];
+        gather8(o, row, k0, K, idx);
+        if (o.g.pre) {
+            // pieces were made beforehand: pure data movement
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t w0 = idx[j] >= 0 ? X[idx[j]] : 0u;
+                pc[j][0] = w0 & 0xFFFFu;
+                if (P >= 2) pc[j][P >= 2 ? 1 : 0] = w0 >> 16;
+                if (P >= 3) pc[j][P >= 3 ? 2 : 0] = idx[j] >= 0 ? X[(size_t)o.g.plane + idx[j]] : 0u;
+            }
+            rounded = true;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = idx[j] >= 0 ? X[idx[j]] : 0u;
+        }
+    } else if (kcontig && o.vec4 && row < rows && k0 + 8 <= K) {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(X + (size_t)row * ld + k0);
         const u32x4 lo = __builtin_nontemporal_load(src), hi = __builtin_nontemporal_load(src + 1);
 #pragma unroll
@@ -146,9 +310,10 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
             v[j] = ok ? X[idx] : 0u;
         }
     }
-    uint32_t pc[8][P];
+    if (!rounded) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
+        for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
+    }
     const int rb = row / kUnitRows, rr = row % kUnitRows;
     const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
 #pragma unroll
@@ -170,8 +335,8 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
 // of partial sums (summed by reduce_kernel).
 template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
-                                                      float *__restrict__ C, int M, int N, int64_t ldc, int kblocks,
-                                                      int tiles_m, int tiles_n, int kb_per_split)
+                                                      float *__restrict__ C, int M, int N, int64_t ldc, int img,
+                                                      int kblocks, int tiles_m, int tiles_n, int kb_per_split)
 {
     constexpr int P = pieces_of(PS);
     constexpr int UA = 2 * TM, UB = 2 * TN;              // 32-row units per operand in the workgroup tile
@@ -364,10 +529,15 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
             const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
             const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
             if (col < N) {
+                // plain: C[row][col] with leading dimension ldc; img > 0: column = (image, position),
+                // element (row, col) goes to C[image][row][position] (NCHW with `img` positions)
+                const bool nchw = !SPLIT && img > 0;
+                const size_t coff = nchw ? (size_t)(col / img) * M * img + col % img : (size_t)col;
+                const size_t rs = nchw ? (size_t)img : (size_t)ldc;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < M) out[(size_t)row * ldc + col] = acc[i][j][v];
+                    if (row < M) out[(size_t)row * rs + coff] = acc[i][j][v];
                 }
             }
         }
@@ -375,13 +545,17 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
 
 // C[r][c] = sum over the k parts of part[s][r][c]  (parts are dense M x N slabs)
 __global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ part, int nsplit, float *__restrict__ C,
-                                                     int M, int N, int64_t ldc)
+                                                     int M, int N, int64_t ldc, int img)
 {
     const size_t total = (size_t)M * N;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         float s = 0.0f;
         for (int q = 0; q < nsplit; ++q) s += part[(size_t)q * total + i];
-        C[(i / N) * ldc + i % N] = s;
+        const size_t row = i / N, col = i % N;
+        if (img > 0)
+            C[((col / img) * M + row) * img + col % img] = s;
+        else
+            C[row * ldc + col] = s;
     }
 }
 
@@ -447,7 +621,7 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
 }
 
 template <int PS, int TM, int TN, bool SPLIT, bool SCHED>
-static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int kblocks,
+static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
                             int nsplit, hipStream_t stream)
 {
     constexpr int KS = Pipe<TM, TN>::ks, NST = Pipe<TM, TN>::nst;
@@ -463,35 +637,53 @@ static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M,
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), lds, stream, Aw, Bw, out, M, N, ld,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), lds, stream, Aw, Bw, out, M, N, ld, img,
                        kblocks, tiles_m, tiles_n, kb_per);
     FMT_HIP_CHECK(hipGetLastError());
     return FMT_OK;
 }
 
 template <int PS, int TM, int TN>
-static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int kblocks,
+static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int img, int kblocks,
                           const Plan &plan, float *part, hipStream_t stream)
 {
     if (lds_bytes(TM, TN, pieces_of(PS), Pipe<TM, TN>::ks, Pipe<TM, TN>::nst) > 160 * 1024) return FMT_ERR_SHAPE;   // never planned
     if (plan.nsplit == 1) {
-        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream)
-                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, kblocks, 1, stream);
+        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream)
+                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream);
     }
     int rc = plan.sched
-                 ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream)
-                 : launch_product_v<PS, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, kblocks, plan.nsplit, stream);
+                 ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream)
+                 : launch_product_v<PS, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream);
     if (rc != FMT_OK) return rc;
     const size_t total = (size_t)M * N;
     const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
-    hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc);
+    hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc, img);
     FMT_HIP_CHECK(hipGetLastError());
     return FMT_OK;
 }
 
+// One operand of a product as the caller describes it: a plain matrix (kind kSrcMatrix, leading
+// dimension ld) or a gathered view of a convolution tensor.
+struct OperandSpec {
+    const float *X;
+    int64_t ld;
+    bool kcontig;
+    Gather g;
+    int64_t pre_elems;   // > 0: round and split the tensor (that many elements) once before gathering from it
+};
+
+// Where the M x N result goes: plain row-major with leading dimension ldc, or (img > 0) NCHW with
+// columns = (image, position) and `img` positions per image.
+struct OutSpec {
+    float *C;
+    int64_t ldc;
+    int img;
+};
+
 template <int MODE, bool FTZ, int PS>
-static int run(int transA, int transB, int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
-               float *C, int64_t ldc, const QuantParams &p, hipStream_t stream)
+static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
+               const QuantParams &p, hipStream_t stream)
 {
     constexpr int P = pieces_of(PS);
     int cus = 0;
@@ -504,35 +696,46 @@ static int run(int transA, int transB, int M, int N, int K, const float *A, int6
     const size_t a_vec = (size_t)units_m * kblocks * P * kUnitVec;
     const size_t b_vec = (size_t)units_n * kblocks * P * kUnitVec;
     const size_t part_bytes = plan.nsplit > 1 ? (size_t)plan.nsplit * M * N * sizeof(float) : 0;
+    const size_t pre_a = ((size_t)sa.pre_elems * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16;
+    const size_t pre_b = ((size_t)sb.pre_elems * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16;
     Scratch s;
-    rc = get_scratch(stream, 0, (a_vec + b_vec) * sizeof(u32x4) + part_bytes, &s);
+    rc = get_scratch(stream, 0, (a_vec + b_vec) * sizeof(u32x4) + part_bytes + pre_a + pre_b, &s);
     if (rc != FMT_OK) return rc;
     u32x4 *Aw = static_cast<u32x4 *>(s.gemm_ws);
     u32x4 *Bw = Aw + a_vec;
     float *part = reinterpret_cast<float *>(Bw + b_vec);
-    const uint32_t *Au = reinterpret_cast<const uint32_t *>(A), *Bu = reinterpret_cast<const uint32_t *>(B);
+    uint32_t *pre_a_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(part) + part_bytes);
+    uint32_t *pre_b_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(pre_a_buf) + pre_a);
 
-    // op(A) is M x K: k-contiguous unless transposed.  op(B) is K x N, consumed as N rows of K:
-    // k-contiguous when B is stored transposed (N x K).
     if ((int64_t)kblocks * units_m + (int64_t)kblocks * units_n >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
-    auto operand = [&](const uint32_t *X, int64_t ld, int rows, int units, bool kcontig, u32x4 *W) {
+    auto operand = [&](const OperandSpec &sp, int rows, int units, u32x4 *W, uint32_t *pre_buf) {
         PrepOperand o;
-        o.X = X;
+        o.X = reinterpret_cast<const uint32_t *>(sp.X);
+        o.g = sp.g;
+        if (sp.pre_elems > 0) {
+            const int n = (int)sp.pre_elems;
+            const int grid = (n + 1023) / 1024 < 4096 ? (n + 1023) / 1024 : 4096;
+            hipLaunchKernelGGL((round_split_kernel<MODE, FTZ, PS>), dim3(grid), dim3(256), 0, stream, o.X, pre_buf, n, p);
+            o.X = pre_buf;
+            o.g.pre = 1;
+            o.g.plane = n;
+        }
         o.W = W;
-        o.ld = ld;
+        o.ld = sp.ld;
         o.rows = rows;
-        o.kcontig = kcontig;
-        o.vec4 = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 4 == 0;
-        o.nblocks = kcontig ? (unsigned)((kblocks + 1) / 2) * units : (unsigned)kblocks * (units / 2);
+        o.kcontig = sp.kcontig;
+        o.vec4 = (reinterpret_cast<uintptr_t>(sp.X) & 15) == 0 && sp.ld % 4 == 0;
+        o.nblocks = sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units : (unsigned)kblocks * (units / 2);
         return o;
     };
-    const PrepOperand oa = operand(Au, lda, M, units_m, !transA, Aw);
-    const PrepOperand ob = operand(Bu, ldb, N, units_n, transB != 0, Bw);
+    const PrepOperand oa = operand(sa, M, units_m, Aw, pre_a_buf);
+    const PrepOperand ob = operand(sb, N, units_n, Bw, pre_b_buf);
+    FMT_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(oa.nblocks + ob.nblocks), dim3(256), 0, stream, oa, ob, K,
                        kblocks, p);
     FMT_HIP_CHECK(hipGetLastError());
 #define FMT_PRODUCT(TMV, TNV) \
-    launch_product<PS, TMV, TNV>(Aw, Bw, C, M, N, ldc, kblocks, plan, part, stream)
+    launch_product<PS, TMV, TNV>(Aw, Bw, out.C, M, N, out.ldc, out.img, kblocks, plan, part, stream)
     if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
     if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
     if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
@@ -542,15 +745,42 @@ static int run(int transA, int transB, int M, int N, int K, const float *A, int6
 }
 
 template <int MODE, bool FTZ>
-static int run_p(int pieces, int transA, int transB, int M, int N, int K, const float *A, int64_t lda, const float *B,
-                 int64_t ldb, float *C, int64_t ldc, const QuantParams &p, hipStream_t stream)
+static int run_p(int pieces, int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
+                 const QuantParams &p, hipStream_t stream)
 {
     switch (pieces) {
-        case 0: return run<MODE, FTZ, 0>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
-        case 1: return run<MODE, FTZ, 1>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
-        case 2: return run<MODE, FTZ, 2>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
-        default: return run<MODE, FTZ, 3>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream);
+        case 0: return run<MODE, FTZ, 0>(M, N, K, sa, sb, out, p, stream);
+        case 1: return run<MODE, FTZ, 1>(M, N, K, sa, sb, out, p, stream);
+        case 2: return run<MODE, FTZ, 2>(M, N, K, sa, sb, out, p, stream);
+        default: return run<MODE, FTZ, 3>(M, N, K, sa, sb, out, p, stream);
     }
+}
+
+// Product of two described operands (K > 0): picks the piece scheme and the rounding variant.
+static int run_product(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
+                       fmt_format_t f, const QuantParams &p, hipStream_t stream)
+{
+    // piece scheme: one fp16 piece for formats inside binary16, else 1-3 bf16 pieces by significand width
+    const int pieces = f.m <= 7 ? 1 : (f.e <= 5 && f.m <= 10 ? 0 : (f.m <= 15 ? 2 : 3));
+    const bool ftz = f.denorm == 0;
+#define FMT_RUN(MD)                                                                     \
+    (ftz ? run_p<MD, true>(pieces, M, N, K, sa, sb, out, p, stream)                      \
+         : run_p<MD, false>(pieces, M, N, K, sa, sb, out, p, stream))
+    if (p.mode == kModeMagic) return FMT_RUN(kModeMagic);
+    if (p.mode == kModeInteger) return FMT_RUN(kModeInteger);
+    return FMT_RUN(kModeMixed);
+#undef FMT_RUN
+}
+
+static int zero_fill(float *C, int64_t rows, int64_t cols, int64_t ldc, hipStream_t stream)
+{
+    if (rows == 0 || cols == 0) return FMT_OK;
+    const int64_t col_blocks = (cols + 255) / 256;
+    if (col_blocks * rows >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
+    hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)(col_blocks * rows)), dim3(256), 0, stream, C, (int)rows, (int)cols,
+                       ldc, (int)col_blocks);
+    FMT_HIP_CHECK(hipGetLastError());
+    return FMT_OK;
 }
 
 int launch_gemm(int transA, int transB, int64_t M64, int64_t N64, int64_t K64, const float *A, int64_t lda,
@@ -558,23 +788,72 @@ int launch_gemm(int transA, int transB, int64_t M64, int64_t N64, int64_t K64, c
                 hipStream_t stream)
 {
     const int M = (int)M64, N = (int)N64, K = (int)K64;
-    if (K == 0) {
-        const int col_blocks = (N + 255) / 256;
-        if ((int64_t)col_blocks * M >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
-        hipLaunchKernelGGL(zero_fill_kernel, dim3(col_blocks * M), dim3(256), 0, stream, C, M, N, ldc, col_blocks);
-        FMT_HIP_CHECK(hipGetLastError());
-        return FMT_OK;
+    if (K == 0) return zero_fill(C, M, N, ldc, stream);
+    // op(A) is M x K: k-contiguous unless transposed.  op(B) is K x N, consumed as N rows of K:
+    // k-contiguous when B is stored transposed (N x K).
+    const OperandSpec sa{A, lda, !transA, Gather{}, 0};
+    const OperandSpec sb{B, ldb, transB != 0, Gather{}, 0};
+    return run_product(M, N, K, sa, sb, OutSpec{C, ldc, 0}, f, p, stream);
+}
+
+// Convolutions (Sec. IV-A) as products of gathered operands; the patch matrix is never written.
+//   forward  Y[n][k][p][q]:  M = K filters (rows of the filter matrix [K][C*R*S]),
+//            N = n*P*Q output positions (patches of X), k = C*R*S, result stored NCHW
+//   dgrad    dX[n][c][h][w]: M = C (filter seen as [C][K*R*S]), N = n*H*W input positions
+//            (patches of dY through the taps that reach them), k = K*R*S, result stored NCHW
+//   wgrad    dW[k][c][r][s]: M = K (dY as [K][n*P*Q]), N = C*R*S (patches of X, transposed),
+//            k = n*P*Q, result is the plain [K][C*R*S] matrix
+int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, fmt_format_t f,
+                  const QuantParams &p, hipStream_t stream)
+{
+    const int64_t P = (g.h + 2 * g.pad_h - g.r) / g.stride_h + 1, Q = (g.w + 2 * g.pad_w - g.s) / g.stride_w + 1;
+    Gather patch{};
+    patch.R = g.r;
+    patch.S = g.s;
+    Gather none{};
+    if (which == 0) {
+        const int64_t M = g.k, N = (int64_t)g.n * P * Q, K = (int64_t)g.c * g.r * g.s;
+        if (M == 0 || N == 0) return FMT_OK;
+        patch.kind = kSrcPatchRows;
+        patch.tc = g.c; patch.th = g.h; patch.tw = g.w;
+        patch.gy = (int)P; patch.gx = (int)Q;
+        patch.mul_y = g.stride_h; patch.mul_x = g.stride_w; patch.off_y = -g.pad_h; patch.off_x = -g.pad_w;
+        patch.tap = 1; patch.den_y = 1; patch.den_x = 1;
+        if (K == 0) return zero_fill(out, (int64_t)g.n * M, P * Q, P * Q, stream);
+        const OperandSpec sa{b, K, true, none, 0};                 // filter [K][C*R*S]
+        const OperandSpec sb{a, 0, false, patch, (int64_t)g.n * g.c * g.h * g.w};   // patches of X, lanes along positions
+        return run_product((int)M, (int)N, (int)K, sa, sb, OutSpec{out, 0, (int)(P * Q)}, f, p, stream);
     }
-    // piece scheme: one fp16 piece for formats inside binary16, else 1-3 bf16 pieces by significand width
-    const int pieces = f.m <= 7 ? 1 : (f.e <= 5 && f.m <= 10 ? 0 : (f.m <= 15 ? 2 : 3));
-    const bool ftz = f.denorm == 0;
-#define FMT_RUN(MD)                                                                                       \
-    (ftz ? run_p<MD, true>(pieces, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream)              \
-         : run_p<MD, false>(pieces, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, p, stream))
-    if (p.mode == kModeMagic) return FMT_RUN(kModeMagic);
-    if (p.mode == kModeInteger) return FMT_RUN(kModeInteger);
-    return FMT_RUN(kModeMixed);
-#undef FMT_RUN
+    if (which == 1) {
+        const int64_t M = g.c, N = (int64_t)g.n * g.h * g.w, K = (int64_t)g.k * g.r * g.s;
+        if (M == 0 || N == 0) return FMT_OK;
+        patch.kind = kSrcPatchRows;
+        patch.tc = g.k; patch.th = (int)P; patch.tw = (int)Q;
+        patch.gy = g.h; patch.gx = g.w;
+        patch.mul_y = 1; patch.mul_x = 1; patch.off_y = g.pad_h; patch.off_x = g.pad_w;
+        patch.tap = -1; patch.den_y = g.stride_h; patch.den_x = g.stride_w;
+        if (K == 0) return zero_fill(out, (int64_t)g.n * M, (int64_t)g.h * g.w, (int64_t)g.h * g.w, stream);
+        Gather ft{};
+        ft.kind = kSrcFilterT;
+        ft.tc = g.c; ft.R = g.r; ft.S = g.s;
+        const OperandSpec sa{b, 0, true, ft, 0};                   // filter as [C][K*R*S]
+        const OperandSpec sb{a, 0, false, patch, (int64_t)g.n * g.k * P * Q};       // patches of dY
+        return run_product((int)M, (int)N, (int)K, sa, sb, OutSpec{out, 0, g.h * g.w}, f, p, stream);
+    }
+    const int64_t M = g.k, N = (int64_t)g.c * g.r * g.s, K = (int64_t)g.n * P * Q;
+    if (M == 0 || N == 0) return FMT_OK;
+    if (K == 0) return zero_fill(out, M, N, N, stream);
+    Gather ch{};
+    ch.kind = kSrcChannelRows;
+    ch.tc = g.k; ch.th = (int)P; ch.tw = (int)Q;
+    patch.kind = kSrcPatchK;
+    patch.tc = g.c; patch.th = g.h; patch.tw = g.w;
+    patch.gy = (int)P; patch.gx = (int)Q;
+    patch.mul_y = g.stride_h; patch.mul_x = g.stride_w; patch.off_y = -g.pad_h; patch.off_x = -g.pad_w;
+    patch.tap = 1; patch.den_y = 1; patch.den_x = 1;
+    const OperandSpec sa{a, 0, true, ch, 0};                       // dY as [K][n*P*Q]
+    const OperandSpec sb{b, 0, true, patch, (int64_t)g.n * g.c * g.h * g.w};      // patches of X, k along positions
+    return run_product((int)M, (int)N, (int)K, sa, sb, OutSpec{out, N, 0}, f, p, stream);
 }
 
 }  // namespace fmt

@@ -52,6 +52,10 @@ int launch_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
                 const float *A, int64_t lda, const float *B, int64_t ldb,
                 float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
 
+// Convolutions as products of gathered operands (fmt_gemm.hip); which: 0 forward, 1 dgrad, 2 wgrad
+int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, fmt_format_t f,
+                  const QuantParams &p, hipStream_t stream);
+
 // FMAC-8 GEMM (fmt_fmac8.hip)
 int launch_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const float *A, int64_t lda, const float *B, int64_t ldb,

@@ -102,6 +102,27 @@ def test_argument_validation_without_gpu():
     assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, None, base + 8, 2, f, None, -48, None) == -6     # Y over X
     assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, base + 132, base + 128, 2, f, None, -48, None) == -6  # Y over b
     assert lib.fmt_linear(0, 2, 2, None, 2, None, 2, None, None, 2, f, None, -48, None) == 0
+    # convolutions: geometry first, then pointers
+    G = fmt._CConv2d
+    ok = G(2, 3, 5, 5, 4, 3, 3, 1, 1, 1, 1)            # X 2x3x5x5 (150), W 4x3x3x3 (108), Y 2x4x5x5 (200)
+    big = (ctypes.c_float * 4096)()
+    b0 = ctypes.addressof(big)
+    for fn in (lib.fmt_conv2d_fwd, lib.fmt_conv2d_dgrad, lib.fmt_conv2d_wgrad):
+        assert fn(ok, b0, b0 + 4096, b0 + 8192, bad, None) == -1
+        assert fn(G(2, 3, 5, 5, 4, 0, 3, 1, 1, 1, 1), b0, b0 + 4096, b0 + 8192, f, None) == -3   # r < 1
+        assert fn(G(2, 3, 5, 5, 4, 3, 3, 1, 1, 0, 1), b0, b0 + 4096, b0 + 8192, f, None) == -3   # stride < 1
+        assert fn(G(2, 3, 5, 5, 4, 3, 3, -1, 1, 1, 1), b0, b0 + 4096, b0 + 8192, f, None) == -3  # pad < 0
+        assert fn(G(2, 3, 2, 5, 4, 7, 3, 1, 1, 1, 1), b0, b0 + 4096, b0 + 8192, f, None) == -3   # filter beyond the padded image
+        assert fn(G(-1, 3, 5, 5, 4, 3, 3, 1, 1, 1, 1), b0, b0 + 4096, b0 + 8192, f, None) == -3
+        assert fn(G(1 << 20, 1 << 10, 5, 5, 4, 3, 3, 1, 1, 1, 1), b0, b0 + 4096, b0 + 8192, f, None) == -3   # too large
+        assert fn(ok, None, b0 + 4096, b0 + 8192, f, None) == -2
+        assert fn(ok, b0, None, b0 + 8192, f, None) == -2
+        assert fn(ok, b0, b0 + 4096, None, f, None) == -2
+        assert fn(ok, b0 + 2, b0 + 4096, b0 + 8192, f, None) == -4
+        assert fn(ok, b0, b0 + 4096, b0 + 16, f, None) == -6                                     # output over the first input
+        assert fn(ok, b0, b0 + 4096, b0 + 4096 + 64, f, None) == -6                              # output over the second input
+    assert lib.fmt_conv2d_fwd(G(0, 3, 5, 5, 4, 3, 3, 1, 1, 1, 1), None, None, None, f, None) == 0
+    assert lib.fmt_conv2d_wgrad(G(2, 3, 5, 5, 0, 3, 3, 1, 1, 1, 1), None, None, None, f, None) == 0
     # loss-scale controller
     P = fmt._CDlsParams
     good = P(2.0, 0.5, 2000, 1.0, 65536.0)

@@ -1,0 +1,165 @@
+"""GPU parity of fmt_conv2d_fwd / _dgrad / _wgrad (convolutions of Sec. IV-A on rounded operands,
+patches gathered on the fly) against the CPU oracle's plain definitions: bit for bit where every
+partial sum is exact in fp32, within the GEMM tolerance (1e-5 relative Frobenius) otherwise."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL = 1e-5
+VARIANTS = [(5, 10, True), (5, 10, False), (6, 9, True), (6, 9, False), (8, 7, True), (8, 7, False)]
+GEOMS = [  # N, C, H, W, K, R, S, pad, stride
+    (2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1)),
+    (1, 2, 9, 8, 3, 3, 3, (1, 1), (2, 2)),
+    (2, 4, 6, 6, 5, 1, 1, (0, 0), (1, 1)),
+    (1, 3, 8, 9, 2, 5, 3, (2, 1), (1, 2)),
+    (3, 2, 5, 5, 3, 2, 2, (0, 0), (1, 1)),
+    (1, 1, 10, 7, 2, 3, 3, (0, 2), (3, 1)),
+    (2, 40, 14, 14, 70, 3, 3, (1, 1), (1, 1)),       # several tiles and k-blocks, ragged everywhere
+    (3, 33, 15, 13, 65, 3, 3, (1, 1), (2, 2)),
+]
+
+
+@pytest.fixture(scope="module")
+def fmt():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_2103_15940_amd as lib
+    return lib
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_err(got, ref):
+    return float(np.linalg.norm(got.astype(np.float64) - ref.astype(np.float64)) /
+                 max(np.linalg.norm(ref.astype(np.float64)), 1e-300))
+
+
+def run_all(fmt, X, W, dY, f, pad, stride):
+    Y = fmt.fmt_conv2d_fwd(dev(X), dev(W), f, pad=pad, stride=stride)
+    dX = fmt.fmt_conv2d_dgrad(dev(dY), dev(W), X.shape, f, pad=pad, stride=stride)
+    dW = fmt.fmt_conv2d_wgrad(dev(dY), dev(X), W.shape, f, pad=pad, stride=stride)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy(), dX.cpu().numpy(), dW.cpu().numpy()
+
+
+def oracle_all(X, W, dY, f, pad, stride):
+    e, m, d = f
+    return (oracle.conv2d_fwd(X, W, e, m, d, pad, stride), oracle.conv2d_dgrad(dY, W, X.shape, e, m, d, pad, stride),
+            oracle.conv2d_wgrad(dY, X, W.shape, e, m, d, pad, stride))
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("f", [(6, 9, True), (5, 10, False), (8, 7, True)])
+def test_bit_exact_integer_data(fmt, geom, f):
+    """Small integers times powers of two: every partial sum is exact in fp32 in any order."""
+    n, c, h, w, k, r, s, pad, stride = geom
+    rng = np.random.default_rng(n + 10 * c + 100 * h)
+    X = (rng.integers(-4, 5, (n, c, h, w)) * 0.5).astype(np.float32)
+    W = (rng.integers(-4, 5, (k, c, r, s)) * 0.25).astype(np.float32)
+    P, Q = oracle.conv_out_size(h, w, r, s, pad, stride)
+    dY = (rng.integers(-4, 5, (n, k, P, Q)) * 2.0 ** -6).astype(np.float32)
+    got = run_all(fmt, X, W, dY, f, pad, stride)
+    want = oracle_all(X, W, dY, f, pad, stride)
+    for name, g_, w_ in zip(("Y", "dX", "dW"), got, want):
+        assert g_.shape == w_.shape
+        assert np.array_equal(g_.view(np.uint32), w_.view(np.uint32)), "%s differs for %r" % (name, geom)
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("f", VARIANTS)
+def test_real_data_within_tolerance(fmt, geom, f):
+    n, c, h, w, k, r, s, pad, stride = geom
+    rng = np.random.default_rng(7 * n + c + f[0])
+    X = np.maximum(rng.standard_normal((n, c, h, w)), 0).astype(np.float32)         # ReLU activations
+    W = (rng.standard_normal((k, c, r, s)) * np.sqrt(2.0 / (c * r * s))).astype(np.float32)
+    P, Q = oracle.conv_out_size(h, w, r, s, pad, stride)
+    dY = workloads.log2_normal((n, k, P, Q), -12.0, 3.0, 0.0, rng)
+    got = run_all(fmt, X, W, dY, f, pad, stride)
+    want = oracle_all(X, W, dY, f, pad, stride)
+    for name, g_, w_ in zip(("Y", "dX", "dW"), got, want):
+        assert rel_err(g_, w_) <= TOL, "%s: %.3g for %r" % (name, rel_err(g_, w_), geom)
+
+
+def test_operands_are_rounded(fmt):
+    """The convolution of unrounded operands differs; the convolution of pre-rounded operands agrees."""
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((2, 8, 10, 10)).astype(np.float32)
+    W = rng.standard_normal((6, 8, 3, 3)).astype(np.float32)
+    f = (5, 10, True)
+    Y = fmt.fmt_conv2d_fwd(dev(X), dev(W), f).cpu().numpy()
+    Yq = fmt.fmt_conv2d_fwd(dev(oracle.quantize(X, *f)), dev(oracle.quantize(W, *f)), f).cpu().numpy()
+    Y32 = torch.nn.functional.conv2d(torch.from_numpy(X).double(), torch.from_numpy(W).double(), padding=1).numpy()
+    assert np.array_equal(Y, Yq)
+    assert rel_err(Y, Y32) > 1e-4
+
+
+def test_empty_and_degenerate(fmt):
+    f = (6, 9, True)
+    cuda = torch.device("cuda")
+    # no images / no filters: empty outputs
+    Y = fmt.fmt_conv2d_fwd(torch.empty((0, 3, 5, 5), device=cuda), torch.empty((4, 3, 3, 3), device=cuda), f)
+    assert tuple(Y.shape) == (0, 4, 5, 5)
+    Y = fmt.fmt_conv2d_fwd(torch.empty((2, 3, 5, 5), device=cuda), torch.empty((0, 3, 3, 3), device=cuda), f)
+    assert tuple(Y.shape) == (2, 0, 5, 5)
+    # no input channels: an empty sum, zeros
+    Y = fmt.fmt_conv2d_fwd(torch.empty((2, 0, 5, 5), device=cuda), torch.empty((4, 0, 3, 3), device=cuda), f,
+                           out=torch.full((2, 4, 5, 5), 7.0, device=cuda))
+    torch.cuda.synchronize()
+    assert float(Y.abs().sum()) == 0.0
+    # wgrad over an empty batch: zeros
+    dW = fmt.fmt_conv2d_wgrad(torch.empty((0, 4, 5, 5), device=cuda), torch.empty((0, 3, 5, 5), device=cuda), (4, 3, 3, 3), f,
+                              out=torch.full((4, 3, 3, 3), 7.0, device=cuda))
+    torch.cuda.synchronize()
+    assert float(dW.abs().sum()) == 0.0
+    # a filter as large as the padded image: one output position
+    rng = np.random.default_rng(0)
+    X = rng.integers(-3, 4, (1, 2, 3, 3)).astype(np.float32)
+    W = rng.integers(-3, 4, (2, 2, 5, 5)).astype(np.float32)
+    Y = fmt.fmt_conv2d_fwd(dev(X), dev(W), f, pad=1).cpu().numpy()
+    assert Y.shape == (1, 2, 1, 1)
+    assert np.array_equal(Y, oracle.conv2d_fwd(X, W, 6, 9, True, (1, 1), (1, 1)))
+
+
+@pytest.mark.parametrize("f", [(6, 9, True), (5, 10, True), (8, 7, False)])
+def test_config3_full_size_sampled(fmt, f):
+    """ResNet-style 3x3 convolution of config 3 (batch 64, 256 -> 256 channels, 14 x 14), forward,
+    dgrad and wgrad at full size: 4000 sampled outputs each against the oracle, error measured
+    against the norm of the sampled reference values."""
+    cfg = workloads.config3()
+    X, W2, dY2 = cfg["X"], cfg["W"], cfg["dY"]
+    n, c, h, w = X.shape
+    k = W2.shape[0]
+    W = W2.reshape(k, c, 3, 3)
+    dY = np.ascontiguousarray(dY2.reshape(n, h, w, k).transpose(0, 3, 1, 2))        # the same values as NCHW
+    Y, dX, dW = run_all(fmt, X, W, dY, f, (1, 1), (1, 1))
+    e, m, d = f
+    rng = np.random.default_rng(33)
+    for name, got, ref_fn in (("Y", Y, lambda s: oracle.conv2d_fwd(X, W, e, m, d, sample=s)),
+                              ("dX", dX, lambda s: oracle.conv2d_dgrad(dY, W, X.shape, e, m, d, sample=s)),
+                              ("dW", dW, lambda s: oracle.conv2d_wgrad(dY, X, W.shape, e, m, d, sample=s))):
+        idx = rng.integers(0, got.size, 4000)
+        ref = ref_fn(idx)
+        assert np.all(np.isfinite(got))
+        assert rel_err(got.ravel()[idx], ref) <= TOL, "%s: %.3g" % (name, rel_err(got.ravel()[idx], ref))
+
+
+def test_equals_im2col_product_config3_shape(fmt):
+    """Forward through the gathered loader against fmt_gemm on the materialised patch matrix: the
+    same operands reach the same product kernels, only the tile/accumulation order may differ."""
+    rng = np.random.default_rng(12)
+    X = np.maximum(rng.standard_normal((4, 64, 14, 14)), 0).astype(np.float32)
+    W = (rng.standard_normal((96, 64, 3, 3)) * 0.05).astype(np.float32)
+    f = (6, 9, True)
+    Y = fmt.fmt_conv2d_fwd(dev(X), dev(W), f).cpu().numpy()
+    Xcol = workloads.im2col_3x3(X)
+    Y2 = fmt.fmt_gemm(dev(Xcol), dev(W.reshape(96, -1)), f, transB=True).cpu().numpy()    # [n*h*w, k]
+    Y2 = Y2.reshape(4, 14, 14, 96).transpose(0, 3, 1, 2)
+    assert rel_err(Y, Y2) <= 2e-7
