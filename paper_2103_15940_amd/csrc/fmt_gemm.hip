@@ -98,6 +98,32 @@ enum {
     kSrcFilterT = 4     // filter [K][C][R][S] with row = c, k = (kout, r, s)
 };
 
+// Division of a 31-bit dividend by a divisor fixed at launch, as a multiply-high and a shift
+// (m = floor(2^(31+l) / d) + 1 with l = ceil(log2 d) gives floor(a / d) for every 0 <= a < 2^31).
+struct FastDiv {
+    uint32_t m;
+    int sh;      // l - 1; d == 1 is handled apart
+    int d;
+};
+
+static FastDiv make_fastdiv(int d)
+{
+    FastDiv f{0u, 0, d < 1 ? 1 : d};
+    if (f.d > 1) {
+        int l = 0;
+        while (((int64_t)1 << l) < f.d) ++l;
+        f.m = (uint32_t)((((uint64_t)1 << (31 + l)) / (uint64_t)f.d) + 1);
+        f.sh = l - 1;
+    }
+    return f;
+}
+
+__device__ __forceinline__ void divmod(const FastDiv &f, int a, int &q, int &r)
+{
+    q = f.d == 1 ? a : (int)(__umulhi((uint32_t)a, f.m) >> f.sh);
+    r = a - q * f.d;
+}
+
 // Geometry of a gathered operand.  Patches read T[n][ch][iy][ix] of an NCHW tensor with tc
 // channels of th x tw, where iy = (y*mul_y + off_y + tap*r) / den_y must divide exactly and lie in
 // [0, th) (else the element is zero), likewise ix.  Forward and wgrad: mul = stride, off = -pad,
@@ -113,6 +139,12 @@ struct Gather {
     // the piece patterns, two per 32-bit word, in (P+1)/2 planes of `plane` elements each (a patch
     // element is reused R*S times, so rounding it once pays)
     int pre, plane;
+    // fast != 0 (patch rows, den == 1, R*S <= 32, pre): the taps inside the tensor are kept as a
+    // per-lane bit mask and the element offset splits into a per-lane and a per-k (scalar) part;
+    // element plane-1 of the rounded tensor is a zero that out-of-range taps read
+    int fast;
+    // divisors of the index decompositions: rows by (r0 inner, r1 outer), k by (k0 inner, k1 outer)
+    FastDiv r0, r1, k0, k1;
 };
 
 // One operand of a prepare launch: X is fp32, `rows` x K after op(); for a plain matrix element
@@ -153,28 +185,40 @@ __device__ __forceinline__ void gather_patches(const PrepOperand &o, int row, in
     const Gather &g = o.g;
     const int hw = g.th * g.tw;
     if (g.kind == kSrcPatchRows) {
-        // fixed position (n, y, x); k runs over (ch, r, s)
-        const int x = row % g.gx, t = row / g.gx, y = t % g.gy, n = t / g.gy;
+        // fixed position (n, y, x); k runs over (ch, r, s).  Lanes run along rows in this layout, so
+        // k0 is the same in the whole wave and its decomposition and the walk over the taps are
+        // scalar work.
+        int x, t, y, n;
+        divmod(g.r0, row, t, x);
+        divmod(g.r1, t, n, y);
         const int by = y * g.mul_y + g.off_y, bx = x * g.mul_x + g.off_x;
-        int s = k0 % g.S, t2 = k0 / g.S, r = t2 % g.R;
-        int plane = (n * g.tc + t2 / g.R) * hw;
+        const int ku = __builtin_amdgcn_readfirstlane(k0);
+        int s, t2, r, ch;
+        divmod(g.k0, ku, t2, s);
+        divmod(g.k1, t2, ch, r);
+        const int nplane = n * g.tc * hw;
+        int cplane = ch * hw;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int off = tap_offset<DIV>(g, by, bx, r, s);
-            if (k0 + j < K && off >= 0) idx[j] = plane + off;
+            if (ku + j < K && off >= 0) idx[j] = nplane + cplane + off;
             if (++s == g.S) {
                 s = 0;
                 if (++r == g.R) {
                     r = 0;
-                    plane += hw;
+                    cplane += hw;
                 }
             }
         }
     } else {
         // fixed tap (ch, r, s); k runs over the positions (n, y, x)
-        const int s = row % g.S, t = row / g.S, r = t % g.R, ch = t / g.R;
-        int x = k0 % g.gx, t2 = k0 / g.gx, y = t2 % g.gy;
-        int plane = ((t2 / g.gy) * g.tc + ch) * hw;
+        int s, t, r, ch;
+        divmod(g.r0, row, t, s);
+        divmod(g.r1, t, ch, r);
+        int x, t2, y, n;
+        divmod(g.k0, k0, t2, x);
+        divmod(g.k1, t2, n, y);
+        int plane = (n * g.tc + ch) * hw;
         const int step = g.tc * hw;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -204,10 +248,13 @@ __device__ __forceinline__ void gather8(const PrepOperand &o, int row, int k0, i
             gather_patches<false>(o, row, k0, K, idx);
         else
             gather_patches<true>(o, row, k0, K, idx);
-    } else if (g.kind == kSrcChannelRows) {
-        const int L = g.th * g.tw;
-        int pos = k0 % L;
-        int base = ((k0 / L) * g.tc + row) * L;
+    } else {
+        // kSrcChannelRows: k = (image, position), L = g.k0.d positions; kSrcFilterT: k = (filter, tap),
+        // L = R*S taps; element (row, k) sits at ((k / L) * tc + row) * L + k % L in both
+        const int L = g.k0.d;
+        int pos, q;
+        divmod(g.k0, k0, q, pos);
+        int base = (q * g.tc + row) * L;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (k0 + j < K) idx[j] = base + pos;
@@ -216,33 +263,27 @@ __device__ __forceinline__ void gather8(const PrepOperand &o, int row, int k0, i
                 base += g.tc * L;
             }
         }
-    } else {   // kSrcFilterT
-        const int RS = g.R * g.S;
-        int rs = k0 % RS;
-        int base = ((k0 / RS) * g.tc + row) * RS;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (k0 + j < K) idx[j] = base + rs;
-            if (++rs == RS) {
-                rs = 0;
-                base += g.tc * RS;
-            }
-        }
     }
 }
 
 // Rounds a tensor to the format and splits it once, elementwise, for operands that are gathered
-// many times: word plane w (at out + w*n) holds piece 2w in its low half and piece 2w+1 in its high half.
+// many times: word plane w (n + 1 words, the last one zero) holds piece 2w in its low half and
+// piece 2w+1 in its high half.
 template <int MODE, bool FTZ, int PS>
 __global__ __launch_bounds__(256) void round_split_kernel(const uint32_t *__restrict__ x, uint32_t *__restrict__ out,
                                                           int n, QuantParams p)
 {
     constexpr int P = pieces_of(PS);
+    const size_t plane = (size_t)n + 1;          // one extra element per plane, always zero
     for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
         uint32_t pc[P];
         round_and_split<MODE, FTZ, PS>(x[i], p, pc);
         out[i] = pc[0] | (P >= 2 ? pc[P >= 2 ? 1 : 0] << 16 : 0u);
-        if (P >= 3) out[(size_t)n + i] = pc[P >= 3 ? 2 : 0];
+        if (P >= 3) out[plane + i] = pc[P >= 3 ? 2 : 0];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        out[n] = 0u;
+        if (P >= 3) out[plane + n] = 0u;
     }
 }
 
@@ -255,9 +296,16 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
 {
     constexpr int P = pieces_of(PS);
     const int tid = threadIdx.x;
-    const bool second = blockIdx.x >= a.nblocks;
+    // Each operand owns a run of workgroup ids padded to a multiple of 8.  Consecutive ids go to
+    // different XCDs (each with its own L2), so the ids are remapped to give every XCD a contiguous
+    // range of rows: a gathered tensor is then read into each L2 once, not eight times.
+    const unsigned a_ids = (a.nblocks + 7u) / 8u * 8u;
+    const bool second = blockIdx.x >= a_ids;
     const PrepOperand &o = second ? b : a;
-    const unsigned bid = blockIdx.x - (second ? a.nblocks : 0u);
+    const unsigned lid = blockIdx.x - (second ? a_ids : 0u);
+    const unsigned per_xcd = (o.nblocks + 7u) / 8u;
+    const unsigned bid = (lid % 8u) * per_xcd + lid / 8u;
+    if (bid >= o.nblocks) return;
     const uint32_t *__restrict__ X = o.X;
     const int64_t ld = o.ld;
     const int rows = o.rows;
@@ -274,24 +322,70 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
     }
     if (k0 >= kblocks * kUnitK) return;      // k-contiguous slabs cover two k-blocks; the last may be half
     uint32_t v[8];
-    uint32_t pc[8][P];
-    bool rounded = false;
-    if (o.g.kind != kSrcMatrix) {
+    uint32_t w01[8], w2[P >= 3 ? 8 : 1];     // pre-rounded source: pieces 0|1 packed per element, piece 2
+    bool packed = false;
+    if (o.g.fast) {
+        // Patches, lanes along positions: which taps (r, s) fall inside the tensor is a per-lane bit
+        // mask, the offset of a tap is per-lane base + a term that depends on k alone, and k is
+        // the same in the whole wave, so walking the 8 taps is scalar work.
+        const Gather &g = o.g;
+        const int hw = g.th * g.tw;
+        int x, t, y, n;
+        divmod(g.r0, row, t, x);
+        divmod(g.r1, t, n, y);
+        const int by = y * g.mul_y + g.off_y, bx = x * g.mul_x + g.off_x;
+        const int lo_r = g.tap > 0 ? max(0, -by) : max(0, by - g.th + 1), hi_r = g.tap > 0 ? min(g.R, g.th - by) : min(g.R, by + 1);
+        const int lo_s = g.tap > 0 ? max(0, -bx) : max(0, bx - g.tw + 1), hi_s = g.tap > 0 ? min(g.S, g.tw - bx) : min(g.S, bx + 1);
+        const int ns = hi_s - lo_s;
+        const uint32_t mx = ns <= 0 ? 0u : ((ns >= 32 ? 0xFFFFFFFFu : (1u << ns) - 1u) << lo_s);
+        uint32_t mask = 0u;
+        for (int r = 0; r < g.R; ++r)
+            if (r >= lo_r && r < hi_r) mask |= mx << (r * g.S);
+        if (row >= rows) mask = 0u;
+        const int lane_base = n * g.tc * hw + by * g.tw + bx;
+        const int ku = __builtin_amdgcn_readfirstlane(k0);
+        int s, t2, r, ch;
+        divmod(g.k0, ku, t2, s);
+        divmod(g.k1, t2, ch, r);
+        int rs = r * g.S + s;
+        int delta = ch * hw + g.tap * (r * g.tw + s);
+        const int zero = g.plane - 1;
+        const uint32_t *__restrict__ X2 = X + g.plane;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool ok = (ku + j < K) && ((mask >> rs) & 1u);
+            const uint32_t idx = (uint32_t)(ok ? lane_base + delta : zero);
+            w01[j] = X[idx];
+            if (P >= 3) w2[j] = X2[idx];
+            ++rs;
+            delta += g.tap;
+            if (++s == g.S) {
+                s = 0;
+                delta += g.tap * (g.tw - g.S);
+                if (++r == g.R) {
+                    r = 0;
+                    rs = 0;
+                    delta += hw - g.tap * g.R * g.tw;
+                }
+            }
+        }
+        packed = true;
+    } else if (o.g.kind != kSrcMatrix) {
         int idx[8];
         gather8(o, row, k0, K, idx);
         if (o.g.pre) {
-            // pieces were made beforehand: pure data movement
+            // pieces were made beforehand: pure data movement (element plane-1 is a zero)
+            const uint32_t *__restrict__ X2 = X + o.g.plane;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t w0 = idx[j] >= 0 ? X[idx[j]] : 0u;
-                pc[j][0] = w0 & 0xFFFFu;
-                if (P >= 2) pc[j][P >= 2 ? 1 : 0] = w0 >> 16;
-                if (P >= 3) pc[j][P >= 3 ? 2 : 0] = idx[j] >= 0 ? X[(size_t)o.g.plane + idx[j]] : 0u;
+                const uint32_t at = (uint32_t)(idx[j] >= 0 ? idx[j] : o.g.plane - 1);
+                w01[j] = X[at];
+                if (P >= 3) w2[j] = X2[at];
             }
-            rounded = true;
+            packed = true;
         } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = idx[j] >= 0 ? X[idx[j]] : 0u;
+            for (int j = 0; j < 8; ++j) v[j] = idx[j] >= 0 ? X[(uint32_t)idx[j]] : 0u;
         }
     } else if (kcontig && o.vec4 && row < rows && k0 + 8 <= K) {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(X + (size_t)row * ld + k0);
@@ -310,12 +404,26 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
             v[j] = ok ? X[idx] : 0u;
         }
     }
-    if (!rounded) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
-    }
     const int rb = row / kUnitRows, rr = row % kUnitRows;
     const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
+    if (packed) {
+        // two elements' 16-bit halves into one word with a byte permute
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            u32x4 w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (q == 0) w[i] = __builtin_amdgcn_perm(w01[2 * i + 1], w01[2 * i], 0x05040100u);
+                if (q == 1) w[i] = __builtin_amdgcn_perm(w01[2 * i + 1], w01[2 * i], 0x07060302u);
+                if (q == 2) w[i] = __builtin_amdgcn_perm(w2[P >= 3 ? 2 * i + 1 : 0], w2[P >= 3 ? 2 * i : 0], 0x05040100u);
+            }
+            o.W[unit_vec_index(rb, kb, kblocks, P, q, c, rr)] = w;
+        }
+        return;
+    }
+    uint32_t pc[8][P];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
 #pragma unroll
     for (int q = 0; q < P; ++q) {
         u32x4 w;
@@ -696,8 +804,8 @@ static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb
     const size_t a_vec = (size_t)units_m * kblocks * P * kUnitVec;
     const size_t b_vec = (size_t)units_n * kblocks * P * kUnitVec;
     const size_t part_bytes = plan.nsplit > 1 ? (size_t)plan.nsplit * M * N * sizeof(float) : 0;
-    const size_t pre_a = ((size_t)sa.pre_elems * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16;
-    const size_t pre_b = ((size_t)sb.pre_elems * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16;
+    const size_t pre_a = sa.pre_elems ? ((size_t)(sa.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
+    const size_t pre_b = sb.pre_elems ? ((size_t)(sb.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
     Scratch s;
     rc = get_scratch(stream, 0, (a_vec + b_vec) * sizeof(u32x4) + part_bytes + pre_a + pre_b, &s);
     if (rc != FMT_OK) return rc;
@@ -718,7 +826,8 @@ static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb
             hipLaunchKernelGGL((round_split_kernel<MODE, FTZ, PS>), dim3(grid), dim3(256), 0, stream, o.X, pre_buf, n, p);
             o.X = pre_buf;
             o.g.pre = 1;
-            o.g.plane = n;
+            o.g.plane = n + 1;
+            o.g.fast = o.g.kind == kSrcPatchRows && !sp.kcontig && o.g.den_y == 1 && o.g.den_x == 1 && o.g.R * o.g.S <= 32;
         }
         o.W = W;
         o.ld = sp.ld;
@@ -731,8 +840,8 @@ static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb
     const PrepOperand oa = operand(sa, M, units_m, Aw, pre_a_buf);
     const PrepOperand ob = operand(sb, N, units_n, Bw, pre_b_buf);
     FMT_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(oa.nblocks + ob.nblocks), dim3(256), 0, stream, oa, ob, K,
-                       kblocks, p);
+    const unsigned prep_grid = (oa.nblocks + 7u) / 8u * 8u + (ob.nblocks + 7u) / 8u * 8u;
+    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p);
     FMT_HIP_CHECK(hipGetLastError());
 #define FMT_PRODUCT(TMV, TNV) \
     launch_product<PS, TMV, TNV>(Aw, Bw, out.C, M, N, out.ldc, out.img, kblocks, plan, part, stream)
@@ -819,6 +928,8 @@ int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float 
         patch.gy = (int)P; patch.gx = (int)Q;
         patch.mul_y = g.stride_h; patch.mul_x = g.stride_w; patch.off_y = -g.pad_h; patch.off_x = -g.pad_w;
         patch.tap = 1; patch.den_y = 1; patch.den_x = 1;
+        patch.r0 = make_fastdiv(patch.gx); patch.r1 = make_fastdiv(patch.gy);
+        patch.k0 = make_fastdiv(g.s); patch.k1 = make_fastdiv(g.r);
         if (K == 0) return zero_fill(out, (int64_t)g.n * M, P * Q, P * Q, stream);
         const OperandSpec sa{b, K, true, none, 0};                 // filter [K][C*R*S]
         const OperandSpec sb{a, 0, false, patch, (int64_t)g.n * g.c * g.h * g.w};   // patches of X, lanes along positions
@@ -832,10 +943,13 @@ int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float 
         patch.gy = g.h; patch.gx = g.w;
         patch.mul_y = 1; patch.mul_x = 1; patch.off_y = g.pad_h; patch.off_x = g.pad_w;
         patch.tap = -1; patch.den_y = g.stride_h; patch.den_x = g.stride_w;
+        patch.r0 = make_fastdiv(patch.gx); patch.r1 = make_fastdiv(patch.gy);
+        patch.k0 = make_fastdiv(g.s); patch.k1 = make_fastdiv(g.r);
         if (K == 0) return zero_fill(out, (int64_t)g.n * M, (int64_t)g.h * g.w, (int64_t)g.h * g.w, stream);
         Gather ft{};
         ft.kind = kSrcFilterT;
         ft.tc = g.c; ft.R = g.r; ft.S = g.s;
+        ft.k0 = make_fastdiv(g.r * g.s);
         const OperandSpec sa{b, 0, true, ft, 0};                   // filter as [C][K*R*S]
         const OperandSpec sb{a, 0, false, patch, (int64_t)g.n * g.k * P * Q};       // patches of dY
         return run_product((int)M, (int)N, (int)K, sa, sb, OutSpec{out, 0, g.h * g.w}, f, p, stream);
@@ -846,11 +960,14 @@ int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float 
     Gather ch{};
     ch.kind = kSrcChannelRows;
     ch.tc = g.k; ch.th = (int)P; ch.tw = (int)Q;
+    ch.k0 = make_fastdiv((int)(P * Q));
     patch.kind = kSrcPatchK;
     patch.tc = g.c; patch.th = g.h; patch.tw = g.w;
     patch.gy = (int)P; patch.gx = (int)Q;
     patch.mul_y = g.stride_h; patch.mul_x = g.stride_w; patch.off_y = -g.pad_h; patch.off_x = -g.pad_w;
     patch.tap = 1; patch.den_y = 1; patch.den_x = 1;
+    patch.r0 = make_fastdiv(g.s); patch.r1 = make_fastdiv(g.r);
+    patch.k0 = make_fastdiv(patch.gx); patch.k1 = make_fastdiv(patch.gy);
     const OperandSpec sa{a, 0, true, ch, 0};                       // dY as [K][n*P*Q]
     const OperandSpec sb{b, 0, true, patch, (int64_t)g.n * g.c * g.h * g.w};      // patches of X, k along positions
     return run_product((int)M, (int)N, (int)K, sa, sb, OutSpec{out, N, 0}, f, p, stream);
