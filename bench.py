@@ -236,6 +236,56 @@ def main() -> int:
         per_format[name] = round(3 * 2.0 * M * N * K / (a.elapsed_time(b) / max(args.steps // 2, 1) * 1e-3) / 1e12, 1)
     result["gemm_config3"]["useful_tflops_by_format"] = per_format
 
+    # the layers built on top of the three base calls (outside the step; informational)
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    reps = max(args.steps // 2, 1)
+    # configuration 3 through the convolution entry points (patches gathered by the operand loader)
+    X4d = torch.from_numpy(cfg3["X"]).to(dev)
+    nb, cin, hh, ww = X4d.shape
+    W4d = w.reshape(N, cin, 3, 3).contiguous()
+    dY4d = dy.reshape(nb, hh, ww, N).permute(0, 3, 1, 2).contiguous()           # the same values as NCHW
+    Yc, dXc, dWc = torch.empty_like(dY4d), torch.empty_like(X4d), torch.empty_like(W4d)
+
+    def conv_all():
+        fmt.fmt_conv2d_fwd(X4d, W4d, f169, out=Yc)
+        fmt.fmt_conv2d_dgrad(dY4d, W4d, X4d.shape, f169, out=dXc)
+        fmt.fmt_conv2d_wgrad(dY4d, X4d, W4d.shape, f169, out=dWc)
+    conv_ms = timed(conv_all, reps)
+    result["conv_config3"] = {"workload": "config 3 via fmt_conv2d_fwd/_dgrad/_wgrad, 1/6/9/d, no patch matrix in memory",
+                              "ms": round(conv_ms, 4), "value": round(3 * 2.0 * M * N * K / (conv_ms * 1e-3) / 1e12, 2),
+                              "unit": "TFLOP/s (useful)"}
+    # quantized Linear forward of the four encoder layers: product, bias, both output roundings, statistics of t
+    biases = [torch.zeros(L["W"].shape[0], dtype=torch.float32, device=dev) for L in layers]
+
+    def linear_all():
+        for L, b in zip(layers, biases):
+            fmt.fmt_linear(L["X"], L["W"], b, f169, out=L["Y"], hist=L["h"][0])
+    lin_ms = timed(linear_all, reps)
+    result["linear_config4"] = {"workload": "fmt_linear forward of the 4 encoder layers (bias, output roundings, "
+                                            "statistics of the output), 1/6/9/d",
+                                "ms": round(lin_ms, 4), "value": round(cfg4_flops / 3 / (lin_ms * 1e-3) / 1e12, 2),
+                                "unit": "TFLOP/s (useful)"}
+    # FMAC-8 accumulation (Algorithm 1): a sequential chain of roundings per output, vector ALUs only
+    A8 = torch.randn((2048, 1024), device=dev)
+    B8 = torch.randn((1024, 2048), device=dev) * 0.05
+    C8 = torch.empty((2048, 2048), device=dev)
+    f8_ms = timed(lambda: fmt.fmt_gemm_fmac8(A8, B8, f169, out=C8), reps)
+    result["fmac8"] = {"workload": "fmt_gemm_fmac8 2048x2048x1024, 1/6/9/d", "ms": round(f8_ms, 4),
+                       "value": round(2048.0 * 2048 * 1024 / (f8_ms * 1e-3) / 1e12, 3), "unit": "T fused-MAC/s"}
+    # loss-scale controller on the nine statistics records of configuration 4's gradient tensors
+    recs = torch.stack([L["h"][2] for L in layers])
+    st = fmt.fmt_dls_init(1024.0)
+    result["dls_step_us"] = round(timed(lambda: fmt.fmt_dls_step(recs, st), 20) * 1e3, 2)
+
     if not args.no_cpu_baseline:
         import oracle
         sample = min(n, 1 << 26)

@@ -98,11 +98,12 @@ int launch_v(float *Y, int64_t ldy, int M, int N, const float *bias, const Quant
     int rc = device_cu_count(&cus);
     if (rc != FMT_OK) return rc;
     const int strips = (N + kLBlock * 4 - 1) / (kLBlock * 4);
-    // about 16 workgroups per compute unit; with statistics at least 32 rows each so that clearing
-    // and folding the LDS table stays a small part of a workgroup's work
+    // about 16 workgroups per compute unit (fewer leave the memory system idle: a lane has only four
+    // loads in flight); with statistics at least 8 rows each so that clearing and folding the LDS
+    // table stays a small part of a workgroup's work
     const int64_t want = (int64_t)cus * 16;
     int64_t row_groups = (want + strips - 1) / strips;
-    const int min_rows = HIST ? 32 : kLRows;
+    const int min_rows = HIST ? 8 : kLRows;
     int64_t rows_per_wg = (M + row_groups - 1) / row_groups;
     if (rows_per_wg < min_rows) rows_per_wg = min_rows;
     rows_per_wg = (rows_per_wg + kLRows - 1) / kLRows * kLRows;
