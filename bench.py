@@ -52,6 +52,9 @@ def main() -> int:
                     help="also run three plain device-to-device copies of the stream tensor before the warm-up: "
                          "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
+    ap.add_argument("--gemm", default=None, metavar="M,N,K[,transA,transB[,e,m,d]]",
+                    help="profiling aid: run only fmt_gemm on one N(0,1) problem of this shape (default NN, 1/6/9/d), "
+                         "--steps times after --warmup untimed calls, print its time and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); "
@@ -69,6 +72,28 @@ def main() -> int:
         return 2
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.gemm:
+        v = [int(t) for t in args.gemm.split(",")]
+        v += [0, 0][len(v) - 3:] if len(v) < 5 else []
+        v += [6, 9, 1] if len(v) < 8 else []
+        Mg, Ng, Kg, tA, tB, e_, m_, d_ = v[:8]
+        torch.manual_seed(0)
+        A = torch.randn((Kg, Mg) if tA else (Mg, Kg), device=dev)
+        B = torch.randn((Ng, Kg) if tB else (Kg, Ng), device=dev)
+        C = torch.empty((Mg, Ng), device=dev)
+        for _ in range(args.warmup):
+            fmt.fmt_gemm(A, B, (e_, m_, bool(d_)), transA=bool(tA), transB=bool(tB), out=C)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            fmt.fmt_gemm(A, B, (e_, m_, bool(d_)), transA=bool(tA), transB=bool(tB), out=C)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        print(json.dumps({"gemm": [Mg, Ng, Kg, tA, tB], "format": [e_, m_, d_], "ms": round(ms, 4),
+                          "useful_tflops": round(2.0 * Mg * Ng * Kg / (ms * 1e-3) / 1e12, 2)}))
+        return 0
 
     # ------------------------------------------------------------------ inputs (resident before timing)
     t0 = time.time()
