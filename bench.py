@@ -11,7 +11,9 @@ One "step" is one pass of the whole hot path over one batch of synthetic, paper-
                                      1/6/9/d: for each of the four linear layers (QKV, attention
                                      output, FFN1, FFN2) fused quantize + histogram of X, W and
                                      dY, then forward (NT), dgrad (NN) and wgrad (TN): 12 products,
-                                     309 GFLOP
+                                     309 GFLOP, issued round-robin on two side streams (they are
+                                     independent; one product's operand preparation overlaps
+                                     another's MFMA kernel)
   conv section (configuration 3)     the ResNet-style 3x3 conv as im2col GEMM in 1/6/9/d:
                                      fused quantize + histogram of X_col, W and dY, then the
                                      forward, dgrad and wgrad products (M=12544, N=256, K=2304
@@ -52,6 +54,8 @@ def main() -> int:
                     help="also run three plain device-to-device copies of the stream tensor before the warm-up: "
                          "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
+    ap.add_argument("--gemm-streams", type=int, default=2,
+                    help="side streams the 12 independent products of configuration 4 are spread over")
     ap.add_argument("--gemm", default=None, metavar="M,N,K[,transA,transB[,e,m,d]]",
                     help="profiling aid: run only fmt_gemm on one N(0,1) problem of this shape (default NN, 1/6/9/d), "
                          "--steps times after --warmup untimed calls, print its time and exit")
@@ -128,6 +132,7 @@ def main() -> int:
     gen_s = time.time() - t0
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
+    side = [torch.cuda.Stream() for _ in range(max(args.gemm_streams, 1))]
 
     def step(record=None):
         marks = []
@@ -147,10 +152,25 @@ def main() -> int:
             fmt.fmt_quantize(L["W"], f169, out=L["Wq"], hist=L["h"][1])
             fmt.fmt_quantize(L["dY"], f169, out=L["dYq"], hist=L["h"][2])
         mark()
-        for L in layers:                                                     # configuration 4, products
-            fmt.fmt_gemm(L["Xq"], L["Wq"], f169, transB=True, out=L["Y"])    # Y  = X W^T
-            fmt.fmt_gemm(L["dYq"], L["Wq"], f169, out=L["dX"])               # dX = dY W
-            fmt.fmt_gemm(L["dYq"], L["Xq"], f169, transA=True, out=L["dW"])  # dW = dY^T X
+        # configuration 4, products: the 12 products are independent of each other, so they go
+        # round-robin onto side streams (each stream has its own library scratch) and the HBM-bound
+        # operand preparation of one product overlaps the MFMA-bound kernel of another
+        fork = ev()
+        fork.record()
+        jobs = []
+        for L in layers:
+            jobs.append((L["Xq"], L["Wq"], False, True, L["Y"]))              # Y  = X W^T
+            jobs.append((L["dYq"], L["Wq"], False, False, L["dX"]))           # dX = dY W
+            jobs.append((L["dYq"], L["Xq"], True, False, L["dW"]))            # dW = dY^T X
+        for j, (A_, B_, tA_, tB_, C_) in enumerate(jobs):
+            st_ = side[j % len(side)]
+            if j < len(side):
+                st_.wait_event(fork)
+            fmt.fmt_gemm(A_, B_, f169, transA=tA_, transB=tB_, out=C_, stream=st_)
+        for st_ in side:
+            join = ev()
+            join.record(st_)
+            torch.cuda.current_stream().wait_event(join)
         mark()
         fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6])              # configuration 3
         fmt.fmt_quantize(w, f169, out=w_q, hist=hists[7])
