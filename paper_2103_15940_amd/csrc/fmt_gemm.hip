@@ -89,6 +89,58 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
     return (((size_t)rb * kblocks + kb) * P + piece) * kUnitVec + c * kUnitRows + row;
 }
 
+// A kernel launched with a gate runs only when the flag it points to is non-zero (run_if = 1) or zero
+// (run_if = 0): the choice between the single-fp16-piece scheme and its exact fallback is made on the
+// device, so both sets of kernels are launched and one of them returns at once.
+struct Gate {
+    const int *flag;     // nullptr: always run
+    int run_if;
+};
+
+__device__ __forceinline__ bool gate_closed(const Gate &g) { return g.flag != nullptr && ((*g.flag != 0) != (g.run_if != 0)); }
+
+// Single-fp16-piece scheme for formats with a 6-bit exponent and at most 11 significant bits
+// (1/6/9): such a value fits binary16's significand, only its exponent range (71 binades with the
+// denormals) does not.  Every row of an operand gets a power-of-two scale 2^S (exact) that moves a
+// window of binades into binary16's exactly representable range; the product of the scaled operands
+// runs as ONE fp16 MFMA product per multiply and the result is scaled back by 2^-(S_row + S_col).
+// Elements outside their row's window ("outliers", rare for tensors of neural networks) are left out
+// of the piece (zero) and recorded per row; their products are added afterwards, exactly, in a fixed
+// order.  A row with more than `cap` outliers raises the flag and the product falls back to the
+// two-bf16-piece scheme.
+struct Window {
+    int *S;              // scale exponent per (padded) row
+    uint32_t *cnt;       // outliers recorded per row (may exceed cap: then the flag is set)
+    uint2 *list;         // [row][cap] of (k, fp32 pattern of the rounded value)
+    int *flag;
+    int cap;
+};
+
+// fp16 pattern of r * 2^S for the fp32 pattern r of a value of the format, when that product is a
+// binary16 value (ok = true); otherwise ok = false and 0 is returned.  Infinities and NaN pass.
+__device__ __forceinline__ uint32_t window_half(uint32_t r, int S, bool &ok)
+{
+    const uint32_t a = r & 0x7FFFFFFFu, sign = (r >> 16) & 0x8000u;
+    ok = true;
+    if (a == 0u) return sign;
+    if (a >= 0x7F800000u) return sign | (a > 0x7F800000u ? 0x7E00u : 0x7C00u);
+    const uint32_t as = a + ((uint32_t)S << 23);        // exact: the exponent field stays inside (0, 255)
+    if (as >= 0x47800000u) {                            // 65536 or more
+        ok = false;
+        return 0u;
+    }
+    if (as >= 0x38800000u) {                            // binary16's normal range: at most 11 significant bits
+        ok = (as & 0x1FFFu) == 0u;
+        return ok ? sign | ((as - 0x38000000u) >> 13) : 0u;
+    }
+    const float x = __uint_as_float(as) * 16777216.0f;  // number of 2^-24 steps
+    const uint32_t n = (uint32_t)x;
+    ok = (float)n == x;
+    return ok ? sign | n : 0u;
+}
+
+constexpr int kWinTmin = -24, kWinTmax = 32;            // range of a window's top binade (S = 15 - T)
+
 // How element (row, k) of an operand is found in memory.
 enum {
     kSrcMatrix = 0,     // X[row*ld + k] (kcontig) or X[k*ld + row]
@@ -160,6 +212,7 @@ struct PrepOperand {
     int vec4;
     unsigned nblocks;   // workgroups of this operand: slabs * row groups
     Gather g;
+    Window win;         // win.S != nullptr: single scaled fp16 piece (PS == 0 only)
 };
 
 // Offset of tap (r, s) seen from the spatial base (by, bx) = (y*mul + off) inside one h x w plane,
@@ -292,9 +345,11 @@ __global__ __launch_bounds__(256) void round_split_kernel(const uint32_t *__rest
 // 256 contiguous bytes of a row; transposed input: 64 rows x 32 k, a wave reads 256 contiguous
 // bytes for each k.
 template <int MODE, bool FTZ, int PS>
-__global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p)
+__global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p,
+                                                      Gate gate)
 {
     constexpr int P = pieces_of(PS);
+    if (gate_closed(gate)) return;
     const int tid = threadIdx.x;
     // Each operand owns a run of workgroup ids padded to a multiple of 8.  Consecutive ids go to
     // different XCDs (each with its own L2), so the ids are remapped to give every XCD a contiguous
@@ -422,8 +477,41 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
         return;
     }
     uint32_t pc[8][P];
+    if (PS == 0 && o.win.S != nullptr) {
+        // scaled single piece: round, scale by the row's power of two, keep what is a binary16 value
+        const int S = o.win.S[row];
+        const uint32_t shift = (uint32_t)S << 23;
+        uint32_t rr8[8];
+        bool plain = true;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
+        for (int j = 0; j < 8; ++j) {
+            // the common case without branches: zero, or inside binary16's normal range after scaling
+            const uint32_t r = quantize_bits<MODE, FTZ>(v[j], p);
+            const uint32_t ab = r & 0x7FFFFFFFu, as = ab + shift;
+            const bool normal = as - 0x38800000u < 0x47800000u - 0x38800000u && ab < 0x7F800000u;
+            rr8[j] = r;
+            pc[j][0] = ab == 0u ? 0u : (((as - 0x38000000u) >> 13) | ((r >> 16) & 0x8000u));
+            plain = plain && (normal || ab == 0u);
+        }
+        if (__ballot(!plain) != 0ull) {                    // some lane holds a denormal, a non-finite value or an outlier
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t r = rr8[j];
+            bool ok;
+            pc[j][0] = window_half(r, S, ok);
+            if (!ok) {                                    // never for padding (zeros pass)
+                const uint32_t slot = atomicAdd(&o.win.cnt[row], 1u);
+                if (slot < (uint32_t)o.win.cap)
+                    o.win.list[(size_t)row * o.win.cap + slot] = make_uint2((uint32_t)(k0 + j), r);
+                else
+                    *o.win.flag = 1;
+            }
+        }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
+    }
 #pragma unroll
     for (int q = 0; q < P; ++q) {
         u32x4 w;
@@ -444,9 +532,11 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
 template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int img,
-                                                      int kblocks, int tiles_m, int tiles_n, int kb_per_split)
+                                                      int kblocks, int tiles_m, int tiles_n, int kb_per_split,
+                                                      const int *__restrict__ Sa, const int *__restrict__ Sb, Gate gate)
 {
     constexpr int P = pieces_of(PS);
+    if (gate_closed(gate)) return;
     constexpr int UA = 2 * TM, UB = 2 * TN;              // 32-row units per operand in the workgroup tile
     constexpr int kHalf = 64;                            // vectors of one piece of one unit per 16 k
     constexpr int SV = kHalf * KS;                       // ... per stage
@@ -642,10 +732,26 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 const bool nchw = !SPLIT && img > 0;
                 const size_t coff = nchw ? (size_t)(col / img) * M * img + col % img : (size_t)col;
                 const size_t rs = nchw ? (size_t)img : (size_t)ldc;
+                if (Sa != nullptr) {
+                    // scaled operands: undo 2^(S_row + S_col), exactly.  The scale arrays are padded to
+                    // the tile grid and 16-byte aligned; a lane's rows come in groups of four.
+                    const int sb = Sb[col];
+                    typedef int i32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < M) out[(size_t)row * rs + coff] = acc[i][j][v];
+                    for (int g = 0; g < 4; ++g) {
+                        const i32x4 s4 = *reinterpret_cast<const i32x4 *>(Sa + row0 + g * 8);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int row = row0 + g * 8 + q;
+                            if (row < M) out[(size_t)row * rs + coff] = ldexpf(acc[i][j][g * 4 + q], -(s4[q] + sb));
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int row = row0 + (v >> 2) * 8 + (v & 3);
+                        if (row < M) out[(size_t)row * rs + coff] = acc[i][j][v];
+                    }
                 }
             }
         }
@@ -653,8 +759,9 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
 
 // C[r][c] = sum over the k parts of part[s][r][c]  (parts are dense M x N slabs)
 __global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ part, int nsplit, float *__restrict__ C,
-                                                     int M, int N, int64_t ldc, int img)
+                                                     int M, int N, int64_t ldc, int img, Gate gate)
 {
+    if (gate_closed(gate)) return;
     const size_t total = (size_t)M * N;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         float s = 0.0f;
@@ -730,7 +837,7 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
 
 template <int PS, int TM, int TN, bool SPLIT, bool SCHED>
 static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
-                            int nsplit, hipStream_t stream)
+                            int nsplit, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
 {
     constexpr int KS = Pipe<TM, TN>::ks, NST = Pipe<TM, TN>::nst;
     constexpr size_t lds = lds_bytes(TM, TN, pieces_of(PS), KS, NST);
@@ -746,27 +853,27 @@ static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M,
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), lds, stream, Aw, Bw, out, M, N, ld, img,
-                       kblocks, tiles_m, tiles_n, kb_per);
+                       kblocks, tiles_m, tiles_n, kb_per, Sa, Sb, gate);
     FMT_HIP_CHECK(hipGetLastError());
     return FMT_OK;
 }
 
 template <int PS, int TM, int TN>
 static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int img, int kblocks,
-                          const Plan &plan, float *part, hipStream_t stream)
+                          const Plan &plan, float *part, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
 {
     if (lds_bytes(TM, TN, pieces_of(PS), Pipe<TM, TN>::ks, Pipe<TM, TN>::nst) > 160 * 1024) return FMT_ERR_SHAPE;   // never planned
     if (plan.nsplit == 1) {
-        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream)
-                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream);
+        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, Sa, Sb, gate)
+                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, Sa, Sb, gate);
     }
     int rc = plan.sched
-                 ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream)
-                 : launch_product_v<PS, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream);
+                 ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream, Sa, Sb, gate)
+                 : launch_product_v<PS, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream, Sa, Sb, gate);
     if (rc != FMT_OK) return rc;
     const size_t total = (size_t)M * N;
     const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
-    hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc, img);
+    hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc, img, gate);
     FMT_HIP_CHECK(hipGetLastError());
     return FMT_OK;
 }
@@ -789,34 +896,48 @@ struct OutSpec {
     int img;
 };
 
-template <int MODE, bool FTZ, int PS>
-static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
-               const QuantParams &p, hipStream_t stream)
+// Workspace layout of one product: prepared operands, split-k partial sums, pre-rounded tensors.
+struct Layout {
+    Plan plan;
+    int kblocks, units_m, units_n;
+    size_t a_vec, b_vec, part_bytes, pre_a, pre_b;
+    size_t bytes() const { return (a_vec + b_vec) * sizeof(u32x4) + part_bytes + pre_a + pre_b; }
+};
+
+static int make_layout(int M, int N, int K, int P, const OperandSpec &sa, const OperandSpec &sb, Layout *L)
 {
-    constexpr int P = pieces_of(PS);
     int cus = 0;
     int rc = device_cu_count(&cus);
     if (rc != FMT_OK) return rc;
-    const int kblocks = (K + kUnitK - 1) / kUnitK;
-    const Plan plan = make_plan(M, N, kblocks, cus, P);
-    const int units_m = (M + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
-    const int units_n = (N + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
-    const size_t a_vec = (size_t)units_m * kblocks * P * kUnitVec;
-    const size_t b_vec = (size_t)units_n * kblocks * P * kUnitVec;
-    const size_t part_bytes = plan.nsplit > 1 ? (size_t)plan.nsplit * M * N * sizeof(float) : 0;
-    const size_t pre_a = sa.pre_elems ? ((size_t)(sa.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
-    const size_t pre_b = sb.pre_elems ? ((size_t)(sb.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
-    Scratch s;
-    rc = get_scratch(stream, 0, (a_vec + b_vec) * sizeof(u32x4) + part_bytes + pre_a + pre_b, &s);
-    if (rc != FMT_OK) return rc;
-    u32x4 *Aw = static_cast<u32x4 *>(s.gemm_ws);
-    u32x4 *Bw = Aw + a_vec;
-    float *part = reinterpret_cast<float *>(Bw + b_vec);
-    uint32_t *pre_a_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(part) + part_bytes);
-    uint32_t *pre_b_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(pre_a_buf) + pre_a);
+    L->kblocks = (K + kUnitK - 1) / kUnitK;
+    L->plan = make_plan(M, N, L->kblocks, cus, P);
+    L->units_m = (M + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
+    L->units_n = (N + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
+    L->a_vec = (size_t)L->units_m * L->kblocks * P * kUnitVec;
+    L->b_vec = (size_t)L->units_n * L->kblocks * P * kUnitVec;
+    L->part_bytes = L->plan.nsplit > 1 ? ((size_t)L->plan.nsplit * M * N * sizeof(float) + 15) / 16 * 16 : 0;
+    L->pre_a = sa.pre_elems ? ((size_t)(sa.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
+    L->pre_b = sb.pre_elems ? ((size_t)(sb.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
+    if ((int64_t)L->kblocks * L->units_m + (int64_t)L->kblocks * L->units_n >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
+    return FMT_OK;
+}
 
-    if ((int64_t)kblocks * units_m + (int64_t)kblocks * units_n >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
-    auto operand = [&](const OperandSpec &sp, int rows, int units, u32x4 *W, uint32_t *pre_buf) {
+// Prepare + product (+ reduction) of one piece scheme in the workspace at `ws`.  wa / wb: per-row
+// scales and outlier records of the scaled single-piece scheme (PS == 0), or nullptr.
+template <int MODE, bool FTZ, int PS>
+static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
+                    const QuantParams &p, hipStream_t stream, const Layout &L, char *ws, const Window *wa,
+                    const Window *wb, Gate gate)
+{
+    const int kblocks = L.kblocks;
+    const Plan &plan = L.plan;
+    u32x4 *Aw = reinterpret_cast<u32x4 *>(ws);
+    u32x4 *Bw = Aw + L.a_vec;
+    float *part = reinterpret_cast<float *>(Bw + L.b_vec);
+    uint32_t *pre_a_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(part) + L.part_bytes);
+    uint32_t *pre_b_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(pre_a_buf) + L.pre_a);
+
+    auto operand = [&](const OperandSpec &sp, int rows, int units, u32x4 *W, uint32_t *pre_buf, const Window *win) {
         PrepOperand o;
         o.X = reinterpret_cast<const uint32_t *>(sp.X);
         o.g = sp.g;
@@ -835,22 +956,278 @@ static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb
         o.kcontig = sp.kcontig;
         o.vec4 = (reinterpret_cast<uintptr_t>(sp.X) & 15) == 0 && sp.ld % 4 == 0;
         o.nblocks = sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units : (unsigned)kblocks * (units / 2);
+        o.win = win ? *win : Window{nullptr, nullptr, nullptr, nullptr, 0};
         return o;
     };
-    const PrepOperand oa = operand(sa, M, units_m, Aw, pre_a_buf);
-    const PrepOperand ob = operand(sb, N, units_n, Bw, pre_b_buf);
+    const PrepOperand oa = operand(sa, M, L.units_m, Aw, pre_a_buf, wa);
+    const PrepOperand ob = operand(sb, N, L.units_n, Bw, pre_b_buf, wb);
     FMT_HIP_CHECK(hipGetLastError());
     const unsigned prep_grid = (oa.nblocks + 7u) / 8u * 8u + (ob.nblocks + 7u) / 8u * 8u;
-    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p);
+    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p, gate);
     FMT_HIP_CHECK(hipGetLastError());
+    const int *Sa = wa ? wa->S : nullptr, *Sb = wb ? wb->S : nullptr;
 #define FMT_PRODUCT(TMV, TNV) \
-    launch_product<PS, TMV, TNV>(Aw, Bw, out.C, M, N, out.ldc, out.img, kblocks, plan, part, stream)
+    launch_product<PS, TMV, TNV>(Aw, Bw, out.C, M, N, out.ldc, out.img, kblocks, plan, part, stream, Sa, Sb, gate)
     if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
     if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
     if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
     if (plan.tm == 2 && plan.tn == 2) return FMT_PRODUCT(2, 2);
     return FMT_PRODUCT(1, 1);
 #undef FMT_PRODUCT
+}
+
+template <int MODE, bool FTZ, int PS>
+static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
+               const QuantParams &p, hipStream_t stream)
+{
+    Layout L;
+    int rc = make_layout(M, N, K, pieces_of(PS), sa, sb, &L);
+    if (rc != FMT_OK) return rc;
+    Scratch s;
+    rc = get_scratch(stream, 0, L.bytes(), &s);
+    if (rc != FMT_OK) return rc;
+    return run_core<MODE, FTZ, PS>(M, N, K, sa, sb, out, p, stream, L, static_cast<char *>(s.gemm_ws), nullptr, nullptr,
+                                   Gate{nullptr, 0});
+}
+
+// ---- single scaled fp16 piece: row statistics, outlier products, host logic ----------------------
+
+struct StatOperand {
+    const uint32_t *X;
+    int64_t ld;
+    int rows;
+    int rows_pad;
+    int kcontig;
+    int *S;
+    uint32_t *cnt;
+    unsigned nblocks;
+};
+
+// Picks each row's window from the binades of (a sample of) its elements: hi = largest binade,
+// lo = smallest binade of an element that is normal in the format (an element in the format's
+// denormal range counts as Emin: its grid 2^(Emin-m) needs the same scale as a normal at Emin).
+// A window whose top binade is T holds [T - wid, T] exactly; T = min(hi + 1, lo + wid) keeps the
+// small elements when the row spans more than the window (+1: rounding may carry into the next
+// binade).  Any choice is correct (what falls outside becomes an outlier); the choice only decides
+// how many outliers there are, so a sample (every kstep-th slab of k) is enough.  Also clears the row's
+// outlier count and, once, the flag.
+__global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int K, int kstep_a, int kstep_b,
+                                                           int emin, int m, int *flag)
+{
+    __shared__ int s_hi[8][32], s_lo[8][32];
+    const int tid = threadIdx.x;
+    if (blockIdx.x == 0 && tid == 0) *flag = 0;
+    const bool second = blockIdx.x >= a.nblocks;
+    const StatOperand &o = second ? b : a;
+    const int by = blockIdx.x - (second ? a.nblocks : 0u);
+    const int kstep = second ? kstep_b : kstep_a;
+    const int wid = 39 - m;                       // binades a scaled binary16 holds with m + 1 significant bits
+    int hi = -1000, lo = 1000;
+    auto look = [&](uint32_t u) {
+        const uint32_t ab = u & 0x7FFFFFFFu;
+        const int E = (int)(ab >> 23) - 127;
+        if (ab < 0x7F800000u && E >= emin - m - 1) {
+            hi = max(hi, E);
+            lo = min(lo, max(E, emin));
+        }
+    };
+    // 32 rows per workgroup, 8 lanes per row; eight loads are issued before any is looked at
+    const int row = by * 32 + (o.kcontig ? tid / 8 : tid % 32);
+    const int kl = o.kcontig ? tid % 8 : tid / 32;
+    if (row < o.rows) {
+        for (int k0 = kl * 8; k0 < K; k0 += 64 * kstep) {
+            uint32_t u[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int k = min(k0 + j, K - 1);      // a repeated element does not change max / min
+                u[j] = o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) look(u[j]);
+        }
+    }
+    if (o.kcontig) {
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) {
+            hi = max(hi, __shfl_xor(hi, off, 64));
+            lo = min(lo, __shfl_xor(lo, off, 64));
+        }
+        if (kl != 0) return;
+    } else {
+        s_hi[kl][tid % 32] = hi;
+        s_lo[kl][tid % 32] = lo;
+        __syncthreads();
+        if (kl != 0) return;
+#pragma unroll
+        for (int q = 1; q < 8; ++q) {
+            hi = max(hi, s_hi[q][tid]);
+            lo = min(lo, s_lo[q][tid]);
+        }
+    }
+    if (row >= o.rows_pad) return;
+    int T = hi == -1000 ? 0 : min(hi + 1, lo + wid);
+    T = max(kWinTmin, min(kWinTmax, T));
+    o.S[row] = 15 - T;
+    o.cnt[row] = 0u;
+}
+
+struct FixOperand {
+    const uint32_t *X;   // the fp32 operand as the caller passed it
+    int64_t ld;
+    int kcontig;
+    Window win;
+};
+
+__device__ __forceinline__ uint32_t fix_fetch(const FixOperand &o, int row, int k)
+{
+    return o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
+}
+
+// The recorded outliers of one row, sorted by k (at most `cap`, a handful): a fixed order makes the
+// corrected sums reproducible whatever order the atomics recorded them in.
+template <int CAP>
+__device__ __forceinline__ int sorted_outliers(const Window &w, int row, uint32_t (&k)[CAP], uint32_t (&v)[CAP])
+{
+    const int n = min((int)w.cnt[row], CAP);
+    for (int t = 0; t < n; ++t) {
+        const uint2 e = w.list[(size_t)row * CAP + t];
+        int q = t;
+        while (q > 0 && k[q - 1] > e.x) {
+            k[q] = k[q - 1];
+            v[q] = v[q - 1];
+            --q;
+        }
+        k[q] = e.x;
+        v[q] = e.y;
+    }
+    return n;
+}
+
+constexpr int kWinCap = 8;                        // outliers recorded per row before the fallback takes over
+
+// Adds the products that the scaled pieces left out, each output element by exactly one wave and in
+// a fixed order (A's outliers of its row by increasing k, then B's outliers of its column by
+// increasing k), so the corrected sums are reproducible.  Workgroups [0, ceil(M/4)) take the rows of
+// op(A) that have outliers, one wave per row, all columns; the others take the columns of op(B) that
+// have outliers, one wave per column, only the rows WITHOUT outliers of their own.  A product
+// a * b with a an outlier is added by the row pass whatever b is; a product with only b an outlier
+// takes a from the operand if it lies inside its row's window (if not it is an outlier itself).
+// fp32 fused multiply-add: the product is exact either way, one rounding per accumulation as in
+// the product kernel.
+__global__ __launch_bounds__(256) void outlier_kernel(FixOperand A, FixOperand B, float *__restrict__ C, int64_t ldc, int M,
+                                                      int N, QuantParams p, int ftz, Gate gate)
+{
+    if (gate_closed(gate)) return;
+    const int row_blocks = (M + 3) / 4;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t k[kWinCap], v[kWinCap];
+    if ((int)blockIdx.x < row_blocks) {
+        const int i = blockIdx.x * 4 + wave;
+        if (i >= M || A.win.cnt[i] == 0u) return;
+        const int n = sorted_outliers<kWinCap>(A.win, i, k, v);
+        const int S = A.win.S[i];
+        for (int j = lane; j < N; j += 64) {
+            float c = C[(size_t)i * ldc + j];
+            for (int t = 0; t < n; ++t) {
+                const uint32_t bq = quantize_bits_rt(fix_fetch(B, j, (int)k[t]), p, ftz != 0);
+                c = __fmaf_rn(__uint_as_float(v[t]), __uint_as_float(bq), c);
+            }
+            if (B.win.cnt[j] != 0u) {                     // this column's outliers too (rare)
+                uint32_t kb[kWinCap], vb[kWinCap];
+                const int nb = sorted_outliers<kWinCap>(B.win, j, kb, vb);
+                for (int t = 0; t < nb; ++t) {
+                    const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)kb[t]), p, ftz != 0);
+                    bool inside;
+                    (void)window_half(aq, S, inside);
+                    if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(vb[t]), c);
+                }
+            }
+            C[(size_t)i * ldc + j] = c;
+        }
+        return;
+    }
+    const int j = ((int)blockIdx.x - row_blocks) * 4 + wave;
+    if (j >= N || B.win.cnt[j] == 0u) return;
+    const int n = sorted_outliers<kWinCap>(B.win, j, k, v);
+    for (int i = lane; i < M; i += 64) {
+        if (A.win.cnt[i] != 0u) continue;                 // done by the row pass
+        const int S = A.win.S[i];
+        float c = C[(size_t)i * ldc + j];
+        for (int t = 0; t < n; ++t) {
+            const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)k[t]), p, ftz != 0);
+            bool inside;
+            (void)window_half(aq, S, inside);
+            if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(v[t]), c);
+        }
+        C[(size_t)i * ldc + j] = c;
+    }
+}
+
+// 0: never, 1: always (when the format allows), 2: by size.  Environment override for tests and tuning.
+static int window_mode()
+{
+    if (const char *env = getenv("FMT_GEMM_WINDOW")) return env[0] == '0' ? 0 : (env[0] == '1' ? 1 : 2);
+    return 2;
+}
+
+// Product of two plain matrices in a format with e == 6 and 8 <= m <= 10: scaled single fp16 piece
+// with outlier products, and the two-bf16-piece scheme as the fallback chosen on the device.
+template <int MODE, bool FTZ>
+static int run_window(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
+                      fmt_format_t f, const QuantParams &p, hipStream_t stream)
+{
+    Layout L1, L2;
+    int rc = make_layout(M, N, K, 1, sa, sb, &L1);
+    if (rc != FMT_OK) return rc;
+    rc = make_layout(M, N, K, 2, sa, sb, &L2);
+    if (rc != FMT_OK) return rc;
+    const int mp = L1.units_m * kUnitRows, np = L1.units_n * kUnitRows;       // padded rows
+    auto align16 = [](size_t b) { return (b + 15) / 16 * 16; };
+    const size_t s_bytes = align16((size_t)(mp + np) * sizeof(int)), c_bytes = align16((size_t)(mp + np) * sizeof(uint32_t));
+    const size_t l_bytes = align16((size_t)(mp + np) * kWinCap * sizeof(uint2));
+    Scratch s;
+    rc = get_scratch(stream, 0, L1.bytes() + L2.bytes() + s_bytes + c_bytes + l_bytes + 16, &s);
+    if (rc != FMT_OK) return rc;
+    char *ws1 = static_cast<char *>(s.gemm_ws), *ws2 = ws1 + L1.bytes(), *wx = ws2 + L2.bytes();
+    int *S = reinterpret_cast<int *>(wx);
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(wx + s_bytes);
+    uint2 *list = reinterpret_cast<uint2 *>(wx + s_bytes + c_bytes);
+    int *flag = reinterpret_cast<int *>(wx + s_bytes + c_bytes + l_bytes);
+    const Window wa{S, cnt, list, flag, kWinCap}, wb{S + mp, cnt + mp, list + (size_t)mp * kWinCap, flag, kWinCap};
+
+    const int bias = (1 << (f.e - 1)) - 1, emin = 1 - bias;
+    auto stat = [&](const OperandSpec &sp, int rows, int rows_pad, const Window &w) {
+        StatOperand o;
+        o.X = reinterpret_cast<const uint32_t *>(sp.X);
+        o.ld = sp.ld;
+        o.rows = rows;
+        o.rows_pad = rows_pad;
+        o.kcontig = sp.kcontig;
+        o.S = w.S;
+        o.cnt = w.cnt;
+        o.nblocks = (unsigned)(rows_pad / 32);
+        return o;
+    };
+    const StatOperand ta = stat(sa, M, mp, wa), tb = stat(sb, N, np, wb);
+    // a sample of at most 4 slabs of 64 k per row (256 elements): the window only has to be a good guess
+    const int slabs = (K + 63) / 64;
+    const int kstep_a = (slabs + 3) / 4, kstep_b = kstep_a;
+    hipLaunchKernelGGL(window_stats_kernel, dim3(ta.nblocks + tb.nblocks), dim3(256), 0, stream, ta, tb, K, kstep_a,
+                       kstep_b, emin, f.m, flag);
+    FMT_HIP_CHECK(hipGetLastError());
+
+    // The flag is final once the scaled prepare has run; every later kernel of either scheme checks it.
+    // (Launching the fallback's kernels on a side stream so that their empty launches overlap the
+    // product was tried: their workgroups queue between the product's and slow it by half.)
+    const Gate fast{flag, 0}, slow{flag, 1};
+    rc = run_core<MODE, FTZ, 0>(M, N, K, sa, sb, out, p, stream, L1, ws1, &wa, &wb, fast);
+    if (rc != FMT_OK) return rc;
+    const FixOperand fa{reinterpret_cast<const uint32_t *>(sa.X), sa.ld, sa.kcontig, wa};
+    const FixOperand fb{reinterpret_cast<const uint32_t *>(sb.X), sb.ld, sb.kcontig, wb};
+    hipLaunchKernelGGL(outlier_kernel, dim3((M + 3) / 4 + (N + 3) / 4), dim3(256), 0, stream, fa, fb, out.C, out.ldc, M, N,
+                       p, FTZ ? 1 : 0, fast);
+    FMT_HIP_CHECK(hipGetLastError());
+    return run_core<MODE, FTZ, 2>(M, N, K, sa, sb, out, p, stream, L2, ws2, nullptr, nullptr, slow);
 }
 
 template <int MODE, bool FTZ>
@@ -872,6 +1249,13 @@ static int run_product(int M, int N, int K, const OperandSpec &sa, const Operand
     // piece scheme: one fp16 piece for formats inside binary16, else 1-3 bf16 pieces by significand width
     const int pieces = f.m <= 7 ? 1 : (f.e <= 5 && f.m <= 10 ? 0 : (f.m <= 15 ? 2 : 3));
     const bool ftz = f.denorm == 0;
+    // 1/6/9 and its neighbours: one scaled fp16 piece (a quarter of the MFMA work) when the product is
+    // large and deep enough to pay for the extra launches (statistics, outlier pass)
+    const int wmode = window_mode();
+    if (f.e == 6 && f.m >= 8 && f.m <= 10 && sa.g.kind == kSrcMatrix && sb.g.kind == kSrcMatrix && out.img == 0 &&
+        (wmode == 1 || (wmode == 2 && K >= 1024 && 2.0 * M * N * K >= 4e9)))
+        return ftz ? run_window<kModeMagic, true>(M, N, K, sa, sb, out, f, p, stream)
+                   : run_window<kModeMagic, false>(M, N, K, sa, sb, out, f, p, stream);
 #define FMT_RUN(MD)                                                                     \
     (ftz ? run_p<MD, true>(pieces, M, N, K, sa, sb, out, p, stream)                      \
          : run_p<MD, false>(pieces, M, N, K, sa, sb, out, p, stream))

@@ -39,4 +39,13 @@ __device__ __forceinline__ uint32_t quantize_bits(uint32_t u, const QuantParams 
     return (a > 0x7F800000u) ? 0x7FC00000u : r;
 }
 
+// The same rounding with the variant chosen at run time (uniform per launch), for kernels that
+// round a handful of values and are not worth six instantiations.
+__device__ __forceinline__ uint32_t quantize_bits_rt(uint32_t u, const QuantParams &p, bool ftz)
+{
+    if (p.mode == kModeMagic) return ftz ? quantize_bits<kModeMagic, true>(u, p) : quantize_bits<kModeMagic, false>(u, p);
+    if (p.mode == kModeInteger) return ftz ? quantize_bits<kModeInteger, true>(u, p) : quantize_bits<kModeInteger, false>(u, p);
+    return ftz ? quantize_bits<kModeMixed, true>(u, p) : quantize_bits<kModeMixed, false>(u, p);
+}
+
 }  // namespace fmt
