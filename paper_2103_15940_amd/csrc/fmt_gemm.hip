@@ -529,7 +529,9 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
 // into LDS (global_load_lds, 16 bytes per lane) through a ring of NST stage buffers, one barrier
 // per stage.  With SPLIT the k range is cut into parts and each part writes its own M x N slab
 // of partial sums (summed by reduce_kernel).
-template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED>
+// SCALED (single fp16 piece only): the operands carry per-row power-of-two scales Sa / Sb, undone on
+// the way out.
+template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int img,
                                                       int kblocks, int tiles_m, int tiles_n, int kb_per_split,
@@ -720,6 +722,34 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
     // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
     float *out = SPLIT ? C + (size_t)split * M * ldc : C;
     const int col_in = lane & 31, row_half = (lane >> 5) * 4;
+    if (SCALED) {
+        // Scaled operands: undo 2^(S_row + S_col), exactly.  The scale arrays are padded to the tile
+        // grid and 16-byte aligned, and a lane's rows come in groups of four: all of a lane's
+        // scales of one row of tiles are fetched together, with vector loads, ahead of its stores.
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        int sbv[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) sbv[j] = Sb[(tn * 2 + wn) * (32 * TN) + j * 32 + col_in];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const i32x4 sa4 = *reinterpret_cast<const i32x4 *>(Sa + row0 + g * 8);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int row = row0 + g * 8 + q;
+                        if (row < M && col < N)
+                            out[(size_t)row * ldc + col] = ldexpf(acc[i][j][g * 4 + q], -(sa4[q] + sbv[j]));
+                    }
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -732,26 +762,10 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 const bool nchw = !SPLIT && img > 0;
                 const size_t coff = nchw ? (size_t)(col / img) * M * img + col % img : (size_t)col;
                 const size_t rs = nchw ? (size_t)img : (size_t)ldc;
-                if (Sa != nullptr) {
-                    // scaled operands: undo 2^(S_row + S_col), exactly.  The scale arrays are padded to
-                    // the tile grid and 16-byte aligned; a lane's rows come in groups of four.
-                    const int sb = Sb[col];
-                    typedef int i32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const i32x4 s4 = *reinterpret_cast<const i32x4 *>(Sa + row0 + g * 8);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int row = row0 + g * 8 + q;
-                            if (row < M) out[(size_t)row * rs + coff] = ldexpf(acc[i][j][g * 4 + q], -(s4[q] + sb));
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = row0 + (v >> 2) * 8 + (v & 3);
-                        if (row < M) out[(size_t)row * rs + coff] = acc[i][j][v];
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + (v >> 2) * 8 + (v & 3);
+                    if (row < M) out[(size_t)row * rs + coff] = acc[i][j][v];
                 }
             }
         }
@@ -835,8 +849,8 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
     return best;
 }
 
-template <int PS, int TM, int TN, bool SPLIT, bool SCHED>
-static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
+template <int PS, int TM, int TN, bool SPLIT, bool SCHED, bool SCALED>
+static int launch_product_v2(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
                             int nsplit, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
 {
     constexpr int KS = Pipe<TM, TN>::ks, NST = Pipe<TM, TN>::nst;
@@ -845,7 +859,7 @@ static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M,
     const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
     if (per_xcd * 8 * nsplit >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
     const int kb_per = (kblocks + nsplit - 1) / nsplit;
-    auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED>;
+    auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED, SCALED>;
     static bool attr_done = false;
     if (!attr_done) {
         FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -856,6 +870,19 @@ static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M,
                        kblocks, tiles_m, tiles_n, kb_per, Sa, Sb, gate);
     FMT_HIP_CHECK(hipGetLastError());
     return FMT_OK;
+}
+
+template <int PS, int TM, int TN, bool SPLIT, bool SCHED>
+static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
+                            int nsplit, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
+{
+    if constexpr (PS == 0) {
+        if (Sa != nullptr)
+            return launch_product_v2<PS, TM, TN, SPLIT, SCHED, true>(Aw, Bw, out, M, N, ld, img, kblocks, nsplit, stream, Sa,
+                                                                    Sb, gate);
+    }
+    return launch_product_v2<PS, TM, TN, SPLIT, SCHED, false>(Aw, Bw, out, M, N, ld, img, kblocks, nsplit, stream, Sa, Sb,
+                                                             gate);
 }
 
 template <int PS, int TM, int TN>
@@ -1035,16 +1062,21 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
     const int row = by * 32 + (o.kcontig ? tid / 8 : tid % 32);
     const int kl = o.kcontig ? tid % 8 : tid / 32;
     if (row < o.rows) {
-        for (int k0 = kl * 8; k0 < K; k0 += 64 * kstep) {
-            uint32_t u[8];
+        // at most four slabs are visited (kstep = ceil(slabs / 4)); all their loads are issued first
+        uint32_t u[4][8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k0 = min(kl * 8 + i * 64 * kstep, K - 1);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int k = min(k0 + j, K - 1);      // a repeated element does not change max / min
-                u[j] = o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
+                const int k = min(k0 + j, K - 1);          // a repeated element does not change max / min
+                u[i][j] = o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
             }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) look(u[j]);
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) look(u[i][j]);
     }
     if (o.kcontig) {
 #pragma unroll
