@@ -114,6 +114,7 @@ struct Window {
     uint2 *list;         // [row][cap] of (k, fp32 pattern of the rounded value)
     int *flag;
     int cap;
+    int *dirty;          // rows that have outliers, in the order they were found; dirty[-1] is their number
 };
 
 // fp16 pattern of r * 2^S for the fp32 pattern r of a value of the format, when that product is a
@@ -485,13 +486,19 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
         bool plain = true;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            // the common case without branches: zero, or inside binary16's normal range after scaling
+            // the common cases without branches: zero, or a binary16 value (normal or denormal range)
+            // after scaling; only non-finite values and outliers take the general routine below
             const uint32_t r = quantize_bits<MODE, FTZ>(v[j], p);
             const uint32_t ab = r & 0x7FFFFFFFu, as = ab + shift;
-            const bool normal = as - 0x38800000u < 0x47800000u - 0x38800000u && ab < 0x7F800000u;
+            const bool normal = as - 0x38800000u < 0x47800000u - 0x38800000u;
+            const float steps = __uint_as_float(as) * 16777216.0f;          // multiples of 2^-24 (denormal range)
+            const uint32_t nd = (uint32_t)steps;
+            const bool den = as < 0x38800000u && (float)nd == steps;
+            const bool fine = ab == 0u || (ab < 0x7F800000u && (normal || den));
             rr8[j] = r;
-            pc[j][0] = ab == 0u ? 0u : (((as - 0x38000000u) >> 13) | ((r >> 16) & 0x8000u));
-            plain = plain && (normal || ab == 0u);
+            const uint32_t h = normal ? (as - 0x38000000u) >> 13 : nd;
+            pc[j][0] = ab == 0u ? 0u : (h | ((r >> 16) & 0x8000u));
+            plain = plain && fine;
         }
         if (__ballot(!plain) != 0ull) {                    // some lane holds a denormal, a non-finite value or an outlier
 #pragma unroll
@@ -501,6 +508,7 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
             pc[j][0] = window_half(r, S, ok);
             if (!ok) {                                    // never for padding (zeros pass)
                 const uint32_t slot = atomicAdd(&o.win.cnt[row], 1u);
+                if (slot == 0u) o.win.dirty[atomicAdd(&o.win.dirty[-1], 1)] = row;
                 if (slot < (uint32_t)o.win.cap)
                     o.win.list[(size_t)row * o.win.cap + slot] = make_uint2((uint32_t)(k0 + j), r);
                 else
@@ -728,22 +736,25 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
         // scales of one row of tiles are fetched together, with vector loads, ahead of its stores.
         typedef int i32x4 __attribute__((ext_vector_type(4)));
         int sbv[TN];
+        i32x4 sav[TM][4];                          // all loads first: one wait instead of one per group of rows
 #pragma unroll
         for (int j = 0; j < TN; ++j) sbv[j] = Sb[(tn * 2 + wn) * (32 * TN) + j * 32 + col_in];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                sav[i][g] = *reinterpret_cast<const i32x4 *>(Sa + (tm * 2 + wm) * (32 * TM) + i * 32 + row_half + g * 8);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const i32x4 sa4 = *reinterpret_cast<const i32x4 *>(Sa + row0 + g * 8);
+            for (int j = 0; j < TN; ++j) {
+                const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
+                if (col < N) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int row = row0 + g * 8 + q;
-                        if (row < M && col < N)
-                            out[(size_t)row * ldc + col] = ldexpf(acc[i][j][g * 4 + q], -(sa4[q] + sbv[j]));
+                    for (int v = 0; v < 16; ++v) {
+                        const int row = row0 + (v >> 2) * 8 + (v & 3);
+                        if (row < M) out[(size_t)row * ldc + col] = ldexpf(acc[i][j][v], -(sav[i][v >> 2][v & 3] + sbv[j]));
                     }
                 }
             }
@@ -983,7 +994,7 @@ static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpe
         o.kcontig = sp.kcontig;
         o.vec4 = (reinterpret_cast<uintptr_t>(sp.X) & 15) == 0 && sp.ld % 4 == 0;
         o.nblocks = sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units : (unsigned)kblocks * (units / 2);
-        o.win = win ? *win : Window{nullptr, nullptr, nullptr, nullptr, 0};
+        o.win = win ? *win : Window{nullptr, nullptr, nullptr, nullptr, 0, nullptr};
         return o;
     };
     const PrepOperand oa = operand(sa, M, L.units_m, Aw, pre_a_buf, wa);
@@ -1027,23 +1038,32 @@ struct StatOperand {
     int kcontig;
     int *S;
     uint32_t *cnt;
+    int *dirty;
     unsigned nblocks;
 };
 
-// Picks each row's window from the binades of (a sample of) its elements: hi = largest binade,
-// lo = smallest binade of an element that is normal in the format (an element in the format's
-// denormal range counts as Emin: its grid 2^(Emin-m) needs the same scale as a normal at Emin).
-// A window whose top binade is T holds [T - wid, T] exactly; T = min(hi + 1, lo + wid) keeps the
-// small elements when the row spans more than the window (+1: rounding may carry into the next
-// binade).  Any choice is correct (what falls outside becomes an outlier); the choice only decides
-// how many outliers there are, so a sample (every kstep-th slab of k) is enough.  Also clears the row's
-// outlier count and, once, the flag.
+// Picks each row's window from the binades of a sample of its elements (every kstep-th slab of k).
+// A window whose top binade is T holds the normal values of binades [T - wid, T] exactly, and the
+// format's denormal values (multiples of 2^(Emin-m)) exactly iff T <= 9 - m.  With hi the largest
+// binade seen (+1: rounding may carry) and lo the smallest binade of a value that is normal in the
+// format, every T in [hi + 1, lo + wid] leaves no outliers among the elements seen:
+//   - a denormal value was seen: T = 9 - m, the highest window that keeps the denormals (an exact
+//     bound, unseen elements cannot lower it further; gradient tensors live here);
+//   - otherwise up to three binades above hi + 1 (not beyond the middle of [hi + 1, lo + wid]),
+//     which leaves room on both sides for the elements the sample did not see; if the row spans
+//     more than a window, T = lo + wid (the small values stay, the large ones become outliers).
+// Any choice is correct -- what falls outside becomes an outlier -- the choice only decides how many
+// there are.  Also clears the row's outlier count and, once, the flag.
 __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int K, int kstep_a, int kstep_b,
                                                            int emin, int m, int *flag)
 {
     __shared__ int s_hi[8][32], s_lo[8][32];
     const int tid = threadIdx.x;
-    if (blockIdx.x == 0 && tid == 0) *flag = 0;
+    if (blockIdx.x == 0 && tid == 0) {
+        *flag = 0;
+        a.dirty[-1] = 0;
+        b.dirty[-1] = 0;
+    }
     const bool second = blockIdx.x >= a.nblocks;
     const StatOperand &o = second ? b : a;
     const int by = blockIdx.x - (second ? a.nblocks : 0u);
@@ -1055,7 +1075,7 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
         const int E = (int)(ab >> 23) - 127;
         if (ab < 0x7F800000u && E >= emin - m - 1) {
             hi = max(hi, E);
-            lo = min(lo, max(E, emin));
+            lo = min(lo, max(E, emin - 1));           // emin - 1: a value in the format's denormal range
         }
     };
     // 32 rows per workgroup, 8 lanes per row; eight loads are issued before any is looked at
@@ -1097,7 +1117,11 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
         }
     }
     if (row >= o.rows_pad) return;
-    int T = hi == -1000 ? 0 : min(hi + 1, lo + wid);
+    int T = 0;
+    if (hi != -1000) {
+        const int top = hi + 1, room = lo + wid;
+        T = lo < emin ? 9 - m : (top >= room ? room : top + min(3, (room - top) / 2));
+    }
     T = max(kWinTmin, min(kWinTmax, T));
     o.S[row] = 15 - T;
     o.cnt[row] = 0u;
@@ -1137,61 +1161,59 @@ __device__ __forceinline__ int sorted_outliers(const Window &w, int row, uint32_
 
 constexpr int kWinCap = 8;                        // outliers recorded per row before the fallback takes over
 
-// Adds the products that the scaled pieces left out, each output element by exactly one wave and in
-// a fixed order (A's outliers of its row by increasing k, then B's outliers of its column by
-// increasing k), so the corrected sums are reproducible.  Workgroups [0, ceil(M/4)) take the rows of
-// op(A) that have outliers, one wave per row, all columns; the others take the columns of op(B) that
-// have outliers, one wave per column, only the rows WITHOUT outliers of their own.  A product
-// a * b with a an outlier is added by the row pass whatever b is; a product with only b an outlier
-// takes a from the operand if it lies inside its row's window (if not it is an outlier itself).
-// fp32 fused multiply-add: the product is exact either way, one rounding per accumulation as in
-// the product kernel.
+// Adds the products that the scaled pieces left out, each output element by exactly one thread and
+// in a fixed order (A's outliers of its row by increasing k, then B's outliers of its column by
+// increasing k), so the corrected sums are reproducible.  Work items are (row with outliers, chunk of
+// 256 columns) and (column with outliers, chunk of 256 rows), taken from the lists the prepare kernel
+// filled; an element whose row has outliers belongs to the row item, also for its column's outliers.
+// A product a * b with a an outlier is added whatever b is; a product with only b an outlier takes a
+// from the operand if it lies inside its row's window (if not it is an outlier itself and was added
+// with the row).  fp32 fused multiply-add: the product is exact either way, one rounding per
+// accumulation as in the product kernel.
 __global__ __launch_bounds__(256) void outlier_kernel(FixOperand A, FixOperand B, float *__restrict__ C, int64_t ldc, int M,
                                                       int N, QuantParams p, int ftz, Gate gate)
 {
     if (gate_closed(gate)) return;
-    const int row_blocks = (M + 3) / 4;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nda = A.win.dirty[-1], ndb = B.win.dirty[-1];
+    const int cn = (N + 255) / 256, cm = (M + 255) / 256;
+    const long long row_items = (long long)nda * cn, total = row_items + (long long)ndb * cm;
     uint32_t k[kWinCap], v[kWinCap];
-    if ((int)blockIdx.x < row_blocks) {
-        const int i = blockIdx.x * 4 + wave;
-        if (i >= M || A.win.cnt[i] == 0u) return;
-        const int n = sorted_outliers<kWinCap>(A.win, i, k, v);
-        const int S = A.win.S[i];
-        for (int j = lane; j < N; j += 64) {
+    for (long long t = blockIdx.x; t < total; t += gridDim.x) {
+        if (t < row_items) {
+            const int i = A.win.dirty[t / cn], j = (int)(t % cn) * 256 + (int)threadIdx.x;
+            if (j >= N) continue;
+            const int n = sorted_outliers<kWinCap>(A.win, i, k, v);
             float c = C[(size_t)i * ldc + j];
-            for (int t = 0; t < n; ++t) {
-                const uint32_t bq = quantize_bits_rt(fix_fetch(B, j, (int)k[t]), p, ftz != 0);
-                c = __fmaf_rn(__uint_as_float(v[t]), __uint_as_float(bq), c);
+            for (int q = 0; q < n; ++q) {
+                const uint32_t bq = quantize_bits_rt(fix_fetch(B, j, (int)k[q]), p, ftz != 0);
+                c = __fmaf_rn(__uint_as_float(v[q]), __uint_as_float(bq), c);
             }
             if (B.win.cnt[j] != 0u) {                     // this column's outliers too (rare)
-                uint32_t kb[kWinCap], vb[kWinCap];
-                const int nb = sorted_outliers<kWinCap>(B.win, j, kb, vb);
-                for (int t = 0; t < nb; ++t) {
-                    const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)kb[t]), p, ftz != 0);
+                const int S = A.win.S[i];
+                const int nb = sorted_outliers<kWinCap>(B.win, j, k, v);
+                for (int q = 0; q < nb; ++q) {
+                    const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)k[q]), p, ftz != 0);
                     bool inside;
                     (void)window_half(aq, S, inside);
-                    if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(vb[t]), c);
+                    if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(v[q]), c);
                 }
             }
             C[(size_t)i * ldc + j] = c;
+        } else {
+            const long long u = t - row_items;
+            const int j = B.win.dirty[u / cm], i = (int)(u % cm) * 256 + (int)threadIdx.x;
+            if (i >= M || A.win.cnt[i] != 0u) continue;   // rows with outliers were done as row items
+            const int n = sorted_outliers<kWinCap>(B.win, j, k, v);
+            const int S = A.win.S[i];
+            float c = C[(size_t)i * ldc + j];
+            for (int q = 0; q < n; ++q) {
+                const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)k[q]), p, ftz != 0);
+                bool inside;
+                (void)window_half(aq, S, inside);
+                if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(v[q]), c);
+            }
+            C[(size_t)i * ldc + j] = c;
         }
-        return;
-    }
-    const int j = ((int)blockIdx.x - row_blocks) * 4 + wave;
-    if (j >= N || B.win.cnt[j] == 0u) return;
-    const int n = sorted_outliers<kWinCap>(B.win, j, k, v);
-    for (int i = lane; i < M; i += 64) {
-        if (A.win.cnt[i] != 0u) continue;                 // done by the row pass
-        const int S = A.win.S[i];
-        float c = C[(size_t)i * ldc + j];
-        for (int t = 0; t < n; ++t) {
-            const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)k[t]), p, ftz != 0);
-            bool inside;
-            (void)window_half(aq, S, inside);
-            if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(v[t]), c);
-        }
-        C[(size_t)i * ldc + j] = c;
     }
 }
 
@@ -1217,15 +1239,18 @@ static int run_window(int M, int N, int K, const OperandSpec &sa, const OperandS
     auto align16 = [](size_t b) { return (b + 15) / 16 * 16; };
     const size_t s_bytes = align16((size_t)(mp + np) * sizeof(int)), c_bytes = align16((size_t)(mp + np) * sizeof(uint32_t));
     const size_t l_bytes = align16((size_t)(mp + np) * kWinCap * sizeof(uint2));
+    const size_t d_bytes = align16((size_t)(mp + np + 2) * sizeof(int));
     Scratch s;
-    rc = get_scratch(stream, 0, L1.bytes() + L2.bytes() + s_bytes + c_bytes + l_bytes + 16, &s);
+    rc = get_scratch(stream, 0, L1.bytes() + L2.bytes() + s_bytes + c_bytes + l_bytes + d_bytes + 16, &s);
     if (rc != FMT_OK) return rc;
     char *ws1 = static_cast<char *>(s.gemm_ws), *ws2 = ws1 + L1.bytes(), *wx = ws2 + L2.bytes();
     int *S = reinterpret_cast<int *>(wx);
     uint32_t *cnt = reinterpret_cast<uint32_t *>(wx + s_bytes);
     uint2 *list = reinterpret_cast<uint2 *>(wx + s_bytes + c_bytes);
-    int *flag = reinterpret_cast<int *>(wx + s_bytes + c_bytes + l_bytes);
-    const Window wa{S, cnt, list, flag, kWinCap}, wb{S + mp, cnt + mp, list + (size_t)mp * kWinCap, flag, kWinCap};
+    int *dirty = reinterpret_cast<int *>(wx + s_bytes + c_bytes + l_bytes);      // [count, mp rows][count, np rows]
+    int *flag = reinterpret_cast<int *>(wx + s_bytes + c_bytes + l_bytes + d_bytes);
+    const Window wa{S, cnt, list, flag, kWinCap, dirty + 1};
+    const Window wb{S + mp, cnt + mp, list + (size_t)mp * kWinCap, flag, kWinCap, dirty + 1 + mp + 1};
 
     const int bias = (1 << (f.e - 1)) - 1, emin = 1 - bias;
     auto stat = [&](const OperandSpec &sp, int rows, int rows_pad, const Window &w) {
@@ -1237,6 +1262,7 @@ static int run_window(int M, int N, int K, const OperandSpec &sa, const OperandS
         o.kcontig = sp.kcontig;
         o.S = w.S;
         o.cnt = w.cnt;
+        o.dirty = w.dirty;
         o.nblocks = (unsigned)(rows_pad / 32);
         return o;
     };
@@ -1256,8 +1282,7 @@ static int run_window(int M, int N, int K, const OperandSpec &sa, const OperandS
     if (rc != FMT_OK) return rc;
     const FixOperand fa{reinterpret_cast<const uint32_t *>(sa.X), sa.ld, sa.kcontig, wa};
     const FixOperand fb{reinterpret_cast<const uint32_t *>(sb.X), sb.ld, sb.kcontig, wb};
-    hipLaunchKernelGGL(outlier_kernel, dim3((M + 3) / 4 + (N + 3) / 4), dim3(256), 0, stream, fa, fb, out.C, out.ldc, M, N,
-                       p, FTZ ? 1 : 0, fast);
+    hipLaunchKernelGGL(outlier_kernel, dim3(1024), dim3(256), 0, stream, fa, fb, out.C, out.ldc, M, N, p, FTZ ? 1 : 0, fast);
     FMT_HIP_CHECK(hipGetLastError());
     return run_core<MODE, FTZ, 2>(M, N, K, sa, sb, out, p, stream, L2, ws2, nullptr, nullptr, slow);
 }
