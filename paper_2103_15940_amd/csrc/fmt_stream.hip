@@ -43,7 +43,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBlock = FMT_STREAM_BLOCK;  // threads per workgroup
 constexpr int kCopies = 32;              // replicas of the exponent table (one per LDS bank)
 constexpr int kUnroll = FMT_STREAM_UNROLL;  // independent 128-bit loads in flight per thread
-constexpr int kGridPerCU = FMT_STREAM_GRID_PER_CU;   // workgroups launched per compute unit (at most)
+constexpr int kGridPerCU = FMT_STREAM_GRID_PER_CU;   // workgroups launched per compute unit (at most): statistics only
+constexpr int kGridFused = 64;           // ... fused quantize + statistics
+constexpr int kGridStore = 256;          // ... quantize only
 template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP>
 __device__ __forceinline__ u32x4 do_vec(u32x4 v, bool valid, const QuantParams &p, uint32_t *tbl, uint32_t lane32,
                                         Counts &w)
@@ -195,7 +197,11 @@ static int launch_variant(const float *x, float *y, size_t n, size_t head, size_
     if (rc != FMT_OK) return rc;
     const size_t per_block = (size_t)kBlock * (VEC ? 4 * kUnroll : 4);
     const size_t want = (n + per_block - 1) / per_block;
-    const size_t cap = (size_t)cus * kGridPerCU;
+    // Workgroups per compute unit, measured on 2^28 elements: a pure stream likes one 16 KiB tile per
+    // workgroup (6.4 TB/s against 5.9 with 16 per CU: the hardware balances the tail); every workgroup
+    // of a statistics pass pays for clearing and folding its LDS table, so the read-only pass keeps 16
+    // per CU (6.3 TB/s) and the fused pass settles in between (64 per CU: 6.07 against 5.77 TB/s).
+    const size_t cap = (size_t)cus * (HIST ? (STORE ? kGridFused : kGridPerCU) : kGridStore);
     int grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
     unsigned long long *partials = nullptr;
