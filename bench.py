@@ -40,7 +40,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/stream_kernel_config5_hbm_traffic.md), scaled by the same counters on a plain 1 GiB copy.
-MEASURED_TRAFFIC_BYTES = 2150070806   # profiles/stream_kernel_config5_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = 2157505500   # profiles/stream_kernel_config5_hbm_traffic.md
 
 
 def main() -> int:
