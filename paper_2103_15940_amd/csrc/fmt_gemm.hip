@@ -28,11 +28,11 @@
 #ifndef FMT_GEMM_KS
 #define FMT_GEMM_KS 2      // 16-k steps per LDS stage
 #endif
-#ifndef FMT_GEMM_NST
-#define FMT_GEMM_NST 2     // LDS stage buffers
+#ifndef FMT_GEMM_KS_MULTI
+#define FMT_GEMM_KS_MULTI 1  // ... with two or three pieces per operand (twice / three times the bytes per k)
 #endif
-#ifndef FMT_GEMM_REGSTAGE_P1
-#define FMT_GEMM_REGSTAGE_P1 1
+#ifndef FMT_GEMM_NST
+#define FMT_GEMM_NST 4     // LDS stage buffers (at most; see pipe_nst)
 #endif
 
 namespace fmt {
@@ -553,13 +553,16 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
     constexpr int VA = UA * P * SV, VB = UB * P * SV;    // 16-byte vectors per operand per stage
     constexpr int LA = (VA + 255) / 256, LB = (VB + 255) / 256;   // loads per lane per stage
     constexpr int kWaitLanded = ((NST - 2) * (LA + LB));  // stage loads that may still be in flight
-    static_assert(kWaitLanded < 64 && (KS == 1 || KS == 2) && NST >= 2, "unsupported pipeline shape");
-    // Stage copies: loads straight into LDS, or through registers.  Single-piece operands move
-    // four times the bytes per MFMA; their small tiles are bound by the L2 -> compute unit
-    // bandwidth and measure about 10 % faster with plain loads and a late LDS store.
-    constexpr bool kDma = !(FMT_GEMM_REGSTAGE_P1 && P == 1 && TM * TN <= 4);
-    static_assert(kDma || NST == 2, "register staging uses two stage buffers");
-    extern __shared__ u32x4 smem[];                      // [NST][VA + VB]
+    static_assert(kWaitLanded < 64 && (KS == 1 || KS == 2) && NST >= 2 && NST <= 4, "unsupported pipeline shape");
+    static_assert(NST == 2 || (VA % 256 == 0 && VB % 256 == 0), "the wait for a stage counts the same loads in every wave");
+    // One LDS array per stage buffer, each addressed with a compile-time index: the compiler then knows
+    // which loads-to-LDS an LDS read can depend on and leaves the younger stages in flight.
+    constexpr int STV = VA + VB;
+    __shared__ u32x4 st0[STV];
+    __shared__ u32x4 st1[STV];
+    __shared__ u32x4 st2[NST > 2 ? STV : 1];
+    __shared__ u32x4 st3[NST > 3 ? STV : 1];
+    auto stage = [&](int b) -> u32x4 * { return b == 0 ? st0 : b == 1 ? st1 : b == 2 ? st2 : st3; };
     typedef __attribute__((address_space(3))) void lds_void;
     typedef const __attribute__((address_space(1))) void glb_void;
 
@@ -614,9 +617,9 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
 
     // Loads of stage t (clamped to the last one, so that the number of loads in flight is the
     // same in every trip; a clamped load lands in a buffer nobody reads any more).
-    auto issue = [&](int t) {
+    auto issue = [&](int t, int buf) {
         const int tc = min(t, steps - 1);
-        u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
+        u32x4 *sa = stage(buf), *sb = sa + VA;
         const size_t off = KS == 2 ? (size_t)tc * P * kUnitVec : (size_t)(tc >> 1) * P * kUnitVec + (tc & 1) * kHalf;
 #pragma unroll
         for (int j = 0; j < LA; ++j)
@@ -628,102 +631,83 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 __builtin_amdgcn_global_load_lds((glb_void *)(gb[j] + off), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
     };
 
-    // Register-staged variant of the same stage copy: global -> VGPR (gload), VGPR -> LDS (lstore).
-    u32x4 ra[kDma ? 1 : LA], rb[kDma ? 1 : LB];
-    auto gload = [&](int t) {
-        const int tc = min(t, steps - 1);
-        const size_t off = KS == 2 ? (size_t)tc * P * kUnitVec : (size_t)(tc >> 1) * P * kUnitVec + (tc & 1) * kHalf;
-#pragma unroll
-        for (int j = 0; j < LA; ++j) ra[kDma ? 0 : j] = ga[j][off];
-#pragma unroll
-        for (int j = 0; j < LB; ++j) rb[kDma ? 0 : j] = gb[j][off];
-    };
-    auto lstore = [&](int t) {
-        u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
-#pragma unroll
-        for (int j = 0; j < LA; ++j)
-            if (VA % 256 == 0 || j * 256 + tid < VA) sa[j * 256 + tid] = ra[kDma ? 0 : j];
-#pragma unroll
-        for (int j = 0; j < LB; ++j)
-            if (VB % 256 == 0 || j * 256 + tid < VB) sb[j * 256 + tid] = rb[kDma ? 0 : j];
-    };
-
     if (steps > 0) {
-        if (kDma) {
 #pragma unroll
-            for (int t = 0; t < NST - 1; ++t) issue(t);
-        } else {
-            gload(0);
-            lstore(0);
-            gload(1);
-        }
+        for (int t = 0; t < NST - 1; ++t) issue(t, t);
     }
-    for (int t = 0; t < steps; ++t) {
-        if (kDma) {
+    // The trips are unrolled over the ring, so that trip t0 + b works on buffer b.  The barrier is the
+    // bare instruction behind the waits it needs (this wave's LDS reads and writes retired, its stage
+    // landed): __syncthreads() would also wait for every load-to-LDS still in flight.
+    // The loop over whole turns of the ring has a single exit (with early exits the compiler falls back
+    // to waiting for all loads at the loop head); the last steps % NST trips follow it.
+    auto trip = [&](int t, int b) __attribute__((always_inline)) {
+        {
             // stage t has landed once at most the loads of the NST-2 younger stages are in flight
             __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLanded & 0xF) | ((kWaitLanded >> 4) << 14));
-        }
-        __syncthreads();                         // ... for every wave; and stage t-1 is no longer read
-        const u32x4 *sa = smem + (t % NST) * (VA + VB), *sb = sa + VA;
-        // all operand fragments of the stage first, then the refill of stage t-1's buffer: the
-        // compiler keeps LDS reads and loads-to-LDS in program order, so only this order lets
-        // it thread the global loads between the MFMAs
-        bf16x8 fa[KS][TM][P], fb[KS][TN][P];
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int q = 0; q < P; ++q)
-                    fa[kk][i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int q = 0; q < P; ++q)
-                    fb[kk][j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
-        }
-        if (kDma) issue(t + NST - 1);            // refills the buffer of stage t-1
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // ... for every wave; stage t-1 is no longer read
+            const u32x4 *sa = stage(b), *sb = sa + VA;
+            // all operand fragments of the stage first, then the refill of stage t-1's buffer: the
+            // compiler keeps LDS reads and loads-to-LDS in program order, so only this order lets
+            // it thread the global loads between the MFMAs
+            bf16x8 fa[KS][TM][P], fb[KS][TN][P];
+    #pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+    #pragma unroll
+                    for (int q = 0; q < P; ++q)
+                        fa[kk][i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
+    #pragma unroll
                 for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int qa = 0; qa < P; ++qa)
-#pragma unroll
-                        for (int qb = 0; qb < P; ++qb)
-                            acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[kk][i][qa]),
-                                                                                         __builtin_bit_cast(f16x8, fb[kk][j][qb]),
-                                                                                         acc[i][j], 0, 0, 0)
-                                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i][qa], fb[kk][j][qb], acc[i][j], 0, 0, 0);
-        }
-        // Issue order inside one trip: a few operand reads up front, then LDS reads and the next
-        // stage's global loads threaded between MFMAs so that they issue in the MFMAs' shadow.
-        if (SCHED) {
-            constexpr int kMfma = TM * TN * P * P * KS, kReads = (TM + TN) * P * KS, kLoads = LA + LB;
-            constexpr int kFront = (TM + TN) * P / 2 > 4 ? (TM + TN) * P / 2 : 4;
-            __builtin_amdgcn_sched_group_barrier(0x100, kFront, 0);
-#pragma unroll
-            for (int r = 0; r < kReads - kFront; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    #pragma unroll
+                    for (int q = 0; q < P; ++q)
+                        fb[kk][j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
             }
-            constexpr int kLeft = kMfma - (kReads - kFront);
-            constexpr int kPer = kLeft / (kLoads + 1) > 0 ? kLeft / (kLoads + 1) : 1;
-#pragma unroll
-            for (int r = 0; r < kLoads; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            issue(t + NST - 1, (b + NST - 1) % NST);             // refills the buffer of stage t-1
+    #pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+    #pragma unroll
+                    for (int j = 0; j < TN; ++j)
+    #pragma unroll
+                        for (int qa = 0; qa < P; ++qa)
+    #pragma unroll
+                            for (int qb = 0; qb < P; ++qb)
+                                acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[kk][i][qa]),
+                                                                                             __builtin_bit_cast(f16x8, fb[kk][j][qb]),
+                                                                                             acc[i][j], 0, 0, 0)
+                                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i][qa], fb[kk][j][qb], acc[i][j], 0, 0, 0);
+            }
+            // Issue order inside one trip: a few operand reads up front, then LDS reads and the next
+            // stage's global loads threaded between MFMAs so that they issue in the MFMAs' shadow.
+            if (SCHED) {
+                constexpr int kMfma = TM * TN * P * P * KS, kReads = (TM + TN) * P * KS, kLoads = LA + LB;
+                constexpr int kFront = (TM + TN) * P / 2 > 4 ? (TM + TN) * P / 2 : 4;
+                __builtin_amdgcn_sched_group_barrier(0x100, kFront, 0);
+    #pragma unroll
+                for (int r = 0; r < kReads - kFront; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                constexpr int kLeft = kMfma - (kReads - kFront);
+                constexpr int kPer = kLeft / (kLoads + 1) > 0 ? kLeft / (kLoads + 1) : 1;
+    #pragma unroll
+                for (int r = 0; r < kLoads; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
             }
         }
-        if (!kDma) {
-            // stage t+1 (in registers since the previous trip) goes into the buffer stage t-1 was
-            // read from, then the loads of stage t+2 start
-            lstore(t + 1);
-            gload(t + 2);
-        }
+    };
+    int t0 = 0;
+    for (; t0 + NST <= steps; t0 += NST) {
+#pragma unroll
+        for (int b = 0; b < NST; ++b) trip(t0 + b, b);
     }
+#pragma unroll
+    for (int b = 0; b < NST - 1; ++b)
+        if (t0 + b < steps) trip(t0 + b, b);
     // every load-to-LDS of this wave must have landed before the workgroup's LDS is handed back
     __builtin_amdgcn_s_waitcnt(0x0F70);
 
@@ -812,13 +796,26 @@ struct Plan {
     int sched;       // 1: pin the issue order inside a trip (sched_group_barrier), 0: leave it to the compiler
 };
 
-// Pipeline shape per tile shape: k16 steps per stage and number of stage buffers.
-template <int TM, int TN> struct Pipe { static constexpr int ks = FMT_GEMM_KS, nst = FMT_GEMM_NST; };
-
 static constexpr size_t lds_bytes(int tm, int tn, int pieces, int ks, int nst)
 {
     return (size_t)nst * (2 * tm + 2 * tn) * pieces * 64 * ks * sizeof(u32x4);
 }
+
+// Pipeline shape per piece scheme and tile shape: k16 steps per stage, and as many stage buffers (at
+// most FMT_GEMM_NST, at least two) as fit the tile's share of the 160 KiB of LDS -- all of it for the
+// large tiles, half for 128 x 128 (two resident workgroups), a quarter for 64 x 64. 
+static constexpr int pipe_ks(int pieces) { return pieces == 1 ? FMT_GEMM_KS : FMT_GEMM_KS_MULTI; }
+static constexpr int pipe_nst(int tm, int tn, int pieces, int ks)
+{
+    if ((tm * pieces * ks) % 2 || (tn * pieces * ks) % 2) return 2;   // stage not a whole number of loads per wave
+    const size_t budget = (size_t)160 * 1024 / (tm * tn > 4 ? 1 : tm * tn == 4 ? 2 : 4);
+    int n = FMT_GEMM_NST;
+    while (n > 2 && lds_bytes(tm, tn, pieces, ks, n) > budget) --n;
+    return n;
+}
+template <int PS, int TM, int TN> struct Pipe {
+    static constexpr int ks = pipe_ks(pieces_of(PS)), nst = pipe_nst(TM, TN, pieces_of(PS), ks);
+};
 
 // Picks the workgroup tile and the number of k parts from a small cost model fitted to
 // measurements on MI355X: large tiles move fewer LDS and L2 bytes per MFMA, small tiles need
@@ -827,21 +824,27 @@ static constexpr size_t lds_bytes(int tm, int tn, int pieces, int ks, int nst)
 static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
 {
     // eff1 / effmax: relative MFMA rate of a compute unit with one / with max_occ resident workgroups
-    static const struct { int tm, tn, max_occ; double eff1, effmax; } shapes[] = {
+    struct Shape { int tm, tn, max_occ; double eff1, effmax; };
+    static const Shape multi[] = {
         {4, 4, 1, 1.15, 1.15}, {4, 2, 1, 1.0, 1.0}, {2, 4, 1, 1.03, 1.03}, {2, 2, 2, 0.80, 0.95}, {1, 1, 4, 0.45, 0.78}};
+    // one piece: a quarter of the MFMA work per byte, the small tiles lose less
+    static const Shape single[] = {
+        {4, 4, 1, 1.21, 1.21}, {4, 2, 1, 1.0, 1.0}, {2, 4, 1, 1.03, 1.03}, {2, 2, 2, 0.98, 1.11}, {1, 1, 4, 0.53, 0.68}};
+    const Shape(&shapes)[5] = pieces == 1 ? single : multi;
+    const double wg_cost = pieces == 1 ? 68.0 : 40.0, split_cost = pieces == 1 ? 5.76 : 2.5;
     if (const char *env = getenv("FMT_GEMM_PLAN")) {      // tuning override: "tm,tn,nsplit[,sched]"
         Plan forced{2, 2, 1, 1};
         if (sscanf(env, "%d,%d,%d,%d", &forced.tm, &forced.tn, &forced.nsplit, &forced.sched) >= 3) {
             for (const auto &sh : shapes)
                 if (sh.tm == forced.tm && sh.tn == forced.tn && forced.nsplit >= 1 && forced.nsplit <= 64 &&
-                    lds_bytes(sh.tm, sh.tn, pieces, FMT_GEMM_KS, FMT_GEMM_NST) <= 160 * 1024)
+                    lds_bytes(sh.tm, sh.tn, pieces, pipe_ks(pieces), 2) <= 160 * 1024)
                     return forced;
         }
     }
     Plan best{2, 2, 1, 0};
     double best_t = 1e300;
     for (const auto &sh : shapes) {
-        if (lds_bytes(sh.tm, sh.tn, pieces, FMT_GEMM_KS, FMT_GEMM_NST) > 160 * 1024) continue;
+        if (lds_bytes(sh.tm, sh.tn, pieces, pipe_ks(pieces), 2) > 160 * 1024) continue;
         const int bm = 64 * sh.tm, bn = 64 * sh.tn;
         const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         for (int ns = 1; ns <= 32; ns = ns < 4 ? ns + 1 : ns * 2) {
@@ -852,8 +855,8 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
             const long resident = per_cu < sh.max_occ ? per_cu : sh.max_occ;
             const double eff = sh.max_occ > 1 ? sh.eff1 + (sh.effmax - sh.eff1) * (resident - 1) / (sh.max_occ - 1) : sh.eff1;
             // MFMA time on that compute unit (arbitrary units) + start-up / epilogue cost per workgroup
-            double t = per_cu * ((double)bm * bn * kb_per / eff + 40.0 * bm * bn / 128.0);
-            if (ns > 1) t += 2.5 * (double)M * N * (ns + 1) / cus * 8.0;   // partial sums out and back
+            double t = per_cu * ((double)bm * bn * kb_per / eff + wg_cost * bm * bn / 128.0);
+            if (ns > 1) t += split_cost * (double)M * N * (ns + 1) / cus * 8.0;   // partial sums out and back
             if (t < best_t) { best_t = t; best = Plan{sh.tm, sh.tn, ns, sh.tm * sh.tn > 4}; }
         }
     }
@@ -864,23 +867,20 @@ template <int PS, int TM, int TN, bool SPLIT, bool SCHED, bool SCALED>
 static int launch_product_v2(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
                             int nsplit, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
 {
-    constexpr int KS = Pipe<TM, TN>::ks, NST = Pipe<TM, TN>::nst;
-    constexpr size_t lds = lds_bytes(TM, TN, pieces_of(PS), KS, NST);
-    const int tiles_m = (M + 64 * TM - 1) / (64 * TM), tiles_n = (N + 64 * TN - 1) / (64 * TN);
-    const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
-    if (per_xcd * 8 * nsplit >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
-    const int kb_per = (kblocks + nsplit - 1) / nsplit;
-    auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED, SCALED>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        FMT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_done = true;
+    constexpr int KS = Pipe<PS, TM, TN>::ks, NST = Pipe<PS, TM, TN>::nst;
+    if constexpr (lds_bytes(TM, TN, pieces_of(PS), KS, NST) > 160 * 1024) {
+        return FMT_ERR_SHAPE;                            // never planned (make_plan skips such tiles)
+    } else {
+        const int tiles_m = (M + 64 * TM - 1) / (64 * TM), tiles_n = (N + 64 * TN - 1) / (64 * TN);
+        const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
+        if (per_xcd * 8 * nsplit >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
+        const int kb_per = (kblocks + nsplit - 1) / nsplit;
+        auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED, SCALED>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), 0, stream, Aw, Bw, out, M, N, ld, img,
+                           kblocks, tiles_m, tiles_n, kb_per, Sa, Sb, gate);
+        FMT_HIP_CHECK(hipGetLastError());
+        return FMT_OK;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), lds, stream, Aw, Bw, out, M, N, ld, img,
-                       kblocks, tiles_m, tiles_n, kb_per, Sa, Sb, gate);
-    FMT_HIP_CHECK(hipGetLastError());
-    return FMT_OK;
 }
 
 template <int PS, int TM, int TN, bool SPLIT, bool SCHED>
@@ -900,7 +900,6 @@ template <int PS, int TM, int TN>
 static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int img, int kblocks,
                           const Plan &plan, float *part, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
 {
-    if (lds_bytes(TM, TN, pieces_of(PS), Pipe<TM, TN>::ks, Pipe<TM, TN>::nst) > 160 * 1024) return FMT_ERR_SHAPE;   // never planned
     if (plan.nsplit == 1) {
         return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, Sa, Sb, gate)
                           : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, Sa, Sb, gate);
