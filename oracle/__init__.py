@@ -87,6 +87,13 @@ def _load():
         lib.oracle_gemm_fmac8.restype = ctypes.c_int
         lib.oracle_encode.argtypes = [ctypes.c_float, ctypes.c_int, ctypes.c_int]
         lib.oracle_encode.restype = ctypes.c_uint32
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        lib.oracle_decode.argtypes = [ctypes.c_uint32, ctypes.c_int, ctypes.c_int]
+        lib.oracle_decode.restype = ctypes.c_float
+        lib.oracle_pack16.argtypes = [f32p, u16p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_pack16.restype = ctypes.c_int
+        lib.oracle_unpack16.argtypes = [u16p, f32p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int]
+        lib.oracle_unpack16.restype = ctypes.c_int
         lib.oracle_conv2d.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int32), f32p, f32p, i64p, ctypes.c_int64, f32p,
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.oracle_conv2d.restype = ctypes.c_int
@@ -246,6 +253,28 @@ def encode(v, e: int, m: int) -> np.ndarray:
     lib = _load()
     va = _f32(v).ravel()
     return np.array([lib.oracle_encode(float(t), e, m) for t in va], dtype=np.uint32).reshape(np.shape(v))
+
+
+def pack16(x, e: int, m: int, d: bool) -> np.ndarray:
+    """Codes (uint16, 1+e+m <= 16 bits used) of roundfp(x, e, m, d): Sec. IV-A rounding, Sec. III encoding."""
+    lib = _load()
+    xa = _f32(x)
+    codes = np.empty(xa.shape, dtype=np.uint16)
+    rc = lib.oracle_pack16(_ptr(xa), codes.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), xa.size, e, m, int(bool(d)))
+    if rc:
+        raise ValueError("format 1/%d/%d has no 16-bit code" % (e, m))
+    return codes
+
+
+def unpack16(codes, e: int, m: int) -> np.ndarray:
+    """float32 values of (1+e+m)-bit codes (Sec. III); NaN codes give the canonical quiet NaN."""
+    lib = _load()
+    ca = np.ascontiguousarray(codes, dtype=np.uint16)
+    y = np.empty(ca.shape, dtype=np.float32)
+    rc = lib.oracle_unpack16(ca.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), _ptr(y), ca.size, e, m)
+    if rc:
+        raise ValueError("format 1/%d/%d has no 16-bit code" % (e, m))
+    return y
 
 
 def dls_init(loss_scale: float) -> DlsState:

@@ -19,6 +19,7 @@
  *   - the quantized Linear layer Y = R(R(R(W^T) R(X)) + R(B))          (Sec. IV-A)
  *   - FMAC and the FMAC-8 dot product                                 (Sec. III-B, Sec. IV-A, Algorithm 1)
  *   - denormal fraction of a tensor                                   (Sec. V)
+ *   - the (1+e+m)-bit codes of the format's values                    (Sec. III)
  *
  * Notation used below: e = exponent bits, m = stored mantissa bits (the "p" of
  * Def. III.2 and Table I), bias = 2^(e-1)-1 ("vanilla" bias), Emax = bias,
@@ -338,6 +339,52 @@ uint32_t oracle_encode(float v, int e, int m)
         mant = (uint32_t)(ldexp(f, m + 1)) - (1u << m);
     }
     return (sign << (e + m)) | (field << m) | mant;
+}
+
+/*
+ * Value of a (1+e+m)-bit code (Sec. III, Def. III.1 with the hidden-bit convention and the special
+ * encodings): sign s, stored exponent field f, mantissa field t;
+ *   f == 0:         (-1)^s * t * 2^(Emin-m)                 zero and the denormal range
+ *   0 < f < 2^e-1:  (-1)^s * (2^m + t) * 2^(f-bias-m)       normal numbers, E = f - bias
+ *   f == 2^e-1:     t == 0: (-1)^s * infinity, else NaN (returned as the canonical quiet NaN)
+ * Bits of `code` above bit e+m are ignored.  Every such value is an fp32 value (e <= 8, m <= 23).
+ */
+float oracle_decode(uint32_t code, int e, int m)
+{
+    int bias = (1 << (e - 1)) - 1;
+    int emin = 1 - bias;
+    uint32_t top = (1u << e) - 1u;
+    uint32_t sign = (code >> (e + m)) & 1u;
+    uint32_t field = (code >> m) & top;
+    uint32_t mant = code & ((1u << m) - 1u);
+    double v;
+    if (field == top) {
+        if (mant != 0) return canonical_nan();
+        v = INFINITY;
+    } else if (field == 0) {
+        v = ldexp((double)mant, emin - m);
+    } else {
+        v = ldexp((double)((1u << m) + mant), (int)field - bias - m);
+    }
+    return (float)(sign ? -v : v);
+}
+
+/*
+ * Packed storage of a tensor in the format: codes[i] = code of roundfp(x[i]) (Sec. IV-A rounding,
+ * Sec. III encoding), and back.  Needs 1 + e + m <= 16.
+ */
+int oracle_pack16(const float *x, uint16_t *codes, size_t n, int e, int m, int d)
+{
+    if (!fmt_ok(e, m) || 1 + e + m > 16) return -1;
+    for (size_t i = 0; i < n; ++i) codes[i] = (uint16_t)oracle_encode(oracle_quantize_one(x[i], e, m, d), e, m);
+    return 0;
+}
+
+int oracle_unpack16(const uint16_t *codes, float *y, size_t n, int e, int m)
+{
+    if (!fmt_ok(e, m) || 1 + e + m > 16) return -1;
+    for (size_t i = 0; i < n; ++i) y[i] = oracle_decode(codes[i], e, m);
+    return 0;
 }
 
 /*

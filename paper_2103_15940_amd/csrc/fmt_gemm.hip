@@ -650,29 +650,29 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
             // compiler keeps LDS reads and loads-to-LDS in program order, so only this order lets
             // it thread the global loads between the MFMAs
             bf16x8 fa[KS][TM][P], fb[KS][TN][P];
-    #pragma unroll
+#pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
-    #pragma unroll
+#pragma unroll
                 for (int i = 0; i < TM; ++i)
-    #pragma unroll
+#pragma unroll
                     for (int q = 0; q < P; ++q)
                         fa[kk][i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
-    #pragma unroll
+#pragma unroll
                 for (int j = 0; j < TN; ++j)
-    #pragma unroll
+#pragma unroll
                     for (int q = 0; q < P; ++q)
                         fb[kk][j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
             }
             issue(t + NST - 1, (b + NST - 1) % NST);             // refills the buffer of stage t-1
-    #pragma unroll
+#pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
-    #pragma unroll
+#pragma unroll
                 for (int i = 0; i < TM; ++i)
-    #pragma unroll
+#pragma unroll
                     for (int j = 0; j < TN; ++j)
-    #pragma unroll
+#pragma unroll
                         for (int qa = 0; qa < P; ++qa)
-    #pragma unroll
+#pragma unroll
                             for (int qb = 0; qb < P; ++qb)
                                 acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[kk][i][qa]),
                                                                                              __builtin_bit_cast(f16x8, fb[kk][j][qb]),
@@ -685,14 +685,14 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 constexpr int kMfma = TM * TN * P * P * KS, kReads = (TM + TN) * P * KS, kLoads = LA + LB;
                 constexpr int kFront = (TM + TN) * P / 2 > 4 ? (TM + TN) * P / 2 : 4;
                 __builtin_amdgcn_sched_group_barrier(0x100, kFront, 0);
-    #pragma unroll
+#pragma unroll
                 for (int r = 0; r < kReads - kFront; ++r) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
                 constexpr int kLeft = kMfma - (kReads - kFront);
                 constexpr int kPer = kLeft / (kLoads + 1) > 0 ? kLeft / (kLoads + 1) : 1;
-    #pragma unroll
+#pragma unroll
                 for (int r = 0; r < kLoads; ++r) {
                     __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
                     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
