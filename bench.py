@@ -363,6 +363,23 @@ def main() -> int:
                                             "statistics of the output), 1/6/9/d",
                                 "ms": round(lin_ms, 4), "value": round(cfg4_flops / 3 / (lin_ms * 1e-3) / 1e12, 2),
                                 "unit": "TFLOP/s (useful)"}
+    # the same layers and the config 5 stream with 16-bit code output (2 instead of 4 bytes written per element)
+    Y16 = [torch.empty(L["Y"].shape, dtype=torch.int16, device=dev) for L in layers]
+
+    def linear16_all():
+        for L, b, o in zip(layers, biases, Y16):
+            fmt.fmt_linear_pack16(L["X"], L["W"], b, f169, out=o, hist=L["h"][0])
+    lin16_ms = timed(linear16_all, reps)
+    codes = torch.empty(x.shape, dtype=torch.int16, device=dev)
+    pack_ms = timed(lambda: fmt.fmt_pack16(x, f169, out=codes, hist=hists[0]), reps)
+    unpack_ms = timed(lambda: fmt.fmt_unpack16(codes, f169, out=y), reps)
+    result["pack16"] = {"workload": "16-bit code storage, 1/6/9/d: fmt_pack16 (+ statistics) and fmt_unpack16 on the "
+                                    "config 5 tensor (6 B per element each), fmt_linear_pack16 on the 4 encoder layers",
+                        "pack_gbps": round(6.0 * n / (pack_ms * 1e-3) / 1e9, 1),
+                        "unpack_gbps": round(6.0 * n / (unpack_ms * 1e-3) / 1e9, 1),
+                        "linear_ms": round(lin16_ms, 4),
+                        "linear_tflops": round(cfg4_flops / 3 / (lin16_ms * 1e-3) / 1e12, 2)}
+    del codes, Y16
     # FMAC-8 accumulation (Algorithm 1): a sequential chain of roundings per output, vector ALUs only
     A8 = torch.randn((2048, 1024), device=dev)
     B8 = torch.randn((1024, 2048), device=dev) * 0.05

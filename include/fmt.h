@@ -26,6 +26,8 @@
  * and, beyond these three:
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
  *   fmt_linear     the quantized fully connected layer of Sec. IV-A (product, bias, output roundings, statistics)
+ *   fmt_pack16 / fmt_unpack16 / fmt_linear_pack16   the same roundings with the result stored as the
+ *                  format's own 16-bit codes (Sec. III) instead of fp32: half the bytes written
  *   fmt_conv2d_*   convolution forward / dgrad / wgrad as the same product on patches gathered on the fly
  *   fmt_dls_step   loss-scale controller and denormal-fraction monitor on the device (Sec. II, Sec. V)
  *
@@ -208,6 +210,43 @@ int fmt_linear(int64_t M, int64_t N, int64_t K,
                const float *X, int64_t ldx, const float *W, int64_t ldw, const float *b,
                float *Y, int64_t ldy, fmt_format_t f,
                fmt_hist_t *hist, int32_t exp_lo, void *stream);
+
+/*
+ * Packed storage.  A value of a 1/e/m format with 1 + e + m <= 16 has a code of that many bits
+ * (Sec. III: Def. III.1 with the hidden bit not stored, the "vanilla" bias, and the reserved
+ * encodings), kept in the low bits of a uint16_t, upper bits zero:
+ *     bit e+m          sign
+ *     bits [m, e+m)    stored exponent: 0 = zero / denormal range (value = mantissa * 2^(Emin-m)),
+ *                      2^e - 1 = infinity (mantissa 0) or NaN, otherwise E + bias
+ *     bits [0, m)      stored mantissa (normal numbers: the bits after the hidden leading 1)
+ * 1/5/10 codes are IEEE binary16 patterns, 1/8/7 codes are bfloat16 patterns (the upper half of the
+ * fp32 pattern).  Formats with 1 + e + m > 16 have no such code: FMT_ERR_FORMAT.
+ *
+ * fmt_pack16   codes[i] = code of Q_{e,m,d|n}(x[i]), the rounding of fmt_quantize (any NaN gives the
+ *              quiet-NaN code: sign 0, exponent all ones, top mantissa bit).  hist as in fmt_quantize:
+ *              statistics of x in the same pass, or NULL.  6 bytes move per element instead of 8.
+ *              codes: device, n uint16_t, 2-byte aligned (8-byte alignment, with x 16-byte aligned,
+ *              enables the fastest path); must not overlap x.
+ * fmt_unpack16 y[i] = value of codes[i] as fp32 (exact; NaN codes give 0x7FC00000; bits of a code
+ *              above bit e+m are ignored).  f.denorm is not used: a code of the denormal range is
+ *              decoded as what it says.  y must not overlap codes.
+ * n == 0 succeeds without a launch (*hist, when given, is zeroed).  n must be below 2^40.
+ */
+int fmt_pack16(const float *x, uint16_t *codes, size_t n, fmt_format_t f,
+               fmt_hist_t *hist, int32_t exp_lo, void *stream);
+int fmt_unpack16(const uint16_t *codes, float *y, size_t n, fmt_format_t f, void *stream);
+
+/*
+ * fmt_linear_pack16 -- fmt_linear with the layer's output stored as 16-bit codes (see fmt_pack16):
+ * Y16[i][j] = code of Y[i][j], the M x N result of fmt_linear (ldy >= N, in uint16_t elements).
+ * The fp32 accumulators live in library scratch (M*N floats, grown on first use like the other
+ * scratch), so the output stage reads 4 bytes and writes 2 per element.  Everything else --
+ * arguments, statistics, limits, errors -- as for fmt_linear; needs 1 + e + m <= 16.
+ */
+int fmt_linear_pack16(int64_t M, int64_t N, int64_t K,
+                      const float *X, int64_t ldx, const float *W, int64_t ldw, const float *b,
+                      uint16_t *Y16, int64_t ldy, fmt_format_t f,
+                      fmt_hist_t *hist, int32_t exp_lo, void *stream);
 
 /*
  * Convolution layers (Sec. IV-A: the inner matrix multiplies "or convolutions" of the forward and

@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_release_scratch", "fmt_status_string")
 
 
@@ -89,6 +89,12 @@ def _load() -> ctypes.CDLL:
     lib.fmt_gemm_fmac8.restype = ctypes.c_int
     lib.fmt_linear.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, _CFormat, vp, i32, vp]
     lib.fmt_linear.restype = ctypes.c_int
+    lib.fmt_pack16.argtypes = [vp, vp, sz, _CFormat, vp, i32, vp]
+    lib.fmt_pack16.restype = ctypes.c_int
+    lib.fmt_unpack16.argtypes = [vp, vp, sz, _CFormat, vp]
+    lib.fmt_unpack16.restype = ctypes.c_int
+    lib.fmt_linear_pack16.argtypes = lib.fmt_linear.argtypes
+    lib.fmt_linear_pack16.restype = ctypes.c_int
     for fn in (lib.fmt_conv2d_fwd, lib.fmt_conv2d_dgrad, lib.fmt_conv2d_wgrad):
         fn.argtypes = [_CConv2d, vp, vp, vp, _CFormat, vp]
         fn.restype = ctypes.c_int
@@ -263,6 +269,87 @@ def fmt_linear(X, W, bias, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAUL
     rc = _lib.fmt_linear(M, N, K, X.data_ptr(), ldx, W.data_ptr(), ldw, bp, out.data_ptr(), ldy, _cfmt(fmt),
                          hp, int(exp_lo), _stream_ptr(stream))
     _check(rc, "fmt_linear")
+    return out
+
+
+def _dev_codes(t, name: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or t.dtype not in (torch.int16, torch.uint16) or not t.is_cuda:
+        raise TypeError("%s must be a GPU int16 (or uint16) tensor holding the 16-bit codes" % name)
+    return t
+
+
+def _hist_ptr(hist):
+    import torch
+    if hist is None:
+        return None
+    if hist.dtype != torch.int64 or hist.numel() != 8 + FMT_NBINS or not hist.is_cuda:
+        raise TypeError("hist must be a GPU int64 tensor of 72 elements")
+    return hist.data_ptr()
+
+
+def fmt_pack16(x, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None):
+    """:func:`fmt_quantize` with the result stored as the format's own 16-bit codes (Sec. III;
+    needs 1 + e + m <= 16): returns an int16 tensor of x's shape holding the code bit patterns."""
+    import torch
+    _dev_f32(x, "x")
+    if not x.is_contiguous():
+        raise ValueError("x must be contiguous")
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.int16, device=x.device)
+    _dev_codes(out, "out")
+    if not out.is_contiguous() or out.numel() != x.numel():
+        raise ValueError("out must be contiguous and as large as x")
+    rc = _lib.fmt_pack16(x.data_ptr(), out.data_ptr(), x.numel(), _cfmt(fmt), _hist_ptr(hist), int(exp_lo),
+                         _stream_ptr(stream))
+    _check(rc, "fmt_pack16")
+    return out
+
+
+def fmt_unpack16(codes, fmt, out=None, stream=None):
+    """fp32 values of 16-bit codes (the inverse of :func:`fmt_pack16` on its results)."""
+    import torch
+    _dev_codes(codes, "codes")
+    if not codes.is_contiguous():
+        raise ValueError("codes must be contiguous")
+    if out is None:
+        out = torch.empty(codes.shape, dtype=torch.float32, device=codes.device)
+    _dev_f32(out, "out")
+    if not out.is_contiguous() or out.numel() != codes.numel():
+        raise ValueError("out must be contiguous and as large as codes")
+    rc = _lib.fmt_unpack16(codes.data_ptr(), out.data_ptr(), codes.numel(), _cfmt(fmt), _stream_ptr(stream))
+    _check(rc, "fmt_unpack16")
+    return out
+
+
+def fmt_linear_pack16(X, W, bias, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None):
+    """:func:`fmt_linear` with the output stored as 16-bit codes (int16 tensor [batch, out])."""
+    import torch
+    for t, name in ((X, "X"), (W, "W")):
+        _dev_f32(t, name)
+        if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("%s must be 2-D with unit column stride" % name)
+    M, K = X.shape
+    N, K2 = W.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, K2))
+    bp = None
+    if bias is not None:
+        _dev_f32(bias, "bias")
+        if bias.dim() != 1 or bias.numel() != N or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous vector with one value per output column")
+        bp = bias.data_ptr()
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int16, device=X.device)
+    _dev_codes(out, "out")
+    if out.dim() != 2 or tuple(out.shape) != (M, N) or (N > 1 and out.stride(1) != 1):
+        raise ValueError("out must be an M x N tensor with unit column stride")
+    ldx = X.stride(0) if M > 1 else max(K, 1)
+    ldw = W.stride(0) if N > 1 else max(K, 1)
+    ldy = out.stride(0) if M > 1 else max(N, 1)
+    rc = _lib.fmt_linear_pack16(M, N, K, X.data_ptr(), ldx, W.data_ptr(), ldw, bp, out.data_ptr(), ldy, _cfmt(fmt),
+                                _hist_ptr(hist), int(exp_lo), _stream_ptr(stream))
+    _check(rc, "fmt_linear_pack16")
     return out
 
 

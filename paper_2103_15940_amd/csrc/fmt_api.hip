@@ -54,6 +54,8 @@ int make_quant_params(fmt_format_t f, int32_t exp_lo, QuantParams *p)
     const uint32_t maxn_bits = ((uint32_t)(emax + 127) << 23) | (((1u << m) - 1u) << shift);
     p->t_ovf = (m <= 22) ? maxn_bits + (1u << (shift - 1)) : (uint32_t)(emax + 128) << 23;
     p->exp_lo = exp_lo;
+    p->sign_pos = (uint32_t)(e + m);
+    p->top_code = ((1u << e) - 1u) << m;
     return FMT_OK;
 }
 
@@ -88,6 +90,18 @@ int get_scratch(hipStream_t stream, size_t hist_bytes, size_t gemm_bytes, Scratc
     rc = grow(&s.gemm_ws, &s.gemm_bytes, gemm_bytes);
     if (rc != FMT_OK) return rc;
     *out = s;
+    return FMT_OK;
+}
+
+int get_acc_scratch(hipStream_t stream, size_t bytes, float **out)
+{
+    int dev = 0;
+    FMT_HIP_CHECK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_mu);
+    Scratch &s = g_scratch[std::make_pair(dev, stream)];
+    int rc = grow(&s.acc_ws, &s.acc_bytes, bytes);
+    if (rc != FMT_OK) return rc;
+    *out = static_cast<float *>(s.acc_ws);
     return FMT_OK;
 }
 
@@ -226,6 +240,67 @@ int fmt_linear(int64_t M, int64_t N, int64_t K,
     return launch_linear_epilogue(Y, ldy, M, N, b, p, f.denorm == 0, hist, s);
 }
 
+static bool has_code16(fmt_format_t f) { return 1 + f.e + f.m <= 16; }
+
+int fmt_pack16(const float *x, uint16_t *codes, size_t n, fmt_format_t f,
+               fmt_hist_t *hist, int32_t exp_lo, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, hist ? exp_lo : FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (!has_code16(f)) return FMT_ERR_FORMAT;
+    if (n >= ((size_t)1 << 40)) return FMT_ERR_SHAPE;
+    if (n > 0 && (!x || !codes)) return FMT_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(codes, 2) || !aligned(hist, 8)) return FMT_ERR_ALIGN;
+    if (n > 0 && overlap(x, n * 4, codes, n * 2)) return FMT_ERR_ALIAS;
+    if (n == 0 && !hist) return FMT_OK;
+    return launch_stream(x, codes, n, p, f.denorm == 0, hist, static_cast<hipStream_t>(stream), true);
+}
+
+int fmt_unpack16(const uint16_t *codes, float *y, size_t n, fmt_format_t f, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (!has_code16(f)) return FMT_ERR_FORMAT;
+    if (n >= ((size_t)1 << 40)) return FMT_ERR_SHAPE;
+    if (n > 0 && (!codes || !y)) return FMT_ERR_NULL;
+    if (!aligned(codes, 2) || !aligned(y, 4)) return FMT_ERR_ALIGN;
+    if (n > 0 && overlap(codes, n * 2, y, n * 4)) return FMT_ERR_ALIAS;
+    return launch_unpack16(codes, y, n, p, static_cast<hipStream_t>(stream));
+}
+
+int fmt_linear_pack16(int64_t M, int64_t N, int64_t K,
+                      const float *X, int64_t ldx, const float *W, int64_t ldw, const float *b,
+                      uint16_t *Y16, int64_t ldy, fmt_format_t f,
+                      fmt_hist_t *hist, int32_t exp_lo, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, hist ? exp_lo : FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (!has_code16(f)) return FMT_ERR_FORMAT;
+    if (hist && !aligned(hist, 8)) return FMT_ERR_ALIGN;
+    const int64_t lim = (int64_t)1 << 31;
+    if (M < 0 || N < 0 || K < 0 || M >= lim || N >= lim || K >= lim) return FMT_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M == 0 || N == 0) return launch_linear_epilogue_pack16(nullptr, 0, Y16, ldy, 0, 0, nullptr, p, f.denorm == 0, hist, s);
+    if (!Y16 || (K > 0 && (!X || !W))) return FMT_ERR_NULL;
+    if (ldy < N || ldy >= lim) return FMT_ERR_SHAPE;
+    if (K > 0 && (ldx < K || ldw < K || ldx >= lim || ldw >= lim)) return FMT_ERR_SHAPE;
+    if (!aligned(X, 4) || !aligned(W, 4) || !aligned(Y16, 2) || !aligned(b, 4)) return FMT_ERR_ALIGN;
+    const size_t ybytes = 2 * (size_t)((M - 1) * ldy + N);
+    if (K > 0 && (overlap(Y16, ybytes, X, 4 * (size_t)((M - 1) * ldx + K)) ||
+                  overlap(Y16, ybytes, W, 4 * (size_t)((N - 1) * ldw + K))))
+        return FMT_ERR_ALIAS;
+    if (b && overlap(Y16, ybytes, b, 4 * (size_t)N)) return FMT_ERR_ALIAS;
+    float *acc = nullptr;
+    rc = get_acc_scratch(s, (size_t)M * (size_t)N * sizeof(float), &acc);
+    if (rc != FMT_OK) return rc;
+    rc = launch_gemm(0, 1, M, N, K, X, ldx, W, ldw, acc, N, f, p, s);
+    if (rc != FMT_OK) return rc;
+    return launch_linear_epilogue_pack16(acc, N, Y16, ldy, M, N, b, p, f.denorm == 0, hist, s);
+}
+
 // Validates a convolution call; *launch is false when the output is empty.  which: 0 forward
 // (a = X, b = W, out = Y), 1 dgrad (dY, W, dX), 2 wgrad (dY, X, dW).
 static int check_conv_args(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, bool *launch)
@@ -336,6 +411,7 @@ int fmt_release_scratch(void)
     for (auto it = g_scratch.begin(); it != g_scratch.end();) {
         if (it->first.first == dev) {
             if (it->second.hist_partials) (void)hipFree(it->second.hist_partials);
+            if (it->second.acc_ws) (void)hipFree(it->second.acc_ws);
             if (it->second.gemm_ws) (void)hipFree(it->second.gemm_ws);
             it = g_scratch.erase(it);
         } else {

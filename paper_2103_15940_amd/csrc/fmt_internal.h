@@ -25,6 +25,8 @@ struct QuantParams {
     uint32_t t_den;       // result is below minN  <=>  a <  t_den    (minN - minD/2, the tie goes to minN)
     uint32_t t_ovf;       // result is infinite    <=>  a >= t_ovf    (maxN + ulp/2, the tie goes to infinity)
     int32_t exp_lo;       // lowest binade of the histogram window
+    uint32_t sign_pos;    // e + m: position of the sign in the format's (1+e+m)-bit code
+    uint32_t top_code;    // (2^e - 1) << m: code of +infinity
 };
 
 // Fills p from the format; returns FMT_OK or FMT_ERR_FORMAT / FMT_ERR_RANGE.
@@ -36,6 +38,8 @@ struct Scratch {
     size_t hist_bytes = 0;
     void *gemm_ws = nullptr;        // pre-split GEMM operands
     size_t gemm_bytes = 0;
+    void *acc_ws = nullptr;         // fp32 accumulators of fmt_linear_pack16
+    size_t acc_bytes = 0;
 };
 
 // Returns the scratch record for (current device, stream), growing the requested buffers.
@@ -43,9 +47,10 @@ int get_scratch(hipStream_t stream, size_t hist_bytes, size_t gemm_bytes, Scratc
 
 int device_cu_count(int *cus);
 
-// Stream kernels (fmt_stream.hip)
-int launch_stream(const float *x, float *y, size_t n, const QuantParams &p, bool ftz,
-                  fmt_hist_t *hist, hipStream_t stream);
+// Stream kernels (fmt_stream.hip).  y: n floats, or with pack16 n uint16_t codes, or nullptr (statistics only).
+int launch_stream(const float *x, void *y, size_t n, const QuantParams &p, bool ftz,
+                  fmt_hist_t *hist, hipStream_t stream, bool pack16 = false);
+int launch_unpack16(const uint16_t *codes, float *y, size_t n, const QuantParams &p, hipStream_t stream);
 
 // GEMM (fmt_gemm.hip)
 int launch_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
@@ -61,9 +66,15 @@ int launch_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const float *A, int64_t lda, const float *B, int64_t ldb,
                       float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
 
-// Output roundings of the Linear layer, in place on Y (fmt_linear.hip)
+// Output roundings of the Linear layer (fmt_linear.hip): in place on Y, or from the accumulators
+// acc (leading dimension lda) into 16-bit codes Y16.
 int launch_linear_epilogue(float *Y, int64_t ldy, int64_t M, int64_t N, const float *bias, const QuantParams &p,
                            bool ftz, fmt_hist_t *hist, hipStream_t stream);
+int launch_linear_epilogue_pack16(const float *acc, int64_t lda, uint16_t *Y16, int64_t ldy, int64_t M, int64_t N,
+                                  const float *bias, const QuantParams &p, bool ftz, fmt_hist_t *hist,
+                                  hipStream_t stream);
+// Library scratch for the accumulators of fmt_linear_pack16 (per device and stream, grown on demand).
+int get_acc_scratch(hipStream_t stream, size_t bytes, float **out);
 
 // Loss-scale controller (fmt_dls.hip)
 int launch_dls_init(fmt_dls_state_t *state, float loss_scale, hipStream_t stream);

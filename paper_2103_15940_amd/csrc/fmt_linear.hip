@@ -4,6 +4,9 @@
 // format.  The statistics of Sec. V are taken of t = R(acc) + R(b), the tensor that enters the
 // last rounding, in the same pass.
 //
+// With PACK the accumulators come from a buffer of their own and the result is stored as the
+// format's 16-bit codes (Sec. III): 6 bytes per element instead of 8.
+//
 // HBM-bound: one read and one write of the M x N output (8 bytes per element), the bias row is
 // rounded once per thread and kept in registers.  A workgroup owns a strip of 1024 columns
 // (256 lanes x 4) and a range of rows; rows are walked four at a time so that four 128-bit loads
@@ -17,15 +20,22 @@ namespace fmt {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kLBlock = 256;
 constexpr int kLCopies = 32;
 constexpr int kLRows = 4;                 // rows per trip (independent loads in flight)
 
-template <int MODE, bool FTZ, bool HIST, bool DEEP, bool VEC>
-__global__ __launch_bounds__(kLBlock) void linear_epilogue_kernel(uint32_t *__restrict__ Y, int64_t ldy, int M, int N,
-                                                                  const uint32_t *__restrict__ bias, int rows_per_wg,
-                                                                  QuantParams p, unsigned long long *__restrict__ partials)
+// A: accumulators (leading dimension lda); Y: output, fp32 patterns (== A, in place) or, with PACK,
+// uint16_t codes.  VEC: 128-bit loads and full-width stores are possible for whole lanes.
+template <int MODE, bool FTZ, bool HIST, bool DEEP, bool VEC, bool PACK>
+__global__ __launch_bounds__(kLBlock) void linear_epilogue_kernel(const uint32_t *A, int64_t lda, void *Yv, int64_t ldy,
+                                                                  int M, int N, const uint32_t *__restrict__ bias,
+                                                                  int rows_per_wg, QuantParams p,
+                                                                  unsigned long long *__restrict__ partials)
 {
+    constexpr int EM = MODE == kModeInteger ? kModeInteger : kModeMagic;
+    uint32_t *Y = static_cast<uint32_t *>(Yv);
+    uint16_t *Y16 = static_cast<uint16_t *>(Yv);
     __shared__ __attribute__((aligned(16))) uint32_t tbl[HIST ? kHistRows * kLCopies : 4];
     __shared__ uint32_t s_bins[FMT_NBINS];
     __shared__ uint32_t s_cls[8];
@@ -51,7 +61,7 @@ __global__ __launch_bounds__(kLBlock) void linear_epilogue_kernel(uint32_t *__re
         for (int i = 0; i < kLRows; ++i) {
             v[i] = u32x4{0u, 0u, 0u, 0u};
             if (r + i < r_end) {
-                uint32_t *row = Y + (size_t)(r + i) * ldy + c0;
+                const uint32_t *row = A + (size_t)(r + i) * lda + c0;
                 if (full) {
                     v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row));
                 } else {
@@ -73,7 +83,19 @@ __global__ __launch_bounds__(kLBlock) void linear_epilogue_kernel(uint32_t *__re
                 if (HIST) account<DEEP, kLCopies>(t & 0x7FFFFFFFu, rv && j < ncol, p, tbl, copy, w);
                 o[j] = quantize_bits<MODE, FTZ>(t, p);
             }
-            if (rv) {
+            if (rv && PACK) {
+                uint16_t *row = Y16 + (size_t)(r + i) * ldy + c0;
+                uint32_t c[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c[j] = encode_bits<EM>(o[j], p);
+                if (full) {
+                    __builtin_nontemporal_store(u32x2{c[0] | (c[1] << 16), c[2] | (c[3] << 16)}, reinterpret_cast<u32x2 *>(row));
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (j < ncol) row[j] = (uint16_t)c[j];
+                }
+            } else if (rv) {
                 uint32_t *row = Y + (size_t)(r + i) * ldy + c0;
                 if (full) {
                     __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(row));
@@ -90,9 +112,9 @@ __global__ __launch_bounds__(kLBlock) void linear_epilogue_kernel(uint32_t *__re
                                     (blockIdx.y * gridDim.x + blockIdx.x) % kShards, tid);
 }
 
-template <int MODE, bool FTZ, bool HIST, bool DEEP>
-int launch_v(float *Y, int64_t ldy, int M, int N, const float *bias, const QuantParams &p, fmt_hist_t *hist,
-             hipStream_t stream)
+template <int MODE, bool FTZ, bool HIST, bool DEEP, bool PACK>
+int launch_v(const float *A, int64_t lda, void *Y, int64_t ldy, int M, int N, const float *bias, const QuantParams &p,
+             fmt_hist_t *hist, hipStream_t stream)
 {
     int cus = 0;
     int rc = device_cu_count(&cus);
@@ -119,28 +141,29 @@ int launch_v(float *Y, int64_t ldy, int M, int N, const float *bias, const Quant
         if (rc != FMT_OK) return rc;
         partials = static_cast<unsigned long long *>(s.hist_partials);
     }
-    const bool vec = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
+    const bool vec = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 4 == 0) &&
+                     (reinterpret_cast<uintptr_t>(Y) % (PACK ? 8 : 16) == 0) && (ldy % 4 == 0);
     const dim3 grid((unsigned)strips, (unsigned)row_groups);
-    uint32_t *y = reinterpret_cast<uint32_t *>(Y);
+    const uint32_t *a = reinterpret_cast<const uint32_t *>(A);
     const uint32_t *b = reinterpret_cast<const uint32_t *>(bias);
     if (vec)
-        hipLaunchKernelGGL((linear_epilogue_kernel<MODE, FTZ, HIST, DEEP, true>), grid, dim3(kLBlock), 0, stream, y, ldy,
-                           M, N, b, (int)rows_per_wg, p, partials);
+        hipLaunchKernelGGL((linear_epilogue_kernel<MODE, FTZ, HIST, DEEP, true, PACK>), grid, dim3(kLBlock), 0, stream, a,
+                           lda, Y, ldy, M, N, b, (int)rows_per_wg, p, partials);
     else
-        hipLaunchKernelGGL((linear_epilogue_kernel<MODE, FTZ, HIST, DEEP, false>), grid, dim3(kLBlock), 0, stream, y,
-                           ldy, M, N, b, (int)rows_per_wg, p, partials);
+        hipLaunchKernelGGL((linear_epilogue_kernel<MODE, FTZ, HIST, DEEP, false, PACK>), grid, dim3(kLBlock), 0, stream, a,
+                           lda, Y, ldy, M, N, b, (int)rows_per_wg, p, partials);
     FMT_HIP_CHECK(hipGetLastError());
     if (HIST) return launch_hist_finalize(partials, (size_t)M * (size_t)N, hist, stream);
     return FMT_OK;
 }
 
-template <int MODE, bool FTZ>
-int launch_h(float *Y, int64_t ldy, int M, int N, const float *bias, const QuantParams &p, fmt_hist_t *hist,
-             hipStream_t stream)
+template <int MODE, bool FTZ, bool PACK>
+int launch_h(const float *A, int64_t lda, void *Y, int64_t ldy, int M, int N, const float *bias, const QuantParams &p,
+             fmt_hist_t *hist, hipStream_t stream)
 {
-    if (!hist) return launch_v<MODE, FTZ, false, false>(Y, ldy, M, N, bias, p, hist, stream);
-    if (p.exp_lo < -126) return launch_v<MODE, FTZ, true, true>(Y, ldy, M, N, bias, p, hist, stream);
-    return launch_v<MODE, FTZ, true, false>(Y, ldy, M, N, bias, p, hist, stream);
+    if (!hist) return launch_v<MODE, FTZ, false, false, PACK>(A, lda, Y, ldy, M, N, bias, p, hist, stream);
+    if (p.exp_lo < -126) return launch_v<MODE, FTZ, true, true, PACK>(A, lda, Y, ldy, M, N, bias, p, hist, stream);
+    return launch_v<MODE, FTZ, true, false, PACK>(A, lda, Y, ldy, M, N, bias, p, hist, stream);
 }
 
 }  // namespace
@@ -153,11 +176,28 @@ int launch_linear_epilogue(float *Y, int64_t ldy, int64_t M, int64_t N, const fl
         return FMT_OK;
     }
 #define FMT_RUN(MD)                                                                                                   \
-    (ftz ? launch_h<MD, true>(Y, ldy, (int)M, (int)N, bias, p, hist, stream)                                         \
-         : launch_h<MD, false>(Y, ldy, (int)M, (int)N, bias, p, hist, stream))
+    (ftz ? launch_h<MD, true, false>(Y, ldy, Y, ldy, (int)M, (int)N, bias, p, hist, stream)                          \
+         : launch_h<MD, false, false>(Y, ldy, Y, ldy, (int)M, (int)N, bias, p, hist, stream))
     if (p.mode == kModeMagic) return FMT_RUN(kModeMagic);
     if (p.mode == kModeInteger) return FMT_RUN(kModeInteger);
     return FMT_RUN(kModeMixed);
+#undef FMT_RUN
+}
+
+int launch_linear_epilogue_pack16(const float *acc, int64_t lda, uint16_t *Y16, int64_t ldy, int64_t M, int64_t N,
+                                  const float *bias, const QuantParams &p, bool ftz, fmt_hist_t *hist,
+                                  hipStream_t stream)
+{
+    if (p.mode == kModeMixed) return FMT_ERR_FORMAT;     // m == 23 has no 16-bit code
+    if (M == 0 || N == 0) {
+        if (hist) return launch_hist_finalize(nullptr, 0, hist, stream);
+        return FMT_OK;
+    }
+#define FMT_RUN(MD)                                                                                                   \
+    (ftz ? launch_h<MD, true, true>(acc, lda, Y16, ldy, (int)M, (int)N, bias, p, hist, stream)                       \
+         : launch_h<MD, false, true>(acc, lda, Y16, ldy, (int)M, (int)N, bias, p, hist, stream))
+    if (p.mode == kModeInteger) return FMT_RUN(kModeInteger);
+    return FMT_RUN(kModeMagic);
 #undef FMT_RUN
 }
 

@@ -39,6 +39,7 @@
 namespace fmt {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = FMT_STREAM_BLOCK;  // threads per workgroup
 constexpr int kCopies = 32;              // replicas of the exponent table (one per LDS bank)
@@ -64,11 +65,31 @@ __device__ __forceinline__ u32x4 do_vec(u32x4 v, bool valid, const QuantParams &
 // x + head (and y + head when STORE) 16-byte aligned; the at most 6 remaining elements at both
 // ends are handled one per lane by the first wave of workgroup 0.  VEC = false is the fallback
 // for x and y misaligned relative to each other: the whole range goes one dword per lane.
-template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC>
+// PACK: y holds the format's 16-bit codes instead of fp32 values (two bytes written per element; the
+// vector body then needs y + head 8-byte aligned).
+template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC, bool PACK>
 __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restrict__ x, uint32_t *__restrict__ y,
                                                         size_t n, size_t head, size_t nvec, QuantParams p,
                                                         unsigned long long *__restrict__ partials)
 {
+    constexpr int EM = MODE == kModeInteger ? kModeInteger : kModeMagic;   // encode_bits' variant
+    uint16_t *__restrict__ y16 = reinterpret_cast<uint16_t *>(y);
+    auto put = [&](size_t vec_index, u32x4 o) {
+        if (PACK) {
+            u32x2 c;
+            c[0] = encode_bits<EM>(o[0], p) | (encode_bits<EM>(o[1], p) << 16);
+            c[1] = encode_bits<EM>(o[2], p) | (encode_bits<EM>(o[3], p) << 16);
+            __builtin_nontemporal_store(c, reinterpret_cast<u32x2 *>(y16 + head) + vec_index);
+        } else {
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(y + head) + vec_index);
+        }
+    };
+    auto put_one = [&](size_t idx, uint32_t r) {
+        if (PACK)
+            y16[idx] = (uint16_t)encode_bits<EM>(r, p);
+        else
+            y[idx] = r;
+    };
     __shared__ __attribute__((aligned(16))) uint32_t tbl[HIST ? kHistRows * kCopies : 4];
     __shared__ uint32_t s_bins[FMT_NBINS];
     __shared__ uint32_t s_cls[8];
@@ -80,7 +101,6 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
 
     if (VEC) {
         const u32x4 *xv = reinterpret_cast<const u32x4 *>(x + head);
-        u32x4 *yv = reinterpret_cast<u32x4 *>(y + head);
         // A tile is kBlock*kUnroll consecutive vectors; workgroup b takes tiles b, b+grid, ...
         // Every lane of the workgroup runs the same trips, and all tiles but the last are full.
         constexpr size_t kTileVec = (size_t)kBlock * kUnroll;
@@ -93,7 +113,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
 #pragma unroll
             for (int k = 0; k < kUnroll; ++k) {
                 u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v[k], true, p, tbl, lane32, w);
-                if (STORE) __builtin_nontemporal_store(o, yv + i + k * kBlock);
+                if (STORE) put(i + k * kBlock, o);
             }
         }
         if (blockIdx.x == full_tiles % gridDim.x && full_tiles * kTileVec < nvec) {
@@ -105,7 +125,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (valid) v = __builtin_nontemporal_load(xv + i);
                 u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v, valid, p, tbl, lane32, w);
-                if (STORE && valid) __builtin_nontemporal_store(o, yv + i);
+                if (STORE && valid) put(i, o);
             }
         }
         if (blockIdx.x == 0 && tid < 64) {
@@ -117,7 +137,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
             if (!valid) idx = 0;
             const uint32_t u = valid ? x[idx] : 0u;
             if (HIST) account<DEEP, kCopies>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
-            if (STORE && valid) y[idx] = quantize_bits<MODE, FTZ>(u, p);
+            if (STORE && valid) put_one(idx, quantize_bits<MODE, FTZ>(u, p));
         }
     } else {
         const size_t stride = (size_t)gridDim.x * kBlock;
@@ -128,7 +148,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
             const bool valid = i < n;
             const uint32_t u = valid ? x[i] : 0u;
             if (HIST) account<DEEP, kCopies>(u & 0x7FFFFFFFu, valid, p, tbl, lane32, w);
-            if (STORE && valid) y[i] = quantize_bits<MODE, FTZ>(u, p);
+            if (STORE && valid) put_one(i, quantize_bits<MODE, FTZ>(u, p));
         }
     }
 
@@ -187,11 +207,11 @@ int launch_hist_finalize(unsigned long long *partials, size_t n, fmt_hist_t *his
     return FMT_OK;
 }
 
-template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC>
-static int launch_variant(const float *x, float *y, size_t n, size_t head, size_t nvec, const QuantParams &p,
+template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC, bool PACK>
+static int launch_variant(const float *x, void *y, size_t n, size_t head, size_t nvec, const QuantParams &p,
                           fmt_hist_t *hist, hipStream_t stream)
 {
-    auto kern = stream_kernel<MODE, STORE, FTZ, HIST, DEEP, VEC>;
+    auto kern = stream_kernel<MODE, STORE, FTZ, HIST, DEEP, VEC, PACK>;
     int cus = 0;
     int rc = device_cu_count(&cus);
     if (rc != FMT_OK) return rc;
@@ -218,8 +238,8 @@ static int launch_variant(const float *x, float *y, size_t n, size_t head, size_
     return FMT_OK;
 }
 
-int launch_stream(const float *x, float *y, size_t n, const QuantParams &p, bool ftz, fmt_hist_t *hist,
-                  hipStream_t stream)
+int launch_stream(const float *x, void *y, size_t n, const QuantParams &p, bool ftz, fmt_hist_t *hist,
+                  hipStream_t stream, bool pack16)
 {
     const bool store = y != nullptr;
     const bool do_hist = hist != nullptr;
@@ -228,30 +248,112 @@ int launch_stream(const float *x, float *y, size_t n, const QuantParams &p, bool
         if (do_hist) return launch_hist_finalize(nullptr, 0, hist, stream);
         return FMT_OK;
     }
-    // elements before the first 16-byte boundary of x (and of y: both must agree for the vector path)
+    // elements before the first 16-byte boundary of x, and before the first 16-byte (codes: 8-byte)
+    // boundary of y: both must agree for the vector path
     const size_t hx = ((16 - (reinterpret_cast<uintptr_t>(x) & 15)) & 15) / 4;
-    const size_t hy = store ? ((16 - (reinterpret_cast<uintptr_t>(y) & 15)) & 15) / 4 : hx;
+    const size_t hy = !store ? hx
+                      : pack16 ? ((8 - (reinterpret_cast<uintptr_t>(y) & 7)) & 7) / 2
+                               : ((16 - (reinterpret_cast<uintptr_t>(y) & 15)) & 15) / 4;
     const bool vec = hx == hy;
     size_t head = hx < n ? hx : n;
     size_t nvec = vec ? (n - head) / 4 : 0;
     if (!vec) head = 0;
 
-#define FMT_LAUNCH_M(MD, S, F, H, D)                                                                         \
-    (vec ? launch_variant<MD, S, F, H, D, true>(x, y, n, head, nvec, p, hist, stream)               \
-         : launch_variant<MD, S, F, H, D, false>(x, y, n, head, nvec, p, hist, stream))
+#define FMT_LAUNCH_M(MD, S, F, H, D, PK)                                                                     \
+    (vec ? launch_variant<MD, S, F, H, D, true, PK>(x, y, n, head, nvec, p, hist, stream)           \
+         : launch_variant<MD, S, F, H, D, false, PK>(x, y, n, head, nvec, p, hist, stream))
 #define FMT_LAUNCH(S, F, H, D)                                                                               \
-    (p.mode == kModeMagic ? FMT_LAUNCH_M(kModeMagic, S, F, H, D)                                             \
-     : p.mode == kModeInteger ? FMT_LAUNCH_M(kModeInteger, S, F, H, D)                                       \
-                              : FMT_LAUNCH_M(kModeMixed, S, F, H, D))
+    (p.mode == kModeMagic ? FMT_LAUNCH_M(kModeMagic, S, F, H, D, false)                                      \
+     : p.mode == kModeInteger ? FMT_LAUNCH_M(kModeInteger, S, F, H, D, false)                                \
+                              : FMT_LAUNCH_M(kModeMixed, S, F, H, D, false))
+    // formats with a 16-bit code have m <= 14: never the m == 23 variant
+#define FMT_LAUNCH_PACK(F, H, D)                                                                             \
+    (p.mode == kModeInteger ? FMT_LAUNCH_M(kModeInteger, true, F, H, D, true) : FMT_LAUNCH_M(kModeMagic, true, F, H, D, true))
+    if (pack16) {
+        if (!store || p.mode == kModeMixed) return FMT_ERR_FORMAT;
+        if (!do_hist) return ftz ? FMT_LAUNCH_PACK(true, false, false) : FMT_LAUNCH_PACK(false, false, false);
+        if (deep) return ftz ? FMT_LAUNCH_PACK(true, true, true) : FMT_LAUNCH_PACK(false, true, true);
+        return ftz ? FMT_LAUNCH_PACK(true, true, false) : FMT_LAUNCH_PACK(false, true, false);
+    }
     // the statistics do not depend on how the rounding is carried out: one instantiation serves all
     if (!store)
-        return deep ? FMT_LAUNCH_M(kModeMagic, false, false, true, true)
-                    : FMT_LAUNCH_M(kModeMagic, false, false, true, false);
+        return deep ? FMT_LAUNCH_M(kModeMagic, false, false, true, true, false)
+                    : FMT_LAUNCH_M(kModeMagic, false, false, true, false, false);
     if (!do_hist) return ftz ? FMT_LAUNCH(true, true, false, false) : FMT_LAUNCH(true, false, false, false);
     if (deep) return ftz ? FMT_LAUNCH(true, true, true, true) : FMT_LAUNCH(true, false, true, true);
     return ftz ? FMT_LAUNCH(true, true, true, false) : FMT_LAUNCH(true, false, true, false);
+#undef FMT_LAUNCH_PACK
 #undef FMT_LAUNCH_M
 #undef FMT_LAUNCH
+}
+
+// codes -> fp32: 2 bytes read, 4 written per element.  Eight codes per lane and trip in the vector
+// body (one 128-bit load, two 128-bit stores); the at most 14 elements around it go one per lane.
+template <bool INTEGER, bool VEC>
+__global__ __launch_bounds__(kBlock) void unpack16_kernel(const uint16_t *__restrict__ codes, uint32_t *__restrict__ y,
+                                                          size_t n, size_t head, size_t nvec, QuantParams p)
+{
+    const uint32_t tid = threadIdx.x;
+    if (VEC) {
+        const u32x4 *cv = reinterpret_cast<const u32x4 *>(codes + head);
+        u32x4 *yv = reinterpret_cast<u32x4 *>(y + head);
+        for (size_t i = (size_t)blockIdx.x * kBlock + tid; i < nvec; i += (size_t)gridDim.x * kBlock) {
+            const u32x4 c = __builtin_nontemporal_load(cv + i);
+            u32x4 lo, hi;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                lo[2 * j] = decode_bits<INTEGER>(c[j] & 0xFFFFu, p);
+                lo[2 * j + 1] = decode_bits<INTEGER>(c[j] >> 16, p);
+                hi[2 * j] = decode_bits<INTEGER>(c[2 + j] & 0xFFFFu, p);
+                hi[2 * j + 1] = decode_bits<INTEGER>(c[2 + j] >> 16, p);
+            }
+            __builtin_nontemporal_store(lo, yv + 2 * i);
+            __builtin_nontemporal_store(hi, yv + 2 * i + 1);
+        }
+        if (blockIdx.x == 0 && tid < 64) {
+            const size_t body_end = head + 8 * nvec;
+            const size_t ntail = n - body_end;
+            const size_t idx = tid < head ? tid : body_end + (tid - head);
+            if (tid < head + ntail) y[idx] = decode_bits<INTEGER>(codes[idx], p);
+        }
+    } else {
+        for (size_t i = (size_t)blockIdx.x * kBlock + tid; i < n; i += (size_t)gridDim.x * kBlock)
+            y[i] = decode_bits<INTEGER>(codes[i], p);
+    }
+}
+
+int launch_unpack16(const uint16_t *codes, float *y, size_t n, const QuantParams &p, hipStream_t stream)
+{
+    if (n == 0) return FMT_OK;
+    if (p.mode == kModeMixed) return FMT_ERR_FORMAT;
+    int cus = 0;
+    int rc = device_cu_count(&cus);
+    if (rc != FMT_OK) return rc;
+    // codes before the first 16-byte boundary of the codes, values before the first 16-byte boundary of y
+    const size_t hc = ((16 - (reinterpret_cast<uintptr_t>(codes) & 15)) & 15) / 2;     // 0..7
+    const size_t hy = ((16 - (reinterpret_cast<uintptr_t>(y) & 15)) & 15) / 4;         // 0..3
+    const bool vec = (hc & 3) == hy;                     // then y + hc is 16-byte aligned as well
+    const size_t head = vec ? (hc < n ? hc : n) : 0;
+    const size_t nvec = vec ? (n - head) / 8 : 0;
+    const size_t per_block = (size_t)kBlock * (vec ? 8 : 1);
+    const size_t want = (n + per_block - 1) / per_block;
+    const size_t cap = (size_t)cus * kGridStore;
+    const int grid = (int)(want < cap ? (want ? want : 1) : cap);
+    uint32_t *yo = reinterpret_cast<uint32_t *>(y);
+    const bool integer = p.mode == kModeInteger;
+    if (vec) {
+        if (integer)
+            hipLaunchKernelGGL((unpack16_kernel<true, true>), dim3(grid), dim3(kBlock), 0, stream, codes, yo, n, head, nvec, p);
+        else
+            hipLaunchKernelGGL((unpack16_kernel<false, true>), dim3(grid), dim3(kBlock), 0, stream, codes, yo, n, head, nvec, p);
+    } else {
+        if (integer)
+            hipLaunchKernelGGL((unpack16_kernel<true, false>), dim3(grid), dim3(kBlock), 0, stream, codes, yo, n, head, nvec, p);
+        else
+            hipLaunchKernelGGL((unpack16_kernel<false, false>), dim3(grid), dim3(kBlock), 0, stream, codes, yo, n, head, nvec, p);
+    }
+    FMT_HIP_CHECK(hipGetLastError());
+    return FMT_OK;
 }
 
 }  // namespace fmt

@@ -102,6 +102,24 @@ def test_argument_validation_without_gpu():
     assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, None, base + 8, 2, f, None, -48, None) == -6     # Y over X
     assert lib.fmt_linear(2, 2, 2, base, 2, base + 64, 2, base + 132, base + 128, 2, f, None, -48, None) == -6  # Y over b
     assert lib.fmt_linear(0, 2, 2, None, 2, None, 2, None, None, 2, f, None, -48, None) == 0
+    # packed 16-bit codes: only formats with 1 + e + m <= 16 have them
+    wide = fmt._CFormat(8, 8, 1)
+    assert lib.fmt_pack16(base, base + 64, 4, wide, None, -48, None) == -1
+    assert lib.fmt_unpack16(base, base + 64, 4, wide, None) == -1
+    assert lib.fmt_linear_pack16(2, 2, 2, base, 2, base + 64, 2, None, base + 128, 2, wide, None, -48, None) == -1
+    assert lib.fmt_pack16(base, None, 4, f, None, -48, None) == -2
+    assert lib.fmt_pack16(base, base + 65, 4, f, None, -48, None) == -4            # codes need 2-byte alignment
+    assert lib.fmt_pack16(base, base + 8, 4, f, None, -48, None) == -6             # codes over x
+    assert lib.fmt_pack16(None, None, 0, f, None, -48, None) == 0
+    assert lib.fmt_unpack16(None, base, 4, f, None) == -2
+    assert lib.fmt_unpack16(base + 1, base + 64, 4, f, None) == -4
+    assert lib.fmt_unpack16(base + 4, base, 4, f, None) == -6
+    assert lib.fmt_unpack16(None, None, 0, f, None) == 0
+    assert lib.fmt_linear_pack16(2, 2, 2, base, 2, base + 64, 2, None, None, 2, f, None, -48, None) == -2
+    assert lib.fmt_linear_pack16(2, 4, 2, base, 2, base + 64, 2, None, base + 128, 3, f, None, -48, None) == -3   # ldy < N
+    assert lib.fmt_linear_pack16(2, 2, 2, base, 2, base + 64, 2, None, base + 129, 2, f, None, -48, None) == -4
+    assert lib.fmt_linear_pack16(2, 2, 2, base, 2, base + 64, 2, None, base + 4, 2, f, None, -48, None) == -6     # Y16 over X
+    assert lib.fmt_linear_pack16(0, 2, 2, None, 2, None, 2, None, None, 2, f, None, -48, None) == 0
     # convolutions: geometry first, then pointers
     G = fmt._CConv2d
     ok = G(2, 3, 5, 5, 4, 3, 3, 1, 1, 1, 1)            # X 2x3x5x5 (150), W 4x3x3x3 (108), Y 2x4x5x5 (200)
