@@ -216,6 +216,25 @@ struct PrepOperand {
     Window win;         // win.S != nullptr: single scaled fp16 piece (PS == 0 only)
 };
 
+// An operand as the outlier pass of the single-scaled-piece scheme sees it.
+struct FixOperand {
+    const uint32_t *X;   // the fp32 operand as the caller passed it
+    int64_t ld;
+    int kcontig;
+    Window win;
+};
+
+// What follows the scaled product: the outlier products (flag clear) or the fallback's prepare pass
+// (flag set), in one launch.
+struct TailJob {
+    FixOperand A, B;
+    float *C;
+    int64_t ldc;
+    int M, N;
+    int ftz;
+    const int *flag;
+};
+
 // Offset of tap (r, s) seen from the spatial base (by, bx) = (y*mul + off) inside one h x w plane,
 // or -1 when the tap falls outside the tensor (or, for dgrad, between the strides).  All tensors
 // have fewer than 2^31 elements, so 32-bit offsets suffice.
@@ -346,19 +365,18 @@ __global__ __launch_bounds__(256) void round_split_kernel(const uint32_t *__rest
 // 256 contiguous bytes of a row; transposed input: 64 rows x 32 k, a wave reads 256 contiguous
 // bytes for each k.
 template <int MODE, bool FTZ, int PS>
-__global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p,
-                                                      Gate gate)
+__device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOperand &b, int K, int kblocks,
+                                              const QuantParams &p, unsigned block)
 {
     constexpr int P = pieces_of(PS);
-    if (gate_closed(gate)) return;
     const int tid = threadIdx.x;
     // Each operand owns a run of workgroup ids padded to a multiple of 8.  Consecutive ids go to
     // different XCDs (each with its own L2), so the ids are remapped to give every XCD a contiguous
     // range of rows: a gathered tensor is then read into each L2 once, not eight times.
     const unsigned a_ids = (a.nblocks + 7u) / 8u * 8u;
-    const bool second = blockIdx.x >= a_ids;
+    const bool second = block >= a_ids;
     const PrepOperand &o = second ? b : a;
-    const unsigned lid = blockIdx.x - (second ? a_ids : 0u);
+    const unsigned lid = block - (second ? a_ids : 0u);
     const unsigned per_xcd = (o.nblocks + 7u) / 8u;
     const unsigned bid = (lid % 8u) * per_xcd + lid / 8u;
     if (bid >= o.nblocks) return;
@@ -529,6 +547,14 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
         w[3] = pc[6][q] | (pc[7][q] << 16);
         o.W[unit_vec_index(rb, kb, kblocks, P, q, c, rr)] = w;
     }
+}
+
+template <int MODE, bool FTZ, int PS>
+__global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p,
+                                                      Gate gate)
+{
+    if (gate_closed(gate)) return;
+    prepare_block<MODE, FTZ, PS>(a, b, K, kblocks, p, blockIdx.x);
 }
 
 // product: Aw / Bw are prepared operands (rows padded to a multiple of kRowPad, k to a multiple
@@ -961,10 +987,15 @@ static int make_layout(int M, int N, int K, int P, const OperandSpec &sa, const 
 
 // Prepare + product (+ reduction) of one piece scheme in the workspace at `ws`.  wa / wb: per-row
 // scales and outlier records of the scaled single-piece scheme (PS == 0), or nullptr.
+constexpr unsigned kTailGrid = 2048;
+template <int MODE, bool FTZ>
+__global__ void window_tail_kernel(TailJob job, PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p,
+                                   unsigned prep_blocks);
+
 template <int MODE, bool FTZ, int PS>
 static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
                     const QuantParams &p, hipStream_t stream, const Layout &L, char *ws, const Window *wa,
-                    const Window *wb, Gate gate)
+                    const Window *wb, Gate gate, const TailJob *tail = nullptr)
 {
     const int kblocks = L.kblocks;
     const Plan &plan = L.plan;
@@ -1000,7 +1031,15 @@ static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpe
     const PrepOperand ob = operand(sb, N, L.units_n, Bw, pre_b_buf, wb);
     FMT_HIP_CHECK(hipGetLastError());
     const unsigned prep_grid = (oa.nblocks + 7u) / 8u * 8u + (ob.nblocks + 7u) / 8u * 8u;
-    hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p, gate);
+    if (PS == 2 && tail != nullptr) {
+        // the fallback's prepare pass shares its launch with the outlier pass of the scaled scheme
+        const unsigned grid = prep_grid < kTailGrid ? prep_grid : kTailGrid;
+        hipLaunchKernelGGL((window_tail_kernel<MODE, FTZ>), dim3(grid), dim3(256), 0, stream, *tail, oa, ob, K, kblocks, p,
+                           prep_grid);
+    } else {
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p,
+                           gate);
+    }
     FMT_HIP_CHECK(hipGetLastError());
     const int *Sa = wa ? wa->S : nullptr, *Sb = wb ? wb->S : nullptr;
 #define FMT_PRODUCT(TMV, TNV) \
@@ -1126,13 +1165,6 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
     o.cnt[row] = 0u;
 }
 
-struct FixOperand {
-    const uint32_t *X;   // the fp32 operand as the caller passed it
-    int64_t ld;
-    int kcontig;
-    Window win;
-};
-
 __device__ __forceinline__ uint32_t fix_fetch(const FixOperand &o, int row, int k)
 {
     return o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
@@ -1169,10 +1201,9 @@ constexpr int kWinCap = 8;                        // outliers recorded per row b
 // from the operand if it lies inside its row's window (if not it is an outlier itself and was added
 // with the row).  fp32 fused multiply-add: the product is exact either way, one rounding per
 // accumulation as in the product kernel.
-__global__ __launch_bounds__(256) void outlier_kernel(FixOperand A, FixOperand B, float *__restrict__ C, int64_t ldc, int M,
-                                                      int N, QuantParams p, int ftz, Gate gate)
+__device__ __forceinline__ void outlier_pass(const FixOperand &A, const FixOperand &B, float *__restrict__ C, int64_t ldc,
+                                             int M, int N, const QuantParams &p, int ftz)
 {
-    if (gate_closed(gate)) return;
     const int nda = A.win.dirty[-1], ndb = B.win.dirty[-1];
     const int cn = (N + 255) / 256, cm = (M + 255) / 256;
     const long long row_items = (long long)nda * cn, total = row_items + (long long)ndb * cm;
@@ -1214,6 +1245,20 @@ __global__ __launch_bounds__(256) void outlier_kernel(FixOperand A, FixOperand B
             C[(size_t)i * ldc + j] = c;
         }
     }
+}
+
+// The launch after the scaled product.  Flag clear (no row overflowed its outlier list): the outlier
+// pass.  Flag set: the prepare pass of the two-piece fallback, its blocks walked by a capped grid.
+template <int MODE, bool FTZ>
+__global__ __launch_bounds__(256) void window_tail_kernel(TailJob job, PrepOperand a, PrepOperand b, int K, int kblocks,
+                                                          QuantParams p, unsigned prep_blocks)
+{
+    if (*job.flag == 0) {
+        outlier_pass(job.A, job.B, job.C, job.ldc, job.M, job.N, p, job.ftz);
+        return;
+    }
+    for (unsigned block = blockIdx.x; block < prep_blocks; block += gridDim.x)
+        prepare_block<MODE, FTZ, 2>(a, b, K, kblocks, p, block);
 }
 
 // 0: never, 1: always (when the format allows), 2: by size.  Environment override for tests and tuning.
@@ -1281,9 +1326,8 @@ static int run_window(int M, int N, int K, const OperandSpec &sa, const OperandS
     if (rc != FMT_OK) return rc;
     const FixOperand fa{reinterpret_cast<const uint32_t *>(sa.X), sa.ld, sa.kcontig, wa};
     const FixOperand fb{reinterpret_cast<const uint32_t *>(sb.X), sb.ld, sb.kcontig, wb};
-    hipLaunchKernelGGL(outlier_kernel, dim3(1024), dim3(256), 0, stream, fa, fb, out.C, out.ldc, M, N, p, FTZ ? 1 : 0, fast);
-    FMT_HIP_CHECK(hipGetLastError());
-    return run_core<MODE, FTZ, 2>(M, N, K, sa, sb, out, p, stream, L2, ws2, nullptr, nullptr, slow);
+    const TailJob tail{fa, fb, out.C, out.ldc, M, N, FTZ ? 1 : 0, flag};
+    return run_core<MODE, FTZ, 2>(M, N, K, sa, sb, out, p, stream, L2, ws2, nullptr, nullptr, slow, &tail);
 }
 
 template <int MODE, bool FTZ>
