@@ -246,7 +246,7 @@ def main() -> int:
                     "per multiply) is measured under two_piece for comparison",
         },
         "gemm_config3": {
-            "workload": "config 3, 3 products, 1/6/9/d (forward and wgrad: one scaled fp16 piece; dgrad, K = 256: two bf16 pieces)",
+            "workload": "config 3, 3 products, 1/6/9/d (one scaled fp16 piece each)",
             "value": round(cfg3_tflops, 2), "unit": "TFLOP/s (useful)",
         },
         "roofline": {

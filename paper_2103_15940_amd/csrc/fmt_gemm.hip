@@ -1350,10 +1350,11 @@ static int run_product(int M, int N, int K, const OperandSpec &sa, const Operand
     const int pieces = f.m <= 7 ? 1 : (f.e <= 5 && f.m <= 10 ? 0 : (f.m <= 15 ? 2 : 3));
     const bool ftz = f.denorm == 0;
     // 1/6/9 and its neighbours: one scaled fp16 piece (a quarter of the MFMA work) when the product is
-    // large and deep enough to pay for the extra launches (statistics, outlier pass)
+    // large enough to pay for the extra launches (statistics, tail, the fallback's gated product:
+    // about 15 us against 2.6 us saved per GFLOP), twice as large when k is short
     const int wmode = window_mode();
     if (f.e == 6 && f.m >= 8 && f.m <= 10 && sa.g.kind == kSrcMatrix && sb.g.kind == kSrcMatrix && out.img == 0 &&
-        (wmode == 1 || (wmode == 2 && K >= 1024 && 2.0 * M * N * K >= 4e9)))
+        (wmode == 1 || (wmode == 2 && ((K >= 1024 && 2.0 * M * N * K >= 4e9) || (K >= 128 && 2.0 * M * N * K >= 8e9)))))
         return ftz ? run_window<kModeMagic, true>(M, N, K, sa, sb, out, f, p, stream)
                    : run_window<kModeMagic, false>(M, N, K, sa, sb, out, f, p, stream);
 #define FMT_RUN(MD)                                                                     \
