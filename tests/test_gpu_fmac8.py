@@ -57,7 +57,8 @@ def test_bit_exact_random(fmt, e, m, d, tA, tB):
     assert np.array_equal(oracle.quantize(got, e, m, d).view(np.uint32), got.view(np.uint32))
 
 
-@pytest.mark.parametrize("e,m,d", VARIANTS + [(4, 3, True), (7, 14, False), (3, 5, True)])
+@pytest.mark.parametrize("e,m,d", VARIANTS + [(4, 3, True), (7, 14, False), (3, 5, True), (6, 11, True), (6, 11, False),
+                                             (2, 11, True), (6, 12, True), (7, 9, True)])
 def test_bit_exact_wide_range(fmt, e, m, d):
     """Operands spread over the whole range of the format: accumulator and product exponents far
     apart (the sticky-bit cases), denormal and flushed accumulators, overflowing accumulators."""
@@ -70,6 +71,24 @@ def test_bit_exact_wide_range(fmt, e, m, d):
     nan = np.isnan(ref)
     assert np.array_equal(np.isnan(got), nan)
     assert_bits(np.where(nan, 0, got).astype(np.float32), np.where(nan, 0, ref).astype(np.float32), "wide range")
+
+
+@pytest.mark.parametrize("e,m,d", [(5, 10, True), (6, 9, True), (6, 9, False), (6, 11, True)])
+def test_single_and_double_precision_steps_agree(fmt, e, m, d, monkeypatch):
+    """Formats with e <= 6 and m <= 11 run the fused step in single precision; forced onto the
+    double-precision step they must give the same bits (and both equal the oracle)."""
+    rng = np.random.default_rng(e + m)
+    c = oracle.format_constants(e, m)
+    span = c["Emax"] - c["Emin"]
+    A = workloads.log2_normal((70, 96), (c["Emin"] + c["Emax"]) / 4, span / 5, 0.05, rng)
+    B = workloads.log2_normal((96, 66), (c["Emin"] + c["Emax"]) / 4, span / 5, 0.05, rng)
+    fast, ref = run(fmt, A, B, (e, m, d))
+    monkeypatch.setenv("FMT_FMAC8_F64", "1")
+    slow, _ = run(fmt, A, B, (e, m, d))
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(fast), nan) and np.array_equal(np.isnan(slow), nan)
+    assert np.array_equal(fast[~nan].view(np.uint32), slow[~nan].view(np.uint32))
+    assert np.array_equal(fast[~nan].view(np.uint32), ref[~nan].view(np.uint32))
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (64, 64, 8), (65, 63, 9), (10, 300, 40), (200, 17, 1000)])
