@@ -222,7 +222,15 @@ static int launch_variant(const float *x, void *y, size_t n, size_t head, size_t
     // of a statistics pass pays for clearing and folding its LDS table, so the read-only pass keeps 16
     // per CU (6.3 TB/s) and the fused pass settles in between (64 per CU: 6.07 against 5.77 TB/s).
     const size_t cap = (size_t)cus * (HIST ? (STORE ? kGridFused : kGridPerCU) : kGridStore);
-    int grid = (int)(want < cap ? want : cap);
+    size_t g = want;
+    if (HIST) {
+        // mid-size tensors: at least four tiles per workgroup (one tile does not pay for the table),
+        // but no fewer workgroups than the four per compute unit that the LDS table lets run at once
+        const size_t resident = (size_t)cus * 4;
+        g = (want + 3) / 4;
+        if (g < resident) g = want < resident ? want : resident;
+    }
+    int grid = (int)(g < cap ? g : cap);
     if (grid < 1) grid = 1;
     unsigned long long *partials = nullptr;
     if (HIST) {
