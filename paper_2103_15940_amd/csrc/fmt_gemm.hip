@@ -657,83 +657,106 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 __builtin_amdgcn_global_load_lds((glb_void *)(gb[j] + off), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
     };
 
+    // Operand fragments live in two register sets: while the MFMAs of stage t run on one, the LDS
+    // reads of stage t + 1 fill the other, so that no MFMA waits for LDS latency (a workgroup tile
+    // of 128 x 128 has one wave per SIMD and nothing else to run meanwhile).
+    bf16x8 fa[2][KS][TM][P], fb[2][KS][TN][P];
+    auto read_frags = [&](int buf, int set) __attribute__((always_inline)) {
+        const u32x4 *sa = stage(buf), *sb = sa + VA;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int q = 0; q < P; ++q)
+                    fa[set][kk][i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < P; ++q)
+                    fb[set][kk][j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
+        }
+    };
+    // The barrier is the bare instruction behind the waits it needs (this wave's LDS reads retired,
+    // its stage landed): __syncthreads() would also wait for every load-to-LDS still in flight.
+    auto barrier = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
     if (steps > 0) {
 #pragma unroll
-        for (int t = 0; t < NST - 1; ++t) issue(t, t);
+        for (int t = 0; t < NST; ++t) issue(t, t);
+        constexpr int kWaitFirst = (NST - 1) * (LA + LB);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitFirst & 0xF) | ((kWaitFirst >> 4) << 14));
+        barrier();
+        read_frags(0, 0);
     }
-    // The trips are unrolled over the ring, so that trip t0 + b works on buffer b.  The barrier is the
-    // bare instruction behind the waits it needs (this wave's LDS reads and writes retired, its stage
-    // landed): __syncthreads() would also wait for every load-to-LDS still in flight.
-    // The loop over whole turns of the ring has a single exit (with early exits the compiler falls back
-    // to waiting for all loads at the loop head); the last steps % NST trips follow it.
-    auto trip = [&](int t, int b) __attribute__((always_inline)) {
-        {
-            // stage t has landed once at most the loads of the NST-2 younger stages are in flight
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLanded & 0xF) | ((kWaitLanded >> 4) << 14));
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // ... for every wave; stage t-1 is no longer read
-            const u32x4 *sa = stage(b), *sb = sa + VA;
-            // all operand fragments of the stage first, then the refill of stage t-1's buffer: the
-            // compiler keeps LDS reads and loads-to-LDS in program order, so only this order lets
-            // it thread the global loads between the MFMAs
-            bf16x8 fa[KS][TM][P], fb[KS][TN][P];
+    // Trip t: stage t is in register set `cur`; stage t + 1 (buffer b + 1) is read into the other set
+    // and stage t + NST is loaded into buffer b, which every wave has finished reading once it is past
+    // the barrier.  The trips are unrolled over the ring and the two register sets, so that buffer and
+    // set are compile-time constants, and the loop over whole turns has a single exit (with early
+    // exits the compiler falls back to waiting for all loads at the loop head); the remaining trips
+    // follow it.
+    auto trip = [&](int t, int b, int cur) __attribute__((always_inline)) {
+        // stage t + 1 has landed once at most the loads of the NST-2 younger stages are in flight
+        __builtin_amdgcn_sched_barrier(0);       // MFMAs are not memory operations: without this they drift across the barrier
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLanded & 0xF) | ((kWaitLanded >> 4) << 14));
+        barrier();                               // ... for every wave; and every wave holds stage t in registers
+        read_frags((b + 1) % NST, cur ^ 1);
+        issue(t + NST, b);
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
+        for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int q = 0; q < P; ++q)
-                        fa[kk][i][q] = __builtin_bit_cast(bf16x8, sa[((wm * TM + i) * P + q) * SV + kk * kHalf + lane]);
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int q = 0; q < P; ++q)
-                        fb[kk][j][q] = __builtin_bit_cast(bf16x8, sb[((wn * TN + j) * P + q) * SV + kk * kHalf + lane]);
+                    for (int qa = 0; qa < P; ++qa)
+#pragma unroll
+                        for (int qb = 0; qb < P; ++qb)
+                            acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[cur][kk][i][qa]),
+                                                                                         __builtin_bit_cast(f16x8, fb[cur][kk][j][qb]),
+                                                                                         acc[i][j], 0, 0, 0)
+                                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][kk][i][qa], fb[cur][kk][j][qb], acc[i][j], 0, 0, 0);
+        }
+        // Issue order inside one trip: the next stage's LDS reads, then its global loads, threaded
+        // between the MFMAs so that they issue in the MFMAs' shadow.
+        if constexpr (SCHED) {
+            constexpr int kMfma = TM * TN * P * P * KS, kReads = (TM + TN) * P * KS, kLoads = LA + LB;
+            constexpr int kDsEach = (kReads + kMfma - 1) / kMfma;            // LDS reads behind each of the first MFMAs
+            constexpr int kPairs = (kReads + kDsEach - 1) / kDsEach;
+#pragma unroll
+            for (int r = 0; r < kPairs; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, kDsEach, 0);
             }
-            issue(t + NST - 1, (b + NST - 1) % NST);             // refills the buffer of stage t-1
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int qa = 0; qa < P; ++qa)
-#pragma unroll
-                            for (int qb = 0; qb < P; ++qb)
-                                acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[kk][i][qa]),
-                                                                                             __builtin_bit_cast(f16x8, fb[kk][j][qb]),
-                                                                                             acc[i][j], 0, 0, 0)
-                                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i][qa], fb[kk][j][qb], acc[i][j], 0, 0, 0);
-            }
-            // Issue order inside one trip: a few operand reads up front, then LDS reads and the next
-            // stage's global loads threaded between MFMAs so that they issue in the MFMAs' shadow.
-            if (SCHED) {
-                constexpr int kMfma = TM * TN * P * P * KS, kReads = (TM + TN) * P * KS, kLoads = LA + LB;
-                constexpr int kFront = (TM + TN) * P / 2 > 4 ? (TM + TN) * P / 2 : 4;
-                __builtin_amdgcn_sched_group_barrier(0x100, kFront, 0);
-#pragma unroll
-                for (int r = 0; r < kReads - kFront; ++r) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                }
-                constexpr int kLeft = kMfma - (kReads - kFront);
-                constexpr int kPer = kLeft / (kLoads + 1) > 0 ? kLeft / (kLoads + 1) : 1;
+            constexpr int kLeft = kMfma - kPairs;                            // MFMAs left for the global loads
+            if constexpr (kLeft > kLoads) {
+                constexpr int kPer = kLeft / (kLoads + 1);
 #pragma unroll
                 for (int r = 0; r < kLoads; ++r) {
                     __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
                     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                 }
+            } else if constexpr (kLeft > 0) {
+                constexpr int kEach = (kLoads + kLeft - 1) / kLeft;
+#pragma unroll
+                for (int r = 0; r < kLeft; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, kEach, 0);
+                }
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x020, kLoads, 0);
             }
         }
     };
+    constexpr int kTurn = NST % 2 == 0 ? NST : 2 * NST;      // trips after which buffer and register set repeat
     int t0 = 0;
-    for (; t0 + NST <= steps; t0 += NST) {
+    for (; t0 + kTurn <= steps; t0 += kTurn) {
 #pragma unroll
-        for (int b = 0; b < NST; ++b) trip(t0 + b, b);
+        for (int u = 0; u < kTurn; ++u) trip(t0 + u, u % NST, u & 1);
     }
 #pragma unroll
-    for (int b = 0; b < NST - 1; ++b)
-        if (t0 + b < steps) trip(t0 + b, b);
+    for (int u = 0; u < kTurn - 1; ++u)
+        if (t0 + u < steps) trip(t0 + u, u % NST, u & 1);
     // every load-to-LDS of this wave must have landed before the workgroup's LDS is handed back
     __builtin_amdgcn_s_waitcnt(0x0F70);
 
@@ -867,7 +890,7 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
                     return forced;
         }
     }
-    Plan best{2, 2, 1, 0};
+    Plan best{2, 2, 1, 1};
     double best_t = 1e300;
     for (const auto &sh : shapes) {
         if (lds_bytes(sh.tm, sh.tn, pieces, pipe_ks(pieces), 2) > 160 * 1024) continue;
@@ -883,7 +906,7 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
             // MFMA time on that compute unit (arbitrary units) + start-up / epilogue cost per workgroup
             double t = per_cu * ((double)bm * bn * kb_per / eff + wg_cost * bm * bn / 128.0);
             if (ns > 1) t += split_cost * (double)M * N * (ns + 1) / cus * 8.0;   // partial sums out and back
-            if (t < best_t) { best_t = t; best = Plan{sh.tm, sh.tn, ns, sh.tm * sh.tn > 4}; }
+            if (t < best_t) { best_t = t; best = Plan{sh.tm, sh.tn, ns, 1}; }
         }
     }
     return best;
