@@ -277,6 +277,39 @@ def test_every_tile_shape_and_split(fmt, plan, monkeypatch):
     assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("plan", ["1,1,1", "2,2,1", "4,4,1", "4,2,1", "2,2,2"])
+@pytest.mark.parametrize("f", [(5, 10, True), (6, 9, True), (7, 18, True)])
+def test_every_depth_of_the_stage_ring(fmt, plan, f, monkeypatch):
+    """k from 1 to 21 blocks of 16: the product kernel's ring of stage buffers runs through every
+    number of whole turns and left-over trips, for one, two and three pieces per operand.  Integer
+    operands: the result is exact, so it must equal the oracle's bit for bit."""
+    monkeypatch.setenv("FMT_GEMM_PLAN", plan)
+    monkeypatch.setenv("FMT_GEMM_WINDOW", "0")
+    rng = np.random.default_rng(77)
+    M, N = 150, 140
+    for kb in range(1, 22):
+        K = 16 * kb - (3 if kb % 4 == 0 else 0)                      # some depths with a ragged last block
+        A = rng.integers(-7, 8, (M, K)).astype(np.float32)
+        B = rng.integers(-7, 8, (K, N)).astype(np.float32)
+        got, ref = run(fmt, A, B, f, False, kb % 2 == 1)
+        assert np.array_equal(got, ref), (plan, f, K)
+
+
+def test_every_depth_of_the_stage_ring_scaled_piece(fmt, monkeypatch):
+    """The same through the single scaled fp16 piece of the 1/6/m formats."""
+    monkeypatch.setenv("FMT_GEMM_WINDOW", "1")
+    rng = np.random.default_rng(78)
+    M, N = 150, 140
+    for plan in ["2,2,1", "4,4,1", "1,1,2"]:
+        monkeypatch.setenv("FMT_GEMM_PLAN", plan)
+        for kb in range(1, 22):
+            K = 16 * kb - (5 if kb % 3 == 0 else 0)
+            A = (rng.integers(-7, 8, (M, K)) * 2.0 ** -12).astype(np.float32)
+            B = rng.integers(-7, 8, (K, N)).astype(np.float32)
+            got, ref = run(fmt, A, B, (6, 9, True), kb % 2 == 0, False)
+            assert np.array_equal(got, ref), (plan, K)
+
+
 def test_binary16_denormal_operands(fmt):
     """1/5/10/d operands below 2^-14 (binary16 denormals) times large values: nothing may be
     flushed on the way through the fp16 matrix path; products are small integers times powers of
