@@ -295,31 +295,40 @@ int launch_stream(const float *x, void *y, size_t n, const QuantParams &p, bool 
 #undef FMT_LAUNCH
 }
 
-// codes -> fp32: 2 bytes read, 4 written per element.  Eight codes per lane and trip in the vector
-// body (one 128-bit load, two 128-bit stores); the at most 14 elements around it go one per lane.
+// codes -> fp32: 2 bytes read, 4 written per element.  In the vector body a lane turns four codes (one
+// 64-bit load) into four values (one 128-bit store), four such units per trip, consecutive lanes on
+// consecutive units so that loads and stores of a wave are contiguous; the at most 6 elements around
+// the body go one per lane.
 template <bool INTEGER, bool VEC>
 __global__ __launch_bounds__(kBlock) void unpack16_kernel(const uint16_t *__restrict__ codes, uint32_t *__restrict__ y,
                                                           size_t n, size_t head, size_t nvec, QuantParams p)
 {
     const uint32_t tid = threadIdx.x;
     if (VEC) {
-        const u32x4 *cv = reinterpret_cast<const u32x4 *>(codes + head);
+        const u32x2 *cv = reinterpret_cast<const u32x2 *>(codes + head);
         u32x4 *yv = reinterpret_cast<u32x4 *>(y + head);
-        for (size_t i = (size_t)blockIdx.x * kBlock + tid; i < nvec; i += (size_t)gridDim.x * kBlock) {
-            const u32x4 c = __builtin_nontemporal_load(cv + i);
-            u32x4 lo, hi;
+        constexpr int kU = 4;
+        for (size_t base = (size_t)blockIdx.x * kBlock * kU; base < nvec; base += (size_t)gridDim.x * kBlock * kU) {
+            u32x2 c[kU];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                lo[2 * j] = decode_bits<INTEGER>(c[j] & 0xFFFFu, p);
-                lo[2 * j + 1] = decode_bits<INTEGER>(c[j] >> 16, p);
-                hi[2 * j] = decode_bits<INTEGER>(c[2 + j] & 0xFFFFu, p);
-                hi[2 * j + 1] = decode_bits<INTEGER>(c[2 + j] >> 16, p);
+            for (int k = 0; k < kU; ++k) {
+                const size_t i = base + (size_t)k * kBlock + tid;
+                c[k] = u32x2{0u, 0u};
+                if (i < nvec) c[k] = __builtin_nontemporal_load(cv + i);
             }
-            __builtin_nontemporal_store(lo, yv + 2 * i);
-            __builtin_nontemporal_store(hi, yv + 2 * i + 1);
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                const size_t i = base + (size_t)k * kBlock + tid;
+                u32x4 o;
+                o[0] = decode_bits<INTEGER>(c[k][0] & 0xFFFFu, p);
+                o[1] = decode_bits<INTEGER>(c[k][0] >> 16, p);
+                o[2] = decode_bits<INTEGER>(c[k][1] & 0xFFFFu, p);
+                o[3] = decode_bits<INTEGER>(c[k][1] >> 16, p);
+                if (i < nvec) __builtin_nontemporal_store(o, yv + i);
+            }
         }
         if (blockIdx.x == 0 && tid < 64) {
-            const size_t body_end = head + 8 * nvec;
+            const size_t body_end = head + 4 * nvec;
             const size_t ntail = n - body_end;
             const size_t idx = tid < head ? tid : body_end + (tid - head);
             if (tid < head + ntail) y[idx] = decode_bits<INTEGER>(codes[idx], p);
@@ -337,13 +346,14 @@ int launch_unpack16(const uint16_t *codes, float *y, size_t n, const QuantParams
     int cus = 0;
     int rc = device_cu_count(&cus);
     if (rc != FMT_OK) return rc;
-    // codes before the first 16-byte boundary of the codes, values before the first 16-byte boundary of y
-    const size_t hc = ((16 - (reinterpret_cast<uintptr_t>(codes) & 15)) & 15) / 2;     // 0..7
+    // codes before the first 8-byte boundary of the codes, values before the first 16-byte boundary of y:
+    // both must agree for the vector body
+    const size_t hc = ((8 - (reinterpret_cast<uintptr_t>(codes) & 7)) & 7) / 2;        // 0..3
     const size_t hy = ((16 - (reinterpret_cast<uintptr_t>(y) & 15)) & 15) / 4;         // 0..3
-    const bool vec = (hc & 3) == hy;                     // then y + hc is 16-byte aligned as well
+    const bool vec = hc == hy;
     const size_t head = vec ? (hc < n ? hc : n) : 0;
-    const size_t nvec = vec ? (n - head) / 8 : 0;
-    const size_t per_block = (size_t)kBlock * (vec ? 8 : 1);
+    const size_t nvec = vec ? (n - head) / 4 : 0;
+    const size_t per_block = (size_t)kBlock * (vec ? 16 : 1);
     const size_t want = (n + per_block - 1) / per_block;
     const size_t cap = (size_t)cus * kGridStore;
     const int grid = (int)(want < cap ? (want ? want : 1) : cap);
