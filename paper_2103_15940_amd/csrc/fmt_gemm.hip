@@ -48,6 +48,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kUnitRows = 32;                 // rows per unit (one MFMA fragment)
 constexpr int kUnitK = 32;                    // k per unit (two MFMA steps of 16)
 constexpr int kUnitVec = kUnitRows * kUnitK * 2 / 16;   // 16-byte vectors per unit per piece = 128
+constexpr int kFastRows = 4;                  // groups of 64 rows per workgroup in the fast patch gather (kRowPad = 64 * kFastRows)
 constexpr int kRowPad = 256;                  // prepared operands are padded to a multiple of this many rows
 
 // Rounds one fp32 pattern to the format and splits the result into the 16-bit patterns of its
@@ -391,7 +392,8 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
         row = by * 32 + tid / 8;
         k0 = bx * 64 + (tid % 8) * 8;
     } else {
-        row = by * 64 + tid % 64;
+        // the fast gather takes kFastRows groups of 64 rows per workgroup, the other paths one
+        row = by * 64 * (o.g.fast ? kFastRows : 1) + tid % 64;
         k0 = bx * 32 + (tid / 64) * 8;
     }
     if (k0 >= kblocks * kUnitK) return;      // k-contiguous slabs cover two k-blocks; the last may be half
@@ -402,21 +404,29 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
         // Patches, lanes along positions: which taps (r, s) fall inside the tensor is a per-lane bit
         // mask, the offset of a tap is per-lane base + a term that depends on k alone, and k is
         // the same in the whole wave, so walking the 8 taps is scalar work.
+        // The walk is shared by kFastRows groups of 64 positions (the scalar unit, not the vector unit
+        // or memory, bounds this path), each lane owning one position per group.
         const Gather &g = o.g;
         const int hw = g.th * g.tw;
-        int x, t, y, n;
-        divmod(g.r0, row, t, x);
-        divmod(g.r1, t, n, y);
-        const int by = y * g.mul_y + g.off_y, bx = x * g.mul_x + g.off_x;
-        const int lo_r = g.tap > 0 ? max(0, -by) : max(0, by - g.th + 1), hi_r = g.tap > 0 ? min(g.R, g.th - by) : min(g.R, by + 1);
-        const int lo_s = g.tap > 0 ? max(0, -bx) : max(0, bx - g.tw + 1), hi_s = g.tap > 0 ? min(g.S, g.tw - bx) : min(g.S, bx + 1);
-        const int ns = hi_s - lo_s;
-        const uint32_t mx = ns <= 0 ? 0u : ((ns >= 32 ? 0xFFFFFFFFu : (1u << ns) - 1u) << lo_s);
-        uint32_t mask = 0u;
-        for (int r = 0; r < g.R; ++r)
-            if (r >= lo_r && r < hi_r) mask |= mx << (r * g.S);
-        if (row >= rows) mask = 0u;
-        const int lane_base = n * g.tc * hw + by * g.tw + bx;
+        uint32_t mask[kFastRows];
+        int lane_base[kFastRows];
+#pragma unroll
+        for (int q = 0; q < kFastRows; ++q) {
+            const int rq = row + 64 * q;
+            int x, t, y, n;
+            divmod(g.r0, rq, t, x);
+            divmod(g.r1, t, n, y);
+            const int by = y * g.mul_y + g.off_y, bx = x * g.mul_x + g.off_x;
+            const int lo_r = g.tap > 0 ? max(0, -by) : max(0, by - g.th + 1), hi_r = g.tap > 0 ? min(g.R, g.th - by) : min(g.R, by + 1);
+            const int lo_s = g.tap > 0 ? max(0, -bx) : max(0, bx - g.tw + 1), hi_s = g.tap > 0 ? min(g.S, g.tw - bx) : min(g.S, bx + 1);
+            const int ns = hi_s - lo_s;
+            const uint32_t mx = ns <= 0 ? 0u : ((ns >= 32 ? 0xFFFFFFFFu : (1u << ns) - 1u) << lo_s);
+            uint32_t mq = 0u;
+            for (int r = 0; r < g.R; ++r)
+                if (r >= lo_r && r < hi_r) mq |= mx << (r * g.S);
+            mask[q] = rq < rows ? mq : 0u;
+            lane_base[q] = n * g.tc * hw + by * g.tw + bx;
+        }
         const int ku = __builtin_amdgcn_readfirstlane(k0);
         int s, t2, r, ch;
         divmod(g.k0, ku, t2, s);
@@ -425,12 +435,17 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
         int delta = ch * hw + g.tap * (r * g.tw + s);
         const int zero = g.plane - 1;
         const uint32_t *__restrict__ X2 = X + g.plane;
+        uint32_t f01[kFastRows][8], f2[kFastRows][P >= 3 ? 8 : 1];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const bool ok = (ku + j < K) && ((mask >> rs) & 1u);
-            const uint32_t idx = (uint32_t)(ok ? lane_base + delta : zero);
-            w01[j] = X[idx];
-            if (P >= 3) w2[j] = X2[idx];
+            const bool kin = ku + j < K;
+#pragma unroll
+            for (int q = 0; q < kFastRows; ++q) {
+                const bool ok = kin && ((mask[q] >> rs) & 1u);
+                const uint32_t idx = (uint32_t)(ok ? lane_base[q] + delta : zero);
+                f01[q][j] = X[idx];
+                if (P >= 3) f2[q][j] = X2[idx];
+            }
             ++rs;
             delta += g.tap;
             if (++s == g.S) {
@@ -443,7 +458,25 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
                 }
             }
         }
-        packed = true;
+        // two elements' 16-bit halves into one word with a byte permute
+        const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
+#pragma unroll
+        for (int q = 0; q < kFastRows; ++q) {
+            const int rq = row + 64 * q;
+            const int rb = rq / kUnitRows, rr = rq % kUnitRows;
+#pragma unroll
+            for (int pc = 0; pc < P; ++pc) {
+                u32x4 w;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (pc == 0) w[i] = __builtin_amdgcn_perm(f01[q][2 * i + 1], f01[q][2 * i], 0x05040100u);
+                    if (pc == 1) w[i] = __builtin_amdgcn_perm(f01[q][2 * i + 1], f01[q][2 * i], 0x07060302u);
+                    if (pc == 2) w[i] = __builtin_amdgcn_perm(f2[q][P >= 3 ? 2 * i + 1 : 0], f2[q][P >= 3 ? 2 * i : 0], 0x05040100u);
+                }
+                o.W[unit_vec_index(rb, kb, kblocks, P, pc, c, rr)] = w;
+            }
+        }
+        return;
     } else if (o.g.kind != kSrcMatrix) {
         int idx[8];
         gather8(o, row, k0, K, idx);
@@ -1046,7 +1079,8 @@ static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpe
         o.rows = rows;
         o.kcontig = sp.kcontig;
         o.vec4 = (reinterpret_cast<uintptr_t>(sp.X) & 15) == 0 && sp.ld % 4 == 0;
-        o.nblocks = sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units : (unsigned)kblocks * (units / 2);
+        o.nblocks = sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units
+                               : (unsigned)kblocks * (units / (o.g.fast ? 2 * kFastRows : 2));
         o.win = win ? *win : Window{nullptr, nullptr, nullptr, nullptr, 0, nullptr};
         return o;
     };
