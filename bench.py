@@ -380,6 +380,32 @@ def main() -> int:
                         "linear_ms": round(lin16_ms, 4),
                         "linear_tflops": round(cfg4_flops / 3 / (lin16_ms * 1e-3) / 1e12, 2)}
     del codes, Y16
+    # configurations 1 and 2: cache-resident tensors and small products -- latency-bound, reported as times
+    c1 = workloads.config1()
+    x1 = torch.from_numpy(c1["x"]).to(dev)
+    y1 = torch.empty_like(x1)
+    A1, B1 = torch.from_numpy(c1["A"]).to(dev), torch.from_numpy(c1["B"]).to(dev)
+    C1 = torch.empty((256, 256), dtype=torch.float32, device=dev)
+    c2 = workloads.config2()
+    X2 = torch.from_numpy(c2["X"]).to(dev)
+    W2 = [torch.from_numpy(wl).to(dev) for wl in c2["W"]]
+    acts = [X2] + [torch.rand((X2.shape[0], wl.shape[0]), device=dev) for wl in W2[:-1]]
+    grads = [torch.randn((X2.shape[0], wl.shape[0]), device=dev) * 1e-3 for wl in W2]
+    outs2 = [(torch.empty((a.shape[0], wl.shape[0]), device=dev), torch.empty_like(a), torch.empty_like(wl))
+             for a, wl in zip(acts, W2)]
+
+    def mlp_products():
+        for a, wl, gl, (yo, dxo, dwo) in zip(acts, W2, grads, outs2):
+            fmt.fmt_gemm(a, wl, f169, transB=True, out=yo)          # forward  (batch x in)(out x in)^T
+            fmt.fmt_gemm(gl, wl, f169, out=dxo)                      # dgrad    (batch x out)(out x in)
+            fmt.fmt_gemm(gl, a, f169, transA=True, out=dwo)          # wgrad    (batch x out)^T(batch x in)
+    result["small_configs"] = {
+        "workload": "config 1 (2^20 elements, 256^3 product) and config 2 (MLP 784-1024-1024-10, batch 256: 9 products), "
+                    "1/6/9/d; latency-bound, times per call",
+        "config1_quantize_hist_us": round(timed(lambda: fmt.fmt_quantize(x1, f169, out=y1, hist=hists[0]), 50) * 1e3, 2),
+        "config1_gemm_us": round(timed(lambda: fmt.fmt_gemm(A1, B1, f169, out=C1), 50) * 1e3, 2),
+        "config2_products_us": round(timed(mlp_products, 20) * 1e3, 2),
+    }
     # FMAC-8 accumulation (Algorithm 1): a sequential chain of roundings per output, vector ALUs only
     A8 = torch.randn((2048, 1024), device=dev)
     B8 = torch.randn((1024, 2048), device=dev) * 0.05
