@@ -399,12 +399,25 @@ def main() -> int:
             fmt.fmt_gemm(a, wl, f169, transB=True, out=yo)          # forward  (batch x in)(out x in)^T
             fmt.fmt_gemm(gl, wl, f169, out=dxo)                      # dgrad    (batch x out)(out x in)
             fmt.fmt_gemm(gl, a, f169, transA=True, out=dwo)          # wgrad    (batch x out)^T(batch x in)
+    # the same nine products replayed from a HIP graph (the calls neither allocate nor synchronise once a
+    # first call on the stream has grown the library's scratch, so they can be captured)
+    gstream = torch.cuda.Stream()
+    gstream.wait_stream(torch.cuda.current_stream())
+    mlp_graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(gstream):
+        mlp_products()
+        gstream.synchronize()
+        with torch.cuda.graph(mlp_graph, stream=gstream):
+            mlp_products()
+    torch.cuda.current_stream().wait_stream(gstream)
+    torch.cuda.synchronize()
     result["small_configs"] = {
         "workload": "config 1 (2^20 elements, 256^3 product) and config 2 (MLP 784-1024-1024-10, batch 256: 9 products), "
                     "1/6/9/d; latency-bound, times per call",
         "config1_quantize_hist_us": round(timed(lambda: fmt.fmt_quantize(x1, f169, out=y1, hist=hists[0]), 50) * 1e3, 2),
         "config1_gemm_us": round(timed(lambda: fmt.fmt_gemm(A1, B1, f169, out=C1), 50) * 1e3, 2),
         "config2_products_us": round(timed(mlp_products, 20) * 1e3, 2),
+        "config2_products_graph_replay_us": round(timed(mlp_graph.replay, 20) * 1e3, 2),
     }
     # FMAC-8 accumulation (Algorithm 1): a sequential chain of roundings per output, vector ALUs only
     A8 = torch.randn((2048, 1024), device=dev)

@@ -40,7 +40,10 @@
  *     histogram counts; pre-split GEMM operands).  They are created on first use with
  *     hipMalloc, grow when a larger problem arrives, and live until fmt_release_scratch()
  *     or process exit.  Calls on one stream are serialised by the stream; calls on
- *     different streams use different scratch and may overlap.
+ *     different streams use different scratch and may overlap.  Once a call of the same
+ *     kind and size has run on a stream, further calls on it neither allocate nor
+ *     synchronise (scratch is cleared by kernels, not by memset), so they can be recorded
+ *     into a HIP graph on that stream and replayed.
  *   - Arguments are validated before any GPU call, so argument errors are reported
  *     even on a host without a GPU.  No exception or abort crosses this boundary:
  *     every call returns FMT_OK (0) or a negative fmt_status.

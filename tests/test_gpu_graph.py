@@ -1,0 +1,88 @@
+"""The library's calls can be recorded into a HIP graph (after a first eager call has grown the
+scratch buffers: nothing allocates or synchronises afterwards) and replayed: every replay, with new
+contents in the same input buffers and eager work in between, gives exactly what the eager calls
+give -- statistics included, whose partial records a kernel clears (no memset node in the graph)."""
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def fmt():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_2103_15940_amd as lib
+    return lib
+
+
+def test_graph_replays_match_eager(fmt):
+    dev = torch.device("cuda")
+    f = (6, 9, True)
+    rng = np.random.default_rng(11)
+    n = 3 * 4096 + 77
+    M, N, K = 320, 272, 1088                       # large enough for the single-scaled-piece scheme when forced
+    x = torch.empty(n, device=dev)
+    A = torch.empty((M, K), device=dev)
+    B = torch.empty((N, K), device=dev)
+    bias = torch.empty(N, device=dev)
+    y = torch.empty_like(x)
+    codes = torch.empty(n, dtype=torch.int16, device=dev)
+    C = torch.empty((M, N), device=dev)
+    Y = torch.empty((M, N), device=dev)
+    h1, h2 = fmt.new_hist(dev), fmt.new_hist(dev)
+
+    def fill(seed):
+        r = np.random.default_rng(seed)
+        x.copy_(torch.from_numpy(workloads.log2_normal(n, -14, 6, 0.01, r)))
+        A.copy_(torch.from_numpy(r.standard_normal((M, K)).astype(np.float32)))
+        B.copy_(torch.from_numpy((r.standard_normal((N, K)) * 0.02).astype(np.float32)))
+        bias.copy_(torch.from_numpy(r.standard_normal(N).astype(np.float32)))
+
+    def calls():
+        fmt.fmt_quantize(x, f, out=y, hist=h1)
+        fmt.fmt_pack16(x, f, out=codes)
+        fmt.fmt_gemm(A, B, f, transB=True, out=C)
+        fmt.fmt_linear(A, B, bias, f, out=Y, hist=h2)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (y, codes, C, Y, h1, h2)]
+
+    import os
+    old = os.environ.get("FMT_GEMM_WINDOW")
+    os.environ["FMT_GEMM_WINDOW"] = "1"            # statistics, scaled product, tail and gated kernels all in the graph
+    try:
+        fill(0)
+        calls()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            calls()                                # eager warm-up on the capture stream: scratch is per stream and grown here
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                calls()
+        torch.cuda.current_stream().wait_stream(side)
+        for seed in (1, 2, 3):
+            fill(seed)
+            calls()
+            want = snapshot()
+            for t in (y, codes, C, Y, h1, h2):
+                t.zero_()
+            (A @ B.t()).sum().item()               # unrelated eager work and a synchronisation between replays
+            graph.replay()
+            got = snapshot()
+            for g, w, name in zip(got, want, ("quantize", "codes", "gemm", "linear", "hist", "linear hist")):
+                assert torch.equal(g.view(torch.int32) if g.dtype == torch.float32 else g,
+                                   w.view(torch.int32) if w.dtype == torch.float32 else w), (seed, name)
+    finally:
+        if old is None:
+            os.environ.pop("FMT_GEMM_WINDOW", None)
+        else:
+            os.environ["FMT_GEMM_WINDOW"] = old
