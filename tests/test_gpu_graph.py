@@ -86,3 +86,49 @@ def test_graph_replays_match_eager(fmt):
             os.environ.pop("FMT_GEMM_WINDOW", None)
         else:
             os.environ["FMT_GEMM_WINDOW"] = old
+
+
+def test_overlapping_calls_on_two_streams(fmt):
+    """bench.py issues configuration 4's products round-robin on two streams.  Calls on different
+    streams use different scratch (workspaces, partial statistics, the device flag of the scaled-piece
+    scheme) and may overlap: interleaved on two streams, many times, they must give exactly the
+    results of the same calls issued one after the other."""
+    dev = torch.device("cuda")
+    f = (6, 9, True)
+    rng = np.random.default_rng(5)
+    shapes = [(512, 384, 1024), (300, 520, 1100), (1024, 256, 2048), (257, 129, 1031)]
+    ops = []
+    for (M, N, K) in shapes:
+        A = torch.from_numpy(rng.standard_normal((M, K)).astype(np.float32)).to(dev)
+        B = torch.from_numpy((rng.standard_normal((N, K)) * 0.02).astype(np.float32)).to(dev)
+        x = torch.from_numpy(workloads.log2_normal(M * K, -20, 6, 0.01, rng)).to(dev)
+        ops.append((A, B, x))
+    import os
+    old = os.environ.get("FMT_GEMM_WINDOW")
+    os.environ["FMT_GEMM_WINDOW"] = "1"
+    try:
+        serial = []
+        for (A, B, x) in ops:
+            h = fmt.new_hist(dev)
+            serial.append((fmt.fmt_gemm(A, B, f, transB=True), fmt.fmt_quantize(x, f, hist=h), h))
+        torch.cuda.synchronize()
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for s in streams:
+            s.wait_stream(torch.cuda.current_stream())
+        for rep in range(10):
+            outs = []
+            for i, (A, B, x) in enumerate(ops):
+                s = streams[(i + rep) % 2]
+                with torch.cuda.stream(s):
+                    h = fmt.new_hist(dev)
+                    outs.append((fmt.fmt_gemm(A, B, f, transB=True, stream=s), fmt.fmt_quantize(x, f, hist=h, stream=s), h))
+            torch.cuda.synchronize()
+            for (c0, y0, h0), (c1, y1, h1) in zip(serial, outs):
+                assert torch.equal(c0.view(torch.int32), c1.view(torch.int32)), rep
+                assert torch.equal(y0.view(torch.int32), y1.view(torch.int32)), rep
+                assert torch.equal(h0, h1), rep
+    finally:
+        if old is None:
+            os.environ.pop("FMT_GEMM_WINDOW", None)
+        else:
+            os.environ["FMT_GEMM_WINDOW"] = old
