@@ -197,6 +197,7 @@ struct Gather {
     // per-lane bit mask and the element offset splits into a per-lane and a per-k (scalar) part;
     // element plane-1 of the rounded tensor is a zero that out-of-range taps read
     int fast;
+    // fast == 2: the same for the transposed patches (rows = taps, k = positions; see gather_taps)
     // divisors of the index decompositions: rows by (r0 inner, r1 outer), k by (k0 inner, k1 outer)
     FastDiv r0, r1, k0, k1;
 };
@@ -361,11 +362,101 @@ __global__ __launch_bounds__(256) void round_split_kernel(const uint32_t *__rest
     }
 }
 
+// Transposed patches (wgrad: rows = taps (ch, r, s), k = positions (n, y, x)), pre-rounded tensor.
+// A workgroup takes one unit of 32 taps and 256 positions, one position per lane: which taps fall
+// inside the tensor is a per-lane bit mask and the walk over the taps is scalar work, exactly as in
+// the forward gather; what differs is the output, which wants 8 consecutive positions of ONE tap in
+// a lane.  Each wave therefore passes its 8 taps x 64 positions through a tile of its own in LDS and
+// reads them back transposed (rows padded to 72 words against bank conflicts).
+template <int P>
+__device__ __forceinline__ void gather_taps(const PrepOperand &o, unsigned bid, int K, int kblocks)
+{
+    constexpr int NW = (P + 1) / 2;                    // 32-bit word planes per element
+    __shared__ uint32_t tile[4][NW][8][72];
+    const Gather &g = o.g;
+    const uint32_t *__restrict__ X = o.X;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ngroups = (kblocks + 7) / 8;
+    const int pg = (int)(bid % (unsigned)ngroups), rb = (int)(bid / (unsigned)ngroups);
+    const int hw = g.th * g.tw;
+    const int pos = pg * 256 + tid;
+    int x, t, y, n;
+    divmod(g.k0, pos, t, x);
+    divmod(g.k1, t, n, y);
+    const int by = y * g.mul_y + g.off_y, bx = x * g.mul_x + g.off_x;
+    const int lo_r = max(0, -by), hi_r = min(g.R, g.th - by);
+    const int lo_s = max(0, -bx), hi_s = min(g.S, g.tw - bx);
+    const int ns = hi_s - lo_s;
+    const uint32_t mx = ns <= 0 ? 0u : ((ns >= 32 ? 0xFFFFFFFFu : (1u << ns) - 1u) << lo_s);
+    uint32_t mask = 0u;
+    for (int r = 0; r < g.R; ++r)
+        if (r >= lo_r && r < hi_r) mask |= mx << (r * g.S);
+    if (pos >= K) mask = 0u;
+    const int lane_base = n * g.tc * hw + by * g.tw + bx;
+    const int zero = g.plane - 1;
+    const int gi = lane >> 3, li = lane & 7;           // after the transpose: positions gi*8 .. gi*8+7 of tap li
+    const int pb = pg * 256 + wave * 64 + gi * 8;       // first of this lane's 8 positions
+    const int kb = pb / kUnitK, c = (pb % kUnitK) / 8;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int tap0 = rb * 32 + pass * 8;           // the same in the whole workgroup
+        int s, t2, r, ch;
+        divmod(g.r0, tap0, t2, s);
+        divmod(g.r1, t2, ch, r);
+        int rs = r * g.S + s;
+        int delta = ch * hw + r * g.tw + s;
+        uint32_t w[NW][8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool ok = tap0 + j < o.rows && ((mask >> rs) & 1u);
+            const uint32_t idx = (uint32_t)(ok ? lane_base + delta : zero);
+#pragma unroll
+            for (int q = 0; q < NW; ++q) w[q][j] = X[(size_t)q * g.plane + idx];
+            ++rs;
+            ++delta;
+            if (++s == g.S) {
+                s = 0;
+                delta += g.tw - g.S;
+                if (++r == g.R) {
+                    r = 0;
+                    rs = 0;
+                    delta += hw - g.R * g.tw;
+                }
+            }
+        }
+        __syncthreads();                               // the previous pass's tile has been read
+#pragma unroll
+        for (int q = 0; q < NW; ++q)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) tile[wave][q][j][lane] = w[q][j];
+        __syncthreads();
+        uint32_t v[NW][8];
+#pragma unroll
+        for (int q = 0; q < NW; ++q)
+#pragma unroll
+            for (int m = 0; m < 8; ++m) v[q][m] = tile[wave][q][li][gi * 8 + m];
+        if (kb < kblocks) {
+            const int rr = pass * 8 + li;
+#pragma unroll
+            for (int pc = 0; pc < P; ++pc) {
+                u32x4 out;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t hi = v[pc / 2][2 * i + 1], lo = v[pc / 2][2 * i];
+                    out[i] = __builtin_amdgcn_perm(hi, lo, (pc & 1) ? 0x07060302u : 0x05040100u);
+                }
+                o.W[unit_vec_index(rb, kb, kblocks, P, pc, c, rr)] = out;
+            }
+        }
+    }
+}
+
 // prepare: both operands of a product in one launch (workgroups [0, a.nblocks) take op(A), the
 // rest op(B)).  k-contiguous input: a workgroup takes 32 rows x 64 k, 8 neighbouring lanes read
 // 256 contiguous bytes of a row; transposed input: 64 rows x 32 k, a wave reads 256 contiguous
 // bytes for each k.
-template <int MODE, bool FTZ, int PS>
+// TAPS: one of the operands may take gather_taps (whose LDS tile and barriers the other launches do
+// not pay for).
+template <int MODE, bool FTZ, int PS, bool TAPS = false>
 __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOperand &b, int K, int kblocks,
                                               const QuantParams &p, unsigned block)
 {
@@ -381,6 +472,12 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
     const unsigned per_xcd = (o.nblocks + 7u) / 8u;
     const unsigned bid = (lid % 8u) * per_xcd + lid / 8u;
     if (bid >= o.nblocks) return;
+    if constexpr (TAPS) {
+        if (o.g.fast == 2) {                 // block-uniform: every thread takes part in its barriers
+            gather_taps<P>(o, bid, K, kblocks);
+            return;
+        }
+    }
     const uint32_t *__restrict__ X = o.X;
     const int64_t ld = o.ld;
     const int rows = o.rows;
@@ -393,14 +490,14 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
         k0 = bx * 64 + (tid % 8) * 8;
     } else {
         // the fast gather takes kFastRows groups of 64 rows per workgroup, the other paths one
-        row = by * 64 * (o.g.fast ? kFastRows : 1) + tid % 64;
+        row = by * 64 * (o.g.fast == 1 ? kFastRows : 1) + tid % 64;
         k0 = bx * 32 + (tid / 64) * 8;
     }
     if (k0 >= kblocks * kUnitK) return;      // k-contiguous slabs cover two k-blocks; the last may be half
     uint32_t v[8];
     uint32_t w01[8], w2[P >= 3 ? 8 : 1];     // pre-rounded source: pieces 0|1 packed per element, piece 2
     bool packed = false;
-    if (o.g.fast) {
+    if (o.g.fast == 1) {
         // Patches, lanes along positions: which taps (r, s) fall inside the tensor is a per-lane bit
         // mask, the offset of a tap is per-lane base + a term that depends on k alone, and k is
         // the same in the whole wave, so walking the 8 taps is scalar work.
@@ -582,12 +679,12 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
     }
 }
 
-template <int MODE, bool FTZ, int PS>
+template <int MODE, bool FTZ, int PS, bool TAPS>
 __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p,
                                                       Gate gate)
 {
     if (gate_closed(gate)) return;
-    prepare_block<MODE, FTZ, PS>(a, b, K, kblocks, p, blockIdx.x);
+    prepare_block<MODE, FTZ, PS, TAPS>(a, b, K, kblocks, p, blockIdx.x);
 }
 
 // product: Aw / Bw are prepared operands (rows padded to a multiple of kRowPad, k to a multiple
@@ -1072,15 +1169,18 @@ static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpe
             o.X = pre_buf;
             o.g.pre = 1;
             o.g.plane = n + 1;
-            o.g.fast = o.g.kind == kSrcPatchRows && !sp.kcontig && o.g.den_y == 1 && o.g.den_x == 1 && o.g.R * o.g.S <= 32;
+            const bool simple = o.g.den_y == 1 && o.g.den_x == 1 && o.g.R * o.g.S <= 32;
+            o.g.fast = simple && o.g.kind == kSrcPatchRows && !sp.kcontig ? 1
+                       : simple && o.g.kind == kSrcPatchK && sp.kcontig && o.g.tap > 0 ? 2 : 0;
         }
         o.W = W;
         o.ld = sp.ld;
         o.rows = rows;
         o.kcontig = sp.kcontig;
         o.vec4 = (reinterpret_cast<uintptr_t>(sp.X) & 15) == 0 && sp.ld % 4 == 0;
-        o.nblocks = sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units
-                               : (unsigned)kblocks * (units / (o.g.fast ? 2 * kFastRows : 2));
+        o.nblocks = o.g.fast == 2 ? (unsigned)((kblocks + 7) / 8) * units            // 32 taps x 256 positions each
+                    : sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units
+                                 : (unsigned)kblocks * (units / (o.g.fast ? 2 * kFastRows : 2));
         o.win = win ? *win : Window{nullptr, nullptr, nullptr, nullptr, 0, nullptr};
         return o;
     };
@@ -1094,8 +1194,12 @@ static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpe
         hipLaunchKernelGGL((window_tail_kernel<MODE, FTZ>), dim3(grid), dim3(256), 0, stream, *tail, oa, ob, K, kblocks, p,
                            prep_grid);
     } else {
-        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p,
-                           gate);
+        if (oa.g.fast == 2 || ob.g.fast == 2)
+            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS, true>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K,
+                               kblocks, p, gate);
+        else
+            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS, false>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K,
+                               kblocks, p, gate);
     }
     FMT_HIP_CHECK(hipGetLastError());
     const int *Sa = wa ? wa->S : nullptr, *Sb = wb ? wb->S : nullptr;
