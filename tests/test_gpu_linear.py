@@ -243,3 +243,44 @@ def test_mlp_forward_config2(fmt):
         assert_hist(fmt.hist_to_dict(h), To, (e, m, d), "layer %d" % li)
         A_ref = np.maximum(Yo, 0)
         act = torch.clamp_min(Y, 0)
+
+
+def test_config4_full_size_sampled(fmt):
+    """Configuration 4's QKV layer (4096 tokens, 1024 -> 3072) at full size, the shape bench.py times
+    (the product goes through the single scaled fp16 piece): 4000 sampled outputs of fmt_linear and of
+    fmt_linear_pack16 against the oracle's fp64-accumulated layer, each within one step of the format
+    as in the test above; the statistics cover all M*N values."""
+    e, m, d = 6, 9, True
+    layer = workloads.config4()["layers"][0]
+    X, W = layer["X"], layer["W"]
+    M, K = X.shape
+    N = W.shape[0]
+    rng = np.random.default_rng(44)
+    b = (rng.standard_normal(N) * 0.05).astype(np.float32)
+    rows, cols = rng.integers(0, M, 4000), rng.integers(0, N, 4000)
+    acc = oracle.gemm_sampled(X, W, rows, cols, e, m, d, transB=True)
+    Yo, _ = oracle.linear_epilogue(acc[None, :], b[cols], e, m, d)
+    Yo = Yo[0]
+    h = fmt.new_hist(torch.device("cuda"))
+    Xd, Wd, bd = dev(X), dev(W), dev(b)
+    Y = fmt.fmt_linear(Xd, Wd, bd, (e, m, d), hist=h, exp_lo=EXP_LO)
+    C = fmt.fmt_linear_pack16(Xd, Wd, bd, (e, m, d))
+    torch.cuda.synchronize()
+    Yh = Y.cpu().numpy()
+    got = Yh[rows, cols]
+    c = oracle.format_constants(e, m)
+
+    def step_at(v):
+        mag = np.maximum(np.abs(v.astype(np.float64)), float(c["minN"]))
+        return np.exp2(np.floor(np.log2(mag)) - m)
+
+    bound = 2 * step_at(acc) + 2 * step_at(Yo)
+    diff = np.abs(got.astype(np.float64) - Yo.astype(np.float64))
+    assert np.all(diff <= bound * (1 + 1e-12))
+    assert np.count_nonzero(got != Yo) / got.size < 0.03
+    # every output is a value of the format, and the packed entry point stores exactly its code
+    assert np.array_equal(oracle.quantize(Yh, e, m, d).view(np.uint32), Yh.view(np.uint32))
+    assert np.array_equal(C.cpu().numpy().view(np.uint16), oracle.pack16(Yh, e, m, True))
+    hd = fmt.hist_to_dict(h)
+    assert int(hd["total"]) == M * N
+    assert sum(int(hd[k]) for k in ("zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")) == M * N
