@@ -10,7 +10,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfmt.so")
 SOURCES = ["fmt_api.hip", "fmt_stream.hip", "fmt_gemm.hip", "fmt_fmac8.hip", "fmt_linear.hip", "fmt_dls.hip"]
-# packed-fp32 instructions are kept out of the generated code on purpose
+# packed-fp32 instructions (v_pk_add_f32 and friends) are kept out of the generated code on purpose:
+# the rounding relies on every fp32 addition being one correctly rounded scalar operation
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
