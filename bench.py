@@ -11,13 +11,15 @@ One "step" is one pass of the whole hot path over one batch of synthetic, paper-
                                      1/6/9/d: for each of the four linear layers (QKV, attention
                                      output, FFN1, FFN2) fused quantize + histogram of X, W and
                                      dY, then forward (NT), dgrad (NN) and wgrad (TN): 12 products,
-                                     309 GFLOP, issued round-robin on two side streams (they are
-                                     independent; one product's operand preparation overlaps
-                                     another's MFMA kernel)
+                                     309 GFLOP
   conv section (configuration 3)     the ResNet-style 3x3 conv as im2col GEMM in 1/6/9/d:
                                      fused quantize + histogram of X_col, W and dY, then the
                                      forward, dgrad and wgrad products (M=12544, N=256, K=2304
                                      and permutations, 14.8 GFLOP each)
+
+The calls inside the configuration 4 and configuration 3 sections are independent of each other and
+are issued round-robin on three side streams (--gemm-streams): one product's operand preparation
+overlaps another's MFMA kernel.  The stream section runs on one stream.
 
 `value` is the quantize+histogram HBM rate of the stream section (GB/s, algorithmic bytes over
 the section's event-timed duration); the GEMM section's useful TFLOP/s and its MFMA fraction are
@@ -54,8 +56,8 @@ def main() -> int:
                     help="also run three plain device-to-device copies of the stream tensor before the warm-up: "
                          "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
-    ap.add_argument("--gemm-streams", type=int, default=2,
-                    help="side streams the 12 independent products of configuration 4 are spread over")
+    ap.add_argument("--gemm-streams", type=int, default=3,
+                    help="side streams the independent calls of the configuration 4 and 3 sections are spread over")
     ap.add_argument("--gemm", default=None, metavar="M,N,K[,transA,transB[,e,m,d]]",
                     help="profiling aid: run only fmt_gemm on one N(0,1) problem of this shape (default NN, 1/6/9/d), "
                          "--steps times after --warmup untimed calls, print its time and exit")
@@ -147,38 +149,45 @@ def main() -> int:
         for i, f in enumerate(variants):                                     # configuration 5
             fmt.fmt_quantize(x, f, out=y, hist=hists[i])
         mark()
+
+        # Independent calls of one section go round-robin onto side streams (each stream has its own
+        # library scratch): the HBM-bound operand preparation of one product overlaps the MFMA-bound
+        # kernel of another, and the small kernels between the large ones (statistics, sums of partial
+        # records) stop being gaps.  The section ends when every side stream has been joined.
+        def fan_out(calls):
+            fork = ev()
+            fork.record()
+            for j, call in enumerate(calls):
+                st_ = side[j % len(side)]
+                if j < len(side):
+                    st_.wait_event(fork)
+                call(st_)
+            for st_ in side[:min(len(side), len(calls))]:
+                join = ev()
+                join.record(st_)
+                torch.cuda.current_stream().wait_event(join)
+
+        q4 = []
         for L in layers:                                                     # configuration 4, quantize
-            fmt.fmt_quantize(L["X"], f169, out=L["Xq"], hist=L["h"][0])
-            fmt.fmt_quantize(L["W"], f169, out=L["Wq"], hist=L["h"][1])
-            fmt.fmt_quantize(L["dY"], f169, out=L["dYq"], hist=L["h"][2])
+            for src, dst, hi in (("X", "Xq", 0), ("W", "Wq", 1), ("dY", "dYq", 2)):
+                q4.append(lambda st_, L=L, src=src, dst=dst, hi=hi:
+                          fmt.fmt_quantize(L[src], f169, out=L[dst], hist=L["h"][hi], stream=st_))
+        fan_out(q4)
         mark()
-        # configuration 4, products: the 12 products are independent of each other, so they go
-        # round-robin onto side streams (each stream has its own library scratch) and the HBM-bound
-        # operand preparation of one product overlaps the MFMA-bound kernel of another
-        fork = ev()
-        fork.record()
-        jobs = []
+        g4 = []                                                              # configuration 4, products
         for L in layers:
-            jobs.append((L["Xq"], L["Wq"], False, True, L["Y"]))              # Y  = X W^T
-            jobs.append((L["dYq"], L["Wq"], False, False, L["dX"]))           # dX = dY W
-            jobs.append((L["dYq"], L["Xq"], True, False, L["dW"]))            # dW = dY^T X
-        for j, (A_, B_, tA_, tB_, C_) in enumerate(jobs):
-            st_ = side[j % len(side)]
-            if j < len(side):
-                st_.wait_event(fork)
-            fmt.fmt_gemm(A_, B_, f169, transA=tA_, transB=tB_, out=C_, stream=st_)
-        for st_ in side:
-            join = ev()
-            join.record(st_)
-            torch.cuda.current_stream().wait_event(join)
+            g4.append(lambda st_, L=L: fmt.fmt_gemm(L["Xq"], L["Wq"], f169, transB=True, out=L["Y"], stream=st_))     # Y  = X W^T
+            g4.append(lambda st_, L=L: fmt.fmt_gemm(L["dYq"], L["Wq"], f169, out=L["dX"], stream=st_))                # dX = dY W
+            g4.append(lambda st_, L=L: fmt.fmt_gemm(L["dYq"], L["Xq"], f169, transA=True, out=L["dW"], stream=st_))   # dW = dY^T X
+        fan_out(g4)
         mark()
-        fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6])              # configuration 3
-        fmt.fmt_quantize(w, f169, out=w_q, hist=hists[7])
-        fmt.fmt_quantize(dy, f169, out=dy_q, hist=hists[8])
+        fan_out([lambda st_: fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6], stream=st_),       # configuration 3
+                 lambda st_: fmt.fmt_quantize(w, f169, out=w_q, hist=hists[7], stream=st_),
+                 lambda st_: fmt.fmt_quantize(dy, f169, out=dy_q, hist=hists[8], stream=st_)])
         mark()
-        fmt.fmt_gemm(xcol_q, w_q, f169, transB=True, out=out_fwd)            # Y    = X_col W^T
-        fmt.fmt_gemm(dy_q, w_q, f169, out=out_dgrad)                         # dX   = dY W
-        fmt.fmt_gemm(dy_q, xcol_q, f169, transA=True, out=out_wgrad)         # dW   = dY^T X_col
+        fan_out([lambda st_: fmt.fmt_gemm(xcol_q, w_q, f169, transB=True, out=out_fwd, stream=st_),     # Y  = X_col W^T
+                 lambda st_: fmt.fmt_gemm(dy_q, w_q, f169, out=out_dgrad, stream=st_),                  # dX = dY W
+                 lambda st_: fmt.fmt_gemm(dy_q, xcol_q, f169, transA=True, out=out_wgrad, stream=st_)])  # dW = dY^T X_col
         mark()
         if record is not None:
             record.append(marks)
@@ -232,6 +241,7 @@ def main() -> int:
             "stream_passes": len(variants),
             "config4_gemm_gflop": round(cfg4_flops / 1e9, 1),
             "config3_gemm_shape": [M, N, K],
+            "side_streams": len(side),
         },
         "sections_ms": {"config5_stream": round(stream_ms, 4), "config4_quantize": round(cfg4_q_ms, 4),
                         "config4_gemms": round(cfg4_gemm_ms, 4), "config3_quantize": round(cfg3_q_ms, 4),
