@@ -123,3 +123,20 @@ def test_mlp_layer_shapes(fmt):
     for f in [(6, 9, True), (5, 10, True)]:
         got, ref = run(fmt, cfg["X"], cfg["W"][0].T.copy(), f)
         assert_bits(got, ref, "mlp layer 1 %s" % (f,))
+
+
+@pytest.mark.parametrize("f", [(6, 9, True), (5, 10, False)])
+def test_bench_size_sampled(fmt, f):
+    """The size the bench times (2048 x 2048 x 1024): every output is its own chain of K fused steps,
+    so the oracle run on 48 sampled rows of A and 48 sampled columns of B gives those 48 x 48 outputs."""
+    M, N, K = 2048, 2048, 1024
+    rng = np.random.default_rng(17)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    C = fmt.fmt_gemm_fmac8(dev(A), dev(B), f)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([rng.integers(0, M, 44), [0, 1, M - 2, M - 1]]))
+    cols = np.unique(np.concatenate([rng.integers(0, N, 44), [0, 1, N - 2, N - 1]]))
+    ref = oracle.gemm_fmac8(np.ascontiguousarray(A[rows]), np.ascontiguousarray(B[:, cols]), f[0], f[1], f[2])
+    got = C.cpu().numpy()[np.ix_(rows, cols)]
+    assert_bits(np.ascontiguousarray(got), ref, "sampled %s" % (f,))
