@@ -140,3 +140,22 @@ def test_bench_size_sampled(fmt, f):
     ref = oracle.gemm_fmac8(np.ascontiguousarray(A[rows]), np.ascontiguousarray(B[:, cols]), f[0], f[1], f[2])
     got = C.cpu().numpy()[np.ix_(rows, cols)]
     assert_bits(np.ascontiguousarray(got), ref, "sampled %s" % (f,))
+
+
+def test_operand_of_more_than_2_to_the_32_elements(fmt):
+    """A is (2^22 + 70) x 1024 (16 GiB), B 1024 x 8: sampled rows bit for bit against the oracle."""
+    M, K, N = (1 << 22) + 70, 1024, 8
+    f = (6, 9, True)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    A = torch.randn((M, K), device="cuda", generator=g)
+    B = torch.randn((K, N), device="cuda", generator=g) * 0.05
+    C = fmt.fmt_gemm_fmac8(A, B, f)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    edge = [(1 << 31) // K, (1 << 32) // K]
+    rows = np.unique(np.concatenate([np.arange(8), np.arange(M - 72, M), rng.integers(0, M, 60)] +
+                                    [np.arange(r - 4, r + 4) for r in edge]))
+    rows_d = torch.from_numpy(rows).cuda()
+    ref = oracle.gemm_fmac8(A[rows_d].cpu().numpy(), B.cpu().numpy(), *f)
+    assert_bits(C[rows_d].cpu().numpy(), ref, "sampled rows, M*K > 2^32")

@@ -328,3 +328,58 @@ def test_binary16_denormal_operands(fmt):
     v = v[np.isfinite(v)].reshape(-1, 64)[:960]
     got, ref = run(fmt, v, np.eye(64, dtype=np.float32), (5, 10, True))
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+def _device_operand(rows, cols, seed, scale=1.0):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.randn((rows, cols), device="cuda", generator=g) * scale
+
+
+@pytest.mark.parametrize("f", [(6, 9, True), (8, 7, True)])
+@pytest.mark.parametrize("tA", [False, True])
+def test_operand_of_more_than_2_to_the_32_elements(fmt, f, tA):
+    """op(A) is (2^22 + 70) x 1024 (16 GiB, element offsets beyond 32 bits) in both storage orders, B is
+    1024 x 16; operands are drawn on the device and the oracle computes sampled rows of the result from
+    the same values (first and last rows, rows around the 2^31- and 2^32-element offsets, random rows)."""
+    M, K, N = (1 << 22) + 70, 1024, 16
+    A = _device_operand(K, M, 21) if tA else _device_operand(M, K, 21)
+    B = _device_operand(K, N, 22, 0.05)
+    C = fmt.fmt_gemm(A, B, f, transA=tA)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    edge = [(1 << 31) // K, (1 << 32) // K]
+    rows = np.unique(np.concatenate([np.arange(40), np.arange(M - 80, M), rng.integers(0, M, 300)] +
+                                    [np.arange(r - 20, r + 20) for r in edge]))
+    rows_d = torch.from_numpy(rows).cuda()
+    A_rows = (A[:, rows_d].T if tA else A[rows_d]).contiguous().cpu().numpy()
+    ref = oracle.gemm(A_rows, B.cpu().numpy(), *f)
+    got = C[rows_d].cpu().numpy()
+    assert rel_fro(got, ref) <= TOL
+    # per sampled row as well: a misplaced row would hide in the norm of 500 good ones
+    err = np.linalg.norm(got.astype(np.float64) - ref, axis=1) / np.linalg.norm(ref.astype(np.float64), axis=1)
+    assert err.max() <= 1e-4, (rows[err.argmax()], err.max())
+    assert bool(torch.isfinite(C).all())
+
+
+def test_result_of_more_than_2_to_the_32_elements(fmt):
+    """C is 65600 x 65600 (16 GiB) with K = 64: output offsets beyond 32 bits.  Sampled outputs against the
+    oracle, around the rows where the offset passes 2^31 and 2^32 elements and at the far corner."""
+    M = N = 65600
+    K = 64
+    f = (6, 9, True)
+    A = _device_operand(M, K, 31)
+    B = _device_operand(N, K, 32, 0.05)
+    C = fmt.fmt_gemm(A, B, f, transB=True)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(6)
+    edge = [(1 << 31) // N, (1 << 32) // N]
+    rows = np.unique(np.concatenate([np.arange(8), np.arange(M - 8, M), rng.integers(0, M, 40)] +
+                                    [np.arange(r - 2, r + 3) for r in edge]))
+    cols = np.unique(np.concatenate([np.arange(8), np.arange(N - 8, N), rng.integers(0, N, 100)]))
+    rows_d, cols_d = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    ref = oracle.gemm(A[rows_d].cpu().numpy(), B[cols_d].cpu().numpy(), *f, transB=True)
+    got = C[rows_d][:, cols_d].cpu().numpy()
+    assert rel_fro(got, ref) <= TOL
+    err = np.abs(got.astype(np.float64) - ref) / (np.abs(ref) + 1e-3 * np.abs(ref).mean())
+    assert err.max() <= 1e-3, err.max()

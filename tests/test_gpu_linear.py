@@ -284,3 +284,31 @@ def test_config4_full_size_sampled(fmt):
     hd = fmt.hist_to_dict(h)
     assert int(hd["total"]) == M * N
     assert sum(int(hd[k]) for k in ("zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")) == M * N
+
+
+def test_output_of_more_than_2_to_the_32_elements(fmt):
+    """Y is 65600 x 65600 (16 GiB; element offsets beyond 32 bits) with K = 64, exact operands: sampled
+    rows (first, last, around the 2^31- and 2^32-element offsets, random) bit for bit against the oracle,
+    for the fp32 output and for the 16-bit codes; the statistics count every output once."""
+    M = N = 65600
+    K = 64
+    f = (6, 9, True)
+    rng = np.random.default_rng(77)
+    X, W, b = exact_operands(rng, M, N, K, 6, 9)
+    Xd, Wd, bd = dev(X), dev(W), dev(b)
+    edge = [(1 << 31) // N, (1 << 32) // N]
+    rows = np.unique(np.concatenate([np.arange(4), np.arange(M - 4, M), rng.integers(0, M, 24)] +
+                                    [np.arange(r - 2, r + 3) for r in edge]))
+    rows_d = torch.from_numpy(rows).cuda()
+    Yref, _ = oracle.linear(X[rows], W, b, *f)
+    hist = fmt.new_hist(torch.device("cuda"))
+    Y = fmt.fmt_linear(Xd, Wd, bd, f, hist=hist, exp_lo=EXP_LO)
+    torch.cuda.synchronize()
+    assert_bits(Y[rows_d].cpu().numpy(), Yref, "fp32 output, M*N > 2^32")
+    h = fmt.hist_to_dict(hist)
+    assert h["total"] == M * N == sum(h[k] for k in fmt.CLASS_NAMES[1:])
+    del Y
+    C = fmt.fmt_linear_pack16(Xd, Wd, bd, f)
+    torch.cuda.synchronize()
+    got = C[rows_d].cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, oracle.pack16(Yref, 6, 9, True)), "16-bit codes, M*N > 2^32"

@@ -251,3 +251,46 @@ def test_config5_full_size(fmt):
         assert np.array_equal(h["bins"], want_hist["bins"])
         assert int(h["bins"].sum()) == n - h["zero"] - h["nan"]
         assert h["zero"] == want_hist["zero"] and h["nan"] == want_hist["nan"] and h["inf"] == want_hist["inf"]
+
+
+def test_more_than_2_to_the_32_elements(fmt):
+    """A tensor whose element indices do not fit 32 bits (2^32 + 12293 elements, 16 GiB): the tensor is
+    a 2^24-element chunk repeated, so the statistics are 256 times the chunk's plus those of the ragged
+    rest, and the values are checked on samples around every power-of-two index boundary and at the
+    end.  Fused fp32 pass, statistics-only pass and the 16-bit code pass."""
+    chunk_n = 1 << 24
+    tail = 3 * 4096 + 5
+    n = (1 << 32) + tail
+    chunk = mixed(chunk_n, 1234)
+    xd = dev(chunk).repeat(257)[:n]
+    assert xd.numel() == n
+    hc, ht = oracle.histogram(chunk, 6, 9), oracle.histogram(chunk[:tail], 6, 9)
+    want = {k: 256 * hc[k] + ht[k] for k in fmt.CLASS_NAMES}
+    want["bins"] = 256 * np.asarray(hc["bins"]) + np.asarray(ht["bins"])
+    # sample positions: both ends, around 2^31 and 2^32, and random ones
+    rng = np.random.default_rng(9)
+    near = np.concatenate([np.arange(-2048, 2048) + b for b in (1 << 31, 1 << 32, (1 << 32) - (1 << 24))])
+    idx = np.unique(np.concatenate([np.arange(4096), np.arange(n - 4096, n), near, rng.integers(0, n, 1 << 16)]))
+    idx_d = torch.from_numpy(idx).cuda()
+    src = chunk[idx % chunk_n]
+    f = (6, 9, True)
+
+    hist = fmt.new_hist()
+    y = torch.empty_like(xd)
+    fmt.fmt_quantize(xd, f, out=y, hist=hist)
+    torch.cuda.synchronize()
+    assert_same_hist(fmt, hist, want, "fused, n > 2^32")
+    assert_same_values(y[idx_d].cpu().numpy(), oracle.quantize(src, *f), "sampled values, n > 2^32")
+    del y
+
+    assert_same_hist(fmt, fmt.fmt_histogram(xd, f), want, "statistics only, n > 2^32")
+
+    hist = fmt.new_hist()
+    c = fmt.fmt_pack16(xd, f, hist=hist)
+    torch.cuda.synchronize()
+    assert_same_hist(fmt, hist, want, "pack16, n > 2^32")
+    got = c[idx_d].cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, oracle.pack16(src, *f)), "sampled codes, n > 2^32"
+    back = fmt.fmt_unpack16(c, f)
+    torch.cuda.synchronize()
+    assert_same_values(back[idx_d].cpu().numpy(), oracle.quantize(src, *f), "unpacked values, n > 2^32")
