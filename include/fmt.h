@@ -265,9 +265,10 @@ int fmt_linear_pack16(int64_t M, int64_t N, int64_t K,
  *   fmt_conv2d_wgrad  dW[k][c][r][s] = sum_{n,p,q} Q(dY)[n][k][p][q] * Q(X)[n][c][p*stride_h - pad_h + r][q*stride_w - pad_w + s]
  * (positions outside the tensor contribute zero).  These are fmt_gemm's products on the patch
  * matrix of the convolution -- same rounding of the operands, exact products, fp32 accumulation in
- * unspecified order, unrounded fp32 result, same error bound -- but the patch matrix (r*s times
- * the size of the tensor) is never written to memory: the operand loader gathers the patches
- * while it rounds.
+ * unspecified order, unrounded fp32 result, same error bound -- but nobody forms the fp32 patch
+ * matrix (r*s times the size of the tensor): the tensor is rounded once and the operand preparation
+ * gathers the patches from it straight into the product kernel's 16-bit operand layout in library
+ * scratch (2 bytes per patch element and 16-bit piece of the format; freed by fmt_release_scratch).
  *
  * All pointers are device pointers, 4-byte aligned; the output must not overlap an input.
  * Sizes: n, c, k >= 0; h, w, r, s >= 1; pad >= 0; stride >= 1; h + 2 pad_h >= r, w + 2 pad_w >= s;

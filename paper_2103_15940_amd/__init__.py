@@ -379,7 +379,8 @@ def _dense4(t, name, shape=None):
 
 def fmt_conv2d_fwd(X, W, fmt, pad=1, stride=1, out=None, stream=None):
     """Y = conv(Q(X), Q(W)) with exact products and fp32 accumulation (Sec. IV-A); X [n,c,h,w], W [k,c,r,s],
-    Y [n,k,P,Q].  The patch matrix is gathered on the fly, never materialised."""
+    Y [n,k,P,Q].  No fp32 patch matrix is formed: the library gathers the patches from the rounded tensor
+    straight into its 16-bit operand layout."""
     import torch
     _dense4(X, "X")
     _dense4(W, "W")

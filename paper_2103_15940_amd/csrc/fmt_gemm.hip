@@ -1551,7 +1551,8 @@ int launch_gemm(int transA, int transB, int64_t M64, int64_t N64, int64_t K64, c
     return run_product(M, N, K, sa, sb, OutSpec{C, ldc, 0}, f, p, stream);
 }
 
-// Convolutions (Sec. IV-A) as products of gathered operands; the patch matrix is never written.
+// Convolutions (Sec. IV-A) as products of gathered operands: no fp32 patch matrix is formed, the
+// prepare pass gathers from the (once rounded) tensor straight into the 16-bit operand layout.
 //   forward  Y[n][k][p][q]:  M = K filters (rows of the filter matrix [K][C*R*S]),
 //            N = n*P*Q output positions (patches of X), k = C*R*S, result stored NCHW
 //   dgrad    dX[n][c][h][w]: M = C (filter seen as [C][K*R*S]), N = n*H*W input positions
