@@ -390,6 +390,17 @@ def main() -> int:
                         "linear_ms": round(lin16_ms, 4),
                         "linear_tflops": round(cfg4_flops / 3 / (lin16_ms * 1e-3) / 1e12, 2)}
     del codes, Y16
+    # the other passes over the config 5 tensor, and the device's own copy, beside `value` (informational)
+    hist_ms = timed(lambda: fmt.fmt_histogram(x, f169, hist=hists[0]), reps)
+    quant_ms = timed(lambda: fmt.fmt_quantize(x, f169, out=y), reps)
+    copy_ms = timed(lambda: y.copy_(x), reps)
+    result["stream_context"] = {
+        "workload": "config 5 tensor, 1/6/9/d: fmt_histogram alone (4 B per element), fmt_quantize without "
+                    "statistics (8 B per element), and the runtime's device-to-device copy of the same tensor "
+                    "(8 B per element)",
+        "histogram_only_gbps": round(4.0 * n / (hist_ms * 1e-3) / 1e9, 1),
+        "quantize_only_gbps": round(8.0 * n / (quant_ms * 1e-3) / 1e9, 1),
+        "device_copy_gbps": round(8.0 * n / (copy_ms * 1e-3) / 1e9, 1)}
     # configurations 1 and 2: cache-resident tensors and small products -- latency-bound, reported as times
     c1 = workloads.config1()
     x1 = torch.from_numpy(c1["x"]).to(dev)
