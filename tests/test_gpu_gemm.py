@@ -383,3 +383,44 @@ def test_result_of_more_than_2_to_the_32_elements(fmt):
     assert rel_fro(got, ref) <= TOL
     err = np.abs(got.astype(np.float64) - ref) / (np.abs(ref) + 1e-3 * np.abs(ref).mean())
     assert err.max() <= 1e-3, err.max()
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_seeded_random_cases(fmt, seed, monkeypatch):
+    """Shapes, storage orders, leading dimensions, formats (any 2 <= e <= 8, 1 <= m <= 23, d or n), value
+    scales and the piece scheme drawn from a seeded generator: each case against the oracle.  The value
+    scale keeps the results finite in the format's range; cases with an even seed use small integers times
+    row / column powers of two and must match bit for bit."""
+    rng = np.random.default_rng(1000 + seed)
+    e, m, d = int(rng.integers(2, 9)), int(rng.integers(1, 24)), bool(rng.integers(0, 2))
+    M, N, K = (int(v) for v in rng.integers(1, 321, 3))
+    tA, tB = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    if e == 6 and 8 <= m <= 10:
+        monkeypatch.setenv("FMT_GEMM_WINDOW", str(int(rng.integers(0, 2))))
+    c = oracle.format_constants(e, m)
+    span = int(min(c["Emax"], 20))
+    if seed % 2 == 0:
+        lim = max(span - 4, 0) // 2
+        A = (rng.integers(-3, 4, (M, K)) * np.exp2(rng.integers(-lim, lim + 1, (M, 1)))).astype(np.float32)
+        B = (rng.integers(-3, 4, (K, N)) * np.exp2(rng.integers(-lim, lim + 1, (1, N)))).astype(np.float32)
+    else:
+        A = (rng.standard_normal((M, K)) * 2.0 ** float(rng.uniform(-span / 2, 0))).astype(np.float32)
+        B = (rng.standard_normal((K, N)) * 2.0 ** float(rng.uniform(-span / 2, 0))).astype(np.float32)
+    As, Bs = (A.T if tA else A), (B.T if tB else B)
+    pa, pb, pc = (int(v) for v in rng.integers(0, 6, 3))                # extra leading-dimension padding
+    Ad = torch.full((As.shape[0], As.shape[1] + pa), 7.0, device="cuda")
+    Bd = torch.full((Bs.shape[0], Bs.shape[1] + pb), 7.0, device="cuda")
+    Cd = torch.full((M, N + pc), -3.0, device="cuda")
+    Ad[:, :As.shape[1]] = dev(As)
+    Bd[:, :Bs.shape[1]] = dev(Bs)
+    fmt.fmt_gemm(Ad[:, :As.shape[1]], Bd[:, :Bs.shape[1]], (e, m, d), transA=tA, transB=tB, out=Cd[:, :N])
+    torch.cuda.synchronize()
+    ref = oracle.gemm(np.ascontiguousarray(As), np.ascontiguousarray(Bs), e, m, d, transA=tA, transB=tB)
+    got = Cd.cpu().numpy()
+    what = "seed %d: 1/%d/%d/%s %dx%dx%d tA=%s tB=%s" % (seed, e, m, "d" if d else "n", M, N, K, tA, tB)
+    assert np.all(got[:, N:] == -3.0), what + ": wrote outside the result"
+    assert np.all(np.isfinite(ref)), what
+    if seed % 2 == 0:
+        assert np.array_equal(got[:, :N], ref), what
+    else:
+        assert rel_fro(got[:, :N], ref) <= TOL, what

@@ -294,3 +294,63 @@ def test_more_than_2_to_the_32_elements(fmt):
     back = fmt.fmt_unpack16(c, f)
     torch.cuda.synchronize()
     assert_same_values(back[idx_d].cpu().numpy(), oracle.quantize(src, *f), "unpacked values, n > 2^32")
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_seeded_random_cases(fmt, seed):
+    """Format (any 2 <= e <= 8, 1 <= m <= 23, d or n), length, pointer offsets of input and output,
+    histogram window and call (fused, values only, statistics only, 16-bit codes, in place) drawn from a
+    seeded generator; everything bit for bit against the oracle, and nothing written outside the output."""
+    rng = np.random.default_rng(5000 + seed)
+    e, m, d = int(rng.integers(2, 9)), int(rng.integers(1, 24)), bool(rng.integers(0, 2))
+    n = int(rng.choice([int(rng.integers(0, 64)), int(rng.integers(64, 20000)), int(rng.integers(20000, 400000))]))
+    ox, oy = int(rng.integers(0, 4)), int(rng.integers(0, 4))
+    exp_lo = int(rng.integers(-192, 129))
+    x = mixed(n + 8, seed)[:n] if n else np.zeros(0, np.float32)
+    xb = torch.zeros(n + 8, device="cuda")
+    xb[ox:ox + n] = dev(x)
+    xin = xb[ox:ox + n]
+    want_h = oracle.histogram(x, e, m, exp_lo=exp_lo)
+    want_y = oracle.quantize(x, e, m, d)
+    what = "seed %d: 1/%d/%d/%s n=%d ox=%d oy=%d exp_lo=%d" % (seed, e, m, "d" if d else "n", n, ox, oy, exp_lo)
+    kind = seed % 5
+    if kind == 0:                                   # fused
+        yb = torch.full((n + 8,), 7.0, device="cuda")
+        hist = fmt.new_hist()
+        fmt.fmt_quantize(xin, (e, m, d), out=yb[oy:oy + n], hist=hist, exp_lo=exp_lo)
+        torch.cuda.synchronize()
+        got = yb.cpu().numpy()
+        assert_same_values(got[oy:oy + n], want_y, what)
+        assert np.all(got[:oy] == 7.0) and np.all(got[oy + n:] == 7.0), what
+        assert_same_hist(fmt, hist, want_h, what)
+    elif kind == 1:                                 # values only
+        yb = torch.full((n + 8,), 7.0, device="cuda")
+        fmt.fmt_quantize(xin, (e, m, d), out=yb[oy:oy + n])
+        torch.cuda.synchronize()
+        got = yb.cpu().numpy()
+        assert_same_values(got[oy:oy + n], want_y, what)
+        assert np.all(got[:oy] == 7.0) and np.all(got[oy + n:] == 7.0), what
+    elif kind == 2:                                 # statistics only
+        hist = fmt.new_hist()
+        fmt.fmt_histogram(xin, (e, m, d), hist=hist, exp_lo=exp_lo)
+        torch.cuda.synchronize()
+        assert_same_hist(fmt, hist, want_h, what)
+        assert_same_values(xb.cpu().numpy()[ox:ox + n], x, what + ": input changed")
+    elif kind == 3:                                 # in place, with statistics
+        hist = fmt.new_hist()
+        fmt.fmt_quantize(xin, (e, m, d), out=xin, hist=hist, exp_lo=exp_lo)
+        torch.cuda.synchronize()
+        assert_same_values(xb.cpu().numpy()[ox:ox + n], want_y, what)
+        assert_same_hist(fmt, hist, want_h, what)
+    else:                                           # 16-bit codes where the format has them
+        if 1 + e + m > 16:
+            e, m = 6, 9
+            want_h = oracle.histogram(x, e, m, exp_lo=exp_lo)
+        cb = torch.full((n + 8,), 0x5555, dtype=torch.int16, device="cuda")
+        hist = fmt.new_hist()
+        fmt.fmt_pack16(xin, (e, m, d), out=cb[oy:oy + n], hist=hist, exp_lo=exp_lo)
+        torch.cuda.synchronize()
+        got = cb.cpu().numpy().view(np.uint16)
+        assert np.array_equal(got[oy:oy + n], oracle.pack16(x, e, m, d)), what
+        assert np.all(got[:oy] == 0x5555) and np.all(got[oy + n:] == 0x5555), what
+        assert_same_hist(fmt, hist, want_h, what)
