@@ -163,3 +163,29 @@ def test_equals_im2col_product_config3_shape(fmt):
     Y2 = fmt.fmt_gemm(dev(Xcol), dev(W.reshape(96, -1)), f, transB=True).cpu().numpy()    # [n*h*w, k]
     Y2 = Y2.reshape(4, 14, 14, 96).transpose(0, 3, 1, 2)
     assert rel_err(Y, Y2) <= 2e-7
+
+
+@pytest.mark.parametrize("seed", range(36))
+def test_seeded_random_geometries(fmt, seed):
+    """Batch, channels, image and filter size (filters up to 7 x 6: more than 32 taps included), padding
+    (also wider than the filter), stride and format drawn from a seeded generator; exact data, so
+    forward, dgrad and wgrad must match the oracle bit for bit."""
+    rng = np.random.default_rng(9000 + seed)
+    n, c, k = int(rng.integers(1, 4)), int(rng.integers(1, 41)), int(rng.integers(1, 41))
+    h, w = int(rng.integers(1, 18)), int(rng.integers(1, 18))
+    pad = (int(rng.integers(0, 4)), int(rng.integers(0, 4)))
+    r = int(rng.integers(1, min(7, h + 2 * pad[0]) + 1))
+    s = int(rng.integers(1, min(6, w + 2 * pad[1]) + 1))
+    stride = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+    f = [(6, 9, True), (5, 10, False), (8, 7, True), (6, 9, False), (7, 12, True), (4, 3, True)][seed % 6]
+    X = (rng.integers(-3, 4, (n, c, h, w)) * 0.5).astype(np.float32)
+    W = (rng.integers(-3, 4, (k, c, r, s)) * 0.25).astype(np.float32)
+    P, Q = oracle.conv_out_size(h, w, r, s, pad, stride)
+    dY = (rng.integers(-3, 4, (n, k, P, Q)) * 2.0 ** -3).astype(np.float32)
+    got = run_all(fmt, X, W, dY, f, pad, stride)
+    want = oracle_all(X, W, dY, f, pad, stride)
+    what = "seed %d: n=%d c=%d k=%d %dx%d filter %dx%d pad %r stride %r 1/%d/%d" % (seed, n, c, k, h, w, r, s, pad, stride, f[0], f[1])
+    for name, g_, w_ in zip(("Y", "dX", "dW"), got, want):
+        assert g_.shape == w_.shape, what
+        assert np.all(np.isfinite(w_)), what
+        assert np.array_equal(g_.view(np.uint32), w_.view(np.uint32)), "%s differs, %s" % (name, what)
