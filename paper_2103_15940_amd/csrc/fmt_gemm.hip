@@ -629,26 +629,21 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
     if (PS == 0 && o.win.S != nullptr) {
         // scaled single piece: round, scale by the row's power of two, keep what is a binary16 value
         const int S = o.win.S[row];
-        const uint32_t shift = (uint32_t)S << 23;
         uint32_t rr8[8];
         bool plain = true;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            // the common cases without branches: zero, or a binary16 value (normal or denormal range)
-            // after scaling; only non-finite values and outliers take the general routine below
+            // The common case without branches: r * 2^S (exact, |S| is small) converts to binary16 and
+            // back unchanged -- zeros, values of binary16's normal and denormal range, infinities.
+            // NaN and the outliers (conversion rounds or overflows) take the general routine below.
             const uint32_t r = quantize_bits<MODE, FTZ>(v[j], p);
-            const uint32_t ab = r & 0x7FFFFFFFu, as = ab + shift;
-            const bool normal = as - 0x38800000u < 0x47800000u - 0x38800000u;
-            const float steps = __uint_as_float(as) * 16777216.0f;          // multiples of 2^-24 (denormal range)
-            const uint32_t nd = (uint32_t)steps;
-            const bool den = as < 0x38800000u && (float)nd == steps;
-            const bool fine = ab == 0u || (ab < 0x7F800000u && (normal || den));
+            const float sc = ldexpf(__uint_as_float(r), S);
+            const _Float16 h = static_cast<_Float16>(sc);               // round to nearest even
             rr8[j] = r;
-            const uint32_t h = normal ? (as - 0x38000000u) >> 13 : nd;
-            pc[j][0] = ab == 0u ? 0u : (h | ((r >> 16) & 0x8000u));
-            plain = plain && fine;
+            pc[j][0] = (uint32_t)__builtin_bit_cast(uint16_t, h);
+            plain = plain && static_cast<float>(h) == sc;
         }
-        if (__ballot(!plain) != 0ull) {                    // some lane holds a denormal, a non-finite value or an outlier
+        if (__ballot(!plain) != 0ull) {                    // some lane holds a NaN or an outlier
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t r = rr8[j];
