@@ -10,8 +10,6 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfmt.so")
 SOURCES = ["fmt_api.hip", "fmt_stream.hip", "fmt_gemm.hip", "fmt_fmac8.hip", "fmt_linear.hip", "fmt_dls.hip"]
-# stand-alone timing programs (no part of the library): source -> executable next to this file
-PROBES = {"tile_probe.hip": os.path.join(HERE, "tile_probe")}
 # packed-fp32 instructions (v_pk_add_f32 and friends) are kept out of the generated code on purpose:
 # the rounding relies on every fp32 addition being one correctly rounded scalar operation
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter",
@@ -56,25 +54,7 @@ def build(verbose: bool = False, extra_flags=(), output: str = LIB, tag: str = "
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     os.replace(tmp, output)
-    if output == LIB:
-        build_probes(verbose)
     return output
-
-
-def build_probes(verbose: bool = False) -> None:
-    """Compile the stand-alone timing programs."""
-    for src, exe in PROBES.items():
-        cmd = [hipcc(), *[f for f in FLAGS if f != "-fPIC"], "-o", exe, os.path.join(CSRC, src)]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        out = "\n".join(l for l in p.stdout.splitlines()
-                        if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
-        if p.returncode != 0:
-            sys.stderr.write("hipcc failed on %s:\n%s\n" % (src, out))
-            raise RuntimeError("probe build failed")
-        if verbose and out.strip():
-            print(out)
 
 
 if __name__ == "__main__":
