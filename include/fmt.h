@@ -43,7 +43,12 @@
  *     different streams use different scratch and may overlap.  Once a call of the same
  *     kind and size has run on a stream, further calls on it neither allocate nor
  *     synchronise (scratch is cleared by kernels, not by memset), so they can be recorded
- *     into a HIP graph on that stream and replayed.
+ *     into a HIP graph on that stream and replayed.  A recorded graph holds the addresses of
+ *     the scratch it was recorded with: any later call on that stream that makes the scratch
+ *     grow (a larger problem) frees the old buffers and INVALIDATES every graph recorded
+ *     before it, as does fmt_release_scratch(); record again after either.  A call that
+ *     would have to grow scratch while its stream is being captured allocates nothing,
+ *     launches nothing and returns FMT_ERR_CAPTURE: run the same call once outside capture first.
  *   - Arguments are validated before any GPU call, so argument errors are reported
  *     even on a host without a GPU.  No exception or abort crosses this boundary:
  *     every call returns FMT_OK (0) or a negative fmt_status.
@@ -68,7 +73,8 @@ typedef enum fmt_status {
     FMT_ERR_ALIGN = -4,  /* a data pointer is not aligned to its element size                */
     FMT_ERR_RANGE = -5,  /* a scalar parameter is out of range (exp_lo window, loss-scale parameters) */
     FMT_ERR_ALIAS = -6,  /* GEMM output overlaps an input                                    */
-    FMT_ERR_HIP = -7     /* a HIP runtime call failed (launch, allocation, no device)        */
+    FMT_ERR_HIP = -7,    /* a HIP runtime call failed (launch, allocation, no device)        */
+    FMT_ERR_CAPTURE = -8 /* library scratch would have to grow while the stream is being captured */
 } fmt_status;
 
 /* The format triple of Def. III.2 (sign bits are always 1).

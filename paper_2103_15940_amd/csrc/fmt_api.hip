@@ -63,9 +63,14 @@ int make_quant_params(fmt_format_t f, int32_t exp_lo, QuantParams *p)
 static std::mutex g_mu;
 static std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
 
-static int grow(void **buf, size_t *have, size_t want)
+// Scratch only ever grows outside stream capture: a graph being recorded would keep the addresses of
+// the buffer that is freed here, and hipMalloc / hipFree / hipMemset are not capturable anyway.
+static int grow(hipStream_t stream, void **buf, size_t *have, size_t want)
 {
     if (want <= *have) return FMT_OK;
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    FMT_HIP_CHECK(hipStreamIsCapturing(stream, &capturing));
+    if (capturing != hipStreamCaptureStatusNone) return FMT_ERR_CAPTURE;
     if (*buf) {
         FMT_HIP_CHECK(hipFree(*buf));  // synchronises the device: no kernel still uses it
         *buf = nullptr;
@@ -85,9 +90,9 @@ int get_scratch(hipStream_t stream, size_t hist_bytes, size_t gemm_bytes, Scratc
     FMT_HIP_CHECK(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lk(g_mu);
     Scratch &s = g_scratch[std::make_pair(dev, stream)];
-    int rc = grow(&s.hist_partials, &s.hist_bytes, hist_bytes);
+    int rc = grow(stream, &s.hist_partials, &s.hist_bytes, hist_bytes);
     if (rc != FMT_OK) return rc;
-    rc = grow(&s.gemm_ws, &s.gemm_bytes, gemm_bytes);
+    rc = grow(stream, &s.gemm_ws, &s.gemm_bytes, gemm_bytes);
     if (rc != FMT_OK) return rc;
     *out = s;
     return FMT_OK;
@@ -99,7 +104,7 @@ int get_acc_scratch(hipStream_t stream, size_t bytes, float **out)
     FMT_HIP_CHECK(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lk(g_mu);
     Scratch &s = g_scratch[std::make_pair(dev, stream)];
-    int rc = grow(&s.acc_ws, &s.acc_bytes, bytes);
+    int rc = grow(stream, &s.acc_ws, &s.acc_bytes, bytes);
     if (rc != FMT_OK) return rc;
     *out = static_cast<float *>(s.acc_ws);
     return FMT_OK;
@@ -432,6 +437,7 @@ const char *fmt_status_string(int status)
         case FMT_ERR_RANGE: return "a scalar parameter is out of range (exp_lo window, loss-scale parameters)";
         case FMT_ERR_ALIAS: return "output overlaps an input";
         case FMT_ERR_HIP: return "a HIP runtime call failed";
+        case FMT_ERR_CAPTURE: return "library scratch would have to grow while the stream is being captured into a graph";
         default: return "unknown status";
     }
 }

@@ -33,10 +33,14 @@ def test_struct_layout():
 
 
 def test_status_strings():
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = fmt.status_string(code)
-        assert isinstance(s, str) and s and (code == 0 or s != "ok")
+        assert isinstance(s, str) and s and (code == 0 or s != "ok") and s != "unknown status"
     assert fmt.status_string(-99) == "unknown status"
+    # the status a call returns instead of growing its scratch under stream capture is declared and named
+    text = open(os.path.join(ROOT, "include", "fmt.h")).read()
+    assert re.search(r"FMT_ERR_CAPTURE\s*=\s*-8", text)
+    assert "captured" in fmt.status_string(-8)
 
 
 @pytest.mark.parametrize("e,m", [(5, 10), (6, 9), (8, 7), (2, 1), (8, 23), (7, 16)])

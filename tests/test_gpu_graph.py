@@ -132,3 +132,39 @@ def test_overlapping_calls_on_two_streams(fmt):
             os.environ.pop("FMT_GEMM_WINDOW", None)
         else:
             os.environ["FMT_GEMM_WINDOW"] = old
+
+
+def test_growing_scratch_under_capture_is_refused(fmt):
+    """A call that would have to grow the library's scratch while its stream is being captured returns
+    FMT_ERR_CAPTURE and launches nothing; the same call outside capture succeeds, and can then be
+    captured."""
+    dev = torch.device("cuda")
+    f = (5, 10, True)
+    st = torch.cuda.Stream()
+    rng = np.random.default_rng(5)
+    small = [torch.from_numpy(rng.standard_normal((64, 64)).astype(np.float32)).to(dev) for _ in range(2)]
+    big = [torch.from_numpy(rng.standard_normal((1536, 1536)).astype(np.float32)).to(dev) for _ in range(2)]
+    Cs, Cb = torch.empty((64, 64), device=dev), torch.empty((1536, 1536), device=dev)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        fmt.fmt_gemm(small[0], small[1], f, out=Cs)          # this stream's scratch now fits the small product only
+        st.synchronize()
+        g = torch.cuda.CUDAGraph()
+        status = None
+        with torch.cuda.graph(g, stream=st):
+            fmt.fmt_gemm(small[0], small[1], f, out=Cs)      # fits: recorded
+            try:
+                fmt.fmt_gemm(big[0], big[1], f, out=Cb)      # would grow: refused, nothing recorded
+            except fmt.FmtError as err:
+                status = err.status
+        assert status == -8
+        want = Cs.clone()
+        Cs.zero_()
+        g.replay()
+        st.synchronize()
+        assert torch.equal(Cs, want)
+        fmt.fmt_gemm(big[0], big[1], f, out=Cb)              # outside capture the same call grows the scratch
+        st.synchronize()
+    torch.cuda.synchronize()
+    ref = big[0].half().float().double() @ big[1].half().float().double()
+    assert torch.linalg.norm(Cb.double() - ref) / torch.linalg.norm(ref) < 1e-5
