@@ -140,6 +140,26 @@ int fmt_quantize(const float *x, float *y, size_t n, fmt_format_t f,
                  fmt_hist_t *hist, int32_t exp_lo, void *stream);
 
 /*
+ * fmt_quantize_static -- fmt_quantize for callers that cannot allocate device memory: code that runs
+ * under HIP graph capture from its first call on, tight serving loops, harnesses that forbid
+ * hipMalloc.  Arguments, result and errors are fmt_quantize's, bit for bit; the difference is where
+ * the partial statistics records live while the pass runs: not in per-(device, stream) scratch that
+ * is created with hipMalloc on first use, but in a fixed array of FMT_STATIC_SCRATCH_BYTES inside the
+ * library's device image, of which every GPU holds one copy from the moment the library is loaded
+ * there until the process ends.  The call allocates and frees nothing, on the device or through any
+ * library, and never synchronises.
+ *   - n must not exceed FMT_STATIC_MAX_ELEMENTS (else FMT_ERR_SHAPE, nothing is launched).
+ *   - All calls on one GPU share that GPU's array, whatever their stream: calls with statistics that
+ *     overlap in time on one GPU race on it and give wrong counts.  Put them on one stream, or order
+ *     them with events.  (Calls with hist == NULL do not touch the array.)
+ *   - The array keeps the last call's contents; the call clears it on the stream before it counts.
+ */
+#define FMT_STATIC_SCRATCH_BYTES 36864
+#define FMT_STATIC_MAX_ELEMENTS ((size_t)1 << 36)
+int fmt_quantize_static(const float *x, float *y, size_t n, fmt_format_t f,
+                        fmt_hist_t *hist, int32_t exp_lo, void *stream);
+
+/*
  * fmt_histogram -- per-tensor statistics without writing a quantized copy (the
  * logging of Sec. V: denormal fraction of activations, weights and gradients).
  * *hist (device) is overwritten with the counts described at fmt_hist_t.  The counts

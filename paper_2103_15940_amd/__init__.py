@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_release_scratch", "fmt_status_string")
 
 
@@ -81,6 +81,8 @@ def _load() -> ctypes.CDLL:
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
     lib.fmt_quantize.argtypes = [vp, vp, sz, _CFormat, vp, i32, vp]
     lib.fmt_quantize.restype = ctypes.c_int
+    lib.fmt_quantize_static.argtypes = lib.fmt_quantize.argtypes
+    lib.fmt_quantize_static.restype = ctypes.c_int
     lib.fmt_histogram.argtypes = [vp, sz, _CFormat, vp, i32, vp]
     lib.fmt_histogram.restype = ctypes.c_int
     lib.fmt_gemm.argtypes = [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64, vp, i64, _CFormat, vp]
@@ -160,10 +162,12 @@ def hist_to_dict(hist) -> dict:
     return out
 
 
-def fmt_quantize(x, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None):
+def fmt_quantize(x, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAULT, stream=None, static: bool = False):
     """y = Q_{e,m,d|n}(x) elementwise (Sec. IV-A roundfp); ``out`` may be ``x`` itself.  When a
     ``hist`` buffer (see :func:`new_hist`) is given, the statistics of :func:`fmt_histogram` are
-    produced in the same pass.  Asynchronous on ``stream`` (default: torch's current stream)."""
+    produced in the same pass.  Asynchronous on ``stream`` (default: torch's current stream).
+    ``static=True`` calls ``fmt_quantize_static``, the entry point that allocates nothing (pass ``out``,
+    or this wrapper's own ``torch.empty_like`` allocates the result)."""
     import torch
     _dev_f32(x, "x")
     if not x.is_contiguous():
@@ -178,8 +182,9 @@ def fmt_quantize(x, fmt, out=None, hist=None, exp_lo: int = EXP_LO_DEFAULT, stre
         if hist.dtype != torch.int64 or hist.numel() != 8 + FMT_NBINS or not hist.is_cuda:
             raise TypeError("hist must be a GPU int64 tensor of 72 elements")
         hp = hist.data_ptr()
-    rc = _lib.fmt_quantize(x.data_ptr(), out.data_ptr(), x.numel(), _cfmt(fmt), hp, int(exp_lo), _stream_ptr(stream))
-    _check(rc, "fmt_quantize")
+    entry = _lib.fmt_quantize_static if static else _lib.fmt_quantize
+    rc = entry(x.data_ptr(), out.data_ptr(), x.numel(), _cfmt(fmt), hp, int(exp_lo), _stream_ptr(stream))
+    _check(rc, "fmt_quantize_static" if static else "fmt_quantize")
     return out
 
 

@@ -155,6 +155,20 @@ int fmt_quantize(const float *x, float *y, size_t n, fmt_format_t f,
     return launch_stream(x, y, n, p, f.denorm == 0, hist, static_cast<hipStream_t>(stream));
 }
 
+int fmt_quantize_static(const float *x, float *y, size_t n, fmt_format_t f,
+                        fmt_hist_t *hist, int32_t exp_lo, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, hist ? exp_lo : FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (n > FMT_STATIC_MAX_ELEMENTS) return FMT_ERR_SHAPE;
+    if (n > 0 && (!x || !y)) return FMT_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y, 4) || !aligned(hist, 8)) return FMT_ERR_ALIGN;
+    if (n > 0 && x != y && overlap(x, n * 4, y, n * 4)) return FMT_ERR_ALIAS;
+    if (n == 0 && !hist) return FMT_OK;
+    return launch_stream_static(x, y, n, p, f.denorm == 0, hist, static_cast<hipStream_t>(stream));
+}
+
 int fmt_histogram(const float *x, size_t n, fmt_format_t f,
                   fmt_hist_t *hist, int32_t exp_lo, void *stream)
 {

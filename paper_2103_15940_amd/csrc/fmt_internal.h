@@ -48,8 +48,13 @@ int get_scratch(hipStream_t stream, size_t hist_bytes, size_t gemm_bytes, Scratc
 int device_cu_count(int *cus);
 
 // Stream kernels (fmt_stream.hip).  y: n floats, or with pack16 n uint16_t codes, or nullptr (statistics only).
+// fixed_partials: partial statistics records to use instead of the (device, stream) scratch, or nullptr.
 int launch_stream(const float *x, void *y, size_t n, const QuantParams &p, bool ftz,
-                  fmt_hist_t *hist, hipStream_t stream, bool pack16 = false);
+                  fmt_hist_t *hist, hipStream_t stream, bool pack16 = false,
+                  unsigned long long *fixed_partials = nullptr);
+// The same pass with the partial records in the library's file-scope device array: allocates nothing.
+int launch_stream_static(const float *x, float *y, size_t n, const QuantParams &p, bool ftz,
+                         fmt_hist_t *hist, hipStream_t stream);
 int launch_unpack16(const uint16_t *codes, float *y, size_t n, const QuantParams &p, hipStream_t stream);
 
 // GEMM (fmt_gemm.hip)

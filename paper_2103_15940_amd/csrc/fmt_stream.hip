@@ -22,6 +22,8 @@
 // compare-and-add counters.  Each workgroup folds its table into 64 bins and adds them, with one
 // 64-bit atomic per non-zero slot, into one of 64 partial records in library scratch; a second
 // tiny kernel sums the 64 records into the caller's fmt_hist_t and clears them again.
+#include <mutex>
+
 #include "fmt_hist.h"
 #include "fmt_internal.h"
 #include "fmt_quant.h"
@@ -209,7 +211,7 @@ int launch_hist_finalize(unsigned long long *partials, size_t n, fmt_hist_t *his
 
 template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, bool VEC, bool PACK>
 static int launch_variant(const float *x, void *y, size_t n, size_t head, size_t nvec, const QuantParams &p,
-                          fmt_hist_t *hist, hipStream_t stream)
+                          fmt_hist_t *hist, hipStream_t stream, unsigned long long *fixed_partials)
 {
     auto kern = stream_kernel<MODE, STORE, FTZ, HIST, DEEP, VEC, PACK>;
     int cus = 0;
@@ -232,8 +234,8 @@ static int launch_variant(const float *x, void *y, size_t n, size_t head, size_t
     }
     int grid = (int)(g < cap ? g : cap);
     if (grid < 1) grid = 1;
-    unsigned long long *partials = nullptr;
-    if (HIST) {
+    unsigned long long *partials = fixed_partials;
+    if (HIST && partials == nullptr) {
         Scratch s;
         rc = get_scratch(stream, kHistScratchBytes, 0, &s);
         if (rc != FMT_OK) return rc;
@@ -247,7 +249,7 @@ static int launch_variant(const float *x, void *y, size_t n, size_t head, size_t
 }
 
 int launch_stream(const float *x, void *y, size_t n, const QuantParams &p, bool ftz, fmt_hist_t *hist,
-                  hipStream_t stream, bool pack16)
+                  hipStream_t stream, bool pack16, unsigned long long *fixed_partials)
 {
     const bool store = y != nullptr;
     const bool do_hist = hist != nullptr;
@@ -268,8 +270,8 @@ int launch_stream(const float *x, void *y, size_t n, const QuantParams &p, bool 
     if (!vec) head = 0;
 
 #define FMT_LAUNCH_M(MD, S, F, H, D, PK)                                                                     \
-    (vec ? launch_variant<MD, S, F, H, D, true, PK>(x, y, n, head, nvec, p, hist, stream)           \
-         : launch_variant<MD, S, F, H, D, false, PK>(x, y, n, head, nvec, p, hist, stream))
+    (vec ? launch_variant<MD, S, F, H, D, true, PK>(x, y, n, head, nvec, p, hist, stream, fixed_partials)           \
+         : launch_variant<MD, S, F, H, D, false, PK>(x, y, n, head, nvec, p, hist, stream, fixed_partials))
 #define FMT_LAUNCH(S, F, H, D)                                                                               \
     (p.mode == kModeMagic ? FMT_LAUNCH_M(kModeMagic, S, F, H, D, false)                                      \
      : p.mode == kModeInteger ? FMT_LAUNCH_M(kModeInteger, S, F, H, D, false)                                \
@@ -293,6 +295,56 @@ int launch_stream(const float *x, void *y, size_t n, const QuantParams &p, bool 
 #undef FMT_LAUNCH_PACK
 #undef FMT_LAUNCH_M
 #undef FMT_LAUNCH
+}
+
+// ---- fmt_quantize_static: the partial records in a file-scope device array instead of allocated scratch
+//
+// Every GPU that loads the library holds its own copy of this array (36 KiB) until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the address kernels and
+// fills use is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned long long scratch[kShards * kSlots];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static unsigned long long *g_static_ptr[kMaxDevices];
+
+static int static_partials(unsigned long long **out)
+{
+    int dev = 0;
+    FMT_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return FMT_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (g_static_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        FMT_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr) return FMT_ERR_HIP;
+        g_static_ptr[dev] = static_cast<unsigned long long *>(ptr);
+    }
+    *out = g_static_ptr[dev];
+    return FMT_OK;
+}
+
+__global__ __launch_bounds__(256) void clear_records_kernel(unsigned long long *__restrict__ rec, int n)
+{
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) rec[i] = 0ull;
+}
+
+int launch_stream_static(const float *x, float *y, size_t n, const QuantParams &p, bool ftz, fmt_hist_t *hist,
+                         hipStream_t stream)
+{
+    unsigned long long *rec = nullptr;
+    if (hist != nullptr) {
+        int rc = static_partials(&rec);
+        if (rc != FMT_OK) return rc;
+        // The array keeps whatever the last call on this GPU left in it.  A completed call leaves zeros
+        // (its last kernel clears what it has summed), a call that failed half-way may not have: start clean.
+        // A kernel, not a memset, so that the call can be recorded into a graph.
+        if (n > 0) {
+            hipLaunchKernelGGL(clear_records_kernel, dim3(kShards * kSlots / 256), dim3(256), 0, stream, rec, kShards * kSlots);
+            FMT_HIP_CHECK(hipGetLastError());
+        }
+    }
+    return launch_stream(x, y, n, p, ftz, hist, stream, false, rec);
 }
 
 // codes -> fp32: 2 bytes read, 4 written per element.  In the vector body a lane turns four codes (one
