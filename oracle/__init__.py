@@ -5,6 +5,10 @@ definitions: Sec. III Def. III.1/III.2, Table I, Sec. III-B FMACS, Sec. IV-A rou
 Sec. V denormal fraction).  It shares nothing with the GPU library and must not be
 imported by it: only ``tests/``, the smoke check and the benchmark's ``cpu_baseline``
 leg may use it.  Arrays in, arrays out; no GPU, no torch.
+
+``oracle.fmac_exact`` (pure Python, exact rationals) is the plain definition of FMAC and of
+Algorithm 1; the C routines ``fmac`` / ``fmac8_dot`` / ``gemm_fmac8`` here are the fast checker for
+sizes it cannot reach and are pinned to it.
 """
 from __future__ import annotations
 

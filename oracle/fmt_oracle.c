@@ -234,6 +234,11 @@ int oracle_linear_epilogue(const float *acc, int64_t ldacc, const float *bias, i
  * lies strictly between two fp64 neighbours, and the one whose last bit is odd is kept.  A value
  * rounded to odd at 53 bits rounds to any format of <= 51 bits exactly as the exact sum would
  * (the classic double-rounding remedy).  The format rounding is then the same as in roundfp.
+ *
+ * This routine is the FAST checker (used where the matrices are too large for rational arithmetic).
+ * The definition of FMAC and of Algorithm 1 is oracle/fmac_exact.py -- the exact sum as a rational,
+ * rounded by a search over the enumerated value set -- and tests/test_oracle_fmac_exact.py holds this
+ * routine to it, bit for bit, for every format family (including the e >= 7 formats).
  */
 static double sum_round_to_odd(double a, double p)
 {

@@ -159,3 +159,34 @@ def test_operand_of_more_than_2_to_the_32_elements(fmt):
     rows_d = torch.from_numpy(rows).cuda()
     ref = oracle.gemm_fmac8(A[rows_d].cpu().numpy(), B.cpu().numpy(), *f)
     assert_bits(C[rows_d].cpu().numpy(), ref, "sampled rows, M*K > 2^32")
+
+
+@pytest.mark.parametrize("e,m,d", VARIANTS + [(7, 8, True), (7, 8, False), (4, 3, True)])
+def test_against_the_plain_definition(fmt, e, m, d):
+    """fmt_gemm_fmac8 compared directly with Algorithm 1 run in exact rational arithmetic
+    (oracle/fmac_exact.py: the sum a + w*x as a Fraction, rounded once by a search over the enumerated
+    value set) -- no fp64 construction in between.  Operands span the whole exponent range of the
+    format, so accumulator and product are often far apart; 1/8/7 and 1/7/8 take the kernel's
+    double-precision step, the others its single-precision one.  Small: the definition is slow."""
+    from oracle import fmac_exact
+    rng = np.random.default_rng(1000 + 10 * e + m + int(d))
+    c = oracle.format_constants(e, m)
+    span = c["Emax"] - c["Emin"]
+    M, N, K = 16, 16, 40
+    # two recipes: products mostly inside the range (accumulators wander through the denormal range and
+    # far-apart exponents), and products that often overflow the accumulator or the final rounding
+    for centre, sigma, min_finite in [(-span / 8, span / 6, M * N * 3 // 4), ((c["Emin"] + c["Emax"]) / 4, span / 5, 8)]:
+        A = workloads.log2_normal((M, K), centre, sigma, 0.05, rng)
+        B = workloads.log2_normal((K, N), centre, sigma, 0.05, rng)
+        want = fmac_exact.gemm_fmac8(A, B, e, m, d)
+        assert np.isfinite(want).sum() >= min_finite        # the case is not degenerate
+        for tA, tB in LAYOUTS if (e, m, d) == (6, 9, True) else [(False, False)]:
+            Ain = np.ascontiguousarray(A.T) if tA else A
+            Bin = np.ascontiguousarray(B.T) if tB else B
+            got = fmt.fmt_gemm_fmac8(dev(Ain), dev(Bin), (e, m, d), transA=tA, transB=tB)
+            torch.cuda.synchronize()
+            got = got.cpu().numpy()
+            nan = np.isnan(want)
+            assert np.array_equal(np.isnan(got), nan)
+            assert_bits(np.where(nan, 0, got).astype(np.float32), np.where(nan, 0, want).astype(np.float32),
+                        "definition, 1/%d/%d/%s layout %s" % (e, m, d, (tA, tB)))
