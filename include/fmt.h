@@ -195,6 +195,52 @@ int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
              float *C, int64_t ldc, fmt_format_t f, void *stream);
 
 /*
+ * Prepared operands -- the rounded operand of a product, made once and used by every product that
+ * needs it.
+ *
+ * Sec. IV-A rounds a tensor where it enters a layer and then uses the ROUNDED tensor wherever the
+ * layer needs it: R(X) feeds the forward product and the weight gradient, R(W) the forward product
+ * and the input gradient, R(dY) both gradients.  fmt_gemm is handed fp32 operands and has to round
+ * and re-lay them out on every call; fmt_prepare does that work once per tensor and orientation and
+ * leaves the result -- the values of Q(op(X)) in the 16-bit operand layout of the matrix cores -- in
+ * memory the CALLER owns, and fmt_gemm_prepared multiplies two such operands with one kernel launch:
+ *
+ *     C[i][j] = sum_k Q(a)[i][k] * Q(b)[j][k]        (exact products, fp32 accumulation: FMACS, Sec. III-B)
+ *
+ * bit for bit what fmt_gemm returns for the same operands (same kernels, same order of accumulation).
+ *
+ * fmt_operand_bytes  size in bytes of the device buffer a prepared operand of `rows` x `k` needs.
+ * fmt_prepare        op(X) is `rows` x `k`: trans == 0: X is rows x k, row-major, ld >= k;
+ *                    trans != 0: X is k x rows, row-major, ld >= rows (the operand is X transposed).
+ *                    data: device memory of at least fmt_operand_bytes(rows, k, f) bytes, 256-byte
+ *                    aligned, not overlapping X; *op (HOST memory) is filled in and describes the
+ *                    operand from then on.  The library keeps no reference to either; the operand is
+ *                    valid once the stream has executed the call and until the caller overwrites or
+ *                    frees `data`.  fmt_prepare uses no library scratch, allocates nothing, and can be
+ *                    recorded into a graph.
+ * fmt_gemm_prepared  A->rows = M, B->rows = N, A->k == B->k = K, same format and same scheme (operands
+ *                    prepared by the same build with the same environment); C is M x N, ldc >= N, must
+ *                    not overlap either operand.  For a fully connected layer with X [batch, in],
+ *                    W [out, in], dY [batch, out]:  Y = (X, trans 0)(W, trans 0);  dX = (dY, trans 0)
+ *                    (W, trans 1);  dW = (dY, trans 1)(X, trans 1).
+ * rows, k >= 1 and below 2^31; non-finite operands as for fmt_gemm.  Errors as for fmt_gemm;
+ * FMT_ERR_SHAPE also when `bytes` is too small or the two operands do not fit each other,
+ * FMT_ERR_FORMAT when their formats or schemes differ.
+ */
+typedef struct fmt_operand {
+    void *data;            /* device buffer (caller-owned) */
+    size_t bytes;          /* its size */
+    int64_t rows, k;       /* op(X) is rows x k */
+    fmt_format_t format;
+    int32_t scheme;        /* how the values are represented for the matrix cores (set by fmt_prepare) */
+} fmt_operand_t;
+
+int fmt_operand_bytes(int64_t rows, int64_t k, fmt_format_t f, size_t *bytes);
+int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, fmt_format_t f,
+                void *data, size_t bytes, fmt_operand_t *op, void *stream);
+int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream);
+
+/*
  * fmt_gemm_fmac8 -- matrix product with the FMAC-8 accumulation of Sec. IV-A, Algorithm 1, for
  * hardware that only offers FMAC (Sec. III-B: a16 = o(a16 + x16*y16), one rounding).
  *

@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_gemm_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_release_scratch", "fmt_status_string")
 
 
@@ -66,6 +66,11 @@ class _CDlsState(ctypes.Structure):
                 ("peak_denormal", ctypes.c_uint64), ("peak_total", ctypes.c_uint64)]
 
 
+class _COperand(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("bytes", ctypes.c_size_t), ("rows", ctypes.c_int64), ("k", ctypes.c_int64),
+                ("format", _CFormat), ("scheme", ctypes.c_int32)]
+
+
 class FmtError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -87,6 +92,12 @@ def _load() -> ctypes.CDLL:
     lib.fmt_histogram.restype = ctypes.c_int
     lib.fmt_gemm.argtypes = [ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64, vp, i64, _CFormat, vp]
     lib.fmt_gemm.restype = ctypes.c_int
+    lib.fmt_operand_bytes.argtypes = [i64, i64, _CFormat, ctypes.POINTER(sz)]
+    lib.fmt_operand_bytes.restype = ctypes.c_int
+    lib.fmt_prepare.argtypes = [vp, i64, ctypes.c_int, i64, i64, _CFormat, vp, sz, ctypes.POINTER(_COperand), vp]
+    lib.fmt_prepare.restype = ctypes.c_int
+    lib.fmt_gemm_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, i64, vp]
+    lib.fmt_gemm_prepared.restype = ctypes.c_int
     lib.fmt_gemm_fmac8.argtypes = lib.fmt_gemm.argtypes
     lib.fmt_gemm_fmac8.restype = ctypes.c_int
     lib.fmt_linear.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, _CFormat, vp, i32, vp]
@@ -231,6 +242,66 @@ def fmt_gemm(A, B, fmt, transA: bool = False, transB: bool = False, out=None, st
     A, B are 2-D row-major float32 GPU tensors (a row stride larger than the row length is
     passed on as the leading dimension)."""
     return _gemm_call(_lib.fmt_gemm, "fmt_gemm", A, B, fmt, transA, transB, out, stream)
+
+
+class PreparedOperand:
+    """A rounded operand in the matrix cores' 16-bit layout (see ``fmt_prepare`` in fmt.h): the device
+    buffer (a uint8 tensor that keeps the memory alive) and the descriptor the C calls take."""
+
+    def __init__(self, buf, desc):
+        self.buf = buf
+        self.desc = desc
+
+    @property
+    def rows(self) -> int:
+        return int(self.desc.rows)
+
+    @property
+    def k(self) -> int:
+        return int(self.desc.k)
+
+
+def fmt_operand_bytes(rows: int, k: int, fmt) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.fmt_operand_bytes(int(rows), int(k), _cfmt(fmt), ctypes.byref(n)), "fmt_operand_bytes")
+    return int(n.value)
+
+
+def fmt_prepare(X, fmt, trans: bool = False, out=None, stream=None) -> PreparedOperand:
+    """Rounds the 2-D float32 GPU tensor X to the format once and stores it as a prepared operand of
+    X.shape[0] rows (``trans=False``) or, transposed, of X.shape[1] rows (``trans=True``).  ``out`` may be
+    a uint8 GPU tensor (256-byte aligned, at least :func:`fmt_operand_bytes` long) to prepare into."""
+    import torch
+    _dev_f32(X, "X")
+    if X.dim() != 2 or (X.shape[1] > 1 and X.stride(1) != 1):
+        raise ValueError("X must be 2-D with unit column stride")
+    rows, k = (X.shape[1], X.shape[0]) if trans else (X.shape[0], X.shape[1])
+    need = fmt_operand_bytes(rows, k, fmt)
+    if out is None:
+        out = torch.empty(need, dtype=torch.uint8, device=X.device)
+    if not isinstance(out, torch.Tensor) or out.dtype != torch.uint8 or not out.is_cuda or not out.is_contiguous():
+        raise TypeError("out must be a contiguous GPU uint8 tensor")
+    desc = _COperand()
+    ld = X.stride(0) if X.shape[0] > 1 else max(X.shape[1], 1)
+    rc = _lib.fmt_prepare(X.data_ptr(), ld, int(bool(trans)), rows, k, _cfmt(fmt), out.data_ptr(), out.numel(),
+                          ctypes.byref(desc), _stream_ptr(stream))
+    _check(rc, "fmt_prepare")
+    return PreparedOperand(out, desc)
+
+
+def fmt_gemm_prepared(A: PreparedOperand, B: PreparedOperand, out=None, stream=None):
+    """C[i][j] = sum_k Q(a)[i][k] Q(b)[j][k] on two prepared operands (FMACS, Sec. III-B): one launch."""
+    import torch
+    M, N = A.rows, B.rows
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.buf.device)
+    _dev_f32(out, "out")
+    if out.dim() != 2 or tuple(out.shape) != (M, N) or (N > 1 and out.stride(1) != 1):
+        raise ValueError("out must be an M x N tensor with unit column stride")
+    ldc = out.stride(0) if M > 1 else max(N, 1)
+    rc = _lib.fmt_gemm_prepared(ctypes.byref(A.desc), ctypes.byref(B.desc), out.data_ptr(), ldc, _stream_ptr(stream))
+    _check(rc, "fmt_gemm_prepared")
+    return out
 
 
 def fmt_gemm_fmac8(A, B, fmt, transA: bool = False, transB: bool = False, out=None, stream=None):

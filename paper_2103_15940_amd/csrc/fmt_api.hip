@@ -222,6 +222,71 @@ int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
                        static_cast<hipStream_t>(stream));
 }
 
+int fmt_operand_bytes(int64_t rows, int64_t k, fmt_format_t f, size_t *bytes)
+{
+    if (!format_ok(f)) return FMT_ERR_FORMAT;
+    if (!bytes) return FMT_ERR_NULL;
+    const int64_t lim = (int64_t)1 << 31;
+    if (rows < 1 || k < 1 || rows >= lim || k >= lim) return FMT_ERR_SHAPE;
+    int scheme = 0;
+    return prepared_operand_bytes(rows, k, f, bytes, &scheme);
+}
+
+int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, fmt_format_t f,
+                void *data, size_t bytes, fmt_operand_t *op, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    const int64_t lim = (int64_t)1 << 31;
+    if (rows < 1 || k < 1 || rows >= lim || k >= lim) return FMT_ERR_SHAPE;
+    if (!X || !data || !op) return FMT_ERR_NULL;
+    if (ld < (trans ? rows : k) || ld >= lim) return FMT_ERR_SHAPE;
+    if (!aligned(X, 4) || !aligned(data, 256)) return FMT_ERR_ALIGN;
+    size_t need = 0;
+    int scheme = 0;
+    rc = prepared_operand_bytes(rows, k, f, &need, &scheme);
+    if (rc != FMT_OK) return rc;
+    if (bytes < need) return FMT_ERR_SHAPE;
+    const size_t xbytes = 4 * (size_t)(((trans ? k : rows) - 1) * ld + (trans ? rows : k));
+    if (overlap(data, need, X, xbytes)) return FMT_ERR_ALIAS;
+    rc = launch_prepare_operand(X, ld, trans, rows, k, f, p, data, static_cast<hipStream_t>(stream));
+    if (rc != FMT_OK) return rc;
+    op->data = data;
+    op->bytes = bytes;
+    op->rows = rows;
+    op->k = k;
+    op->format = f;
+    op->scheme = scheme;
+    return FMT_OK;
+}
+
+int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream)
+{
+    if (!A || !B) return FMT_ERR_NULL;
+    if (!format_ok(A->format)) return FMT_ERR_FORMAT;
+    if (A->format.e != B->format.e || A->format.m != B->format.m || (A->format.denorm != 0) != (B->format.denorm != 0) ||
+        A->scheme != B->scheme)
+        return FMT_ERR_FORMAT;
+    const int64_t lim = (int64_t)1 << 31;
+    if (A->rows < 1 || B->rows < 1 || A->k < 1 || A->rows >= lim || B->rows >= lim || A->k >= lim) return FMT_ERR_SHAPE;
+    if (A->k != B->k || ldc < B->rows || ldc >= lim) return FMT_ERR_SHAPE;
+    if (!A->data || !B->data || !C) return FMT_ERR_NULL;
+    if (!aligned(A->data, 256) || !aligned(B->data, 256) || !aligned(C, 4)) return FMT_ERR_ALIGN;
+    size_t na = 0, nb = 0;
+    int sa = 0, sb = 0;
+    int rc = prepared_operand_bytes(A->rows, A->k, A->format, &na, &sa);
+    if (rc != FMT_OK) return rc;
+    rc = prepared_operand_bytes(B->rows, B->k, B->format, &nb, &sb);
+    if (rc != FMT_OK) return rc;
+    if (sa != A->scheme || sb != B->scheme) return FMT_ERR_FORMAT;     // prepared under another scheme selection
+    if (A->bytes < na || B->bytes < nb) return FMT_ERR_SHAPE;
+    const size_t cbytes = 4 * (size_t)((A->rows - 1) * ldc + B->rows);
+    if (overlap(C, cbytes, A->data, na) || overlap(C, cbytes, B->data, nb)) return FMT_ERR_ALIAS;
+    return launch_gemm_prepared(A->data, B->data, A->rows, B->rows, A->k, A->scheme, A->format, C, ldc,
+                                static_cast<hipStream_t>(stream));
+}
+
 int fmt_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,
                    const float *A, int64_t lda, const float *B, int64_t ldb,
                    float *C, int64_t ldc, fmt_format_t f, void *stream)

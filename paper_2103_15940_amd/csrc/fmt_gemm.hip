@@ -16,9 +16,21 @@
 //            order the product kernel consumes: units of 32 rows x 32 k per piece, each unit
 //            stored as [k-chunk of 8][row][8 x bf16] so that a wave's MFMA operand fetch is one
 //            contiguous 1 KiB read.
-//   product  workgroup tiles of 64x64 up to 256x128, 4 waves of MFMA 32x32x16 tiles each, operand
-//            stages loaded from global memory straight into LDS (double-buffered, 32 k per
+//   product  workgroup tiles of 64x64 up to 256x256, 4 waves of MFMA 32x32x16 tiles each, operand
+//            stages loaded from global memory straight into LDS (a ring of stage buffers, 32 k per
 //            stage), optional split of the k range with a deterministic reduction.
+//
+// Formats with a 6-bit exponent and at most 10 significant bits (1/6/9, 1/6/8) take a cheaper exact
+// route, "exponent planes": their significands fit binary16, only their exponent range does not.
+// Every row of an operand gets a power-of-two scale 2^S that moves the binades where the row lives
+// into binary16's exactly representable range (plane 0, the only one the main loop reads: ONE fp16
+// MFMA product per multiply).  A value that does not fit there -- too large, or with bits below
+// binary16's last denormal bit -- fits exactly under the scale 2^(S-w) (plane "above") or 2^(S+w)
+// (plane "below"), w = 40 - m binades being what one plane holds; three planes cover the whole range
+// of the format whatever S is.  A per-(32 rows x 32 k) mask says which planes hold anything; after
+// its main loop the product kernel multiplies the few non-empty plane pairs and adds them in a fixed
+// order, each with its own power-of-two scale undone exactly.  Exact products, fp32 accumulation,
+// no lists, no fallback: the result is reproducible bit for bit.
 #include <cstdio>
 #include <cstdlib>
 
@@ -90,58 +102,21 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
     return (((size_t)rb * kblocks + kb) * P + piece) * kUnitVec + c * kUnitRows + row;
 }
 
-// A kernel launched with a gate runs only when the flag it points to is non-zero (run_if = 1) or zero
-// (run_if = 0): the choice between the single-fp16-piece scheme and its exact fallback is made on the
-// device, so both sets of kernels are launched and one of them returns at once.
-struct Gate {
-    const int *flag;     // nullptr: always run
-    int run_if;
+// Exponent planes of one prepared operand (formats with e == 6 and m <= 9; see the top of this file).
+//   S      scale exponent per (padded) row: plane 0 holds value * 2^S, the plane above value * 2^(S-w),
+//          the plane below value * 2^(S+w), each as a binary16 value
+//   mask   one byte per unit (32 rows x 32 k): bit 0 set always, bit 1 / bit 2 set when the unit has
+//          an element in the plane above / below; only then has that plane's unit been written
+//   plane  16-byte vectors from one plane's pieces to the next (planes 1 and 2 follow plane 0)
+struct Planes {
+    int *S;
+    uint8_t *mask;
+    size_t plane;
+    int w;               // 40 - m: binades one plane holds
 };
 
-__device__ __forceinline__ bool gate_closed(const Gate &g) { return g.flag != nullptr && ((*g.flag != 0) != (g.run_if != 0)); }
-
-// Single-fp16-piece scheme for formats with a 6-bit exponent and at most 11 significant bits
-// (1/6/9): such a value fits binary16's significand, only its exponent range (71 binades with the
-// denormals) does not.  Every row of an operand gets a power-of-two scale 2^S (exact) that moves a
-// window of binades into binary16's exactly representable range; the product of the scaled operands
-// runs as ONE fp16 MFMA product per multiply and the result is scaled back by 2^-(S_row + S_col).
-// Elements outside their row's window ("outliers", rare for tensors of neural networks) are left out
-// of the piece (zero) and recorded per row; their products are added afterwards, exactly, in a fixed
-// order.  A row with more than `cap` outliers raises the flag and the product falls back to the
-// two-bf16-piece scheme.
-struct Window {
-    int *S;              // scale exponent per (padded) row
-    uint32_t *cnt;       // outliers recorded per row (may exceed cap: then the flag is set)
-    uint2 *list;         // [row][cap] of (k, fp32 pattern of the rounded value)
-    int *flag;
-    int cap;
-    int *dirty;          // rows that have outliers, in the order they were found; dirty[-1] is their number
-};
-
-// fp16 pattern of r * 2^S for the fp32 pattern r of a value of the format, when that product is a
-// binary16 value (ok = true); otherwise ok = false and 0 is returned.  Infinities and NaN pass.
-__device__ __forceinline__ uint32_t window_half(uint32_t r, int S, bool &ok)
-{
-    const uint32_t a = r & 0x7FFFFFFFu, sign = (r >> 16) & 0x8000u;
-    ok = true;
-    if (a == 0u) return sign;
-    if (a >= 0x7F800000u) return sign | (a > 0x7F800000u ? 0x7E00u : 0x7C00u);
-    const uint32_t as = a + ((uint32_t)S << 23);        // exact: the exponent field stays inside (0, 255)
-    if (as >= 0x47800000u) {                            // 65536 or more
-        ok = false;
-        return 0u;
-    }
-    if (as >= 0x38800000u) {                            // binary16's normal range: at most 11 significant bits
-        ok = (as & 0x1FFFu) == 0u;
-        return ok ? sign | ((as - 0x38000000u) >> 13) : 0u;
-    }
-    const float x = __uint_as_float(as) * 16777216.0f;  // number of 2^-24 steps
-    const uint32_t n = (uint32_t)x;
-    ok = (float)n == x;
-    return ok ? sign | n : 0u;
-}
-
-constexpr int kWinTmin = -24, kWinTmax = 32;            // range of a window's top binade (S = 15 - T)
+constexpr int kWinTmin = 0, kWinTmax = 31;              // range of plane 0's top binade T (S = 15 - T): with
+                                                        // three planes every value of a 1/6/m format, m <= 9, fits
 
 // How element (row, k) of an operand is found in memory.
 enum {
@@ -215,26 +190,7 @@ struct PrepOperand {
     int vec4;
     unsigned nblocks;   // workgroups of this operand: slabs * row groups
     Gather g;
-    Window win;         // win.S != nullptr: single scaled fp16 piece (PS == 0 only)
-};
-
-// An operand as the outlier pass of the single-scaled-piece scheme sees it.
-struct FixOperand {
-    const uint32_t *X;   // the fp32 operand as the caller passed it
-    int64_t ld;
-    int kcontig;
-    Window win;
-};
-
-// What follows the scaled product: the outlier products (flag clear) or the fallback's prepare pass
-// (flag set), in one launch.
-struct TailJob {
-    FixOperand A, B;
-    float *C;
-    int64_t ldc;
-    int M, N;
-    int ftz;
-    const int *flag;
+    Planes pl;          // pl.S != nullptr: scaled fp16 exponent planes (PS == 0, plain matrices only)
 };
 
 // Offset of tap (r, s) seen from the spatial base (by, bx) = (y*mul + off) inside one h x w plane,
@@ -626,43 +582,8 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
         return;
     }
     uint32_t pc[8][P];
-    if (PS == 0 && o.win.S != nullptr) {
-        // scaled single piece: round, scale by the row's power of two, keep what is a binary16 value
-        const int S = o.win.S[row];
-        uint32_t rr8[8];
-        bool plain = true;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            // The common case without branches: r * 2^S (exact, |S| is small) converts to binary16 and
-            // back unchanged -- zeros, values of binary16's normal and denormal range, infinities.
-            // NaN and the outliers (conversion rounds or overflows) take the general routine below.
-            const uint32_t r = quantize_bits<MODE, FTZ>(v[j], p);
-            const float sc = ldexpf(__uint_as_float(r), S);
-            const _Float16 h = static_cast<_Float16>(sc);               // round to nearest even
-            rr8[j] = r;
-            pc[j][0] = (uint32_t)__builtin_bit_cast(uint16_t, h);
-            plain = plain && static_cast<float>(h) == sc;
-        }
-        if (__ballot(!plain) != 0ull) {                    // some lane holds a NaN or an outlier
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t r = rr8[j];
-            bool ok;
-            pc[j][0] = window_half(r, S, ok);
-            if (!ok) {                                    // never for padding (zeros pass)
-                const uint32_t slot = atomicAdd(&o.win.cnt[row], 1u);
-                if (slot == 0u) o.win.dirty[atomicAdd(&o.win.dirty[-1], 1)] = row;
-                if (slot < (uint32_t)o.win.cap)
-                    o.win.list[(size_t)row * o.win.cap + slot] = make_uint2((uint32_t)(k0 + j), r);
-                else
-                    *o.win.flag = 1;
-            }
-        }
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
-    }
+    for (int j = 0; j < 8; ++j) round_and_split<MODE, FTZ, PS>(v[j], p, pc[j]);
 #pragma unroll
     for (int q = 0; q < P; ++q) {
         u32x4 w;
@@ -674,12 +595,259 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
     }
 }
 
-template <int MODE, bool FTZ, int PS, bool TAPS>
-__global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p,
-                                                      Gate gate)
+// Scaled exponent planes of a plain matrix operand (see the top of this file).  Same element-to-thread
+// mapping as prepare_block, so a workgroup covers exactly two units; which of them has elements
+// outside plane 0 is agreed on through two words of LDS, and only then are the other planes of that
+// unit written (the elements that do not belong to a plane are zero there).
+template <int MODE, bool FTZ>
+__device__ __forceinline__ void prepare_scaled_block(const PrepOperand &o, int K, int kblocks, const QuantParams &p,
+                                                     unsigned bid)
 {
-    if (gate_closed(gate)) return;
+    __shared__ uint32_t s_planes[2];
+    const int tid = threadIdx.x;
+    if (tid < 2) s_planes[tid] = 0u;
+    const uint32_t *__restrict__ X = o.X;
+    const int64_t ld = o.ld;
+    const int rows = o.rows;
+    const bool kcontig = o.kcontig != 0;
+    const int nslabs = kcontig ? (kblocks + 1) / 2 : kblocks;
+    const int bx = bid % nslabs, by = bid / nslabs;
+    int row, k0, u;                              // u: which of the workgroup's two units this thread works on
+    if (kcontig) {
+        row = by * 32 + tid / 8;
+        k0 = bx * 64 + (tid % 8) * 8;
+        u = (tid % 8) / 4;
+    } else {
+        row = by * 64 + tid % 64;
+        k0 = bx * 32 + (tid / 64) * 8;
+        u = (tid % 64) / 32;
+    }
+    const bool live = k0 < kblocks * kUnitK;     // k-contiguous slabs cover two k-blocks; the last may be half
+    uint32_t v[8];
+    if (live && kcontig && o.vec4 && row < rows && k0 + 8 <= K) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(X + (size_t)row * ld + k0);
+        const u32x4 lo = __builtin_nontemporal_load(src), hi = __builtin_nontemporal_load(src + 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v[j] = lo[j];
+            v[4 + j] = hi[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = k0 + j;
+            const bool ok = live && row < rows && k < K;
+            const size_t idx = kcontig ? (size_t)row * ld + k : (size_t)k * ld + row;
+            v[j] = ok ? X[idx] : 0u;
+        }
+    }
+    const int S = o.pl.S[row];                   // S covers the padded rows
+    const int w = o.pl.w;
+    uint32_t h0[8], hx[8];                       // plane 0 pattern; pattern in the other plane, bit 16 = above, bit 17 = below
+    uint32_t mine = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // r * 2^S (exact: |S| is small) converts to binary16 and back unchanged <=> it is a binary16
+        // value -- zeros, the normal and the denormal range, infinities.  NaN stays in plane 0 as well.
+        const uint32_t r = quantize_bits<MODE, FTZ>(v[j], p);
+        const float rf = __uint_as_float(r);
+        const float sc = ldexpf(rf, S);
+        const _Float16 h = static_cast<_Float16>(sc);               // round to nearest even
+        const bool plain = static_cast<float>(h) == sc || (r & 0x7FFFFFFFu) > 0x7F800000u;
+        h0[j] = plain ? (uint32_t)__builtin_bit_cast(uint16_t, h) : 0u;
+        hx[j] = 0u;
+        if (!plain) {
+            // too large for plane 0 -> the plane above; bits below 2^-24 -> the plane below (exact there)
+            const bool up = fabsf(sc) >= 65536.0f;
+            const _Float16 g = static_cast<_Float16>(ldexpf(rf, up ? S - w : S + w));
+            hx[j] = (uint32_t)__builtin_bit_cast(uint16_t, g) | (up ? 0x10000u : 0x20000u);
+            mine |= up ? 2u : 4u;
+        }
+    }
+    __syncthreads();                             // s_planes has been cleared
+    if (mine != 0u) atomicOr(&s_planes[u], mine);
+    __syncthreads();
+    if (!live) return;
+    const uint32_t have = s_planes[u];
+    const int rb = row / kUnitRows, rr = row % kUnitRows;
+    const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
+    const size_t at = unit_vec_index(rb, kb, kblocks, 1, 0, c, rr);
+    u32x4 out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = h0[2 * i] | (h0[2 * i + 1] << 16);
+    o.W[at] = out;
+#pragma unroll
+    for (int q = 1; q <= 2; ++q) {
+        if ((have >> q) & 1u) {
+            const uint32_t tag = 0x8000u << q;   // bit 16 (above) or bit 17 (below)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                out[i] = ((hx[2 * i] & tag) ? (hx[2 * i] & 0xFFFFu) : 0u) | ((hx[2 * i + 1] & tag) ? (hx[2 * i + 1] << 16) : 0u);
+            o.W[(size_t)q * o.pl.plane + at] = out;
+        }
+    }
+    const bool leader = kcontig ? (tid / 8 == 0 && tid % 4 == 0) : (tid / 64 == 0 && tid % 32 == 0);
+    if (leader) o.pl.mask[(size_t)rb * kblocks + kb] = (uint8_t)(1u | have);
+}
+
+// One launch prepares both operands of a product (or one: b.nblocks == 0).
+template <int MODE, bool FTZ, int PS, bool TAPS>
+__global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p)
+{
     prepare_block<MODE, FTZ, PS, TAPS>(a, b, K, kblocks, p, blockIdx.x);
+}
+
+template <int MODE, bool FTZ>
+__global__ __launch_bounds__(256) void prepare_scaled_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p)
+{
+    // operands own runs of workgroup ids padded to a multiple of 8, remapped XCD by XCD as in prepare_block
+    const unsigned a_ids = (a.nblocks + 7u) / 8u * 8u;
+    const bool second = blockIdx.x >= a_ids;
+    const PrepOperand &o = second ? b : a;
+    const unsigned lid = blockIdx.x - (second ? a_ids : 0u);
+    const unsigned per_xcd = (o.nblocks + 7u) / 8u;
+    const unsigned bid = (lid % 8u) * per_xcd + lid / 8u;
+    if (bid >= o.nblocks) return;                // workgroup-uniform: before any barrier
+    prepare_scaled_block<MODE, FTZ>(o, K, kblocks, p, bid);
+}
+
+// Epilogue of the scaled scheme for one wave: out (+)= acc * 2^-(S_row + S_col + shift), exactly.  The
+// scale arrays are padded to the tile grid and 16-byte aligned, and a lane's rows come in groups of
+// four: all of a lane's scales are fetched together, with vector loads, ahead of its stores.
+// 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+template <int TM, int TN>
+__device__ __forceinline__ void scaled_store(const floatx16 (&acc)[TM][TN], float *__restrict__ out, int64_t ldc, int M, int N,
+                                             int tm, int tn, int wm, int wn, int lane, const int *__restrict__ Sa,
+                                             const int *__restrict__ Sb, int shift, bool add)
+{
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const int col_in = lane & 31, row_half = (lane >> 5) * 4;
+    int sbv[TN];
+    i32x4 sav[TM][4];                          // all loads first: one wait instead of one per group of rows
+#pragma unroll
+    for (int j = 0; j < TN; ++j) sbv[j] = Sb[(tn * 2 + wn) * (32 * TN) + j * 32 + col_in];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            sav[i][g] = *reinterpret_cast<const i32x4 *>(Sa + (tm * 2 + wm) * (32 * TM) + i * 32 + row_half + g * 8);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
+            if (col < N) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + (v >> 2) * 8 + (v & 3);
+                    if (row < M) {
+                        float *dst = out + (size_t)row * ldc + col;
+                        const float t = ldexpf(acc[i][j][v], -(sav[i][v >> 2][v & 3] + sbv[j] + shift));
+                        *dst = add ? *dst + t : t;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Stores one 32 x 32 MFMA tile of the scaled scheme: dst (+)= acc * 2^-(S_row + S_col + shift), exactly.
+__device__ __forceinline__ void scaled_store_tile(const floatx16 &acc, float *__restrict__ out, int64_t ldc, int M, int N,
+                                                  int row0, int col, const int *__restrict__ Sa, const int *__restrict__ Sb,
+                                                  int shift, bool add)
+{
+    if (col >= N) return;
+    const int sb = Sb[col];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = row0 + (v >> 2) * 8 + (v & 3);
+        if (row < M) {
+            float *dst = out + (size_t)row * ldc + col;
+            const float t = ldexpf(acc[v], -(Sa[row] + sb + shift));
+            *dst = add ? *dst + t : t;
+        }
+    }
+}
+
+// The plane pairs other than (0, 0) of one workgroup tile (2 x 2 waves of TM x TN MFMA tiles, k blocks
+// [kb0, kb1)): per k block, which planes are present among the tile's units of A and of B is read off
+// the masks; for every pair of planes present at some k the units are staged through `stg` (one LDS
+// stage buffer: a unit-row of either operand), multiplied, and added to the tile with the pair's own
+// scale.  Pairs in a fixed order, k ascending inside a pair: the sums are reproducible.  This path is
+// rare and is written for few registers, not for speed: one MFMA tile of every wave at a time (the
+// staging is repeated per tile), so that it costs the main loop neither registers nor occupancy.
+template <int TM, int TN>
+__device__ __forceinline__ void plane_pairs(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
+                                            float *__restrict__ out, int64_t ldc, int M, int N, int kblocks, int kb0,
+                                            int kb1, int tm, int tn, int wm, int wn, const Planes &pa, const Planes &pb,
+                                            u32x4 *stg)
+{
+    constexpr int UA = 2 * TM, UB = 2 * TN, kHalf = 64, kScan = 256;
+    __shared__ uint8_t s_oa[kScan], s_ob[kScan];
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int base = kb0; base < kb1; base += kScan) {
+        const int kb = base + tid;
+        uint32_t oa = 0u, ob = 0u;
+        if (kb < kb1) {
+#pragma unroll
+            for (int i = 0; i < UA; ++i) oa |= pa.mask[(size_t)(tm * UA + i) * kblocks + kb];
+#pragma unroll
+            for (int j = 0; j < UB; ++j) ob |= pb.mask[(size_t)(tn * UB + j) * kblocks + kb];
+        }
+        if (!__syncthreads_or((int)((oa | ob) & 6u))) continue;
+        s_oa[tid] = (uint8_t)oa;
+        s_ob[tid] = (uint8_t)ob;
+        __syncthreads();
+        const int nhere = min(kScan, kb1 - base);
+#pragma clang loop unroll(disable)
+        for (int pr = 1; pr < 9; ++pr) {
+            const int qa = pr / 3, qb = pr % 3;          // plane of A, plane of B (0 main, 1 above, 2 below)
+            // plane above: scale 2^(S - w); below: 2^(S + w)
+            const int shift = (qa == 1 ? -pa.w : (qa == 2 ? pa.w : 0)) + (qb == 1 ? -pb.w : (qb == 2 ? pb.w : 0));
+#pragma clang loop unroll(disable)
+            for (int ij = 0; ij < TM * TN; ++ij) {
+                const int i = ij / TN, j = ij % TN;      // this wave's MFMA tile; the same (i, j) in all four waves
+                floatx16 acc;
+                bool any = false;
+#pragma clang loop unroll(disable)
+                for (int jj = 0; jj < nhere; ++jj) {
+                    if ((((uint32_t)s_oa[jj] >> qa) & ((uint32_t)s_ob[jj] >> qb) & 1u) == 0u) continue;   // workgroup-uniform
+                    const int kbj = base + jj;
+                    if (!any) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+                        any = true;
+                    }
+                    __syncthreads();                      // the previous fill has been read by every wave
+                    // units i, TM + i of A (the two wave rows) and j, TN + j of B (the two wave columns)
+                    for (int q = tid; q < 4 * kUnitVec; q += 256) {
+                        const int which = q / kUnitVec, vv = q % kUnitVec;
+                        const bool isb = which >= 2;
+                        const Planes &pl = isb ? pb : pa;
+                        const int plane = isb ? qb : qa;
+                        const int unit = isb ? (which - 2) * TN + j : which * TM + i;
+                        const size_t uidx = (size_t)((isb ? tn * UB : tm * UA) + unit) * kblocks + kbj;
+                        u32x4 val = {0u, 0u, 0u, 0u};
+                        if (((uint32_t)pl.mask[uidx] >> plane) & 1u)   // only then has this plane of the unit been written
+                            val = (isb ? Bw : Aw)[(size_t)plane * pl.plane + uidx * kUnitVec + vv];
+                        stg[q] = val;
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int kk = 0; kk < 2; ++kk) {
+                        const f16x8 xa = __builtin_bit_cast(f16x8, stg[wm * kUnitVec + kk * kHalf + lane]);
+                        const f16x8 xb = __builtin_bit_cast(f16x8, stg[(2 + wn) * kUnitVec + kk * kHalf + lane]);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa, xb, acc, 0, 0, 0);
+                    }
+                }
+                if (any)
+                    scaled_store_tile(acc, out, ldc, M, N, (tm * 2 + wm) * (32 * TM) + i * 32 + (lane >> 5) * 4,
+                                      (tn * 2 + wn) * (32 * TN) + j * 32 + (lane & 31), pa.S, pb.S, shift, true);
+            }
+        }
+        __syncthreads();                                  // before s_oa / s_ob are overwritten
+    }
 }
 
 // product: Aw / Bw are prepared operands (rows padded to a multiple of kRowPad, k to a multiple
@@ -688,16 +856,16 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
 // into LDS (global_load_lds, 16 bytes per lane) through a ring of NST stage buffers, one barrier
 // per stage.  With SPLIT the k range is cut into parts and each part writes its own M x N slab
 // of partial sums (summed by reduce_kernel).
-// SCALED (single fp16 piece only): the operands carry per-row power-of-two scales Sa / Sb, undone on
-// the way out.
+// SCALED (single fp16 piece only): the operands are exponent planes with per-row power-of-two scales
+// (pa.S / pb.S), undone on the way out; the main loop multiplies plane 0 by plane 0 and the pairs of
+// the other planes that hold anything follow it.
 template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int img,
                                                       int kblocks, int tiles_m, int tiles_n, int kb_per_split,
-                                                      const int *__restrict__ Sa, const int *__restrict__ Sb, Gate gate)
+                                                      Planes pa, Planes pb)
 {
     constexpr int P = pieces_of(PS);
-    if (gate_closed(gate)) return;
     constexpr int UA = 2 * TM, UB = 2 * TN;              // 32-row units per operand in the workgroup tile
     constexpr int kHalf = 64;                            // vectors of one piece of one unit per 16 k
     constexpr int SV = kHalf * KS;                       // ... per stage
@@ -888,35 +1056,12 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
     // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
     float *out = SPLIT ? C + (size_t)split * M * ldc : C;
     const int col_in = lane & 31, row_half = (lane >> 5) * 4;
-    if (SCALED) {
-        // Scaled operands: undo 2^(S_row + S_col), exactly.  The scale arrays are padded to the tile
-        // grid and 16-byte aligned, and a lane's rows come in groups of four: all of a lane's
-        // scales of one row of tiles are fetched together, with vector loads, ahead of its stores.
-        typedef int i32x4 __attribute__((ext_vector_type(4)));
-        int sbv[TN];
-        i32x4 sav[TM][4];                          // all loads first: one wait instead of one per group of rows
-#pragma unroll
-        for (int j = 0; j < TN; ++j) sbv[j] = Sb[(tn * 2 + wn) * (32 * TN) + j * 32 + col_in];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-                sav[i][g] = *reinterpret_cast<const i32x4 *>(Sa + (tm * 2 + wm) * (32 * TM) + i * 32 + row_half + g * 8);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
-                if (col < N) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = row0 + (v >> 2) * 8 + (v & 3);
-                        if (row < M) out[(size_t)row * ldc + col] = ldexpf(acc[i][j][v], -(sav[i][v >> 2][v & 3] + sbv[j]));
-                    }
-                }
-            }
-        }
+    if constexpr (SCALED) {
+        scaled_store<TM, TN>(acc, out, ldc, M, N, tm, tn, wm, wn, lane, pa.S, pb.S, 0, false);
+        // The other plane pairs: almost always there are none, and the workgroup leaves after one look
+        // at the masks.  Kept out of line so that this rarely taken path costs the main loop no registers.
+        static_assert(KS == 2 && P == 1, "the plane pass reads whole 32-k units");
+        plane_pairs<TM, TN>(Aw, Bw, out, ldc, M, N, kblocks, kb0, kb1, tm, tn, wm, wn, pa, pb, st0);
         return;
     }
 #pragma unroll
@@ -942,9 +1087,8 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
 
 // C[r][c] = sum over the k parts of part[s][r][c]  (parts are dense M x N slabs)
 __global__ __launch_bounds__(256) void reduce_kernel(const float *__restrict__ part, int nsplit, float *__restrict__ C,
-                                                     int M, int N, int64_t ldc, int img, Gate gate)
+                                                     int M, int N, int64_t ldc, int img)
 {
-    if (gate_closed(gate)) return;
     const size_t total = (size_t)M * N;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         float s = 0.0f;
@@ -977,7 +1121,7 @@ static constexpr size_t lds_bytes(int tm, int tn, int pieces, int ks, int nst)
 
 // Pipeline shape per piece scheme and tile shape: k16 steps per stage, and as many stage buffers (at
 // most FMT_GEMM_NST, at least two) as fit the tile's share of the 160 KiB of LDS -- all of it for the
-// large tiles, half for 128 x 128 (two resident workgroups), a quarter for 64 x 64. 
+// large tiles, half for 128 x 128 (two resident workgroups), a quarter for 64 x 64.
 static constexpr int pipe_ks(int pieces) { return pieces == 1 ? FMT_GEMM_KS : FMT_GEMM_KS_MULTI; }
 static constexpr int pipe_nst(int tm, int tn, int pieces, int ks)
 {
@@ -1039,7 +1183,7 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
 
 template <int PS, int TM, int TN, bool SPLIT, bool SCHED, bool SCALED>
 static int launch_product_v2(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
-                            int nsplit, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
+                            int nsplit, hipStream_t stream, const Planes &pa, const Planes &pb)
 {
     constexpr int KS = Pipe<PS, TM, TN>::ks, NST = Pipe<PS, TM, TN>::nst;
     if constexpr (lds_bytes(TM, TN, pieces_of(PS), KS, NST) > 160 * 1024) {
@@ -1051,7 +1195,7 @@ static int launch_product_v2(const u32x4 *Aw, const u32x4 *Bw, float *out, int M
         const int kb_per = (kblocks + nsplit - 1) / nsplit;
         auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED, SCALED>;
         hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), 0, stream, Aw, Bw, out, M, N, ld, img,
-                           kblocks, tiles_m, tiles_n, kb_per, Sa, Sb, gate);
+                           kblocks, tiles_m, tiles_n, kb_per, pa, pb);
         FMT_HIP_CHECK(hipGetLastError());
         return FMT_OK;
     }
@@ -1059,32 +1203,30 @@ static int launch_product_v2(const u32x4 *Aw, const u32x4 *Bw, float *out, int M
 
 template <int PS, int TM, int TN, bool SPLIT, bool SCHED>
 static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
-                            int nsplit, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
+                            int nsplit, hipStream_t stream, const Planes &pa, const Planes &pb)
 {
     if constexpr (PS == 0) {
-        if (Sa != nullptr)
-            return launch_product_v2<PS, TM, TN, SPLIT, SCHED, true>(Aw, Bw, out, M, N, ld, img, kblocks, nsplit, stream, Sa,
-                                                                    Sb, gate);
+        if (pa.S != nullptr)
+            return launch_product_v2<PS, TM, TN, SPLIT, SCHED, true>(Aw, Bw, out, M, N, ld, img, kblocks, nsplit, stream, pa, pb);
     }
-    return launch_product_v2<PS, TM, TN, SPLIT, SCHED, false>(Aw, Bw, out, M, N, ld, img, kblocks, nsplit, stream, Sa, Sb,
-                                                             gate);
+    return launch_product_v2<PS, TM, TN, SPLIT, SCHED, false>(Aw, Bw, out, M, N, ld, img, kblocks, nsplit, stream, pa, pb);
 }
 
 template <int PS, int TM, int TN>
 static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int img, int kblocks,
-                          const Plan &plan, float *part, hipStream_t stream, const int *Sa, const int *Sb, Gate gate)
+                          const Plan &plan, float *part, hipStream_t stream, const Planes &pa, const Planes &pb)
 {
     if (plan.nsplit == 1) {
-        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, Sa, Sb, gate)
-                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, Sa, Sb, gate);
+        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, pa, pb)
+                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, pa, pb);
     }
     int rc = plan.sched
-                 ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream, Sa, Sb, gate)
-                 : launch_product_v<PS, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream, Sa, Sb, gate);
+                 ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream, pa, pb)
+                 : launch_product_v<PS, TM, TN, true, false>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream, pa, pb);
     if (rc != FMT_OK) return rc;
     const size_t total = (size_t)M * N;
     const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
-    hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc, img, gate);
+    hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc, img);
     FMT_HIP_CHECK(hipGetLastError());
     return FMT_OK;
 }
@@ -1107,122 +1249,80 @@ struct OutSpec {
     int img;
 };
 
-// Workspace layout of one product: prepared operands, split-k partial sums, pre-rounded tensors.
-struct Layout {
-    Plan plan;
-    int kblocks, units_m, units_n;
-    size_t a_vec, b_vec, part_bytes, pre_a, pre_b;
-    size_t bytes() const { return (a_vec + b_vec) * sizeof(u32x4) + part_bytes + pre_a + pre_b; }
+// How a format's values reach the matrix cores: ps = piece scheme (0: one fp16 piece, 1-3: that many
+// bf16 pieces); scaled: ps == 0 with per-row scales and exponent planes (1/6/8 and 1/6/9).
+struct Scheme {
+    int ps;
+    bool scaled;
 };
 
-static int make_layout(int M, int N, int K, int P, const OperandSpec &sa, const OperandSpec &sb, Layout *L)
+// 0: never scaled planes, 1: whenever the format allows, 2: by size.  Environment override for tests and tuning.
+static int window_mode()
 {
-    int cus = 0;
-    int rc = device_cu_count(&cus);
-    if (rc != FMT_OK) return rc;
-    L->kblocks = (K + kUnitK - 1) / kUnitK;
-    L->plan = make_plan(M, N, L->kblocks, cus, P);
-    L->units_m = (M + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
-    L->units_n = (N + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows);
-    L->a_vec = (size_t)L->units_m * L->kblocks * P * kUnitVec;
-    L->b_vec = (size_t)L->units_n * L->kblocks * P * kUnitVec;
-    L->part_bytes = L->plan.nsplit > 1 ? ((size_t)L->plan.nsplit * M * N * sizeof(float) + 15) / 16 * 16 : 0;
-    L->pre_a = sa.pre_elems ? ((size_t)(sa.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
-    L->pre_b = sb.pre_elems ? ((size_t)(sb.pre_elems + 1) * ((P + 1) / 2) * sizeof(uint32_t) + 15) / 16 * 16 : 0;
-    if ((int64_t)L->kblocks * L->units_m + (int64_t)L->kblocks * L->units_n >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
+    if (const char *env = getenv("FMT_GEMM_WINDOW")) return env[0] == '0' ? 0 : (env[0] == '1' ? 1 : 2);
+    return 2;
+}
+
+static bool planes_possible(fmt_format_t f) { return f.e == 6 && f.m >= 8 && f.m <= 9; }
+
+static Scheme scheme_of(fmt_format_t f, bool want_planes)
+{
+    if (want_planes && planes_possible(f)) return Scheme{0, true};
+    // one fp16 piece for formats inside binary16, else 1-3 bf16 pieces by significand width
+    return Scheme{f.m <= 7 ? 1 : (f.e <= 5 && f.m <= 10 ? 0 : (f.m <= 15 ? 2 : 3)), false};
+}
+
+// Memory layout of one prepared operand (`rows` x K after op(), padded to kRowPad rows and 32 k):
+//   [pieces]  units x kblocks x P units of 128 vectors; with planes: three planes of units x kblocks units
+//   [S]       with planes: one int per padded row
+//   [mask]    with planes: one byte per unit
+// every part 256-byte aligned.
+struct OperandLayout {
+    Scheme sch;
+    int w;                       // planes: binades per plane
+    int rows, kblocks, units;
+    size_t plane_vec, s_off, mask_off, bytes;
+};
+
+static int operand_layout(int64_t rows, int64_t K, Scheme sch, int m, OperandLayout *L)
+{
+    auto up256 = [](size_t b) { return (b + 255) / 256 * 256; };
+    L->sch = sch;
+    L->w = 40 - m;
+    L->rows = (int)rows;
+    L->kblocks = (int)((K + kUnitK - 1) / kUnitK);
+    L->units = (int)((rows + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows));
+    if ((int64_t)L->kblocks * L->units >= ((int64_t)1 << 30)) return FMT_ERR_SHAPE;
+    const int P = pieces_of(sch.ps);
+    L->plane_vec = (size_t)L->units * L->kblocks * P * kUnitVec;
+    const size_t piece_bytes = up256(L->plane_vec * sizeof(u32x4) * (sch.scaled ? 3 : 1));
+    L->s_off = piece_bytes;
+    L->mask_off = L->s_off + (sch.scaled ? up256((size_t)L->units * kUnitRows * sizeof(int)) : 0);
+    L->bytes = L->mask_off + (sch.scaled ? up256((size_t)L->units * L->kblocks) : 0);
     return FMT_OK;
 }
 
-// Prepare + product (+ reduction) of one piece scheme in the workspace at `ws`.  wa / wb: per-row
-// scales and outlier records of the scaled single-piece scheme (PS == 0), or nullptr.
-constexpr unsigned kTailGrid = 2048;
-template <int MODE, bool FTZ>
-__global__ void window_tail_kernel(TailJob job, PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p,
-                                   unsigned prep_blocks);
+// A prepared operand in memory at `base`.
+struct OperandView {
+    u32x4 *W;
+    Planes pl;
+};
 
-template <int MODE, bool FTZ, int PS>
-static int run_core(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
-                    const QuantParams &p, hipStream_t stream, const Layout &L, char *ws, const Window *wa,
-                    const Window *wb, Gate gate, const TailJob *tail = nullptr)
+static OperandView view_of(void *base, const OperandLayout &L)
 {
-    const int kblocks = L.kblocks;
-    const Plan &plan = L.plan;
-    u32x4 *Aw = reinterpret_cast<u32x4 *>(ws);
-    u32x4 *Bw = Aw + L.a_vec;
-    float *part = reinterpret_cast<float *>(Bw + L.b_vec);
-    uint32_t *pre_a_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(part) + L.part_bytes);
-    uint32_t *pre_b_buf = reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(pre_a_buf) + L.pre_a);
-
-    auto operand = [&](const OperandSpec &sp, int rows, int units, u32x4 *W, uint32_t *pre_buf, const Window *win) {
-        PrepOperand o;
-        o.X = reinterpret_cast<const uint32_t *>(sp.X);
-        o.g = sp.g;
-        if (sp.pre_elems > 0) {
-            const int n = (int)sp.pre_elems;
-            const int grid = (n + 1023) / 1024 < 4096 ? (n + 1023) / 1024 : 4096;
-            hipLaunchKernelGGL((round_split_kernel<MODE, FTZ, PS>), dim3(grid), dim3(256), 0, stream, o.X, pre_buf, n, p);
-            o.X = pre_buf;
-            o.g.pre = 1;
-            o.g.plane = n + 1;
-            const bool simple = o.g.den_y == 1 && o.g.den_x == 1 && o.g.R * o.g.S <= 32;
-            o.g.fast = simple && o.g.kind == kSrcPatchRows && !sp.kcontig ? 1
-                       : simple && o.g.kind == kSrcPatchK && sp.kcontig && o.g.tap > 0 ? 2 : 0;
-        }
-        o.W = W;
-        o.ld = sp.ld;
-        o.rows = rows;
-        o.kcontig = sp.kcontig;
-        o.vec4 = (reinterpret_cast<uintptr_t>(sp.X) & 15) == 0 && sp.ld % 4 == 0;
-        o.nblocks = o.g.fast == 2 ? (unsigned)((kblocks + 7) / 8) * units            // 32 taps x 256 positions each
-                    : sp.kcontig ? (unsigned)((kblocks + 1) / 2) * units
-                                 : (unsigned)kblocks * (units / (o.g.fast ? 2 * kFastRows : 2));
-        o.win = win ? *win : Window{nullptr, nullptr, nullptr, nullptr, 0, nullptr};
-        return o;
-    };
-    const PrepOperand oa = operand(sa, M, L.units_m, Aw, pre_a_buf, wa);
-    const PrepOperand ob = operand(sb, N, L.units_n, Bw, pre_b_buf, wb);
-    FMT_HIP_CHECK(hipGetLastError());
-    const unsigned prep_grid = (oa.nblocks + 7u) / 8u * 8u + (ob.nblocks + 7u) / 8u * 8u;
-    if (PS == 2 && tail != nullptr) {
-        // the fallback's prepare pass shares its launch with the outlier pass of the scaled scheme
-        const unsigned grid = prep_grid < kTailGrid ? prep_grid : kTailGrid;
-        hipLaunchKernelGGL((window_tail_kernel<MODE, FTZ>), dim3(grid), dim3(256), 0, stream, *tail, oa, ob, K, kblocks, p,
-                           prep_grid);
-    } else {
-        if (oa.g.fast == 2 || ob.g.fast == 2)
-            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS, true>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K,
-                               kblocks, p, gate);
-        else
-            hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS, false>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K,
-                               kblocks, p, gate);
+    char *b = static_cast<char *>(base);
+    OperandView v;
+    v.W = reinterpret_cast<u32x4 *>(b);
+    v.pl = Planes{nullptr, nullptr, 0, L.w};
+    if (L.sch.scaled) {
+        v.pl.S = reinterpret_cast<int *>(b + L.s_off);
+        v.pl.mask = reinterpret_cast<uint8_t *>(b + L.mask_off);
+        v.pl.plane = L.plane_vec;
     }
-    FMT_HIP_CHECK(hipGetLastError());
-    const int *Sa = wa ? wa->S : nullptr, *Sb = wb ? wb->S : nullptr;
-#define FMT_PRODUCT(TMV, TNV) \
-    launch_product<PS, TMV, TNV>(Aw, Bw, out.C, M, N, out.ldc, out.img, kblocks, plan, part, stream, Sa, Sb, gate)
-    if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
-    if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
-    if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
-    if (plan.tm == 2 && plan.tn == 2) return FMT_PRODUCT(2, 2);
-    return FMT_PRODUCT(1, 1);
-#undef FMT_PRODUCT
+    return v;
 }
 
-template <int MODE, bool FTZ, int PS>
-static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
-               const QuantParams &p, hipStream_t stream)
-{
-    Layout L;
-    int rc = make_layout(M, N, K, pieces_of(PS), sa, sb, &L);
-    if (rc != FMT_OK) return rc;
-    Scratch s;
-    rc = get_scratch(stream, 0, L.bytes(), &s);
-    if (rc != FMT_OK) return rc;
-    return run_core<MODE, FTZ, PS>(M, N, K, sa, sb, out, p, stream, L, static_cast<char *>(s.gemm_ws), nullptr, nullptr,
-                                   Gate{nullptr, 0});
-}
-
-// ---- single scaled fp16 piece: row statistics, outlier products, host logic ----------------------
+// ---- exponent planes: the scale of every row -------------------------------------------------
 
 struct StatOperand {
     const uint32_t *X;
@@ -1231,38 +1331,29 @@ struct StatOperand {
     int rows_pad;
     int kcontig;
     int *S;
-    uint32_t *cnt;
-    int *dirty;
     unsigned nblocks;
 };
 
-// Picks each row's window from the binades of a sample of its elements (every kstep-th slab of k).
-// A window whose top binade is T holds the normal values of binades [T - wid, T] exactly, and the
-// format's denormal values (multiples of 2^(Emin-m)) exactly iff T <= 9 - m.  With hi the largest
-// binade seen (+1: rounding may carry) and lo the smallest binade of a value that is normal in the
-// format, every T in [hi + 1, lo + wid] leaves no outliers among the elements seen:
-//   - a denormal value was seen: T = 9 - m, the highest window that keeps the denormals (an exact
-//     bound, unseen elements cannot lower it further; gradient tensors live here);
+// Picks each row's scale S = 15 - T, T the top binade of plane 0, from the binades of a sample of its
+// elements (every kstep-th slab of k).  Plane 0 with top T holds the normal values of binades
+// [T - wid, T] exactly, and the format's denormal values (multiples of 2^(Emin-m)) exactly iff
+// T <= 9 - m.  With hi the largest binade seen (+1: rounding may carry) and lo the smallest binade of
+// a value that is normal in the format, every T in [hi + 1, lo + wid] keeps all elements seen in plane 0:
+//   - a denormal value was seen: T = 9 - m, the highest choice that keeps the denormals (gradient
+//     tensors live here);
 //   - otherwise up to three binades above hi + 1 (not beyond the middle of [hi + 1, lo + wid]),
 //     which leaves room on both sides for the elements the sample did not see; if the row spans
-//     more than a window, T = lo + wid (the small values stay, the large ones become outliers).
-// Any choice is correct -- what falls outside becomes an outlier -- the choice only decides how many
-// there are.  Also clears the row's outlier count and, once, the flag.
-__global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int K, int kstep_a, int kstep_b,
-                                                           int emin, int m, int *flag)
+//     more than a plane, T = lo + wid (the small values stay, the large ones go to the plane above).
+// Any T in [kWinTmin, kWinTmax] is correct -- what does not fit plane 0 goes to another plane -- the
+// choice only decides how often the other planes are needed, which is why a sample suffices.
+__global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int K, int kstep, int emin, int m)
 {
     __shared__ int s_hi[8][32], s_lo[8][32];
     const int tid = threadIdx.x;
-    if (blockIdx.x == 0 && tid == 0) {
-        *flag = 0;
-        a.dirty[-1] = 0;
-        b.dirty[-1] = 0;
-    }
     const bool second = blockIdx.x >= a.nblocks;
     const StatOperand &o = second ? b : a;
     const int by = blockIdx.x - (second ? a.nblocks : 0u);
-    const int kstep = second ? kstep_b : kstep_a;
-    const int wid = 39 - m;                       // binades a scaled binary16 holds with m + 1 significant bits
+    const int wid = 39 - m;                       // binades below the top one that a plane holds with m + 1 significant bits
     int hi = -1000, lo = 1000;
     auto look = [&](uint32_t u) {
         const uint32_t ab = u & 0x7FFFFFFFu;
@@ -1318,183 +1409,158 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
     }
     T = max(kWinTmin, min(kWinTmax, T));
     o.S[row] = 15 - T;
-    o.cnt[row] = 0u;
 }
 
-__device__ __forceinline__ uint32_t fix_fetch(const FixOperand &o, int row, int k)
+// ---- operand preparation ------------------------------------------------------------------------
+
+// Launches what turns the described operands into prepared ones: the pre-rounding of a tensor that is
+// gathered from, the row scales of exponent planes, and the prepare kernel.  sb == nullptr: one operand.
+// pre_a / pre_b: room for the pre-rounded tensors (only for specs with pre_elems > 0).
+template <int MODE, bool FTZ, int PS>
+static int prepare_operands(const OperandSpec &sa, const OperandLayout &la, const OperandView &va, uint32_t *pre_a,
+                            const OperandSpec *sb, const OperandLayout *lb, const OperandView *vb, uint32_t *pre_b, int K,
+                            fmt_format_t f, const QuantParams &p, hipStream_t stream)
 {
-    return o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
-}
-
-// The recorded outliers of one row, sorted by k (at most `cap`, a handful): a fixed order makes the
-// corrected sums reproducible whatever order the atomics recorded them in.
-template <int CAP>
-__device__ __forceinline__ int sorted_outliers(const Window &w, int row, uint32_t (&k)[CAP], uint32_t (&v)[CAP])
-{
-    const int n = min((int)w.cnt[row], CAP);
-    for (int t = 0; t < n; ++t) {
-        const uint2 e = w.list[(size_t)row * CAP + t];
-        int q = t;
-        while (q > 0 && k[q - 1] > e.x) {
-            k[q] = k[q - 1];
-            v[q] = v[q - 1];
-            --q;
-        }
-        k[q] = e.x;
-        v[q] = e.y;
-    }
-    return n;
-}
-
-constexpr int kWinCap = 8;                        // outliers recorded per row before the fallback takes over
-
-// Adds the products that the scaled pieces left out, each output element by exactly one thread and
-// in a fixed order (A's outliers of its row by increasing k, then B's outliers of its column by
-// increasing k), so the corrected sums are reproducible.  Work items are (row with outliers, chunk of
-// 256 columns) and (column with outliers, chunk of 256 rows), taken from the lists the prepare kernel
-// filled; an element whose row has outliers belongs to the row item, also for its column's outliers.
-// A product a * b with a an outlier is added whatever b is; a product with only b an outlier takes a
-// from the operand if it lies inside its row's window (if not it is an outlier itself and was added
-// with the row).  fp32 fused multiply-add: the product is exact either way, one rounding per
-// accumulation as in the product kernel.
-__device__ __forceinline__ void outlier_pass(const FixOperand &A, const FixOperand &B, float *__restrict__ C, int64_t ldc,
-                                             int M, int N, const QuantParams &p, int ftz)
-{
-    const int nda = A.win.dirty[-1], ndb = B.win.dirty[-1];
-    const int cn = (N + 255) / 256, cm = (M + 255) / 256;
-    const long long row_items = (long long)nda * cn, total = row_items + (long long)ndb * cm;
-    uint32_t k[kWinCap], v[kWinCap];
-    for (long long t = blockIdx.x; t < total; t += gridDim.x) {
-        if (t < row_items) {
-            const int i = A.win.dirty[t / cn], j = (int)(t % cn) * 256 + (int)threadIdx.x;
-            if (j >= N) continue;
-            const int n = sorted_outliers<kWinCap>(A.win, i, k, v);
-            float c = C[(size_t)i * ldc + j];
-            for (int q = 0; q < n; ++q) {
-                const uint32_t bq = quantize_bits_rt(fix_fetch(B, j, (int)k[q]), p, ftz != 0);
-                c = __fmaf_rn(__uint_as_float(v[q]), __uint_as_float(bq), c);
-            }
-            if (B.win.cnt[j] != 0u) {                     // this column's outliers too (rare)
-                const int S = A.win.S[i];
-                const int nb = sorted_outliers<kWinCap>(B.win, j, k, v);
-                for (int q = 0; q < nb; ++q) {
-                    const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)k[q]), p, ftz != 0);
-                    bool inside;
-                    (void)window_half(aq, S, inside);
-                    if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(v[q]), c);
-                }
-            }
-            C[(size_t)i * ldc + j] = c;
-        } else {
-            const long long u = t - row_items;
-            const int j = B.win.dirty[u / cm], i = (int)(u % cm) * 256 + (int)threadIdx.x;
-            if (i >= M || A.win.cnt[i] != 0u) continue;   // rows with outliers were done as row items
-            const int n = sorted_outliers<kWinCap>(B.win, j, k, v);
-            const int S = A.win.S[i];
-            float c = C[(size_t)i * ldc + j];
-            for (int q = 0; q < n; ++q) {
-                const uint32_t aq = quantize_bits_rt(fix_fetch(A, i, (int)k[q]), p, ftz != 0);
-                bool inside;
-                (void)window_half(aq, S, inside);
-                if (inside) c = __fmaf_rn(__uint_as_float(aq), __uint_as_float(v[q]), c);
-            }
-            C[(size_t)i * ldc + j] = c;
-        }
-    }
-}
-
-// The launch after the scaled product.  Flag clear (no row overflowed its outlier list): the outlier
-// pass.  Flag set: the prepare pass of the two-piece fallback, its blocks walked by a capped grid.
-template <int MODE, bool FTZ>
-__global__ __launch_bounds__(256) void window_tail_kernel(TailJob job, PrepOperand a, PrepOperand b, int K, int kblocks,
-                                                          QuantParams p, unsigned prep_blocks)
-{
-    if (*job.flag == 0) {
-        outlier_pass(job.A, job.B, job.C, job.ldc, job.M, job.N, p, job.ftz);
-        return;
-    }
-    for (unsigned block = blockIdx.x; block < prep_blocks; block += gridDim.x)
-        prepare_block<MODE, FTZ, 2>(a, b, K, kblocks, p, block);
-}
-
-// 0: never, 1: always (when the format allows), 2: by size.  Environment override for tests and tuning.
-static int window_mode()
-{
-    if (const char *env = getenv("FMT_GEMM_WINDOW")) return env[0] == '0' ? 0 : (env[0] == '1' ? 1 : 2);
-    return 2;
-}
-
-// Product of two plain matrices in a format with e == 6 and 8 <= m <= 10: scaled single fp16 piece
-// with outlier products, and the two-bf16-piece scheme as the fallback chosen on the device.
-template <int MODE, bool FTZ>
-static int run_window(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
-                      fmt_format_t f, const QuantParams &p, hipStream_t stream)
-{
-    Layout L1, L2;
-    int rc = make_layout(M, N, K, 1, sa, sb, &L1);
-    if (rc != FMT_OK) return rc;
-    rc = make_layout(M, N, K, 2, sa, sb, &L2);
-    if (rc != FMT_OK) return rc;
-    const int mp = L1.units_m * kUnitRows, np = L1.units_n * kUnitRows;       // padded rows
-    auto align16 = [](size_t b) { return (b + 15) / 16 * 16; };
-    const size_t s_bytes = align16((size_t)(mp + np) * sizeof(int)), c_bytes = align16((size_t)(mp + np) * sizeof(uint32_t));
-    const size_t l_bytes = align16((size_t)(mp + np) * kWinCap * sizeof(uint2));
-    const size_t d_bytes = align16((size_t)(mp + np + 2) * sizeof(int));
-    Scratch s;
-    rc = get_scratch(stream, 0, L1.bytes() + L2.bytes() + s_bytes + c_bytes + l_bytes + d_bytes + 16, &s);
-    if (rc != FMT_OK) return rc;
-    char *ws1 = static_cast<char *>(s.gemm_ws), *ws2 = ws1 + L1.bytes(), *wx = ws2 + L2.bytes();
-    int *S = reinterpret_cast<int *>(wx);
-    uint32_t *cnt = reinterpret_cast<uint32_t *>(wx + s_bytes);
-    uint2 *list = reinterpret_cast<uint2 *>(wx + s_bytes + c_bytes);
-    int *dirty = reinterpret_cast<int *>(wx + s_bytes + c_bytes + l_bytes);      // [count, mp rows][count, np rows]
-    int *flag = reinterpret_cast<int *>(wx + s_bytes + c_bytes + l_bytes + d_bytes);
-    const Window wa{S, cnt, list, flag, kWinCap, dirty + 1};
-    const Window wb{S + mp, cnt + mp, list + (size_t)mp * kWinCap, flag, kWinCap, dirty + 1 + mp + 1};
-
-    const int bias = (1 << (f.e - 1)) - 1, emin = 1 - bias;
-    auto stat = [&](const OperandSpec &sp, int rows, int rows_pad, const Window &w) {
-        StatOperand o;
+    const int kblocks = la.kblocks;
+    const bool scaled = la.sch.scaled;
+    auto operand = [&](const OperandSpec &sp, const OperandLayout &L, const OperandView &v, uint32_t *pre_buf) {
+        PrepOperand o;
         o.X = reinterpret_cast<const uint32_t *>(sp.X);
+        o.g = sp.g;
+        if (sp.pre_elems > 0) {
+            const int n = (int)sp.pre_elems;
+            const int grid = (n + 1023) / 1024 < 4096 ? (n + 1023) / 1024 : 4096;
+            hipLaunchKernelGGL((round_split_kernel<MODE, FTZ, PS>), dim3(grid), dim3(256), 0, stream, o.X, pre_buf, n, p);
+            o.X = pre_buf;
+            o.g.pre = 1;
+            o.g.plane = n + 1;
+            const bool simple = o.g.den_y == 1 && o.g.den_x == 1 && o.g.R * o.g.S <= 32;
+            o.g.fast = simple && o.g.kind == kSrcPatchRows && !sp.kcontig ? 1
+                       : simple && o.g.kind == kSrcPatchK && sp.kcontig && o.g.tap > 0 ? 2 : 0;
+        }
+        o.W = v.W;
         o.ld = sp.ld;
-        o.rows = rows;
-        o.rows_pad = rows_pad;
+        o.rows = L.rows;
         o.kcontig = sp.kcontig;
-        o.S = w.S;
-        o.cnt = w.cnt;
-        o.dirty = w.dirty;
-        o.nblocks = (unsigned)(rows_pad / 32);
+        o.vec4 = (reinterpret_cast<uintptr_t>(sp.X) & 15) == 0 && sp.ld % 4 == 0;
+        o.nblocks = o.g.fast == 2 ? (unsigned)((kblocks + 7) / 8) * L.units            // 32 taps x 256 positions each
+                    : sp.kcontig ? (unsigned)((kblocks + 1) / 2) * L.units
+                                 : (unsigned)kblocks * (L.units / (o.g.fast ? 2 * kFastRows : 2));
+        o.pl = v.pl;
         return o;
     };
-    const StatOperand ta = stat(sa, M, mp, wa), tb = stat(sb, N, np, wb);
-    // a sample of at most 4 slabs of 64 k per row (256 elements): the window only has to be a good guess
-    const int slabs = (K + 63) / 64;
-    const int kstep_a = (slabs + 3) / 4, kstep_b = kstep_a;
-    hipLaunchKernelGGL(window_stats_kernel, dim3(ta.nblocks + tb.nblocks), dim3(256), 0, stream, ta, tb, K, kstep_a,
-                       kstep_b, emin, f.m, flag);
+    const PrepOperand oa = operand(sa, la, va, pre_a);
+    PrepOperand ob = oa;
+    ob.nblocks = 0u;
+    if (sb != nullptr) ob = operand(*sb, *lb, *vb, pre_b);
     FMT_HIP_CHECK(hipGetLastError());
+    const unsigned prep_grid = (oa.nblocks + 7u) / 8u * 8u + (ob.nblocks + 7u) / 8u * 8u;
+    if (scaled) {
+        if constexpr (PS == 0 && MODE == kModeMagic) {
+            auto stat = [&](const PrepOperand &o, const OperandLayout &L, bool present) {
+                StatOperand t;
+                t.X = o.X;
+                t.ld = o.ld;
+                t.rows = L.rows;
+                t.rows_pad = L.units * kUnitRows;
+                t.kcontig = o.kcontig;
+                t.S = o.pl.S;
+                t.nblocks = present ? (unsigned)L.units : 0u;
+                return t;
+            };
+            const StatOperand ta = stat(oa, la, true), tb = stat(ob, sb ? *lb : la, sb != nullptr);
+            // a sample of at most 4 slabs of 64 k per row (256 elements): the scale only has to be a good guess
+            const int slabs = (K + 63) / 64;
+            const int bias = (1 << (f.e - 1)) - 1;
+            hipLaunchKernelGGL(window_stats_kernel, dim3(ta.nblocks + tb.nblocks), dim3(256), 0, stream, ta, tb, K,
+                               (slabs + 3) / 4, 1 - bias, f.m);
+            FMT_HIP_CHECK(hipGetLastError());
+            hipLaunchKernelGGL((prepare_scaled_kernel<MODE, FTZ>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p);
+        } else {
+            return FMT_ERR_FORMAT;               // planes exist for e == 6 formats only (rounding mode kModeMagic)
+        }
+    } else if (oa.g.fast == 2 || ob.g.fast == 2) {
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS, true>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p);
+    } else {
+        hipLaunchKernelGGL((prepare_kernel<MODE, FTZ, PS, false>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p);
+    }
+    FMT_HIP_CHECK(hipGetLastError());
+    return FMT_OK;
+}
 
-    // The flag is final once the scaled prepare has run; every later kernel of either scheme checks it.
-    // (Launching the fallback's kernels on a side stream so that their empty launches overlap the
-    // product was tried: their workgroups queue between the product's and slow it by half.)
-    const Gate fast{flag, 0}, slow{flag, 1};
-    rc = run_core<MODE, FTZ, 0>(M, N, K, sa, sb, out, p, stream, L1, ws1, &wa, &wb, fast);
+// Room for the split-k partial sums of a plan.
+static size_t part_bytes_of(const Plan &plan, int M, int N)
+{
+    return plan.nsplit > 1 ? ((size_t)plan.nsplit * M * N * sizeof(float) + 255) / 256 * 256 : 0;
+}
+
+template <int PS>
+static int product_of_views(const OperandView &va, const OperandView &vb, int M, int N, int kblocks, const OutSpec &out,
+                            const Plan &plan, float *part, hipStream_t stream)
+{
+#define FMT_PRODUCT(TMV, TNV) \
+    launch_product<PS, TMV, TNV>(va.W, vb.W, out.C, M, N, out.ldc, out.img, kblocks, plan, part, stream, va.pl, vb.pl)
+    if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
+    if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
+    if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
+    if (plan.tm == 2 && plan.tn == 2) return FMT_PRODUCT(2, 2);
+    return FMT_PRODUCT(1, 1);
+#undef FMT_PRODUCT
+}
+
+static int product_dispatch(int ps, const OperandView &va, const OperandView &vb, int M, int N, int kblocks,
+                            const OutSpec &out, const Plan &plan, float *part, hipStream_t stream)
+{
+    switch (ps) {
+        case 0: return product_of_views<0>(va, vb, M, N, kblocks, out, plan, part, stream);
+        case 1: return product_of_views<1>(va, vb, M, N, kblocks, out, plan, part, stream);
+        case 2: return product_of_views<2>(va, vb, M, N, kblocks, out, plan, part, stream);
+        default: return product_of_views<3>(va, vb, M, N, kblocks, out, plan, part, stream);
+    }
+}
+
+// Prepare + product (+ reduction) of described operands in library scratch.
+template <int MODE, bool FTZ, int PS>
+static int run(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out, fmt_format_t f,
+               const QuantParams &p, hipStream_t stream, bool scaled)
+{
+    const Scheme sch{PS, scaled};
+    OperandLayout la, lb;
+    int rc = operand_layout(M, K, sch, f.m, &la);
     if (rc != FMT_OK) return rc;
-    const FixOperand fa{reinterpret_cast<const uint32_t *>(sa.X), sa.ld, sa.kcontig, wa};
-    const FixOperand fb{reinterpret_cast<const uint32_t *>(sb.X), sb.ld, sb.kcontig, wb};
-    const TailJob tail{fa, fb, out.C, out.ldc, M, N, FTZ ? 1 : 0, flag};
-    return run_core<MODE, FTZ, 2>(M, N, K, sa, sb, out, p, stream, L2, ws2, nullptr, nullptr, slow, &tail);
+    rc = operand_layout(N, K, sch, f.m, &lb);
+    if (rc != FMT_OK) return rc;
+    int cus = 0;
+    rc = device_cu_count(&cus);
+    if (rc != FMT_OK) return rc;
+    const Plan plan = make_plan(M, N, la.kblocks, cus, pieces_of(PS));
+    auto up256 = [](size_t b) { return (b + 255) / 256 * 256; };
+    const int words = (pieces_of(PS) + 1) / 2;
+    const size_t pre_a = sa.pre_elems ? up256((size_t)(sa.pre_elems + 1) * words * sizeof(uint32_t)) : 0;
+    const size_t pre_b = sb.pre_elems ? up256((size_t)(sb.pre_elems + 1) * words * sizeof(uint32_t)) : 0;
+    const size_t part = part_bytes_of(plan, M, N);
+    Scratch s;
+    rc = get_scratch(stream, 0, la.bytes + lb.bytes + part + pre_a + pre_b, &s);
+    if (rc != FMT_OK) return rc;
+    char *ws = static_cast<char *>(s.gemm_ws);
+    const OperandView va = view_of(ws, la), vb = view_of(ws + la.bytes, lb);
+    float *partp = reinterpret_cast<float *>(ws + la.bytes + lb.bytes);
+    uint32_t *pa = reinterpret_cast<uint32_t *>(ws + la.bytes + lb.bytes + part);
+    uint32_t *pb = reinterpret_cast<uint32_t *>(ws + la.bytes + lb.bytes + part + pre_a);
+    rc = prepare_operands<MODE, FTZ, PS>(sa, la, va, pa, &sb, &lb, &vb, pb, K, f, p, stream);
+    if (rc != FMT_OK) return rc;
+    return product_of_views<PS>(va, vb, M, N, la.kblocks, out, plan, partp, stream);
 }
 
 template <int MODE, bool FTZ>
-static int run_p(int pieces, int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
-                 const QuantParams &p, hipStream_t stream)
+static int run_p(Scheme sch, int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
+                 fmt_format_t f, const QuantParams &p, hipStream_t stream)
 {
-    switch (pieces) {
-        case 0: return run<MODE, FTZ, 0>(M, N, K, sa, sb, out, p, stream);
-        case 1: return run<MODE, FTZ, 1>(M, N, K, sa, sb, out, p, stream);
-        case 2: return run<MODE, FTZ, 2>(M, N, K, sa, sb, out, p, stream);
-        default: return run<MODE, FTZ, 3>(M, N, K, sa, sb, out, p, stream);
+    switch (sch.ps) {
+        case 0: return run<MODE, FTZ, 0>(M, N, K, sa, sb, out, f, p, stream, sch.scaled);
+        case 1: return run<MODE, FTZ, 1>(M, N, K, sa, sb, out, f, p, stream, false);
+        case 2: return run<MODE, FTZ, 2>(M, N, K, sa, sb, out, f, p, stream, false);
+        default: return run<MODE, FTZ, 3>(M, N, K, sa, sb, out, f, p, stream, false);
     }
 }
 
@@ -1502,24 +1568,93 @@ static int run_p(int pieces, int M, int N, int K, const OperandSpec &sa, const O
 static int run_product(int M, int N, int K, const OperandSpec &sa, const OperandSpec &sb, const OutSpec &out,
                        fmt_format_t f, const QuantParams &p, hipStream_t stream)
 {
-    // piece scheme: one fp16 piece for formats inside binary16, else 1-3 bf16 pieces by significand width
-    const int pieces = f.m <= 7 ? 1 : (f.e <= 5 && f.m <= 10 ? 0 : (f.m <= 15 ? 2 : 3));
     const bool ftz = f.denorm == 0;
-    // 1/6/9 and its neighbours: one scaled fp16 piece (a quarter of the MFMA work) when the product is
-    // large enough to pay for the extra launches (statistics, tail, the fallback's gated product:
-    // about 15 us against 2.6 us saved per GFLOP), twice as large when k is short
+    // 1/6/9 and 1/6/8: exponent planes (a quarter of the MFMA work of two bf16 pieces) for plain matrix
+    // operands, when the product is large enough to pay for the launch that picks the row scales
     const int wmode = window_mode();
-    if (f.e == 6 && f.m >= 8 && f.m <= 10 && sa.g.kind == kSrcMatrix && sb.g.kind == kSrcMatrix && out.img == 0 &&
-        (wmode == 1 || (wmode == 2 && ((K >= 1024 && 2.0 * M * N * K >= 4e9) || (K >= 128 && 2.0 * M * N * K >= 8e9)))))
-        return ftz ? run_window<kModeMagic, true>(M, N, K, sa, sb, out, f, p, stream)
-                   : run_window<kModeMagic, false>(M, N, K, sa, sb, out, f, p, stream);
+    const bool planes = sa.g.kind == kSrcMatrix && sb.g.kind == kSrcMatrix && out.img == 0 &&
+                        (wmode == 1 || (wmode == 2 && 2.0 * M * N * K >= 1e9 && K >= 128));
+    const Scheme sch = scheme_of(f, planes);
 #define FMT_RUN(MD)                                                                     \
-    (ftz ? run_p<MD, true>(pieces, M, N, K, sa, sb, out, p, stream)                      \
-         : run_p<MD, false>(pieces, M, N, K, sa, sb, out, p, stream))
+    (ftz ? run_p<MD, true>(sch, M, N, K, sa, sb, out, f, p, stream)                      \
+         : run_p<MD, false>(sch, M, N, K, sa, sb, out, f, p, stream))
     if (p.mode == kModeMagic) return FMT_RUN(kModeMagic);
     if (p.mode == kModeInteger) return FMT_RUN(kModeInteger);
     return FMT_RUN(kModeMixed);
 #undef FMT_RUN
+}
+
+// ---- prepared operands in caller-owned memory ---------------------------------------------------
+
+static Scheme api_scheme(fmt_format_t f) { return scheme_of(f, window_mode() != 0); }
+
+int prepared_operand_bytes(int64_t rows, int64_t K, fmt_format_t f, size_t *bytes, int *scheme)
+{
+    OperandLayout L;
+    const Scheme sch = api_scheme(f);
+    int rc = operand_layout(rows, K, sch, f.m, &L);
+    if (rc != FMT_OK) return rc;
+    *bytes = L.bytes;
+    *scheme = sch.ps + (sch.scaled ? 16 : 0);
+    return FMT_OK;
+}
+
+template <int MODE, bool FTZ>
+static int prepare_one_p(Scheme sch, const OperandSpec &sp, const OperandLayout &L, const OperandView &v, int K,
+                         fmt_format_t f, const QuantParams &p, hipStream_t stream)
+{
+    switch (sch.ps) {
+        case 0: return prepare_operands<MODE, FTZ, 0>(sp, L, v, nullptr, nullptr, nullptr, nullptr, nullptr, K, f, p, stream);
+        case 1: return prepare_operands<MODE, FTZ, 1>(sp, L, v, nullptr, nullptr, nullptr, nullptr, nullptr, K, f, p, stream);
+        case 2: return prepare_operands<MODE, FTZ, 2>(sp, L, v, nullptr, nullptr, nullptr, nullptr, nullptr, K, f, p, stream);
+        default: return prepare_operands<MODE, FTZ, 3>(sp, L, v, nullptr, nullptr, nullptr, nullptr, nullptr, K, f, p, stream);
+    }
+}
+
+// X is `rows` x K after op(): trans == 0: X[r*ld + k], trans != 0: X[k*ld + r].  rows, K > 0.
+int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, int64_t K, fmt_format_t f,
+                           const QuantParams &p, void *buf, hipStream_t stream)
+{
+    const Scheme sch = api_scheme(f);
+    OperandLayout L;
+    int rc = operand_layout(rows, K, sch, f.m, &L);
+    if (rc != FMT_OK) return rc;
+    const OperandView v = view_of(buf, L);
+    const OperandSpec sp{X, ld, trans == 0, Gather{}, 0};
+    const bool ftz = f.denorm == 0;
+#define FMT_PREP(MD)                                                                \
+    (ftz ? prepare_one_p<MD, true>(sch, sp, L, v, (int)K, f, p, stream)              \
+         : prepare_one_p<MD, false>(sch, sp, L, v, (int)K, f, p, stream))
+    if (p.mode == kModeMagic) return FMT_PREP(kModeMagic);
+    if (p.mode == kModeInteger) return FMT_PREP(kModeInteger);
+    return FMT_PREP(kModeMixed);
+#undef FMT_PREP
+}
+
+// C = A B^T on two prepared operands (A: M rows, B: N rows, both with the same K and scheme).
+int launch_gemm_prepared(const void *A, const void *B, int64_t M64, int64_t N64, int64_t K64, int scheme, fmt_format_t f,
+                         float *C, int64_t ldc, hipStream_t stream)
+{
+    const int M = (int)M64, N = (int)N64;
+    const Scheme sch{scheme & 15, (scheme & 16) != 0};
+    OperandLayout la, lb;
+    int rc = operand_layout(M64, K64, sch, f.m, &la);
+    if (rc != FMT_OK) return rc;
+    rc = operand_layout(N64, K64, sch, f.m, &lb);
+    if (rc != FMT_OK) return rc;
+    int cus = 0;
+    rc = device_cu_count(&cus);
+    if (rc != FMT_OK) return rc;
+    const Plan plan = make_plan(M, N, la.kblocks, cus, pieces_of(sch.ps));
+    float *part = nullptr;
+    if (plan.nsplit > 1) {
+        Scratch s;
+        rc = get_scratch(stream, 0, part_bytes_of(plan, M, N), &s);
+        if (rc != FMT_OK) return rc;
+        part = static_cast<float *>(s.gemm_ws);
+    }
+    const OperandView va = view_of(const_cast<void *>(A), la), vb = view_of(const_cast<void *>(B), lb);
+    return product_dispatch(sch.ps, va, vb, M, N, la.kblocks, OutSpec{C, ldc, 0}, plan, part, stream);
 }
 
 static int zero_fill(float *C, int64_t rows, int64_t cols, int64_t ldc, hipStream_t stream)

@@ -62,6 +62,13 @@ int launch_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
                 const float *A, int64_t lda, const float *B, int64_t ldb,
                 float *C, int64_t ldc, fmt_format_t f, const QuantParams &p, hipStream_t stream);
 
+// Prepared operands in caller-owned memory (fmt_gemm.hip).  scheme: opaque tag of the representation.
+int prepared_operand_bytes(int64_t rows, int64_t K, fmt_format_t f, size_t *bytes, int *scheme);
+int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, int64_t K, fmt_format_t f,
+                           const QuantParams &p, void *buf, hipStream_t stream);
+int launch_gemm_prepared(const void *A, const void *B, int64_t M, int64_t N, int64_t K, int scheme, fmt_format_t f,
+                         float *C, int64_t ldc, hipStream_t stream);
+
 // Convolutions as products of gathered operands (fmt_gemm.hip); which: 0 forward, 1 dgrad, 2 wgrad
 int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, fmt_format_t f,
                   const QuantParams &p, hipStream_t stream);
