@@ -9,17 +9,18 @@ One "step" is one pass of the whole hot path over one batch of synthetic, paper-
                                      8 B of algorithmic HBM traffic per element and pass
   GEMM section (configuration 4)     BERT-Large-shaped encoder-layer GEMMs at 4096 tokens in
                                      1/6/9/d: for each of the four linear layers (QKV, attention
-                                     output, FFN1, FFN2) fused quantize + histogram of X, W and
-                                     dY, then forward (NT), dgrad (NN) and wgrad (TN): 12 products,
+                                     output, FFN1, FFN2) the rounding pass over X, W and dY -- fused
+                                     quantize + histogram, and the rounded tensor stored as a prepared
+                                     operand in the two orientations its two products need -- then
+                                     forward, dgrad and wgrad on the prepared operands: 12 products,
                                      309 GFLOP
-  conv section (configuration 3)     the ResNet-style 3x3 conv as im2col GEMM in 1/6/9/d:
-                                     fused quantize + histogram of X_col, W and dY, then the
-                                     forward, dgrad and wgrad products (M=12544, N=256, K=2304
-                                     and permutations, 14.8 GFLOP each)
+  conv section (configuration 3)     the ResNet-style 3x3 conv as im2col GEMM in 1/6/9/d: the same
+                                     rounding pass over X_col, W and dY, then the forward, dgrad and
+                                     wgrad products (M=12544, N=256, K=2304 and permutations,
+                                     14.8 GFLOP each)
 
 The calls inside the configuration 4 and configuration 3 sections are independent of each other and
-are issued round-robin on three side streams (--gemm-streams): one product's operand preparation
-overlaps another's MFMA kernel.  The stream section runs on one stream.
+are issued round-robin on three side streams (--gemm-streams).  The stream section runs on one stream.
 
 `value` is the quantize+histogram HBM rate of the stream section (GB/s, algorithmic bytes over
 the section's event-timed duration); the GEMM section's useful TFLOP/s and its MFMA fraction are
@@ -61,6 +62,8 @@ def main() -> int:
     ap.add_argument("--gemm", default=None, metavar="M,N,K[,transA,transB[,e,m,d]]",
                     help="profiling aid: run only fmt_gemm on one N(0,1) problem of this shape (default NN, 1/6/9/d), "
                          "--steps times after --warmup untimed calls, print its time and exit")
+    ap.add_argument("--prepared", action="store_true",
+                    help="with --gemm: prepare the operands once (untimed) and time fmt_gemm_prepared")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); "
@@ -88,12 +91,18 @@ def main() -> int:
         A = torch.randn((Kg, Mg) if tA else (Mg, Kg), device=dev)
         B = torch.randn((Ng, Kg) if tB else (Kg, Ng), device=dev)
         C = torch.empty((Mg, Ng), device=dev)
+        if args.prepared:
+            Ap = fmt.fmt_prepare(A, (e_, m_, bool(d_)), trans=bool(tA))
+            Bp = fmt.fmt_prepare(B, (e_, m_, bool(d_)), trans=not tB)
+            call = lambda: fmt.fmt_gemm_prepared(Ap, Bp, out=C)
+        else:
+            call = lambda: fmt.fmt_gemm(A, B, (e_, m_, bool(d_)), transA=bool(tA), transB=bool(tB), out=C)
         for _ in range(args.warmup):
-            fmt.fmt_gemm(A, B, (e_, m_, bool(d_)), transA=bool(tA), transB=bool(tB), out=C)
+            call()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(args.steps):
-            fmt.fmt_gemm(A, B, (e_, m_, bool(d_)), transA=bool(tA), transB=bool(tB), out=C)
+            call()
         b.record()
         torch.cuda.synchronize()
         ms = a.elapsed_time(b) / args.steps
@@ -126,10 +135,21 @@ def main() -> int:
                        "Y": torch.empty((X4.shape[0], W4.shape[0]), dtype=torch.float32, device=dev),
                        "dX": torch.empty_like(X4), "dW": torch.empty_like(W4),
                        "h": [fmt.new_hist(dev) for _ in range(3)]})
+    f169 = workloads.FORMATS["1/6/9/d"]
+
+    def operand_bufs(t):
+        """Device buffers for the two prepared operands of a 2-D tensor: as stored, and transposed."""
+        r, c = t.shape
+        return (torch.empty(fmt.fmt_operand_bytes(r, c, f169), dtype=torch.uint8, device=dev),
+                torch.empty(fmt.fmt_operand_bytes(c, r, f169), dtype=torch.uint8, device=dev))
+    for L in layers:
+        L["buf"] = {k: operand_bufs(L[k]) for k in ("X", "W", "dY")}
+        L["op"] = {}
+    c3 = {"t": {"X": xcol, "W": w, "dY": dy}, "op": {}}
+    c3["buf"] = {k: operand_bufs(v) for k, v in c3["t"].items()}
     cfg4_flops = sum(3 * 2.0 * L["X"].shape[0] * L["W"].shape[0] * L["W"].shape[1] for L in layers)
     hists = [fmt.new_hist(dev) for _ in range(9)]
     variants = list(workloads.FORMATS.values())
-    f169 = workloads.FORMATS["1/6/9/d"]
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
@@ -167,27 +187,36 @@ def main() -> int:
                 join.record(st_)
                 torch.cuda.current_stream().wait_event(join)
 
+        # The rounding pass of Sec. IV-A over one tensor: statistics and the rounded fp32 copy in one fused
+        # pass, and the rounded tensor as a prepared operand in both orientations (each feeds one product).
+        def round_tensor(st_, src, dst, hist, bufs, ops, key):
+            fmt.fmt_quantize(src, f169, out=dst, hist=hist, stream=st_)
+            ops[key] = (fmt.fmt_prepare(src, f169, trans=False, out=bufs[0], stream=st_),
+                        fmt.fmt_prepare(src, f169, trans=True, out=bufs[1], stream=st_))
+
         q4 = []
-        for L in layers:                                                     # configuration 4, quantize
+        for L in layers:                                                     # configuration 4, rounding passes
             for src, dst, hi in (("X", "Xq", 0), ("W", "Wq", 1), ("dY", "dYq", 2)):
                 q4.append(lambda st_, L=L, src=src, dst=dst, hi=hi:
-                          fmt.fmt_quantize(L[src], f169, out=L[dst], hist=L["h"][hi], stream=st_))
+                          round_tensor(st_, L[src], L[dst], L["h"][hi], L["buf"][src], L["op"], src))
         fan_out(q4)
         mark()
         g4 = []                                                              # configuration 4, products
         for L in layers:
-            g4.append(lambda st_, L=L: fmt.fmt_gemm(L["Xq"], L["Wq"], f169, transB=True, out=L["Y"], stream=st_))     # Y  = X W^T
-            g4.append(lambda st_, L=L: fmt.fmt_gemm(L["dYq"], L["Wq"], f169, out=L["dX"], stream=st_))                # dX = dY W
-            g4.append(lambda st_, L=L: fmt.fmt_gemm(L["dYq"], L["Xq"], f169, transA=True, out=L["dW"], stream=st_))   # dW = dY^T X
+            o = L["op"]
+            g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["X"][0], o["W"][0], out=L["Y"], stream=st_))     # Y  = X W^T
+            g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["dY"][0], o["W"][1], out=L["dX"], stream=st_))   # dX = dY W
+            g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["dY"][1], o["X"][1], out=L["dW"], stream=st_))   # dW = dY^T X
         fan_out(g4)
         mark()
-        fan_out([lambda st_: fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6], stream=st_),       # configuration 3
-                 lambda st_: fmt.fmt_quantize(w, f169, out=w_q, hist=hists[7], stream=st_),
-                 lambda st_: fmt.fmt_quantize(dy, f169, out=dy_q, hist=hists[8], stream=st_)])
+        fan_out([lambda st_: round_tensor(st_, xcol, xcol_q, hists[6], c3["buf"]["X"], c3["op"], "X"),   # configuration 3
+                 lambda st_: round_tensor(st_, w, w_q, hists[7], c3["buf"]["W"], c3["op"], "W"),
+                 lambda st_: round_tensor(st_, dy, dy_q, hists[8], c3["buf"]["dY"], c3["op"], "dY")])
         mark()
-        fan_out([lambda st_: fmt.fmt_gemm(xcol_q, w_q, f169, transB=True, out=out_fwd, stream=st_),     # Y  = X_col W^T
-                 lambda st_: fmt.fmt_gemm(dy_q, w_q, f169, out=out_dgrad, stream=st_),                  # dX = dY W
-                 lambda st_: fmt.fmt_gemm(dy_q, xcol_q, f169, transA=True, out=out_wgrad, stream=st_)])  # dW = dY^T X_col
+        o3 = c3["op"]
+        fan_out([lambda st_: fmt.fmt_gemm_prepared(o3["X"][0], o3["W"][0], out=out_fwd, stream=st_),      # Y  = X_col W^T
+                 lambda st_: fmt.fmt_gemm_prepared(o3["dY"][0], o3["W"][1], out=out_dgrad, stream=st_),   # dX = dY W
+                 lambda st_: fmt.fmt_gemm_prepared(o3["dY"][1], o3["X"][1], out=out_wgrad, stream=st_)])  # dW = dY^T X_col
         mark()
         if record is not None:
             record.append(marks)
@@ -247,17 +276,22 @@ def main() -> int:
                         "config4_gemms": round(cfg4_gemm_ms, 4), "config3_quantize": round(cfg3_q_ms, 4),
                         "config3_gemms": round(cfg3_gemm_ms, 4)},
         "gemm": {
-            "workload": "config 4, 12 products, 1/6/9/d",
-            "value": round(cfg4_tflops, 2), "unit": "TFLOP/s (useful, 2MNK per product, whole fmt_gemm calls)",
+            "workload": "config 4, 12 products on prepared operands (fmt_gemm_prepared), 1/6/9/d",
+            "value": round(cfg4_tflops, 2), "unit": "TFLOP/s (useful, 2MNK per product, whole fmt_gemm_prepared calls)",
             "mfma_frac": round(cfg4_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
-            "note": "1/6/9 operands run as ONE scaled fp16 piece (per-row power-of-two window, exact outlier "
-                    "products, fallback to two bf16 pieces chosen on the device): 1 MFMA product per multiply, so "
-                    "mfma_frac = useful / 2500 TFLOP/s dense fp16 peak; the two-piece scheme (4 MFMA products "
-                    "per multiply) is measured under two_piece for comparison",
+            "with_rounding_passes_tflops": round(cfg4_flops / ((cfg4_gemm_ms + cfg4_q_ms) * 1e-3) / 1e12, 2),
+            "note": "1/6/9 operands are exponent planes: one scaled fp16 piece per value (per-row power-of-two "
+                    "scale), the few values outside a row's plane in a second or third plane whose products the same "
+                    "kernel adds: 1 MFMA product per multiply, so mfma_frac = useful / 2500 TFLOP/s dense fp16 peak. "
+                    "The rounding passes that make the operands (once per tensor and orientation, shared by the "
+                    "products that use it) are timed in sections_ms.config4_quantize; with_rounding_passes_tflops "
+                    "charges them to the products.  fmt_gemm on fp32 operands (rounds per call) and the two-bf16-piece "
+                    "scheme (4 MFMA products per multiply) are measured beside it",
         },
         "gemm_config3": {
-            "workload": "config 3, 3 products, 1/6/9/d (one scaled fp16 piece each)",
+            "workload": "config 3, 3 products on prepared operands, 1/6/9/d",
             "value": round(cfg3_tflops, 2), "unit": "TFLOP/s (useful)",
+            "with_rounding_passes_tflops": round(3 * 2.0 * M * N * K / ((cfg3_gemm_ms + cfg3_q_ms) * 1e-3) / 1e12, 2),
         },
         "roofline": {
             "kernel": "stream_kernel (fused quantize + histogram)",
@@ -323,7 +357,29 @@ def main() -> int:
     big_one_ms = timed0(lambda: fmt.fmt_gemm(Abig, Bbig, f169, out=Cbig), 3)
     del Abig, Bbig, Cbig
     big_flops = 2.0 * 8192 ** 3
-    result["gemm"]["single_stream_tflops"] = round(cfg4_flops / (one_ms * 1e-3) / 1e12, 2)
+    result["gemm"]["fmt_gemm_fp32_operands_tflops"] = round(cfg4_flops / (one_ms * 1e-3) / 1e12, 2)
+
+    def cfg4_prepared():
+        for L in layers:
+            o = L["op"]
+            fmt.fmt_gemm_prepared(o["X"][0], o["W"][0], out=L["Y"])
+            fmt.fmt_gemm_prepared(o["dY"][0], o["W"][1], out=L["dX"])
+            fmt.fmt_gemm_prepared(o["dY"][1], o["X"][1], out=L["dW"])
+    result["gemm"]["single_stream_tflops"] = round(cfg4_flops / (timed0(cfg4_prepared, max(args.steps // 2, 1)) * 1e-3) / 1e12, 2)
+
+    # Roofline of the product kernel: the largest product of config 4 (FFN1 forward, 4096 x 4096 x 1024,
+    # one launch per call), timed with events on the stream it is launched on.
+    Lf = layers[2]
+    Mr, Nr, Kr = Lf["X"].shape[0], Lf["W"].shape[0], Lf["W"].shape[1]
+    reps_r = max(args.steps, 10)
+    roof_ms = timed0(lambda: fmt.fmt_gemm_prepared(Lf["op"]["X"][0], Lf["op"]["W"][0], out=Lf["Y"]), reps_r)
+    roof_tflops = 2.0 * Mr * Nr * Kr / (roof_ms * 1e-3) / 1e12
+    result["roofline_gemm"] = {
+        "kernel": "product_kernel<PS=0 (fp16 planes), 256x256 tile> on config 4 FFN1 forward %dx%dx%d" % (Mr, Nr, Kr),
+        "bound": "mfma", "achieved": round(roof_tflops, 1), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(roof_tflops / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+        "launch_ms": round(roof_ms, 4), "algorithmic_flops_per_launch": 2.0 * Mr * Nr * Kr,
+        "note": "fp16 MFMA dense peak; one MFMA product per multiply, so issued = useful flops"}
     result["gemm"]["two_piece"] = {
         "value": round(cfg4_flops / (two_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s (useful), one stream",
         "issued_tflops": round(4 * cfg4_flops / (two_ms * 1e-3) / 1e12, 2),
@@ -469,6 +525,34 @@ def main() -> int:
             "sample": "quantize + histogram of the first 2^%d elements of the same tensor in the six format "
                       "variants (%d passes, %.1f s)" % (sample.bit_length() - 1, len(variants), cpu_s),
         }
+        # the same oracle passes spread over all host cores (independent chunks of the sample, one thread each;
+        # the oracle's loops are serial C and release the interpreter lock inside ctypes)
+        import concurrent.futures
+        cores = max(1, min(len(os.sched_getaffinity(0)), 16))
+        chunks = np.array_split(xs, cores)
+
+        def one_chunk(c):
+            for (e, m, d) in variants:
+                oracle.quantize(c, e, m, d)
+                oracle.histogram(c, e, m)
+        t1 = time.perf_counter()
+        with concurrent.futures.ThreadPoolExecutor(cores) as ex:
+            list(ex.map(one_chunk, chunks))
+        par_s = time.perf_counter() - t1
+        result["cpu_baseline"]["all_cores"] = {"value": round(len(variants) * 8.0 * sample / par_s / 1e9, 4),
+                                               "unit": "GB/s", "cores": cores}
+        # the GEMM oracle (fp64 triple loop, OpenMP over rows) on a bounded sample of config 4: the attention-output
+        # layer's forward product with the first 256 tokens
+        La = cfg4["layers"][1]
+        Xs = np.ascontiguousarray(La["X"][:256])
+        t1 = time.perf_counter()
+        oracle.gemm(Xs, La["W"], f169[0], f169[1], f169[2], transB=True)
+        g_s = time.perf_counter() - t1
+        result["cpu_baseline"]["gemm"] = {
+            "value": round(2.0 * Xs.shape[0] * La["W"].shape[0] * La["W"].shape[1] / g_s / 1e12, 5), "unit": "TFLOP/s",
+            "cores": int(os.environ.get("OMP_NUM_THREADS", cores)), "kind": "oracle",
+            "sample": "oracle.gemm of config 4's attention-output forward product on its first 256 tokens "
+                      "(256 x 1024 x 1024, %.1f s)" % g_s}
 
     print(json.dumps(result))
     return 0

@@ -27,12 +27,13 @@
 // MFMA product per multiply).  A value that does not fit there -- too large, or with bits below
 // binary16's last denormal bit -- fits exactly under the scale 2^(S-w) (plane "above") or 2^(S+w)
 // (plane "below"), w = 40 - m binades being what one plane holds; three planes cover the whole range
-// of the format whatever S is.  A per-(32 rows x 32 k) mask says which planes hold anything; after
-// its main loop the product kernel multiplies the few non-empty plane pairs and adds them in a fixed
-// order, each with its own power-of-two scale undone exactly.  Exact products, fp32 accumulation,
-// no lists, no fallback: the result is reproducible bit for bit.
+// of the format whatever S is.  A per-(32 rows x 32 k) mask says which planes hold anything; a small
+// kernel after the product kernel adds the products of the few elements outside plane 0, one fp32
+// fused multiply-add each, in a fixed order.  Exact products, fp32 accumulation, no lists to
+// overflow, no fallback: the result is reproducible bit for bit.
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "fmt_internal.h"
 #include "fmt_quant.h"
@@ -711,14 +712,14 @@ __global__ __launch_bounds__(256) void prepare_scaled_kernel(PrepOperand a, Prep
     prepare_scaled_block<MODE, FTZ>(o, K, kblocks, p, bid);
 }
 
-// Epilogue of the scaled scheme for one wave: out (+)= acc * 2^-(S_row + S_col + shift), exactly.  The
+// Epilogue of the scaled scheme for one wave: out = acc * 2^-(S_row + S_col), exactly.  The
 // scale arrays are padded to the tile grid and 16-byte aligned, and a lane's rows come in groups of
 // four: all of a lane's scales are fetched together, with vector loads, ahead of its stores.
 // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
 template <int TM, int TN>
 __device__ __forceinline__ void scaled_store(const floatx16 (&acc)[TM][TN], float *__restrict__ out, int64_t ldc, int M, int N,
                                              int tm, int tn, int wm, int wn, int lane, const int *__restrict__ Sa,
-                                             const int *__restrict__ Sb, int shift, bool add)
+                                             const int *__restrict__ Sb)
 {
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     const int col_in = lane & 31, row_half = (lane >> 5) * 4;
@@ -741,112 +742,10 @@ __device__ __forceinline__ void scaled_store(const floatx16 (&acc)[TM][TN], floa
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < M) {
-                        float *dst = out + (size_t)row * ldc + col;
-                        const float t = ldexpf(acc[i][j][v], -(sav[i][v >> 2][v & 3] + sbv[j] + shift));
-                        *dst = add ? *dst + t : t;
-                    }
+                    if (row < M) out[(size_t)row * ldc + col] = ldexpf(acc[i][j][v], -(sav[i][v >> 2][v & 3] + sbv[j]));
                 }
             }
         }
-    }
-}
-
-// Stores one 32 x 32 MFMA tile of the scaled scheme: dst (+)= acc * 2^-(S_row + S_col + shift), exactly.
-__device__ __forceinline__ void scaled_store_tile(const floatx16 &acc, float *__restrict__ out, int64_t ldc, int M, int N,
-                                                  int row0, int col, const int *__restrict__ Sa, const int *__restrict__ Sb,
-                                                  int shift, bool add)
-{
-    if (col >= N) return;
-    const int sb = Sb[col];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int row = row0 + (v >> 2) * 8 + (v & 3);
-        if (row < M) {
-            float *dst = out + (size_t)row * ldc + col;
-            const float t = ldexpf(acc[v], -(Sa[row] + sb + shift));
-            *dst = add ? *dst + t : t;
-        }
-    }
-}
-
-// The plane pairs other than (0, 0) of one workgroup tile (2 x 2 waves of TM x TN MFMA tiles, k blocks
-// [kb0, kb1)): per k block, which planes are present among the tile's units of A and of B is read off
-// the masks; for every pair of planes present at some k the units are staged through `stg` (one LDS
-// stage buffer: a unit-row of either operand), multiplied, and added to the tile with the pair's own
-// scale.  Pairs in a fixed order, k ascending inside a pair: the sums are reproducible.  This path is
-// rare and is written for few registers, not for speed: one MFMA tile of every wave at a time (the
-// staging is repeated per tile), so that it costs the main loop neither registers nor occupancy.
-template <int TM, int TN>
-__device__ __forceinline__ void plane_pairs(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
-                                            float *__restrict__ out, int64_t ldc, int M, int N, int kblocks, int kb0,
-                                            int kb1, int tm, int tn, int wm, int wn, const Planes &pa, const Planes &pb,
-                                            u32x4 *stg)
-{
-    constexpr int UA = 2 * TM, UB = 2 * TN, kHalf = 64, kScan = 256;
-    __shared__ uint8_t s_oa[kScan], s_ob[kScan];
-    const int tid = threadIdx.x, lane = tid & 63;
-    for (int base = kb0; base < kb1; base += kScan) {
-        const int kb = base + tid;
-        uint32_t oa = 0u, ob = 0u;
-        if (kb < kb1) {
-#pragma unroll
-            for (int i = 0; i < UA; ++i) oa |= pa.mask[(size_t)(tm * UA + i) * kblocks + kb];
-#pragma unroll
-            for (int j = 0; j < UB; ++j) ob |= pb.mask[(size_t)(tn * UB + j) * kblocks + kb];
-        }
-        if (!__syncthreads_or((int)((oa | ob) & 6u))) continue;
-        s_oa[tid] = (uint8_t)oa;
-        s_ob[tid] = (uint8_t)ob;
-        __syncthreads();
-        const int nhere = min(kScan, kb1 - base);
-#pragma clang loop unroll(disable)
-        for (int pr = 1; pr < 9; ++pr) {
-            const int qa = pr / 3, qb = pr % 3;          // plane of A, plane of B (0 main, 1 above, 2 below)
-            // plane above: scale 2^(S - w); below: 2^(S + w)
-            const int shift = (qa == 1 ? -pa.w : (qa == 2 ? pa.w : 0)) + (qb == 1 ? -pb.w : (qb == 2 ? pb.w : 0));
-#pragma clang loop unroll(disable)
-            for (int ij = 0; ij < TM * TN; ++ij) {
-                const int i = ij / TN, j = ij % TN;      // this wave's MFMA tile; the same (i, j) in all four waves
-                floatx16 acc;
-                bool any = false;
-#pragma clang loop unroll(disable)
-                for (int jj = 0; jj < nhere; ++jj) {
-                    if ((((uint32_t)s_oa[jj] >> qa) & ((uint32_t)s_ob[jj] >> qb) & 1u) == 0u) continue;   // workgroup-uniform
-                    const int kbj = base + jj;
-                    if (!any) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-                        any = true;
-                    }
-                    __syncthreads();                      // the previous fill has been read by every wave
-                    // units i, TM + i of A (the two wave rows) and j, TN + j of B (the two wave columns)
-                    for (int q = tid; q < 4 * kUnitVec; q += 256) {
-                        const int which = q / kUnitVec, vv = q % kUnitVec;
-                        const bool isb = which >= 2;
-                        const Planes &pl = isb ? pb : pa;
-                        const int plane = isb ? qb : qa;
-                        const int unit = isb ? (which - 2) * TN + j : which * TM + i;
-                        const size_t uidx = (size_t)((isb ? tn * UB : tm * UA) + unit) * kblocks + kbj;
-                        u32x4 val = {0u, 0u, 0u, 0u};
-                        if (((uint32_t)pl.mask[uidx] >> plane) & 1u)   // only then has this plane of the unit been written
-                            val = (isb ? Bw : Aw)[(size_t)plane * pl.plane + uidx * kUnitVec + vv];
-                        stg[q] = val;
-                    }
-                    __syncthreads();
-#pragma unroll
-                    for (int kk = 0; kk < 2; ++kk) {
-                        const f16x8 xa = __builtin_bit_cast(f16x8, stg[wm * kUnitVec + kk * kHalf + lane]);
-                        const f16x8 xb = __builtin_bit_cast(f16x8, stg[(2 + wn) * kUnitVec + kk * kHalf + lane]);
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa, xb, acc, 0, 0, 0);
-                    }
-                }
-                if (any)
-                    scaled_store_tile(acc, out, ldc, M, N, (tm * 2 + wm) * (32 * TM) + i * 32 + (lane >> 5) * 4,
-                                      (tn * 2 + wn) * (32 * TN) + j * 32 + (lane & 31), pa.S, pb.S, shift, true);
-            }
-        }
-        __syncthreads();                                  // before s_oa / s_ob are overwritten
     }
 }
 
@@ -857,8 +756,8 @@ __device__ __forceinline__ void plane_pairs(const u32x4 *__restrict__ Aw, const 
 // per stage.  With SPLIT the k range is cut into parts and each part writes its own M x N slab
 // of partial sums (summed by reduce_kernel).
 // SCALED (single fp16 piece only): the operands are exponent planes with per-row power-of-two scales
-// (pa.S / pb.S), undone on the way out; the main loop multiplies plane 0 by plane 0 and the pairs of
-// the other planes that hold anything follow it.
+// (pa.S / pb.S), undone on the way out; this kernel multiplies plane 0 by plane 0, planes_tail_kernel
+// adds the products of the elements that live in the other planes.
 template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int img,
@@ -1057,11 +956,7 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
     float *out = SPLIT ? C + (size_t)split * M * ldc : C;
     const int col_in = lane & 31, row_half = (lane >> 5) * 4;
     if constexpr (SCALED) {
-        scaled_store<TM, TN>(acc, out, ldc, M, N, tm, tn, wm, wn, lane, pa.S, pb.S, 0, false);
-        // The other plane pairs: almost always there are none, and the workgroup leaves after one look
-        // at the masks.  Kept out of line so that this rarely taken path costs the main loop no registers.
-        static_assert(KS == 2 && P == 1, "the plane pass reads whole 32-k units");
-        plane_pairs<TM, TN>(Aw, Bw, out, ldc, M, N, kblocks, kb0, kb1, tm, tn, wm, wn, pa, pb, st0);
+        scaled_store<TM, TN>(acc, out, ldc, M, N, tm, tn, wm, wn, lane, pa.S, pb.S);
         return;
     }
 #pragma unroll
@@ -1083,6 +978,192 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
                 }
             }
         }
+}
+
+// Half h (0..7) of a 16-byte vector of eight 16-bit patterns, as a float (binary16 -> fp32 is exact).
+__device__ __forceinline__ float half_of(const u32x4 &v, int h)
+{
+    const uint32_t w = (h >> 1) == 0 ? v[0] : (h >> 1) == 1 ? v[1] : (h >> 1) == 2 ? v[2] : v[3];
+    return static_cast<float>(__builtin_bit_cast(_Float16, (uint16_t)((h & 1) ? w >> 16 : w & 0xFFFFu)));
+}
+
+// Element (row r of the unit, k-chunk c, position h) of the unit whose plane-0 vectors start at W + unit_vec,
+// in the scale of plane 0, whichever plane holds it: plane 0 as stored, the plane above times 2^w, the
+// plane below times 2^-w (exact: a binary16 value times a power of two, far inside fp32's range).
+__device__ __forceinline__ float unit_value(const u32x4 *__restrict__ W, size_t unit_vec, const Planes &pl, uint32_t planes,
+                                            int c, int r, int h)
+{
+    const size_t at = unit_vec + (size_t)(c * kUnitRows + r);
+    float x = half_of(W[at], h);
+    if (planes & 6u) {                            // rare
+        if (planes & 2u) x += ldexpf(half_of(W[pl.plane + at], h), pl.w);
+        if (planes & 4u) x += ldexpf(half_of(W[2 * pl.plane + at], h), -pl.w);
+    }
+    return x;
+}
+
+// The products of the elements that live outside plane 0, added to C after the product kernel has stored
+// plane 0 x plane 0.  Such elements are rare (a few per million for tensors of neural networks) and each
+// contributes to one row or one column of C, so they are added one product at a time with fp32 fused
+// multiply-adds on the TRUE values (the binary16 pattern with its plane's and its row's scale undone: a
+// value of the format, exactly an fp32) -- exact product, one rounding per accumulation, FMACS.
+// One workgroup owns a block of 32 rows (one unit of A) x 256 columns (8 units of B) of C:
+//   1. every element a of A's other planes in its rows meets the FULL value of B (all planes) at that k
+//      in each of its columns, elements in the order (k block, plane, position in the unit);
+//   2. then every element b of B's other planes in its columns meets the plane-0 value of A in each of its
+//      rows (an element of A outside plane 0 has met b in step 1), in the same kind of order.
+// Every element of C has one owner and a fixed order of additions: the result is reproducible bit for bit.
+// A block whose units hold nothing but plane 0 -- the usual case -- leaves after reading its masks.
+constexpr int kTailRecs = 4096;                  // element records kept before they are applied (a unit holds at most 1024 per plane)
+
+__global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw, Planes pa,
+                                                          Planes pb, float *__restrict__ C, int64_t ldc, int M, int N, int kblocks,
+                                                          int col_chunks)
+{
+    __shared__ uint32_t s_rec[kTailRecs];        // row-or-column in the unit (5 bits) | k << 5
+    __shared__ float s_val[kTailRecs];           // the element's true value
+    __shared__ uint32_t s_list[256];             // k blocks (of one scan of 256) whose unit has other planes | planes << 16
+    __shared__ int s_cnt[4];
+    __shared__ int s_n;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rb = blockIdx.x / col_chunks, cc = blockIdx.x % col_chunks;
+    const int ub0 = cc * 8;                      // first unit of B of this block (B is padded to whole groups of 8 units)
+
+    bool any_a = false, any_b = false;
+    for (int kb = tid; kb < kblocks; kb += 256) any_a |= (pa.mask[(size_t)rb * kblocks + kb] & 6u) != 0u;
+    for (int i = tid; i < 8 * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
+    const bool do_a = __syncthreads_or((int)any_a) != 0, do_b = __syncthreads_or((int)any_b) != 0;
+    if (!do_a && !do_b) return;
+
+    // Ordered compaction over the workgroup: thread t contributes `have` items; returns the index of its
+    // first one and, in total, the number of items.  Two barriers.
+    auto place = [&](int have, int &total) __attribute__((always_inline)) {
+        int incl = have;                                   // inclusive prefix inside the wave
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        __syncthreads();                                   // s_cnt is free again
+        if (lane == 63) s_cnt[wave] = incl;
+        __syncthreads();
+        int before = 0;
+        total = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            before += q < wave ? s_cnt[q] : 0;
+            total += s_cnt[q];
+        }
+        return before + incl - have;
+    };
+
+    // Collects the elements of the other planes of one unit (plane-0 vectors at W + unit_vec, planes per
+    // `planes`) as records (position along the unit's rows, k, true value with the row scales S of that
+    // unit undone), appended to s_rec / s_val in the order (plane, vector, position).  All threads call it.
+    auto collect = [&](const u32x4 *__restrict__ W, const Planes &pl, size_t unit_vec, uint32_t planes, int kb, const int *S32) {
+        for (int q = 1; q <= 2; ++q) {
+            if (((planes >> q) & 1u) == 0u) continue;      // workgroup-uniform
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (tid < kUnitVec) v = W[(size_t)q * pl.plane + unit_vec + tid];     // vector tid: k-chunk tid / 32, row tid % 32
+            int have = 0;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) have += (((t & 1) ? v[t >> 1] >> 16 : v[t >> 1]) & 0x7FFFu) != 0u ? 1 : 0;
+            int total;
+            int at = s_n + place(have, total);
+            if (have) {
+                const int r = tid & 31, c = tid >> 5;
+                const int undo = -(S32[r] + (q == 1 ? -pl.w : pl.w));        // the plane above carries 2^(S - w), the one below 2^(S + w)
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const uint32_t hp = ((t & 1) ? v[t >> 1] >> 16 : v[t >> 1]) & 0xFFFFu;
+                    if (hp & 0x7FFFu) {
+                        s_rec[at] = (uint32_t)r | ((uint32_t)(kb * kUnitK + c * 8 + t) << 5);
+                        s_val[at] = ldexpf(static_cast<float>(__builtin_bit_cast(_Float16, (uint16_t)hp)), undo);
+                        ++at;
+                    }
+                }
+            }
+            __syncthreads();
+            if (tid == 0) s_n += total;
+            __syncthreads();
+        }
+    };
+
+    // Walks the units of one row of units (mask row `mrow`) that have other planes, k ascending, collecting
+    // their elements; `apply` is called whenever the records must be used up (and once at the end).
+    auto walk = [&](const u32x4 *__restrict__ W, const Planes &pl, size_t urow, const int *S32, auto &&apply) {
+        if (tid == 0) s_n = 0;
+        for (int base = 0; base < kblocks; base += 256) {
+            const int kb = base + tid;
+            const uint32_t m = kb < kblocks ? (uint32_t)pl.mask[urow * kblocks + kb] & 6u : 0u;
+            int total;
+            const int at = place(m != 0u ? 1 : 0, total);
+            if (m != 0u) s_list[at] = (uint32_t)tid | (m << 16);
+            __syncthreads();
+            for (int n = 0; n < total; ++n) {
+                const uint32_t e = s_list[n];
+                if (s_n > kTailRecs - 2 * kUnitRows * kUnitK) {          // room for one more unit's two planes?
+                    apply(s_n);
+                    __syncthreads();
+                    if (tid == 0) s_n = 0;
+                    __syncthreads();
+                }
+                const int kbn = base + (int)(e & 0xFFFFu);
+                collect(W, pl, (urow * kblocks + kbn) * kUnitVec, e >> 16, kbn, S32);
+            }
+            __syncthreads();                                 // s_list is rewritten by the next scan
+        }
+        apply(s_n);
+        __syncthreads();
+    };
+
+    if (do_a) {
+        // 1. this block's column of thread tid: C[row][col] += a * b(k, col) for the records (row, k, a) in order
+        const int col = cc * 256 + tid;
+        const int ub = col / kUnitRows, cr = col % kUnitRows;
+        const int sb = col < N ? pb.S[col] : 0;
+        walk(Aw, pa, (size_t)rb, pa.S + rb * kUnitRows, [&](int n) {
+            if (col >= N) return;
+            int cur = -1;
+            float c = 0.0f;
+            for (int i = 0; i < n; ++i) {
+                const uint32_t rec = s_rec[i];
+                const int row = rb * kUnitRows + (int)(rec & 31u), k = (int)(rec >> 5);
+                if (row >= M) continue;
+                if (row != cur) {                            // records of one row are consecutive only per unit: keep C in a register while they are
+                    if (cur >= 0) C[(size_t)cur * ldc + col] = c;
+                    cur = row;
+                    c = C[(size_t)row * ldc + col];
+                }
+                const int kbk = k / kUnitK;
+                const size_t uidx = (size_t)ub * kblocks + kbk;
+                const float x = unit_value(Bw, uidx * kUnitVec, pb, pb.mask[uidx], (k % kUnitK) / 8, cr, k % 8);
+                c = __fmaf_rn(s_val[i], ldexpf(x, -sb), c);
+            }
+            if (cur >= 0) C[(size_t)cur * ldc + col] = c;
+        });
+    }
+    if (do_b) {
+        // 2. the rows of this block, one per lane of the first half-wave: C[row][col0] += a0(row, k) * b
+        const int row = rb * kUnitRows + (tid & 31);
+        const int sa = pa.S[rb * kUnitRows + (tid & 31)];
+        for (int u = 0; u < 8; ++u) {
+            const int ub = ub0 + u;
+            if (ub * kUnitRows >= N) break;                  // workgroup-uniform
+            walk(Bw, pb, (size_t)ub, pb.S + ub * kUnitRows, [&](int n) {
+                if (tid >= 32 || row >= M) return;
+                for (int i = 0; i < n; ++i) {
+                    const uint32_t rec = s_rec[i];
+                    const int col = ub * kUnitRows + (int)(rec & 31u), k = (int)(rec >> 5);
+                    if (col >= N) continue;
+                    const size_t at = ((size_t)rb * kblocks + k / kUnitK) * kUnitVec + (size_t)(((k % kUnitK) / 8) * kUnitRows + (tid & 31));
+                    const float a = ldexpf(half_of(Aw[at], k % 8), -sa);      // plane 0 only
+                    float *dst = C + (size_t)row * ldc + col;
+                    *dst = __fmaf_rn(a, s_val[i], *dst);
+                }
+            });
+        }
+    }
 }
 
 // C[r][c] = sum over the k parts of part[s][r][c]  (parts are dense M x N slabs)
@@ -1216,9 +1297,21 @@ template <int PS, int TM, int TN>
 static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int img, int kblocks,
                           const Plan &plan, float *part, hipStream_t stream, const Planes &pa, const Planes &pb)
 {
+    // the elements outside plane 0 of exponent-plane operands follow the product (plain row-major results only)
+    auto tail = [&]() {
+        if (PS != 0 || pa.S == nullptr) return FMT_OK;
+        if (img != 0) return FMT_ERR_SHAPE;
+        const int64_t col_chunks = (N + 255) / 256, blocks = (int64_t)((M + kUnitRows - 1) / kUnitRows) * col_chunks;
+        if (blocks >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
+        hipLaunchKernelGGL(planes_tail_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, Aw, Bw, pa, pb, C, ldc, M, N, kblocks,
+                           (int)col_chunks);
+        FMT_HIP_CHECK(hipGetLastError());
+        return FMT_OK;
+    };
     if (plan.nsplit == 1) {
-        return plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, pa, pb)
-                          : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, pa, pb);
+        int rc1 = plan.sched ? launch_product_v<PS, TM, TN, false, true>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, pa, pb)
+                             : launch_product_v<PS, TM, TN, false, false>(Aw, Bw, C, M, N, ldc, img, kblocks, 1, stream, pa, pb);
+        return rc1 != FMT_OK ? rc1 : tail();
     }
     int rc = plan.sched
                  ? launch_product_v<PS, TM, TN, true, true>(Aw, Bw, part, M, N, (int64_t)N, 0, kblocks, plan.nsplit, stream, pa, pb)
@@ -1228,7 +1321,7 @@ static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int
     const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
     hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc, img);
     FMT_HIP_CHECK(hipGetLastError());
-    return FMT_OK;
+    return tail();
 }
 
 // One operand of a product as the caller describes it: a plain matrix (kind kSrcMatrix, leading
