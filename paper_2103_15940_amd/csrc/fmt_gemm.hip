@@ -109,11 +109,13 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
 //   mask   one byte per unit (32 rows x 32 k): bit 0 set always, bit 1 / bit 2 set when the unit has
 //          an element in the plane above / below; only then has that plane's unit been written
 //   plane  16-byte vectors from one plane's pieces to the next (planes 1 and 2 follow plane 0)
+//   any    cleared by the kernel that picks the scales, set by the prepare kernel
 struct Planes {
     int *S;
     uint8_t *mask;
     size_t plane;
     int w;               // 40 - m: binades one plane holds
+    int *any;            // one word per operand: non-zero when some unit has an element outside plane 0
 };
 
 constexpr int kWinTmin = 0, kWinTmax = 31;              // range of plane 0's top binade T (S = 15 - T): with
@@ -688,7 +690,10 @@ __device__ __forceinline__ void prepare_scaled_block(const PrepOperand &o, int K
         }
     }
     const bool leader = kcontig ? (tid / 8 == 0 && tid % 4 == 0) : (tid / 64 == 0 && tid % 32 == 0);
-    if (leader) o.pl.mask[(size_t)rb * kblocks + kb] = (uint8_t)(1u | have);
+    if (leader) {
+        o.pl.mask[(size_t)rb * kblocks + kb] = (uint8_t)(1u | have);
+        if (have != 0u) *o.pl.any = 1;           // every writer stores the same value
+    }
 }
 
 // One launch prepares both operands of a product (or one: b.nblocks == 0).
@@ -1029,9 +1034,13 @@ __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restric
     const int rb = blockIdx.x / col_chunks, cc = blockIdx.x % col_chunks;
     const int ub0 = cc * 8;                      // first unit of B of this block (B is padded to whole groups of 8 units)
 
+    const bool some_a = *pa.any != 0, some_b = *pb.any != 0;     // workgroup-uniform
+    if (!some_a && !some_b) return;
     bool any_a = false, any_b = false;
-    for (int kb = tid; kb < kblocks; kb += 256) any_a |= (pa.mask[(size_t)rb * kblocks + kb] & 6u) != 0u;
-    for (int i = tid; i < 8 * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
+    if (some_a)
+        for (int kb = tid; kb < kblocks; kb += 256) any_a |= (pa.mask[(size_t)rb * kblocks + kb] & 6u) != 0u;
+    if (some_b)
+        for (int i = tid; i < 8 * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
     const bool do_a = __syncthreads_or((int)any_a) != 0, do_b = __syncthreads_or((int)any_b) != 0;
     if (!do_a && !do_b) return;
 
@@ -1124,23 +1133,51 @@ __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restric
         const int sb = col < N ? pb.S[col] : 0;
         walk(Aw, pa, (size_t)rb, pa.S + rb * kUnitRows, [&](int n) {
             if (col >= N) return;
-            int cur = -1;
-            float c = 0.0f;
-            for (int i = 0; i < n; ++i) {
-                const uint32_t rec = s_rec[i];
-                const int row = rb * kUnitRows + (int)(rec & 31u), k = (int)(rec >> 5);
-                if (row >= M) continue;
-                if (row != cur) {                            // records of one row are consecutive only per unit: keep C in a register while they are
-                    if (cur >= 0) C[(size_t)cur * ldc + col] = c;
-                    cur = row;
-                    c = C[(size_t)row * ldc + col];
+            // four records at a time: their loads (B's vector and mask, C) are issued together, then the
+            // additions follow in record order; a row met earlier in the batch hands its sum on in registers
+            for (int i0 = 0; i0 < n; i0 += 4) {
+                int row[4], k[4];
+                float a[4], c[4];
+                u32x4 xv[4];
+                uint32_t mk[4];
+                size_t uv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const bool live = i0 + u < n;
+                    const uint32_t rec = live ? s_rec[i0 + u] : 0u;
+                    row[u] = rb * kUnitRows + (int)(rec & 31u);
+                    k[u] = (int)(rec >> 5);
+                    a[u] = live ? s_val[i0 + u] : 0.0f;
+                    if (!live || row[u] >= M) row[u] = -1;
+                    const size_t uidx = (size_t)ub * kblocks + k[u] / kUnitK;
+                    uv[u] = uidx * kUnitVec;
+                    mk[u] = 0u;
+                    xv[u] = u32x4{0u, 0u, 0u, 0u};
+                    c[u] = 0.0f;
+                    if (row[u] >= 0) {
+                        mk[u] = pb.mask[uidx];
+                        xv[u] = Bw[uv[u] + (size_t)(((k[u] % kUnitK) / 8) * kUnitRows + cr)];
+                        c[u] = C[(size_t)row[u] * ldc + col];
+                    }
                 }
-                const int kbk = k / kUnitK;
-                const size_t uidx = (size_t)ub * kblocks + kbk;
-                const float x = unit_value(Bw, uidx * kUnitVec, pb, pb.mask[uidx], (k % kUnitK) / 8, cr, k % 8);
-                c = __fmaf_rn(s_val[i], ldexpf(x, -sb), c);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (row[u] < 0) continue;
+#pragma unroll
+                    for (int v = 0; v < u; ++v)
+                        if (row[v] == row[u]) c[u] = c[v];           // the latest sum of that row (v ascending)
+                    float x = half_of(xv[u], k[u] % 8);
+                    if (mk[u] & 6u) x = unit_value(Bw, uv[u], pb, mk[u], (k[u] % kUnitK) / 8, cr, k[u] % 8);
+                    c[u] = __fmaf_rn(a[u], ldexpf(x, -sb), c[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    bool last = row[u] >= 0;
+#pragma unroll
+                    for (int v = u + 1; v < 4; ++v) last = last && row[v] != row[u];
+                    if (last) C[(size_t)row[u] * ldc + col] = c[u];
+                }
             }
-            if (cur >= 0) C[(size_t)cur * ldc + col] = c;
         });
     }
     if (do_b) {
@@ -1369,12 +1406,13 @@ static Scheme scheme_of(fmt_format_t f, bool want_planes)
 //   [pieces]  units x kblocks x P units of 128 vectors; with planes: three planes of units x kblocks units
 //   [S]       with planes: one int per padded row
 //   [mask]    with planes: one byte per unit
+//   [any]     with planes: one word
 // every part 256-byte aligned.
 struct OperandLayout {
     Scheme sch;
     int w;                       // planes: binades per plane
     int rows, kblocks, units;
-    size_t plane_vec, s_off, mask_off, bytes;
+    size_t plane_vec, s_off, mask_off, any_off, bytes;
 };
 
 static int operand_layout(int64_t rows, int64_t K, Scheme sch, int m, OperandLayout *L)
@@ -1391,7 +1429,8 @@ static int operand_layout(int64_t rows, int64_t K, Scheme sch, int m, OperandLay
     const size_t piece_bytes = up256(L->plane_vec * sizeof(u32x4) * (sch.scaled ? 3 : 1));
     L->s_off = piece_bytes;
     L->mask_off = L->s_off + (sch.scaled ? up256((size_t)L->units * kUnitRows * sizeof(int)) : 0);
-    L->bytes = L->mask_off + (sch.scaled ? up256((size_t)L->units * L->kblocks) : 0);
+    L->any_off = L->mask_off + (sch.scaled ? up256((size_t)L->units * L->kblocks) : 0);
+    L->bytes = L->any_off + (sch.scaled ? 256 : 0);
     return FMT_OK;
 }
 
@@ -1406,11 +1445,12 @@ static OperandView view_of(void *base, const OperandLayout &L)
     char *b = static_cast<char *>(base);
     OperandView v;
     v.W = reinterpret_cast<u32x4 *>(b);
-    v.pl = Planes{nullptr, nullptr, 0, L.w};
+    v.pl = Planes{nullptr, nullptr, 0, L.w, nullptr};
     if (L.sch.scaled) {
         v.pl.S = reinterpret_cast<int *>(b + L.s_off);
         v.pl.mask = reinterpret_cast<uint8_t *>(b + L.mask_off);
         v.pl.plane = L.plane_vec;
+        v.pl.any = reinterpret_cast<int *>(b + L.any_off);
     }
     return v;
 }
@@ -1424,6 +1464,7 @@ struct StatOperand {
     int rows_pad;
     int kcontig;
     int *S;
+    int *any;
     unsigned nblocks;
 };
 
@@ -1443,6 +1484,10 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
 {
     __shared__ int s_hi[8][32], s_lo[8][32];
     const int tid = threadIdx.x;
+    if (blockIdx.x == 0 && tid == 0) {           // the prepare kernel that follows sets these again
+        *a.any = 0;
+        if (b.nblocks != 0u) *b.any = 0;
+    }
     const bool second = blockIdx.x >= a.nblocks;
     const StatOperand &o = second ? b : a;
     const int by = blockIdx.x - (second ? a.nblocks : 0u);
@@ -1558,6 +1603,7 @@ static int prepare_operands(const OperandSpec &sa, const OperandLayout &la, cons
                 t.rows_pad = L.units * kUnitRows;
                 t.kcontig = o.kcontig;
                 t.S = o.pl.S;
+                t.any = o.pl.any;
                 t.nblocks = present ? (unsigned)L.units : 0u;
                 return t;
             };

@@ -184,3 +184,48 @@ def test_thresholds_match_oracle_for_every_format():
             assert np.isfinite(q[4]) and q[4] == c["maxN"], (e, m)
             assert np.isinf(q[5]), (e, m)
             assert tz < td < to <= 0x7F800000
+
+
+def test_prepared_operand_calls_validate_without_gpu():
+    """fmt_operand_bytes is a host computation; fmt_prepare and fmt_gemm_prepared check their arguments
+    before any HIP call."""
+    lib = fmt.raw_library()
+    f = fmt._CFormat(6, 9, 1)
+    n = ctypes.c_size_t()
+    assert lib.fmt_operand_bytes(100, 200, f, ctypes.byref(n)) == 0
+    # 100 rows pad to 256, 200 k to 224: at least 2 bytes per padded element, at most 6 plus the row scales and masks
+    assert 256 * 224 * 2 <= n.value <= 256 * 224 * 6 + 16384 and n.value % 256 == 0
+    bigger = ctypes.c_size_t()
+    assert lib.fmt_operand_bytes(1000, 200, f, ctypes.byref(bigger)) == 0 and bigger.value > n.value
+    assert lib.fmt_operand_bytes(0, 200, f, ctypes.byref(n)) == -3
+    assert lib.fmt_operand_bytes(100, 1 << 31, f, ctypes.byref(n)) == -3
+    assert lib.fmt_operand_bytes(100, 200, fmt._CFormat(9, 9, 1), ctypes.byref(n)) == -1
+    assert lib.fmt_operand_bytes(100, 200, f, None) == -2
+    buf = (ctypes.c_char * 1024)()
+    base = (ctypes.addressof(buf) + 255) // 256 * 256
+    op = fmt._COperand()
+    x = ctypes.c_void_p(base)
+    assert lib.fmt_prepare(None, 200, 0, 100, 200, f, base, 1 << 30, ctypes.byref(op), None) == -2
+    assert lib.fmt_prepare(x, 100, 0, 100, 200, f, base + 512, 1 << 30, ctypes.byref(op), None) == -3      # ld < k
+    assert lib.fmt_prepare(x, 200, 0, 100, 200, f, base + 512 + 4, 1 << 30, ctypes.byref(op), None) == -4  # data not 256-byte aligned
+    assert lib.fmt_prepare(x, 200, 0, 100, 200, f, base + 512, 64, ctypes.byref(op), None) == -3           # buffer too small
+    assert lib.fmt_prepare(x, 200, 0, 100, 200, f, base, 1 << 30, ctypes.byref(op), None) == -6            # buffer overlaps X
+    need = ctypes.c_size_t()
+    lib.fmt_operand_bytes(64, 96, f, ctypes.byref(need))
+    a = fmt._COperand(base, need.value, 64, 96, f, 16)
+    b = fmt._COperand(base + (1 << 20), need.value, 64, 64, f, 16)
+    c = ctypes.c_void_p(base + (1 << 21))
+    assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), c, 64, None) == -3        # k differs
+    b.k = 96
+    assert lib.fmt_gemm_prepared(ctypes.byref(a), None, c, 64, None) == -2
+    assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), c, 32, None) == -3        # ldc < N
+    b.format = fmt._CFormat(5, 10, 1)
+    assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), c, 64, None) == -1        # formats differ
+    b.format = f
+    b.scheme = 2
+    assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), c, 64, None) == -1        # schemes differ
+    b.scheme = 16
+    a.bytes = 128
+    assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), c, 64, None) == -3        # operand buffer too small
+    a.bytes = need.value
+    assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), ctypes.c_void_p(base + 256), 64, None) == -6   # C overlaps A

@@ -131,8 +131,10 @@ def test_empty_and_degenerate(fmt):
 @pytest.mark.parametrize("f", [(6, 9, True), (5, 10, True), (8, 7, False)])
 def test_config3_full_size_sampled(fmt, f):
     """ResNet-style 3x3 convolution of config 3 (batch 64, 256 -> 256 channels, 14 x 14), forward,
-    dgrad and wgrad at full size: 4000 sampled outputs each against the oracle, error measured
-    against the norm of the sampled reference values."""
+    dgrad and wgrad at full size: sampled outputs against the oracle -- one in every 64 x 64 block of
+    the underlying product (rows: filters or channels; columns: positions or taps), the smallest tile
+    the product kernel has, so that no tile and no k part can be skipped, plus 2000 random ones --
+    error measured against the norm of the sampled reference values."""
     cfg = workloads.config3()
     X, W2, dY2 = cfg["X"], cfg["W"], cfg["dY"]
     n, c, h, w = X.shape
@@ -142,10 +144,18 @@ def test_config3_full_size_sampled(fmt, f):
     Y, dX, dW = run_all(fmt, X, W, dY, f, (1, 1), (1, 1))
     e, m, d = f
     rng = np.random.default_rng(33)
-    for name, got, ref_fn in (("Y", Y, lambda s: oracle.conv2d_fwd(X, W, e, m, d, sample=s)),
-                              ("dX", dX, lambda s: oracle.conv2d_dgrad(dY, W, X.shape, e, m, d, sample=s)),
-                              ("dW", dW, lambda s: oracle.conv2d_wgrad(dY, X, W.shape, e, m, d, sample=s))):
-        idx = rng.integers(0, got.size, 4000)
+    def blocks(rows, cols, to_flat):
+        bi, bj = np.meshgrid(np.arange(0, rows, 64), np.arange(0, cols, 64), indexing="ij")
+        r = np.minimum(bi + rng.integers(0, 64, bi.shape), rows - 1).ravel()
+        q = np.minimum(bj + rng.integers(0, 64, bj.shape), cols - 1).ravel()
+        return to_flat(r, q)
+    hw = h * w
+    nchw = lambda chans: (lambda r, q: ((q // hw) * chans + r) * hw + q % hw)       # row = channel, column = (image, position)
+    for name, got, ref_fn, pinned in (
+            ("Y", Y, lambda s: oracle.conv2d_fwd(X, W, e, m, d, sample=s), blocks(k, n * hw, nchw(k))),
+            ("dX", dX, lambda s: oracle.conv2d_dgrad(dY, W, X.shape, e, m, d, sample=s), blocks(c, n * hw, nchw(c))),
+            ("dW", dW, lambda s: oracle.conv2d_wgrad(dY, X, W.shape, e, m, d, sample=s), blocks(k, c * 9, lambda r, q: r * c * 9 + q))):
+        idx = np.concatenate([pinned, rng.integers(0, got.size, 2000)])
         ref = ref_fn(idx)
         assert np.all(np.isfinite(got))
         assert rel_err(got.ravel()[idx], ref) <= TOL, "%s: %.3g" % (name, rel_err(got.ravel()[idx], ref))

@@ -212,21 +212,36 @@ def test_config2_mlp_shapes(fmt):
             dY = (out * (acts[l] > 0)).astype(np.float32)
 
 
+def _block_samples(M, N, seed, block=64):
+    """One output position in every block x block square of an M x N result (64 is the smallest
+    workgroup tile, and every k part of a split feeds every output of its tile: no tile of any plan and
+    no k part can be skipped), plus the corners."""
+    rng = np.random.default_rng(seed)
+    bi, bj = np.meshgrid(np.arange(0, M, block), np.arange(0, N, block), indexing="ij")
+    rows = np.minimum(bi + rng.integers(0, block, bi.shape), M - 1).ravel()
+    cols = np.minimum(bj + rng.integers(0, block, bj.shape), N - 1).ravel()
+    return np.concatenate([rows, [0, 0, M - 1, M - 1]]), np.concatenate([cols, [0, N - 1, 0, N - 1]])
+
+
 def _sampled_check(fmt, A, B, f, tA, tB, nsamp, seed):
-    """Full-size product on the GPU; the oracle computes `nsamp` sampled outputs one by one."""
+    """Full-size product on the GPU; the oracle computes sampled outputs one by one: one in every
+    64 x 64 block of the result.  Besides the relative Frobenius error over the samples, every sample is
+    held against the size of the terms it sums (fp32 accumulation of K exact products errs by a few
+    sqrt(K) 2^-24 of sum |a||b|), so a wrong tile cannot hide behind large neighbours."""
     Ad, Bd = dev(A), dev(B)
     C = fmt.fmt_gemm(Ad, Bd, f, transA=tA, transB=tB)
     torch.cuda.synchronize()
     M, N = C.shape
-    rng = np.random.default_rng(seed)
-    rows = rng.integers(0, M, nsamp)
-    cols = rng.integers(0, N, nsamp)
-    # always include the corners and the last row/column (ragged-edge handling)
-    rows[:4] = [0, 0, M - 1, M - 1]
-    cols[:4] = [0, N - 1, 0, N - 1]
+    rows, cols = _block_samples(M, N, seed)
     got = C[torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()].cpu().numpy()
     ref = oracle.gemm_sampled(A, B, rows, cols, f[0], f[1], f[2], transA=tA, transB=tB)
-    return rel_fro(got, ref), C
+    terms = oracle.gemm_sampled(np.abs(A), np.abs(B), rows, cols, f[0], f[1], f[2], transA=tA, transB=tB).astype(np.float64)
+    K = A.shape[0] if tA else A.shape[1]
+    ok = np.isfinite(ref)
+    err = np.abs(got.astype(np.float64)[ok] - ref.astype(np.float64)[ok])
+    assert np.all(err <= 16 * np.sqrt(K) * 2.0 ** -24 * terms[ok] + 1e-45), (f, tA, tB, int(np.argmax(err / (terms[ok] + 1e-300))))
+    assert np.array_equal(np.isfinite(got), ok)
+    return rel_fro(got[ok], ref[ok]), C
 
 
 def test_config3_conv_im2col_full_size(fmt):

@@ -354,3 +354,43 @@ def test_seeded_random_cases(fmt, seed):
         assert np.array_equal(got[oy:oy + n], oracle.pack16(x, e, m, d)), what
         assert np.all(got[:oy] == 0x5555) and np.all(got[oy + n:] == 0x5555), what
         assert_same_hist(fmt, hist, want_h, what)
+
+
+def test_config2_every_tensor_of_a_step(fmt):
+    """Config 2 call by call: one forward + backward step of the 784-1024-1024-10 MLP at batch 256 with
+    loss scale 1024; fmt_quantize + statistics of EVERY tensor the step rounds -- the input, the three
+    weight matrices, the three layer outputs, the loss-scaled gradient of the logits and the two
+    back-propagated gradients (256 x 784 ... 256 x 10) -- against the oracle, bit for bit, in the three
+    formats.  The step itself (products, ReLU, softmax) is harness glue in float64 on the host: parity is
+    per call on identical inputs."""
+    import oracle
+    cfg = workloads.config2()
+    X, W = cfg["X"], cfg["W"]
+    tensors = [("X", X)] + [("W%d" % l, W[l]) for l in range(3)]
+    acts = [X.astype(np.float64)]
+    for l in range(3):
+        z = acts[-1] @ W[l].astype(np.float64).T
+        tensors.append(("Y%d" % l, z.astype(np.float32)))
+        acts.append(np.maximum(z, 0) if l < 2 else z)
+    z = acts[-1]
+    p = np.exp(z - z.max(1, keepdims=True))
+    p /= p.sum(1, keepdims=True)
+    p[np.arange(z.shape[0]), cfg["labels"]] -= 1.0
+    g = p / z.shape[0] * cfg["loss_scale"]
+    tensors.append(("dY2", g.astype(np.float32)))
+    for l in (2, 1):
+        g = (g @ W[l].astype(np.float64)) * (acts[l] > 0)
+        tensors.append(("dY%d" % (l - 1), g.astype(np.float32)))
+    assert {t.shape for _, t in tensors} >= {(256, 784), (1024, 784), (256, 1024), (10, 1024), (256, 10)}
+    for e, m, d in [(6, 9, True), (5, 10, True), (8, 7, False)]:
+        for name, t in tensors:
+            flat = np.ascontiguousarray(t).ravel()
+            xd = torch.from_numpy(flat).cuda()
+            hist = fmt.new_hist(xd.device)
+            y = fmt.fmt_quantize(xd, (e, m, d), hist=hist)
+            torch.cuda.synchronize()
+            want = oracle.quantize(flat, e, m, d)
+            assert np.array_equal(y.cpu().numpy().view(np.uint32), want.view(np.uint32)), (name, e, m, d)
+            got, ho = fmt.hist_to_dict(hist), oracle.histogram(flat, e, m)
+            assert all(got[k] == ho[k] for k in fmt.CLASS_NAMES), (name, e, m, d, got, ho)
+            assert np.array_equal(got["bins"], ho["bins"]), (name, e, m, d)
