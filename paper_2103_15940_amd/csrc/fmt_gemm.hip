@@ -109,13 +109,11 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
 //   mask   one byte per unit (32 rows x 32 k): bit 0 set always, bit 1 / bit 2 set when the unit has
 //          an element in the plane above / below; only then has that plane's unit been written
 //   plane  16-byte vectors from one plane's pieces to the next (planes 1 and 2 follow plane 0)
-//   any    cleared by the kernel that picks the scales, set by the prepare kernel
 struct Planes {
     int *S;
     uint8_t *mask;
     size_t plane;
     int w;               // 40 - m: binades one plane holds
-    int *any;            // one word per operand: non-zero when some unit has an element outside plane 0
 };
 
 constexpr int kWinTmin = 0, kWinTmax = 31;              // range of plane 0's top binade T (S = 15 - T): with
@@ -690,10 +688,7 @@ __device__ __forceinline__ void prepare_scaled_block(const PrepOperand &o, int K
         }
     }
     const bool leader = kcontig ? (tid / 8 == 0 && tid % 4 == 0) : (tid / 64 == 0 && tid % 32 == 0);
-    if (leader) {
-        o.pl.mask[(size_t)rb * kblocks + kb] = (uint8_t)(1u | have);
-        if (have != 0u) *o.pl.any = 1;           // every writer stores the same value
-    }
+    if (leader) o.pl.mask[(size_t)rb * kblocks + kb] = (uint8_t)(1u | have);
 }
 
 // One launch prepares both operands of a product (or one: b.nblocks == 0).
@@ -1019,7 +1014,7 @@ __device__ __forceinline__ float unit_value(const u32x4 *__restrict__ W, size_t 
 //      rows (an element of A outside plane 0 has met b in step 1), in the same kind of order.
 // Every element of C has one owner and a fixed order of additions: the result is reproducible bit for bit.
 // A block whose units hold nothing but plane 0 -- the usual case -- leaves after reading its masks.
-constexpr int kTailRecs = 4096;                  // element records kept before they are applied (a unit holds at most 1024 per plane)
+constexpr int kTailRecs = kUnitRows * kUnitK;    // element records held at a time: one plane of one unit always fits
 
 __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw, Planes pa,
                                                           Planes pb, float *__restrict__ C, int64_t ldc, int M, int N, int kblocks,
@@ -1029,18 +1024,15 @@ __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restric
     __shared__ float s_val[kTailRecs];           // the element's true value
     __shared__ uint32_t s_list[256];             // k blocks (of one scan of 256) whose unit has other planes | planes << 16
     __shared__ int s_cnt[4];
-    __shared__ int s_n;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rb = blockIdx.x / col_chunks, cc = blockIdx.x % col_chunks;
     const int ub0 = cc * 8;                      // first unit of B of this block (B is padded to whole groups of 8 units)
 
-    const bool some_a = *pa.any != 0, some_b = *pb.any != 0;     // workgroup-uniform
-    if (!some_a && !some_b) return;
-    bool any_a = false, any_b = false;
-    if (some_a)
-        for (int kb = tid; kb < kblocks; kb += 256) any_a |= (pa.mask[(size_t)rb * kblocks + kb] & 6u) != 0u;
-    if (some_b)
-        for (int i = tid; i < 8 * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
+    // this thread's mask byte of the row of units of A (k block tid); rows longer than 256 k blocks are re-read later
+    const uint32_t first_a = tid < kblocks ? (uint32_t)pa.mask[(size_t)rb * kblocks + tid] & 6u : 0u;
+    bool any_a = first_a != 0u, any_b = false;
+    for (int kb = 256 + tid; kb < kblocks; kb += 256) any_a |= (pa.mask[(size_t)rb * kblocks + kb] & 6u) != 0u;
+    for (int i = tid; i < 8 * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
     const bool do_a = __syncthreads_or((int)any_a) != 0, do_b = __syncthreads_or((int)any_b) != 0;
     if (!do_a && !do_b) return;
 
@@ -1066,64 +1058,73 @@ __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restric
         return before + incl - have;
     };
 
-    // Collects the elements of the other planes of one unit (plane-0 vectors at W + unit_vec, planes per
-    // `planes`) as records (position along the unit's rows, k, true value with the row scales S of that
-    // unit undone), appended to s_rec / s_val in the order (plane, vector, position).  All threads call it.
-    auto collect = [&](const u32x4 *__restrict__ W, const Planes &pl, size_t unit_vec, uint32_t planes, int kb, const int *S32) {
-        for (int q = 1; q <= 2; ++q) {
-            if (((planes >> q) & 1u) == 0u) continue;      // workgroup-uniform
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (tid < kUnitVec) v = W[(size_t)q * pl.plane + unit_vec + tid];     // vector tid: k-chunk tid / 32, row tid % 32
-            int have = 0;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) have += (((t & 1) ? v[t >> 1] >> 16 : v[t >> 1]) & 0x7FFFu) != 0u ? 1 : 0;
-            int total;
-            int at = s_n + place(have, total);
-            if (have) {
-                const int r = tid & 31, c = tid >> 5;
-                const int undo = -(S32[r] + (q == 1 ? -pl.w : pl.w));        // the plane above carries 2^(S - w), the one below 2^(S + w)
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const uint32_t hp = ((t & 1) ? v[t >> 1] >> 16 : v[t >> 1]) & 0xFFFFu;
-                    if (hp & 0x7FFFu) {
-                        s_rec[at] = (uint32_t)r | ((uint32_t)(kb * kUnitK + c * 8 + t) << 5);
-                        s_val[at] = ldexpf(static_cast<float>(__builtin_bit_cast(_Float16, (uint16_t)hp)), undo);
-                        ++at;
-                    }
-                }
-            }
-            __syncthreads();
-            if (tid == 0) s_n += total;
-            __syncthreads();
-        }
-    };
-
-    // Walks the units of one row of units (mask row `mrow`) that have other planes, k ascending, collecting
-    // their elements; `apply` is called whenever the records must be used up (and once at the end).
-    auto walk = [&](const u32x4 *__restrict__ W, const Planes &pl, size_t urow, const int *S32, auto &&apply) {
-        if (tid == 0) s_n = 0;
+    // Walks the units of one row of units (mask row urow of operand W / pl, row scales S32) that have
+    // other planes, k ascending, four units at a time: the two other planes of a unit are 256 vectors, one
+    // per thread (threads 0..127 the plane above, vector tid: k-chunk tid / 32, row tid % 32; threads
+    // 128..255 the plane below), all four units' loads are issued together, their non-zero elements become
+    // records (row in the unit, k, TRUE value: the pattern with the plane's and the row's scale undone) in a
+    // fixed order (thread, unit, position), and `apply(n)` uses up the n records of the group.
+    auto walk = [&](const u32x4 *__restrict__ W, const Planes &pl, size_t urow, const int *S32, uint32_t first, bool have_first,
+                    auto &&apply) {
+        const int q = tid < kUnitVec ? 1 : 2, vec = tid & (kUnitVec - 1);
+        const int r = vec & 31, c = vec >> 5;
+        const int undo = -(S32[r] + (q == 1 ? -pl.w : pl.w));   // the plane above carries 2^(S - w), the one below 2^(S + w)
         for (int base = 0; base < kblocks; base += 256) {
             const int kb = base + tid;
-            const uint32_t m = kb < kblocks ? (uint32_t)pl.mask[urow * kblocks + kb] & 6u : 0u;
+            const uint32_t m = base == 0 && have_first ? first : (kb < kblocks ? (uint32_t)pl.mask[urow * kblocks + kb] & 6u : 0u);
             int total;
             const int at = place(m != 0u ? 1 : 0, total);
             if (m != 0u) s_list[at] = (uint32_t)tid | (m << 16);
             __syncthreads();
-            for (int n = 0; n < total; ++n) {
-                const uint32_t e = s_list[n];
-                if (s_n > kTailRecs - 2 * kUnitRows * kUnitK) {          // room for one more unit's two planes?
-                    apply(s_n);
-                    __syncthreads();
-                    if (tid == 0) s_n = 0;
-                    __syncthreads();
+            for (int n0 = 0; n0 < total; n0 += 4) {
+                u32x4 v[4];
+                int kbn[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t e = n0 + u < total ? s_list[n0 + u] : 0u;
+                    kbn[u] = base + (int)(e & 0xFFFFu);
+                    v[u] = u32x4{0u, 0u, 0u, 0u};
+                    if ((e >> (16 + q)) & 1u) v[u] = W[(size_t)q * pl.plane + (urow * kblocks + kbn[u]) * kUnitVec + vec];
                 }
-                const int kbn = base + (int)(e & 0xFFFFu);
-                collect(W, pl, (urow * kblocks + kbn) * kUnitVec, e >> 16, kbn, S32);
+                // records of unit u (all four: u < 0) and plane qq (both: qq == 0) of this group, then their use
+                auto emit = [&](int only_u, int only_q) {
+                    const bool mine = only_q == 0 || only_q == q;
+                    int cnt = 0;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (mine && (only_u < 0 || only_u == u)) {
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) cnt += (((t & 1) ? v[u][t >> 1] >> 16 : v[u][t >> 1]) & 0x7FFFu) != 0u ? 1 : 0;
+                        }
+                    int nrec;
+                    int at2 = place(cnt, nrec);
+                    if (nrec > kTailRecs) return nrec;       // workgroup-uniform: the caller splits the group
+                    if (cnt) {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            if (only_u < 0 || only_u == u) {
+#pragma unroll
+                                for (int t = 0; t < 8; ++t) {
+                                    const uint32_t hp = ((t & 1) ? v[u][t >> 1] >> 16 : v[u][t >> 1]) & 0xFFFFu;
+                                    if (hp & 0x7FFFu) {
+                                        s_rec[at2] = (uint32_t)r | ((uint32_t)(kbn[u] * kUnitK + c * 8 + t) << 5);
+                                        s_val[at2] = ldexpf(static_cast<float>(__builtin_bit_cast(_Float16, (uint16_t)hp)), undo);
+                                        ++at2;
+                                    }
+                                }
+                            }
+                    }
+                    __syncthreads();
+                    apply(nrec);
+                    __syncthreads();                         // the records are free again
+                    return nrec;
+                };
+                if (emit(-1, 0) > kTailRecs) {               // rare: many elements outside plane 0 -- one plane of one unit at a time
+                    for (int u = 0; u < 4; ++u)
+                        for (int qq = 1; qq <= 2; ++qq) (void)emit(u, qq);
+                }
             }
-            __syncthreads();                                 // s_list is rewritten by the next scan
         }
-        apply(s_n);
-        __syncthreads();
     };
 
     if (do_a) {
@@ -1131,7 +1132,7 @@ __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restric
         const int col = cc * 256 + tid;
         const int ub = col / kUnitRows, cr = col % kUnitRows;
         const int sb = col < N ? pb.S[col] : 0;
-        walk(Aw, pa, (size_t)rb, pa.S + rb * kUnitRows, [&](int n) {
+        walk(Aw, pa, (size_t)rb, pa.S + rb * kUnitRows, first_a, true, [&](int n) {
             if (col >= N) return;
             // four records at a time: their loads (B's vector and mask, C) are issued together, then the
             // additions follow in record order; a row met earlier in the batch hands its sum on in registers
@@ -1187,7 +1188,7 @@ __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restric
         for (int u = 0; u < 8; ++u) {
             const int ub = ub0 + u;
             if (ub * kUnitRows >= N) break;                  // workgroup-uniform
-            walk(Bw, pb, (size_t)ub, pb.S + ub * kUnitRows, [&](int n) {
+            walk(Bw, pb, (size_t)ub, pb.S + ub * kUnitRows, 0u, false, [&](int n) {
                 if (tid >= 32 || row >= M) return;
                 for (int i = 0; i < n; ++i) {
                     const uint32_t rec = s_rec[i];
@@ -1406,13 +1407,12 @@ static Scheme scheme_of(fmt_format_t f, bool want_planes)
 //   [pieces]  units x kblocks x P units of 128 vectors; with planes: three planes of units x kblocks units
 //   [S]       with planes: one int per padded row
 //   [mask]    with planes: one byte per unit
-//   [any]     with planes: one word
 // every part 256-byte aligned.
 struct OperandLayout {
     Scheme sch;
     int w;                       // planes: binades per plane
     int rows, kblocks, units;
-    size_t plane_vec, s_off, mask_off, any_off, bytes;
+    size_t plane_vec, s_off, mask_off, bytes;
 };
 
 static int operand_layout(int64_t rows, int64_t K, Scheme sch, int m, OperandLayout *L)
@@ -1429,8 +1429,7 @@ static int operand_layout(int64_t rows, int64_t K, Scheme sch, int m, OperandLay
     const size_t piece_bytes = up256(L->plane_vec * sizeof(u32x4) * (sch.scaled ? 3 : 1));
     L->s_off = piece_bytes;
     L->mask_off = L->s_off + (sch.scaled ? up256((size_t)L->units * kUnitRows * sizeof(int)) : 0);
-    L->any_off = L->mask_off + (sch.scaled ? up256((size_t)L->units * L->kblocks) : 0);
-    L->bytes = L->any_off + (sch.scaled ? 256 : 0);
+    L->bytes = L->mask_off + (sch.scaled ? up256((size_t)L->units * L->kblocks) : 0);
     return FMT_OK;
 }
 
@@ -1445,12 +1444,11 @@ static OperandView view_of(void *base, const OperandLayout &L)
     char *b = static_cast<char *>(base);
     OperandView v;
     v.W = reinterpret_cast<u32x4 *>(b);
-    v.pl = Planes{nullptr, nullptr, 0, L.w, nullptr};
+    v.pl = Planes{nullptr, nullptr, 0, L.w};
     if (L.sch.scaled) {
         v.pl.S = reinterpret_cast<int *>(b + L.s_off);
         v.pl.mask = reinterpret_cast<uint8_t *>(b + L.mask_off);
         v.pl.plane = L.plane_vec;
-        v.pl.any = reinterpret_cast<int *>(b + L.any_off);
     }
     return v;
 }
@@ -1464,7 +1462,6 @@ struct StatOperand {
     int rows_pad;
     int kcontig;
     int *S;
-    int *any;
     unsigned nblocks;
 };
 
@@ -1484,10 +1481,6 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
 {
     __shared__ int s_hi[8][32], s_lo[8][32];
     const int tid = threadIdx.x;
-    if (blockIdx.x == 0 && tid == 0) {           // the prepare kernel that follows sets these again
-        *a.any = 0;
-        if (b.nblocks != 0u) *b.any = 0;
-    }
     const bool second = blockIdx.x >= a.nblocks;
     const StatOperand &o = second ? b : a;
     const int by = blockIdx.x - (second ? a.nblocks : 0u);
@@ -1603,7 +1596,6 @@ static int prepare_operands(const OperandSpec &sa, const OperandLayout &la, cons
                 t.rows_pad = L.units * kUnitRows;
                 t.kcontig = o.kcontig;
                 t.S = o.pl.S;
-                t.any = o.pl.any;
                 t.nblocks = present ? (unsigned)L.units : 0u;
                 return t;
             };
