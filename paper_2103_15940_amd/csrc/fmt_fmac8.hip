@@ -1,11 +1,20 @@
 // fmt_gemm_fmac8: matrix product with the FMAC-8 accumulation of Sec. IV-A, Algorithm 1.
 //
-// Every output element is one dot product run exactly as the algorithm lists it: a 16-bit
-// accumulator a takes 8 consecutive FMACs, a = Q(a + w_i * x_i) with ONE rounding of the exact sum
-// to the format (FMAC of Sec. III-B); at every i that is a multiple of 8 it is added into an fp32
-// master accumulator with an fp32 addition and reset; the result is Q(master).  The chain of
-// roundings is sequential by definition, so this is plain ALU work (no matrix cores): the bound
-// is the vector rate (single precision where the fused step is exact in it, else double).
+// Every output element is a dot product taken in groups of 8 consecutive k: inside a group a 16-bit
+// accumulator a (a value of the format, starting at zero) takes 8 fused multiply-adds,
+// a = Q(a + w_k * x_k) with ONE rounding of the exact sum to the format (FMAC of Sec. III-B); after
+// the group it is added into an fp32 master accumulator with one fp32 addition; the result is
+// Q(master).  (Operands are zero-padded to whole groups: a + 0 * 0 = a is a value of the format, so a
+// padded step changes nothing.)  The chain of roundings is sequential by definition, so this is plain
+// ALU work (no matrix cores), bound by the rate at which the vector units issue instructions: one per
+// lane and clock.
+//
+// Formats with e <= 6 and m <= 11 run the fused step in single precision around the hardware's own
+// fused multiply-add, s = fma(w, x, a): the exact sum rounded ONCE to 24 bits.  Rounding s to the
+// format afterwards equals rounding the exact sum directly unless s lands exactly on a midpoint of
+// the format's grid while the exact sum does not; only a wave that holds such a lane (rare) computes
+// the exact error of the sum and puts that lane on the side of the midpoint where the exact sum lies.
+// 14 vector instructions per fused step instead of 22.
 //
 // The fused step is done in fp64: the product of two <= 24-bit significands is exact; the sum
 // a + w*x is rounded to odd (TwoSum gives the exact error; if it is non-zero and the fp64 sum is
@@ -58,24 +67,50 @@ __device__ __forceinline__ double add_round_to_odd(double a, double p)
 }
 
 // The fused step in single precision, for formats with e <= 6 and m <= 11: the product of two
-// (m+1)-bit significands has at most 24 bits and, with Emin >= -30, lies in fp32's normal range,
-// so w * x is exact; TwoSum's error term is exact for the same reason; the sum rounded to odd has
-// 24 significant bits, at least two more than the format, so rounding it to the format equals one
-// rounding of the exact sum -- with quantize_bits, the rounding every other kernel uses.  Half the
-// register file and twice the vector rate of the fp64 step.
-template <int MODE, bool FTZ>
-__device__ __forceinline__ float fmac_f32(float a, float w, float x, const QuantParams &qp)
+// (m+1)-bit significands has at most 24 bits and, with Emin >= -30, lies in fp32's normal range, so
+// w * x and the error term of TwoSum are exact in fp32.
+// The step around the hardware FMA (see the top of the file), in two parts so that the rare exact
+// correction costs one branch per 16 steps instead of one per step.
+struct FmaConsts {
+    float minn, tovf, inf2;     // 2^Emin; the input magnitude from which the result is infinite; 2^(Emax+1)
+};
+
+// Common path: returns Q(fma(w, x, a)) and, in `tie`, whether the 24-bit sum sits exactly on a midpoint
+// of the format's grid (then fmac_fix decides).
+template <bool FTZ>
+__device__ __forceinline__ float fmac_try(float a, float w, float x, const QuantParams &qp, const FmaConsts &k, bool &tie)
 {
-    const float p = __fmul_rn(w, x);
-    const float s = __fadd_rn(a, p);
+    const float s = __fmaf_rn(w, x, a);                   // exact product, exact sum, one rounding to 24 bits
+    // C = 2^(max(E, Emin) + 23 - m): (|s| + C) - C rounds |s| to the format's grid around it (RNE).  For an
+    // infinite or NaN s the pattern of C is a NaN, so r is: the selection below restores the infinity.
+    const uint32_t ce = max(__float_as_uint(s) & 0x7F800000u, qp.minn_bits) + qp.shift23;
+    const float c = __uint_as_float(ce), fa = fabsf(s);
+    float r = __fsub_rn(__fadd_rn(fa, c), c);
+    tie = fabsf(__fsub_rn(fa, r)) == __uint_as_float(ce - (24u << 23));   // moved by exactly half a step, C * 2^-24
+    if (FTZ) r = r < k.minn ? 0.0f : r;                   // the flush acts on the rounded value
+    r = fa >= k.tovf ? __uint_as_float(0x7F800000u) : r;  // false for NaN, which stays NaN
+    return copysignf(r, s);
+}
+
+// Exact correction for the lanes where fmac_try reported a midpoint: a + w*x = s + err exactly (TwoSum on
+// the exact product); a non-zero err puts the exact sum off the midpoint, on err's side, and the result
+// is the grid neighbour on that side.
+template <bool FTZ>
+__device__ __forceinline__ float fmac_fix(float tried, float a, float w, float x, const QuantParams &qp, const FmaConsts &k)
+{
+    const float p = __fmul_rn(w, x);                       // exact (two (m+1)-bit significands)
+    const float s = __fadd_rn(a, p);                       // the same 24-bit sum the FMA gave
     const float bb = __fsub_rn(s, a);
     const float err = __fadd_rn(__fsub_rn(a, __fsub_rn(s, bb)), __fsub_rn(p, bb));
-    uint32_t u = __float_as_uint(s);
-    if (err != 0.0f && err == err && (u & 1u) == 0u) {
-        const bool away = (err > 0.0f) == (s > 0.0f);
-        u += away ? 1u : 0xFFFFFFFFu;
-    }
-    return __uint_as_float(quantize_bits<MODE, FTZ>(u, qp));
+    const uint32_t ce = max(__float_as_uint(s) & 0x7F800000u, qp.minn_bits) + qp.shift23;
+    const float c = __uint_as_float(ce), fa = fabsf(s), half = __uint_as_float(ce - (24u << 23));
+    const float r0 = __fsub_rn(__fadd_rn(fa, c), c);
+    const bool tie = fabsf(__fsub_rn(fa, r0)) == half;
+    if (!tie || !(err != 0.0f)) return tried;              // a true tie keeps the even neighbour the adder chose
+    float r = ((err > 0.0f) == (s > 0.0f)) ? __fadd_rn(fa, half) : __fsub_rn(fa, half);
+    if (FTZ) r = r < k.minn ? 0.0f : r;
+    r = r >= k.inf2 ? __uint_as_float(0x7F800000u) : r;
+    return copysignf(r, s);
 }
 
 constexpr int kFTile = 64;     // outputs per workgroup edge
@@ -93,15 +128,13 @@ __global__ __launch_bounds__(256) void fmac8_kernel(const uint32_t *__restrict__
     const int row0 = (blockIdx.x / tiles_n) * kFTile, col0 = (blockIdx.x % tiles_n) * kFTile;
 
     typedef typename std::conditional<F32, float, double>::type acc_t;
-    acc_t acc16[4][4];                             // the 16-bit accumulators (values of the format)
     float acc32[4][4];                             // the fp32 master accumulators
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            acc16[i][j] = (acc_t)0;
-            acc32[i][j] = 0.0f;
-        }
+        for (int j = 0; j < 4; ++j) acc32[i][j] = 0.0f;
+    const FmaConsts fk = {__uint_as_float(qp.minn_bits), __uint_as_float(qp.t_ovf),
+                          __uint_as_float((qp.t_ovf & 0x7F800000u) + 0x00800000u)};   // t_ovf lies in the top binade
 
     for (int k0 = 0; k0 < K; k0 += kFK) {
         // stage: 64 x 32 values of each operand, rounded to the format on the way in
@@ -120,32 +153,56 @@ __global__ __launch_bounds__(256) void fmac8_kernel(const uint32_t *__restrict__
             sb[bk][br] = __uint_as_float(quantize_bits<MODE, FTZ>(vb, qp));
         }
         __syncthreads();
-        const int kmax = min(kFK, K - k0);
-        for (int kk = 0; kk < kmax; ++kk) {
-            if ((kk & 7) == 0) {                   // global index k0 + kk is a multiple of 8 as well
+        // groups of 8 k (the stage is zero-padded beyond K): 8 fused steps from a = 0, then one fp32 addition
+        for (int g = 0; g < kFK / 8; ++g) {
+            acc_t a16[4][4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        acc32[i][j] = acc32[i][j] + (float)acc16[i][j];   // single-precision addition
-                        acc16[i][j] = (acc_t)0;
+                for (int j = 0; j < 4; ++j) a16[i][j] = (acc_t)0;
+#pragma unroll
+            for (int kk = g * 8; kk < g * 8 + 8; ++kk) {
+                acc_t w[4], x[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w[i] = (acc_t)sa[kk][ty * 4 + i];
+                    x[i] = (acc_t)sb[kk][tx * 4 + i];
+                }
+                if constexpr (F32) {
+                    // the 16 chains take their step; which lanes met a midpoint is kept as wave masks
+                    float nx[4][4];
+                    unsigned long long met[4][4], any = 0ull;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            bool tie;
+                            nx[i][j] = fmac_try<FTZ>(a16[i][j], w[i], x[j], qp, fk, tie);
+                            met[i][j] = __ballot(tie);
+                            any |= met[i][j];
+                        }
+                    if (any != 0ull) {                     // wave-uniform; about one step in eight
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                if (met[i][j] != 0ull) nx[i][j] = fmac_fix<FTZ>(nx[i][j], a16[i][j], w[i], x[j], qp, fk);
                     }
-            }
-            acc_t w[4], x[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                w[i] = (acc_t)sa[kk][ty * 4 + i];
-                x[i] = (acc_t)sb[kk][tx * 4 + i];
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) a16[i][j] = nx[i][j];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) a16[i][j] = quantize_f64(add_round_to_odd(a16[i][j], w[i] * x[j]), fp);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if constexpr (F32)
-                        acc16[i][j] = fmac_f32<MODE, FTZ>(acc16[i][j], w[i], x[j], qp);
-                    else
-                        acc16[i][j] = quantize_f64(add_round_to_odd(acc16[i][j], w[i] * x[j]), fp);
-                }
+                for (int j = 0; j < 4; ++j) acc32[i][j] = acc32[i][j] + (float)a16[i][j];   // single-precision addition
         }
         __syncthreads();
     }
@@ -155,10 +212,8 @@ __global__ __launch_bounds__(256) void fmac8_kernel(const uint32_t *__restrict__
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int c = col0 + tx * 4 + j;
-            if (r < M && c < N) {
-                const float master = acc32[i][j] + (float)acc16[i][j];
-                C[(size_t)r * ldc + c] = __uint_as_float(quantize_bits<MODE, FTZ>(__float_as_uint(master), qp));
-            }
+            if (r < M && c < N)
+                C[(size_t)r * ldc + c] = __uint_as_float(quantize_bits<MODE, FTZ>(__float_as_uint(acc32[i][j]), qp));
         }
     }
 }
