@@ -43,7 +43,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/stream_kernel_config5_hbm_traffic.md), scaled by the same counters on a plain 1 GiB copy.
-MEASURED_TRAFFIC_BYTES = 2157505500   # profiles/stream_kernel_config5_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = 2157514900   # profiles/stream_kernel_config5_hbm_traffic.md
 
 
 def main() -> int:
@@ -54,7 +54,7 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=1 << 28, help="elements of the stream tensor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-copy", action="store_true",
-                    help="also run three plain device-to-device copies of the stream tensor before the warm-up: "
+                    help="also run three plain device-to-device copies of the stream tensor (with --gemm: of a 1 GiB tensor) before the warm-up: "
                          "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
     ap.add_argument("--gemm-streams", type=int, default=3,
@@ -97,6 +97,11 @@ def main() -> int:
             call = lambda: fmt.fmt_gemm_prepared(Ap, Bp, out=C)
         else:
             call = lambda: fmt.fmt_gemm(A, B, (e_, m_, bool(d_)), transA=bool(tA), transB=bool(tB), out=C)
+        if args.profile_copy:                     # 1 GiB read + 1 GiB written: calibrates FETCH_SIZE / WRITE_SIZE
+            src = torch.zeros(1 << 28, device=dev)
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
         for _ in range(args.warmup):
             call()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
