@@ -41,6 +41,39 @@ __device__ __forceinline__ void account(uint32_t a, bool valid, const QuantParam
     }
 }
 
+// The same statistics for a run of elements that are all valid, in two parts.  account_run does the
+// table increment and the three counters every element needs, and keeps the largest pattern seen in
+// amax; after the run, account_run_top looks at amax once and recounts the run's elements for the
+// overflow / infinity / NaN counters only if one of them can be non-zero anywhere in the wave.
+template <bool DEEP, int COPIES>
+__device__ __forceinline__ void account_run(uint32_t a, const QuantParams &p, uint32_t *tbl, uint32_t copy, Counts &w,
+                                            uint32_t &amax)
+{
+    uint32_t row = a >> 23;
+    if (DEEP) {
+        if (a - 1u < 0x007FFFFFu) row = 256u + (31u - (uint32_t)__builtin_clz(a));
+    }
+    __hip_atomic_fetch_add(&tbl[row * COPIES + copy], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    w.z += a == 0u ? 1u : 0u;
+    w.zu += a <= p.t_zero ? 1u : 0u;
+    w.zud += a < p.t_den ? 1u : 0u;
+    amax = a > amax ? a : amax;
+}
+
+template <int N>
+__device__ __forceinline__ void account_run_top(const uint32_t (&u)[N], uint32_t amax, const QuantParams &p, Counts &w)
+{
+    if (__ballot(amax >= p.t_ovf)) {     // wave-uniform: rare for real tensors
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const uint32_t a = u[j] & 0x7FFFFFFFu;
+            w.top += a >= p.t_ovf ? 1u : 0u;
+            w.infnan += a >= 0x7F800000u ? 1u : 0u;
+            w.nan += a > 0x7F800000u ? 1u : 0u;
+        }
+    }
+}
+
 // Zeroes the table and the two small arrays; ends with a barrier.  tbl must be 16-byte aligned.
 template <int COPIES, int BLOCK>
 __device__ __forceinline__ void hist_begin(uint32_t *tbl, uint32_t *s_bins, uint32_t *s_cls, uint32_t tid)

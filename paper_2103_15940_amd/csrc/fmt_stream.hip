@@ -44,12 +44,17 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = FMT_STREAM_BLOCK;  // threads per workgroup
-constexpr int kCopies = 32;              // replicas of the exponent table (one per LDS bank)
+// Replicas of the exponent table in LDS, lane l uses replica l % copies.  The fused kernel that writes fp32 keeps
+// one replica per bank (32: 35 KiB, 4 workgroups per compute unit); the statistics-only kernel and the one that writes
+// 16-bit codes run 8 to 12 % faster with 16 (17.5 KiB, 8 workgroups per compute unit), the fused fp32 one does not.
+constexpr int kCopiesFused = 32;
+constexpr int kCopiesLight = 16;
 constexpr int kUnroll = FMT_STREAM_UNROLL;  // independent 128-bit loads in flight per thread
 constexpr int kGridPerCU = FMT_STREAM_GRID_PER_CU;   // workgroups launched per compute unit (at most): statistics only
-constexpr int kGridFused = 64;           // ... fused quantize + statistics
+constexpr int kGridFused = 64;           // ... fused quantize + statistics, fp32 out
+constexpr int kGridPack = 128;           // ... fused quantize + statistics, 16-bit codes out
 constexpr int kGridStore = 256;          // ... quantize only
-template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP>
+template <int MODE, bool STORE, bool FTZ, bool HIST, bool DEEP, int kCopies>
 __device__ __forceinline__ u32x4 do_vec(u32x4 v, bool valid, const QuantParams &p, uint32_t *tbl, uint32_t lane32,
                                         Counts &w)
 {
@@ -75,6 +80,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
                                                         unsigned long long *__restrict__ partials)
 {
     constexpr int EM = MODE == kModeInteger ? kModeInteger : kModeMagic;   // encode_bits' variant
+    constexpr int kCopies = (STORE && !PACK) ? kCopiesFused : kCopiesLight;
     uint16_t *__restrict__ y16 = reinterpret_cast<uint16_t *>(y);
     auto put = [&](size_t vec_index, u32x4 o) {
         if (PACK) {
@@ -112,10 +118,25 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
             u32x4 v[kUnroll];
 #pragma unroll
             for (int k = 0; k < kUnroll; ++k) v[k] = __builtin_nontemporal_load(xv + i + k * kBlock);
+            uint32_t amax = 0u;
 #pragma unroll
             for (int k = 0; k < kUnroll; ++k) {
-                u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v[k], true, p, tbl, lane32, w);
+                u32x4 o = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t u = v[k][j];
+                    if (HIST) account_run<DEEP, kCopies>(u & 0x7FFFFFFFu, p, tbl, lane32, w, amax);
+                    if (STORE) o[j] = quantize_bits<MODE, FTZ>(u, p);
+                }
                 if (STORE) put(i + k * kBlock, o);
+            }
+            if (HIST) {
+                uint32_t flat[4 * kUnroll];
+#pragma unroll
+                for (int k = 0; k < kUnroll; ++k)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) flat[4 * k + j] = v[k][j];
+                account_run_top(flat, amax, p, w);
             }
         }
         if (blockIdx.x == full_tiles % gridDim.x && full_tiles * kTileVec < nvec) {
@@ -126,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
                 const bool valid = i < nvec;
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (valid) v = __builtin_nontemporal_load(xv + i);
-                u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP>(v, valid, p, tbl, lane32, w);
+                u32x4 o = do_vec<MODE, STORE, FTZ, HIST, DEEP, kCopies>(v, valid, p, tbl, lane32, w);
                 if (STORE && valid) put(i, o);
             }
         }
@@ -222,8 +243,9 @@ static int launch_variant(const float *x, void *y, size_t n, size_t head, size_t
     // Workgroups per compute unit, measured on 2^28 elements: a pure stream likes one 16 KiB tile per
     // workgroup (6.4 TB/s against 5.9 with 16 per CU: the hardware balances the tail); every workgroup
     // of a statistics pass pays for clearing and folding its LDS table, so the read-only pass keeps 16
-    // per CU (6.3 TB/s) and the fused pass settles in between (64 per CU: 6.07 against 5.77 TB/s).
-    const size_t cap = (size_t)cus * (HIST ? (STORE ? kGridFused : kGridPerCU) : kGridStore);
+    // per CU (6.3 TB/s) and the fused pass settles in between (64 per CU: 6.07 against 5.77 TB/s; 128 per
+    // CU when it writes 16-bit codes, where 8 workgroups fit a compute unit).
+    const size_t cap = (size_t)cus * (HIST ? (STORE ? (PACK ? kGridPack : kGridFused) : kGridPerCU) : kGridStore);
     size_t g = want;
     if (HIST) {
         // mid-size tensors: at least four tiles per workgroup (one tile does not pay for the table),
