@@ -43,6 +43,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/stream_kernel_config5_hbm_traffic.md), scaled by the same counters on a plain 1 GiB copy.
+# Vector-ALU issue rate of the chip (one instruction per lane and clock: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz)
+# and the vector instructions one FMAC-8 step takes on the single-precision path (rounded count from the ISA).
+VALU_LANE_INSTR_PER_S = 256 * 64 * 2.4e9
+FMAC8_INSTR_PER_MAC = 12.0
 MEASURED_TRAFFIC_BYTES = 2157514900   # profiles/stream_kernel_config5_hbm_traffic.md
 
 
@@ -507,7 +511,15 @@ def main() -> int:
     C8 = torch.empty((2048, 2048), device=dev)
     f8_ms = timed(lambda: fmt.fmt_gemm_fmac8(A8, B8, f169, out=C8), reps)
     result["fmac8"] = {"workload": "fmt_gemm_fmac8 2048x2048x1024, 1/6/9/d", "ms": round(f8_ms, 4),
-                       "value": round(2048.0 * 2048 * 1024 / (f8_ms * 1e-3) / 1e12, 3), "unit": "T fused-MAC/s"}
+                       "value": round(2048.0 * 2048 * 1024 / (f8_ms * 1e-3) / 1e12, 3), "unit": "T fused-MAC/s",
+                       "roofline": {"bound": "alu", "unit": "T fused-MAC/s",
+                                    "peak": round(VALU_LANE_INSTR_PER_S / FMAC8_INSTR_PER_MAC / 1e12, 3),
+                                    "achieved": round(2048.0 * 2048 * 1024 / (f8_ms * 1e-3) / 1e12, 3),
+                                    "frac": round(2048.0 * 2048 * 1024 / (f8_ms * 1e-3)
+                                                  / (VALU_LANE_INSTR_PER_S / FMAC8_INSTR_PER_MAC), 4),
+                                    "note": "vector issue rate 256 CUs x 64 lanes x 2.4 GHz = 39.3 T "
+                                            "lane-instructions/s over about 12 instructions per fused step "
+                                            "of the single-precision path"}}
     # loss-scale controller on the nine statistics records of configuration 4's gradient tensors
     recs = torch.stack([L["h"][2] for L in layers])
     st = fmt.fmt_dls_init(1024.0)

@@ -24,12 +24,16 @@
  *                  used for fully connected layers and im2col convolutions in forward,
  *                  dgrad and wgrad (Sec. IV-A)
  * and, beyond these three:
+ *   fmt_operand_bytes / fmt_prepare / fmt_gemm_prepared   fmt_gemm in two steps: a tensor is rounded once
+ *                  into a reusable operand in caller-owned memory (Sec. IV-A rounds each tensor once and
+ *                  uses it in several products), and products run on two such operands
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
  *   fmt_linear     the quantized fully connected layer of Sec. IV-A (product, bias, output roundings, statistics)
  *   fmt_pack16 / fmt_unpack16 / fmt_linear_pack16   the same roundings with the result stored as the
  *                  format's own 16-bit codes (Sec. III) instead of fp32: half the bytes written
  *   fmt_conv2d_*   convolution forward / dgrad / wgrad as the same product on patches gathered on the fly
  *   fmt_dls_step   loss-scale controller and denormal-fraction monitor on the device (Sec. II, Sec. V)
+ *   fmt_quantize_static   fmt_quantize for callers that cannot allocate device memory
  *
  * Conventions common to all calls
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
