@@ -424,7 +424,7 @@ def main() -> int:
         fmt.fmt_conv2d_dgrad(dY4d, W4d, X4d.shape, f169, out=dXc)
         fmt.fmt_conv2d_wgrad(dY4d, X4d, W4d.shape, f169, out=dWc)
     conv_ms = timed(conv_all, reps)
-    result["conv_config3"] = {"workload": "config 3 via fmt_conv2d_fwd/_dgrad/_wgrad, 1/6/9/d: no fp32 patch matrix, patches gathered from the tensors into the 16-bit operand layout",
+    result["conv_config3"] = {"workload": "config 3 via fmt_conv2d_fwd/_dgrad/_wgrad, 1/6/9/d, rounding of the tensors included: forward and dgrad gather the patches inside the product kernel (scratch of the tensor's size), wgrad through a gathered 16-bit operand; two bf16 pieces (4 MFMA products per multiply)",
                               "ms": round(conv_ms, 4), "value": round(3 * 2.0 * M * N * K / (conv_ms * 1e-3) / 1e12, 2),
                               "unit": "TFLOP/s (useful)"}
     # quantized Linear forward of the four encoder layers: product, bias, both output roundings, statistics of t

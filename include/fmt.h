@@ -342,9 +342,12 @@ int fmt_linear_pack16(int64_t M, int64_t N, int64_t K,
  * (positions outside the tensor contribute zero).  These are fmt_gemm's products on the patch
  * matrix of the convolution -- same rounding of the operands, exact products, fp32 accumulation in
  * unspecified order, unrounded fp32 result, same error bound -- but nobody forms the fp32 patch
- * matrix (r*s times the size of the tensor): the tensor is rounded once and the operand preparation
- * gathers the patches from it straight into the product kernel's 16-bit operand layout in library
- * scratch (2 bytes per patch element and 16-bit piece of the format; freed by fmt_release_scratch).
+ * matrix (r*s times the size of the tensor): the tensor is rounded once into 16-bit pieces in library
+ * scratch (2 bytes per tensor element and piece of the format; freed by fmt_release_scratch) and the
+ * patches are gathered from that.  fmt_conv2d_fwd with c a multiple of 32, and fmt_conv2d_dgrad with k a
+ * multiple of 32 and stride 1, both with r*s <= 32, gather inside the product kernel: their scratch is of
+ * the size of the tensor.  The other cases and fmt_conv2d_wgrad gather in the operand preparation, into a
+ * 16-bit operand of the size of the patch matrix (2 bytes per patch element and piece) in scratch.
  *
  * All pointers are device pointers, 4-byte aligned; the output must not overlap an input.
  * Sizes: n, c, k >= 0; h, w, r, s >= 1; pad >= 0; stride >= 1; h + 2 pad_h >= r, w + 2 pad_w >= s;

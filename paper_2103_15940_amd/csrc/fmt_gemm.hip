@@ -125,7 +125,9 @@ enum {
     kSrcPatchRows = 1,  // convolution patches: row = (n, y, x) on a grid gy x gx, k = (ch, r, s)
     kSrcPatchK = 2,     // the same patches transposed: row = (ch, r, s), k = (n, y, x)
     kSrcChannelRows = 3,  // NCHW tensor as a matrix: row = channel, k = (n, position)
-    kSrcFilterT = 4     // filter [K][C][R][S] with row = c, k = (kout, r, s)
+    kSrcFilterT = 4,    // filter [K][C][R][S] with row = c, k = (kout, r, s)
+    kSrcFilterTap = 5   // filter [K][C][R][S] with k = (tap, channel): element (row, k) sits at
+                        // row*th + (k % D)*tw + k / D, D = k0.d channels (th, tw hold the two strides)
 };
 
 // Division of a 31-bit dividend by a divisor fixed at launch, as a multiply-high and a shift
@@ -192,6 +194,26 @@ struct PrepOperand {
     unsigned nblocks;   // workgroups of this operand: slabs * row groups
     Gather g;
     Planes pl;          // pl.S != nullptr: scaled fp16 exponent planes (PS == 0, plain matrices only)
+};
+
+// Operand B of a convolution product gathered by the product kernel itself: row = position (n, y, x)
+// on a grid gy x gx, k = (tap, channel) with the channel running fastest, read from the rounded tensor
+// in pixel-major order T[piece][n][iy][ix][channel] (16-bit pieces, 8 channels per 16-byte vector; tc is a
+// multiple of 32, so a stage of 16 or 32 k lies inside one tap).  iy = y*mul_y + off_y + tap_sign*r, likewise
+// ix; a tap outside the tensor reads the zero vector at index `zero`.  Every index counts 16-byte vectors
+// from T and fits 31 bits.
+struct Implicit {
+    const u32x4 *T;
+    int piece_vec;      // vectors per piece
+    int zero;           // index of a vector of zeros
+    int c8;             // channels / 8
+    int th, tw, gy, gx;
+    int mul_y, mul_x, off_y, off_x, tap_sign;
+    int R, S;
+    int rows;
+    FastDiv r0, r1;     // row -> (n, y, x): by gx, then by gy
+    FastDiv kc;         // stage number -> (tap, channel block): by channels / (k per stage)
+    FastDiv ks;         // tap -> (r, s): by S
 };
 
 // Offset of tap (r, s) seen from the spatial base (by, bx) = (y*mul + off) inside one h x w plane,
@@ -280,6 +302,17 @@ __device__ __forceinline__ void gather8(const PrepOperand &o, int row, int k0, i
             gather_patches<false>(o, row, k0, K, idx);
         else
             gather_patches<true>(o, row, k0, K, idx);
+    } else if (g.kind == kSrcFilterTap) {
+        int ch, tap;
+        divmod(g.k0, k0, tap, ch);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (k0 + j < K) idx[j] = row * g.th + ch * g.tw + tap;
+            if (++ch == g.k0.d) {
+                ch = 0;
+                ++tap;
+            }
+        }
     } else {
         // kSrcChannelRows: k = (image, position), L = g.k0.d positions; kSrcFilterT: k = (filter, tap),
         // L = R*S taps; element (row, k) sits at ((k / L) * tc + row) * L + k % L in both
@@ -317,6 +350,50 @@ __global__ __launch_bounds__(256) void round_split_kernel(const uint32_t *__rest
         out[n] = 0u;
         if (P >= 3) out[plane + n] = 0u;
     }
+}
+
+// Rounds an NCHW tensor (C a multiple of 32) to the format, splits it, and writes the pieces in
+// pixel-major order out[piece][pixel][channel] (16 bits per element) -- the operand the product kernel
+// gathers convolution patches from.  A workgroup takes 64 consecutive pixels (of the flattened n*h*w)
+// by 32 channels: reads run along pixels, the transposition goes through LDS, and a lane writes 8
+// consecutive channels of one pixel as one 16-byte vector.  One vector of zeros follows the last piece.
+template <int MODE, bool FTZ, int PS>
+__global__ __launch_bounds__(256) void nhwc_split_kernel(const uint32_t *__restrict__ x, u32x4 *__restrict__ out, int C,
+                                                         int HW, int npix, QuantParams p)
+{
+    constexpr int P = pieces_of(PS);
+    constexpr int kPitch = 18;                                  // 32-bit words per pixel row (16 + 2: odd multiple of 2)
+    __shared__ uint32_t tile[P][64][kPitch];
+    const int tid = threadIdx.x;
+    const int pix = tid % 64, cg = tid / 64;
+    const int gp = blockIdx.x * 64 + pix, cb = blockIdx.y;
+    const bool valid = gp < npix;
+    const int n = valid ? gp / HW : 0, hw = valid ? gp - n * HW : 0;
+    const uint32_t *src = x + ((size_t)n * C + cb * 32 + cg * 8) * HW + hw;
+    uint32_t pc[8][P];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t u = valid ? src[(size_t)i * HW] : 0u;
+        round_and_split<MODE, FTZ, PS>(u, p, pc[i]);
+    }
+#pragma unroll
+    for (int q = 0; q < P; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tile[q][pix][cg * 4 + i] = pc[2 * i][q] | (pc[2 * i + 1][q] << 16);
+    __syncthreads();
+    const int opix = tid / 4, part = tid % 4;
+    const int ogp = blockIdx.x * 64 + opix;
+    const size_t piece_vec = (size_t)npix * (C / 8);
+    if (ogp < npix) {
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            u32x4 w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[i] = tile[q][opix][part * 4 + i];
+            out[q * piece_vec + (size_t)ogp * (C / 8) + cb * 4 + part] = w;
+        }
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) out[P * piece_vec] = u32x4{0u, 0u, 0u, 0u};
 }
 
 // Transposed patches (wgrad: rows = taps (ch, r, s), k = positions (n, y, x)), pre-rounded tensor.
@@ -758,11 +835,16 @@ __device__ __forceinline__ void scaled_store(const floatx16 (&acc)[TM][TN], floa
 // SCALED (single fp16 piece only): the operands are exponent planes with per-row power-of-two scales
 // (pa.S / pb.S), undone on the way out; this kernel multiplies plane 0 by plane 0, planes_tail_kernel
 // adds the products of the elements that live in the other planes.
-template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED>
+// GATHER: operand B is not a prepared operand but a rounded convolution tensor in pixel-major order (`im`,
+// Bw unused): a lane's 16-byte load of (position, 8 consecutive k) is 8 consecutive channels of one pixel,
+// whose address is a per-lane base (the position's corner pixel) plus a per-stage term (the tap and the
+// channel block), or the zero vector where the tap falls outside the tensor (a per-lane bit mask over
+// the taps).  The stage image in LDS and everything after it are the same.
+template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED, bool GATHER = false>
 __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
                                                       float *__restrict__ C, int M, int N, int64_t ldc, int img,
                                                       int kblocks, int tiles_m, int tiles_n, int kb_per_split,
-                                                      Planes pa, Planes pb)
+                                                      Planes pa, Planes pb, Implicit im)
 {
     constexpr int P = pieces_of(PS);
     constexpr int UA = 2 * TM, UB = 2 * TN;              // 32-row units per operand in the workgroup tile
@@ -818,11 +900,31 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
         const int rbl = q / (P * SV), piece = (q % (P * SV)) / SV, v = q % SV;
         ga[j] = Aw + ((size_t)tm * UA + rbl) * rb_stride + (size_t)kb0 * P * kUnitVec + piece * kUnitVec + v;
     }
+    int gbase[GATHER ? LB : 1];          // GATHER: vector index of the position's corner pixel (+ piece, + k chunk)
+    uint32_t gmask[GATHER ? LB : 1];     // ... and the taps that fall inside the tensor
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
         const int q = min(j * 256 + tid, VB - 1);
         const int rbl = q / (P * SV), piece = (q % (P * SV)) / SV, v = q % SV;
-        gb[j] = Bw + ((size_t)tn * UB + rbl) * rb_stride + (size_t)kb0 * P * kUnitVec + piece * kUnitVec + v;
+        if constexpr (GATHER) {
+            const int row = (tn * UB + rbl) * kUnitRows + v % kUnitRows;
+            int x, t, y, n;
+            divmod(im.r0, min(row, im.rows - 1), t, x);
+            divmod(im.r1, t, n, y);
+            const int by = y * im.mul_y + im.off_y, bx = x * im.mul_x + im.off_x;
+            uint32_t mq = 0u;
+            int tap = 0;
+            for (int r = 0; r < im.R; ++r)
+                for (int s2 = 0; s2 < im.S; ++s2, ++tap) {
+                    const int iy = by + im.tap_sign * r, ix = bx + im.tap_sign * s2;
+                    if ((unsigned)iy < (unsigned)im.th && (unsigned)ix < (unsigned)im.tw) mq |= 1u << tap;
+                }
+            gmask[j] = row < im.rows ? mq : 0u;
+            gbase[j] = piece * im.piece_vec + ((n * im.th + by) * im.tw + bx) * im.c8 + v / kUnitRows;
+            gb[j] = im.T;
+        } else {
+            gb[j] = Bw + ((size_t)tn * UB + rbl) * rb_stride + (size_t)kb0 * P * kUnitVec + piece * kUnitVec + v;
+        }
     }
 
     floatx16 acc[TM][TN];
@@ -843,10 +945,24 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
         for (int j = 0; j < LA; ++j)
             if (VA % 256 == 0 || j * 256 + wave * 64 < VA)
                 __builtin_amdgcn_global_load_lds((glb_void *)(ga[j] + off), (lds_void *)(sa + j * 256 + wave * 64), 16, 0, 0);
+        if constexpr (GATHER) {
+            // stage number (in stages of 16*KS k) -> tap and channel block: the same in the whole workgroup
+            int tap, cb, r, s2;
+            divmod(im.kc, kb0 * (2 / KS) + tc, tap, cb);
+            divmod(im.ks, tap, r, s2);
+            const int toff = im.tap_sign * (r * im.tw + s2) * im.c8 + cb * (2 * KS);
 #pragma unroll
-        for (int j = 0; j < LB; ++j)
-            if (VB % 256 == 0 || j * 256 + wave * 64 < VB)
-                __builtin_amdgcn_global_load_lds((glb_void *)(gb[j] + off), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
+            for (int j = 0; j < LB; ++j)
+                if (VB % 256 == 0 || j * 256 + wave * 64 < VB) {
+                    const int at = ((gmask[j] >> tap) & 1u) ? gbase[j] + toff : im.zero;
+                    __builtin_amdgcn_global_load_lds((glb_void *)(im.T + at), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < LB; ++j)
+                if (VB % 256 == 0 || j * 256 + wave * 64 < VB)
+                    __builtin_amdgcn_global_load_lds((glb_void *)(gb[j] + off), (lds_void *)(sb + j * 256 + wave * 64), 16, 0, 0);
+        }
     };
 
     // Operand fragments live in two register sets: while the MFMAs of stage t run on one, the LDS
@@ -1300,9 +1416,9 @@ static Plan make_plan(int M, int N, int kblocks, int cus, int pieces)
     return best;
 }
 
-template <int PS, int TM, int TN, bool SPLIT, bool SCHED, bool SCALED>
+template <int PS, int TM, int TN, bool SPLIT, bool SCHED, bool SCALED, bool GATHER = false>
 static int launch_product_v2(const u32x4 *Aw, const u32x4 *Bw, float *out, int M, int N, int64_t ld, int img, int kblocks,
-                            int nsplit, hipStream_t stream, const Planes &pa, const Planes &pb)
+                            int nsplit, hipStream_t stream, const Planes &pa, const Planes &pb, const Implicit &im = Implicit{})
 {
     constexpr int KS = Pipe<PS, TM, TN>::ks, NST = Pipe<PS, TM, TN>::nst;
     if constexpr (lds_bytes(TM, TN, pieces_of(PS), KS, NST) > 160 * 1024) {
@@ -1312,9 +1428,11 @@ static int launch_product_v2(const u32x4 *Aw, const u32x4 *Bw, float *out, int M
         const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
         if (per_xcd * 8 * nsplit >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
         const int kb_per = (kblocks + nsplit - 1) / nsplit;
-        auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED, SCALED>;
+        auto kern = product_kernel<PS, TM, TN, KS, NST, SPLIT, SCHED, SCALED, GATHER>;
+        Implicit imk = im;
+        if (GATHER) imk.kc = make_fastdiv(im.c8 * 8 / (16 * KS));   // stages of 16*KS k per tap
         hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8 * nsplit)), dim3(256), 0, stream, Aw, Bw, out, M, N, ld, img,
-                           kblocks, tiles_m, tiles_n, kb_per, pa, pb);
+                           kblocks, tiles_m, tiles_n, kb_per, pa, pb, imk);
         FMT_HIP_CHECK(hipGetLastError());
         return FMT_OK;
     }
@@ -1333,8 +1451,23 @@ static int launch_product_v(const u32x4 *Aw, const u32x4 *Bw, float *out, int M,
 
 template <int PS, int TM, int TN>
 static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int N, int64_t ldc, int img, int kblocks,
-                          const Plan &plan, float *part, hipStream_t stream, const Planes &pa, const Planes &pb)
+                          const Plan &plan, float *part, hipStream_t stream, const Planes &pa, const Planes &pb,
+                          const Implicit *im = nullptr)
 {
+    if (im != nullptr) {
+        // operand B gathered inside the product kernel (convolutions); no planes, pinned issue order only
+        if (plan.nsplit == 1)
+            return launch_product_v2<PS, TM, TN, false, true, false, true>(Aw, nullptr, C, M, N, ldc, img, kblocks, 1, stream, pa,
+                                                                          pb, *im);
+        int rcg = launch_product_v2<PS, TM, TN, true, true, false, true>(Aw, nullptr, part, M, N, (int64_t)N, 0, kblocks,
+                                                                        plan.nsplit, stream, pa, pb, *im);
+        if (rcg != FMT_OK) return rcg;
+        const size_t total_g = (size_t)M * N;
+        const unsigned rgrid_g = (unsigned)((total_g + 1023) / 1024 < 4096 ? (total_g + 1023) / 1024 : 4096);
+        hipLaunchKernelGGL(reduce_kernel, dim3(rgrid_g ? rgrid_g : 1), dim3(256), 0, stream, part, plan.nsplit, C, M, N, ldc, img);
+        FMT_HIP_CHECK(hipGetLastError());
+        return FMT_OK;
+    }
     // the elements outside plane 0 of exponent-plane operands follow the product (plain row-major results only)
     auto tail = [&]() {
         if (PS != 0 || pa.S == nullptr) return FMT_OK;
@@ -1812,14 +1945,116 @@ int launch_gemm(int transA, int transB, int64_t M64, int64_t N64, int64_t K64, c
     return run_product(M, N, K, sa, sb, OutSpec{C, ldc, 0}, f, p, stream);
 }
 
-// Convolutions (Sec. IV-A) as products of gathered operands: no fp32 patch matrix is formed, the
-// prepare pass gathers from the (once rounded) tensor straight into the 16-bit operand layout.
-//   forward  Y[n][k][p][q]:  M = K filters (rows of the filter matrix [K][C*R*S]),
-//            N = n*P*Q output positions (patches of X), k = C*R*S, result stored NCHW
-//   dgrad    dX[n][c][h][w]: M = C (filter seen as [C][K*R*S]), N = n*H*W input positions
+// Forward and dgrad with the patches gathered inside the product kernel: the tensor behind the patches is
+// rounded once into pixel-major 16-bit pieces (2P bytes per tensor element), the filter into an ordinary
+// prepared operand whose k runs (tap, channel), and no patch-sized operand exists anywhere.
+template <int MODE, bool FTZ, int PS>
+static int run_implicit(int M, int N, int K, const OperandSpec &sa, const float *tensor, int64_t tensor_elems, int HW,
+                        Implicit im, const OutSpec &out, fmt_format_t f, const QuantParams &p, hipStream_t stream)
+{
+    constexpr int P = pieces_of(PS);
+    const Scheme sch{PS, false};
+    OperandLayout la;
+    int rc = operand_layout(M, K, sch, f.m, &la);
+    if (rc != FMT_OK) return rc;
+    int cus = 0;
+    rc = device_cu_count(&cus);
+    if (rc != FMT_OK) return rc;
+    const Plan plan = make_plan(M, N, la.kblocks, cus, P);
+    auto up256 = [](size_t b) { return (b + 255) / 256 * 256; };
+    const int C = im.c8 * 8;
+    const int npix = (int)(tensor_elems / C);
+    const size_t piece_vec = (size_t)npix * im.c8;
+    const size_t nhwc = up256((P * piece_vec + 1) * sizeof(u32x4));
+    const size_t part = part_bytes_of(plan, M, N);
+    Scratch s;
+    rc = get_scratch(stream, 0, la.bytes + nhwc + part, &s);
+    if (rc != FMT_OK) return rc;
+    char *ws = static_cast<char *>(s.gemm_ws);
+    const OperandView va = view_of(ws, la);
+    u32x4 *T = reinterpret_cast<u32x4 *>(ws + la.bytes);
+    float *partp = reinterpret_cast<float *>(ws + la.bytes + nhwc);
+    rc = prepare_operands<MODE, FTZ, PS>(sa, la, va, nullptr, nullptr, nullptr, nullptr, nullptr, K, f, p, stream);
+    if (rc != FMT_OK) return rc;
+    hipLaunchKernelGGL((nhwc_split_kernel<MODE, FTZ, PS>), dim3((unsigned)((npix + 63) / 64), (unsigned)(C / 32)), dim3(256), 0,
+                       stream, reinterpret_cast<const uint32_t *>(tensor), T, C, HW, npix, p);
+    FMT_HIP_CHECK(hipGetLastError());
+    im.T = T;
+    im.piece_vec = (int)piece_vec;
+    im.zero = (int)(P * piece_vec);
+    const Planes none{nullptr, nullptr, 0, 0};
+#define FMT_PRODUCT(TMV, TNV) \
+    launch_product<PS, TMV, TNV>(va.W, nullptr, out.C, M, N, out.ldc, out.img, la.kblocks, plan, partp, stream, none, none, &im)
+    if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
+    if (plan.tm == 4 && plan.tn == 2) return FMT_PRODUCT(4, 2);
+    if (plan.tm == 2 && plan.tn == 4) return FMT_PRODUCT(2, 4);
+    if (plan.tm == 2 && plan.tn == 2) return FMT_PRODUCT(2, 2);
+    return FMT_PRODUCT(1, 1);
+#undef FMT_PRODUCT
+}
+
+// In-kernel gather for forward (which == 0) and dgrad (which == 1): returns FMT_OK after launching, or 1 when
+// the geometry is not covered (channels of the gathered tensor not a multiple of 32, more than 32 taps, dgrad
+// with a stride, index ranges), in which case the caller takes the route through a gathered operand.
+static int conv_implicit(int which, const fmt_conv2d_t &g, int64_t P, int64_t Q, const float *tensor, const float *filt,
+                         float *out, fmt_format_t f, const QuantParams &p, hipStream_t stream)
+{
+    if (const char *env = getenv("FMT_CONV_IMPLICIT"))
+        if (env[0] == '0') return 1;
+    const int tc = which == 0 ? g.c : g.k;                       // channels of the gathered tensor
+    const int64_t th = which == 0 ? g.h : P, tw = which == 0 ? g.w : Q;
+    const int64_t elems = (int64_t)g.n * tc * th * tw;
+    if (tc % 32 != 0 || g.r * g.s > 32 || elems >= ((int64_t)1 << 31)) return 1;
+    if (which == 1 && (g.stride_h != 1 || g.stride_w != 1)) return 1;
+    const Scheme sch = scheme_of(f, false);
+    if ((elems / 8) * pieces_of(sch.ps) + (int64_t)(g.r * tw + g.s) * (tc / 8) >= ((int64_t)1 << 31)) return 1;
+    const int rs = g.r * g.s;
+    const int64_t M = which == 0 ? g.k : g.c, K = (int64_t)tc * rs;
+    const int64_t gy = which == 0 ? P : g.h, gx = which == 0 ? Q : g.w;
+    const int64_t N = (int64_t)g.n * gy * gx;
+    Implicit im{};
+    im.c8 = tc / 8;
+    im.th = (int)th; im.tw = (int)tw; im.gy = (int)gy; im.gx = (int)gx;
+    im.mul_y = which == 0 ? g.stride_h : 1; im.mul_x = which == 0 ? g.stride_w : 1;
+    im.off_y = which == 0 ? -g.pad_h : g.pad_h; im.off_x = which == 0 ? -g.pad_w : g.pad_w;
+    im.tap_sign = which == 0 ? 1 : -1;
+    im.R = g.r; im.S = g.s;
+    im.rows = (int)N;
+    im.r0 = make_fastdiv((int)gx); im.r1 = make_fastdiv((int)gy);
+    im.ks = make_fastdiv(g.s);
+    Gather ft{};
+    ft.kind = kSrcFilterTap;
+    ft.k0 = make_fastdiv(tc);
+    // filter [K][C][R][S]: forward row = filter, k = (tap, c); dgrad row = c, k = (tap, filter)
+    ft.th = which == 0 ? g.c * rs : rs;
+    ft.tw = which == 0 ? rs : g.c * rs;
+    const OperandSpec sa{filt, 0, true, ft, 0};
+    const OutSpec os{out, 0, (int)(gy * gx)};
+    const bool ftz = f.denorm == 0;
+#define FMT_IMPL2(MD, FZ)                                                                                                     \
+    (sch.ps == 0   ? run_implicit<MD, FZ, 0>((int)M, (int)N, (int)K, sa, tensor, elems, (int)(th * tw), im, os, f, p, stream) \
+     : sch.ps == 1 ? run_implicit<MD, FZ, 1>((int)M, (int)N, (int)K, sa, tensor, elems, (int)(th * tw), im, os, f, p, stream) \
+     : sch.ps == 2 ? run_implicit<MD, FZ, 2>((int)M, (int)N, (int)K, sa, tensor, elems, (int)(th * tw), im, os, f, p, stream) \
+                   : run_implicit<MD, FZ, 3>((int)M, (int)N, (int)K, sa, tensor, elems, (int)(th * tw), im, os, f, p, stream))
+#define FMT_IMPL(MD) (ftz ? FMT_IMPL2(MD, true) : FMT_IMPL2(MD, false))
+    if (p.mode == kModeMagic) return FMT_IMPL(kModeMagic);
+    if (p.mode == kModeInteger) return FMT_IMPL(kModeInteger);
+    return FMT_IMPL(kModeMixed);
+#undef FMT_IMPL
+#undef FMT_IMPL2
+}
+
+// Convolutions (Sec. IV-A) as products on patches that are never materialised in fp32.
+//   forward  Y[n][k][p][q]:  M = K filters (rows of the filter matrix), N = n*P*Q output positions
+//            (patches of X), k = C*R*S, result stored NCHW
+//   dgrad    dX[n][c][h][w]: M = C (filter seen from the input channel), N = n*H*W input positions
 //            (patches of dY through the taps that reach them), k = K*R*S, result stored NCHW
 //   wgrad    dW[k][c][r][s]: M = K (dY as [K][n*P*Q]), N = C*R*S (patches of X, transposed),
 //            k = n*P*Q, result is the plain [K][C*R*S] matrix
+// Forward and (stride 1) dgrad with a channel count that is a multiple of 32 and at most 32 taps gather
+// the patches inside the product kernel from the once-rounded tensor (conv_implicit: scratch is 2P bytes
+// per TENSOR element); the other cases, and wgrad, go through a prepare pass that gathers from the once
+// rounded tensor into a patch-sized 16-bit prepared operand.
 int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, fmt_format_t f,
                   const QuantParams &p, hipStream_t stream)
 {
@@ -1839,6 +2074,10 @@ int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float 
         patch.r0 = make_fastdiv(patch.gx); patch.r1 = make_fastdiv(patch.gy);
         patch.k0 = make_fastdiv(g.s); patch.k1 = make_fastdiv(g.r);
         if (K == 0) return zero_fill(out, (int64_t)g.n * M, P * Q, P * Q, stream);
+        {
+            const int rci = conv_implicit(0, g, P, Q, a, b, out, f, p, stream);
+            if (rci <= 0) return rci;
+        }
         const OperandSpec sa{b, K, true, none, 0};                 // filter [K][C*R*S]
         const OperandSpec sb{a, 0, false, patch, (int64_t)g.n * g.c * g.h * g.w};   // patches of X, lanes along positions
         return run_product((int)M, (int)N, (int)K, sa, sb, OutSpec{out, 0, (int)(P * Q)}, f, p, stream);
@@ -1854,6 +2093,10 @@ int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float 
         patch.r0 = make_fastdiv(patch.gx); patch.r1 = make_fastdiv(patch.gy);
         patch.k0 = make_fastdiv(g.s); patch.k1 = make_fastdiv(g.r);
         if (K == 0) return zero_fill(out, (int64_t)g.n * M, (int64_t)g.h * g.w, (int64_t)g.h * g.w, stream);
+        {
+            const int rci = conv_implicit(1, g, P, Q, a, b, out, f, p, stream);
+            if (rci <= 0) return rci;
+        }
         Gather ft{};
         ft.kind = kSrcFilterT;
         ft.tc = g.c; ft.R = g.r; ft.S = g.s;
