@@ -1837,7 +1837,7 @@ static int run_product(int M, int N, int K, const OperandSpec &sa, const Operand
     // operands, when the product is large enough to pay for the launch that picks the row scales
     const int wmode = window_mode();
     const bool planes = sa.g.kind == kSrcMatrix && sb.g.kind == kSrcMatrix && out.img == 0 &&
-                        (wmode == 1 || (wmode == 2 && 2.0 * M * N * K >= 1e9 && K >= 128));
+                        K < (1 << 27) && (wmode == 1 || (wmode == 2 && 2.0 * M * N * K >= 1e9 && K >= 128));
     const Scheme sch = scheme_of(f, planes);
 #define FMT_RUN(MD)                                                                     \
     (ftz ? run_p<MD, true>(sch, M, N, K, sa, sb, out, f, p, stream)                      \
@@ -1850,12 +1850,13 @@ static int run_product(int M, int N, int K, const OperandSpec &sa, const Operand
 
 // ---- prepared operands in caller-owned memory ---------------------------------------------------
 
-static Scheme api_scheme(fmt_format_t f) { return scheme_of(f, window_mode() != 0); }
+// (the tail's element records hold k in 27 bits: longer sums take the bf16 pieces)
+static Scheme api_scheme(fmt_format_t f, int64_t K) { return scheme_of(f, window_mode() != 0 && K < ((int64_t)1 << 27)); }
 
 int prepared_operand_bytes(int64_t rows, int64_t K, fmt_format_t f, size_t *bytes, int *scheme)
 {
     OperandLayout L;
-    const Scheme sch = api_scheme(f);
+    const Scheme sch = api_scheme(f, K);
     int rc = operand_layout(rows, K, sch, f.m, &L);
     if (rc != FMT_OK) return rc;
     *bytes = L.bytes;
@@ -1879,7 +1880,7 @@ static int prepare_one_p(Scheme sch, const OperandSpec &sp, const OperandLayout 
 int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, int64_t K, fmt_format_t f,
                            const QuantParams &p, void *buf, hipStream_t stream)
 {
-    const Scheme sch = api_scheme(f);
+    const Scheme sch = api_scheme(f, K);
     OperandLayout L;
     int rc = operand_layout(rows, K, sch, f.m, &L);
     if (rc != FMT_OK) return rc;
