@@ -191,8 +191,12 @@ int fmt_histogram(const float *x, size_t n, fmt_format_t f,
  * A, B, C are device pointers, 4-byte aligned; C must not overlap A or B.  M, N or K
  * equal to 0 succeeds (K == 0 with M, N > 0 zero-fills C).  Dimensions must be below 2^31.
  * Infinite or NaN operands (including finite inputs that overflow the format) give
- * non-finite results in the affected outputs; whether such an output is an infinity or
- * a NaN is not specified.
+ * non-finite results in exactly the affected outputs: NaN where the sum of Sec. III-B is NaN;
+ * where that sum is an infinity, that infinity or NaN (which of the two is not specified).
+ * Formats with e == 8 and m >= 8 (fp32's exponent range with more mantissa than bfloat16; none of
+ * the paper's): an operand value enters the products without its bits below 2^-133, i.e. values
+ * of magnitude below 2^(m-133) may lose up to 2^-133; every other format, 1/8/7 included, is exact.
+ * This holds for every product call of this header (prepared operands, fmt_linear, convolutions).
  */
 int fmt_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
              const float *A, int64_t lda, const float *B, int64_t ldb,

@@ -91,6 +91,26 @@ def test_wide_range_operands(fmt, e, m, d):
     assert rel_fro(got, ref) <= TOL
 
 
+@pytest.mark.parametrize("m", [9, 23])
+def test_fp32_exponent_range_formats_wider_than_bfloat16(fmt, m):
+    """1/8/m with m >= 8 (none of the paper's formats): bf16 pieces hold no bit below 2^-133, so an operand
+    value is split exactly iff its lowest set bit is at 2^-133 or above.  Pinned: operands with all bits at or
+    above 2^-133 give the oracle's product bit for bit (integer data, exact sums); operands that reach below
+    lose less than 2^-133 each, so every output is within sum_k |b_k| * 2^-133 of the oracle's."""
+    rng = np.random.default_rng(800 + m)
+    M, N, K = 40, 24, 64
+    bits = min(m + 1, 12)
+    ints = rng.integers(-(1 << bits) + 1, 1 << bits, (M, K)).astype(np.float64)
+    B = rng.integers(-3, 4, (K, N)).astype(np.float32)
+    A = (ints * 2.0 ** -133).astype(np.float32)                  # every set bit at 2^-133 or above
+    got, ref = run(fmt, A, B, (8, m, True), False, False)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    A2 = (ints * 2.0 ** -(133 + bits - 2)).astype(np.float32)     # low bits below 2^-133 (fp32 denormals: exact inputs)
+    got2, ref2 = run(fmt, A2, B, (8, m, True), False, False)
+    bound = np.abs(B).sum(axis=0, dtype=np.float64)[None, :] * 2.0 ** -133
+    assert np.all(np.abs(got2.astype(np.float64) - ref2.astype(np.float64)) <= bound)
+
+
 @pytest.mark.parametrize("shape", [(1, 1, 1), (1, 7, 3), (5, 1, 40), (33, 31, 1), (128, 128, 32), (129, 127, 33),
                                    (256, 10, 1024), (10, 1024, 256), (64, 300, 17)])
 def test_shapes(fmt, shape):

@@ -156,7 +156,15 @@ def test_denormals_zeros_and_extremes(fmt):
     assert np.array_equal(got[6].view(np.uint32), want[6].view(np.uint32))   # integers times 2^-39: exact
 
 
-def test_nonfinite_operands(fmt):
+@pytest.mark.parametrize("window", ["0", "1"])
+def test_nonfinite_operands(fmt, window, monkeypatch):
+    """Infinite and NaN operands, and a finite one that overflows the format, through the exponent planes (1)
+    and through the two bf16 pieces (0).  What is pinned: an output is non-finite exactly where the oracle's
+    is; where the oracle has NaN (a NaN operand, infinity times zero, infinities of both signs) so has the
+    library; where the oracle has an infinity the library has that infinity or NaN (splitting an infinite
+    value into pieces leaves inf - inf = NaN in the lower piece: the documented latitude); everything else
+    is finite and within the tolerance."""
+    monkeypatch.setenv("FMT_GEMM_WINDOW", window)
     f = (6, 9, True)
     rng = np.random.default_rng(600)
     A = rng.standard_normal((40, 64)).astype(np.float32)
@@ -164,9 +172,17 @@ def test_nonfinite_operands(fmt):
     A[3, 10] = np.inf
     A[9, 0] = np.nan
     A[20, 5] = 1e30                                   # overflows the format: rounds to infinity
+    A[25, 7] = -np.inf
+    B[7, 11] = 0.0                                    # -inf * 0 in C[25][11]
+    A[30, 1], A[30, 2] = np.inf, np.inf
+    B[1, 4], B[2, 4] = 1.0, -1.0                      # inf - inf in C[30][4]
     got, want = gpu(fmt, A, B, f), ref(A, B, f)
     bad = ~np.isfinite(want)
     assert np.array_equal(~np.isfinite(got), bad)
+    assert np.isnan(want[25, 11]) and np.isnan(want[30, 4]) and np.isinf(want[3, 0])
+    assert np.all(np.isnan(got[np.isnan(want)]))
+    inf_at = np.isinf(want)
+    assert np.all(np.isnan(got[inf_at]) | (got[inf_at] == want[inf_at]))
     assert rel_err(np.where(bad, 0, got), np.where(bad, 0, want)) <= TOL
 
 
