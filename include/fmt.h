@@ -444,6 +444,15 @@ int fmt_format_info(fmt_format_t f, double *maxN, double *minN, double *minD,
  */
 int fmt_format_thresholds(fmt_format_t f, uint32_t *out);
 
+/*
+ * fmt_scratch_bytes -- bytes of library-owned scratch that the current device holds for `stream`
+ * right now: out[0] partial statistics records, out[1] the product workspace (prepared operands of
+ * fmt_gemm / fmt_linear / the convolutions, rounded convolution tensors, split-k partial sums),
+ * out[2] the accumulators of fmt_linear_pack16.  out is a HOST pointer to three size_t.  Host-only
+ * bookkeeping: no GPU call besides looking up the current device, no synchronisation.
+ */
+int fmt_scratch_bytes(void *stream, size_t *out);
+
 /* Frees the library-owned scratch buffers of the current device (synchronises it first). */
 int fmt_release_scratch(void);
 

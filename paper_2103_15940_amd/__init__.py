@@ -25,7 +25,7 @@ FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
 EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_gemm_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
-           "fmt_release_scratch", "fmt_status_string")
+           "fmt_scratch_bytes", "fmt_release_scratch", "fmt_status_string")
 
 
 class Format(NamedTuple):
@@ -120,6 +120,8 @@ def _load() -> ctypes.CDLL:
     lib.fmt_format_info.restype = ctypes.c_int
     lib.fmt_format_thresholds.argtypes = [_CFormat, ctypes.POINTER(ctypes.c_uint32)]
     lib.fmt_format_thresholds.restype = ctypes.c_int
+    lib.fmt_scratch_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.fmt_scratch_bytes.restype = ctypes.c_int
     lib.fmt_release_scratch.argtypes = []
     lib.fmt_release_scratch.restype = ctypes.c_int
     lib.fmt_status_string.argtypes = [ctypes.c_int]
@@ -549,6 +551,13 @@ def fmt_format_thresholds(fmt) -> dict:
     out = (ctypes.c_uint32 * 3)()
     _check(_lib.fmt_format_thresholds(_cfmt(fmt), out), "fmt_format_thresholds")
     return {"t_zero": int(out[0]), "t_den": int(out[1]), "t_ovf": int(out[2])}
+
+
+def fmt_scratch_bytes(stream=None) -> dict:
+    """Bytes of library-owned scratch held for `stream` on the current device."""
+    out = (ctypes.c_size_t * 3)()
+    _check(_lib.fmt_scratch_bytes(_stream_ptr(stream), out), "fmt_scratch_bytes")
+    return {"statistics": int(out[0]), "products": int(out[1]), "accumulators": int(out[2])}
 
 
 def fmt_release_scratch() -> None:

@@ -486,6 +486,22 @@ int fmt_format_thresholds(fmt_format_t f, uint32_t *out)
     return FMT_OK;
 }
 
+int fmt_scratch_bytes(void *stream, size_t *out)
+{
+    if (out == nullptr) return FMT_ERR_NULL;
+    int dev = 0;
+    FMT_HIP_CHECK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_mu);
+    out[0] = out[1] = out[2] = 0;
+    auto it = g_scratch.find(std::make_pair(dev, static_cast<hipStream_t>(stream)));
+    if (it != g_scratch.end()) {
+        out[0] = it->second.hist_bytes;
+        out[1] = it->second.gemm_bytes;
+        out[2] = it->second.acc_bytes;
+    }
+    return FMT_OK;
+}
+
 int fmt_release_scratch(void)
 {
     int dev = 0;

@@ -229,3 +229,9 @@ def test_prepared_operand_calls_validate_without_gpu():
     assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), c, 64, None) == -3        # operand buffer too small
     a.bytes = need.value
     assert lib.fmt_gemm_prepared(ctypes.byref(a), ctypes.byref(b), ctypes.c_void_p(base + 256), 64, None) == -6   # C overlaps A
+
+
+def test_scratch_query_rejects_null():
+    """fmt_scratch_bytes validates its output pointer before any GPU call."""
+    lib = fmt.raw_library()
+    assert lib.fmt_scratch_bytes(None, None) == -2          # FMT_ERR_NULL

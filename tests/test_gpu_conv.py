@@ -236,3 +236,38 @@ def test_in_kernel_gather_equals_gathered_operand(fmt, monkeypatch):
                 assert np.array_equal(g_.view(np.uint32), w_.view(np.uint32)), name
             else:
                 assert rel_err(g_, w_) <= TOL, name
+
+
+def test_scratch_of_forward_and_dgrad_is_of_the_size_of_the_tensor(fmt):
+    """With the patches gathered inside the product kernel, forward and dgrad hold the rounded tensor (two
+    bytes per element and 16-bit piece: 4 B for 1/6/9), the prepared filter and, when k is split, partial sums
+    in scratch -- nothing of the size of the patch matrix (R*S times the tensor).  wgrad still prepares a
+    patch-sized operand, which the last assertion records."""
+    n, c, h, w, k, r, s = 8, 64, 28, 28, 64, 3, 3
+    rng = np.random.default_rng(5)
+    X = dev(rng.standard_normal((n, c, h, w)).astype(np.float32))
+    W = dev((rng.standard_normal((k, c, r, s)) * 0.05).astype(np.float32))
+    dY = dev((rng.standard_normal((n, k, h, w)) * 1e-3).astype(np.float32))
+    f = (6, 9, True)
+    tensor = n * c * h * w
+    patch_operand = tensor * r * s * 4                      # what a gathered operand of two 16-bit pieces takes
+    filt = 256 * c * r * s * 4                              # the filter operand, rows padded to 256
+    slabs = 8 * k * n * h * w * 4                           # generous room for split-k partial sums
+    torch.cuda.synchronize()
+    fmt.fmt_release_scratch()
+    fmt.fmt_conv2d_fwd(X, W, f, pad=(1, 1))
+    torch.cuda.synchronize()
+    fwd = fmt.fmt_scratch_bytes()["products"]
+    assert 4 * tensor <= fwd <= 4 * tensor + filt + slabs + 65536
+    assert fwd < patch_operand / 2
+    fmt.fmt_release_scratch()
+    fmt.fmt_conv2d_dgrad(dY, W, (n, c, h, w), f, pad=(1, 1))
+    torch.cuda.synchronize()
+    dgrad = fmt.fmt_scratch_bytes()["products"]
+    assert 4 * tensor <= dgrad <= 4 * tensor + filt + slabs + 65536
+    assert dgrad < patch_operand / 2
+    fmt.fmt_release_scratch()
+    fmt.fmt_conv2d_wgrad(dY, X, (k, c, r, s), f, pad=(1, 1))
+    torch.cuda.synchronize()
+    assert fmt.fmt_scratch_bytes()["products"] >= patch_operand
+    fmt.fmt_release_scratch()
