@@ -518,8 +518,10 @@ def main() -> int:
                                     "frac": round(2048.0 * 2048 * 1024 / (f8_ms * 1e-3)
                                                   / (VALU_LANE_INSTR_PER_S / FMAC8_INSTR_PER_MAC), 4),
                                     "note": "vector issue rate 256 CUs x 64 lanes x 2.4 GHz = 39.3 T "
-                                            "lane-instructions/s over about 12 instructions per fused step "
-                                            "of the single-precision path"}}
+                                            "lane-instructions/s over the 12 instructions of the fused step "
+                                            "of the single-precision path (17 are executed per step with the "
+                                            "midpoint handling, operand rounding and master additions: "
+                                            "profiles/fmac8_kernel_counters.md)"}}
     # loss-scale controller on the nine statistics records of configuration 4's gradient tensors
     recs = torch.stack([L["h"][2] for L in layers])
     st = fmt.fmt_dls_init(1024.0)
