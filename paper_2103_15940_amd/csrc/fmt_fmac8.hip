@@ -76,17 +76,18 @@ struct FmaConsts {
 };
 
 // Common path: returns Q(fma(w, x, a)) and, in `tie`, whether the 24-bit sum sits exactly on a midpoint
-// of the format's grid (then fmac_fix decides).
-template <bool FTZ>
+// of the format's grid (then fmac_fix decides).  FIRST: the step from a zero accumulator -- the sum is the
+// product itself, exact in 24 bits, so its rounding needs no second look (a midpoint there is a true tie).
+template <bool FTZ, bool FIRST = false>
 __device__ __forceinline__ float fmac_try(float a, float w, float x, const QuantParams &qp, const FmaConsts &k, bool &tie)
 {
-    const float s = __fmaf_rn(w, x, a);                   // exact product, exact sum, one rounding to 24 bits
+    const float s = FIRST ? __fmul_rn(w, x) : __fmaf_rn(w, x, a);   // exact product, exact sum, one rounding to 24 bits
     // C = 2^(max(E, Emin) + 23 - m): (|s| + C) - C rounds |s| to the format's grid around it (RNE).  For an
     // infinite or NaN s the pattern of C is a NaN, so r is: the selection below restores the infinity.
     const uint32_t ce = max(__float_as_uint(s) & 0x7F800000u, qp.minn_bits) + qp.shift23;
     const float c = __uint_as_float(ce), fa = fabsf(s);
     float r = __fsub_rn(__fadd_rn(fa, c), c);
-    tie = fabsf(__fsub_rn(fa, r)) == __uint_as_float(ce - (24u << 23));   // moved by exactly half a step, C * 2^-24
+    tie = !FIRST && fabsf(__fsub_rn(fa, r)) == __uint_as_float(ce - (24u << 23));   // moved by exactly half a step, C * 2^-24
     if (FTZ) r = r < k.minn ? 0.0f : r;                   // the flush acts on the rounded value
     r = fa >= k.tovf ? __uint_as_float(0x7F800000u) : r;  // false for NaN, which stays NaN
     return copysignf(r, s);
@@ -172,16 +173,18 @@ __global__ __launch_bounds__(256) void fmac8_kernel(const uint32_t *__restrict__
                     // the 16 chains take their step; which lanes met a midpoint is kept as wave masks
                     float nx[4][4];
                     unsigned long long met[4][4], any = 0ull;
+                    const bool first = kk == g * 8;        // known at compile time: the loop over kk is unrolled
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             bool tie;
-                            nx[i][j] = fmac_try<FTZ>(a16[i][j], w[i], x[j], qp, fk, tie);
+                            nx[i][j] = first ? fmac_try<FTZ, true>(a16[i][j], w[i], x[j], qp, fk, tie)
+                                             : fmac_try<FTZ, false>(a16[i][j], w[i], x[j], qp, fk, tie);
                             met[i][j] = __ballot(tie);
                             any |= met[i][j];
                         }
-                    if (any != 0ull) {                     // wave-uniform; about one step in eight
+                    if (any != 0ull) {                     // wave-uniform
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
 #pragma unroll
