@@ -438,6 +438,15 @@ def main() -> int:
                                             "statistics of the output), 1/6/9/d",
                                 "ms": round(lin_ms, 4), "value": round(cfg4_flops / 3 / (lin_ms * 1e-3) / 1e12, 2),
                                 "unit": "TFLOP/s (useful)"}
+
+    # the same four layers on the operands the step prepared (X and W as stored): no rounding pass in the call
+    def linear_prepared_all():
+        for L, b in zip(layers, biases):
+            fmt.fmt_linear_prepared(L["op"]["X"][0], L["op"]["W"][0], b, out=L["Y"], hist=L["h"][0])
+    linp_ms = timed(linear_prepared_all, reps)
+    result["linear_config4"]["prepared"] = {"workload": "fmt_linear_prepared on the prepared operands of the step",
+                                            "ms": round(linp_ms, 4),
+                                            "value": round(cfg4_flops / 3 / (linp_ms * 1e-3) / 1e12, 2)}
     # the same layers and the config 5 stream with 16-bit code output (2 instead of 4 bytes written per element)
     Y16 = [torch.empty(L["Y"].shape, dtype=torch.int16, device=dev) for L in layers]
 

@@ -24,7 +24,7 @@
  *                  used for fully connected layers and im2col convolutions in forward,
  *                  dgrad and wgrad (Sec. IV-A)
  * and, beyond these three:
- *   fmt_operand_bytes / fmt_prepare / fmt_gemm_prepared   fmt_gemm in two steps: a tensor is rounded once
+ *   fmt_operand_bytes / fmt_prepare / fmt_gemm_prepared / fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
  *                  into a reusable operand in caller-owned memory (Sec. IV-A rounds each tensor once and
  *                  uses it in several products), and products run on two such operands
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
@@ -247,6 +247,19 @@ int fmt_operand_bytes(int64_t rows, int64_t k, fmt_format_t f, size_t *bytes);
 int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, fmt_format_t f,
                 void *data, size_t bytes, fmt_operand_t *op, void *stream);
 int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream);
+
+/*
+ * fmt_linear_prepared -- fmt_linear (below) on operands prepared with fmt_prepare: the quantized fully connected
+ * layer of Sec. IV-A, Y = R( R(acc) + R(b) ) with acc[i][j] = sum_k Q(x)[i][k] Q(w)[j][k], where X holds the
+ * M = X->rows rows of the input and W the N = W->rows rows of the weight matrix (both with the same k, format and
+ * scheme; the format is the operands').  b (N values, may be NULL: no bias), Y (M x N, ldy >= N), hist
+ * (may be NULL) and exp_lo as for fmt_linear; the result and the statistics are those of fmt_linear on the tensors
+ * the operands were prepared from whenever the accumulation order does not matter (it is unspecified in both).
+ * A weight operand prepared once serves every forward call until the weights change.  Errors as for
+ * fmt_gemm_prepared and fmt_linear.
+ */
+int fmt_linear_prepared(const fmt_operand_t *X, const fmt_operand_t *W, const float *b, float *Y, int64_t ldy,
+                        fmt_hist_t *hist, int32_t exp_lo, void *stream);
 
 /*
  * fmt_gemm_fmac8 -- matrix product with the FMAC-8 accumulation of Sec. IV-A, Algorithm 1, for

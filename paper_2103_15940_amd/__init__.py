@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_gemm_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_gemm_prepared", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_scratch_bytes", "fmt_release_scratch", "fmt_status_string")
 
 
@@ -98,6 +98,8 @@ def _load() -> ctypes.CDLL:
     lib.fmt_prepare.restype = ctypes.c_int
     lib.fmt_gemm_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, i64, vp]
     lib.fmt_gemm_prepared.restype = ctypes.c_int
+    lib.fmt_linear_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, vp, i64, vp, i32, vp]
+    lib.fmt_linear_prepared.restype = ctypes.c_int
     lib.fmt_gemm_fmac8.argtypes = lib.fmt_gemm.argtypes
     lib.fmt_gemm_fmac8.restype = ctypes.c_int
     lib.fmt_linear.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, _CFormat, vp, i32, vp]
@@ -303,6 +305,36 @@ def fmt_gemm_prepared(A: PreparedOperand, B: PreparedOperand, out=None, stream=N
     ldc = out.stride(0) if M > 1 else max(N, 1)
     rc = _lib.fmt_gemm_prepared(ctypes.byref(A.desc), ctypes.byref(B.desc), out.data_ptr(), ldc, _stream_ptr(stream))
     _check(rc, "fmt_gemm_prepared")
+    return out
+
+
+def fmt_linear_prepared(X: PreparedOperand, W: PreparedOperand, bias, out=None, hist=None,
+                        exp_lo: int = EXP_LO_DEFAULT, stream=None):
+    """:func:`fmt_linear` on operands prepared with :func:`fmt_prepare` (X: the batch rows, W: the rows of the
+    weight matrix): product, bias, output roundings and the statistics of the output, with no rounding or
+    layout pass over X and W in the call (Sec. IV-A)."""
+    import torch
+    M, N = X.rows, W.rows
+    bp = None
+    if bias is not None:
+        _dev_f32(bias, "bias")
+        if bias.dim() != 1 or bias.numel() != N or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous vector with one value per output column")
+        bp = bias.data_ptr()
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=X.buf.device)
+    _dev_f32(out, "out")
+    if out.dim() != 2 or tuple(out.shape) != (M, N) or (N > 1 and out.stride(1) != 1):
+        raise ValueError("out must be an M x N tensor with unit column stride")
+    hp = None
+    if hist is not None:
+        if hist.dtype != torch.int64 or hist.numel() != 8 + FMT_NBINS or not hist.is_cuda:
+            raise TypeError("hist must be a GPU int64 tensor of 72 elements")
+        hp = hist.data_ptr()
+    ldy = out.stride(0) if M > 1 else max(N, 1)
+    rc = _lib.fmt_linear_prepared(ctypes.byref(X.desc), ctypes.byref(W.desc), bp, out.data_ptr(), ldy, hp, int(exp_lo),
+                                  _stream_ptr(stream))
+    _check(rc, "fmt_linear_prepared")
     return out
 
 

@@ -261,7 +261,8 @@ int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, 
     return FMT_OK;
 }
 
-int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream)
+// Everything fmt_gemm_prepared checks before it launches.
+static int check_prepared(const fmt_operand_t *A, const fmt_operand_t *B, const float *C, int64_t ldc)
 {
     if (!A || !B) return FMT_ERR_NULL;
     if (!format_ok(A->format)) return FMT_ERR_FORMAT;
@@ -283,8 +284,34 @@ int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, 
     if (A->bytes < na || B->bytes < nb) return FMT_ERR_SHAPE;
     const size_t cbytes = 4 * (size_t)((A->rows - 1) * ldc + B->rows);
     if (overlap(C, cbytes, A->data, na) || overlap(C, cbytes, B->data, nb)) return FMT_ERR_ALIAS;
+    return FMT_OK;
+}
+
+int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream)
+{
+    const int rc = check_prepared(A, B, C, ldc);
+    if (rc != FMT_OK) return rc;
     return launch_gemm_prepared(A->data, B->data, A->rows, B->rows, A->k, A->scheme, A->format, C, ldc,
                                 static_cast<hipStream_t>(stream));
+}
+
+int fmt_linear_prepared(const fmt_operand_t *X, const fmt_operand_t *W, const float *b, float *Y, int64_t ldy,
+                        fmt_hist_t *hist, int32_t exp_lo, void *stream)
+{
+    int rc = check_prepared(X, W, Y, ldy);
+    if (rc != FMT_OK) return rc;
+    QuantParams p;
+    rc = make_quant_params(X->format, hist ? exp_lo : FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (hist && !aligned(hist, 8)) return FMT_ERR_ALIGN;
+    if (b) {
+        if (!aligned(b, 4)) return FMT_ERR_ALIGN;
+        if (overlap(Y, 4 * (size_t)((X->rows - 1) * ldy + W->rows), b, 4 * (size_t)W->rows)) return FMT_ERR_ALIAS;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = launch_gemm_prepared(X->data, W->data, X->rows, W->rows, X->k, X->scheme, X->format, Y, ldy, s);
+    if (rc != FMT_OK) return rc;
+    return launch_linear_epilogue(Y, ldy, X->rows, W->rows, b, p, X->format.denorm == 0, hist, s);
 }
 
 int fmt_gemm_fmac8(int transA, int transB, int64_t M, int64_t N, int64_t K,

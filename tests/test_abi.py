@@ -235,3 +235,14 @@ def test_scratch_query_rejects_null():
     """fmt_scratch_bytes validates its output pointer before any GPU call."""
     lib = fmt.raw_library()
     assert lib.fmt_scratch_bytes(None, None) == -2          # FMT_ERR_NULL
+
+
+def test_linear_prepared_validates_before_any_gpu_call():
+    """fmt_linear_prepared: NULL operands and a mismatch of the two operands are refused on a host without a GPU."""
+    import ctypes
+    lib = fmt.raw_library()
+    assert lib.fmt_linear_prepared(None, None, None, None, 0, None, -48, None) == -2     # FMT_ERR_NULL
+    a = fmt._COperand(ctypes.c_void_p(256), 1 << 20, 32, 64, fmt._CFormat(6, 9, 1), 16)
+    b = fmt._COperand(ctypes.c_void_p(1 << 30), 1 << 20, 32, 64, fmt._CFormat(5, 10, 1), 0)
+    y = ctypes.c_void_p(1 << 40)
+    assert lib.fmt_linear_prepared(ctypes.byref(a), ctypes.byref(b), None, y, 32, None, -48, None) == -1   # formats differ

@@ -116,6 +116,46 @@ def test_shapes(fmt, shape, bias):
     assert_bits(Y2, Yo, "no statistics, shape %r" % (shape,))
 
 
+def run_prepared(fmt, X, W, b, f, want_hist=True):
+    h = fmt.new_hist(torch.device("cuda")) if want_hist else None
+    Xp, Wp = fmt.fmt_prepare(dev(X), f), fmt.fmt_prepare(dev(W), f)
+    Y = fmt.fmt_linear_prepared(Xp, Wp, None if b is None else dev(b), hist=h, exp_lo=EXP_LO)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy(), (fmt.hist_to_dict(h) if want_hist else None)
+
+
+@pytest.mark.parametrize("e,m,d", VARIANTS + [(4, 3, True), (7, 14, False)])
+def test_prepared_operands_bit_exact_end_to_end(fmt, e, m, d):
+    """fmt_linear_prepared (the layer on operands rounded once with fmt_prepare) against the oracle, on
+    operands whose partial sums are exact: output and statistics bit for bit, with and without bias."""
+    rng = np.random.default_rng(2000 * e + m + int(d))
+    for (M, N, K), bias in (((203, 1190, 150), True), ((65, 1025, 33), False), ((300, 7, 40), True)):
+        X, W, b = exact_operands(rng, M, N, K, e, m)
+        if not bias:
+            b = None
+        Yo, To = oracle.linear(X, W, b, e, m, d)
+        Y, h = run_prepared(fmt, X, W, b, (e, m, d))
+        assert_bits(Y, Yo, "Y 1/%d/%d/%s %r" % (e, m, d, (M, N, K)))
+        assert_hist(h, To, (e, m, d), "statistics of t")
+        Y2, _ = run_prepared(fmt, X, W, b, (e, m, d), want_hist=False)
+        assert_bits(Y2, Yo, "no statistics")
+
+
+def test_prepared_operands_config4_layer_equals_fmt_linear(fmt):
+    """A config 4 layer (4096 tokens, 1024 -> 1024) through fmt_linear_prepared and through fmt_linear: the same
+    product kernels on the same prepared planes, so the same bits and the same statistics."""
+    L = workloads.config4()["layers"][1]
+    f = (6, 9, True)
+    X, W = dev(L["X"]), dev(L["W"])
+    b = dev(np.random.default_rng(3).standard_normal(W.shape[0]).astype(np.float32) * 0.1)
+    h1, h2 = fmt.new_hist(torch.device("cuda")), fmt.new_hist(torch.device("cuda"))
+    Y1 = fmt.fmt_linear(X, W, b, f, hist=h1, exp_lo=EXP_LO)
+    Y2 = fmt.fmt_linear_prepared(fmt.fmt_prepare(X, f), fmt.fmt_prepare(W, f), b, hist=h2, exp_lo=EXP_LO)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1.view(torch.int32), Y2.view(torch.int32))
+    assert torch.equal(h1, h2)
+
+
 def test_strided_and_unaligned_output(fmt):
     """Leading dimensions larger than the rows, an output that is not 16-byte aligned and one whose
     leading dimension is odd (scalar accesses); the padding must stay untouched."""
