@@ -210,6 +210,34 @@ def test_seeded_random_geometries(fmt, seed):
         assert np.array_equal(g_.view(np.uint32), w_.view(np.uint32)), "%s differs, %s" % (name, what)
 
 
+@pytest.mark.parametrize("seed", range(30))
+def test_seeded_random_geometries_with_channel_multiples_of_32(fmt, seed):
+    """The same draw with channel and filter counts from {32, 64, 96, 128} and at most 32 taps, so that forward
+    (any stride) and dgrad (stride 1, every third seed at least) gather their patches inside the product kernel:
+    images of several sizes incl. one pixel, padding wider than the filter, strides, six formats (one, two and
+    three 16-bit pieces); exact data, bit for bit against the oracle."""
+    rng = np.random.default_rng(9500 + seed)
+    n = int(rng.integers(1, 4))
+    c, k = int(rng.choice([32, 64, 96, 128])), int(rng.choice([32, 64, 96, 128]))
+    h, w = int(rng.integers(1, 16)), int(rng.integers(1, 16))
+    pad = (int(rng.integers(0, 4)), int(rng.integers(0, 4)))
+    r = int(rng.integers(1, min(5, h + 2 * pad[0]) + 1))
+    s = int(rng.integers(1, min(6, w + 2 * pad[1]) + 1))
+    stride = (1, 1) if seed % 3 == 0 else (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+    f = [(6, 9, True), (5, 10, False), (8, 7, True), (6, 9, False), (7, 20, True), (4, 3, True)][seed % 6]
+    X = (rng.integers(-3, 4, (n, c, h, w)) * 0.5).astype(np.float32)
+    W = (rng.integers(-3, 4, (k, c, r, s)) * 0.25).astype(np.float32)
+    P, Q = oracle.conv_out_size(h, w, r, s, pad, stride)
+    dY = (rng.integers(-3, 4, (n, k, P, Q)) * 2.0 ** -3).astype(np.float32)
+    got = run_all(fmt, X, W, dY, f, pad, stride)
+    want = oracle_all(X, W, dY, f, pad, stride)
+    what = "seed %d: n=%d c=%d k=%d %dx%d filter %dx%d pad %r stride %r 1/%d/%d" % (seed, n, c, k, h, w, r, s, pad, stride, f[0], f[1])
+    for name, g_, w_ in zip(("Y", "dX", "dW"), got, want):
+        assert g_.shape == w_.shape, what
+        assert np.all(np.isfinite(w_)), what
+        assert np.array_equal(g_.view(np.uint32), w_.view(np.uint32)), "%s differs, %s" % (name, what)
+
+
 def test_in_kernel_gather_equals_gathered_operand(fmt, monkeypatch):
     """Forward and dgrad with the patches gathered inside the product kernel give, on data whose partial sums
     are exact, the same bits as the route through a gathered operand (FMT_CONV_IMPLICIT=0), and within the
