@@ -197,11 +197,10 @@ def main() -> int:
                 torch.cuda.current_stream().wait_event(join)
 
         # The rounding pass of Sec. IV-A over one tensor: statistics and the rounded fp32 copy in one fused
-        # pass, and the rounded tensor as a prepared operand in both orientations (each feeds one product).
+        # pass, and the rounded tensor as a prepared operand in both orientations (each feeds one product; one call).
         def round_tensor(st_, src, dst, hist, bufs, ops, key):
             fmt.fmt_quantize(src, f169, out=dst, hist=hist, stream=st_)
-            ops[key] = (fmt.fmt_prepare(src, f169, trans=False, out=bufs[0], stream=st_),
-                        fmt.fmt_prepare(src, f169, trans=True, out=bufs[1], stream=st_))
+            ops[key] = fmt.fmt_prepare_pair(src, f169, out=bufs[0], out_t=bufs[1], stream=st_)
 
         q4 = []
         for L in layers:                                                     # configuration 4, rounding passes

@@ -24,7 +24,7 @@
  *                  used for fully connected layers and im2col convolutions in forward,
  *                  dgrad and wgrad (Sec. IV-A)
  * and, beyond these three:
- *   fmt_operand_bytes / fmt_prepare / fmt_gemm_prepared / fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
+ *   fmt_operand_bytes / fmt_prepare / fmt_prepare_pair / fmt_gemm_prepared / fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
  *                  into a reusable operand in caller-owned memory (Sec. IV-A rounds each tensor once and
  *                  uses it in several products), and products run on two such operands
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
@@ -246,6 +246,19 @@ typedef struct fmt_operand {
 int fmt_operand_bytes(int64_t rows, int64_t k, fmt_format_t f, size_t *bytes);
 int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, fmt_format_t f,
                 void *data, size_t bytes, fmt_operand_t *op, void *stream);
+
+/*
+ * fmt_prepare_pair -- both orientations of one matrix X (rows x cols, element (r, c) at X[r*ld + c], ld >= cols) in
+ * one call: `op` = X as stored (rows = rows, k = cols), `op_t` = X transposed (rows = cols, k = rows), exactly the
+ * operands that fmt_prepare(X, ld, 0, rows, cols, ...) and fmt_prepare(X, ld, 1, cols, rows, ...) produce, in
+ * data / data_t (sizes from fmt_operand_bytes(rows, cols, ...) and fmt_operand_bytes(cols, rows, ...); the two
+ * buffers must not overlap each other or X).  A training step uses each of X, W and dY in both orientations
+ * (Sec. IV-A: Y = X W^T, dX = dY W, dW = dY^T X), and preparing the two together takes half the launches.
+ * Errors as for fmt_prepare.
+ */
+int fmt_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f,
+                     void *data, size_t bytes, fmt_operand_t *op,
+                     void *data_t, size_t bytes_t, fmt_operand_t *op_t, void *stream);
 int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream);
 
 /*

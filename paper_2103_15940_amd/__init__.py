@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_gemm_prepared", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_prepare_pair", "fmt_gemm_prepared", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_scratch_bytes", "fmt_release_scratch", "fmt_status_string")
 
 
@@ -96,6 +96,9 @@ def _load() -> ctypes.CDLL:
     lib.fmt_operand_bytes.restype = ctypes.c_int
     lib.fmt_prepare.argtypes = [vp, i64, ctypes.c_int, i64, i64, _CFormat, vp, sz, ctypes.POINTER(_COperand), vp]
     lib.fmt_prepare.restype = ctypes.c_int
+    lib.fmt_prepare_pair.argtypes = [vp, i64, i64, i64, _CFormat, vp, sz, ctypes.POINTER(_COperand), vp, sz,
+                                     ctypes.POINTER(_COperand), vp]
+    lib.fmt_prepare_pair.restype = ctypes.c_int
     lib.fmt_gemm_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, i64, vp]
     lib.fmt_gemm_prepared.restype = ctypes.c_int
     lib.fmt_linear_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, vp, i64, vp, i32, vp]
@@ -291,6 +294,29 @@ def fmt_prepare(X, fmt, trans: bool = False, out=None, stream=None) -> PreparedO
                           ctypes.byref(desc), _stream_ptr(stream))
     _check(rc, "fmt_prepare")
     return PreparedOperand(out, desc)
+
+
+def fmt_prepare_pair(X, fmt, out=None, out_t=None, stream=None):
+    """Both orientations of the 2-D float32 GPU tensor X as prepared operands in one call: returns
+    (X as stored, X transposed), the operands :func:`fmt_prepare` gives with ``trans=False`` and ``trans=True``."""
+    import torch
+    _dev_f32(X, "X")
+    if X.dim() != 2 or (X.shape[1] > 1 and X.stride(1) != 1):
+        raise ValueError("X must be 2-D with unit column stride")
+    rows, cols = X.shape
+    bufs = []
+    for buf, (r, k) in ((out, (rows, cols)), (out_t, (cols, rows))):
+        if buf is None:
+            buf = torch.empty(fmt_operand_bytes(r, k, fmt), dtype=torch.uint8, device=X.device)
+        if not isinstance(buf, torch.Tensor) or buf.dtype != torch.uint8 or not buf.is_cuda or not buf.is_contiguous():
+            raise TypeError("out and out_t must be contiguous GPU uint8 tensors")
+        bufs.append(buf)
+    d0, d1 = _COperand(), _COperand()
+    ld = X.stride(0) if rows > 1 else max(cols, 1)
+    rc = _lib.fmt_prepare_pair(X.data_ptr(), ld, rows, cols, _cfmt(fmt), bufs[0].data_ptr(), bufs[0].numel(), ctypes.byref(d0),
+                               bufs[1].data_ptr(), bufs[1].numel(), ctypes.byref(d1), _stream_ptr(stream))
+    _check(rc, "fmt_prepare_pair")
+    return PreparedOperand(bufs[0], d0), PreparedOperand(bufs[1], d1)
 
 
 def fmt_gemm_prepared(A: PreparedOperand, B: PreparedOperand, out=None, stream=None):

@@ -261,6 +261,35 @@ int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, 
     return FMT_OK;
 }
 
+int fmt_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f,
+                     void *data, size_t bytes, fmt_operand_t *op,
+                     void *data_t, size_t bytes_t, fmt_operand_t *op_t, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    const int64_t lim = (int64_t)1 << 31;
+    if (rows < 1 || cols < 1 || rows >= lim || cols >= lim) return FMT_ERR_SHAPE;
+    if (!X || !data || !op || !data_t || !op_t) return FMT_ERR_NULL;
+    if (ld < cols || ld >= lim) return FMT_ERR_SHAPE;
+    if (!aligned(X, 4) || !aligned(data, 256) || !aligned(data_t, 256)) return FMT_ERR_ALIGN;
+    size_t need = 0, need_t = 0;
+    int scheme = 0, scheme_t = 0;
+    rc = prepared_operand_bytes(rows, cols, f, &need, &scheme);
+    if (rc != FMT_OK) return rc;
+    rc = prepared_operand_bytes(cols, rows, f, &need_t, &scheme_t);
+    if (rc != FMT_OK) return rc;
+    if (bytes < need || bytes_t < need_t) return FMT_ERR_SHAPE;
+    const size_t xbytes = 4 * (size_t)((rows - 1) * ld + cols);
+    if (overlap(data, need, X, xbytes) || overlap(data_t, need_t, X, xbytes) || overlap(data, need, data_t, need_t))
+        return FMT_ERR_ALIAS;
+    rc = launch_prepare_pair(X, ld, rows, cols, f, p, data, data_t, static_cast<hipStream_t>(stream));
+    if (rc != FMT_OK) return rc;
+    *op = fmt_operand_t{data, bytes, rows, cols, f, scheme};
+    *op_t = fmt_operand_t{data_t, bytes_t, cols, rows, f, scheme_t};
+    return FMT_OK;
+}
+
 // Everything fmt_gemm_prepared checks before it launches.
 static int check_prepared(const fmt_operand_t *A, const fmt_operand_t *B, const float *C, int64_t ldc)
 {

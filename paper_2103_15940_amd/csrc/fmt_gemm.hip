@@ -776,7 +776,8 @@ __global__ __launch_bounds__(256) void prepare_kernel(PrepOperand a, PrepOperand
 }
 
 template <int MODE, bool FTZ>
-__global__ __launch_bounds__(256) void prepare_scaled_kernel(PrepOperand a, PrepOperand b, int K, int kblocks, QuantParams p)
+__global__ __launch_bounds__(256) void prepare_scaled_kernel(PrepOperand a, PrepOperand b, int Ka, int kblocks_a, int Kb,
+                                                             int kblocks_b, QuantParams p)
 {
     // operands own runs of workgroup ids padded to a multiple of 8, remapped XCD by XCD as in prepare_block
     const unsigned a_ids = (a.nblocks + 7u) / 8u * 8u;
@@ -786,7 +787,7 @@ __global__ __launch_bounds__(256) void prepare_scaled_kernel(PrepOperand a, Prep
     const unsigned per_xcd = (o.nblocks + 7u) / 8u;
     const unsigned bid = (lid % 8u) * per_xcd + lid / 8u;
     if (bid >= o.nblocks) return;                // workgroup-uniform: before any barrier
-    prepare_scaled_block<MODE, FTZ>(o, K, kblocks, p, bid);
+    prepare_scaled_block<MODE, FTZ>(o, second ? Kb : Ka, second ? kblocks_b : kblocks_a, p, bid);
 }
 
 // Epilogue of the scaled scheme for one wave: out = acc * 2^-(S_row + S_col), exactly.  The
@@ -1610,12 +1611,14 @@ struct StatOperand {
 //     more than a plane, T = lo + wid (the small values stay, the large ones go to the plane above).
 // Any T in [kWinTmin, kWinTmax] is correct -- what does not fit plane 0 goes to another plane -- the
 // choice only decides how often the other planes are needed, which is why a sample suffices.
-__global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int K, int kstep, int emin, int m)
+__global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int Ka, int kstep_a, int Kb,
+                                                           int kstep_b, int emin, int m)
 {
     __shared__ int s_hi[8][32], s_lo[8][32];
     const int tid = threadIdx.x;
     const bool second = blockIdx.x >= a.nblocks;
     const StatOperand &o = second ? b : a;
+    const int K = second ? Kb : Ka, kstep = second ? kstep_b : kstep_a;
     const int by = blockIdx.x - (second ? a.nblocks : 0u);
     const int wid = 39 - m;                       // binades below the top one that a plane holds with m + 1 significant bits
     int hi = -1000, lo = 1000;
@@ -1737,9 +1740,10 @@ static int prepare_operands(const OperandSpec &sa, const OperandLayout &la, cons
             const int slabs = (K + 63) / 64;
             const int bias = (1 << (f.e - 1)) - 1;
             hipLaunchKernelGGL(window_stats_kernel, dim3(ta.nblocks + tb.nblocks), dim3(256), 0, stream, ta, tb, K,
-                               (slabs + 3) / 4, 1 - bias, f.m);
+                               (slabs + 3) / 4, K, (slabs + 3) / 4, 1 - bias, f.m);
             FMT_HIP_CHECK(hipGetLastError());
-            hipLaunchKernelGGL((prepare_scaled_kernel<MODE, FTZ>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, p);
+            hipLaunchKernelGGL((prepare_scaled_kernel<MODE, FTZ>), dim3(prep_grid), dim3(256), 0, stream, oa, ob, K, kblocks, K,
+                               kblocks, p);
         } else {
             return FMT_ERR_FORMAT;               // planes exist for e == 6 formats only (rounding mode kModeMagic)
         }
@@ -1894,6 +1898,69 @@ int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, 
     if (p.mode == kModeInteger) return FMT_PREP(kModeInteger);
     return FMT_PREP(kModeMixed);
 #undef FMT_PREP
+}
+
+// Both orientations of one matrix X (rows x cols, X[r*ld + c]) as prepared operands: buf0 = X as stored
+// (rows, k = cols), buf1 = X transposed (cols, k = rows).  Exponent planes: one statistics launch and one
+// prepare launch serve both (the second pass over X comes out of the caches); other schemes: two prepare calls.
+template <bool FTZ>
+static int prepare_pair_planes(const float *X, int64_t ld, const OperandLayout &L0, const OperandView &v0, int K0,
+                               const OperandLayout &L1, const OperandView &v1, int K1, fmt_format_t f, const QuantParams &p,
+                               hipStream_t stream)
+{
+    auto operand = [&](bool kcontig, const OperandLayout &L, const OperandView &v) {
+        PrepOperand o;
+        o.X = reinterpret_cast<const uint32_t *>(X);
+        o.g = Gather{};
+        o.W = v.W;
+        o.ld = ld;
+        o.rows = L.rows;
+        o.kcontig = kcontig;
+        o.vec4 = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 4 == 0;
+        o.nblocks = kcontig ? (unsigned)((L.kblocks + 1) / 2) * L.units : (unsigned)L.kblocks * (L.units / 2);
+        o.pl = v.pl;
+        return o;
+    };
+    const PrepOperand o0 = operand(true, L0, v0), o1 = operand(false, L1, v1);
+    auto stat = [&](const PrepOperand &o, const OperandLayout &L) {
+        StatOperand t;
+        t.X = o.X;
+        t.ld = o.ld;
+        t.rows = L.rows;
+        t.rows_pad = L.units * kUnitRows;
+        t.kcontig = o.kcontig;
+        t.S = o.pl.S;
+        t.nblocks = (unsigned)L.units;
+        return t;
+    };
+    const StatOperand t0 = stat(o0, L0), t1 = stat(o1, L1);
+    const int bias = (1 << (f.e - 1)) - 1;
+    hipLaunchKernelGGL(window_stats_kernel, dim3(t0.nblocks + t1.nblocks), dim3(256), 0, stream, t0, t1, K0,
+                       ((K0 + 63) / 64 + 3) / 4, K1, ((K1 + 63) / 64 + 3) / 4, 1 - bias, f.m);
+    FMT_HIP_CHECK(hipGetLastError());
+    const unsigned grid = (o0.nblocks + 7u) / 8u * 8u + (o1.nblocks + 7u) / 8u * 8u;
+    hipLaunchKernelGGL((prepare_scaled_kernel<kModeMagic, FTZ>), dim3(grid), dim3(256), 0, stream, o0, o1, K0, L0.kblocks, K1,
+                       L1.kblocks, p);
+    FMT_HIP_CHECK(hipGetLastError());
+    return FMT_OK;
+}
+
+int launch_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f, const QuantParams &p, void *buf0,
+                        void *buf1, hipStream_t stream)
+{
+    const Scheme s0 = api_scheme(f, cols), s1 = api_scheme(f, rows);
+    if (s0.scaled && s1.scaled && p.mode == kModeMagic) {
+        OperandLayout L0, L1;
+        int rc = operand_layout(rows, cols, s0, f.m, &L0);
+        if (rc != FMT_OK) return rc;
+        rc = operand_layout(cols, rows, s1, f.m, &L1);
+        if (rc != FMT_OK) return rc;
+        const OperandView v0 = view_of(buf0, L0), v1 = view_of(buf1, L1);
+        return f.denorm == 0 ? prepare_pair_planes<true>(X, ld, L0, v0, (int)cols, L1, v1, (int)rows, f, p, stream)
+                             : prepare_pair_planes<false>(X, ld, L0, v0, (int)cols, L1, v1, (int)rows, f, p, stream);
+    }
+    const int rc = launch_prepare_operand(X, ld, 0, rows, cols, f, p, buf0, stream);
+    return rc != FMT_OK ? rc : launch_prepare_operand(X, ld, 1, cols, rows, f, p, buf1, stream);
 }
 
 // C = A B^T on two prepared operands (A: M rows, B: N rows, both with the same K and scheme).

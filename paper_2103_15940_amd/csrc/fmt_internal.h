@@ -66,6 +66,8 @@ int launch_gemm(int transA, int transB, int64_t M, int64_t N, int64_t K,
 int prepared_operand_bytes(int64_t rows, int64_t K, fmt_format_t f, size_t *bytes, int *scheme);
 int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, int64_t K, fmt_format_t f,
                            const QuantParams &p, void *buf, hipStream_t stream);
+int launch_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f, const QuantParams &p, void *buf0,
+                        void *buf1, hipStream_t stream);
 int launch_gemm_prepared(const void *A, const void *B, int64_t M, int64_t N, int64_t K, int scheme, fmt_format_t f,
                          float *C, int64_t ldc, hipStream_t stream);
 

@@ -239,3 +239,29 @@ def test_argument_errors(fmt):
     with pytest.raises(fmt.FmtError) as ei:
         fmt.fmt_prepare(x, f, out=small)
     assert ei.value.status == -3
+
+
+@pytest.mark.parametrize("f", [(6, 9, True), (6, 8, False), (5, 10, True), (8, 7, False)])
+def test_prepare_pair_equals_two_prepares(fmt, f):
+    """fmt_prepare_pair gives the two operands that fmt_prepare gives with trans=False and trans=True (ragged
+    shape, a row stride larger than the row, gradient-like rows that use all three planes): products on them
+    have the same bits, and match the oracle."""
+    rng = np.random.default_rng(77)
+    rows, cols = 203, 150
+    base = workloads.log2_normal((rows, cols + 6), -20.0, 7.0, 0.05, rng)
+    X = dev(base)[:, :cols]                                        # ld = cols + 6
+    need0, need1 = fmt.fmt_operand_bytes(rows, cols, f), fmt.fmt_operand_bytes(cols, rows, f)
+    fill = lambda n: torch.full((n,), 0xAB, dtype=torch.uint8, device="cuda")
+    a0, a1, b0, b1 = fill(need0), fill(need1), fill(need0), fill(need1)
+    p0, p1 = fmt.fmt_prepare_pair(X, f, out=a0, out_t=a1)
+    q0, q1 = fmt.fmt_prepare(X, f, trans=False, out=b0), fmt.fmt_prepare(X, f, trans=True, out=b1)
+    B = dev(rng.standard_normal((64, cols)).astype(np.float32))
+    Bt = dev(rng.standard_normal((48, rows)).astype(np.float32))
+    Bp, Btp = fmt.fmt_prepare(B, f), fmt.fmt_prepare(Bt, f)
+    C0, D0 = fmt.fmt_gemm_prepared(p0, Bp), fmt.fmt_gemm_prepared(q0, Bp)
+    C1, D1 = fmt.fmt_gemm_prepared(p1, Btp), fmt.fmt_gemm_prepared(q1, Btp)
+    torch.cuda.synchronize()
+    assert (p0.rows, p0.k, p1.rows, p1.k) == (rows, cols, cols, rows)
+    assert torch.equal(C0.view(torch.int32), D0.view(torch.int32)) and torch.equal(C1.view(torch.int32), D1.view(torch.int32))
+    ref = oracle.gemm(np.ascontiguousarray(base[:, :cols]), B.cpu().numpy(), f[0], f[1], f[2], transB=True)
+    assert rel_err(C0.cpu().numpy(), ref) <= TOL
