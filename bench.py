@@ -527,7 +527,7 @@ def main() -> int:
                                                   / (VALU_LANE_INSTR_PER_S / FMAC8_INSTR_PER_MAC), 4),
                                     "note": "vector issue rate 256 CUs x 64 lanes x 2.4 GHz = 39.3 T "
                                             "lane-instructions/s over the 12 instructions of the fused step "
-                                            "of the single-precision path (17 are executed per step with the "
+                                            "of the single-precision path (16 are executed per step with the "
                                             "midpoint handling, operand rounding and master additions: "
                                             "profiles/fmac8_kernel_counters.md)"}}
     # loss-scale controller on the nine statistics records of configuration 4's gradient tensors
