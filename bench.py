@@ -426,6 +426,14 @@ def main() -> int:
     result["conv_config3"] = {"workload": "config 3 via fmt_conv2d_fwd/_dgrad/_wgrad, 1/6/9/d, rounding of the tensors included: forward and dgrad gather the patches inside the product kernel (scratch of the tensor's size), wgrad through a gathered 16-bit operand; two bf16 pieces (4 MFMA products per multiply)",
                               "ms": round(conv_ms, 4), "value": round(3 * 2.0 * M * N * K / (conv_ms * 1e-3) / 1e12, 2),
                               "unit": "TFLOP/s (useful)"}
+    by_format = {}
+    for name, fv in workloads.FORMATS.items():          # binary16 and bfloat16 take one 16-bit piece (1 MFMA product per multiply)
+        def conv_f(fv=fv):
+            fmt.fmt_conv2d_fwd(X4d, W4d, fv, out=Yc)
+            fmt.fmt_conv2d_dgrad(dY4d, W4d, X4d.shape, fv, out=dXc)
+            fmt.fmt_conv2d_wgrad(dY4d, X4d, W4d.shape, fv, out=dWc)
+        by_format[name] = round(3 * 2.0 * M * N * K / (timed(conv_f, max(reps // 2, 1)) * 1e-3) / 1e12, 1)
+    result["conv_config3"]["useful_tflops_by_format"] = by_format
     # quantized Linear forward of the four encoder layers: product, bias, both output roundings, statistics of t
     biases = [torch.zeros(L["W"].shape[0], dtype=torch.float32, device=dev) for L in layers]
 
