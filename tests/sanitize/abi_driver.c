@@ -83,6 +83,18 @@ int main(void)
     EXPECT(fmt_gemm_prepared(&a, NULL, y, 4, NULL), FMT_ERR_NULL);
     b.k = 8; b.format = bad;
     EXPECT(fmt_gemm_prepared(&a, &b, y, 4, NULL), FMT_ERR_FORMAT);
+    EXPECT(fmt_linear_prepared(&a, &b, NULL, y, 4, NULL, -48, NULL), FMT_ERR_FORMAT);
+    EXPECT(fmt_linear_prepared(NULL, &b, NULL, y, 4, NULL, -48, NULL), FMT_ERR_NULL);
+    b.format = f; b.k = 16;
+    EXPECT(fmt_linear_prepared(&a, &b, NULL, y, 4, NULL, -48, NULL), FMT_ERR_SHAPE);
+    fmt_operand_t op_t;
+    EXPECT(fmt_prepare_pair(x, 4, 4, 8, f, base + 2048, 4096, &op, base + 8192, 4096, &op_t, NULL), FMT_ERR_SHAPE);
+    EXPECT(fmt_prepare_pair(x, 8, 4, 8, f, base + 2048, 64, &op, base + 8192, 64, &op_t, NULL), FMT_ERR_SHAPE);
+    EXPECT(fmt_prepare_pair(x, 8, 4, 8, f, base + 2048, (size_t)1 << 30, &op, base + 8196, (size_t)1 << 30, &op_t, NULL), FMT_ERR_ALIGN);
+    EXPECT(fmt_prepare_pair(x, 8, 4, 8, f, base + 2048, (size_t)1 << 30, &op, base + 2304, (size_t)1 << 30, &op_t, NULL), FMT_ERR_ALIAS);
+    EXPECT(fmt_prepare_pair(x, 8, 4, 8, f, base + 2048, (size_t)1 << 30, &op, NULL, (size_t)1 << 30, &op_t, NULL), FMT_ERR_NULL);
+    EXPECT(fmt_prepare_pair(x, 8, 0, 8, f, base + 2048, (size_t)1 << 30, &op, base + 8192, (size_t)1 << 30, &op_t, NULL), FMT_ERR_SHAPE);
+    EXPECT(fmt_scratch_bytes(NULL, NULL), FMT_ERR_NULL);
     /* convolutions */
     fmt_conv2d_t g = {1, 1, 4, 4, 1, 3, 3, 1, 1, 1, 1};
     EXPECT(fmt_conv2d_fwd(g, NULL, x, y, f, NULL), FMT_ERR_NULL);
