@@ -61,6 +61,9 @@ def main() -> int:
                     help="also run three plain device-to-device copies of the stream tensor (with --gemm: of a 1 GiB tensor) before the warm-up: "
                          "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
+    ap.add_argument("--no-batch", action="store_true",
+                    help="issue the products of the configuration 4 and 3 sections as single fmt_gemm_prepared calls on the "
+                         "side streams instead of one fmt_gemm_prepared_batch call per section")
     ap.add_argument("--gemm-streams", type=int, default=3,
                     help="side streams the independent calls of the configuration 4 and 3 sections are spread over")
     ap.add_argument("--gemm", default=None, metavar="M,N,K[,transA,transB[,e,m,d]]",
@@ -165,6 +168,16 @@ def main() -> int:
     ev = lambda: torch.cuda.Event(enable_timing=True)
     side = [torch.cuda.Stream() for _ in range(max(args.gemm_streams, 1))]
 
+    def cfg4_batched():
+        # Y = X W^T, dX = dY W, dW = dY^T X of the four layers handed over together (Sec. IV-A)
+        A4, B4, C4 = [], [], []
+        for L in layers:
+            o = L["op"]
+            A4 += [o["X"][0], o["dY"][0], o["dY"][1]]
+            B4 += [o["W"][0], o["W"][1], o["X"][1]]
+            C4 += [L["Y"], L["dX"], L["dW"]]
+        fmt.fmt_gemm_prepared_batch(A4, B4, out=C4)
+
     def step(record=None):
         marks = []
 
@@ -209,22 +222,29 @@ def main() -> int:
                           round_tensor(st_, L[src], L[dst], L["h"][hi], L["buf"][src], L["op"], src))
         fan_out(q4)
         mark()
-        g4 = []                                                              # configuration 4, products
-        for L in layers:
-            o = L["op"]
-            g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["X"][0], o["W"][0], out=L["Y"], stream=st_))     # Y  = X W^T
-            g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["dY"][0], o["W"][1], out=L["dX"], stream=st_))   # dX = dY W
-            g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["dY"][1], o["X"][1], out=L["dW"], stream=st_))   # dW = dY^T X
-        fan_out(g4)
+        if args.no_batch:                                                    # configuration 4, products
+            g4 = []
+            for L in layers:
+                o = L["op"]
+                g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["X"][0], o["W"][0], out=L["Y"], stream=st_))     # Y  = X W^T
+                g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["dY"][0], o["W"][1], out=L["dX"], stream=st_))   # dX = dY W
+                g4.append(lambda st_, L=L, o=o: fmt.fmt_gemm_prepared(o["dY"][1], o["X"][1], out=L["dW"], stream=st_))   # dW = dY^T X
+            fan_out(g4)
+        else:
+            cfg4_batched()                                                   # the same twelve products, one call
         mark()
         fan_out([lambda st_: round_tensor(st_, xcol, xcol_q, hists[6], c3["buf"]["X"], c3["op"], "X"),   # configuration 3
                  lambda st_: round_tensor(st_, w, w_q, hists[7], c3["buf"]["W"], c3["op"], "W"),
                  lambda st_: round_tensor(st_, dy, dy_q, hists[8], c3["buf"]["dY"], c3["op"], "dY")])
         mark()
         o3 = c3["op"]
-        fan_out([lambda st_: fmt.fmt_gemm_prepared(o3["X"][0], o3["W"][0], out=out_fwd, stream=st_),      # Y  = X_col W^T
-                 lambda st_: fmt.fmt_gemm_prepared(o3["dY"][0], o3["W"][1], out=out_dgrad, stream=st_),   # dX = dY W
-                 lambda st_: fmt.fmt_gemm_prepared(o3["dY"][1], o3["X"][1], out=out_wgrad, stream=st_)])  # dW = dY^T X_col
+        if args.no_batch:
+            fan_out([lambda st_: fmt.fmt_gemm_prepared(o3["X"][0], o3["W"][0], out=out_fwd, stream=st_),      # Y  = X_col W^T
+                     lambda st_: fmt.fmt_gemm_prepared(o3["dY"][0], o3["W"][1], out=out_dgrad, stream=st_),   # dX = dY W
+                     lambda st_: fmt.fmt_gemm_prepared(o3["dY"][1], o3["X"][1], out=out_wgrad, stream=st_)])  # dW = dY^T X_col
+        else:
+            fmt.fmt_gemm_prepared_batch([o3["X"][0], o3["dY"][0], o3["dY"][1]], [o3["W"][0], o3["W"][1], o3["X"][1]],
+                                        out=[out_fwd, out_dgrad, out_wgrad])
         mark()
         if record is not None:
             record.append(marks)
@@ -284,8 +304,10 @@ def main() -> int:
                         "config4_gemms": round(cfg4_gemm_ms, 4), "config3_quantize": round(cfg3_q_ms, 4),
                         "config3_gemms": round(cfg3_gemm_ms, 4)},
         "gemm": {
-            "workload": "config 4, 12 products on prepared operands (fmt_gemm_prepared), 1/6/9/d",
-            "value": round(cfg4_tflops, 2), "unit": "TFLOP/s (useful, 2MNK per product, whole fmt_gemm_prepared calls)",
+            "workload": "config 4, 12 products on prepared operands, 1/6/9/d, " +
+                        ("12 fmt_gemm_prepared calls on %d side streams" % len(side) if args.no_batch
+                         else "one fmt_gemm_prepared_batch call"),
+            "value": round(cfg4_tflops, 2), "unit": "TFLOP/s (useful, 2MNK per product, whole calls)",
             "mfma_frac": round(cfg4_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
             "with_rounding_passes_tflops": round(cfg4_flops / ((cfg4_gemm_ms + cfg4_q_ms) * 1e-3) / 1e12, 2),
             "note": "1/6/9 operands are exponent planes: one scaled fp16 piece per value (per-row power-of-two "
@@ -297,7 +319,8 @@ def main() -> int:
                     "scheme (4 MFMA products per multiply) are measured beside it",
         },
         "gemm_config3": {
-            "workload": "config 3, 3 products on prepared operands, 1/6/9/d",
+            "workload": "config 3, 3 products on prepared operands, 1/6/9/d, " +
+                        ("3 fmt_gemm_prepared calls on side streams" if args.no_batch else "one fmt_gemm_prepared_batch call"),
             "value": round(cfg3_tflops, 2), "unit": "TFLOP/s (useful)",
             "with_rounding_passes_tflops": round(3 * 2.0 * M * N * K / ((cfg3_gemm_ms + cfg3_q_ms) * 1e-3) / 1e12, 2),
         },
@@ -373,7 +396,8 @@ def main() -> int:
             fmt.fmt_gemm_prepared(o["X"][0], o["W"][0], out=L["Y"])
             fmt.fmt_gemm_prepared(o["dY"][0], o["W"][1], out=L["dX"])
             fmt.fmt_gemm_prepared(o["dY"][1], o["X"][1], out=L["dW"])
-    result["gemm"]["single_stream_tflops"] = round(cfg4_flops / (timed0(cfg4_prepared, max(args.steps // 2, 1)) * 1e-3) / 1e12, 2)
+    result["gemm"]["single_calls_one_stream_tflops"] = round(cfg4_flops / (timed0(cfg4_prepared, max(args.steps // 2, 1)) * 1e-3) / 1e12, 2)
+    result["gemm"]["batch_call_tflops"] = round(cfg4_flops / (timed0(cfg4_batched, max(args.steps // 2, 1)) * 1e-3) / 1e12, 2)
 
     # Roofline of the product kernel: the largest product of config 4 (FFN1 forward, 4096 x 4096 x 1024,
     # one launch per call), timed with events on the stream it is launched on.

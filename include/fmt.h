@@ -24,7 +24,8 @@
  *                  used for fully connected layers and im2col convolutions in forward,
  *                  dgrad and wgrad (Sec. IV-A)
  * and, beyond these three:
- *   fmt_operand_bytes / fmt_prepare / fmt_prepare_pair / fmt_gemm_prepared / fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
+ *   fmt_operand_bytes / fmt_prepare / fmt_prepare_pair / fmt_gemm_prepared / fmt_gemm_prepared_batch /
+ *   fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
  *                  into a reusable operand in caller-owned memory (Sec. IV-A rounds each tensor once and
  *                  uses it in several products), and products run on two such operands
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
@@ -260,6 +261,24 @@ int fmt_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt
                      void *data, size_t bytes, fmt_operand_t *op,
                      void *data_t, size_t bytes_t, fmt_operand_t *op_t, void *stream);
 int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream);
+
+/*
+ * fmt_gemm_prepared_batch -- `count` independent products on prepared operands in one call:
+ * C[i] = A[i] B[i]^T for i in [0, count), each exactly what fmt_gemm_prepared(A[i], B[i], C[i], ldc[i]) computes
+ * (the FMACS sums of Sec. III-B; the order of accumulation is unspecified in both).  A training step of a
+ * network holds many products of modest size whose operands are all known when the step's tensors have been
+ * rounded (Sec. IV-A: three products per layer); handing them over together lets the library run the small
+ * ones in shared kernel launches, so that a launch's start-up and drain are paid once per batch and not once
+ * per product.  An operand may serve several products of the batch.
+ * A, B, C, ldc: HOST arrays of `count` entries (read before the call returns); the fmt_operand_t they point to
+ * are host memory as everywhere.  All operands of the batch share one format and one scheme (FMT_ERR_FORMAT
+ * otherwise).  No C[i] may overlap another C[j] or any operand of the batch (FMT_ERR_ALIAS): the products are
+ * not ordered among themselves.  count == 0 succeeds; count < 0 or > 4096: FMT_ERR_SHAPE.  Other errors as for
+ * fmt_gemm_prepared, found before anything is launched.  Uses the library's per-stream scratch only for the
+ * products that fmt_gemm_prepared itself would split over k.
+ */
+int fmt_gemm_prepared_batch(int64_t count, const fmt_operand_t *const *A, const fmt_operand_t *const *B,
+                            float *const *C, const int64_t *ldc, void *stream);
 
 /*
  * fmt_linear_prepared -- fmt_linear (below) on operands prepared with fmt_prepare: the quantized fully connected

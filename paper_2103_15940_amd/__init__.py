@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_prepare_pair", "fmt_gemm_prepared", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_prepare_pair", "fmt_gemm_prepared", "fmt_gemm_prepared_batch", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_scratch_bytes", "fmt_release_scratch", "fmt_status_string")
 
 
@@ -101,6 +101,10 @@ def _load() -> ctypes.CDLL:
     lib.fmt_prepare_pair.restype = ctypes.c_int
     lib.fmt_gemm_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, i64, vp]
     lib.fmt_gemm_prepared.restype = ctypes.c_int
+    lib.fmt_gemm_prepared_batch.argtypes = [i64, ctypes.POINTER(ctypes.POINTER(_COperand)),
+                                            ctypes.POINTER(ctypes.POINTER(_COperand)), ctypes.POINTER(vp),
+                                            ctypes.POINTER(i64), vp]
+    lib.fmt_gemm_prepared_batch.restype = ctypes.c_int
     lib.fmt_linear_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, vp, i64, vp, i32, vp]
     lib.fmt_linear_prepared.restype = ctypes.c_int
     lib.fmt_gemm_fmac8.argtypes = lib.fmt_gemm.argtypes
@@ -331,6 +335,35 @@ def fmt_gemm_prepared(A: PreparedOperand, B: PreparedOperand, out=None, stream=N
     ldc = out.stride(0) if M > 1 else max(N, 1)
     rc = _lib.fmt_gemm_prepared(ctypes.byref(A.desc), ctypes.byref(B.desc), out.data_ptr(), ldc, _stream_ptr(stream))
     _check(rc, "fmt_gemm_prepared")
+    return out
+
+
+def fmt_gemm_prepared_batch(A, B, out=None, stream=None):
+    """The products C[i] = A[i] B[i]^T of two equally long sequences of prepared operands in one call; the small
+    ones share kernel launches (Sec. IV-A: the three products of every layer are known once the step's tensors
+    are rounded).  Returns the list of results."""
+    import torch
+    A, B = list(A), list(B)
+    n = len(A)
+    if len(B) != n:
+        raise ValueError("A and B must hold the same number of operands")
+    if out is None:
+        out = [torch.empty((a.rows, b.rows), dtype=torch.float32, device=a.buf.device) for a, b in zip(A, B)]
+    out = list(out)
+    if len(out) != n:
+        raise ValueError("out must hold one tensor per product")
+    ldc = []
+    for a, b, c in zip(A, B, out):
+        _dev_f32(c, "out")
+        if c.dim() != 2 or tuple(c.shape) != (a.rows, b.rows) or (b.rows > 1 and c.stride(1) != 1):
+            raise ValueError("every out must be an M x N tensor with unit column stride")
+        ldc.append(c.stride(0) if a.rows > 1 else max(b.rows, 1))
+    PA = (ctypes.POINTER(_COperand) * max(n, 1))(*[ctypes.pointer(a.desc) for a in A])
+    PB = (ctypes.POINTER(_COperand) * max(n, 1))(*[ctypes.pointer(b.desc) for b in B])
+    PC = (ctypes.c_void_p * max(n, 1))(*[c.data_ptr() for c in out])
+    LD = (ctypes.c_int64 * max(n, 1))(*ldc)
+    rc = _lib.fmt_gemm_prepared_batch(n, PA, PB, PC, LD, _stream_ptr(stream))
+    _check(rc, "fmt_gemm_prepared_batch")
     return out
 
 

@@ -1,5 +1,6 @@
 // C-ABI entry points of libfmt: argument validation, format constants, scratch management.
 // The arithmetic lives in fmt_stream.hip (quantize / histogram) and fmt_gemm.hip.
+#include <vector>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -322,6 +323,33 @@ int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, 
     if (rc != FMT_OK) return rc;
     return launch_gemm_prepared(A->data, B->data, A->rows, B->rows, A->k, A->scheme, A->format, C, ldc,
                                 static_cast<hipStream_t>(stream));
+}
+
+int fmt_gemm_prepared_batch(int64_t count, const fmt_operand_t *const *A, const fmt_operand_t *const *B, float *const *C,
+                            const int64_t *ldc, void *stream)
+{
+    if (count < 0 || count > 4096) return FMT_ERR_SHAPE;
+    if (count == 0) return FMT_OK;
+    if (!A || !B || !C || !ldc) return FMT_ERR_NULL;
+    std::vector<BatchItem> items((size_t)count);
+    for (int64_t i = 0; i < count; ++i) {
+        const int rc = check_prepared(A[i], B[i], C[i], ldc[i]);
+        if (rc != FMT_OK) return rc;
+        const fmt_operand_t &a = *A[i], &a0 = *A[0];
+        if (a.format.e != a0.format.e || a.format.m != a0.format.m || (a.format.denorm != 0) != (a0.format.denorm != 0) ||
+            a.scheme != a0.scheme)
+            return FMT_ERR_FORMAT;
+        items[(size_t)i] = BatchItem{a.data, B[i]->data, a.rows, B[i]->rows, a.k, C[i], ldc[i]};
+    }
+    // no result may overlap another result or any operand of the batch (the products run concurrently)
+    auto cbytes = [&](int64_t i) { return 4 * (size_t)((A[i]->rows - 1) * ldc[i] + B[i]->rows); };
+    for (int64_t i = 0; i < count; ++i)
+        for (int64_t j = 0; j < count; ++j) {
+            if (j > i && overlap(C[i], cbytes(i), C[j], cbytes(j))) return FMT_ERR_ALIAS;
+            if (j != i && (overlap(C[i], cbytes(i), A[j]->data, A[j]->bytes) || overlap(C[i], cbytes(i), B[j]->data, B[j]->bytes)))
+                return FMT_ERR_ALIAS;
+        }
+    return launch_gemm_prepared_batch((int)count, items.data(), A[0]->scheme, A[0]->format, static_cast<hipStream_t>(stream));
 }
 
 int fmt_linear_prepared(const fmt_operand_t *X, const fmt_operand_t *W, const float *b, float *Y, int64_t ldy,

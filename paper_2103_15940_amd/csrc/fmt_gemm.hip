@@ -35,6 +35,9 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include <algorithm>
+#include <vector>
+
 #include "fmt_internal.h"
 #include "fmt_quant.h"
 
@@ -841,11 +844,13 @@ __device__ __forceinline__ void scaled_store(const floatx16 (&acc)[TM][TN], floa
 // whose address is a per-lane base (the position's corner pixel) plus a per-stage term (the tap and the
 // channel block), or the zero vector where the tap falls outside the tensor (a per-lane bit mask over
 // the taps).  The stage image in LDS and everything after it are the same.
+// The body is shared by the kernel of one product (bid = blockIdx.x) and the kernel of a group of products
+// (bid = the workgroup's index within its product).
 template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED, bool GATHER = false>
-__global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
-                                                      float *__restrict__ C, int M, int N, int64_t ldc, int img,
-                                                      int kblocks, int tiles_m, int tiles_n, int kb_per_split,
-                                                      Planes pa, Planes pb, Implicit im)
+__device__ __forceinline__ void product_body(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
+                                             float *__restrict__ C, int M, int N, int64_t ldc, int img,
+                                             int kblocks, int tiles_m, int tiles_n, int kb_per_split,
+                                             const Planes &pa, const Planes &pb, const Implicit &im, const unsigned bid)
 {
     constexpr int P = pieces_of(PS);
     constexpr int UA = 2 * TM, UB = 2 * TN;              // 32-row units per operand in the workgroup tile
@@ -876,8 +881,8 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
     // each with its own L2), so ids are remapped to give every XCD a contiguous run of tiles.
     const int ntiles = tiles_m * tiles_n;
     const int per_xcd = (ntiles + 7) / 8;
-    const int wg = blockIdx.x % (per_xcd * 8);
-    const int split = blockIdx.x / (per_xcd * 8);
+    const int wg = (int)(bid % (unsigned)(per_xcd * 8));
+    const int split = (int)(bid / (unsigned)(per_xcd * 8));
     const int tile = (wg % 8) * per_xcd + wg / 8;
     if (tile >= ntiles) return;
     // Within the run, tiles are walked in groups of kGroup tile rows, column by column, so that
@@ -1097,6 +1102,48 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
         }
 }
 
+template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED, bool GATHER = false>
+__global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw,
+                                                      float *__restrict__ C, int M, int N, int64_t ldc, int img,
+                                                      int kblocks, int tiles_m, int tiles_n, int kb_per_split,
+                                                      Planes pa, Planes pb, Implicit im)
+{
+    product_body<PS, TM, TN, KS, NST, SPLIT, SCHED, SCALED, GATHER>(Aw, Bw, C, M, N, ldc, img, kblocks, tiles_m, tiles_n,
+                                                                  kb_per_split, pa, pb, im, blockIdx.x);
+}
+
+// A group of independent products in one launch (fmt_gemm_prepared_batch): workgroup ids [first, next first)
+// belong to product g, each product's run of ids is a multiple of 8 long (so that id % 8, the XCD, means the
+// same inside every run), and every product runs the same kernel variant -- no k split, plain row-major output.
+// One launch instead of one per product: launch, pipeline fill and drain -- about a third of the time of a
+// product with K = 1024 -- are paid once, and the tiles of the next product fill the compute units that the
+// last tiles of the previous one leave idle.
+constexpr int kMaxGroup = 16;
+struct GroupItem {
+    const u32x4 *Aw, *Bw;
+    float *C;
+    int64_t ldc;
+    int M, N, kblocks, tiles_m, tiles_n;
+    unsigned first;
+    Planes pa, pb;
+};
+struct Group {
+    int count;
+    GroupItem p[kMaxGroup];
+};
+
+template <int PS, int TM, int TN, int KS, int NST, bool SCHED, bool SCALED>
+__global__ __launch_bounds__(256) void product_group_kernel(Group grp)
+{
+    int g = 0;
+    for (int i = 1; i < grp.count; ++i)
+        if (blockIdx.x >= grp.p[i].first) g = i;         // the same in the whole workgroup
+    const GroupItem &it = grp.p[g];
+    product_body<PS, TM, TN, KS, NST, false, SCHED, SCALED, false>(it.Aw, it.Bw, it.C, it.M, it.N, it.ldc, 0, it.kblocks, it.tiles_m,
+                                                                 it.tiles_n, it.kblocks, it.pa, it.pb, Implicit{},
+                                                                 blockIdx.x - it.first);
+}
+
 // Half h (0..7) of a 16-byte vector of eight 16-bit patterns, as a float (binary16 -> fp32 is exact).
 __device__ __forceinline__ float half_of(const u32x4 &v, int h)
 {
@@ -1133,16 +1180,16 @@ __device__ __forceinline__ float unit_value(const u32x4 *__restrict__ W, size_t 
 // A block whose units hold nothing but plane 0 -- the usual case -- leaves after reading its masks.
 constexpr int kTailRecs = kUnitRows * kUnitK;    // element records held at a time: one plane of one unit always fits
 
-__global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw, Planes pa,
-                                                          Planes pb, float *__restrict__ C, int64_t ldc, int M, int N, int kblocks,
-                                                          int col_chunks)
+__device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw, const Planes &pa,
+                                                 const Planes &pb, float *__restrict__ C, int64_t ldc, int M, int N, int kblocks,
+                                                 int col_chunks, const unsigned bid)
 {
     __shared__ uint32_t s_rec[kTailRecs];        // row-or-column in the unit (5 bits) | k << 5
     __shared__ float s_val[kTailRecs];           // the element's true value
     __shared__ uint32_t s_list[256];             // k blocks (of one scan of 256) whose unit has other planes | planes << 16
     __shared__ int s_cnt[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rb = blockIdx.x / col_chunks, cc = blockIdx.x % col_chunks;
+    const int rb = (int)(bid / (unsigned)col_chunks), cc = (int)(bid % (unsigned)col_chunks);
     const int ub0 = cc * 8;                      // first unit of B of this block (B is padded to whole groups of 8 units)
 
     // this thread's mask byte of the row of units of A (k block tid); rows longer than 256 k blocks are re-read later
@@ -1319,6 +1366,36 @@ __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restric
             });
         }
     }
+}
+
+__global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw, Planes pa,
+                                                          Planes pb, float *__restrict__ C, int64_t ldc, int M, int N, int kblocks,
+                                                          int col_chunks)
+{
+    planes_tail_body(Aw, Bw, pa, pb, C, ldc, M, N, kblocks, col_chunks, blockIdx.x);
+}
+
+// The tails of a group of products in one launch: blocks [first, next first) belong to product g.
+struct TailGroupItem {
+    const u32x4 *Aw, *Bw;
+    float *C;
+    int64_t ldc;
+    int M, N, kblocks, col_chunks;
+    unsigned first;
+    Planes pa, pb;
+};
+struct TailGroup {
+    int count;
+    TailGroupItem p[kMaxGroup];
+};
+
+__global__ __launch_bounds__(256) void planes_tail_group_kernel(TailGroup grp)
+{
+    int g = 0;
+    for (int i = 1; i < grp.count; ++i)
+        if (blockIdx.x >= grp.p[i].first) g = i;         // the same in the whole workgroup
+    const TailGroupItem &it = grp.p[g];
+    planes_tail_body(it.Aw, it.Bw, it.pa, it.pb, it.C, it.ldc, it.M, it.N, it.kblocks, it.col_chunks, blockIdx.x - it.first);
 }
 
 // C[r][c] = sum over the k parts of part[s][r][c]  (parts are dense M x N slabs)
@@ -1987,6 +2064,128 @@ int launch_gemm_prepared(const void *A, const void *B, int64_t M64, int64_t N64,
     }
     const OperandView va = view_of(const_cast<void *>(A), la), vb = view_of(const_cast<void *>(B), lb);
     return product_dispatch(sch.ps, va, vb, M, N, la.kblocks, OutSpec{C, ldc, 0}, plan, part, stream);
+}
+
+template <int PS, bool SCALED, int T>
+static int launch_group_t(const Group &grp, unsigned grid, hipStream_t stream)
+{
+    constexpr int KS = Pipe<PS, T, T>::ks, NST = Pipe<PS, T, T>::nst;
+    if constexpr (lds_bytes(T, T, pieces_of(PS), KS, NST) > 160 * 1024) {
+        return FMT_ERR_SHAPE;                            // never chosen (group_tile checks the same bound)
+    } else {
+        hipLaunchKernelGGL((product_group_kernel<PS, T, T, KS, NST, true, SCALED>), dim3(grid), dim3(256), 0, stream, grp);
+        FMT_HIP_CHECK(hipGetLastError());
+        return FMT_OK;
+    }
+}
+
+template <int PS, bool SCALED>
+static int launch_group(const Group &grp, unsigned grid, int t, hipStream_t stream)
+{
+    return t == 4 ? launch_group_t<PS, SCALED, 4>(grp, grid, stream) : launch_group_t<PS, SCALED, 2>(grp, grid, stream);
+}
+
+// Workgroup tile of a shared launch: 64 t x 64 t with t = 2 or 4.  The 256 x 256 tile has the faster main loop
+// (half the LDS bytes per MFMA) but runs one workgroup per compute unit, so nothing hides a tile's start and
+// its stores; the 128 x 128 tile runs two.  Measured on MI355X: products of k = 1024 alone run a few per cent
+// faster on the small tile, a mix in which most of the multiplications belong to products of k = 4096 runs
+// 10 - 20 % faster on the large one.  The large tile is taken when the multiplication-weighted mean k of the
+// group is 1536 or more and its tiles fill every compute unit.
+static int group_tile(const BatchItem *items, const std::vector<int> &grouped, size_t g0, int n, int cus, int pieces)
+{
+    if (const char *env = getenv("FMT_GEMM_GROUP_TILE")) {      // tuning override: "2" or "4"
+        const int t = atoi(env);
+        if (t == 2 || (t == 4 && lds_bytes(4, 4, pieces, pipe_ks(pieces), 2) <= 160 * 1024)) return t;
+    }
+    if (lds_bytes(4, 4, pieces, pipe_ks(pieces), 2) > 160 * 1024) return 2;
+    double mults = 0.0, weighted = 0.0;
+    int64_t tiles4 = 0;
+    for (int j = 0; j < n; ++j) {
+        const BatchItem &it = items[grouped[g0 + j]];
+        const double w = (double)it.M * it.N * it.K;
+        mults += w;
+        weighted += w * it.K;
+        tiles4 += ((it.M + 255) / 256) * ((it.N + 255) / 256);
+    }
+    return weighted >= 1536.0 * mults && tiles4 >= cus ? 4 : 2;
+}
+
+// Several products on prepared operands (all of one format and scheme).  A product joins a shared launch when
+// it needs no split over k: its own plan has none, or one of its tiles is no longer than the work the whole
+// batch leaves to each compute unit (then the other products fill the machine while its few long tiles run).
+// Shared launches hold up to kMaxGroup products, longest k first (their tiles take longest and workgroups start
+// in id order); the other products run one by one as launch_gemm_prepared runs them.
+int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fmt_format_t f, hipStream_t stream)
+{
+    const Scheme sch{scheme & 15, (scheme & 16) != 0};
+    int cus = 0;
+    int rc = device_cu_count(&cus);
+    if (rc != FMT_OK) return rc;
+    std::vector<int> grouped, alone;
+    double load = 0.0;                                   // 256 x 256 x 32 blocks of multiplications per compute unit
+    for (int i = 0; i < count; ++i)
+        load += (double)((items[i].M + 255) / 256) * (double)((items[i].N + 255) / 256) * (double)((items[i].K + kUnitK - 1) / kUnitK);
+    load /= cus;
+    for (int i = 0; i < count; ++i) {
+        const int kblocks = (int)((items[i].K + kUnitK - 1) / kUnitK);
+        const Plan plan = make_plan((int)items[i].M, (int)items[i].N, kblocks, cus, pieces_of(sch.ps));
+        (plan.nsplit == 1 || kblocks <= load ? grouped : alone).push_back(i);
+    }
+    if (grouped.size() == 1) {
+        alone.push_back(grouped[0]);
+        grouped.clear();
+    }
+    std::stable_sort(grouped.begin(), grouped.end(), [&](int a, int b) { return items[a].K > items[b].K; });
+
+    for (size_t g0 = 0; g0 < grouped.size(); g0 += kMaxGroup) {
+        const int n = (int)std::min<size_t>(kMaxGroup, grouped.size() - g0);
+        const int gt = group_tile(items, grouped, g0, n, cus, pieces_of(sch.ps));
+        Group grp{};
+        TailGroup tg{};
+        grp.count = tg.count = n;
+        uint64_t ids = 0, blocks = 0;
+        for (int j = 0; j < n; ++j) {
+            const BatchItem &it = items[grouped[g0 + j]];
+            OperandLayout la, lb;
+            rc = operand_layout(it.M, it.K, sch, f.m, &la);
+            if (rc != FMT_OK) return rc;
+            rc = operand_layout(it.N, it.K, sch, f.m, &lb);
+            if (rc != FMT_OK) return rc;
+            const OperandView va = view_of(const_cast<void *>(it.A), la), vb = view_of(const_cast<void *>(it.B), lb);
+            const int M = (int)it.M, N = (int)it.N;
+            GroupItem &p = grp.p[j];
+            p.Aw = va.W; p.Bw = vb.W; p.C = it.C; p.ldc = it.ldc;
+            p.M = M; p.N = N; p.kblocks = la.kblocks;
+            p.tiles_m = (M + 64 * gt - 1) / (64 * gt); p.tiles_n = (N + 64 * gt - 1) / (64 * gt);
+            p.first = (unsigned)ids;
+            p.pa = va.pl; p.pb = vb.pl;
+            ids += ((uint64_t)p.tiles_m * p.tiles_n + 7) / 8 * 8;
+            TailGroupItem &t = tg.p[j];
+            t.Aw = va.W; t.Bw = vb.W; t.C = it.C; t.ldc = it.ldc;
+            t.M = M; t.N = N; t.kblocks = la.kblocks; t.col_chunks = (N + 255) / 256;
+            t.first = (unsigned)blocks;
+            t.pa = va.pl; t.pb = vb.pl;
+            blocks += (uint64_t)((M + kUnitRows - 1) / kUnitRows) * t.col_chunks;
+            if (ids >= ((uint64_t)1 << 31) || blocks >= ((uint64_t)1 << 31)) return FMT_ERR_SHAPE;
+        }
+        switch (sch.ps) {
+            case 0: rc = sch.scaled ? launch_group<0, true>(grp, (unsigned)ids, gt, stream) : launch_group<0, false>(grp, (unsigned)ids, gt, stream); break;
+            case 1: rc = launch_group<1, false>(grp, (unsigned)ids, gt, stream); break;
+            case 2: rc = launch_group<2, false>(grp, (unsigned)ids, gt, stream); break;
+            default: rc = launch_group<3, false>(grp, (unsigned)ids, gt, stream); break;
+        }
+        if (rc != FMT_OK) return rc;
+        if (sch.scaled) {
+            hipLaunchKernelGGL(planes_tail_group_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, tg);
+            FMT_HIP_CHECK(hipGetLastError());
+        }
+    }
+    for (int i : alone) {
+        rc = launch_gemm_prepared(items[i].A, items[i].B, items[i].M, items[i].N, items[i].K, scheme, f, items[i].C, items[i].ldc,
+                                  stream);
+        if (rc != FMT_OK) return rc;
+    }
+    return FMT_OK;
 }
 
 static int zero_fill(float *C, int64_t rows, int64_t cols, int64_t ldc, hipStream_t stream)

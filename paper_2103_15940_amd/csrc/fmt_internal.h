@@ -70,6 +70,14 @@ int launch_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, 
                         void *buf1, hipStream_t stream);
 int launch_gemm_prepared(const void *A, const void *B, int64_t M, int64_t N, int64_t K, int scheme, fmt_format_t f,
                          float *C, int64_t ldc, hipStream_t stream);
+// One product of a batch on prepared operands: C (M x N, leading dimension ldc) = A (M rows) B^T (N rows), both of k = K.
+struct BatchItem {
+    const void *A, *B;
+    int64_t M, N, K;
+    float *C;
+    int64_t ldc;
+};
+int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fmt_format_t f, hipStream_t stream);
 
 // Convolutions as products of gathered operands (fmt_gemm.hip); which: 0 forward, 1 dgrad, 2 wgrad
 int launch_conv2d(int which, const fmt_conv2d_t &g, const float *a, const float *b, float *out, fmt_format_t f,

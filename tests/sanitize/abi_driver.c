@@ -95,6 +95,17 @@ int main(void)
     EXPECT(fmt_prepare_pair(x, 8, 4, 8, f, base + 2048, (size_t)1 << 30, &op, NULL, (size_t)1 << 30, &op_t, NULL), FMT_ERR_NULL);
     EXPECT(fmt_prepare_pair(x, 8, 0, 8, f, base + 2048, (size_t)1 << 30, &op, base + 8192, (size_t)1 << 30, &op_t, NULL), FMT_ERR_SHAPE);
     EXPECT(fmt_scratch_bytes(NULL, NULL), FMT_ERR_NULL);
+    {
+        const fmt_operand_t *pa[2] = {&a, &a}, *pb[2] = {&b, NULL};
+        float *pc[2] = {y, y};
+        int64_t ld[2] = {4, 4};
+        EXPECT(fmt_gemm_prepared_batch(0, NULL, NULL, NULL, NULL, NULL), FMT_OK);
+        EXPECT(fmt_gemm_prepared_batch(-1, pa, pb, pc, ld, NULL), FMT_ERR_SHAPE);
+        EXPECT(fmt_gemm_prepared_batch(2, pa, NULL, pc, ld, NULL), FMT_ERR_NULL);
+        EXPECT(fmt_gemm_prepared_batch(2, pa, pb, pc, ld, NULL), FMT_ERR_SHAPE);     /* first product: k differs */
+        pb[0] = NULL;
+        EXPECT(fmt_gemm_prepared_batch(2, pa, pb, pc, ld, NULL), FMT_ERR_NULL);      /* first product: no B */
+    }
     /* convolutions */
     fmt_conv2d_t g = {1, 1, 4, 4, 1, 3, 3, 1, 1, 1, 1};
     EXPECT(fmt_conv2d_fwd(g, NULL, x, y, f, NULL), FMT_ERR_NULL);

@@ -246,3 +246,29 @@ def test_linear_prepared_validates_before_any_gpu_call():
     b = fmt._COperand(ctypes.c_void_p(1 << 30), 1 << 20, 32, 64, fmt._CFormat(5, 10, 1), 0)
     y = ctypes.c_void_p(1 << 40)
     assert lib.fmt_linear_prepared(ctypes.byref(a), ctypes.byref(b), None, y, 32, None, -48, None) == -1   # formats differ
+
+
+def test_gemm_prepared_batch_validates_before_any_gpu_call():
+    """fmt_gemm_prepared_batch: count, NULL arrays, mixed formats and overlapping results are refused on a host
+    without a GPU; an empty batch succeeds."""
+    import ctypes
+    lib = fmt.raw_library()
+    assert lib.fmt_gemm_prepared_batch(0, None, None, None, None, None) == 0
+    assert lib.fmt_gemm_prepared_batch(-1, None, None, None, None, None) == -3
+    assert lib.fmt_gemm_prepared_batch(2, None, None, None, None, None) == -2
+    P = ctypes.POINTER(fmt._COperand)
+    a = fmt._COperand(ctypes.c_void_p(256), 1 << 20, 32, 64, fmt._CFormat(6, 9, 1), 16)
+    b = fmt._COperand(ctypes.c_void_p(1 << 30), 1 << 20, 32, 64, fmt._CFormat(6, 9, 1), 16)
+    ah = fmt._COperand(ctypes.c_void_p(1 << 31), 1 << 20, 32, 64, fmt._CFormat(5, 10, 1), 0)
+    bh = fmt._COperand(ctypes.c_void_p(1 << 32), 1 << 20, 32, 64, fmt._CFormat(5, 10, 1), 0)
+    ld = (ctypes.c_int64 * 2)(32, 32)
+    C = (ctypes.c_void_p * 2)(1 << 40, 1 << 41)
+    A2, B2 = (P * 2)(ctypes.pointer(a), ctypes.pointer(ah)), (P * 2)(ctypes.pointer(b), ctypes.pointer(bh))
+    assert lib.fmt_gemm_prepared_batch(2, A2, B2, C, ld, None) == -1          # two formats in one batch
+    A1, B1 = (P * 2)(ctypes.pointer(a), ctypes.pointer(a)), (P * 2)(ctypes.pointer(b), ctypes.pointer(b))
+    Csame = (ctypes.c_void_p * 2)(1 << 40, (1 << 40) + 64)
+    assert lib.fmt_gemm_prepared_batch(2, A1, B1, Csame, ld, None) == -6      # results overlap
+    Cop = (ctypes.c_void_p * 2)(1 << 40, 256)
+    assert lib.fmt_gemm_prepared_batch(2, A1, B1, Cop, ld, None) == -6        # a result overlaps an operand
+    A0 = (P * 2)(ctypes.pointer(a), None)
+    assert lib.fmt_gemm_prepared_batch(2, A0, B1, C, ld, None) == -2
