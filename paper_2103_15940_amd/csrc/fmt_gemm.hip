@@ -36,6 +36,7 @@
 #include <type_traits>
 
 #include <algorithm>
+#include <cmath>
 #include <vector>
 
 #include "fmt_internal.h"
@@ -793,41 +794,115 @@ __global__ __launch_bounds__(256) void prepare_scaled_kernel(PrepOperand a, Prep
     prepare_scaled_block<MODE, FTZ>(o, second ? Kb : Ka, second ? kblocks_b : kblocks_a, p, bid);
 }
 
-// Epilogue of the scaled scheme for one wave: out = acc * 2^-(S_row + S_col), exactly.  The
-// scale arrays are padded to the tile grid and 16-byte aligned, and a lane's rows come in groups of
-// four: all of a lane's scales are fetched together, with vector loads, ahead of its stores.
-// 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
-template <int TM, int TN>
-__device__ __forceinline__ void scaled_store(const floatx16 (&acc)[TM][TN], float *__restrict__ out, int64_t ldc, int M, int N,
-                                             int tm, int tn, int wm, int wn, int lane, const int *__restrict__ Sa,
-                                             const int *__restrict__ Sb)
+// Epilogue of one wave.  The MFMAs are fed operand B's fragment first and A's second, so a 32 x 32 accumulator
+// block holds the TRANSPOSE of the usual layout: register v of lane l holds row l % 32 and column
+// 8*(v/4) + 4*(l/32) + v%4 of the block of C -- four consecutive columns per group of four registers, which
+// leave in one 16-byte store per lane (64 store instructions per wave for a 256 x 256 tile instead of 256;
+// nothing is assumed about alignment beyond 4 bytes).
+// SCALED: out = acc * 2^-(S_row + S_col), exactly; the scale arrays are padded to the tile grid and 16-byte
+// aligned, and all of a lane's scales are fetched together ahead of its stores.
+// img > 0: column = (image, position), element (row, col) goes to out[image][row][position] (NCHW with `img`
+// positions); the four columns of a group go out together when they fall into one image.
+// A wave whose block of C lies inside the matrix (all but the last row and column of tiles) takes a path without
+// per-lane tests, in two phases: first every accumulator is scaled in place, then the stores go out straight
+// from the accumulator registers.  Measured on a 256 x 256 tile (one wave per SIMD): stores interleaved with
+// the arithmetic that refills their data registers take 20 - 25 us per tile when every compute unit stores at
+// once (a store holds its data registers until the memory pipeline has taken them), the two phases 8 us, of
+// which the stores are 5.
+template <int TM, int TN, bool SCALED>
+__device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], float *__restrict__ out, int64_t ld, int M, int N, int img,
+                                           int row_base, int col_base, int lane, const int *__restrict__ Sa,
+                                           const int *__restrict__ Sb)
 {
     typedef int i32x4 __attribute__((ext_vector_type(4)));
-    const int col_in = lane & 31, row_half = (lane >> 5) * 4;
-    int sbv[TN];
-    i32x4 sav[TM][4];                          // all loads first: one wait instead of one per group of rows
+    typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+    const int r_in = lane & 31, c_half = (lane >> 5) * 4;
+    int sa[TM];
+    i32x4 sb[TN][4];
+    if constexpr (SCALED) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) sbv[j] = Sb[(tn * 2 + wn) * (32 * TN) + j * 32 + col_in];
+        for (int i = 0; i < TM; ++i) sa[i] = Sa[row_base + i * 32 + r_in];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-            sav[i][g] = *reinterpret_cast<const i32x4 *>(Sa + (tm * 2 + wm) * (32 * TM) + i * 32 + row_half + g * 8);
+            for (int g = 0; g < 4; ++g) sb[j][g] = -*reinterpret_cast<const i32x4 *>(Sb + col_base + j * 32 + g * 8 + c_half);
+    }
+    // rows are `rs` elements apart in both output maps
+    const size_t rs = img > 0 ? (size_t)img : (size_t)ld;
+    float *rowp[TM];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
+    for (int i = 0; i < TM; ++i) rowp[i] = out + (size_t)(row_base + i * 32 + r_in) * rs;
+
+    if (row_base + 32 * TM <= M && col_base + 32 * TN <= N && (img & 3) == 0) {      // the same in the whole wave
+        if constexpr (SCALED) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
-            if (col < N) {
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < M) out[(size_t)row * ldc + col] = ldexpf(acc[i][j][v], -(sav[i][v >> 2][v & 3] + sbv[j]));
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = ldexpf(acc[i][j][v], sb[j][v >> 2][v & 3] - sa[i]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col0 = col_base + j * 32 + g * 8 + c_half;
+                size_t coff = (size_t)col0;
+                if (img > 0) {                   // img is a multiple of 4 and so is col0: one image holds the four columns
+                    const int image = col0 / img;
+                    coff = (size_t)image * M * img + (col0 - image * img);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    f32x4u v;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) v[c] = acc[i][j][g * 4 + c];
+                    *reinterpret_cast<f32x4u *>(rowp[i] + coff) = v;
+                }
+            }
+        return;
+    }
+    // the last row or column of tiles, and NCHW maps whose images are not a multiple of 4 positions long
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int col0 = col_base + j * 32 + g * 8 + c_half;
+            if (col0 >= N) continue;
+            // offset of column col0 within a row of the output map; whether its four columns are adjacent there
+            size_t coff = (size_t)col0;
+            bool together = col0 + 3 < N;
+            if (img > 0) {
+                const int image = col0 / img, pos = col0 - image * img;
+                coff = (size_t)image * M * img + pos;
+                together = together && pos + 3 < img;
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if (row_base + i * 32 + r_in >= M) continue;
+                f32x4u v;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    v[c] = acc[i][j][g * 4 + c];
+                    if constexpr (SCALED) v[c] = ldexpf(v[c], sb[j][g][c] - sa[i]);
+                }
+                if (together) {
+                    *reinterpret_cast<f32x4u *>(rowp[i] + coff) = v;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (col0 + c < N) {
+                            size_t off = coff + c;
+                            if (img > 0) {
+                                const int image = (col0 + c) / img;
+                                off = (size_t)image * M * img + (col0 + c - image * img);
+                            }
+                            rowp[i][off] = v[c];
+                        }
                 }
             }
         }
-    }
 }
 
 // product: Aw / Bw are prepared operands (rows padded to a multiple of kRowPad, k to a multiple
@@ -1026,10 +1101,11 @@ __device__ __forceinline__ void product_body(const u32x4 *__restrict__ Aw, const
                     for (int qa = 0; qa < P; ++qa)
 #pragma unroll
                         for (int qb = 0; qb < P; ++qb)
-                            acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[cur][kk][i][qa]),
-                                                                                         __builtin_bit_cast(f16x8, fb[cur][kk][j][qb]),
+                            // B's fragment first: the block comes out transposed (see store_tile)
+                            acc[i][j] = PS == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fb[cur][kk][j][qb]),
+                                                                                         __builtin_bit_cast(f16x8, fa[cur][kk][i][qa]),
                                                                                          acc[i][j], 0, 0, 0)
-                                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][kk][i][qa], fb[cur][kk][j][qb], acc[i][j], 0, 0, 0);
+                                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][kk][j][qb], fa[cur][kk][i][qa], acc[i][j], 0, 0, 0);
         }
         // Issue order inside one trip: the next stage's LDS reads, then its global loads, threaded
         // between the MFMAs so that they issue in the MFMAs' shadow.
@@ -1074,32 +1150,10 @@ __device__ __forceinline__ void product_body(const u32x4 *__restrict__ Aw, const
     // every load-to-LDS of this wave must have landed before the workgroup's LDS is handed back
     __builtin_amdgcn_s_waitcnt(0x0F70);
 
-    // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    // plain: C[row][col] with leading dimension ldc; a part of a split k: its own M x N slab; img > 0: NCHW
     float *out = SPLIT ? C + (size_t)split * M * ldc : C;
-    const int col_in = lane & 31, row_half = (lane >> 5) * 4;
-    if constexpr (SCALED) {
-        scaled_store<TM, TN>(acc, out, ldc, M, N, tm, tn, wm, wn, lane, pa.S, pb.S);
-        return;
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = (tn * 2 + wn) * (32 * TN) + j * 32 + col_in;
-            const int row0 = (tm * 2 + wm) * (32 * TM) + i * 32 + row_half;
-            if (col < N) {
-                // plain: C[row][col] with leading dimension ldc; img > 0: column = (image, position),
-                // element (row, col) goes to C[image][row][position] (NCHW with `img` positions)
-                const bool nchw = !SPLIT && img > 0;
-                const size_t coff = nchw ? (size_t)(col / img) * M * img + col % img : (size_t)col;
-                const size_t rs = nchw ? (size_t)img : (size_t)ldc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < M) out[(size_t)row * rs + coff] = acc[i][j][v];
-                }
-            }
-        }
+    store_tile<TM, TN, SCALED>(acc, out, ldc, M, N, SPLIT ? 0 : img, (tm * 2 + wm) * (32 * TM), (tn * 2 + wn) * (32 * TN), lane, pa.S,
+                               pb.S);
 }
 
 template <int PS, int TM, int TN, int KS, int NST, bool SPLIT, bool SCHED, bool SCALED, bool GATHER = false>
@@ -2085,12 +2139,14 @@ static int launch_group(const Group &grp, unsigned grid, int t, hipStream_t stre
     return t == 4 ? launch_group_t<PS, SCALED, 4>(grp, grid, stream) : launch_group_t<PS, SCALED, 2>(grp, grid, stream);
 }
 
-// Workgroup tile of a shared launch: 64 t x 64 t with t = 2 or 4.  The 256 x 256 tile has the faster main loop
-// (half the LDS bytes per MFMA) but runs one workgroup per compute unit, so nothing hides a tile's start and
-// its stores; the 128 x 128 tile runs two.  Measured on MI355X: products of k = 1024 alone run a few per cent
-// faster on the small tile, a mix in which most of the multiplications belong to products of k = 4096 runs
-// 10 - 20 % faster on the large one.  The large tile is taken when the multiplication-weighted mean k of the
-// group is 1536 or more and its tiles fill every compute unit.
+// Workgroup tile of a shared launch: 64 t x 64 t with t = 2 or 4.  The 256 x 256 tile runs one workgroup per
+// compute unit, the 128 x 128 tile two; per unit of k both keep the matrix cores about equally busy when every
+// slot has work, so what decides is how the tiles fill the slots.  A tile of kb blocks of 32 k takes about
+// 9.5 + 0.89 kb us (large) or 9.8 + 0.47 kb us (small, two to a compute unit) on one fp16 piece -- fitted to
+// per-workgroup timestamps on MI355X -- and P x P times the k term on P bf16 pieces.  Workgroups start in
+// id order, longest tiles first, so the launch takes about as long as the larger of: all tile time spread
+// over all slots; for each product, the rounds that the tiles up to and including its own need, times its
+// tile time.  The shape with the smaller estimate is taken.
 static int group_tile(const BatchItem *items, const std::vector<int> &grouped, size_t g0, int n, int cus, int pieces)
 {
     if (const char *env = getenv("FMT_GEMM_GROUP_TILE")) {      // tuning override: "2" or "4"
@@ -2098,16 +2154,21 @@ static int group_tile(const BatchItem *items, const std::vector<int> &grouped, s
         if (t == 2 || (t == 4 && lds_bytes(4, 4, pieces, pipe_ks(pieces), 2) <= 160 * 1024)) return t;
     }
     if (lds_bytes(4, 4, pieces, pipe_ks(pieces), 2) > 160 * 1024) return 2;
-    double mults = 0.0, weighted = 0.0;
-    int64_t tiles4 = 0;
-    for (int j = 0; j < n; ++j) {
-        const BatchItem &it = items[grouped[g0 + j]];
-        const double w = (double)it.M * it.N * it.K;
-        mults += w;
-        weighted += w * it.K;
-        tiles4 += ((it.M + 255) / 256) * ((it.N + 255) / 256);
-    }
-    return weighted >= 1536.0 * mults && tiles4 >= cus ? 4 : 2;
+    auto estimate = [&](int t) {
+        const double fixed = t == 4 ? 9.5 : 9.8, per_kb = (t == 4 ? 0.89 : 0.47) * pieces * pieces;
+        const double slots = (double)cus * (t == 4 ? 1 : 2);
+        double work = 0.0, tiles = 0.0, rounds_bound = 0.0;
+        for (int j = 0; j < n; ++j) {                            // longest k first
+            const BatchItem &it = items[grouped[g0 + j]];
+            const double tile_time = fixed + per_kb * (double)((it.K + kUnitK - 1) / kUnitK);
+            const double nt = (double)((it.M + 64 * t - 1) / (64 * t)) * (double)((it.N + 64 * t - 1) / (64 * t));
+            tiles += nt;
+            work += nt * tile_time;
+            rounds_bound = std::max(rounds_bound, std::ceil(tiles / slots) * tile_time);
+        }
+        return std::max(work / slots, rounds_bound);
+    };
+    return estimate(4) < estimate(2) ? 4 : 2;
 }
 
 // Several products on prepared operands (all of one format and scheme).  A product joins a shared launch when
