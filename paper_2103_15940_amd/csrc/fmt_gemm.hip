@@ -843,24 +843,29 @@ __device__ __forceinline__ void store_tile(floatx16 (&acc)[TM][TN], float *__res
                     for (int v = 0; v < 16; ++v) acc[i][j][v] = ldexpf(acc[i][j][v], sb[j][v >> 2][v & 3] - sa[i]);
             __builtin_amdgcn_sched_barrier(0);
         }
+        // the four stores that complete the 128-byte lines of a block go out back to back
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j) {
+            size_t coff[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int col0 = col_base + j * 32 + g * 8 + c_half;
-                size_t coff = (size_t)col0;
+                coff[g] = (size_t)col0;
                 if (img > 0) {                   // img is a multiple of 4 and so is col0: one image holds the four columns
                     const int image = col0 / img;
-                    coff = (size_t)image * M * img + (col0 - image * img);
+                    coff[g] = (size_t)image * M * img + (col0 - image * img);
                 }
+            }
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
                     f32x4u v;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) v[c] = acc[i][j][g * 4 + c];
-                    *reinterpret_cast<f32x4u *>(rowp[i] + coff) = v;
+                    *reinterpret_cast<f32x4u *>(rowp[i] + coff[g]) = v;
                 }
-            }
+        }
         return;
     }
     // the last row or column of tiles, and NCHW maps whose images are not a multiple of 4 positions long
@@ -1225,7 +1230,10 @@ __device__ __forceinline__ float unit_value(const u32x4 *__restrict__ W, size_t 
 // contributes to one row or one column of C, so they are added one product at a time with fp32 fused
 // multiply-adds on the TRUE values (the binary16 pattern with its plane's and its row's scale undone: a
 // value of the format, exactly an fp32) -- exact product, one rounding per accumulation, FMACS.
-// One workgroup owns a block of 32 rows (one unit of A) x 256 columns (8 units of B) of C:
+// One workgroup owns a block of 32 rows (one unit of A) x tail_cols columns (8, 16 or 32 units of B) of C.
+// Finding the elements of a row of units (masks, the other planes' vectors, the records) is a chain of dependent
+// loads and barriers that costs more than using them, and every block of the same rows repeats it: wide blocks
+// when the launch has blocks enough to fill the machine anyway, narrow ones otherwise (tail_cols_for).
 //   1. every element a of A's other planes in its rows meets the FULL value of B (all planes) at that k
 //      in each of its columns, elements in the order (k block, plane, position in the unit);
 //   2. then every element b of B's other planes in its columns meets the plane-0 value of A in each of its
@@ -1236,7 +1244,7 @@ constexpr int kTailRecs = kUnitRows * kUnitK;    // element records held at a ti
 
 __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw, const Planes &pa,
                                                  const Planes &pb, float *__restrict__ C, int64_t ldc, int M, int N, int kblocks,
-                                                 int col_chunks, const unsigned bid)
+                                                 int col_chunks, int tail_cols, const unsigned bid)
 {
     __shared__ uint32_t s_rec[kTailRecs];        // row-or-column in the unit (5 bits) | k << 5
     __shared__ float s_val[kTailRecs];           // the element's true value
@@ -1244,13 +1252,14 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
     __shared__ int s_cnt[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rb = (int)(bid / (unsigned)col_chunks), cc = (int)(bid % (unsigned)col_chunks);
-    const int ub0 = cc * 8;                      // first unit of B of this block (B is padded to whole groups of 8 units)
+    const int ub0 = cc * (tail_cols / kUnitRows);    // first unit of B of this block
+    const int nub = min(tail_cols / kUnitRows, (N + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows) - ub0);   // B is padded to whole groups of 8 units
 
     // this thread's mask byte of the row of units of A (k block tid); rows longer than 256 k blocks are re-read later
     const uint32_t first_a = tid < kblocks ? (uint32_t)pa.mask[(size_t)rb * kblocks + tid] & 6u : 0u;
     bool any_a = first_a != 0u, any_b = false;
     for (int kb = 256 + tid; kb < kblocks; kb += 256) any_a |= (pa.mask[(size_t)rb * kblocks + kb] & 6u) != 0u;
-    for (int i = tid; i < 8 * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
+    for (int i = tid; i < nub * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
     const bool do_a = __syncthreads_or((int)any_a) != 0, do_b = __syncthreads_or((int)any_b) != 0;
     if (!do_a && !do_b) return;
 
@@ -1346,12 +1355,15 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
     };
 
     if (do_a) {
-        // 1. this block's column of thread tid: C[row][col] += a * b(k, col) for the records (row, k, a) in order
-        const int col = cc * 256 + tid;
-        const int ub = col / kUnitRows, cr = col % kUnitRows;
-        const int sb = col < N ? pb.S[col] : 0;
+        // 1. this block's columns of thread tid, one after the other: C[row][col] += a * b(k, col) for the
+        //    records (row, k, a) in order
         walk(Aw, pa, (size_t)rb, pa.S + rb * kUnitRows, first_a, true, [&](int n) {
+#pragma unroll 1
+          for (int j = 0; j < tail_cols / 256; ++j) {
+            const int col = cc * tail_cols + j * 256 + tid;
             if (col >= N) return;
+            const int ub = col / kUnitRows, cr = col % kUnitRows;
+            const int sb = pb.S[col];
             // four records at a time: their loads (B's vector and mask, C) are issued together, then the
             // additions follow in record order; a row met earlier in the batch hands its sum on in registers
             for (int i0 = 0; i0 < n; i0 += 4) {
@@ -1397,13 +1409,14 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
                     if (last) C[(size_t)row[u] * ldc + col] = c[u];
                 }
             }
+          }
         });
     }
     if (do_b) {
         // 2. the rows of this block, one per lane of the first half-wave: C[row][col0] += a0(row, k) * b
         const int row = rb * kUnitRows + (tid & 31);
         const int sa = pa.S[rb * kUnitRows + (tid & 31)];
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < nub; ++u) {
             const int ub = ub0 + u;
             if (ub * kUnitRows >= N) break;                  // workgroup-uniform
             walk(Bw, pb, (size_t)ub, pb.S + ub * kUnitRows, 0u, false, [&](int n) {
@@ -1424,9 +1437,9 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
 
 __global__ __launch_bounds__(256) void planes_tail_kernel(const u32x4 *__restrict__ Aw, const u32x4 *__restrict__ Bw, Planes pa,
                                                           Planes pb, float *__restrict__ C, int64_t ldc, int M, int N, int kblocks,
-                                                          int col_chunks)
+                                                          int col_chunks, int tail_cols)
 {
-    planes_tail_body(Aw, Bw, pa, pb, C, ldc, M, N, kblocks, col_chunks, blockIdx.x);
+    planes_tail_body(Aw, Bw, pa, pb, C, ldc, M, N, kblocks, col_chunks, tail_cols, blockIdx.x);
 }
 
 // The tails of a group of products in one launch: blocks [first, next first) belong to product g.
@@ -1439,7 +1452,7 @@ struct TailGroupItem {
     Planes pa, pb;
 };
 struct TailGroup {
-    int count;
+    int count, tail_cols;
     TailGroupItem p[kMaxGroup];
 };
 
@@ -1449,7 +1462,20 @@ __global__ __launch_bounds__(256) void planes_tail_group_kernel(TailGroup grp)
     for (int i = 1; i < grp.count; ++i)
         if (blockIdx.x >= grp.p[i].first) g = i;         // the same in the whole workgroup
     const TailGroupItem &it = grp.p[g];
-    planes_tail_body(it.Aw, it.Bw, it.pa, it.pb, it.C, it.ldc, it.M, it.N, it.kblocks, it.col_chunks, blockIdx.x - it.first);
+    planes_tail_body(it.Aw, it.Bw, it.pa, it.pb, it.C, it.ldc, it.M, it.N, it.kblocks, it.col_chunks, grp.tail_cols,
+                     blockIdx.x - it.first);
+}
+
+// Columns per tail block for a launch whose blocks would number `blocks256` at 256 columns each: the widest
+// of 1024, 512, 256 that still leaves four blocks per resident slot (three workgroups per compute unit).
+static int tail_cols_for(uint64_t blocks256, int cus)
+{
+    if (const char *env = getenv("FMT_GEMM_TAIL_COLS")) {        // tuning override
+        const int t = atoi(env);
+        if (t == 256 || t == 512 || t == 1024) return t;
+    }
+    const uint64_t want = (uint64_t)cus * 12;
+    return blocks256 / 4 >= want ? 1024 : blocks256 / 2 >= want ? 512 : 256;
 }
 
 // C[r][c] = sum over the k parts of part[s][r][c]  (parts are dense M x N slabs)
@@ -1601,13 +1627,18 @@ static int launch_product(const u32x4 *Aw, const u32x4 *Bw, float *C, int M, int
         return FMT_OK;
     }
     // the elements outside plane 0 of exponent-plane operands follow the product (plain row-major results only)
-    auto tail = [&]() {
+    auto tail = [&]() -> int {
         if (PS != 0 || pa.S == nullptr) return FMT_OK;
         if (img != 0) return FMT_ERR_SHAPE;
-        const int64_t col_chunks = (N + 255) / 256, blocks = (int64_t)((M + kUnitRows - 1) / kUnitRows) * col_chunks;
+        int cus = 0;
+        const int rcc = device_cu_count(&cus);
+        if (rcc != FMT_OK) return rcc;
+        const int64_t rbs = (M + kUnitRows - 1) / kUnitRows;
+        const int tc = tail_cols_for((uint64_t)rbs * ((N + 255) / 256), cus);
+        const int64_t col_chunks = (N + tc - 1) / tc, blocks = rbs * col_chunks;
         if (blocks >= ((int64_t)1 << 31)) return FMT_ERR_SHAPE;
         hipLaunchKernelGGL(planes_tail_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, Aw, Bw, pa, pb, C, ldc, M, N, kblocks,
-                           (int)col_chunks);
+                           (int)col_chunks, tc);
         FMT_HIP_CHECK(hipGetLastError());
         return FMT_OK;
     };
@@ -2204,7 +2235,12 @@ int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fm
         Group grp{};
         TailGroup tg{};
         grp.count = tg.count = n;
-        uint64_t ids = 0, blocks = 0;
+        uint64_t ids = 0, blocks = 0, blocks256 = 0;
+        for (int j = 0; j < n; ++j) {
+            const BatchItem &it = items[grouped[g0 + j]];
+            blocks256 += (uint64_t)((it.M + kUnitRows - 1) / kUnitRows) * (uint64_t)((it.N + 255) / 256);
+        }
+        tg.tail_cols = tail_cols_for(blocks256, cus);
         for (int j = 0; j < n; ++j) {
             const BatchItem &it = items[grouped[g0 + j]];
             OperandLayout la, lb;
@@ -2223,7 +2259,7 @@ int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fm
             ids += ((uint64_t)p.tiles_m * p.tiles_n + 7) / 8 * 8;
             TailGroupItem &t = tg.p[j];
             t.Aw = va.W; t.Bw = vb.W; t.C = it.C; t.ldc = it.ldc;
-            t.M = M; t.N = N; t.kblocks = la.kblocks; t.col_chunks = (N + 255) / 256;
+            t.M = M; t.N = N; t.kblocks = la.kblocks; t.col_chunks = (N + tg.tail_cols - 1) / tg.tail_cols;
             t.first = (unsigned)blocks;
             t.pa = va.pl; t.pb = vb.pl;
             blocks += (uint64_t)((M + kUnitRows - 1) / kUnitRows) * t.col_chunks;
