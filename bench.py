@@ -19,8 +19,10 @@ One "step" is one pass of the whole hot path over one batch of synthetic, paper-
                                      wgrad products (M=12544, N=256, K=2304 and permutations,
                                      14.8 GFLOP each)
 
-The calls inside the configuration 4 and configuration 3 sections are independent of each other and
-are issued round-robin on three side streams (--gemm-streams).  The stream section runs on one stream.
+The rounding passes inside the configuration 4 and configuration 3 sections are independent of each other
+and are issued round-robin on three side streams (--gemm-streams); the products of a section are handed to the
+library in one fmt_gemm_prepared_batch call (--no-batch: one fmt_gemm_prepared call per product on the side
+streams).  The stream section runs on one stream.
 
 `value` is the quantize+histogram HBM rate of the stream section (GB/s, algorithmic bytes over
 the section's event-timed duration); the GEMM section's useful TFLOP/s and its MFMA fraction are
