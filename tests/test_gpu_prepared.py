@@ -265,3 +265,58 @@ def test_prepare_pair_equals_two_prepares(fmt, f):
     assert torch.equal(C0.view(torch.int32), D0.view(torch.int32)) and torch.equal(C1.view(torch.int32), D1.view(torch.int32))
     ref = oracle.gemm(np.ascontiguousarray(base[:, :cols]), B.cpu().numpy(), f[0], f[1], f[2], transB=True)
     assert rel_err(C0.cpu().numpy(), ref) <= TOL
+
+
+@pytest.mark.parametrize("cols", ["256", "512", "1024"])
+def test_tail_blocks_of_every_width(fmt, cols, monkeypatch):
+    """The kernel that adds the products of the elements outside plane 0 owns blocks of 32 rows x 256, 512 or
+    1024 columns of C (the library picks the width per launch; the variable forces it).  N = 2100 gives several
+    blocks per row and a ragged last one at every width; both operands hold elements of all three planes, at
+    equal and at different k.  Integers times powers of two: exact in any order, bit for bit."""
+    monkeypatch.setenv("FMT_GEMM_TAIL_COLS", cols)
+    f = (6, 9, True)
+    rng = np.random.default_rng(int(cols))
+    M, N, K = 70, 2100, 160
+    ea = np.zeros((M, K), np.int64)
+    eb = np.zeros((N, K), np.int64)
+    for e, n in ((ea, M), (eb, N)):
+        hit = rng.random((n, K)) < 0.03
+        e[hit] = rng.choice([-38, -36, 18, 20], size=int(hit.sum()))
+    ea[:, 3], eb[:, 3] = 20, -38
+    ea[:, 4], eb[:, 4] = -38, -38
+    a = (rng.integers(1, 4, (M, K)) * rng.choice([-1, 1], (M, K)) * np.exp2(ea.astype(np.float64))).astype(np.float32)
+    b = (rng.integers(1, 4, (N, K)) * rng.choice([-1, 1], (N, K)) * np.exp2(eb.astype(np.float64))).astype(np.float32)
+    got, ref = product(fmt, a, b, f), want(a, b, f)
+    assert rel_err(got, ref) <= TOL
+    # columns of k that hold one plane pair each: single products, exact
+    for ks in ([3], [4], [9]):
+        a1 = np.zeros_like(a)
+        b1 = np.zeros_like(b)
+        a1[:, ks], b1[:, ks] = a[:, ks], b[:, ks]
+        got1, ref1 = product(fmt, a1, b1, f), want(a1, b1, f)
+        assert np.array_equal(got1.view(np.uint32), ref1.view(np.uint32)), ks
+
+
+@pytest.mark.parametrize("plan", ["4,4,1,1", "2,2,1,1", "1,1,1,1", "2,4,1,1", "2,2,3,1"])
+@pytest.mark.parametrize("f", [(6, 9, True), (5, 10, True), (6, 12, True)])
+def test_results_at_any_alignment(fmt, f, plan, monkeypatch):
+    """The product kernel stores 16 bytes per lane wherever four columns of a row are in range; nothing may
+    depend on C being 16-byte aligned.  C is a window of a larger tensor with an odd leading dimension and
+    every column offset 0..3 (addresses 4, 8 and 12 bytes off a 16-byte boundary); the rest of the tensor
+    must stay untouched.  Exact data, bit for bit."""
+    monkeypatch.setenv("FMT_GEMM_PLAN", plan)
+    rng = np.random.default_rng(7)
+    M, N, K = 300, 270, 96
+    a = rng.integers(-7, 8, (M, K)).astype(np.float32)
+    b = rng.integers(-7, 8, (N, K)).astype(np.float32)
+    A, B = fmt.fmt_prepare(dev(a), f), fmt.fmt_prepare(dev(b), f)
+    ref = want(a, b, f)
+    for off in range(4):
+        big = torch.full((M + 2, 277), -5.0, device="cuda")
+        out = big[1:M + 1, off:off + N]
+        fmt.fmt_gemm_prepared(A, B, out=out)
+        torch.cuda.synchronize()
+        h = big.cpu().numpy()
+        assert np.array_equal(h[1:M + 1, off:off + N], ref), off
+        h[1:M + 1, off:off + N] = -5.0
+        assert np.all(h == -5.0), off
