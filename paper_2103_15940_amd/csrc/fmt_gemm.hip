@@ -1180,9 +1180,10 @@ __global__ __launch_bounds__(256) void product_kernel(const u32x4 *__restrict__ 
 constexpr int kMaxGroup = 16;
 struct GroupItem {
     const u32x4 *Aw, *Bw;
-    float *C;
+    float *C;               // the result, or (k in parts) the first of the parts' dense M x N slabs (then ldc = N)
     int64_t ldc;
     int M, N, kblocks, tiles_m, tiles_n;
+    int kb_per_part;        // k blocks per part (= kblocks: one part); the product's run of ids holds one run of tiles per part
     unsigned first;
     Planes pa, pb;
 };
@@ -1198,9 +1199,9 @@ __global__ __launch_bounds__(256) void product_group_kernel(Group grp)
     for (int i = 1; i < grp.count; ++i)
         if (blockIdx.x >= grp.p[i].first) g = i;         // the same in the whole workgroup
     const GroupItem &it = grp.p[g];
-    product_body<PS, TM, TN, KS, NST, false, SCHED, SCALED, false>(it.Aw, it.Bw, it.C, it.M, it.N, it.ldc, 0, it.kblocks, it.tiles_m,
-                                                                 it.tiles_n, it.kblocks, it.pa, it.pb, Implicit{},
-                                                                 blockIdx.x - it.first);
+    product_body<PS, TM, TN, KS, NST, true, SCHED, SCALED, false>(it.Aw, it.Bw, it.C, it.M, it.N, it.ldc, 0, it.kblocks, it.tiles_m,
+                                                                it.tiles_n, it.kb_per_part, it.pa, it.pb, Implicit{},
+                                                                blockIdx.x - it.first);
 }
 
 // Half h (0..7) of a 16-byte vector of eight 16-bit patterns, as a float (binary16 -> fp32 is exact).
@@ -2178,71 +2179,119 @@ static int launch_group(const Group &grp, unsigned grid, int t, hipStream_t stre
 // id order, longest tiles first, so the launch takes about as long as the larger of: all tile time spread
 // over all slots; for each product, the rounds that the tiles up to and including its own need, times its
 // tile time.  The shape with the smaller estimate is taken.
-static int group_tile(const BatchItem *items, const std::vector<int> &grouped, size_t g0, int n, int cus, int pieces)
+struct GroupEntry {
+    int item;            // index into the batch
+    int nparts;          // k parts (1: the product writes its result itself)
+    int kb_per_part;     // k blocks per part
+    size_t part_off;     // bytes from the start of the scratch to this product's slabs
+};
+
+// time estimate (us) of a shared launch of entries [g0, g0 + n) with workgroup tiles of 64 t x 64 t
+static double group_estimate(const BatchItem *items, const std::vector<GroupEntry> &e, size_t g0, int n, int cus, int pieces, int t)
+{
+    const double fixed = t == 4 ? 9.5 : 9.8, per_kb = (t == 4 ? 0.89 : 0.47) * pieces * pieces;
+    const double slots = (double)cus * (t == 4 ? 1 : 2);
+    double work = 0.0, tiles = 0.0, rounds_bound = 0.0;
+    for (int j = 0; j < n; ++j) {                            // longest parts first
+        const BatchItem &it = items[e[g0 + j].item];
+        const double tile_time = fixed + per_kb * e[g0 + j].kb_per_part;
+        const double nt = (double)((it.M + 64 * t - 1) / (64 * t)) * (double)((it.N + 64 * t - 1) / (64 * t)) * e[g0 + j].nparts;
+        tiles += nt;
+        work += nt * tile_time;
+        rounds_bound = std::max(rounds_bound, std::ceil(tiles / slots) * tile_time);
+    }
+    return std::max(work / slots, rounds_bound);
+}
+
+static int group_tile(const BatchItem *items, const std::vector<GroupEntry> &e, size_t g0, int n, int cus, int pieces)
 {
     if (const char *env = getenv("FMT_GEMM_GROUP_TILE")) {      // tuning override: "2" or "4"
         const int t = atoi(env);
         if (t == 2 || (t == 4 && lds_bytes(4, 4, pieces, pipe_ks(pieces), 2) <= 160 * 1024)) return t;
     }
     if (lds_bytes(4, 4, pieces, pipe_ks(pieces), 2) > 160 * 1024) return 2;
-    auto estimate = [&](int t) {
-        const double fixed = t == 4 ? 9.5 : 9.8, per_kb = (t == 4 ? 0.89 : 0.47) * pieces * pieces;
-        const double slots = (double)cus * (t == 4 ? 1 : 2);
-        double work = 0.0, tiles = 0.0, rounds_bound = 0.0;
-        for (int j = 0; j < n; ++j) {                            // longest k first
-            const BatchItem &it = items[grouped[g0 + j]];
-            const double tile_time = fixed + per_kb * (double)((it.K + kUnitK - 1) / kUnitK);
-            const double nt = (double)((it.M + 64 * t - 1) / (64 * t)) * (double)((it.N + 64 * t - 1) / (64 * t));
-            tiles += nt;
-            work += nt * tile_time;
-            rounds_bound = std::max(rounds_bound, std::ceil(tiles / slots) * tile_time);
-        }
-        return std::max(work / slots, rounds_bound);
-    };
-    return estimate(4) < estimate(2) ? 4 : 2;
+    return group_estimate(items, e, g0, n, cus, pieces, 4) < group_estimate(items, e, g0, n, cus, pieces, 2) ? 4 : 2;
 }
 
 // Several products on prepared operands (all of one format and scheme).  A product joins a shared launch when
 // it needs no split over k: its own plan has none, or one of its tiles is no longer than the work the whole
 // batch leaves to each compute unit (then the other products fill the machine while its few long tiles run).
-// Shared launches hold up to kMaxGroup products, longest k first (their tiles take longest and workgroups start
-// in id order); the other products run one by one as launch_gemm_prepared runs them.
+// A product that does need its k in parts (few tiles, long k) joins with its parts -- each part a run of tiles
+// of its own that writes a slab of partial sums, summed by reduce_kernel after the launch -- when a part's
+// tile takes no longer than the launch is estimated to take without it.  Shared launches hold up to kMaxGroup
+// products, longest parts first (their tiles take longest and workgroups start in id order); what is left
+// runs one by one as launch_gemm_prepared runs it.
 int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fmt_format_t f, hipStream_t stream)
 {
     const Scheme sch{scheme & 15, (scheme & 16) != 0};
+    const int pieces = pieces_of(sch.ps);
     int cus = 0;
     int rc = device_cu_count(&cus);
     if (rc != FMT_OK) return rc;
-    std::vector<int> grouped, alone;
+    std::vector<GroupEntry> grouped;
+    std::vector<int> alone, parted;
+    std::vector<Plan> plans((size_t)count);
     double load = 0.0;                                   // 256 x 256 x 32 blocks of multiplications per compute unit
     for (int i = 0; i < count; ++i)
         load += (double)((items[i].M + 255) / 256) * (double)((items[i].N + 255) / 256) * (double)((items[i].K + kUnitK - 1) / kUnitK);
     load /= cus;
     for (int i = 0; i < count; ++i) {
         const int kblocks = (int)((items[i].K + kUnitK - 1) / kUnitK);
-        const Plan plan = make_plan((int)items[i].M, (int)items[i].N, kblocks, cus, pieces_of(sch.ps));
-        (plan.nsplit == 1 || kblocks <= load ? grouped : alone).push_back(i);
+        plans[(size_t)i] = make_plan((int)items[i].M, (int)items[i].N, kblocks, cus, pieces);
+        if (plans[(size_t)i].nsplit == 1 || kblocks <= load) grouped.push_back(GroupEntry{i, 1, kblocks, 0});
+        else parted.push_back(i);
     }
-    if (grouped.size() == 1) {
-        alone.push_back(grouped[0]);
+    size_t part_bytes = 0;
+    if (!grouped.empty() && !parted.empty()) {
+        const int n0 = (int)std::min<size_t>(kMaxGroup, grouped.size());
+        const int t0 = group_tile(items, grouped, 0, n0, cus, pieces);
+        const double base = group_estimate(items, grouped, 0, n0, cus, pieces, t0);
+        const double fixed = t0 == 4 ? 9.5 : 9.8, per_kb = (t0 == 4 ? 0.89 : 0.47) * pieces * pieces;
+        for (int i : parted) {
+            const int kblocks = (int)((items[i].K + kUnitK - 1) / kUnitK);
+            const int ns = plans[(size_t)i].nsplit, kb_per = (kblocks + ns - 1) / ns;
+            if (fixed + per_kb * kb_per <= base) {
+                grouped.push_back(GroupEntry{i, ns, kb_per, part_bytes});
+                part_bytes += ((size_t)ns * items[i].M * items[i].N * sizeof(float) + 255) / 256 * 256;
+            } else {
+                alone.push_back(i);
+            }
+        }
+    } else {
+        alone = parted;
+    }
+    if (grouped.size() == 1 && grouped[0].nparts == 1) {
+        alone.push_back(grouped[0].item);
         grouped.clear();
     }
-    std::stable_sort(grouped.begin(), grouped.end(), [&](int a, int b) { return items[a].K > items[b].K; });
+    // the scratch for every slab of partial sums of the call, before anything is launched (growing it waits for the device)
+    size_t need = part_bytes;
+    for (int i : alone) need = std::max(need, part_bytes_of(plans[(size_t)i], (int)items[i].M, (int)items[i].N));
+    char *scratch = nullptr;
+    if (need > 0) {
+        Scratch sc;
+        rc = get_scratch(stream, 0, need, &sc);
+        if (rc != FMT_OK) return rc;
+        scratch = static_cast<char *>(sc.gemm_ws);
+    }
+    std::stable_sort(grouped.begin(), grouped.end(),
+                     [&](const GroupEntry &a, const GroupEntry &b) { return a.kb_per_part > b.kb_per_part; });
 
     for (size_t g0 = 0; g0 < grouped.size(); g0 += kMaxGroup) {
         const int n = (int)std::min<size_t>(kMaxGroup, grouped.size() - g0);
-        const int gt = group_tile(items, grouped, g0, n, cus, pieces_of(sch.ps));
+        const int gt = group_tile(items, grouped, g0, n, cus, pieces);
         Group grp{};
         TailGroup tg{};
         grp.count = tg.count = n;
         uint64_t ids = 0, blocks = 0, blocks256 = 0;
         for (int j = 0; j < n; ++j) {
-            const BatchItem &it = items[grouped[g0 + j]];
+            const BatchItem &it = items[grouped[g0 + j].item];
             blocks256 += (uint64_t)((it.M + kUnitRows - 1) / kUnitRows) * (uint64_t)((it.N + 255) / 256);
         }
         tg.tail_cols = tail_cols_for(blocks256, cus);
         for (int j = 0; j < n; ++j) {
-            const BatchItem &it = items[grouped[g0 + j]];
+            const GroupEntry &ge = grouped[g0 + j];
+            const BatchItem &it = items[ge.item];
             OperandLayout la, lb;
             rc = operand_layout(it.M, it.K, sch, f.m, &la);
             if (rc != FMT_OK) return rc;
@@ -2251,12 +2300,14 @@ int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fm
             const OperandView va = view_of(const_cast<void *>(it.A), la), vb = view_of(const_cast<void *>(it.B), lb);
             const int M = (int)it.M, N = (int)it.N;
             GroupItem &p = grp.p[j];
-            p.Aw = va.W; p.Bw = vb.W; p.C = it.C; p.ldc = it.ldc;
-            p.M = M; p.N = N; p.kblocks = la.kblocks;
+            p.Aw = va.W; p.Bw = vb.W;
+            p.C = ge.nparts > 1 ? reinterpret_cast<float *>(scratch + ge.part_off) : it.C;
+            p.ldc = ge.nparts > 1 ? (int64_t)N : it.ldc;
+            p.M = M; p.N = N; p.kblocks = la.kblocks; p.kb_per_part = ge.kb_per_part;
             p.tiles_m = (M + 64 * gt - 1) / (64 * gt); p.tiles_n = (N + 64 * gt - 1) / (64 * gt);
             p.first = (unsigned)ids;
             p.pa = va.pl; p.pb = vb.pl;
-            ids += ((uint64_t)p.tiles_m * p.tiles_n + 7) / 8 * 8;
+            ids += ((uint64_t)p.tiles_m * p.tiles_n + 7) / 8 * 8 * (uint64_t)ge.nparts;
             TailGroupItem &t = tg.p[j];
             t.Aw = va.W; t.Bw = vb.W; t.C = it.C; t.ldc = it.ldc;
             t.M = M; t.N = N; t.kblocks = la.kblocks; t.col_chunks = (N + tg.tail_cols - 1) / tg.tail_cols;
@@ -2272,6 +2323,16 @@ int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fm
             default: rc = launch_group<3, false>(grp, (unsigned)ids, gt, stream); break;
         }
         if (rc != FMT_OK) return rc;
+        for (int j = 0; j < n; ++j) {                        // the sums of the parts, in part order
+            const GroupEntry &ge = grouped[g0 + j];
+            if (ge.nparts == 1) continue;
+            const BatchItem &it = items[ge.item];
+            const size_t total = (size_t)it.M * it.N;
+            const unsigned rgrid = (unsigned)((total + 1023) / 1024 < 4096 ? (total + 1023) / 1024 : 4096);
+            hipLaunchKernelGGL(reduce_kernel, dim3(rgrid ? rgrid : 1), dim3(256), 0, stream,
+                               reinterpret_cast<const float *>(scratch + ge.part_off), ge.nparts, it.C, (int)it.M, (int)it.N, it.ldc, 0);
+            FMT_HIP_CHECK(hipGetLastError());
+        }
         if (sch.scaled) {
             hipLaunchKernelGGL(planes_tail_group_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, tg);
             FMT_HIP_CHECK(hipGetLastError());

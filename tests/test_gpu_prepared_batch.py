@@ -217,3 +217,60 @@ def test_config4_layer_twelve_products_one_call_sampled(fmt):
         got = c.cpu().numpy()[ii[sel], jj[sel]].astype(np.float64)
         scale = np.sqrt(np.sum(qa * qa, axis=1) * np.sum(qb * qb, axis=1))
         assert np.all(np.abs(got - ref) <= 1e-5 * scale)
+
+
+@pytest.mark.parametrize("tile", [None, "2", "4"])
+@pytest.mark.parametrize("f", [(6, 9, True), (5, 10, True), (6, 12, True)])
+def test_member_with_k_in_parts(fmt, f, tile, monkeypatch):
+    """A product of few tiles and long k beside products that fill the machine: the library runs its k in parts
+    inside the shared launch (each part a run of tiles writing a slab of partial sums, summed in part order
+    afterwards), or alone -- either way exact data must come out bit for bit, also for a second such member and
+    for ragged shapes."""
+    if tile is not None:
+        monkeypatch.setenv("FMT_GEMM_GROUP_TILE", tile)
+    rng = np.random.default_rng(77 + f[1])
+    shapes = [(1024, 1024, 512)] * 8 + [(64, 64, 8192), (100, 70, 6000), (256, 256, 96)]
+    ab = []
+    for M, N, K in shapes:
+        a, b = exact_operands(rng, f, M, N, K)
+        a[:, 700:] = 0                                   # sums below 2^24 units whatever k
+        ab.append((a, b))
+    A = [fmt.fmt_prepare(dev(a), f) for a, _ in ab]
+    B = [fmt.fmt_prepare(dev(b), f) for _, b in ab]
+    out = fmt.fmt_gemm_prepared_batch(A, B)
+    torch.cuda.synchronize()
+    for (a, b), c, shape in zip(ab, out, shapes):
+        ref = oracle.gemm(a, b, f[0], f[1], f[2], transB=True)
+        assert np.array_equal(c.cpu().numpy().view(np.uint32), ref.view(np.uint32)), shape
+
+
+def test_config3_products_one_call_sampled(fmt):
+    """Configuration 3's three products (forward, dgrad, wgrad of the 3x3 convolution as im2col products:
+    12544 x 256 x 2304 and its permutations) in one call at full size, as the benchmark issues them; one sampled
+    element per 128 x 128 tile against the oracle's dot product."""
+    f = (6, 9, True)
+    M, N, K = 12544, 256, 2304
+    g = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.randn(M, K, device="cuda", generator=g)
+    w = torch.randn(N, K, device="cuda", generator=g) * 0.03
+    dy = torch.randn(M, N, device="cuda", generator=g) * 1e-3
+    X, Xt = fmt.fmt_prepare_pair(x, f)
+    W, Wt = fmt.fmt_prepare_pair(w, f)
+    D, Dt = fmt.fmt_prepare_pair(dy, f)
+    out = fmt.fmt_gemm_prepared_batch([X, D, Dt], [W, Wt, Xt])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(33)
+    for (a, b), c in zip([(x, w), (dy, w.t()), (dy.t(), x.t())], out):
+        m, n = c.shape
+        tm, tn = (m + 127) // 128, (n + 127) // 128
+        ii = np.minimum(np.arange(tm)[:, None] * 128 + rng.integers(0, 128, (tm, tn)), m - 1).ravel()
+        jj = np.minimum(np.arange(tn)[None, :] * 128 + rng.integers(0, 128, (tm, tn)), n - 1).ravel()
+        sel = rng.choice(ii.size, min(96, ii.size), replace=False)
+        ah = a[torch.from_numpy(ii[sel]).cuda()].cpu().numpy()
+        bh = b[torch.from_numpy(jj[sel]).cuda()].cpu().numpy()
+        qa = oracle.quantize(ah, f[0], f[1], f[2]).astype(np.float64)
+        qb = oracle.quantize(bh, f[0], f[1], f[2]).astype(np.float64)
+        ref = np.sum(qa * qb, axis=1)
+        got = c.cpu().numpy()[ii[sel], jj[sel]].astype(np.float64)
+        scale = np.sqrt(np.sum(qa * qa, axis=1) * np.sum(qb * qb, axis=1))
+        assert np.all(np.abs(got - ref) <= 1e-5 * scale)
