@@ -113,12 +113,18 @@ __device__ __forceinline__ size_t unit_vec_index(int rb, int kb, int kblocks, in
 //   mask   one byte per unit (32 rows x 32 k): bit 0 set always, bit 1 / bit 2 set when the unit has
 //          an element in the plane above / below; only then has that plane's unit been written
 //   plane  16-byte vectors from one plane's pieces to the next (planes 1 and 2 follow plane 0)
+//   recs   per row of units (32 rows x all k), the elements outside plane 0 as records (k << 5 | row in the unit,
+//          true value as fp32 bits), in no particular order, and rec_cnt how many there are; a row of units
+//          with more than kRecCap of them keeps only the count (its elements are then found through the masks)
 struct Planes {
     int *S;
     uint8_t *mask;
     size_t plane;
     int w;               // 40 - m: binades one plane holds
+    uint32_t *rec_cnt;
+    uint32_t *recs;      // pairs of words, kRecCap pairs per row of units
 };
+constexpr int kRecCap = 64;
 
 constexpr int kWinTmin = 0, kWinTmax = 31;              // range of plane 0's top binade T (S = 15 - T): with
                                                         // three planes every value of a 1/6/m format, m <= 9, fits
@@ -744,6 +750,13 @@ __device__ __forceinline__ void prepare_scaled_block(const PrepOperand &o, int K
             const _Float16 g = static_cast<_Float16>(ldexpf(rf, up ? S - w : S + w));
             hx[j] = (uint32_t)__builtin_bit_cast(uint16_t, g) | (up ? 0x10000u : 0x20000u);
             mine |= up ? 2u : 4u;
+            // and a record for the kernel that adds these elements' products
+            const uint32_t slot = atomicAdd(&o.pl.rec_cnt[row / kUnitRows], 1u);
+            if (slot < (uint32_t)kRecCap) {
+                uint32_t *rec = o.pl.recs + ((size_t)(row / kUnitRows) * kRecCap + slot) * 2;
+                rec[0] = ((uint32_t)(k0 + j) << 5) | (uint32_t)(row % kUnitRows);
+                rec[1] = r;
+            }
         }
     }
     __syncthreads();                             // s_planes has been cleared
@@ -1256,13 +1269,31 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
     const int ub0 = cc * (tail_cols / kUnitRows);    // first unit of B of this block
     const int nub = min(tail_cols / kUnitRows, (N + kRowPad - 1) / kRowPad * (kRowPad / kUnitRows) - ub0);   // B is padded to whole groups of 8 units
 
-    // this thread's mask byte of the row of units of A (k block tid); rows longer than 256 k blocks are re-read later
-    const uint32_t first_a = tid < kblocks ? (uint32_t)pa.mask[(size_t)rb * kblocks + tid] & 6u : 0u;
-    bool any_a = first_a != 0u, any_b = false;
-    for (int kb = 256 + tid; kb < kblocks; kb += 256) any_a |= (pa.mask[(size_t)rb * kblocks + kb] & 6u) != 0u;
-    for (int i = tid; i < nub * kblocks; i += 256) any_b |= (pb.mask[(size_t)ub0 * kblocks + i] & 6u) != 0u;
-    const bool do_a = __syncthreads_or((int)any_a) != 0, do_b = __syncthreads_or((int)any_b) != 0;
+    // how many elements outside plane 0 A's row of units and B's rows of units hold (counted by the prepare pass)
+    const uint32_t cnt_a = pa.rec_cnt[rb];
+    const bool do_a = cnt_a != 0u;
+    const bool do_b = __syncthreads_or(tid < nub && pb.rec_cnt[ub0 + tid] != 0u ? 1 : 0) != 0;
     if (!do_a && !do_b) return;
+
+    // The records of a row of units whose count fits its list: read, and put into the order (k, row) -- the
+    // prepare pass appends them in whatever order its workgroups run, and the additions below must not depend
+    // on that.  One barrier before (the record arrays are free), one after.
+    auto take_list = [&](const Planes &pl, size_t urow, int n) __attribute__((always_inline)) {
+        uint32_t key = 0u, val = 0u;
+        if (tid < n) {
+            key = pl.recs[(urow * kRecCap + tid) * 2];
+            val = pl.recs[(urow * kRecCap + tid) * 2 + 1];
+            s_list[tid] = key;
+        }
+        __syncthreads();
+        if (tid < n) {
+            int rank = 0;
+            for (int i = 0; i < n; ++i) rank += s_list[i] < key ? 1 : 0;
+            s_rec[rank] = key;
+            s_val[rank] = __uint_as_float(val);
+        }
+        __syncthreads();
+    };
 
     // Ordered compaction over the workgroup: thread t contributes `have` items; returns the index of its
     // first one and, in total, the number of items.  Two barriers.
@@ -1358,7 +1389,7 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
     if (do_a) {
         // 1. this block's columns of thread tid, one after the other: C[row][col] += a * b(k, col) for the
         //    records (row, k, a) in order
-        walk(Aw, pa, (size_t)rb, pa.S + rb * kUnitRows, first_a, true, [&](int n) {
+        auto apply_a = [&](int n) {
 #pragma unroll 1
           for (int j = 0; j < tail_cols / 256; ++j) {
             const int col = cc * tail_cols + j * 256 + tid;
@@ -1411,7 +1442,14 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
                 }
             }
           }
-        });
+        };
+        if (cnt_a <= (uint32_t)kRecCap) {
+            take_list(pa, (size_t)rb, (int)cnt_a);
+            apply_a((int)cnt_a);
+            __syncthreads();                                 // the records are free again
+        } else {
+            walk(Aw, pa, (size_t)rb, pa.S + rb * kUnitRows, 0u, false, apply_a);
+        }
     }
     if (do_b) {
         // 2. the rows of this block, one per lane of the first half-wave: C[row][col0] += a0(row, k) * b
@@ -1420,7 +1458,9 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
         for (int u = 0; u < nub; ++u) {
             const int ub = ub0 + u;
             if (ub * kUnitRows >= N) break;                  // workgroup-uniform
-            walk(Bw, pb, (size_t)ub, pb.S + ub * kUnitRows, 0u, false, [&](int n) {
+            const uint32_t cnt_b = pb.rec_cnt[ub];
+            if (cnt_b == 0u) continue;                       // workgroup-uniform
+            auto apply_b = [&](int n) {
                 if (tid >= 32 || row >= M) return;
                 for (int i = 0; i < n; ++i) {
                     const uint32_t rec = s_rec[i];
@@ -1431,7 +1471,14 @@ __device__ __forceinline__ void planes_tail_body(const u32x4 *__restrict__ Aw, c
                     float *dst = C + (size_t)row * ldc + col;
                     *dst = __fmaf_rn(a, s_val[i], *dst);
                 }
-            });
+            };
+            if (cnt_b <= (uint32_t)kRecCap) {
+                take_list(pb, (size_t)ub, (int)cnt_b);
+                apply_b((int)cnt_b);
+                __syncthreads();
+            } else {
+                walk(Bw, pb, (size_t)ub, pb.S + ub * kUnitRows, 0u, false, apply_b);
+            }
         }
     }
 }
@@ -1709,7 +1756,7 @@ struct OperandLayout {
     Scheme sch;
     int w;                       // planes: binades per plane
     int rows, kblocks, units;
-    size_t plane_vec, s_off, mask_off, bytes;
+    size_t plane_vec, s_off, mask_off, cnt_off, rec_off, bytes;
 };
 
 static int operand_layout(int64_t rows, int64_t K, Scheme sch, int m, OperandLayout *L)
@@ -1726,7 +1773,9 @@ static int operand_layout(int64_t rows, int64_t K, Scheme sch, int m, OperandLay
     const size_t piece_bytes = up256(L->plane_vec * sizeof(u32x4) * (sch.scaled ? 3 : 1));
     L->s_off = piece_bytes;
     L->mask_off = L->s_off + (sch.scaled ? up256((size_t)L->units * kUnitRows * sizeof(int)) : 0);
-    L->bytes = L->mask_off + (sch.scaled ? up256((size_t)L->units * L->kblocks) : 0);
+    L->cnt_off = L->mask_off + (sch.scaled ? up256((size_t)L->units * L->kblocks) : 0);
+    L->rec_off = L->cnt_off + (sch.scaled ? up256((size_t)L->units * sizeof(uint32_t)) : 0);
+    L->bytes = L->rec_off + (sch.scaled ? up256((size_t)L->units * kRecCap * 2 * sizeof(uint32_t)) : 0);
     return FMT_OK;
 }
 
@@ -1741,11 +1790,13 @@ static OperandView view_of(void *base, const OperandLayout &L)
     char *b = static_cast<char *>(base);
     OperandView v;
     v.W = reinterpret_cast<u32x4 *>(b);
-    v.pl = Planes{nullptr, nullptr, 0, L.w};
+    v.pl = Planes{nullptr, nullptr, 0, L.w, nullptr, nullptr};
     if (L.sch.scaled) {
         v.pl.S = reinterpret_cast<int *>(b + L.s_off);
         v.pl.mask = reinterpret_cast<uint8_t *>(b + L.mask_off);
         v.pl.plane = L.plane_vec;
+        v.pl.rec_cnt = reinterpret_cast<uint32_t *>(b + L.cnt_off);
+        v.pl.recs = reinterpret_cast<uint32_t *>(b + L.rec_off);
     }
     return v;
 }
@@ -1759,6 +1810,7 @@ struct StatOperand {
     int rows_pad;
     int kcontig;
     int *S;
+    uint32_t *rec_cnt;       // record counts of the operand's rows of units: cleared here, filled by the prepare pass
     unsigned nblocks;
 };
 
@@ -1839,6 +1891,7 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
     }
     T = max(kWinTmin, min(kWinTmax, T));
     o.S[row] = 15 - T;
+    if (row % kUnitRows == 0) o.rec_cnt[row / kUnitRows] = 0u;
 }
 
 // ---- operand preparation ------------------------------------------------------------------------
@@ -1895,6 +1948,7 @@ static int prepare_operands(const OperandSpec &sa, const OperandLayout &la, cons
                 t.rows_pad = L.units * kUnitRows;
                 t.kcontig = o.kcontig;
                 t.S = o.pl.S;
+                t.rec_cnt = o.pl.rec_cnt;
                 t.nblocks = present ? (unsigned)L.units : 0u;
                 return t;
             };
@@ -2093,6 +2147,7 @@ static int prepare_pair_planes(const float *X, int64_t ld, const OperandLayout &
         t.rows_pad = L.units * kUnitRows;
         t.kcontig = o.kcontig;
         t.S = o.pl.S;
+        t.rec_cnt = o.pl.rec_cnt;
         t.nblocks = (unsigned)L.units;
         return t;
     };
