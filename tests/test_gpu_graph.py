@@ -168,3 +168,57 @@ def test_growing_scratch_under_capture_is_refused(fmt):
     torch.cuda.synchronize()
     ref = big[0].half().float().double() @ big[1].half().float().double()
     assert torch.linalg.norm(Cb.double() - ref) / torch.linalg.norm(ref) < 1e-5
+
+
+def test_prepare_and_batch_replays_match_eager(fmt):
+    """fmt_prepare_pair and fmt_gemm_prepared_batch in a graph: the shared product launch (with a member whose k
+    runs in parts through library scratch), the sum of its parts and the shared tail launch, replayed three
+    times on new tensor contents, bit for bit what the eager calls give."""
+    dev = torch.device("cuda")
+    f = (6, 9, True)
+    shapes = [(1024, 1024, 512)] * 6 + [(64, 96, 6144), (200, 130, 96)]
+    X = [torch.empty((M, K), device=dev) for M, N, K in shapes]
+    W = [torch.empty((N, K), device=dev) for M, N, K in shapes]
+    C = [torch.empty((M, N), device=dev) for M, N, K in shapes]
+    bufs = [(torch.empty(fmt.fmt_operand_bytes(M, K, f), dtype=torch.uint8, device=dev),
+             torch.empty(fmt.fmt_operand_bytes(K, M, f), dtype=torch.uint8, device=dev),
+             torch.empty(fmt.fmt_operand_bytes(N, K, f), dtype=torch.uint8, device=dev),
+             torch.empty(fmt.fmt_operand_bytes(K, N, f), dtype=torch.uint8, device=dev)) for M, N, K in shapes]
+
+    def fill(seed):
+        r = np.random.default_rng(seed)
+        for x, w in zip(X, W):
+            x.copy_(torch.from_numpy(workloads.log2_normal(tuple(x.shape), -20, 6, 0.01, r)))
+            w.copy_(torch.from_numpy((r.standard_normal(tuple(w.shape)) * 0.02).astype(np.float32)))
+
+    def calls():
+        A, B = [], []
+        for x, w, b in zip(X, W, bufs):
+            A.append(fmt.fmt_prepare_pair(x, f, out=b[0], out_t=b[1])[0])
+            B.append(fmt.fmt_prepare_pair(w, f, out=b[2], out_t=b[3])[0])
+        fmt.fmt_gemm_prepared_batch(A, B, out=C)
+
+    fill(0)
+    calls()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        calls()                                    # eager warm-up on the capture stream: its scratch holds the slabs
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            calls()
+    torch.cuda.current_stream().wait_stream(side)
+    for seed in (1, 2, 3):
+        fill(seed)
+        calls()
+        torch.cuda.synchronize()
+        want = [c.clone() for c in C]
+        for c in C:
+            c.zero_()
+        (X[0] @ W[0].t()).sum().item()             # unrelated eager work and a synchronisation between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (g, w) in enumerate(zip(C, want)):
+            assert torch.equal(g.view(torch.int32), w.view(torch.int32)), (seed, shapes[i])
