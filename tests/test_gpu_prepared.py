@@ -320,3 +320,40 @@ def test_results_at_any_alignment(fmt, f, plan, monkeypatch):
         assert np.array_equal(h[1:M + 1, off:off + N], ref), off
         h[1:M + 1, off:off + N] = -5.0
         assert np.all(h == -5.0), off
+
+
+@pytest.mark.parametrize("count", [1, 2, 63, 64, 65, 200])
+def test_record_lists_at_their_capacity(fmt, count):
+    """A prepared plane operand lists up to 64 elements outside plane 0 per 32 rows; a row block with more has
+    only its count and is walked through its mask bytes instead.  `count` such elements in ONE block of 32 rows
+    of A (and as many in one block of rows of B), at distinct (row, k), some sharing a row, some sharing a k
+    with an element of the other operand; every other block has none.  Integers times powers of two: every
+    partial sum is exact, so the result must equal the oracle's bit for bit on either path."""
+    f = (6, 9, True)
+    rng = np.random.default_rng(1000 + count)
+    M, N, K = 96, 300, 224
+    a = rng.integers(-3, 4, (M, K)).astype(np.float32)
+    b = rng.integers(-3, 4, (N, K)).astype(np.float32)
+    pos_a = rng.choice(32 * K, count, replace=False)
+    pos_b = rng.choice(32 * K, count, replace=False)
+    for p in pos_a:                                         # rows 32..63 of A: the plane above and the plane below
+        a[32 + p // K, p % K] = float(rng.choice([-3, -1, 1, 2])) * 2.0 ** float(rng.choice([18, 19, -36, -37]))
+    for p in pos_b:                                         # rows 64..95 of B
+        b[64 + p // K, p % K] = float(rng.choice([-3, -1, 1, 2])) * 2.0 ** float(rng.choice([18, 19, -36, -37]))
+    if count >= 2:                                          # an element of A and one of B at the same k
+        a[33, 7] = 2.0 ** 19
+        b[65, 7] = -(2.0 ** -36)
+    got, ref = product(fmt, a, b, f), want(a, b, f)
+    assert rel_err(got, ref) <= TOL
+    # rows and columns whose sums stay exact: one scale per sum (no mixing of 2^18 and 2^-36 terms in one element)
+    clean_rows = np.setdiff1d(np.arange(M), np.arange(32, 64))
+    clean_cols = np.setdiff1d(np.arange(N), np.arange(64, 96))
+    assert np.array_equal(got[np.ix_(clean_rows, clean_cols)].view(np.uint32), ref[np.ix_(clean_rows, clean_cols)].view(np.uint32))
+    # and one element at a time, exactly, through both paths
+    for (r, k) in [(32 + pos_a[0] // K, pos_a[0] % K)]:
+        a1 = np.zeros_like(a)
+        a1[r, k] = a[r, k]
+        got1, ref1 = product(fmt, a1, b, f), want(a1, b, f)
+        keep = np.ones(N, bool)
+        keep[64:96] = np.abs(b[64:96, k]) < 8                # products of two elements outside plane 0 included where exact
+        assert np.array_equal(got1[:, keep].view(np.uint32), ref1[:, keep].view(np.uint32))
