@@ -27,16 +27,20 @@
 // MFMA product per multiply).  A value that does not fit there -- too large, or with bits below
 // binary16's last denormal bit -- fits exactly under the scale 2^(S-w) (plane "above") or 2^(S+w)
 // (plane "below"), w = 40 - m binades being what one plane holds; three planes cover the whole range
-// of the format whatever S is.  A per-(32 rows x 32 k) mask says which planes hold anything; a small
-// kernel after the product kernel adds the products of the few elements outside plane 0, one fp32
-// fused multiply-add each, in a fixed order.  Exact products, fp32 accumulation, no lists to
-// overflow, no fallback: the result is reproducible bit for bit.
+// of the format whatever S is.  A per-(32 rows x 32 k) mask says which planes hold anything, and every 32
+// rows carry a short list of their elements outside plane 0 (with a count that says when the list did
+// not hold them all: then the masks lead to them); a small kernel after the product kernel adds the
+// products of those few elements, one fp32 fused multiply-add each, in a fixed order.  Exact products,
+// fp32 accumulation, nothing that can overflow into a wrong result, no fallback product: the result is
+// reproducible bit for bit.
+//
+// Several products on prepared operands can share launches (launch_gemm_prepared_batch): the product and the
+// tail kernel exist in a form that takes a table of products and finds a workgroup's product from its id.
+#include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
-
-#include <algorithm>
-#include <cmath>
 #include <vector>
 
 #include "fmt_internal.h"
