@@ -299,3 +299,22 @@ def test_scratch_of_forward_and_dgrad_is_of_the_size_of_the_tensor(fmt):
     torch.cuda.synchronize()
     assert fmt.fmt_scratch_bytes()["products"] >= patch_operand
     fmt.fmt_release_scratch()
+
+
+def test_config3_full_size_every_element(fmt):
+    """Config 3 at full size, 1/6/9/d: every element of forward, dgrad and wgrad against the oracle's full
+    convolutions (3 x 14.8 GFLOP on the host's cores), within the 1e-5 relative Frobenius bound."""
+    f = (6, 9, True)
+    cfg = workloads.config3()
+    X, W2, dY2 = cfg["X"], cfg["W"], cfg["dY"]
+    n, c, h, w = X.shape
+    k = W2.shape[0]
+    W = W2.reshape(k, c, 3, 3)
+    dY = np.ascontiguousarray(dY2.reshape(n, h, w, k).transpose(0, 3, 1, 2))
+    Y, dX, dW = run_all(fmt, X, W, dY, f, (1, 1), (1, 1))
+    e, m, d = f
+    for name, got, ref in (("Y", Y, oracle.conv2d_fwd(X, W, e, m, d)),
+                           ("dX", dX, oracle.conv2d_dgrad(dY, W, X.shape, e, m, d)),
+                           ("dW", dW, oracle.conv2d_wgrad(dY, X, W.shape, e, m, d))):
+        assert got.shape == ref.shape and np.all(np.isfinite(got)), name
+        assert rel_err(got, ref) <= TOL, "%s: %.3g" % (name, rel_err(got, ref))
