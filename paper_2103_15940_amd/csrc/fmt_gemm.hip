@@ -1206,16 +1206,23 @@ struct GroupItem {
 };
 struct Group {
     int count;
+    unsigned first[kMaxGroup];     // p[i].first again, side by side (one scalar load), 0xFFFFFFFF beyond count
     GroupItem p[kMaxGroup];
 };
+
+// Which product a workgroup id belongs to: the number of runs that start at or before it, minus one.
+__device__ __forceinline__ int group_member(const unsigned (&first)[kMaxGroup], unsigned id)
+{
+    int g = -1;
+#pragma unroll
+    for (int i = 0; i < kMaxGroup; ++i) g += id >= first[i] ? 1 : 0;
+    return g;
+}
 
 template <int PS, int TM, int TN, int KS, int NST, bool SCHED, bool SCALED>
 __global__ __launch_bounds__(256) void product_group_kernel(Group grp)
 {
-    int g = 0;
-    for (int i = 1; i < grp.count; ++i)
-        if (blockIdx.x >= grp.p[i].first) g = i;         // the same in the whole workgroup
-    const GroupItem &it = grp.p[g];
+    const GroupItem &it = grp.p[group_member(grp.first, blockIdx.x)];      // the same in the whole workgroup
     product_body<PS, TM, TN, KS, NST, true, SCHED, SCALED, false>(it.Aw, it.Bw, it.C, it.M, it.N, it.ldc, 0, it.kblocks, it.tiles_m,
                                                                 it.tiles_n, it.kb_per_part, it.pa, it.pb, Implicit{},
                                                                 blockIdx.x - it.first);
@@ -1505,15 +1512,13 @@ struct TailGroupItem {
 };
 struct TailGroup {
     int count, tail_cols;
+    unsigned first[kMaxGroup];
     TailGroupItem p[kMaxGroup];
 };
 
 __global__ __launch_bounds__(256) void planes_tail_group_kernel(TailGroup grp)
 {
-    int g = 0;
-    for (int i = 1; i < grp.count; ++i)
-        if (blockIdx.x >= grp.p[i].first) g = i;         // the same in the whole workgroup
-    const TailGroupItem &it = grp.p[g];
+    const TailGroupItem &it = grp.p[group_member(grp.first, blockIdx.x)];  // the same in the whole workgroup
     planes_tail_body(it.Aw, it.Bw, it.pa, it.pb, it.C, it.ldc, it.M, it.N, it.kblocks, it.col_chunks, grp.tail_cols,
                      blockIdx.x - it.first);
 }
@@ -2342,6 +2347,7 @@ int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fm
         Group grp{};
         TailGroup tg{};
         grp.count = tg.count = n;
+        for (int j = 0; j < kMaxGroup; ++j) grp.first[j] = tg.first[j] = 0xFFFFFFFFu;
         uint64_t ids = 0, blocks = 0, blocks256 = 0;
         for (int j = 0; j < n; ++j) {
             const BatchItem &it = items[grouped[g0 + j].item];
@@ -2364,13 +2370,13 @@ int launch_gemm_prepared_batch(int count, const BatchItem *items, int scheme, fm
             p.ldc = ge.nparts > 1 ? (int64_t)N : it.ldc;
             p.M = M; p.N = N; p.kblocks = la.kblocks; p.kb_per_part = ge.kb_per_part;
             p.tiles_m = (M + 64 * gt - 1) / (64 * gt); p.tiles_n = (N + 64 * gt - 1) / (64 * gt);
-            p.first = (unsigned)ids;
+            p.first = grp.first[j] = (unsigned)ids;
             p.pa = va.pl; p.pb = vb.pl;
             ids += ((uint64_t)p.tiles_m * p.tiles_n + 7) / 8 * 8 * (uint64_t)ge.nparts;
             TailGroupItem &t = tg.p[j];
             t.Aw = va.W; t.Bw = vb.W; t.C = it.C; t.ldc = it.ldc;
             t.M = M; t.N = N; t.kblocks = la.kblocks; t.col_chunks = (N + tg.tail_cols - 1) / tg.tail_cols;
-            t.first = (unsigned)blocks;
+            t.first = tg.first[j] = (unsigned)blocks;
             t.pa = va.pl; t.pb = vb.pl;
             blocks += (uint64_t)((M + kUnitRows - 1) / kUnitRows) * t.col_chunks;
             if (ids >= ((uint64_t)1 << 31) || blocks >= ((uint64_t)1 << 31)) return FMT_ERR_SHAPE;
