@@ -415,6 +415,13 @@ def main() -> int:
         "frac": round(roof_tflops / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
         "launch_ms": round(roof_ms, 4), "algorithmic_flops_per_launch": 2.0 * Mr * Nr * Kr,
         "note": "fp16 MFMA dense peak; one MFMA product per multiply, so issued = useful flops"}
+    batch_ms = timed0(cfg4_batched, reps_r)
+    result["roofline_gemm"]["shared_launch"] = {
+        "kernel": "product_group_kernel<PS=0, 256x256 tile> + planes_tail_group_kernel: config 4's twelve products in one "
+                  "fmt_gemm_prepared_batch call",
+        "achieved": round(cfg4_flops / (batch_ms * 1e-3) / 1e12, 1), "unit": "TFLOP/s",
+        "frac": round(cfg4_flops / (batch_ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS, 4), "launch_ms": round(batch_ms, 4),
+        "algorithmic_flops_per_launch": cfg4_flops}
     result["gemm"]["two_piece"] = {
         "value": round(cfg4_flops / (two_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s (useful), one stream",
         "issued_tflops": round(4 * cfg4_flops / (two_ms * 1e-3) / 1e12, 2),
