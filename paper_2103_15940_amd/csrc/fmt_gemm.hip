@@ -2472,7 +2472,7 @@ static int run_implicit(int M, int N, int K, const OperandSpec &sa, const float 
     im.T = T;
     im.piece_vec = (int)piece_vec;
     im.zero = (int)(P * piece_vec);
-    const Planes none{nullptr, nullptr, 0, 0};
+    const Planes none{nullptr, nullptr, 0, 0, nullptr, nullptr};
 #define FMT_PRODUCT(TMV, TNV) \
     launch_product<PS, TMV, TNV>(va.W, nullptr, out.C, M, N, out.ldc, out.img, la.kblocks, plan, partp, stream, none, none, &im)
     if (plan.tm == 4 && plan.tn == 4) return FMT_PRODUCT(4, 4);
