@@ -20,9 +20,10 @@ One "step" is one pass of the whole hot path over one batch of synthetic, paper-
                                      14.8 GFLOP each)
 
 The rounding passes inside the configuration 4 and configuration 3 sections are independent of each other
-and are issued round-robin on three side streams (--gemm-streams); the products of a section are handed to the
-library in one fmt_gemm_prepared_batch call (--no-batch: one fmt_gemm_prepared call per product on the side
-streams).  The stream section runs on one stream.
+and are issued round-robin on three side streams (--gemm-streams): one fmt_prepare_pair_batch call that makes
+the operands of all the section's tensors, and one fmt_quantize call per tensor; the products of a section are
+handed to the library in one fmt_gemm_prepared_batch call (--no-batch: one fmt_prepare_pair call per tensor and
+one fmt_gemm_prepared call per product on the side streams).  The stream section runs on one stream.
 
 `value` is the quantize+histogram HBM rate of the stream section (GB/s, algorithmic bytes over
 the section's event-timed duration); the GEMM section's useful TFLOP/s and its MFMA fraction are
@@ -64,8 +65,8 @@ def main() -> int:
                          "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
     ap.add_argument("--no-batch", action="store_true",
-                    help="issue the products of the configuration 4 and 3 sections as single fmt_gemm_prepared calls on the "
-                         "side streams instead of one fmt_gemm_prepared_batch call per section")
+                    help="configuration 4 and 3 sections: one fmt_prepare_pair call per tensor and one fmt_gemm_prepared call "
+                         "per product on the side streams instead of the batch calls")
     ap.add_argument("--gemm-streams", type=int, default=3,
                     help="side streams the independent calls of the configuration 4 and 3 sections are spread over")
     ap.add_argument("--gemm", default=None, metavar="M,N,K[,transA,transB[,e,m,d]]",
@@ -198,12 +199,20 @@ def main() -> int:
         # library scratch): the HBM-bound operand preparation of one product overlaps the MFMA-bound
         # kernel of another, and the small kernels between the large ones (statistics, sums of partial
         # records) stop being gaps.  The section ends when every side stream has been joined.
-        def fan_out(calls):
+        # alone_first: the first call keeps a side stream to itself (the long one of the section), the others
+        # share the remaining streams.
+        def fan_out(calls, alone_first=False):
             fork = ev()
             fork.record()
+            rest = len(side) - 1 if alone_first and len(side) > 1 else len(side)
             for j, call in enumerate(calls):
-                st_ = side[j % len(side)]
-                if j < len(side):
+                if alone_first and len(side) > 1:
+                    st_ = side[0] if j == 0 else side[1 + (j - 1) % rest]
+                    first_use = j <= rest
+                else:
+                    st_ = side[j % len(side)]
+                    first_use = j < len(side)
+                if first_use:
                     st_.wait_event(fork)
                 call(st_)
             for st_ in side[:min(len(side), len(calls))]:
@@ -217,12 +226,27 @@ def main() -> int:
             fmt.fmt_quantize(src, f169, out=dst, hist=hist, stream=st_)
             ops[key] = fmt.fmt_prepare_pair(src, f169, out=bufs[0], out_t=bufs[1], stream=st_)
 
-        q4 = []
+        # The same with the operands of all the section's tensors prepared by one call (shared launches), beside
+        # the tensors' statistics passes on the side streams.
+        def prepare_all(st_, entries):
+            pairs = fmt.fmt_prepare_pair_batch([e[0] for e in entries], f169, outs=[e[1][0] for e in entries],
+                                               outs_t=[e[1][1] for e in entries], stream=st_)
+            for (_, _, ops, key), pair in zip(entries, pairs):
+                ops[key] = pair
+
+        q4, p4 = [], []
         for L in layers:                                                     # configuration 4, rounding passes
             for src, dst, hi in (("X", "Xq", 0), ("W", "Wq", 1), ("dY", "dYq", 2)):
-                q4.append(lambda st_, L=L, src=src, dst=dst, hi=hi:
-                          round_tensor(st_, L[src], L[dst], L["h"][hi], L["buf"][src], L["op"], src))
-        fan_out(q4)
+                if args.no_batch:
+                    q4.append(lambda st_, L=L, src=src, dst=dst, hi=hi:
+                              round_tensor(st_, L[src], L[dst], L["h"][hi], L["buf"][src], L["op"], src))
+                else:
+                    p4.append((L[src], L["buf"][src], L["op"], src))
+                    q4.append(lambda st_, L=L, src=src, dst=dst, hi=hi:
+                              fmt.fmt_quantize(L[src], f169, out=L[dst], hist=L["h"][hi], stream=st_))
+        if p4:
+            q4.insert(0, lambda st_: prepare_all(st_, p4))
+        fan_out(q4, alone_first=bool(p4))
         mark()
         if args.no_batch:                                                    # configuration 4, products
             g4 = []
@@ -235,9 +259,16 @@ def main() -> int:
         else:
             cfg4_batched()                                                   # the same twelve products, one call
         mark()
-        fan_out([lambda st_: round_tensor(st_, xcol, xcol_q, hists[6], c3["buf"]["X"], c3["op"], "X"),   # configuration 3
-                 lambda st_: round_tensor(st_, w, w_q, hists[7], c3["buf"]["W"], c3["op"], "W"),
-                 lambda st_: round_tensor(st_, dy, dy_q, hists[8], c3["buf"]["dY"], c3["op"], "dY")])
+        if args.no_batch:                                                    # configuration 3
+            fan_out([lambda st_: round_tensor(st_, xcol, xcol_q, hists[6], c3["buf"]["X"], c3["op"], "X"),
+                     lambda st_: round_tensor(st_, w, w_q, hists[7], c3["buf"]["W"], c3["op"], "W"),
+                     lambda st_: round_tensor(st_, dy, dy_q, hists[8], c3["buf"]["dY"], c3["op"], "dY")])
+        else:
+            p3 = [(xcol, c3["buf"]["X"], c3["op"], "X"), (w, c3["buf"]["W"], c3["op"], "W"), (dy, c3["buf"]["dY"], c3["op"], "dY")]
+            fan_out([lambda st_: prepare_all(st_, p3),
+                     lambda st_: fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6], stream=st_),
+                     lambda st_: fmt.fmt_quantize(w, f169, out=w_q, hist=hists[7], stream=st_),
+                     lambda st_: fmt.fmt_quantize(dy, f169, out=dy_q, hist=hists[8], stream=st_)], alone_first=True)
         mark()
         o3 = c3["op"]
         if args.no_batch:

@@ -24,8 +24,8 @@
  *                  used for fully connected layers and im2col convolutions in forward,
  *                  dgrad and wgrad (Sec. IV-A)
  * and, beyond these three:
- *   fmt_operand_bytes / fmt_prepare / fmt_prepare_pair / fmt_gemm_prepared / fmt_gemm_prepared_batch /
- *   fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
+ *   fmt_operand_bytes / fmt_prepare / fmt_prepare_pair / fmt_prepare_pair_batch / fmt_gemm_prepared /
+ *   fmt_gemm_prepared_batch / fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
  *                  into a reusable operand in caller-owned memory (Sec. IV-A rounds each tensor once and
  *                  uses it in several products), and products run on two such operands
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
@@ -260,6 +260,23 @@ int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, 
 int fmt_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f,
                      void *data, size_t bytes, fmt_operand_t *op,
                      void *data_t, size_t bytes_t, fmt_operand_t *op_t, void *stream);
+
+/*
+ * fmt_prepare_pair_batch -- fmt_prepare_pair for `count` matrices in one call: matrix i is X[i] (rows[i] x cols[i],
+ * leading dimension ld[i]), its operands go to data[i] (bytes[i]) and data_t[i] (bytes_t[i]) and are described in
+ * op[i] and op_t[i].  All arrays are HOST arrays of `count` entries (op and op_t are written); X[i], data[i] and
+ * data_t[i] are DEVICE pointers.  One format for all.  The operands equal fmt_prepare_pair's (products on them give
+ * the same bits).  The tensors of a layer's step (Sec. IV-A: input, weights and incoming gradient, each rounded
+ * once and used in both orientations) are small enough that one launch per tensor leaves the device partly idle;
+ * formats whose operands are exponent planes (1/6/m) share one statistics launch and one prepare launch per 16
+ * matrices, other formats are prepared matrix by matrix.
+ * Errors: count < 0 or > 4096 -> FMT_ERR_SHAPE (0 is a no-op); a NULL array or entry -> FMT_ERR_NULL; per matrix as
+ * for fmt_prepare_pair; a prepared buffer that overlaps another matrix's buffers or any input -> FMT_ERR_ALIAS.
+ * Everything is checked before the first launch; no device memory is allocated.
+ */
+int fmt_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *ld, const int64_t *rows, const int64_t *cols,
+                           fmt_format_t f, void *const *data, const size_t *bytes, fmt_operand_t *op,
+                           void *const *data_t, const size_t *bytes_t, fmt_operand_t *op_t, void *stream);
 int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream);
 
 /*

@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_prepare_pair", "fmt_gemm_prepared", "fmt_gemm_prepared_batch", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_prepare_pair", "fmt_prepare_pair_batch", "fmt_gemm_prepared", "fmt_gemm_prepared_batch", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_scratch_bytes", "fmt_release_scratch", "fmt_status_string")
 
 
@@ -99,6 +99,10 @@ def _load() -> ctypes.CDLL:
     lib.fmt_prepare_pair.argtypes = [vp, i64, i64, i64, _CFormat, vp, sz, ctypes.POINTER(_COperand), vp, sz,
                                      ctypes.POINTER(_COperand), vp]
     lib.fmt_prepare_pair.restype = ctypes.c_int
+    lib.fmt_prepare_pair_batch.argtypes = [i64, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                           _CFormat, ctypes.POINTER(vp), ctypes.POINTER(sz), ctypes.POINTER(_COperand),
+                                           ctypes.POINTER(vp), ctypes.POINTER(sz), ctypes.POINTER(_COperand), vp]
+    lib.fmt_prepare_pair_batch.restype = ctypes.c_int
     lib.fmt_gemm_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, i64, vp]
     lib.fmt_gemm_prepared.restype = ctypes.c_int
     lib.fmt_gemm_prepared_batch.argtypes = [i64, ctypes.POINTER(ctypes.POINTER(_COperand)),
@@ -321,6 +325,53 @@ def fmt_prepare_pair(X, fmt, out=None, out_t=None, stream=None):
                                bufs[1].data_ptr(), bufs[1].numel(), ctypes.byref(d1), _stream_ptr(stream))
     _check(rc, "fmt_prepare_pair")
     return PreparedOperand(bufs[0], d0), PreparedOperand(bufs[1], d1)
+
+
+def fmt_prepare_pair_batch(Xs, fmt, outs=None, outs_t=None, stream=None):
+    """:func:`fmt_prepare_pair` for a sequence of 2-D float32 GPU tensors in one call (shared launches for the
+    1/6/m formats).  ``outs`` / ``outs_t``: optional sequences of uint8 GPU tensors to prepare into.  Returns a
+    list of (X as stored, X transposed) operand pairs."""
+    import torch
+    Xs = list(Xs)
+    n = len(Xs)
+    outs = [None] * n if outs is None else list(outs)
+    outs_t = [None] * n if outs_t is None else list(outs_t)
+    if len(outs) != n or len(outs_t) != n:
+        raise ValueError("outs and outs_t must be as long as Xs")
+    bufs, bufs_t = [], []
+    for X, o, ot in zip(Xs, outs, outs_t):
+        _dev_f32(X, "X")
+        if X.dim() != 2 or (X.shape[1] > 1 and X.stride(1) != 1):
+            raise ValueError("every X must be 2-D with unit column stride")
+        rows, cols = X.shape
+        pair = []
+        for buf, (r, k) in ((o, (rows, cols)), (ot, (cols, rows))):
+            if buf is None:
+                buf = torch.empty(fmt_operand_bytes(r, k, fmt), dtype=torch.uint8, device=X.device)
+            if not isinstance(buf, torch.Tensor) or buf.dtype != torch.uint8 or not buf.is_cuda or not buf.is_contiguous():
+                raise TypeError("outs and outs_t must hold contiguous GPU uint8 tensors")
+            pair.append(buf)
+        bufs.append(pair[0])
+        bufs_t.append(pair[1])
+    m = max(n, 1)
+    xp = (ctypes.c_void_p * m)(*[X.data_ptr() for X in Xs])
+    ld = (ctypes.c_int64 * m)(*[X.stride(0) if X.shape[0] > 1 else max(X.shape[1], 1) for X in Xs])
+    rows = (ctypes.c_int64 * m)(*[X.shape[0] for X in Xs])
+    cols = (ctypes.c_int64 * m)(*[X.shape[1] for X in Xs])
+    dp = (ctypes.c_void_p * m)(*[b.data_ptr() for b in bufs])
+    db = (ctypes.c_size_t * m)(*[b.numel() for b in bufs])
+    tp = (ctypes.c_void_p * m)(*[b.data_ptr() for b in bufs_t])
+    tb = (ctypes.c_size_t * m)(*[b.numel() for b in bufs_t])
+    d0, d1 = (_COperand * m)(), (_COperand * m)()
+    rc = _lib.fmt_prepare_pair_batch(n, xp, ld, rows, cols, _cfmt(fmt), dp, db, d0, tp, tb, d1, _stream_ptr(stream))
+    _check(rc, "fmt_prepare_pair_batch")
+    result = []
+    for i in range(n):
+        a, b = _COperand(), _COperand()
+        ctypes.memmove(ctypes.byref(a), ctypes.byref(d0[i]), ctypes.sizeof(_COperand))
+        ctypes.memmove(ctypes.byref(b), ctypes.byref(d1[i]), ctypes.sizeof(_COperand))
+        result.append((PreparedOperand(bufs[i], a), PreparedOperand(bufs_t[i], b)))
+    return result
 
 
 def fmt_gemm_prepared(A: PreparedOperand, B: PreparedOperand, out=None, stream=None):

@@ -262,6 +262,26 @@ int fmt_prepare(const float *X, int64_t ld, int trans, int64_t rows, int64_t k, 
     return FMT_OK;
 }
 
+// Everything fmt_prepare_pair checks before it launches; the bytes and schemes of the two operands come back.
+static int check_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f, const void *data, size_t bytes,
+                      const void *data_t, size_t bytes_t, size_t *need, int *scheme, size_t *need_t, int *scheme_t)
+{
+    const int64_t lim = (int64_t)1 << 31;
+    if (rows < 1 || cols < 1 || rows >= lim || cols >= lim) return FMT_ERR_SHAPE;
+    if (!X || !data || !data_t) return FMT_ERR_NULL;
+    if (ld < cols || ld >= lim) return FMT_ERR_SHAPE;
+    if (!aligned(X, 4) || !aligned(data, 256) || !aligned(data_t, 256)) return FMT_ERR_ALIGN;
+    int rc = prepared_operand_bytes(rows, cols, f, need, scheme);
+    if (rc != FMT_OK) return rc;
+    rc = prepared_operand_bytes(cols, rows, f, need_t, scheme_t);
+    if (rc != FMT_OK) return rc;
+    if (bytes < *need || bytes_t < *need_t) return FMT_ERR_SHAPE;
+    const size_t xbytes = 4 * (size_t)((rows - 1) * ld + cols);
+    if (overlap(data, *need, X, xbytes) || overlap(data_t, *need_t, X, xbytes) || overlap(data, *need, data_t, *need_t))
+        return FMT_ERR_ALIAS;
+    return FMT_OK;
+}
+
 int fmt_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f,
                      void *data, size_t bytes, fmt_operand_t *op,
                      void *data_t, size_t bytes_t, fmt_operand_t *op_t, void *stream)
@@ -269,25 +289,53 @@ int fmt_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt
     QuantParams p;
     int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
     if (rc != FMT_OK) return rc;
-    const int64_t lim = (int64_t)1 << 31;
-    if (rows < 1 || cols < 1 || rows >= lim || cols >= lim) return FMT_ERR_SHAPE;
-    if (!X || !data || !op || !data_t || !op_t) return FMT_ERR_NULL;
-    if (ld < cols || ld >= lim) return FMT_ERR_SHAPE;
-    if (!aligned(X, 4) || !aligned(data, 256) || !aligned(data_t, 256)) return FMT_ERR_ALIGN;
+    if (!op || !op_t) return FMT_ERR_NULL;
     size_t need = 0, need_t = 0;
     int scheme = 0, scheme_t = 0;
-    rc = prepared_operand_bytes(rows, cols, f, &need, &scheme);
+    rc = check_pair(X, ld, rows, cols, f, data, bytes, data_t, bytes_t, &need, &scheme, &need_t, &scheme_t);
     if (rc != FMT_OK) return rc;
-    rc = prepared_operand_bytes(cols, rows, f, &need_t, &scheme_t);
-    if (rc != FMT_OK) return rc;
-    if (bytes < need || bytes_t < need_t) return FMT_ERR_SHAPE;
-    const size_t xbytes = 4 * (size_t)((rows - 1) * ld + cols);
-    if (overlap(data, need, X, xbytes) || overlap(data_t, need_t, X, xbytes) || overlap(data, need, data_t, need_t))
-        return FMT_ERR_ALIAS;
     rc = launch_prepare_pair(X, ld, rows, cols, f, p, data, data_t, static_cast<hipStream_t>(stream));
     if (rc != FMT_OK) return rc;
     *op = fmt_operand_t{data, bytes, rows, cols, f, scheme};
     *op_t = fmt_operand_t{data_t, bytes_t, cols, rows, f, scheme_t};
+    return FMT_OK;
+}
+
+int fmt_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *ld, const int64_t *rows, const int64_t *cols,
+                           fmt_format_t f, void *const *data, const size_t *bytes, fmt_operand_t *op,
+                           void *const *data_t, const size_t *bytes_t, fmt_operand_t *op_t, void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, FMT_EXP_LO_DEFAULT, &p);
+    if (rc != FMT_OK) return rc;
+    if (count < 0 || count > 4096) return FMT_ERR_SHAPE;
+    if (count == 0) return FMT_OK;
+    if (!X || !ld || !rows || !cols || !data || !bytes || !op || !data_t || !bytes_t || !op_t) return FMT_ERR_NULL;
+    std::vector<PrepPairItem> items((size_t)count);
+    std::vector<size_t> need((size_t)count), need_t((size_t)count);
+    std::vector<int> scheme((size_t)count), scheme_t((size_t)count);
+    for (int64_t i = 0; i < count; ++i) {
+        rc = check_pair(X[i], ld[i], rows[i], cols[i], f, data[i], bytes[i], data_t[i], bytes_t[i], &need[i], &scheme[i],
+                        &need_t[i], &scheme_t[i]);
+        if (rc != FMT_OK) return rc;
+        items[i] = PrepPairItem{X[i], ld[i], rows[i], cols[i], data[i], data_t[i]};
+    }
+    // no operand may lie over another tensor's operands or over any of the inputs (the launches are shared)
+    for (int64_t i = 0; i < count; ++i)
+        for (int64_t j = 0; j < count; ++j) {
+            if (j == i) continue;
+            const size_t xbytes = 4 * (size_t)((rows[j] - 1) * ld[j] + cols[j]);
+            if (overlap(data[i], need[i], X[j], xbytes) || overlap(data_t[i], need_t[i], X[j], xbytes) ||
+                overlap(data[i], need[i], data[j], need[j]) || overlap(data[i], need[i], data_t[j], need_t[j]) ||
+                overlap(data_t[i], need_t[i], data_t[j], need_t[j]))
+                return FMT_ERR_ALIAS;
+        }
+    rc = launch_prepare_pair_batch(count, items.data(), f, p, static_cast<hipStream_t>(stream));
+    if (rc != FMT_OK) return rc;
+    for (int64_t i = 0; i < count; ++i) {
+        op[i] = fmt_operand_t{data[i], bytes[i], rows[i], cols[i], f, scheme[i]};
+        op_t[i] = fmt_operand_t{data_t[i], bytes_t[i], cols[i], rows[i], f, scheme_t[i]};
+    }
     return FMT_OK;
 }
 

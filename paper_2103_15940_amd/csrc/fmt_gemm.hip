@@ -687,12 +687,80 @@ __device__ __forceinline__ void prepare_block(const PrepOperand &a, const PrepOp
     }
 }
 
+// Eight rounded values of one thread (fp32 patterns r[], elements k0 .. k0 + 7 of row `row` of operand o) as
+// binary16 patterns, two per word: p0 = plane 0, pa / pb = the planes above / below (zero where an element
+// does not belong to the plane).  Elements outside plane 0 also leave a record in the list of their row of
+// units for the kernel that adds their products.  Returns 2 / 4 if any element went above / below.
+template <class OP>
+__device__ __forceinline__ uint32_t split_planes(const OP &o, int row, int k0, const uint32_t (&r)[8], u32x4 &p0, u32x4 &pa,
+                                                 u32x4 &pb)
+{
+    const int S = o.pl.S[row];                   // S covers the padded rows
+    uint32_t hb[8];
+    bool other[8], any = false;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // r * 2^S (exact: |S| is small) converts to binary16 and back unchanged <=> it is a binary16
+        // value -- zeros, the normal and the denormal range, infinities.  NaN (neither below nor above its
+        // own conversion) stays in plane 0 as well.
+        const float sc = ldexpf(__uint_as_float(r[j]), S);
+        const _Float16 h = static_cast<_Float16>(sc);               // round to nearest even
+        const float back = static_cast<float>(h);
+        other[j] = back < sc || back > sc;
+        any |= other[j];
+        hb[j] = (uint32_t)__builtin_bit_cast(uint16_t, h);
+    }
+    pa = pb = u32x4{0u, 0u, 0u, 0u};
+    uint32_t mine = 0u;
+    if (any) {                                   // rare: the common case does not pay for it element by element
+        const int w = o.pl.w;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (other[j]) {
+                // too large for plane 0 -> the plane above; bits below 2^-24 -> the plane below (exact there)
+                const float rf = __uint_as_float(r[j]);
+                const bool up = fabsf(ldexpf(rf, S)) >= 65536.0f;
+                const _Float16 g = static_cast<_Float16>(ldexpf(rf, up ? S - w : S + w));
+                const uint32_t gb = (uint32_t)__builtin_bit_cast(uint16_t, g) << (16 * (j & 1));
+                pa[j / 2] |= up ? gb : 0u;
+                pb[j / 2] |= up ? 0u : gb;
+                mine |= up ? 2u : 4u;
+                hb[j] = 0u;
+                const uint32_t slot = atomicAdd(&o.pl.rec_cnt[row / kUnitRows], 1u);
+                if (slot < (uint32_t)kRecCap) {
+                    uint32_t *rec = o.pl.recs + ((size_t)(row / kUnitRows) * kRecCap + slot) * 2;
+                    rec[0] = ((uint32_t)(k0 + j) << 5) | (uint32_t)(row % kUnitRows);
+                    rec[1] = r[j];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p0[i] = hb[2 * i] | (hb[2 * i + 1] << 16);
+    return mine;
+}
+
+// Stores what split_planes made: plane 0 always, the planes in `have` (bit 1 above, bit 2 below; agreed on by
+// the threads of the unit); the unit's leader writes the mask.
+template <class OP>
+__device__ __forceinline__ void store_planes(const OP &o, int row, int k0, int kblocks, const u32x4 &p0, const u32x4 &pa,
+                                             const u32x4 &pb, uint32_t have, bool leader)
+{
+    const int rb = row / kUnitRows, rr = row % kUnitRows;
+    const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
+    const size_t at = unit_vec_index(rb, kb, kblocks, 1, 0, c, rr);
+    o.W[at] = p0;
+    if (have & 2u) o.W[o.pl.plane + at] = pa;
+    if (have & 4u) o.W[2 * o.pl.plane + at] = pb;
+    if (leader) o.pl.mask[(size_t)rb * kblocks + kb] = (uint8_t)(1u | have);
+}
+
 // Scaled exponent planes of a plain matrix operand (see the top of this file).  Same element-to-thread
 // mapping as prepare_block, so a workgroup covers exactly two units; which of them has elements
 // outside plane 0 is agreed on through two words of LDS, and only then are the other planes of that
 // unit written (the elements that do not belong to a plane are zero there).
-template <int MODE, bool FTZ>
-__device__ __forceinline__ void prepare_scaled_block(const PrepOperand &o, int K, int kblocks, const QuantParams &p,
+template <int MODE, bool FTZ, class OP>
+__device__ __forceinline__ void prepare_scaled_block(const OP &o, int K, int kblocks, const QuantParams &p,
                                                      unsigned bid)
 {
     __shared__ uint32_t s_planes[2];
@@ -733,60 +801,73 @@ __device__ __forceinline__ void prepare_scaled_block(const PrepOperand &o, int K
             v[j] = ok ? X[idx] : 0u;
         }
     }
-    const int S = o.pl.S[row];                   // S covers the padded rows
-    const int w = o.pl.w;
-    uint32_t h0[8], hx[8];                       // plane 0 pattern; pattern in the other plane, bit 16 = above, bit 17 = below
-    uint32_t mine = 0u;
+    uint32_t r[8];
+    u32x4 p0, pa, pb;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        // r * 2^S (exact: |S| is small) converts to binary16 and back unchanged <=> it is a binary16
-        // value -- zeros, the normal and the denormal range, infinities.  NaN stays in plane 0 as well.
-        const uint32_t r = quantize_bits<MODE, FTZ>(v[j], p);
-        const float rf = __uint_as_float(r);
-        const float sc = ldexpf(rf, S);
-        const _Float16 h = static_cast<_Float16>(sc);               // round to nearest even
-        const bool plain = static_cast<float>(h) == sc || (r & 0x7FFFFFFFu) > 0x7F800000u;
-        h0[j] = plain ? (uint32_t)__builtin_bit_cast(uint16_t, h) : 0u;
-        hx[j] = 0u;
-        if (!plain) {
-            // too large for plane 0 -> the plane above; bits below 2^-24 -> the plane below (exact there)
-            const bool up = fabsf(sc) >= 65536.0f;
-            const _Float16 g = static_cast<_Float16>(ldexpf(rf, up ? S - w : S + w));
-            hx[j] = (uint32_t)__builtin_bit_cast(uint16_t, g) | (up ? 0x10000u : 0x20000u);
-            mine |= up ? 2u : 4u;
-            // and a record for the kernel that adds these elements' products
-            const uint32_t slot = atomicAdd(&o.pl.rec_cnt[row / kUnitRows], 1u);
-            if (slot < (uint32_t)kRecCap) {
-                uint32_t *rec = o.pl.recs + ((size_t)(row / kUnitRows) * kRecCap + slot) * 2;
-                rec[0] = ((uint32_t)(k0 + j) << 5) | (uint32_t)(row % kUnitRows);
-                rec[1] = r;
-            }
-        }
-    }
+    for (int j = 0; j < 8; ++j) r[j] = quantize_bits<MODE, FTZ>(v[j], p);
+    const uint32_t mine = split_planes(o, row, k0, r, p0, pa, pb);
     __syncthreads();                             // s_planes has been cleared
     if (mine != 0u) atomicOr(&s_planes[u], mine);
     __syncthreads();
     if (!live) return;
-    const uint32_t have = s_planes[u];
-    const int rb = row / kUnitRows, rr = row % kUnitRows;
-    const int kb = k0 / kUnitK, c = (k0 % kUnitK) / 8;
-    const size_t at = unit_vec_index(rb, kb, kblocks, 1, 0, c, rr);
-    u32x4 out;
+    store_planes(o, row, k0, kblocks, p0, pa, pb, s_planes[u],
+                 kcontig ? (tid / 8 == 0 && tid % 4 == 0) : (tid / 64 == 0 && tid % 32 == 0));
+}
+
+// Both orientations of one tile of a plain matrix X -- 32 rows (32 ty ..) by 64 columns (64 tx ..) -- as scaled
+// exponent planes: o0 is X as stored (its rows are X's, k runs along X's columns), o1 is X transposed.  The
+// tile is one workgroup's share of either operand in prepare_scaled_block, and the threads keep that function's
+// element mappings: the tile is read and rounded once in o0's mapping (a row's eight consecutive columns per
+// thread), the rounded patterns cross over to o1's mapping (a column's eight consecutive rows) through LDS.
+template <int MODE, bool FTZ, class OP>
+__device__ __forceinline__ void prepare_pair_tile(const OP &o0, const OP &o1, const QuantParams &p, int ty, int tx)
+{
+    __shared__ __align__(16) uint32_t s_r[32][68];      // 68: rows stay 16-byte aligned, 128-bit writes spread over all banks
+    __shared__ uint32_t s_planes[4];                    // o0's two units (halves of k), then o1's two (halves of its rows)
+    const int tid = threadIdx.x;
+    if (tid < 4) s_planes[tid] = 0u;
+    const int R = o0.rows, C = o1.rows;                 // X is R x C
+    const int xr = ty * 32 + tid / 8, xc = tx * 64 + (tid % 8) * 8;
+    uint32_t r[8];
+    {
+        uint32_t v[8];
+        if (o0.vec4 && xr < R && xc + 8 <= C) {
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(o0.X + (size_t)xr * o0.ld + xc);
+            const u32x4 lo = __builtin_nontemporal_load(src), hi = __builtin_nontemporal_load(src + 1);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) out[i] = h0[2 * i] | (h0[2 * i + 1] << 16);
-    o.W[at] = out;
+            for (int j = 0; j < 4; ++j) {
+                v[j] = lo[j];
+                v[4 + j] = hi[j];
+            }
+        } else {
 #pragma unroll
-    for (int q = 1; q <= 2; ++q) {
-        if ((have >> q) & 1u) {
-            const uint32_t tag = 0x8000u << q;   // bit 16 (above) or bit 17 (below)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                out[i] = ((hx[2 * i] & tag) ? (hx[2 * i] & 0xFFFFu) : 0u) | ((hx[2 * i + 1] & tag) ? (hx[2 * i + 1] << 16) : 0u);
-            o.W[(size_t)q * o.pl.plane + at] = out;
+            for (int j = 0; j < 8; ++j) v[j] = (xr < R && xc + j < C) ? o0.X[(size_t)xr * o0.ld + xc + j] : 0u;
         }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = quantize_bits<MODE, FTZ>(v[j], p);
     }
-    const bool leader = kcontig ? (tid / 8 == 0 && tid % 4 == 0) : (tid / 64 == 0 && tid % 32 == 0);
-    if (leader) o.pl.mask[(size_t)rb * kblocks + kb] = (uint8_t)(1u | have);
+    u32x4 *dst = reinterpret_cast<u32x4 *>(&s_r[tid / 8][(tid % 8) * 8]);
+    dst[0] = u32x4{r[0], r[1], r[2], r[3]};
+    dst[1] = u32x4{r[4], r[5], r[6], r[7]};
+    __syncthreads();
+    // beyond an operand's k-blocks there is nothing of it to write (the other operand's padded rows lie there)
+    const bool do0 = tx < (o0.kblocks + 1) / 2, do1 = ty < o1.kblocks;
+    const bool live0 = do0 && xc < o0.kblocks * kUnitK;       // the last slab of o0 may hold one k-block only
+    const int row1 = tx * 64 + tid % 64, k1 = ty * 32 + (tid / 64) * 8;
+    const int u0 = (tid % 8) / 4, u1 = 2 + (tid % 64) / 32;
+    // (where an operand has nothing to write the tile holds zeros only and its rows are padded ones, whose scales
+    // exist: the split is harmless there and leaves no records)
+    uint32_t t[8];
+    u32x4 p0a, paa, pba, p0b, pab, pbb;
+    const uint32_t mine0 = split_planes(o0, xr, xc, r, p0a, paa, pba);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t[j] = s_r[(tid / 64) * 8 + j][tid % 64];
+    const uint32_t mine1 = split_planes(o1, row1, k1, t, p0b, pab, pbb);
+    if (mine0 != 0u) atomicOr(&s_planes[u0], mine0);
+    if (mine1 != 0u) atomicOr(&s_planes[u1], mine1);
+    __syncthreads();
+    if (live0) store_planes(o0, xr, xc, o0.kblocks, p0a, paa, pba, s_planes[u0], tid / 8 == 0 && tid % 4 == 0);
+    if (do1) store_planes(o1, row1, k1, o1.kblocks, p0b, pab, pbb, s_planes[u1], tid / 64 == 0 && tid % 32 == 0);
 }
 
 // One launch prepares both operands of a product (or one: b.nblocks == 0).
@@ -809,6 +890,59 @@ __global__ __launch_bounds__(256) void prepare_scaled_kernel(PrepOperand a, Prep
     const unsigned bid = (lid % 8u) * per_xcd + lid / 8u;
     if (bid >= o.nblocks) return;                // workgroup-uniform: before any barrier
     prepare_scaled_block<MODE, FTZ>(o, second ? Kb : Ka, second ? kblocks_b : kblocks_a, p, bid);
+}
+
+// The exponent planes of both orientations of up to kMaxPrepGroup / 2 plain matrices in one launch.  Operands
+// 2i (X as stored: rows of X, k along its columns) and 2i + 1 (X transposed) belong to matrix i; the table
+// travels by value in the kernel arguments.  A workgroup takes one tile of 32 rows x 64 columns of X and
+// prepares it for both operands (prepare_pair_tile): X is read and rounded once.  Every
+// matrix owns a run of workgroup ids padded to a multiple of 8 (first[] = the runs' first ids, ascending)
+// and remapped XCD by XCD as above.
+constexpr int kMaxPrepGroup = 32;
+
+struct PrepPlain {
+    const uint32_t *X;
+    u32x4 *W;
+    int64_t ld;
+    int rows;
+    int kcontig;
+    int vec4;
+    int units;
+    int K, kblocks;
+    Planes pl;
+};
+
+struct PrepGroup {
+    unsigned first[kMaxPrepGroup / 2];   // 0xFFFFFFFF beyond the last matrix
+    unsigned tiles[kMaxPrepGroup / 2];
+    PrepPlain o[kMaxPrepGroup];
+};
+
+// index of the run that holds workgroup `id`: the number of runs that start at or before it, minus one
+// (first[] ascending, 0xFFFFFFFF beyond the last run)
+template <int CAP>
+__device__ __forceinline__ int run_of(const unsigned (&first)[CAP], unsigned id)
+{
+    int at = -1;
+#pragma unroll
+    for (int i = 0; i < CAP; ++i) at += id >= first[i] ? 1 : 0;
+    return at;
+}
+
+template <int MODE, bool FTZ>
+__global__ __launch_bounds__(256) void prepare_scaled_group_kernel(PrepGroup grp, QuantParams p)
+{
+    const int at = run_of(grp.first, blockIdx.x);
+    const PrepPlain &o0 = grp.o[2 * at], &o1 = grp.o[2 * at + 1];
+    const unsigned lid = blockIdx.x - grp.first[at], ntiles = grp.tiles[at];
+    const unsigned per_xcd = (ntiles + 7u) / 8u;
+    const unsigned t = (lid % 8u) * per_xcd + lid / 8u;
+    if (t >= ntiles) return;                     // workgroup-uniform: before any barrier
+    // rows of X in 32s: o0's units (rows padded to the tile grid) cover o1's k-blocks; columns of X in 64s:
+    // pairs of o1's units cover o0's slabs of two k-blocks
+    const int ntx = o1.units / 2;
+    const int ty = (int)(t / (unsigned)ntx), tx = (int)(t % (unsigned)ntx);
+    prepare_pair_tile<MODE, FTZ>(o0, o1, p, ty, tx);
 }
 
 // Epilogue of one wave.  The MFMAs are fed operand B's fragment first and A's second, so a 32 x 32 accumulator
@@ -1818,6 +1952,7 @@ struct StatOperand {
     int rows;
     int rows_pad;
     int kcontig;
+    int vec4;                // base 16-byte aligned and ld a multiple of 4: a k-contiguous row is read in 16-byte pieces
     int *S;
     uint32_t *rec_cnt;       // record counts of the operand's rows of units: cleared here, filled by the prepare pass
     unsigned nblocks;
@@ -1835,15 +1970,10 @@ struct StatOperand {
 //     more than a plane, T = lo + wid (the small values stay, the large ones go to the plane above).
 // Any T in [kWinTmin, kWinTmax] is correct -- what does not fit plane 0 goes to another plane -- the
 // choice only decides how often the other planes are needed, which is why a sample suffices.
-__global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int Ka, int kstep_a, int Kb,
-                                                           int kstep_b, int emin, int m)
+__device__ __forceinline__ void window_stats_block(const StatOperand &o, int K, int kstep, int emin, int m, int by)
 {
     __shared__ int s_hi[8][32], s_lo[8][32];
     const int tid = threadIdx.x;
-    const bool second = blockIdx.x >= a.nblocks;
-    const StatOperand &o = second ? b : a;
-    const int K = second ? Kb : Ka, kstep = second ? kstep_b : kstep_a;
-    const int by = blockIdx.x - (second ? a.nblocks : 0u);
     const int wid = 39 - m;                       // binades below the top one that a plane holds with m + 1 significant bits
     int hi = -1000, lo = 1000;
     auto look = [&](uint32_t u) {
@@ -1863,10 +1993,20 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int k0 = min(kl * 8 + i * 64 * kstep, K - 1);
+            if (o.kcontig && o.vec4 && k0 + 8 <= K) {      // k0 is a multiple of 8 here
+                const u32x4 *src = reinterpret_cast<const u32x4 *>(o.X + (size_t)row * o.ld + k0);
+                const u32x4 a = src[0], b = src[1];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int k = min(k0 + j, K - 1);          // a repeated element does not change max / min
-                u[i][j] = o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
+                for (int j = 0; j < 4; ++j) {
+                    u[i][j] = a[j];
+                    u[i][4 + j] = b[j];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int k = min(k0 + j, K - 1);      // a repeated element does not change max / min
+                    u[i][j] = o.kcontig ? o.X[(size_t)row * o.ld + k] : o.X[(size_t)k * o.ld + row];
+                }
             }
         }
 #pragma unroll
@@ -1901,6 +2041,27 @@ __global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOp
     T = max(kWinTmin, min(kWinTmax, T));
     o.S[row] = 15 - T;
     if (row % kUnitRows == 0) o.rec_cnt[row / kUnitRows] = 0u;
+}
+
+__global__ __launch_bounds__(256) void window_stats_kernel(StatOperand a, StatOperand b, int Ka, int kstep_a, int Kb,
+                                                           int kstep_b, int emin, int m)
+{
+    const bool second = blockIdx.x >= a.nblocks;
+    window_stats_block(second ? b : a, second ? Kb : Ka, second ? kstep_b : kstep_a, emin, m,
+                       (int)(blockIdx.x - (second ? a.nblocks : 0u)));
+}
+
+// The same for the operands of a prepare group (see prepare_scaled_group_kernel): run i starts at first[i].
+struct StatGroup {
+    unsigned first[kMaxPrepGroup];   // 0xFFFFFFFF beyond the last operand
+    StatOperand o[kMaxPrepGroup];
+    int K[kMaxPrepGroup], kstep[kMaxPrepGroup];
+};
+
+__global__ __launch_bounds__(256) void window_stats_group_kernel(StatGroup grp, int emin, int m)
+{
+    const int at = run_of(grp.first, blockIdx.x);
+    window_stats_block(grp.o[at], grp.K[at], grp.kstep[at], emin, m, (int)(blockIdx.x - grp.first[at]));
 }
 
 // ---- operand preparation ------------------------------------------------------------------------
@@ -1956,6 +2117,7 @@ static int prepare_operands(const OperandSpec &sa, const OperandLayout &la, cons
                 t.rows = L.rows;
                 t.rows_pad = L.units * kUnitRows;
                 t.kcontig = o.kcontig;
+                t.vec4 = o.vec4;
                 t.S = o.pl.S;
                 t.rec_cnt = o.pl.rec_cnt;
                 t.nblocks = present ? (unsigned)L.units : 0u;
@@ -2126,65 +2288,111 @@ int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, 
 #undef FMT_PREP
 }
 
-// Both orientations of one matrix X (rows x cols, X[r*ld + c]) as prepared operands: buf0 = X as stored
-// (rows, k = cols), buf1 = X transposed (cols, k = rows).  Exponent planes: one statistics launch and one
-// prepare launch serve both (the second pass over X comes out of the caches); other schemes: two prepare calls.
-template <bool FTZ>
-static int prepare_pair_planes(const float *X, int64_t ld, const OperandLayout &L0, const OperandView &v0, int K0,
-                               const OperandLayout &L1, const OperandView &v1, int K1, fmt_format_t f, const QuantParams &p,
-                               hipStream_t stream)
+// Both orientations of several matrices (buf0 = X as stored, buf1 = X transposed) with shared launches:
+// matrices whose two operands take exponent planes are gathered, up to kMaxPrepGroup / 2 at a time, into one
+// statistics launch and one prepare launch; the others are prepared operand by operand.  The operands equal
+// those of two launch_prepare_operand calls (the same block functions on the same blocks; only the order of
+// the records within a list may differ, which the product's tail sorts away).
+static_assert(sizeof(PrepGroup) + sizeof(QuantParams) <= 4096 && sizeof(StatGroup) + 8 <= 4096,
+              "group tables travel in the kernel arguments");
+
+int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_format_t f, const QuantParams &p, hipStream_t stream)
 {
-    auto operand = [&](bool kcontig, const OperandLayout &L, const OperandView &v) {
-        PrepOperand o;
-        o.X = reinterpret_cast<const uint32_t *>(X);
-        o.g = Gather{};
+    StatGroup sg;
+    PrepGroup pg;
+    int n = 0;
+    unsigned stat_ids = 0, prep_ids = 0;
+    const int bias = (1 << (f.e - 1)) - 1;
+    auto flush = [&]() -> int {
+        if (n == 0) return FMT_OK;
+        for (int i = n; i < kMaxPrepGroup; ++i) {
+            sg.first[i] = 0xFFFFFFFFu;
+            sg.o[i] = StatOperand{};
+            sg.K[i] = sg.kstep[i] = 0;
+            pg.o[i] = PrepPlain{};
+        }
+        for (int i = n / 2; i < kMaxPrepGroup / 2; ++i) {
+            pg.first[i] = 0xFFFFFFFFu;
+            pg.tiles[i] = 0u;
+        }
+        hipLaunchKernelGGL(window_stats_group_kernel, dim3(stat_ids), dim3(256), 0, stream, sg, 1 - bias, f.m);
+        FMT_HIP_CHECK(hipGetLastError());
+        if (f.denorm == 0)
+            hipLaunchKernelGGL((prepare_scaled_group_kernel<kModeMagic, true>), dim3(prep_ids), dim3(256), 0, stream, pg, p);
+        else
+            hipLaunchKernelGGL((prepare_scaled_group_kernel<kModeMagic, false>), dim3(prep_ids), dim3(256), 0, stream, pg, p);
+        FMT_HIP_CHECK(hipGetLastError());
+        n = 0;
+        stat_ids = prep_ids = 0;
+        return FMT_OK;
+    };
+    auto add = [&](const PrepPairItem &it, bool kcontig, const OperandLayout &L, const OperandView &v, int K) {
+        PrepPlain &o = pg.o[n];
+        o.X = reinterpret_cast<const uint32_t *>(it.X);
         o.W = v.W;
-        o.ld = ld;
+        o.ld = it.ld;
         o.rows = L.rows;
         o.kcontig = kcontig;
-        o.vec4 = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && ld % 4 == 0;
-        o.nblocks = kcontig ? (unsigned)((L.kblocks + 1) / 2) * L.units : (unsigned)L.kblocks * (L.units / 2);
+        o.vec4 = (reinterpret_cast<uintptr_t>(it.X) & 15) == 0 && it.ld % 4 == 0;
+        o.units = L.units;
+        o.K = K;
+        o.kblocks = L.kblocks;
         o.pl = v.pl;
-        return o;
-    };
-    const PrepOperand o0 = operand(true, L0, v0), o1 = operand(false, L1, v1);
-    auto stat = [&](const PrepOperand &o, const OperandLayout &L) {
-        StatOperand t;
+        StatOperand &t = sg.o[n];
         t.X = o.X;
         t.ld = o.ld;
         t.rows = L.rows;
         t.rows_pad = L.units * kUnitRows;
-        t.kcontig = o.kcontig;
-        t.S = o.pl.S;
-        t.rec_cnt = o.pl.rec_cnt;
+        t.kcontig = kcontig;
+        t.vec4 = o.vec4;
+        t.S = v.pl.S;
+        t.rec_cnt = v.pl.rec_cnt;
         t.nblocks = (unsigned)L.units;
-        return t;
+        sg.K[n] = K;
+        sg.kstep[n] = ((K + 63) / 64 + 3) / 4;
+        sg.first[n] = stat_ids;
+        stat_ids += t.nblocks;
+        ++n;
     };
-    const StatOperand t0 = stat(o0, L0), t1 = stat(o1, L1);
-    const int bias = (1 << (f.e - 1)) - 1;
-    hipLaunchKernelGGL(window_stats_kernel, dim3(t0.nblocks + t1.nblocks), dim3(256), 0, stream, t0, t1, K0,
-                       ((K0 + 63) / 64 + 3) / 4, K1, ((K1 + 63) / 64 + 3) / 4, 1 - bias, f.m);
-    FMT_HIP_CHECK(hipGetLastError());
-    const unsigned grid = (o0.nblocks + 7u) / 8u * 8u + (o1.nblocks + 7u) / 8u * 8u;
-    hipLaunchKernelGGL((prepare_scaled_kernel<kModeMagic, FTZ>), dim3(grid), dim3(256), 0, stream, o0, o1, K0, L0.kblocks, K1,
-                       L1.kblocks, p);
-    FMT_HIP_CHECK(hipGetLastError());
-    return FMT_OK;
+    for (int64_t i = 0; i < count; ++i) {
+        const PrepPairItem &it = items[i];
+        const Scheme s0 = api_scheme(f, it.cols), s1 = api_scheme(f, it.rows);
+        if (!(s0.scaled && s1.scaled && p.mode == kModeMagic)) {
+            int rc = launch_prepare_operand(it.X, it.ld, 0, it.rows, it.cols, f, p, it.buf0, stream);
+            if (rc == FMT_OK) rc = launch_prepare_operand(it.X, it.ld, 1, it.cols, it.rows, f, p, it.buf1, stream);
+            if (rc != FMT_OK) return rc;
+            continue;
+        }
+        OperandLayout L0, L1;
+        int rc = operand_layout(it.rows, it.cols, s0, f.m, &L0);
+        if (rc != FMT_OK) return rc;
+        rc = operand_layout(it.cols, it.rows, s1, f.m, &L1);
+        if (rc != FMT_OK) return rc;
+        if (n + 2 > kMaxPrepGroup || prep_ids > 0x40000000u) {
+            rc = flush();
+            if (rc != FMT_OK) return rc;
+        }
+        // tiles of 32 rows x 64 columns of X: L0's units by pairs of L1's units (both cover the other operand's k)
+        const unsigned tiles = (unsigned)L0.units * (unsigned)(L1.units / 2);
+        pg.first[n / 2] = prep_ids;
+        pg.tiles[n / 2] = tiles;
+        prep_ids += (tiles + 7u) / 8u * 8u;
+        add(it, true, L0, view_of(it.buf0, L0), (int)it.cols);
+        add(it, false, L1, view_of(it.buf1, L1), (int)it.rows);
+    }
+    return flush();
 }
 
+// Both orientations of one matrix X (rows x cols, X[r*ld + c]) as prepared operands: buf0 = X as stored
+// (rows, k = cols), buf1 = X transposed (cols, k = rows).  Exponent planes: one statistics launch and one
+// prepare launch that reads X once serve both (launch_prepare_pair_batch); other schemes: two prepare calls.
 int launch_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f, const QuantParams &p, void *buf0,
                         void *buf1, hipStream_t stream)
 {
     const Scheme s0 = api_scheme(f, cols), s1 = api_scheme(f, rows);
     if (s0.scaled && s1.scaled && p.mode == kModeMagic) {
-        OperandLayout L0, L1;
-        int rc = operand_layout(rows, cols, s0, f.m, &L0);
-        if (rc != FMT_OK) return rc;
-        rc = operand_layout(cols, rows, s1, f.m, &L1);
-        if (rc != FMT_OK) return rc;
-        const OperandView v0 = view_of(buf0, L0), v1 = view_of(buf1, L1);
-        return f.denorm == 0 ? prepare_pair_planes<true>(X, ld, L0, v0, (int)cols, L1, v1, (int)rows, f, p, stream)
-                             : prepare_pair_planes<false>(X, ld, L0, v0, (int)cols, L1, v1, (int)rows, f, p, stream);
+        const PrepPairItem it{X, ld, rows, cols, buf0, buf1};
+        return launch_prepare_pair_batch(1, &it, f, p, stream);
     }
     const int rc = launch_prepare_operand(X, ld, 0, rows, cols, f, p, buf0, stream);
     return rc != FMT_OK ? rc : launch_prepare_operand(X, ld, 1, cols, rows, f, p, buf1, stream);

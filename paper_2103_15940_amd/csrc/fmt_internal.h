@@ -68,6 +68,12 @@ int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, 
                            const QuantParams &p, void *buf, hipStream_t stream);
 int launch_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt_format_t f, const QuantParams &p, void *buf0,
                         void *buf1, hipStream_t stream);
+struct PrepPairItem {
+    const float *X;
+    int64_t ld, rows, cols;
+    void *buf0, *buf1;
+};
+int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_format_t f, const QuantParams &p, hipStream_t stream);
 int launch_gemm_prepared(const void *A, const void *B, int64_t M, int64_t N, int64_t K, int scheme, fmt_format_t f,
                          float *C, int64_t ldc, hipStream_t stream);
 // One product of a batch on prepared operands: C (M x N, leading dimension ldc) = A (M rows) B^T (N rows), both of k = K.

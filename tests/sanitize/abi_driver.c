@@ -106,6 +106,20 @@ int main(void)
         pb[0] = NULL;
         EXPECT(fmt_gemm_prepared_batch(2, pa, pb, pc, ld, NULL), FMT_ERR_NULL);      /* first product: no B */
     }
+    {
+        const float *px[2] = {x, x};
+        int64_t d2[2] = {4, 4}, r2[2] = {4, 4}, c2[2] = {4, 4};
+        void *pd[2] = {(void *)0x10000, (void *)0x20000}, *pt[2] = {(void *)0x30000, (void *)0x40000};
+        size_t nb[2] = {0, 0};
+        fmt_operand_t o2[2], t2[2];
+        EXPECT(fmt_prepare_pair_batch(0, NULL, NULL, NULL, NULL, f, NULL, NULL, NULL, NULL, NULL, NULL, NULL), FMT_OK);
+        EXPECT(fmt_prepare_pair_batch(-1, px, d2, r2, c2, f, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_SHAPE);
+        EXPECT(fmt_prepare_pair_batch(2, px, d2, r2, c2, f, pd, nb, NULL, pt, nb, t2, NULL), FMT_ERR_NULL);
+        EXPECT(fmt_prepare_pair_batch(2, px, d2, r2, c2, f, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_SHAPE);  /* buffers of 0 bytes */
+        c2[1] = 5;
+        nb[0] = nb[1] = (size_t)1 << 20;
+        EXPECT(fmt_prepare_pair_batch(2, px, d2, r2, c2, f, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_SHAPE);  /* ld < cols */
+    }
     /* convolutions */
     fmt_conv2d_t g = {1, 1, 4, 4, 1, 3, 3, 1, 1, 1, 1};
     EXPECT(fmt_conv2d_fwd(g, NULL, x, y, f, NULL), FMT_ERR_NULL);

@@ -272,3 +272,39 @@ def test_gemm_prepared_batch_validates_before_any_gpu_call():
     assert lib.fmt_gemm_prepared_batch(2, A1, B1, Cop, ld, None) == -6        # a result overlaps an operand
     A0 = (P * 2)(ctypes.pointer(a), None)
     assert lib.fmt_gemm_prepared_batch(2, A0, B1, C, ld, None) == -2
+
+
+def test_prepare_pair_batch_validates_before_any_gpu_call():
+    """fmt_prepare_pair_batch: count, NULL arrays and entries, small buffers and overlaps across matrices are
+    refused on a host without a GPU; an empty batch succeeds."""
+    import ctypes
+    lib = fmt.raw_library()
+    f = fmt._CFormat(6, 9, 1)
+    none = [None] * 4
+    assert lib.fmt_prepare_pair_batch(0, *none, f, None, None, None, None, None, None, None) == 0
+    assert lib.fmt_prepare_pair_batch(-1, *none, f, None, None, None, None, None, None, None) == -3
+    assert lib.fmt_prepare_pair_batch(5000, *none, f, None, None, None, None, None, None, None) == -3
+    assert lib.fmt_prepare_pair_batch(2, *none, f, None, None, None, None, None, None, None) == -2
+    n0, n1 = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.fmt_operand_bytes(64, 96, f, ctypes.byref(n0)) == 0 and lib.fmt_operand_bytes(96, 64, f, ctypes.byref(n1)) == 0
+    vp2, i2, s2 = ctypes.c_void_p * 2, ctypes.c_int64 * 2, ctypes.c_size_t * 2
+    X = vp2(1 << 30, 1 << 31)
+    ld, rows, cols = i2(96, 96), i2(64, 64), i2(96, 96)
+    data, data_t = vp2(1 << 40, 1 << 41), vp2(1 << 42, 1 << 43)
+    by, by_t = s2(n0.value, n0.value), s2(n1.value, n1.value)
+    op, op_t = (fmt._COperand * 2)(), (fmt._COperand * 2)()
+
+    def call(**kw):
+        a = dict(X=X, ld=ld, rows=rows, cols=cols, data=data, by=by, data_t=data_t, by_t=by_t)
+        a.update(kw)
+        return lib.fmt_prepare_pair_batch(2, a["X"], a["ld"], a["rows"], a["cols"], f, a["data"], a["by"], op, a["data_t"],
+                                          a["by_t"], op_t, None)
+
+    assert call(X=vp2(1 << 30, None)) == -2                                   # an entry without a matrix
+    assert call(by=s2(n0.value, n0.value - 1)) == -3                          # second matrix: buffer too small
+    assert call(ld=i2(96, 95)) == -3                                          # leading dimension below the columns
+    assert call(data=vp2(1 << 40, (1 << 40) + 256)) == -6                     # two matrices' operands overlap
+    assert call(data_t=vp2(1 << 42, (1 << 30) + 256)) == -6                   # an operand over the other matrix's input
+    assert call(data=vp2(1 << 40, (1 << 41) + 1)) == -4                       # alignment
+    assert lib.fmt_prepare_pair_batch(2, X, ld, rows, cols, fmt._CFormat(9, 9, 1), data, by, op, data_t, by_t, op_t, None) == -1
+

@@ -171,7 +171,7 @@ def test_growing_scratch_under_capture_is_refused(fmt):
 
 
 def test_prepare_and_batch_replays_match_eager(fmt):
-    """fmt_prepare_pair and fmt_gemm_prepared_batch in a graph: the shared product launch (with a member whose k
+    """fmt_prepare_pair, fmt_prepare_pair_batch and fmt_gemm_prepared_batch in a graph: the shared prepare launches, the shared product launch (with a member whose k
     runs in parts through library scratch), the sum of its parts and the shared tail launch, replayed three
     times on new tensor contents, bit for bit what the eager calls give."""
     dev = torch.device("cuda")
@@ -192,10 +192,8 @@ def test_prepare_and_batch_replays_match_eager(fmt):
             w.copy_(torch.from_numpy((r.standard_normal(tuple(w.shape)) * 0.02).astype(np.float32)))
 
     def calls():
-        A, B = [], []
-        for x, w, b in zip(X, W, bufs):
-            A.append(fmt.fmt_prepare_pair(x, f, out=b[0], out_t=b[1])[0])
-            B.append(fmt.fmt_prepare_pair(w, f, out=b[2], out_t=b[3])[0])
+        A = [fmt.fmt_prepare_pair(x, f, out=b[0], out_t=b[1])[0] for x, b in zip(X, bufs)]
+        B = [pair[0] for pair in fmt.fmt_prepare_pair_batch(W, f, outs=[b[2] for b in bufs], outs_t=[b[3] for b in bufs])]
         fmt.fmt_gemm_prepared_batch(A, B, out=C)
 
     fill(0)
