@@ -332,7 +332,7 @@ def main() -> int:
             "config4_gemm_gflop": round(cfg4_flops / 1e9, 1),
             "config3_gemm_shape": [M, N, K],
             "side_streams": len(side),
-            "products": "single fmt_gemm_prepared calls on the side streams" if args.no_batch else "one fmt_gemm_prepared_batch call per section",
+            "products": "one fmt_prepare_pair call per tensor and single fmt_gemm_prepared calls on the side streams" if args.no_batch else "one fmt_prepare_pair_batch call and one fmt_gemm_prepared_batch call per section",
         },
         "sections_ms": {"config5_stream": round(stream_ms, 4), "config4_quantize": round(cfg4_q_ms, 4),
                         "config4_gemms": round(cfg4_gemm_ms, 4), "config3_quantize": round(cfg3_q_ms, 4),
