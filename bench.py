@@ -499,6 +499,24 @@ def main() -> int:
             fmt.fmt_conv2d_wgrad(dY4d, X4d, W4d.shape, fv, out=dWc)
         by_format[name] = round(3 * 2.0 * M * N * K / (timed(conv_f, max(reps // 2, 1)) * 1e-3) / 1e12, 1)
     result["conv_config3"]["useful_tflops_by_format"] = by_format
+    # the operands of config 4's twelve tensors, both orientations each, by themselves: one fmt_prepare_pair_batch call
+    # (two launches) against one fmt_prepare_pair call per tensor; 8 algorithmic bytes per element (4 read, 2 + 2 written)
+    p4_keys = [(L, k) for L in layers for k in ("X", "W", "dY")]
+    p4_src = [L[k] for L, k in p4_keys]
+    p4_out, p4_out_t = [L["buf"][k][0] for L, k in p4_keys], [L["buf"][k][1] for L, k in p4_keys]
+    prep_ms = timed(lambda: fmt.fmt_prepare_pair_batch(p4_src, f169, outs=p4_out, outs_t=p4_out_t), reps)
+
+    def prepare_one_by_one():
+        for t, o, ot in zip(p4_src, p4_out, p4_out_t):
+            fmt.fmt_prepare_pair(t, f169, out=o, out_t=ot)
+    prep1_ms = timed(prepare_one_by_one, reps)
+    p4_bytes = 8.0 * sum(t.numel() for t in p4_src)
+    result["prepare_config4"] = {"workload": "fmt_prepare_pair_batch: both prepared orientations of config 4's 12 tensors "
+                                             "(X, W, dY of the four layers), 1/6/9/d, one call",
+                                 "ms": round(prep_ms, 4), "value": round(p4_bytes / (prep_ms * 1e-3) / 1e9, 1),
+                                 "unit": "GB/s (algorithmic: 4 B read + 2 + 2 B written per element; statistics launch included)",
+                                 "hbm_frac": round(p4_bytes / (prep_ms * 1e-3) / 1e9 / 8000.0, 3),
+                                 "single_calls_one_stream_ms": round(prep1_ms, 4)}
     # quantized Linear forward of the four encoder layers: product, bias, both output roundings, statistics of t
     biases = [torch.zeros(L["W"].shape[0], dtype=torch.float32, device=dev) for L in layers]
 
