@@ -20,10 +20,11 @@ One "step" is one pass of the whole hot path over one batch of synthetic, paper-
                                      14.8 GFLOP each)
 
 The rounding passes inside the configuration 4 and configuration 3 sections are independent of each other
-and are issued round-robin on three side streams (--gemm-streams): one fmt_prepare_pair_batch call that makes
-the operands of all the section's tensors, and one fmt_quantize call per tensor; the products of a section are
-handed to the library in one fmt_gemm_prepared_batch call (--no-batch: one fmt_prepare_pair call per tensor and
-one fmt_gemm_prepared call per product on the side streams).  The stream section runs on one stream.
+and are handed to the library in ONE fmt_quantize_prepare_pair_batch call per section (every tensor read once for
+its rounded copy, its statistics and both prepared orientations); the products of a section are handed over in
+one fmt_gemm_prepared_batch call (--no-batch: one fmt_quantize and one fmt_prepare_pair call per tensor and one
+fmt_gemm_prepared call per product, round-robin on three side streams, --gemm-streams).  The stream section runs
+on one stream.
 
 `value` is the quantize+histogram HBM rate of the stream section (GB/s, algorithmic bytes over
 the section's event-timed duration); the GEMM section's useful TFLOP/s and its MFMA fraction are
@@ -65,8 +66,8 @@ def main() -> int:
                          "a kernel of known traffic (4 B read + 4 B written per element) that calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters in rocprofv3 --pmc runs")
     ap.add_argument("--no-batch", action="store_true",
-                    help="configuration 4 and 3 sections: one fmt_prepare_pair call per tensor and one fmt_gemm_prepared call "
-                         "per product on the side streams instead of the batch calls")
+                    help="configuration 4 and 3 sections: one fmt_quantize and one fmt_prepare_pair call per tensor and one "
+                         "fmt_gemm_prepared call per product on the side streams instead of the batch calls")
     ap.add_argument("--gemm-streams", type=int, default=3,
                     help="side streams the independent calls of the configuration 4 and 3 sections are spread over")
     ap.add_argument("--gemm", default=None, metavar="M,N,K[,transA,transB[,e,m,d]]",
@@ -199,20 +200,12 @@ def main() -> int:
         # library scratch): the HBM-bound operand preparation of one product overlaps the MFMA-bound
         # kernel of another, and the small kernels between the large ones (statistics, sums of partial
         # records) stop being gaps.  The section ends when every side stream has been joined.
-        # alone_first: the first call keeps a side stream to itself (the long one of the section), the others
-        # share the remaining streams.
-        def fan_out(calls, alone_first=False):
+        def fan_out(calls):
             fork = ev()
             fork.record()
-            rest = len(side) - 1 if alone_first and len(side) > 1 else len(side)
             for j, call in enumerate(calls):
-                if alone_first and len(side) > 1:
-                    st_ = side[0] if j == 0 else side[1 + (j - 1) % rest]
-                    first_use = j <= rest
-                else:
-                    st_ = side[j % len(side)]
-                    first_use = j < len(side)
-                if first_use:
+                st_ = side[j % len(side)]
+                if j < len(side):
                     st_.wait_event(fork)
                 call(st_)
             for st_ in side[:min(len(side), len(calls))]:
@@ -226,13 +219,14 @@ def main() -> int:
             fmt.fmt_quantize(src, f169, out=dst, hist=hist, stream=st_)
             ops[key] = fmt.fmt_prepare_pair(src, f169, out=bufs[0], out_t=bufs[1], stream=st_)
 
-        # The same with the operands of all the section's tensors prepared by one call (shared launches), beside
-        # the tensors' statistics passes on the side streams.
-        def prepare_all(st_, entries):
-            pairs = fmt.fmt_prepare_pair_batch([e[0] for e in entries], f169, outs=[e[1][0] for e in entries],
-                                               outs_t=[e[1][1] for e in entries], stream=st_)
-            for (_, _, ops, key), pair in zip(entries, pairs):
-                ops[key] = pair
+        # The same for all the section's tensors in ONE call: every tensor is read once for its rounded copy, its
+        # statistics and both prepared orientations (shared launches).
+        def round_all(entries):
+            pairs = fmt.fmt_quantize_prepare_pair_batch([e[0] for e in entries], f169, [e[1] for e in entries],
+                                                        [e[2] for e in entries], outs=[e[3][0] for e in entries],
+                                                        outs_t=[e[3][1] for e in entries])
+            for e, pair in zip(entries, pairs):
+                e[4][e[5]] = pair
 
         q4, p4 = [], []
         for L in layers:                                                     # configuration 4, rounding passes
@@ -241,12 +235,11 @@ def main() -> int:
                     q4.append(lambda st_, L=L, src=src, dst=dst, hi=hi:
                               round_tensor(st_, L[src], L[dst], L["h"][hi], L["buf"][src], L["op"], src))
                 else:
-                    p4.append((L[src], L["buf"][src], L["op"], src))
-                    q4.append(lambda st_, L=L, src=src, dst=dst, hi=hi:
-                              fmt.fmt_quantize(L[src], f169, out=L[dst], hist=L["h"][hi], stream=st_))
-        if p4:
-            q4.insert(0, lambda st_: prepare_all(st_, p4))
-        fan_out(q4, alone_first=bool(p4))
+                    p4.append((L[src], L[dst], L["h"][hi], L["buf"][src], L["op"], src))
+        if args.no_batch:
+            fan_out(q4)
+        else:
+            round_all(p4)
         mark()
         if args.no_batch:                                                    # configuration 4, products
             g4 = []
@@ -264,11 +257,8 @@ def main() -> int:
                      lambda st_: round_tensor(st_, w, w_q, hists[7], c3["buf"]["W"], c3["op"], "W"),
                      lambda st_: round_tensor(st_, dy, dy_q, hists[8], c3["buf"]["dY"], c3["op"], "dY")])
         else:
-            p3 = [(xcol, c3["buf"]["X"], c3["op"], "X"), (w, c3["buf"]["W"], c3["op"], "W"), (dy, c3["buf"]["dY"], c3["op"], "dY")]
-            fan_out([lambda st_: prepare_all(st_, p3),
-                     lambda st_: fmt.fmt_quantize(xcol, f169, out=xcol_q, hist=hists[6], stream=st_),
-                     lambda st_: fmt.fmt_quantize(w, f169, out=w_q, hist=hists[7], stream=st_),
-                     lambda st_: fmt.fmt_quantize(dy, f169, out=dy_q, hist=hists[8], stream=st_)], alone_first=True)
+            round_all([(xcol, xcol_q, hists[6], c3["buf"]["X"], c3["op"], "X"), (w, w_q, hists[7], c3["buf"]["W"], c3["op"], "W"),
+                       (dy, dy_q, hists[8], c3["buf"]["dY"], c3["op"], "dY")])
         mark()
         o3 = c3["op"]
         if args.no_batch:
@@ -332,7 +322,7 @@ def main() -> int:
             "config4_gemm_gflop": round(cfg4_flops / 1e9, 1),
             "config3_gemm_shape": [M, N, K],
             "side_streams": len(side),
-            "products": "one fmt_prepare_pair call per tensor and single fmt_gemm_prepared calls on the side streams" if args.no_batch else "one fmt_prepare_pair_batch call and one fmt_gemm_prepared_batch call per section",
+            "products": "one fmt_prepare_pair call per tensor and single fmt_gemm_prepared calls on the side streams" if args.no_batch else "one fmt_quantize_prepare_pair_batch call and one fmt_gemm_prepared_batch call per section",
         },
         "sections_ms": {"config5_stream": round(stream_ms, 4), "config4_quantize": round(cfg4_q_ms, 4),
                         "config4_gemms": round(cfg4_gemm_ms, 4), "config3_quantize": round(cfg3_q_ms, 4),
@@ -517,6 +507,16 @@ def main() -> int:
                                  "unit": "GB/s (algorithmic: 4 B read + 2 + 2 B written per element; statistics launch included)",
                                  "hbm_frac": round(p4_bytes / (prep_ms * 1e-3) / 1e9 / 8000.0, 3),
                                  "single_calls_one_stream_ms": round(prep1_ms, 4)}
+    # the whole rounding pass over the same tensors (rounded fp32 copy + statistics + both orientations) in one call:
+    # 12 algorithmic bytes per element (4 read, 4 + 2 + 2 written)
+    p4_q = [L[k] for L in layers for k in ("Xq", "Wq", "dYq")]
+    p4_h = [L["h"][i] for L in layers for i in range(3)]
+    round_ms = timed(lambda: fmt.fmt_quantize_prepare_pair_batch(p4_src, f169, p4_q, p4_h, outs=p4_out, outs_t=p4_out_t), reps)
+    result["round_config4"] = {"workload": "fmt_quantize_prepare_pair_batch: rounded fp32 copy, statistics and both prepared "
+                                           "orientations of config 4's 12 tensors, 1/6/9/d, one call",
+                               "ms": round(round_ms, 4), "value": round(1.5 * p4_bytes / (round_ms * 1e-3) / 1e9, 1),
+                               "unit": "GB/s (algorithmic: 4 B read + 4 + 2 + 2 B written per element; statistics launches included)",
+                               "hbm_frac": round(1.5 * p4_bytes / (round_ms * 1e-3) / 1e9 / 8000.0, 3)}
     # quantized Linear forward of the four encoder layers: product, bias, both output roundings, statistics of t
     biases = [torch.zeros(L["W"].shape[0], dtype=torch.float32, device=dev) for L in layers]
 

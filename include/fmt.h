@@ -24,8 +24,8 @@
  *                  used for fully connected layers and im2col convolutions in forward,
  *                  dgrad and wgrad (Sec. IV-A)
  * and, beyond these three:
- *   fmt_operand_bytes / fmt_prepare / fmt_prepare_pair / fmt_prepare_pair_batch / fmt_gemm_prepared /
- *   fmt_gemm_prepared_batch / fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
+ *   fmt_operand_bytes / fmt_prepare / fmt_prepare_pair / fmt_prepare_pair_batch / fmt_quantize_prepare_pair_batch /
+ *   fmt_gemm_prepared / fmt_gemm_prepared_batch / fmt_linear_prepared   fmt_gemm (and fmt_linear) in two steps: a tensor is rounded once
  *                  into a reusable operand in caller-owned memory (Sec. IV-A rounds each tensor once and
  *                  uses it in several products), and products run on two such operands
  *   fmt_gemm_fmac8 the same product with the FMAC-8 accumulation of Algorithm 1 (Sec. IV-A)
@@ -277,6 +277,23 @@ int fmt_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, fmt
 int fmt_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *ld, const int64_t *rows, const int64_t *cols,
                            fmt_format_t f, void *const *data, const size_t *bytes, fmt_operand_t *op,
                            void *const *data_t, const size_t *bytes_t, fmt_operand_t *op_t, void *stream);
+/*
+ * fmt_quantize_prepare_pair_batch -- the whole rounding pass of Sec. IV-A over `count` matrices in one call: for
+ * matrix i what fmt_quantize gives (the rounded values as fp32 in Y[i], leading dimension ldy[i] >= cols[i]; the
+ * statistics of Sec. V in the DEVICE record hist[i], window exp_lo .. exp_lo + 63) and what fmt_prepare_pair_batch
+ * gives (both prepared orientations), from ONE read of X[i].  Formats whose prepared operands are exponent planes
+ * only (1/6/m); other formats -> FMT_ERR_FORMAT (use fmt_quantize and fmt_prepare_pair_batch).  Y[i] may be X[i]
+ * (same address and leading dimension: in place); otherwise nothing written may overlap anything else of the call
+ * (FMT_ERR_ALIAS).  Arrays are HOST arrays of `count` entries; Y[i], hist[i], data[i], data_t[i] DEVICE pointers
+ * (hist[i] 8-byte aligned).  Other arguments and errors as for fmt_prepare_pair_batch; FMT_ERR_RANGE for exp_lo as
+ * for fmt_quantize.  Uses the stream's library scratch for the partial statistics records (576 KiB, allocated on
+ * first use: not inside a stream capture before a first eager call on that stream).
+ */
+int fmt_quantize_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *ld, const int64_t *rows,
+                                    const int64_t *cols, fmt_format_t f, float *const *Y, const int64_t *ldy,
+                                    fmt_hist_t *const *hist, int32_t exp_lo, void *const *data, const size_t *bytes,
+                                    fmt_operand_t *op, void *const *data_t, const size_t *bytes_t, fmt_operand_t *op_t,
+                                    void *stream);
 int fmt_gemm_prepared(const fmt_operand_t *A, const fmt_operand_t *B, float *C, int64_t ldc, void *stream);
 
 /*

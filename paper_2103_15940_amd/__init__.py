@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("FMT_LIB_PATH") or os.path.join(_HERE, "libfmt.so")
 FMT_NBINS = 64
 EXP_LO_DEFAULT = -48
 CLASS_NAMES = ("total", "zero", "underflow", "denormal", "normal", "overflow", "inf", "nan")
-EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_prepare_pair", "fmt_prepare_pair_batch", "fmt_gemm_prepared", "fmt_gemm_prepared_batch", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
+EXPORTS = ("fmt_quantize", "fmt_quantize_static", "fmt_histogram", "fmt_gemm", "fmt_operand_bytes", "fmt_prepare", "fmt_prepare_pair", "fmt_prepare_pair_batch", "fmt_quantize_prepare_pair_batch", "fmt_gemm_prepared", "fmt_gemm_prepared_batch", "fmt_linear_prepared", "fmt_gemm_fmac8", "fmt_linear", "fmt_pack16", "fmt_unpack16", "fmt_linear_pack16", "fmt_conv2d_fwd", "fmt_conv2d_dgrad", "fmt_conv2d_wgrad", "fmt_dls_init", "fmt_dls_step", "fmt_format_info", "fmt_format_thresholds",
            "fmt_scratch_bytes", "fmt_release_scratch", "fmt_status_string")
 
 
@@ -103,6 +103,12 @@ def _load() -> ctypes.CDLL:
                                            _CFormat, ctypes.POINTER(vp), ctypes.POINTER(sz), ctypes.POINTER(_COperand),
                                            ctypes.POINTER(vp), ctypes.POINTER(sz), ctypes.POINTER(_COperand), vp]
     lib.fmt_prepare_pair_batch.restype = ctypes.c_int
+    lib.fmt_quantize_prepare_pair_batch.argtypes = [i64, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                                    ctypes.POINTER(i64), _CFormat, ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                                    ctypes.POINTER(vp), i32, ctypes.POINTER(vp), ctypes.POINTER(sz),
+                                                    ctypes.POINTER(_COperand), ctypes.POINTER(vp), ctypes.POINTER(sz),
+                                                    ctypes.POINTER(_COperand), vp]
+    lib.fmt_quantize_prepare_pair_batch.restype = ctypes.c_int
     lib.fmt_gemm_prepared.argtypes = [ctypes.POINTER(_COperand), ctypes.POINTER(_COperand), vp, i64, vp]
     lib.fmt_gemm_prepared.restype = ctypes.c_int
     lib.fmt_gemm_prepared_batch.argtypes = [i64, ctypes.POINTER(ctypes.POINTER(_COperand)),
@@ -327,12 +333,9 @@ def fmt_prepare_pair(X, fmt, out=None, out_t=None, stream=None):
     return PreparedOperand(bufs[0], d0), PreparedOperand(bufs[1], d1)
 
 
-def fmt_prepare_pair_batch(Xs, fmt, outs=None, outs_t=None, stream=None):
-    """:func:`fmt_prepare_pair` for a sequence of 2-D float32 GPU tensors in one call (shared launches for the
-    1/6/m formats).  ``outs`` / ``outs_t``: optional sequences of uint8 GPU tensors to prepare into.  Returns a
-    list of (X as stored, X transposed) operand pairs."""
+def _pair_batch_args(Xs, fmt, outs, outs_t):
+    """Checks and marshals what the two batch prepare calls share: the matrices and the operand buffers."""
     import torch
-    Xs = list(Xs)
     n = len(Xs)
     outs = [None] * n if outs is None else list(outs)
     outs_t = [None] * n if outs_t is None else list(outs_t)
@@ -354,24 +357,69 @@ def fmt_prepare_pair_batch(Xs, fmt, outs=None, outs_t=None, stream=None):
         bufs.append(pair[0])
         bufs_t.append(pair[1])
     m = max(n, 1)
-    xp = (ctypes.c_void_p * m)(*[X.data_ptr() for X in Xs])
-    ld = (ctypes.c_int64 * m)(*[X.stride(0) if X.shape[0] > 1 else max(X.shape[1], 1) for X in Xs])
-    rows = (ctypes.c_int64 * m)(*[X.shape[0] for X in Xs])
-    cols = (ctypes.c_int64 * m)(*[X.shape[1] for X in Xs])
-    dp = (ctypes.c_void_p * m)(*[b.data_ptr() for b in bufs])
-    db = (ctypes.c_size_t * m)(*[b.numel() for b in bufs])
-    tp = (ctypes.c_void_p * m)(*[b.data_ptr() for b in bufs_t])
-    tb = (ctypes.c_size_t * m)(*[b.numel() for b in bufs_t])
-    d0, d1 = (_COperand * m)(), (_COperand * m)()
-    rc = _lib.fmt_prepare_pair_batch(n, xp, ld, rows, cols, _cfmt(fmt), dp, db, d0, tp, tb, d1, _stream_ptr(stream))
-    _check(rc, "fmt_prepare_pair_batch")
+    c = {
+        "X": (ctypes.c_void_p * m)(*[X.data_ptr() for X in Xs]),
+        "ld": (ctypes.c_int64 * m)(*[X.stride(0) if X.shape[0] > 1 else max(X.shape[1], 1) for X in Xs]),
+        "rows": (ctypes.c_int64 * m)(*[X.shape[0] for X in Xs]),
+        "cols": (ctypes.c_int64 * m)(*[X.shape[1] for X in Xs]),
+        "data": (ctypes.c_void_p * m)(*[b.data_ptr() for b in bufs]),
+        "bytes": (ctypes.c_size_t * m)(*[b.numel() for b in bufs]),
+        "data_t": (ctypes.c_void_p * m)(*[b.data_ptr() for b in bufs_t]),
+        "bytes_t": (ctypes.c_size_t * m)(*[b.numel() for b in bufs_t]),
+        "op": (_COperand * m)(), "op_t": (_COperand * m)(),
+    }
+    return bufs, bufs_t, c
+
+
+def _pair_batch_result(n, bufs, bufs_t, c):
     result = []
     for i in range(n):
         a, b = _COperand(), _COperand()
-        ctypes.memmove(ctypes.byref(a), ctypes.byref(d0[i]), ctypes.sizeof(_COperand))
-        ctypes.memmove(ctypes.byref(b), ctypes.byref(d1[i]), ctypes.sizeof(_COperand))
+        ctypes.memmove(ctypes.byref(a), ctypes.byref(c["op"][i]), ctypes.sizeof(_COperand))
+        ctypes.memmove(ctypes.byref(b), ctypes.byref(c["op_t"][i]), ctypes.sizeof(_COperand))
         result.append((PreparedOperand(bufs[i], a), PreparedOperand(bufs_t[i], b)))
     return result
+
+
+def fmt_prepare_pair_batch(Xs, fmt, outs=None, outs_t=None, stream=None):
+    """:func:`fmt_prepare_pair` for a sequence of 2-D float32 GPU tensors in one call (shared launches for the
+    1/6/m formats).  ``outs`` / ``outs_t``: optional sequences of uint8 GPU tensors to prepare into.  Returns a
+    list of (X as stored, X transposed) operand pairs."""
+    Xs = list(Xs)
+    bufs, bufs_t, c = _pair_batch_args(Xs, fmt, outs, outs_t)
+    rc = _lib.fmt_prepare_pair_batch(len(Xs), c["X"], c["ld"], c["rows"], c["cols"], _cfmt(fmt), c["data"], c["bytes"], c["op"],
+                                     c["data_t"], c["bytes_t"], c["op_t"], _stream_ptr(stream))
+    _check(rc, "fmt_prepare_pair_batch")
+    return _pair_batch_result(len(Xs), bufs, bufs_t, c)
+
+
+def fmt_quantize_prepare_pair_batch(Xs, fmt, Ys, hists, exp_lo: int = EXP_LO_DEFAULT, outs=None, outs_t=None, stream=None):
+    """The rounding pass over a sequence of 2-D float32 GPU tensors in one call (1/6/m formats): ``Ys[i]`` receives
+    ``Xs[i]`` rounded to the format (as :func:`fmt_quantize` gives it; may be ``Xs[i]`` itself), ``hists[i]`` (from
+    :func:`new_hist`) its statistics, and the result is the list of (X as stored, X transposed) operand pairs of
+    :func:`fmt_prepare_pair_batch` -- every tensor is read once."""
+    Xs, Ys, hists = list(Xs), list(Ys), list(hists)
+    n = len(Xs)
+    if len(Ys) != n or len(hists) != n:
+        raise ValueError("Ys and hists must be as long as Xs")
+    for X, Y in zip(Xs, Ys):
+        _dev_f32(Y, "Y")
+        if Y.dim() != 2 or tuple(Y.shape) != tuple(X.shape) or (Y.shape[1] > 1 and Y.stride(1) != 1):
+            raise ValueError("every Y must have the shape of its X and unit column stride")
+    import torch
+    for h in hists:
+        if not isinstance(h, torch.Tensor) or h.dtype != torch.int64 or h.numel() != 8 + FMT_NBINS or not h.is_cuda:
+            raise TypeError("every hist must be a GPU int64 tensor of 72 elements")
+    bufs, bufs_t, c = _pair_batch_args(Xs, fmt, outs, outs_t)
+    m = max(n, 1)
+    yp = (ctypes.c_void_p * m)(*[Y.data_ptr() for Y in Ys])
+    ldy = (ctypes.c_int64 * m)(*[Y.stride(0) if Y.shape[0] > 1 else max(Y.shape[1], 1) for Y in Ys])
+    hp = (ctypes.c_void_p * m)(*[h.data_ptr() for h in hists])
+    rc = _lib.fmt_quantize_prepare_pair_batch(n, c["X"], c["ld"], c["rows"], c["cols"], _cfmt(fmt), yp, ldy, hp, int(exp_lo),
+                                              c["data"], c["bytes"], c["op"], c["data_t"], c["bytes_t"], c["op_t"],
+                                              _stream_ptr(stream))
+    _check(rc, "fmt_quantize_prepare_pair_batch")
+    return _pair_batch_result(n, bufs, bufs_t, c)
 
 
 def fmt_gemm_prepared(A: PreparedOperand, B: PreparedOperand, out=None, stream=None):

@@ -330,7 +330,64 @@ int fmt_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *
                 overlap(data_t[i], need_t[i], data_t[j], need_t[j]))
                 return FMT_ERR_ALIAS;
         }
-    rc = launch_prepare_pair_batch(count, items.data(), f, p, static_cast<hipStream_t>(stream));
+    rc = launch_prepare_pair_batch(count, items.data(), f, p, static_cast<hipStream_t>(stream), nullptr);
+    if (rc != FMT_OK) return rc;
+    for (int64_t i = 0; i < count; ++i) {
+        op[i] = fmt_operand_t{data[i], bytes[i], rows[i], cols[i], f, scheme[i]};
+        op_t[i] = fmt_operand_t{data_t[i], bytes_t[i], cols[i], rows[i], f, scheme_t[i]};
+    }
+    return FMT_OK;
+}
+
+int fmt_quantize_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *ld, const int64_t *rows,
+                                    const int64_t *cols, fmt_format_t f, float *const *Y, const int64_t *ldy,
+                                    fmt_hist_t *const *hist, int32_t exp_lo, void *const *data, const size_t *bytes,
+                                    fmt_operand_t *op, void *const *data_t, const size_t *bytes_t, fmt_operand_t *op_t,
+                                    void *stream)
+{
+    QuantParams p;
+    int rc = make_quant_params(f, exp_lo, &p);
+    if (rc != FMT_OK) return rc;
+    if (count < 0 || count > 4096) return FMT_ERR_SHAPE;
+    if (count == 0) return FMT_OK;
+    if (!X || !ld || !rows || !cols || !Y || !ldy || !hist || !data || !bytes || !op || !data_t || !bytes_t || !op_t)
+        return FMT_ERR_NULL;
+    std::vector<PrepPairItem> items((size_t)count);
+    std::vector<RoundItem> round((size_t)count);
+    std::vector<size_t> need((size_t)count), need_t((size_t)count), xbytes((size_t)count), ybytes((size_t)count);
+    std::vector<int> scheme((size_t)count), scheme_t((size_t)count);
+    const int64_t lim = (int64_t)1 << 31;
+    for (int64_t i = 0; i < count; ++i) {
+        rc = check_pair(X[i], ld[i], rows[i], cols[i], f, data[i], bytes[i], data_t[i], bytes_t[i], &need[i], &scheme[i],
+                        &need_t[i], &scheme_t[i]);
+        if (rc != FMT_OK) return rc;
+        if (!Y[i] || !hist[i]) return FMT_ERR_NULL;
+        if (ldy[i] < cols[i] || ldy[i] >= lim) return FMT_ERR_SHAPE;
+        if (!aligned(Y[i], 4) || !aligned(hist[i], 8)) return FMT_ERR_ALIGN;
+        xbytes[i] = 4 * (size_t)((rows[i] - 1) * ld[i] + cols[i]);
+        ybytes[i] = 4 * (size_t)((rows[i] - 1) * ldy[i] + cols[i]);
+        // in place (same address, same leading dimension) is fine: an element is read and written by one thread
+        if (!(Y[i] == X[i] && ldy[i] == ld[i]) && overlap(Y[i], ybytes[i], X[i], xbytes[i])) return FMT_ERR_ALIAS;
+        if (overlap(Y[i], ybytes[i], data[i], need[i]) || overlap(Y[i], ybytes[i], data_t[i], need_t[i]) ||
+            overlap(hist[i], sizeof(fmt_hist_t), Y[i], ybytes[i]) || overlap(hist[i], sizeof(fmt_hist_t), data[i], need[i]) ||
+            overlap(hist[i], sizeof(fmt_hist_t), data_t[i], need_t[i]))
+            return FMT_ERR_ALIAS;
+        items[i] = PrepPairItem{X[i], ld[i], rows[i], cols[i], data[i], data_t[i]};
+        round[i] = RoundItem{Y[i], ldy[i], hist[i]};
+    }
+    // nothing written for one matrix may lie over anything of another
+    for (int64_t i = 0; i < count; ++i)
+        for (int64_t j = 0; j < count; ++j) {
+            if (j == i) continue;
+            const void *out[4] = {data[i], data_t[i], Y[i], hist[i]};
+            const size_t outb[4] = {need[i], need_t[i], ybytes[i], sizeof(fmt_hist_t)};
+            const void *other[5] = {X[j], data[j], data_t[j], Y[j], hist[j]};
+            const size_t otherb[5] = {xbytes[j], need[j], need_t[j], ybytes[j], sizeof(fmt_hist_t)};
+            for (int a = 0; a < 4; ++a)
+                for (int b = 0; b < 5; ++b)
+                    if (overlap(out[a], outb[a], other[b], otherb[b])) return FMT_ERR_ALIAS;
+        }
+    rc = launch_prepare_pair_batch(count, items.data(), f, p, static_cast<hipStream_t>(stream), round.data());
     if (rc != FMT_OK) return rc;
     for (int64_t i = 0; i < count; ++i) {
         op[i] = fmt_operand_t{data[i], bytes[i], rows[i], cols[i], f, scheme[i]};

@@ -43,6 +43,7 @@
 #include <type_traits>
 #include <vector>
 
+#include "fmt_hist.h"
 #include "fmt_internal.h"
 #include "fmt_quant.h"
 
@@ -823,8 +824,14 @@ __device__ __forceinline__ void prepare_scaled_block(const OP &o, int K, int kbl
 // is worked on (measured: two tiles 2 - 4 % faster than one, four slower than two).
 constexpr int kPairTiles = 2;
 
-template <int MODE, bool FTZ, class OP>
-__device__ __forceinline__ void prepare_pair_tile(const OP &o0, const OP &o1, const QuantParams &p, int ty, int tx0)
+// ROUND: the pass also does what fmt_quantize does with the tensor -- the rounded values go to Y (leading
+// dimension ldy) as fp32 and every element of X is counted in the workgroup's statistics table (tbl, w).
+constexpr int kPairCopies = 8;                          // replicas of the statistics table (lane l uses l % 8)
+constexpr int kRoundSteps = 4;                          // steps of kPairTiles tiles per workgroup of a ROUND launch
+
+template <int MODE, bool FTZ, bool ROUND, bool DEEP, class OP>
+__device__ __forceinline__ void prepare_pair_tile(const OP &o0, const OP &o1, const QuantParams &p, int ty, int tx0,
+                                                  uint32_t *Y, int64_t ldy, uint32_t *tbl, Counts &w)
 {
     __shared__ __align__(16) uint32_t s_r[32][68];      // 68: rows stay 16-byte aligned, 128-bit writes spread over all banks
     __shared__ uint32_t s_planes[4 * kPairTiles];       // per tile: o0's two units (halves of k), then o1's two (halves of its rows)
@@ -856,6 +863,23 @@ __device__ __forceinline__ void prepare_pair_tile(const OP &o0, const OP &o1, co
         uint32_t r[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) r[j] = quantize_bits<MODE, FTZ>(v[n][j], p);
+        if constexpr (ROUND) {
+            const bool row_ok = xr < R;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                account<DEEP, kPairCopies>(v[n][j] & 0x7FFFFFFFu, row_ok && xc + j < C, p, tbl, (uint32_t)tid % kPairCopies, w);
+            if (row_ok) {
+                uint32_t *dstY = Y + (size_t)xr * ldy + xc;
+                if (xc + 8 <= C && ((reinterpret_cast<uintptr_t>(Y) | (uintptr_t)(ldy * 4)) & 15) == 0) {
+                    __builtin_nontemporal_store(u32x4{r[0], r[1], r[2], r[3]}, reinterpret_cast<u32x4 *>(dstY));
+                    __builtin_nontemporal_store(u32x4{r[4], r[5], r[6], r[7]}, reinterpret_cast<u32x4 *>(dstY) + 1);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (xc + j < C) dstY[j] = r[j];
+                }
+            }
+        }
         // (the reads of the tile before this one ended before that tile's second barrier)
         u32x4 *dst = reinterpret_cast<u32x4 *>(&s_r[tid / 8][(tid % 8) * 8]);
         dst[0] = u32x4{r[0], r[1], r[2], r[3]};
@@ -941,20 +965,43 @@ __device__ __forceinline__ int run_of(const unsigned (&first)[CAP], unsigned id)
     return at;
 }
 
-template <int MODE, bool FTZ>
-__global__ __launch_bounds__(256) void prepare_scaled_group_kernel(PrepGroup grp, QuantParams p)
+// what the ROUND variant needs of every matrix: the rounded fp32 copy and the partial statistics records
+struct RoundGroup {
+    uint32_t *Y[kMaxPrepGroup / 2];
+    int64_t ldy[kMaxPrepGroup / 2];
+    unsigned long long *partials[kMaxPrepGroup / 2];
+};
+
+template <int MODE, bool FTZ, bool ROUND, bool DEEP>
+__global__ __launch_bounds__(256) void prepare_scaled_group_kernel(PrepGroup grp, RoundGroup rg, QuantParams p)
 {
+    __shared__ __align__(16) uint32_t tbl[ROUND ? kHistRows * kPairCopies : 4];
+    __shared__ uint32_t s_bins[ROUND ? FMT_NBINS : 1], s_cls[ROUND ? 8 : 1];
     const int at = run_of(grp.first, blockIdx.x);
     const PrepPlain &o0 = grp.o[2 * at], &o1 = grp.o[2 * at + 1];
+    // ROUND: a workgroup takes kRoundSteps consecutive steps of kPairTiles tiles, so that clearing and folding its
+    // statistics table is paid once per 16 K elements (as in the stream kernels)
+    constexpr unsigned kSteps = ROUND ? (unsigned)kRoundSteps : 1u;
     const unsigned lid = blockIdx.x - grp.first[at], ntiles = grp.tiles[at];
-    const unsigned per_xcd = (ntiles + 7u) / 8u;
-    const unsigned t = (lid % 8u) * per_xcd + lid / 8u;
-    if (t >= ntiles) return;                     // workgroup-uniform: before any barrier
+    const unsigned nwg = (ntiles + kSteps - 1u) / kSteps;
+    const unsigned per_xcd = (nwg + 7u) / 8u;
+    const unsigned g = (lid % 8u) * per_xcd + lid / 8u;
+    if (g >= nwg) return;                        // workgroup-uniform: before any barrier
     // rows of X in 32s: o0's units (rows padded to the tile grid) cover o1's k-blocks; columns of X in 64s:
     // pairs of o1's units cover o0's slabs of two k-blocks
     const int ntx = o1.units / (2 * kPairTiles);
-    const int ty = (int)(t / (unsigned)ntx), tx = (int)(t % (unsigned)ntx) * kPairTiles;
-    prepare_pair_tile<MODE, FTZ>(o0, o1, p, ty, tx);
+    Counts w;
+    if constexpr (ROUND) hist_begin<kPairCopies, 256>(tbl, s_bins, s_cls, threadIdx.x);
+#pragma unroll 1
+    for (unsigned step = 0; step < kSteps; ++step) {
+        const unsigned t = g * kSteps + step;
+        if (t >= ntiles) break;                  // workgroup-uniform
+        if (step > 0) __syncthreads();           // the step before has read its words of LDS
+        const int ty = (int)(t / (unsigned)ntx), tx = (int)(t % (unsigned)ntx) * kPairTiles;
+        prepare_pair_tile<MODE, FTZ, ROUND, DEEP>(o0, o1, p, ty, tx, ROUND ? rg.Y[at] : nullptr, ROUND ? rg.ldy[at] : 0, tbl, w);
+    }
+    if constexpr (ROUND)
+        hist_end<kPairCopies, 256>(tbl, s_bins, s_cls, w, p, rg.partials[at], blockIdx.x % kShards, threadIdx.x);
 }
 
 // Epilogue of one wave.  The MFMAs are fed operand B's fragment first and A's second, so a 32 x 32 accumulator
@@ -2305,13 +2352,28 @@ int launch_prepare_operand(const float *X, int64_t ld, int trans, int64_t rows, 
 // statistics launch and one prepare launch; the others are prepared operand by operand.  The operands equal
 // those of two launch_prepare_operand calls (the same block functions on the same blocks; only the order of
 // the records within a list may differ, which the product's tail sorts away).
-static_assert(sizeof(PrepGroup) + sizeof(QuantParams) <= 4096 && sizeof(StatGroup) + 8 <= 4096,
+// round != nullptr: the same launch also writes every matrix rounded to fp32 (round[i].Y) and counts its elements
+// into round[i].hist, as fmt_quantize does (window from p.exp_lo); planes formats only (FMT_ERR_FORMAT otherwise).
+static_assert(sizeof(PrepGroup) + sizeof(RoundGroup) + sizeof(QuantParams) <= 4096 && sizeof(StatGroup) + 8 <= 4096,
               "group tables travel in the kernel arguments");
 
-int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_format_t f, const QuantParams &p, hipStream_t stream)
+int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_format_t f, const QuantParams &p, hipStream_t stream,
+                              const RoundItem *round)
 {
     StatGroup sg;
     PrepGroup pg;
+    RoundGroup rg{};
+    FinalizeGroup fg{};
+    unsigned long long *records = nullptr;
+    if (round != nullptr) {
+        for (int64_t i = 0; i < count; ++i)
+            if (!(api_scheme(f, items[i].cols).scaled && api_scheme(f, items[i].rows).scaled && p.mode == kModeMagic))
+                return FMT_ERR_FORMAT;
+        Scratch sc;
+        const int rc = get_scratch(stream, (size_t)(kMaxPrepGroup / 2) * kHistScratchBytes, 0, &sc);
+        if (rc != FMT_OK) return rc;
+        records = static_cast<unsigned long long *>(sc.hist_partials);
+    }
     int n = 0;
     unsigned stat_ids = 0, prep_ids = 0;
     const int bias = (1 << (f.e - 1)) - 1;
@@ -2329,11 +2391,23 @@ int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_form
         }
         hipLaunchKernelGGL(window_stats_group_kernel, dim3(stat_ids), dim3(256), 0, stream, sg, 1 - bias, f.m);
         FMT_HIP_CHECK(hipGetLastError());
-        if (f.denorm == 0)
-            hipLaunchKernelGGL((prepare_scaled_group_kernel<kModeMagic, true>), dim3(prep_ids), dim3(256), 0, stream, pg, p);
-        else
-            hipLaunchKernelGGL((prepare_scaled_group_kernel<kModeMagic, false>), dim3(prep_ids), dim3(256), 0, stream, pg, p);
+#define FMT_PAIR_LAUNCH(FTZV, ROUNDV, DEEPV)                                                                           \
+    hipLaunchKernelGGL((prepare_scaled_group_kernel<kModeMagic, FTZV, ROUNDV, DEEPV>), dim3(prep_ids), dim3(256), 0, stream, pg, \
+                       rg, p)
+        const bool ftz = f.denorm == 0, deep = p.exp_lo < -126;
+        if (round == nullptr) {
+            if (ftz) FMT_PAIR_LAUNCH(true, false, false); else FMT_PAIR_LAUNCH(false, false, false);
+        } else if (deep) {
+            if (ftz) FMT_PAIR_LAUNCH(true, true, true); else FMT_PAIR_LAUNCH(false, true, true);
+        } else {
+            if (ftz) FMT_PAIR_LAUNCH(true, true, false); else FMT_PAIR_LAUNCH(false, true, false);
+        }
+#undef FMT_PAIR_LAUNCH
         FMT_HIP_CHECK(hipGetLastError());
+        if (round != nullptr) {
+            const int rc = launch_hist_finalize_group(fg, n / 2, stream);     // sums and clears the records
+            if (rc != FMT_OK) return rc;
+        }
         n = 0;
         stat_ids = prep_ids = 0;
         return FMT_OK;
@@ -2389,7 +2463,17 @@ int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_form
         const unsigned tiles = (unsigned)L0.units * (unsigned)(L1.units / (2 * kPairTiles));
         pg.first[n / 2] = prep_ids;
         pg.tiles[n / 2] = tiles;
-        prep_ids += (tiles + 7u) / 8u * 8u;
+        if (round != nullptr) {
+            const int slot = n / 2;
+            rg.Y[slot] = reinterpret_cast<uint32_t *>(round[i].Y);
+            rg.ldy[slot] = round[i].ldy;
+            rg.partials[slot] = records + (size_t)slot * kShards * kSlots;
+            fg.partials[slot] = rg.partials[slot];
+            fg.n[slot] = (unsigned long long)it.rows * (unsigned long long)it.cols;
+            fg.hist[slot] = reinterpret_cast<unsigned long long *>(round[i].hist);
+        }
+        const unsigned steps = round != nullptr ? (unsigned)kRoundSteps : 1u;
+        prep_ids += ((tiles + steps - 1u) / steps + 7u) / 8u * 8u;
         add(it, true, L0, view_of(it.buf0, L0), (int)it.cols);
         add(it, false, L1, view_of(it.buf1, L1), (int)it.rows);
     }
@@ -2405,7 +2489,7 @@ int launch_prepare_pair(const float *X, int64_t ld, int64_t rows, int64_t cols, 
     const Scheme s0 = api_scheme(f, cols), s1 = api_scheme(f, rows);
     if (s0.scaled && s1.scaled && p.mode == kModeMagic) {
         const PrepPairItem it{X, ld, rows, cols, buf0, buf1};
-        return launch_prepare_pair_batch(1, &it, f, p, stream);
+        return launch_prepare_pair_batch(1, &it, f, p, stream, nullptr);
     }
     const int rc = launch_prepare_operand(X, ld, 0, rows, cols, f, p, buf0, stream);
     return rc != FMT_OK ? rc : launch_prepare_operand(X, ld, 1, cols, rows, f, p, buf1, stream);

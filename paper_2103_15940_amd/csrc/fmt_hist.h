@@ -131,6 +131,15 @@ __device__ __forceinline__ void hist_end(uint32_t *tbl, uint32_t *s_bins, uint32
 // Sums the partial records into the caller's fmt_hist_t and clears them (fmt_stream.hip).
 int launch_hist_finalize(unsigned long long *partials, size_t n, fmt_hist_t *hist, hipStream_t stream);
 
+// ... for several tensors in one launch: partial records, element count and result of each (fmt_stream.hip).
+constexpr int kFinalizeGroup = 16;
+struct FinalizeGroup {
+    unsigned long long *partials[kFinalizeGroup];
+    unsigned long long n[kFinalizeGroup];
+    unsigned long long *hist[kFinalizeGroup];
+};
+int launch_hist_finalize_group(const FinalizeGroup &g, int count, hipStream_t stream);
+
 // Scratch bytes the partial records need.
 constexpr size_t kHistScratchBytes = (size_t)kShards * kSlots * sizeof(unsigned long long);
 

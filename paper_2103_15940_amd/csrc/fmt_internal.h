@@ -73,7 +73,13 @@ struct PrepPairItem {
     int64_t ld, rows, cols;
     void *buf0, *buf1;
 };
-int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_format_t f, const QuantParams &p, hipStream_t stream);
+struct RoundItem {              // with the operands: the matrix rounded to fp32 (Y, leading dimension ldy) and its statistics
+    float *Y;
+    int64_t ldy;
+    fmt_hist_t *hist;
+};
+int launch_prepare_pair_batch(int64_t count, const PrepPairItem *items, fmt_format_t f, const QuantParams &p, hipStream_t stream,
+                              const RoundItem *round);
 int launch_gemm_prepared(const void *A, const void *B, int64_t M, int64_t N, int64_t K, int scheme, fmt_format_t f,
                          float *C, int64_t ldc, hipStream_t stream);
 // One product of a batch on prepared operands: C (M x N, leading dimension ldc) = A (M rows) B^T (N rows), both of k = K.

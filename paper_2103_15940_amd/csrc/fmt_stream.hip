@@ -181,8 +181,8 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint32_t *__restri
 // Sums the shard records into the caller's fmt_hist_t and clears them for the next call (one
 // workgroup; the stream orders it after the kernel that filled them).
 constexpr int kFinSplit = 14;
-__global__ __launch_bounds__(1024) void finalize_kernel(unsigned long long *__restrict__ partials, int nrec,
-                                                        unsigned long long n, unsigned long long *__restrict__ hist)
+__device__ __forceinline__ void finalize_body(unsigned long long *__restrict__ partials, int nrec, unsigned long long n,
+                                              unsigned long long *__restrict__ hist)
 {
     __shared__ unsigned long long acc[kSlots * kFinSplit];
     __shared__ unsigned long long tot[kSlots];
@@ -220,6 +220,26 @@ __global__ __launch_bounds__(1024) void finalize_kernel(unsigned long long *__re
         }
         hist[tid] = v;
     }
+}
+
+__global__ __launch_bounds__(1024) void finalize_kernel(unsigned long long *__restrict__ partials, int nrec,
+                                                        unsigned long long n, unsigned long long *__restrict__ hist)
+{
+    finalize_body(partials, nrec, n, hist);
+}
+
+// The same for up to kFinalizeGroup tensors in one launch: workgroup i sums the records of tensor i.
+__global__ __launch_bounds__(1024) void finalize_group_kernel(FinalizeGroup g)
+{
+    finalize_body(g.partials[blockIdx.x], kShards, g.n[blockIdx.x], g.hist[blockIdx.x]);
+}
+
+int launch_hist_finalize_group(const FinalizeGroup &g, int count, hipStream_t stream)
+{
+    if (count < 1 || count > kFinalizeGroup) return FMT_ERR_SHAPE;
+    hipLaunchKernelGGL(finalize_group_kernel, dim3(count), dim3(1024), 0, stream, g);
+    FMT_HIP_CHECK(hipGetLastError());
+    return FMT_OK;
 }
 
 int launch_hist_finalize(unsigned long long *partials, size_t n, fmt_hist_t *hist, hipStream_t stream)

@@ -308,3 +308,37 @@ def test_prepare_pair_batch_validates_before_any_gpu_call():
     assert call(data=vp2(1 << 40, (1 << 41) + 1)) == -4                       # alignment
     assert lib.fmt_prepare_pair_batch(2, X, ld, rows, cols, fmt._CFormat(9, 9, 1), data, by, op, data_t, by_t, op_t, None) == -1
 
+
+def test_quantize_prepare_pair_batch_validates_before_any_gpu_call():
+    """fmt_quantize_prepare_pair_batch: count, NULL arrays and entries, formats without exponent planes are refused
+    by the library itself only at launch, so here: the argument checks that need no GPU."""
+    import ctypes
+    lib = fmt.raw_library()
+    f = fmt._CFormat(6, 9, 1)
+    z = [None] * 4
+    assert lib.fmt_quantize_prepare_pair_batch(0, *z, f, None, None, None, -48, None, None, None, None, None, None, None) == 0
+    assert lib.fmt_quantize_prepare_pair_batch(-1, *z, f, None, None, None, -48, None, None, None, None, None, None, None) == -3
+    assert lib.fmt_quantize_prepare_pair_batch(2, *z, f, None, None, None, -48, None, None, None, None, None, None, None) == -2
+    n0, n1 = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.fmt_operand_bytes(64, 96, f, ctypes.byref(n0)) == 0 and lib.fmt_operand_bytes(96, 64, f, ctypes.byref(n1)) == 0
+    vp2, i2, s2 = ctypes.c_void_p * 2, ctypes.c_int64 * 2, ctypes.c_size_t * 2
+    base = dict(X=vp2(1 << 30, 1 << 31), ld=i2(96, 96), rows=i2(64, 64), cols=i2(96, 96), Y=vp2(1 << 33, 1 << 34),
+                ldy=i2(96, 96), hist=vp2(1 << 35, 1 << 36), data=vp2(1 << 40, 1 << 41), by=s2(n0.value, n0.value),
+                data_t=vp2(1 << 42, 1 << 43), by_t=s2(n1.value, n1.value))
+    op, op_t = (fmt._COperand * 2)(), (fmt._COperand * 2)()
+
+    def call(exp_lo=-48, **kw):
+        a = dict(base)
+        a.update(kw)
+        return lib.fmt_quantize_prepare_pair_batch(2, a["X"], a["ld"], a["rows"], a["cols"], f, a["Y"], a["ldy"], a["hist"], exp_lo,
+                                                   a["data"], a["by"], op, a["data_t"], a["by_t"], op_t, None)
+
+    assert call(Y=vp2(1 << 33, None)) == -2                                   # an entry without a rounded copy
+    assert call(hist=vp2(1 << 35, None)) == -2
+    assert call(ldy=i2(96, 95)) == -3                                         # leading dimension below the columns
+    assert call(hist=vp2(1 << 35, (1 << 36) + 4)) == -4                       # statistics record not 8-byte aligned
+    assert call(Y=vp2(1 << 33, (1 << 31) + 64)) == -6                         # a rounded copy shifted over its input
+    assert call(hist=vp2(1 << 35, 1 << 35)) == -6                             # two matrices, one record
+    assert call(Y=vp2(1 << 33, (1 << 40) + 256)) == -6                        # a rounded copy over another operand
+    assert call(exp_lo=10 ** 6) == -5                                         # window out of range
+
