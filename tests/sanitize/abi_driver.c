@@ -116,6 +116,15 @@ int main(void)
         EXPECT(fmt_prepare_pair_batch(-1, px, d2, r2, c2, f, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_SHAPE);
         EXPECT(fmt_prepare_pair_batch(2, px, d2, r2, c2, f, pd, nb, NULL, pt, nb, t2, NULL), FMT_ERR_NULL);
         EXPECT(fmt_prepare_pair_batch(2, px, d2, r2, c2, f, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_SHAPE);  /* buffers of 0 bytes */
+        {
+            float *py[2] = {y, y + 64};
+            int64_t dy2[2] = {4, 4};
+            fmt_hist_t *ph[2] = {(fmt_hist_t *)0x50000, (fmt_hist_t *)0x60000};
+            EXPECT(fmt_quantize_prepare_pair_batch(0, NULL, NULL, NULL, NULL, f, NULL, NULL, NULL, -48, NULL, NULL, NULL, NULL, NULL, NULL, NULL), FMT_OK);
+            EXPECT(fmt_quantize_prepare_pair_batch(2, px, d2, r2, c2, f, NULL, dy2, ph, -48, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_NULL);
+            EXPECT(fmt_quantize_prepare_pair_batch(2, px, d2, r2, c2, f, py, dy2, ph, -48, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_SHAPE);  /* buffers of 0 bytes */
+            EXPECT(fmt_quantize_prepare_pair_batch(2, px, d2, r2, c2, f, py, dy2, ph, 1 << 20, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_RANGE);
+        }
         c2[1] = 5;
         nb[0] = nb[1] = (size_t)1 << 20;
         EXPECT(fmt_prepare_pair_batch(2, px, d2, r2, c2, f, pd, nb, o2, pt, nb, t2, NULL), FMT_ERR_SHAPE);  /* ld < cols */

@@ -171,7 +171,8 @@ def test_growing_scratch_under_capture_is_refused(fmt):
 
 
 def test_prepare_and_batch_replays_match_eager(fmt):
-    """fmt_prepare_pair, fmt_prepare_pair_batch and fmt_gemm_prepared_batch in a graph: the shared prepare launches, the shared product launch (with a member whose k
+    """fmt_quantize_prepare_pair_batch (rounded copies and statistics through library scratch), fmt_prepare_pair_batch and
+    fmt_gemm_prepared_batch in a graph: the shared prepare launches, the shared product launch (with a member whose k
     runs in parts through library scratch), the sum of its parts and the shared tail launch, replayed three
     times on new tensor contents, bit for bit what the eager calls give."""
     dev = torch.device("cuda")
@@ -180,6 +181,8 @@ def test_prepare_and_batch_replays_match_eager(fmt):
     X = [torch.empty((M, K), device=dev) for M, N, K in shapes]
     W = [torch.empty((N, K), device=dev) for M, N, K in shapes]
     C = [torch.empty((M, N), device=dev) for M, N, K in shapes]
+    Xq = [torch.empty_like(x) for x in X]
+    H = [fmt.new_hist() for _ in X]
     bufs = [(torch.empty(fmt.fmt_operand_bytes(M, K, f), dtype=torch.uint8, device=dev),
              torch.empty(fmt.fmt_operand_bytes(K, M, f), dtype=torch.uint8, device=dev),
              torch.empty(fmt.fmt_operand_bytes(N, K, f), dtype=torch.uint8, device=dev),
@@ -192,7 +195,8 @@ def test_prepare_and_batch_replays_match_eager(fmt):
             w.copy_(torch.from_numpy((r.standard_normal(tuple(w.shape)) * 0.02).astype(np.float32)))
 
     def calls():
-        A = [fmt.fmt_prepare_pair(x, f, out=b[0], out_t=b[1])[0] for x, b in zip(X, bufs)]
+        A = [pair[0] for pair in fmt.fmt_quantize_prepare_pair_batch(X, f, Xq, H, outs=[b[0] for b in bufs],
+                                                                     outs_t=[b[1] for b in bufs])]
         B = [pair[0] for pair in fmt.fmt_prepare_pair_batch(W, f, outs=[b[2] for b in bufs], outs_t=[b[3] for b in bufs])]
         fmt.fmt_gemm_prepared_batch(A, B, out=C)
 
@@ -213,10 +217,14 @@ def test_prepare_and_batch_replays_match_eager(fmt):
         calls()
         torch.cuda.synchronize()
         want = [c.clone() for c in C]
-        for c in C:
+        want_q, want_h = [q.clone() for q in Xq], [h.clone() for h in H]
+        for c in C + Xq + H:
             c.zero_()
         (X[0] @ W[0].t()).sum().item()             # unrelated eager work and a synchronisation between replays
         graph.replay()
         torch.cuda.synchronize()
         for i, (g, w) in enumerate(zip(C, want)):
             assert torch.equal(g.view(torch.int32), w.view(torch.int32)), (seed, shapes[i])
+        for i in range(len(X)):
+            assert torch.equal(Xq[i].view(torch.int32), want_q[i].view(torch.int32)), (seed, i)
+            assert torch.equal(H[i], want_h[i]), (seed, i)
