@@ -286,8 +286,10 @@ int fmt_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *
  * (same address and leading dimension: in place); otherwise nothing written may overlap anything else of the call
  * (FMT_ERR_ALIAS).  Arrays are HOST arrays of `count` entries; Y[i], hist[i], data[i], data_t[i] DEVICE pointers
  * (hist[i] 8-byte aligned).  Other arguments and errors as for fmt_prepare_pair_batch; FMT_ERR_RANGE for exp_lo as
- * for fmt_quantize.  Uses the stream's library scratch for the partial statistics records (576 KiB, allocated on
- * first use: not inside a stream capture before a first eager call on that stream).
+ * for fmt_quantize.  Uses the stream's library scratch for the partial statistics records (576 KiB against the
+ * 36 KiB of fmt_quantize: the first call on a stream makes that scratch grow, which invalidates graphs recorded on
+ * the stream before it, and cannot happen inside a capture -- run the call once eagerly first; see the notes on
+ * scratch at the top).
  */
 int fmt_quantize_prepare_pair_batch(int64_t count, const float *const *X, const int64_t *ld, const int64_t *rows,
                                     const int64_t *cols, fmt_format_t f, float *const *Y, const int64_t *ldy,
